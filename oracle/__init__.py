@@ -1,0 +1,134 @@
+"""ctypes front end of the CPU oracle (``flexq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY.  The tests, the smoke check and the benchmark's
+``cpu_baseline`` leg call it; the product package never does.  It shares no
+code with the GPU library: the C file is compiled with gcc on its own.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "flexq_oracle.c")
+_LIB = os.path.join(_HERE, "libflexq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """gcc -O2, no contraction, no fast-math: every float operation of the
+    quantizer is rounded once, as the oracle's header states."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.orc_half_to_float.restype = ctypes.c_float
+        lib.orc_half_to_float.argtypes = [ctypes.c_uint16]
+        lib.orc_double_to_half.restype = ctypes.c_uint16
+        lib.orc_double_to_half.argtypes = [ctypes.c_double]
+        lib.orc_quantize.restype = ci
+        lib.orc_quantize.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+        lib.orc_dequant.restype = None
+        lib.orc_dequant.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp]
+        lib.orc_linear.restype = ci
+        lib.orc_linear.argtypes = [vp, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        lib.orc_entropy_kl.restype = ci
+        lib.orc_entropy_kl.argtypes = [vp, vp, ci, ci, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def half_to_float(bits: int) -> float:
+    return float(_load().orc_half_to_float(bits))
+
+
+def double_to_half(d: float) -> int:
+    return int(_load().orc_double_to_half(d))
+
+
+def quantize(w: np.ndarray, bits: int, group: int = 128):
+    """w: fp16 [N][K].  Returns (codes u8 [N][K*bits/8], scales f32 [N][K/group],
+    zeros u8 [N][K/group]) in the canonical packed layout (Sec. 2.2 Eq. 2)."""
+    w = np.ascontiguousarray(w, dtype=np.float16)
+    N, K = w.shape
+    if bits not in (4, 8) or group <= 0 or K % group:
+        raise ValueError("bad bits/group")
+    codes = np.zeros((N, K * bits // 8), dtype=np.uint8)
+    scales = np.zeros((N, K // group), dtype=np.float32)
+    zeros = np.zeros((N, K // group), dtype=np.uint8)
+    rc = _load().orc_quantize(_p(w), N, K, bits, group, _p(codes), _p(scales), _p(zeros))
+    if rc != 0:
+        raise ValueError("orc_quantize rejected its input (non-finite weight or bad shape)")
+    return codes, scales, zeros
+
+
+def dequant(codes, scales, zeros, bits: int, group: int = 128) -> np.ndarray:
+    """Sec. 2.2 Eq. 3: float32 [N][K]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    N = codes.shape[0]
+    K = codes.shape[1] * 8 // bits
+    out = np.empty((N, K), dtype=np.float32)
+    _load().orc_dequant(_p(codes), _p(scales), _p(zeros), N, K, bits, group, _p(out))
+    return out
+
+
+def linear(x: np.ndarray, codes, scales, zeros, bits: int, group: int = 128,
+           row0: int = 0, rows: int | None = None) -> np.ndarray:
+    """y[m][n] for n in [row0, row0+rows): fp16 [M][rows].  bits=16: ``codes`` is
+    the fp16 weight matrix itself."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    M, K = x.shape
+    if bits == 16:
+        wt = np.ascontiguousarray(codes, dtype=np.float16)
+        N = wt.shape[0]
+        assert wt.shape[1] == K
+        cp, sp, zp = _p(wt), None, None
+    else:
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        scales = np.ascontiguousarray(scales, dtype=np.float32)
+        zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+        N = codes.shape[0]
+        assert codes.shape[1] * 8 // bits == K
+        cp, sp, zp = _p(codes), _p(scales), _p(zeros)
+    rows = N - row0 if rows is None else rows
+    y = np.empty((M, rows), dtype=np.float16)
+    rc = _load().orc_linear(_p(x), M, cp, sp, zp, N, K, bits, group, row0, rows, _p(y))
+    if rc != 0:
+        raise ValueError("orc_linear rejected its arguments")
+    return y
+
+
+def entropy_kl(a: np.ndarray, b: np.ndarray | None = None):
+    """Per-row entropy of softmax(a) (nats, float64 [R]) and, when ``b`` is given,
+    KL(softmax(a) || softmax(b)).  PPLE of Sec. 4.2 Eq. 5 is exp(entropy)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.ndim == 1:
+        a = a[None, :]
+    R, V = a.shape
+    if b is not None:
+        b = np.ascontiguousarray(b, dtype=np.float32).reshape(R, V)
+    H = np.empty(R, dtype=np.float64)
+    KL = np.empty(R, dtype=np.float64) if b is not None else None
+    rc = _load().orc_entropy_kl(_p(a), _p(b), R, V, _p(H), _p(KL))
+    if rc != 0:
+        raise ValueError("orc_entropy_kl rejected its arguments")
+    return (H, KL) if b is not None else (H, None)

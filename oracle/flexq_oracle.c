@@ -1,0 +1,270 @@
+/*
+ * CPU oracle for the FlexQuant decode hot path.  TEST INFRASTRUCTURE ONLY:
+ * nothing in the product library includes, links or calls this file; it
+ * exists so that the GPU kernels can be checked against a plain, slow,
+ * obviously correct statement of what the paper defines.
+ *
+ * Written from the paper's definitions, one routine per definition:
+ *   orc_quantize     asymmetric uniform quantization, Sec. 2.2 Eq. (2), applied
+ *                    per (output row, group of `group` consecutive inputs)
+ *   orc_dequant      Sec. 2.2 Eq. (3)
+ *   orc_linear       the weight-only quantized linear layer of the decode
+ *                    phase (Sec. 4.1, 4.3): y = x . dequant(W)^T
+ *   orc_entropy_kl   softmax of Sec. 2.3, the entropy inside the perplexity
+ *                    entropy of Sec. 4.2 Eq. (5), and the KL divergence of
+ *                    Sec. 3.1 between two next-token distributions
+ *
+ * Readings taken where the paper is silent (kept in step with the design
+ * notes of this repository):
+ *   - statistics Xmin/Xmax are per (row, group); the range is widened to
+ *     contain 0 so that the zero point fits the code range;
+ *   - the bracket of Eq. (2) is round-half-to-even; s, z and the codes are
+ *     computed in binary32 with one rounding per operation (no fused
+ *     multiply-add, true division);
+ *   - Eq. (2)'s X/s + z is added first and rounded second, then clamped to
+ *     [0, 2^n - 1]; an all-zero group gets s = 1, z = 0;
+ *   - packing: 8-bit codes one per byte; 4-bit codes two per byte, even
+ *     input index in the low nibble;
+ *   - the sum of Eq. (5) runs over the vocabulary, natural logarithm,
+ *     0 log 0 = 0; KL(p || q) takes p from the first logits vector.
+ *
+ * Everything that accumulates does so in double.  No blocking, no fusion.
+ * Build: gcc -O2 -ffp-contract=off (and -fopenmp: rows of orc_linear and of
+ * orc_entropy_kl may run on several threads; each output is still computed by
+ * one thread in index order).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ---- binary16 <-> binary32/64, written out (no compiler half type) ---- */
+
+static float half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    int e = (h >> 10) & 0x1F;
+    uint32_t m = h & 0x3FFu;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24);
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m | 0x400u), e - 25);
+    float f = (float)v; /* exact: every half is a float */
+    if (sign)
+        f = -f;
+    return f;
+}
+
+/* double -> nearest binary16 (ties to even), by explicit search of the two
+ * neighbouring halves; overflow beyond the rounding boundary gives infinity. */
+static uint16_t double_to_half(double d)
+{
+    uint16_t sign = 0;
+    if (isnan(d))
+        return 0x7E00u;
+    if (d < 0 || (d == 0 && signbit(d))) {
+        sign = 0x8000u;
+        d = -d;
+    }
+    if (d >= 65520.0)
+        return (uint16_t)(sign | 0x7C00u);
+    /* largest half <= d by bisection over the ordered bit patterns 0..0x7BFF */
+    uint16_t lo = 0, hi = 0x7BFF;
+    while (lo < hi) {
+        uint16_t mid = (uint16_t)((lo + hi + 1) >> 1);
+        if ((double)half_to_float(mid) <= d)
+            lo = mid;
+        else
+            hi = (uint16_t)(mid - 1);
+    }
+    double below = (double)half_to_float(lo);
+    double above = (lo == 0x7BFF) ? 65536.0 : (double)half_to_float((uint16_t)(lo + 1));
+    double dl = d - below, du = above - d; /* both exact in double */
+    uint16_t r;
+    if (dl < du)
+        r = lo;
+    else if (dl > du)
+        r = (uint16_t)(lo + 1);
+    else
+        r = (lo & 1u) ? (uint16_t)(lo + 1) : lo;
+    return (uint16_t)(sign | r);
+}
+
+float orc_half_to_float(uint16_t h) { return half_to_float(h); }
+uint16_t orc_double_to_half(double d) { return double_to_half(d); }
+
+/* ---- Eq. (2): quantize one matrix, group-wise along the input dimension ---- */
+
+static int code_of(const uint8_t *codes, int bits, long long row_elems, long long n, long long k)
+{
+    if (bits == 8)
+        return codes[n * row_elems + k];
+    uint8_t byte = codes[(n * row_elems + k) / 2];
+    return (k & 1) ? (byte >> 4) : (byte & 0xF);
+}
+
+/*
+ * w: [N][K] binary16 bit patterns.  codes: N*K*bits/8 bytes.  scales: [N][K/group]
+ * float.  zeros: [N][K/group] bytes.  Returns 0, or -1 on a bad argument
+ * (bits not 4 or 8, K not a multiple of group, odd group) or a non-finite weight.
+ */
+int orc_quantize(const uint16_t *w, int N, int K, int bits, int group,
+                 uint8_t *codes, float *scales, uint8_t *zeros)
+{
+    if ((bits != 4 && bits != 8) || group <= 0 || (group & 1) || K % group != 0)
+        return -1;
+    const int G = K / group;
+    const float qmax = (float)((1 << bits) - 1);
+    int bad = 0;
+    if (bits == 4)
+        memset(codes, 0, (size_t)N * K / 2);
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long long n = 0; n < N; n++) {
+        for (int g = 0; g < G; g++) {
+            const uint16_t *wg = w + n * K + (long long)g * group;
+            float lo = 0.0f, hi = 0.0f; /* range always contains 0 */
+            for (int i = 0; i < group; i++) {
+                float v = half_to_float(wg[i]);
+                if (!isfinite(v))
+                    bad |= 1;
+                if (v < lo) lo = v;
+                if (v > hi) hi = v;
+            }
+            float s, zf;
+            if (hi == lo) { /* all-zero group */
+                s = 1.0f;
+                zf = 0.0f;
+            } else {
+                volatile float range = hi - lo;       /* one rounding each; the   */
+                volatile float sv = range / qmax;     /* volatiles forbid folding */
+                s = sv;
+                volatile float neg = -lo;
+                volatile float zq = neg / s;
+                zf = rintf(zq);                        /* q_min = 0 */
+                if (zf < 0.0f) zf = 0.0f;
+                if (zf > qmax) zf = qmax;
+            }
+            scales[n * G + g] = s;
+            zeros[n * G + g] = (uint8_t)zf;
+            for (int i = 0; i < group; i++) {
+                float v = half_to_float(wg[i]);
+                volatile float t = v / s;
+                volatile float u = t + zf;
+                float q = rintf(u);
+                if (q < 0.0f) q = 0.0f;
+                if (q > qmax) q = qmax;
+                long long k = (long long)g * group + i;
+                if (bits == 8)
+                    codes[n * K + k] = (uint8_t)q;
+                else
+                    codes[(n * K + k) / 2] |= (uint8_t)((unsigned)q << ((k & 1) ? 4 : 0));
+            }
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/* ---- Eq. (3): dequantize to float, [N][K] ---- */
+
+void orc_dequant(const uint8_t *codes, const float *scales, const uint8_t *zeros,
+                 int N, int K, int bits, int group, float *w_hat)
+{
+    const int G = K / group;
+    for (long long n = 0; n < N; n++)
+        for (long long k = 0; k < K; k++) {
+            int g = (int)(k / group);
+            float q = (float)code_of(codes, bits, K, n, k);
+            float z = (float)zeros[n * G + g];
+            volatile float d = q - z;
+            w_hat[n * K + k] = d * scales[n * G + g];
+        }
+}
+
+/*
+ * Weight-only quantized linear.  x: [M][K] half bits.  bits 4/8: codes, scales,
+ * zeros as written by orc_quantize; bits 16: `codes` holds [N][K] half weights,
+ * scales/zeros unused.  Rows row0 .. row0+rows-1 of the output are computed
+ * (rows = N, row0 = 0 for all); y: [M][rows] half bits, y[m][n-row0].
+ * Each output: sum over k in index order of (double)x * (double)w_hat, with
+ * w_hat the binary32 value of Eq. (3); rounded once to binary16.
+ */
+int orc_linear(const uint16_t *x, int M, const uint8_t *codes, const float *scales,
+               const uint8_t *zeros, int N, int K, int bits, int group,
+               int row0, int rows, uint16_t *y)
+{
+    if (bits != 4 && bits != 8 && bits != 16)
+        return -1;
+    if (bits != 16 && (group <= 0 || K % group != 0))
+        return -1;
+    if (row0 < 0 || rows < 0 || row0 + rows > N)
+        return -1;
+    const int G = (bits == 16) ? 0 : K / group;
+#pragma omp parallel for schedule(static)
+    for (long long r = 0; r < rows; r++) {
+        long long n = row0 + r;
+        for (int m = 0; m < M; m++) {
+            double acc = 0.0;
+            for (long long k = 0; k < K; k++) {
+                float wv;
+                if (bits == 16) {
+                    wv = half_to_float(((const uint16_t *)codes)[n * K + k]);
+                } else {
+                    int g = (int)(k / group);
+                    float q = (float)code_of(codes, bits, K, n, k);
+                    float z = (float)zeros[n * G + g];
+                    volatile float d = q - z;
+                    volatile float p = d * scales[n * G + g];
+                    wv = p;
+                }
+                acc += (double)half_to_float(x[(long long)m * K + k]) * (double)wv;
+            }
+            y[(long long)m * rows + r] = double_to_half(acc);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Entropy of softmax(a) and KL(softmax(a) || softmax(b)) per row, in nats.
+ * a, b: [R][V] float (b may be NULL: only the entropy is written).
+ * Two passes per row, in double: m = max a; S = sum exp(a - m);
+ * LSE = m + ln S; p_i = exp(a_i - m) / S; H = - sum p_i ln p_i with
+ * ln p_i = a_i - LSE; KL = sum p_i (ln p_i - ln q_i).  Terms with p_i = 0 add 0.
+ */
+int orc_entropy_kl(const float *a, const float *b, int R, int V, double *H, double *KL)
+{
+    if (R < 0 || V < 1)
+        return -1;
+#pragma omp parallel for schedule(static)
+    for (long long r = 0; r < R; r++) {
+        const float *ar = a + r * V;
+        const float *br = b ? b + r * V : 0;
+        double ma = -INFINITY, mb = -INFINITY;
+        for (int i = 0; i < V; i++) {
+            if ((double)ar[i] > ma) ma = ar[i];
+            if (br && (double)br[i] > mb) mb = br[i];
+        }
+        double Sa = 0.0, Sb = 0.0;
+        for (int i = 0; i < V; i++) {
+            Sa += exp((double)ar[i] - ma);
+            if (br) Sb += exp((double)br[i] - mb);
+        }
+        double lse_a = ma + log(Sa), lse_b = br ? mb + log(Sb) : 0.0;
+        double h = 0.0, kl = 0.0;
+        for (int i = 0; i < V; i++) {
+            double p = exp((double)ar[i] - ma) / Sa;
+            if (p == 0.0)
+                continue;
+            double lnp = (double)ar[i] - lse_a;
+            h -= p * lnp;
+            if (br)
+                kl += p * (lnp - ((double)br[i] - lse_b));
+        }
+        H[r] = h;
+        if (br && KL)
+            KL[r] = kl;
+    }
+    return 0;
+}
