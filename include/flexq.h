@@ -1,0 +1,150 @@
+/*
+ * flexq.h -- C ABI of the MI355X (gfx950) library for the decode hot path of
+ * FlexQuant's dynamic precision switching (arXiv 2506.12024).
+ *
+ * What the calls compute is defined by the paper:
+ *   fq_quantize     asymmetric uniform quantization, Sec. 2.2 Eq. (2)
+ *   fq_linear       the weight-only quantized linear layer of the decode phase
+ *                   (Sec. 4.1), weights dequantized on the fly by Eq. (3), the
+ *                   bit-width of every layer chosen per generated token from
+ *                   copies that all stay resident in HBM (Sec. 4.3)
+ *   fq_entropy_kl   entropy of softmax(logits) (Sec. 2.3; PPLE of Sec. 4.2
+ *                   Eq. (5) is exp of it) and the KL divergence used to rank
+ *                   layers (Sec. 3.1, Sec. 4.3)
+ *
+ * Conventions.
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, who keeps it
+ *     alive until the work enqueued on `stream` has finished.  The library never
+ *     allocates, frees or copies tensor memory and never synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued in order on it; a call returns without waiting.
+ *   - Every function returns FQ_OK (0) or a negative fq_status.  Arguments are
+ *     validated before anything is launched; on an error nothing was enqueued.
+ *     fq_last_error() returns a message for the calling thread's last failure.
+ *   - Matrices are row-major.  A linear layer has K inputs and N outputs and its
+ *     weight is W[N][K]; quantization groups are `group` consecutive k of a row.
+ *
+ * Packed layout (the one fq_quantize writes, fq_layer_attach expects and the
+ * kernels stream directly -- a switch of bit-width never repacks anything):
+ *   codes, bits = 8 : u8  [N][K]      byte k of row n is the code of W[n][k]
+ *   codes, bits = 4 : u8  [N][K/2]    byte j of row n = code(2j) | code(2j+1) << 4
+ *   scales          : f32 [N][K/group]
+ *   zeros           : u8  [N][K/group]
+ *   bits = 16       : the fp16 weights W[N][K] themselves, no scales/zeros
+ */
+#ifndef FLEXQ_H
+#define FLEXQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fq_status {
+    FQ_OK = 0,
+    FQ_ERR_NULL = -1,         /* a required pointer is NULL */
+    FQ_ERR_BITS = -2,         /* bit-width not supported by this call */
+    FQ_ERR_SHAPE = -3,        /* a size is out of range or K is not a multiple of group */
+    FQ_ERR_NOT_ATTACHED = -4, /* the layer holds no copy at the requested bit-width */
+    FQ_ERR_ALIGN = -5,        /* a pointer is not aligned as documented */
+    FQ_ERR_HIP = -6           /* the HIP runtime reported an error (see fq_last_error) */
+} fq_status;
+
+typedef struct fq_layer fq_layer; /* opaque: borrows the caller's packed buffers */
+typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch */
+
+#define FQ_GROUP 128      /* the only group size the kernels are built for */
+#define FQ_MAX_DECODE_M 32 /* rows of x served by the skinny (decode) kernels */
+
+/* Message describing the calling thread's most recent error ("" if none). */
+const char *fq_last_error(void);
+
+/*
+ * Bytes of the three packed buffers for an N x K weight at `bits` (4 or 8).
+ * Any of the three outputs may be NULL.  Host-only; launches nothing.
+ */
+int fq_packed_sizes(int N, int K, int bits, int group,
+                    size_t *codes_bytes, size_t *scales_bytes, size_t *zeros_bytes);
+
+/*
+ * Sec. 2.2 Eq. (2), per (row, group): with lo = min(0, min w), hi = max(0, max w),
+ *   s = (hi - lo) / (2^bits - 1),  z = round(-lo / s),  q = clamp(round(w / s + z)),
+ * all in binary32 with one rounding per operation and round-half-to-even; an
+ * all-zero group gets s = 1, z = 0.  Writes the packed layout above.
+ *   w_fp16  device, fp16 [N][K], 16-byte aligned      (read)
+ *   codes   device, fq_packed_sizes bytes, 16-byte aligned (written)
+ *   scales  device, f32 [N][K/group]                   (written)
+ *   zeros   device, u8  [N][K/group]                   (written)
+ * bits in {4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
+ * Non-finite weights give unspecified codes.
+ */
+int fq_quantize(const void *w_fp16, int N, int K, int bits, int group,
+                void *codes, void *scales, void *zeros, void *stream);
+
+/*
+ * A layer handle: a small host object naming the resident copies of one
+ * linear's weight.  fq_layer_attach records (does not copy) the buffers for one
+ * bit-width; any subset of {4, 8, 16} may be attached, each at most once per
+ * value (attaching again replaces the pointers).  For bits = 16 pass the fp16
+ * weights as `codes` and NULL scales/zeros.  Buffers must be 16-byte aligned.
+ * Launches nothing.
+ */
+int fq_layer_create(fq_layer **out, int N, int K, int group);
+int fq_layer_attach(fq_layer *layer, int bits, const void *codes,
+                    const void *scales, const void *zeros);
+int fq_layer_destroy(fq_layer *layer);
+
+/*
+ * Decode-phase linear (Sec. 4.1, Eq. (3)):
+ *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
+ * accumulated in binary32, using the copy attached for `bits` -- chosen at call
+ * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.
+ *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
+ *   y_fp16  device, fp16 [M][N]                    (written)
+ * 1 <= M <= FQ_MAX_DECODE_M selects the memory-bound skinny kernels; larger M
+ * (prefill-shaped, any M >= 1) runs the MFMA dequant-GEMM.
+ */
+int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
+              void *y_fp16, void *stream);
+
+/*
+ * A plan runs `count` linears with ONE launch: entry i computes
+ * ys[i] = linear(layers[i], bits[i], xs[i]) with the same M (1..FQ_MAX_DECODE_M)
+ * for all.  The entries must be independent of each other within one run (no
+ * ys[i] may alias an xs[j]).  The bit-width of every entry is read by the kernel
+ * from DEVICE memory at run time, so the per-token precision pattern of
+ * Sec. 4.4 / Alg. 1 can be written by another kernel or a small copy and the
+ * same plan (and a HIP graph holding it) serves every pattern.
+ *   workspace  device memory of fq_plan_workspace_bytes(count) bytes, 256-byte
+ *              aligned, owned by the caller, must outlive the plan; the
+ *              descriptor table is copied into it on `stream` by fq_plan_create
+ *   bits_dev   device, int32 [count], each 4, 8 or 16 and attached to its layer;
+ *              an entry whose value is anything else is skipped by the kernel
+ *              and its y is left untouched
+ */
+size_t fq_plan_workspace_bytes(int count);
+int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers,
+                   const void *const *xs, void *const *ys, int M,
+                   void *workspace, size_t workspace_bytes, void *stream);
+int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream);
+int fq_plan_destroy(fq_plan *plan);
+
+/*
+ * Per row r of [R][V] fp32 logits (natural logarithm, 0 log 0 = 0):
+ *   entropy_out[r] = - sum_i p_i ln p_i,           p = softmax(logits_p[r])
+ *   kl_out[r]      =   sum_i p_i (ln p_i - ln q_i), q = softmax(logits_q[r])
+ * logits_q and kl_out may both be NULL (entropy only).  One pass over the
+ * inputs.  -inf entries carry no mass; +inf and NaN are unspecified.
+ *   logits_p, logits_q  device, f32 [R][V]     (read)
+ *   entropy_out, kl_out device, f32 [R]        (written)
+ * R >= 0 (R = 0 launches nothing), V >= 1.
+ */
+int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V,
+                  float *entropy_out, float *kl_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXQ_H */

@@ -1,0 +1,327 @@
+// Host side of the C ABI declared in include/flexq.h: argument validation,
+// the layer / plan handles and the launches.  Validation happens before any
+// HIP call so every error path can be exercised on a host without a GPU.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/flexq.h"
+#include "fq_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(FQ_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr uint32_t LAYER_MAGIC = 0x46514C59u; // "FQLY"
+constexpr uint32_t PLAN_MAGIC = 0x4651504Cu;  // "FQPL"
+// The decode kernels keep one row of x (plus its slice sums) in LDS.
+constexpr int MAX_DECODE_K = 24576;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int slot_of(int bits) { return bits == 4 ? 0 : bits == 8 ? 1 : bits == 16 ? 2 : -1; }
+
+} // namespace
+
+struct fq_layer {
+    uint32_t magic;
+    int N, K, group;
+    const void *codes[3];
+    const void *scales[3];
+    const void *zeros[3];
+};
+
+struct fq_plan {
+    uint32_t magic;
+    int count, M, total_tiles, max_K;
+    const FqLinearDesc *table_dev;
+};
+
+namespace {
+
+int check_layer(const fq_layer *l)
+{
+    if (!l)
+        return fail(FQ_ERR_NULL, "layer is NULL");
+    if (l->magic != LAYER_MAGIC)
+        return fail(FQ_ERR_NULL, "layer handle is not valid (destroyed or corrupted)");
+    return FQ_OK;
+}
+
+void fill_desc(FqLinearDesc &d, const fq_layer *l, const void *x, void *y)
+{
+    memset(&d, 0, sizeof d);
+    d.codes4 = (const uint8_t *)l->codes[0];
+    d.scales4 = (const float *)l->scales[0];
+    d.zeros4 = (const uint8_t *)l->zeros[0];
+    d.codes8 = (const uint8_t *)l->codes[1];
+    d.scales8 = (const float *)l->scales[1];
+    d.zeros8 = (const uint8_t *)l->zeros[1];
+    d.w16 = (const uint16_t *)l->codes[2];
+    d.x = (const uint16_t *)x;
+    d.y = (uint16_t *)y;
+    d.N = l->N;
+    d.K = l->K;
+}
+
+int check_shape(int N, int K, int group)
+{
+    if (group != FQ_GROUP)
+        return fail(FQ_ERR_SHAPE, "group must be %d (got %d)", FQ_GROUP, group);
+    if (N < 1 || K < 1)
+        return fail(FQ_ERR_SHAPE, "N and K must be >= 1 (got N=%d K=%d)", N, K);
+    if (K % group != 0)
+        return fail(FQ_ERR_SHAPE, "K=%d is not a multiple of group=%d", K, group);
+    return FQ_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *fq_last_error(void) { return g_err; }
+
+int fq_packed_sizes(int N, int K, int bits, int group, size_t *codes_bytes, size_t *scales_bytes,
+                    size_t *zeros_bytes)
+{
+    if (bits != 4 && bits != 8)
+        return fail(FQ_ERR_BITS, "fq_packed_sizes: bits must be 4 or 8 (got %d)", bits);
+    if (int rc = check_shape(N, K, group))
+        return rc;
+    const size_t groups = (size_t)N * (size_t)(K / group);
+    if (codes_bytes)
+        *codes_bytes = (size_t)N * (size_t)K * (size_t)bits / 8;
+    if (scales_bytes)
+        *scales_bytes = groups * sizeof(float);
+    if (zeros_bytes)
+        *zeros_bytes = groups;
+    return FQ_OK;
+}
+
+int fq_quantize(const void *w_fp16, int N, int K, int bits, int group, void *codes, void *scales,
+                void *zeros, void *stream)
+{
+    if (!w_fp16 || !codes || !scales || !zeros)
+        return fail(FQ_ERR_NULL, "fq_quantize: NULL tensor pointer");
+    if (bits != 4 && bits != 8)
+        return fail(FQ_ERR_BITS, "fq_quantize: bits must be 4 or 8 (got %d)", bits);
+    if (int rc = check_shape(N, K, group))
+        return rc;
+    if (!aligned16(w_fp16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_quantize: w and codes need 16-byte, scales 4-byte alignment");
+    const long long n_groups = (long long)N * (K / group);
+    hipError_t e = fq_launch_quantize(w_fp16, n_groups, bits, codes, scales, zeros, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_quantize launch");
+    return FQ_OK;
+}
+
+int fq_layer_create(fq_layer **out, int N, int K, int group)
+{
+    if (!out)
+        return fail(FQ_ERR_NULL, "fq_layer_create: out is NULL");
+    *out = nullptr;
+    if (int rc = check_shape(N, K, group))
+        return rc;
+    fq_layer *l = new (std::nothrow) fq_layer();
+    if (!l)
+        return fail(FQ_ERR_HIP, "fq_layer_create: out of host memory");
+    l->magic = LAYER_MAGIC;
+    l->N = N;
+    l->K = K;
+    l->group = group;
+    *out = l;
+    return FQ_OK;
+}
+
+int fq_layer_attach(fq_layer *layer, int bits, const void *codes, const void *scales,
+                    const void *zeros)
+{
+    if (int rc = check_layer(layer))
+        return rc;
+    const int slot = slot_of(bits);
+    if (slot < 0)
+        return fail(FQ_ERR_BITS, "fq_layer_attach: bits must be 4, 8 or 16 (got %d)", bits);
+    if (!codes)
+        return fail(FQ_ERR_NULL, "fq_layer_attach: codes is NULL");
+    if (bits != 16 && (!scales || !zeros))
+        return fail(FQ_ERR_NULL, "fq_layer_attach: scales/zeros are NULL for bits=%d", bits);
+    if (!aligned16(codes) || (bits != 16 && (reinterpret_cast<uintptr_t>(scales) & 3u)))
+        return fail(FQ_ERR_ALIGN, "fq_layer_attach: codes need 16-byte, scales 4-byte alignment");
+    layer->codes[slot] = codes;
+    layer->scales[slot] = bits == 16 ? nullptr : scales;
+    layer->zeros[slot] = bits == 16 ? nullptr : zeros;
+    return FQ_OK;
+}
+
+int fq_layer_destroy(fq_layer *layer)
+{
+    if (int rc = check_layer(layer))
+        return rc;
+    layer->magic = 0;
+    delete layer;
+    return FQ_OK;
+}
+
+int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *y_fp16, void *stream)
+{
+    if (int rc = check_layer(layer))
+        return rc;
+    if (!x_fp16 || !y_fp16)
+        return fail(FQ_ERR_NULL, "fq_linear: x or y is NULL");
+    const int slot = slot_of(bits);
+    if (slot < 0)
+        return fail(FQ_ERR_BITS, "fq_linear: bits must be 4, 8 or 16 (got %d)", bits);
+    if (!layer->codes[slot])
+        return fail(FQ_ERR_NOT_ATTACHED, "fq_linear: no %d-bit copy attached to this layer", bits);
+    if (M < 1)
+        return fail(FQ_ERR_SHAPE, "fq_linear: M must be >= 1 (got %d)", M);
+    if (!aligned16(x_fp16) || (reinterpret_cast<uintptr_t>(y_fp16) & 1u))
+        return fail(FQ_ERR_ALIGN, "fq_linear: x needs 16-byte and y 2-byte alignment");
+    FqLinearDesc d;
+    fill_desc(d, layer, x_fp16, y_fp16);
+    hipError_t e;
+    if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
+        const int rows = fq_decode_rows_per_tile(M);
+        const int tiles = (layer->N + rows - 1) / rows;
+        e = fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, layer->K, M, (hipStream_t)stream);
+    } else {
+        e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
+    }
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_linear launch");
+    return FQ_OK;
+}
+
+size_t fq_plan_workspace_bytes(int count)
+{
+    if (count < 1)
+        return 0;
+    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256;
+}
+
+int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, const void *const *xs,
+                   void *const *ys, int M, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out)
+        return fail(FQ_ERR_NULL, "fq_plan_create: out is NULL");
+    *out = nullptr;
+    if (!layers || !xs || !ys || !workspace)
+        return fail(FQ_ERR_NULL, "fq_plan_create: NULL argument");
+    if (count < 1)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create: count must be >= 1 (got %d)", count);
+    if (M < 1 || M > FQ_MAX_DECODE_M)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create: M must be in 1..%d (got %d)", FQ_MAX_DECODE_M, M);
+    if (workspace_bytes < fq_plan_workspace_bytes(count))
+        return fail(FQ_ERR_SHAPE, "fq_plan_create: workspace too small (%zu < %zu bytes)",
+                    workspace_bytes, fq_plan_workspace_bytes(count));
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+        return fail(FQ_ERR_ALIGN, "fq_plan_create: workspace must be 256-byte aligned");
+    std::vector<FqLinearDesc> table((size_t)count);
+    const int rows = fq_decode_rows_per_tile(M);
+    long long tiles = 0;
+    int max_K = 0;
+    for (int i = 0; i < count; i++) {
+        if (int rc = check_layer(layers[i]))
+            return rc;
+        if (!xs[i] || !ys[i])
+            return fail(FQ_ERR_NULL, "fq_plan_create: x or y of entry %d is NULL", i);
+        if (!aligned16(xs[i]) || (reinterpret_cast<uintptr_t>(ys[i]) & 1u))
+            return fail(FQ_ERR_ALIGN, "fq_plan_create: entry %d: x needs 16-byte, y 2-byte alignment", i);
+        if (layers[i]->K > MAX_DECODE_K)
+            return fail(FQ_ERR_SHAPE, "fq_plan_create: entry %d: K=%d exceeds the decode limit %d", i,
+                        layers[i]->K, MAX_DECODE_K);
+        if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2])
+            return fail(FQ_ERR_NOT_ATTACHED, "fq_plan_create: entry %d has no copy attached", i);
+        fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
+        table[(size_t)i].tile_begin = (int)tiles;
+        tiles += (layers[i]->N + rows - 1) / rows;
+        if (layers[i]->K > max_K)
+            max_K = layers[i]->K;
+        if (tiles > 0x7fffffffLL)
+            return fail(FQ_ERR_SHAPE, "fq_plan_create: too many row tiles");
+    }
+    fq_plan *p = new (std::nothrow) fq_plan();
+    if (!p)
+        return fail(FQ_ERR_HIP, "fq_plan_create: out of host memory");
+    // The table is small; a synchronous-with-respect-to-host copy keeps the host vector's
+    // lifetime trivial (hipMemcpyAsync from pageable memory returns after staging the source).
+    hipError_t e = hipMemcpyAsync(workspace, table.data(), (size_t)count * sizeof(FqLinearDesc),
+                                  hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) {
+        delete p;
+        return hip_fail(e, "fq_plan_create table copy");
+    }
+    p->magic = PLAN_MAGIC;
+    p->count = count;
+    p->M = M;
+    p->total_tiles = (int)tiles;
+    p->max_K = max_K;
+    p->table_dev = (const FqLinearDesc *)workspace;
+    *out = p;
+    return FQ_OK;
+}
+
+int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
+{
+    if (!plan || plan->magic != PLAN_MAGIC)
+        return fail(FQ_ERR_NULL, "fq_plan_run: plan is NULL or not valid");
+    if (!bits_dev)
+        return fail(FQ_ERR_NULL, "fq_plan_run: bits_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(bits_dev) & 3u)
+        return fail(FQ_ERR_ALIGN, "fq_plan_run: bits_dev must be 4-byte aligned");
+    hipError_t e = fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count,
+                                    plan->total_tiles, plan->max_K, plan->M, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_plan_run launch");
+    return FQ_OK;
+}
+
+int fq_plan_destroy(fq_plan *plan)
+{
+    if (!plan || plan->magic != PLAN_MAGIC)
+        return fail(FQ_ERR_NULL, "fq_plan_destroy: plan is NULL or not valid");
+    plan->magic = 0;
+    delete plan;
+    return FQ_OK;
+}
+
+int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V, float *entropy_out,
+                  float *kl_out, void *stream)
+{
+    if (R < 0 || V < 1)
+        return fail(FQ_ERR_SHAPE, "fq_entropy_kl: need R >= 0 and V >= 1 (got R=%d V=%d)", R, V);
+    if (!logits_p || !entropy_out)
+        return fail(FQ_ERR_NULL, "fq_entropy_kl: logits_p or entropy_out is NULL");
+    if ((logits_q == nullptr) != (kl_out == nullptr))
+        return fail(FQ_ERR_NULL, "fq_entropy_kl: logits_q and kl_out must both be given or both be NULL");
+    if ((reinterpret_cast<uintptr_t>(logits_p) & 3u) || (reinterpret_cast<uintptr_t>(logits_q) & 3u) ||
+        (reinterpret_cast<uintptr_t>(entropy_out) & 3u) || (reinterpret_cast<uintptr_t>(kl_out) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_entropy_kl: pointers must be 4-byte aligned");
+    hipError_t e = fq_launch_entropy_kl(logits_p, logits_q, R, V, entropy_out, kl_out, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_entropy_kl launch");
+    return FQ_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,234 @@
+// Entropy of softmax(a) and KL(softmax(a) || softmax(b)) per row, one pass.
+// Softmax: Sec. 2.3; the entropy is the exponent's argument of the perplexity
+// entropy, Sec. 4.2 Eq. (5); the KL divergence is the layer-ranking signal of
+// Sec. 3.1 / 4.3, taken between two next-token distributions.
+//
+// One workgroup per row.  Every lane keeps an online (running-max) partial
+//   m  = max a_i            S  = sum e^(a_i - m)
+//   U  = sum e^(a_i - m) (a_i - m)          D = sum e^(a_i - m) (a_i - b_i)
+//   mb = max b_i            Sb = sum e^(b_i - mb)
+// over the 128-bit vectors it streams (coalesced, four in flight), in binary32.
+// Partials are then rescaled to the row maximum and summed across the
+// workgroup in double, and one lane finishes in double:
+//   H  = ln S - U / S
+//   KL = D / S + (mb - m) + ln(Sb / S)
+// so the difference of the two log-sum-exps, which is where binary32 would lose
+// the small KL of two nearly equal distributions, never passes through binary32.
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+
+namespace {
+
+struct Partial {
+    float m, S, U, D, mb, Sb;
+};
+
+__device__ __forceinline__ void part_init(Partial &p)
+{
+    p.m = -FLT_MAX;
+    p.mb = -FLT_MAX;
+    p.S = p.U = p.D = p.Sb = 0.0f;
+}
+
+__device__ __forceinline__ void raise_max_a(Partial &p, float cm)
+{
+    if (cm > p.m) {
+        if (p.S > 0.0f) {
+            const float d = p.m - cm;
+            const float c = expf(d);
+            p.U = c * (p.U + d * p.S);
+            p.S *= c;
+            p.D *= c;
+        }
+        p.m = cm;
+    }
+}
+
+__device__ __forceinline__ void raise_max_b(Partial &p, float cm)
+{
+    if (cm > p.mb) {
+        if (p.Sb > 0.0f)
+            p.Sb *= expf(p.mb - cm);
+        p.mb = cm;
+    }
+}
+
+template <bool HAS_B>
+__device__ __forceinline__ void add_one(Partial &p, float a, float b)
+{
+    const float t = a - p.m;
+    const float e = expf(t);
+    const bool live = e > 0.0f; // e = 0 (a = -inf or far below the maximum) adds nothing
+    p.S += e;
+    p.U += live ? e * t : 0.0f;
+    if (HAS_B) {
+        p.D += live ? e * (a - b) : 0.0f;
+        p.Sb += expf(b - p.mb);
+    }
+}
+
+template <bool HAS_B>
+__device__ __forceinline__ void add_vec(Partial &p, const float4 a, const float4 b)
+{
+    raise_max_a(p, fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w)));
+    if (HAS_B)
+        raise_max_b(p, fmaxf(fmaxf(b.x, b.y), fmaxf(b.z, b.w)));
+    add_one<HAS_B>(p, a.x, b.x);
+    add_one<HAS_B>(p, a.y, b.y);
+    add_one<HAS_B>(p, a.z, b.z);
+    add_one<HAS_B>(p, a.w, b.w);
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+template <int THREADS, bool HAS_B, bool VEC>
+__global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__restrict__ a,
+                                                             const float *__restrict__ b, int V,
+                                                             float *__restrict__ H,
+                                                             float *__restrict__ KL)
+{
+    constexpr int WAVES = THREADS / 64;
+    __shared__ float s_max[2][WAVES];
+    __shared__ double s_sum[4][WAVES];
+
+    const int r = blockIdx.x;
+    const int t = threadIdx.x;
+    const float *ar = a + (size_t)r * V;
+    const float *br = HAS_B ? b + (size_t)r * V : nullptr;
+
+    Partial p;
+    part_init(p);
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (VEC) { // V % 4 == 0 and 16-byte aligned rows
+        const float4 *a4 = reinterpret_cast<const float4 *>(ar);
+        const float4 *b4 = reinterpret_cast<const float4 *>(br);
+        const int nvec = V >> 2;
+        int i = t;
+        for (; i + 3 * THREADS < nvec; i += 4 * THREADS) {
+            const float4 a0 = a4[i], a1 = a4[i + THREADS], a2 = a4[i + 2 * THREADS],
+                         a3 = a4[i + 3 * THREADS];
+            float4 b0 = zero4, b1 = zero4, b2 = zero4, b3 = zero4;
+            if (HAS_B) {
+                b0 = b4[i];
+                b1 = b4[i + THREADS];
+                b2 = b4[i + 2 * THREADS];
+                b3 = b4[i + 3 * THREADS];
+            }
+            add_vec<HAS_B>(p, a0, b0);
+            add_vec<HAS_B>(p, a1, b1);
+            add_vec<HAS_B>(p, a2, b2);
+            add_vec<HAS_B>(p, a3, b3);
+        }
+        for (; i < nvec; i += THREADS)
+            add_vec<HAS_B>(p, a4[i], HAS_B ? b4[i] : zero4);
+    } else {
+        for (int i = t; i < V; i += THREADS) {
+            const float av = ar[i];
+            const float bv = HAS_B ? br[i] : 0.0f;
+            raise_max_a(p, av);
+            if (HAS_B)
+                raise_max_b(p, bv);
+            add_one<HAS_B>(p, av, bv);
+        }
+    }
+
+    // Row maxima.
+    const int wave = t >> 6, lane = t & 63;
+    float gm = wave_max(p.m), gmb = wave_max(p.mb);
+    if (lane == 0) {
+        s_max[0][wave] = gm;
+        s_max[1][wave] = gmb;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < WAVES; w++) {
+        gm = fmaxf(gm, s_max[0][w]);
+        gmb = fmaxf(gmb, s_max[1][w]);
+    }
+    // Rescale this lane's partial to the row maxima, then sum in double.
+    double S = 0.0, U = 0.0, D = 0.0, Sb = 0.0;
+    if (p.S > 0.0f) {
+        const float d = p.m - gm;
+        const double c = (double)expf(d);
+        S = c * (double)p.S;
+        U = c * ((double)p.U + (double)d * (double)p.S);
+        D = c * (double)p.D;
+    }
+    if (HAS_B && p.Sb > 0.0f)
+        Sb = (double)expf(p.mb - gmb) * (double)p.Sb;
+    S = wave_sum(S);
+    U = wave_sum(U);
+    if (HAS_B) {
+        D = wave_sum(D);
+        Sb = wave_sum(Sb);
+    }
+    if (lane == 0) {
+        s_sum[0][wave] = S;
+        s_sum[1][wave] = U;
+        s_sum[2][wave] = D;
+        s_sum[3][wave] = Sb;
+    }
+    __syncthreads();
+    if (t == 0) {
+        S = U = D = Sb = 0.0;
+        for (int w = 0; w < WAVES; w++) {
+            S += s_sum[0][w];
+            U += s_sum[1][w];
+            D += s_sum[2][w];
+            Sb += s_sum[3][w];
+        }
+        H[r] = (float)(log(S) - U / S);
+        if (HAS_B)
+            KL[r] = (float)(D / S + ((double)gmb - (double)gm) + log(Sb / S));
+    }
+}
+
+template <int THREADS>
+hipError_t launch(const float *a, const float *b, int R, int V, float *H, float *KL,
+                  hipStream_t stream)
+{
+    const bool vec = (V % 4 == 0) && (((uintptr_t)a & 15) == 0) && (!b || ((uintptr_t)b & 15) == 0);
+    const dim3 grid((unsigned)R), block(THREADS);
+    if (b) {
+        if (vec)
+            entropy_kl_kernel<THREADS, true, true><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+        else
+            entropy_kl_kernel<THREADS, true, false><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+    } else {
+        if (vec)
+            entropy_kl_kernel<THREADS, false, true><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+        else
+            entropy_kl_kernel<THREADS, false, false><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+    }
+    return hipGetLastError();
+}
+
+} // namespace
+
+hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
+                                hipStream_t stream)
+{
+    if (R == 0)
+        return hipSuccess;
+    // Few rows: one large workgroup per row keeps more loads in flight for the
+    // latency-bound single-vector case; many rows: 256 threads, several rows per CU.
+    if (R < 512)
+        return launch<1024>(a, b, R, V, H, KL, stream);
+    return launch<256>(a, b, R, V, H, KL, stream);
+}

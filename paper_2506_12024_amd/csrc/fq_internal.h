@@ -1,0 +1,43 @@
+// Internal declarations shared by the host API and the kernel files.
+#ifndef FQ_INTERNAL_H
+#define FQ_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// One linear of a launch: which resident copies exist and where x and y live.
+// Plain data, passed by value in the kernel arguments (single call) or read
+// from a device table (plan).
+struct FqLinearDesc {
+    const uint8_t *codes4;  // [N][K/2] or null
+    const float *scales4;   // [N][K/128]
+    const uint8_t *zeros4;  // [N][K/128]
+    const uint8_t *codes8;  // [N][K] or null
+    const float *scales8;
+    const uint8_t *zeros8;
+    const uint16_t *w16;    // fp16 [N][K] or null
+    const uint16_t *x;      // fp16 [M][K]
+    uint16_t *y;            // fp16 [M][N]
+    int N;
+    int K;
+    int tile_begin;         // first row tile of this entry in the plan's global tile numbering
+    int pad;
+};
+
+hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, void *codes,
+                              void *scales, void *zeros, hipStream_t stream);
+
+hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
+                                hipStream_t stream);
+
+// Skinny (decode) linears.  `descs` is a device table of `count` entries when
+// `single` is null, else the one entry is passed by value and bits_host applies.
+hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
+                            const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
+                            int total_tiles, int max_K, int M, hipStream_t stream);
+int fq_decode_rows_per_tile(int M);
+
+// Prefill-shaped dequant-GEMM on MFMA.
+hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream);
+
+#endif

@@ -1,0 +1,106 @@
+"""Host-side logic of the C ABI, checked without a GPU: the library loads, exports every
+symbol include/flexq.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_12024_amd as fq
+from paper_2506_12024_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "flexq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS), "binding.EXPORTS and include/flexq.h disagree"
+    for n in names:
+        assert hasattr(fq.lib, n), n
+
+
+def test_packed_sizes():
+    assert fq.fq_packed_sizes(4096, 4096, 4) == (4096 * 4096 // 2, 4096 * 32 * 4, 4096 * 32)
+    assert fq.fq_packed_sizes(11008, 4096, 8) == (11008 * 4096, 11008 * 32 * 4, 11008 * 32)
+    for args, code in [((4096, 4096, 3, 128), B.FQ_ERR_BITS), ((4096, 4000, 4, 128), B.FQ_ERR_SHAPE),
+                       ((0, 4096, 4, 128), B.FQ_ERR_SHAPE), ((16, 256, 4, 64), B.FQ_ERR_SHAPE)]:
+        with pytest.raises(fq.FlexqError) as ei:
+            fq.fq_packed_sizes(*args)
+        assert ei.value.code == code
+        assert fq.fq_last_error()
+
+
+FAKE = 0x1000  # a non-NULL, 16-byte aligned value; never dereferenced: validation fails first
+
+
+def test_quantize_validation():
+    L = fq.lib
+    assert L.fq_quantize(None, 16, 256, 4, 128, FAKE, FAKE, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_quantize(FAKE, 16, 256, 5, 128, FAKE, FAKE, FAKE, None) == B.FQ_ERR_BITS
+    assert L.fq_quantize(FAKE, 16, 200, 4, 128, FAKE, FAKE, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_quantize(FAKE + 2, 16, 256, 4, 128, FAKE, FAKE, FAKE, None) == B.FQ_ERR_ALIGN
+    assert b"alignment" in L.fq_last_error()
+
+
+def test_layer_and_linear_validation():
+    L = fq.lib
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 16, 200, 128) == B.FQ_ERR_SHAPE
+    assert L.fq_layer_create(None, 16, 256, 128) == B.FQ_ERR_NULL
+    assert L.fq_layer_create(ctypes.byref(h), 16, 256, 128) == B.FQ_OK
+    assert L.fq_layer_attach(h, 3, FAKE, FAKE, FAKE) == B.FQ_ERR_BITS
+    assert L.fq_layer_attach(h, 4, None, FAKE, FAKE) == B.FQ_ERR_NULL
+    assert L.fq_layer_attach(h, 4, FAKE, None, FAKE) == B.FQ_ERR_NULL
+    assert L.fq_layer_attach(h, 4, FAKE + 8, FAKE, FAKE) == B.FQ_ERR_ALIGN
+    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_layer_attach(None, 4, FAKE, FAKE, FAKE) == B.FQ_ERR_NULL
+    # linear: every rejection happens before a launch
+    assert L.fq_linear(h, 8, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
+    assert L.fq_linear(h, 16, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
+    assert L.fq_linear(h, 5, FAKE, 1, FAKE, None) == B.FQ_ERR_BITS
+    assert L.fq_linear(h, 4, None, 1, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linear(h, 4, FAKE, 0, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_linear(h, 4, FAKE + 4, 1, FAKE, None) == B.FQ_ERR_ALIGN
+    assert L.fq_linear(None, 4, FAKE, 1, FAKE, None) == B.FQ_ERR_NULL
+    # plan validation
+    p = ctypes.c_void_p()
+    arr = (ctypes.c_void_p * 1)
+    assert L.fq_plan_workspace_bytes(0) == 0
+    ws = L.fq_plan_workspace_bytes(3)
+    assert ws >= 3 * 64 and ws % 256 == 0
+    assert L.fq_plan_create(ctypes.byref(p), 0, arr(h), arr(FAKE), arr(FAKE), 1, FAKE, 4096, None) == B.FQ_ERR_SHAPE
+    assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(FAKE), arr(FAKE), 33, 0x1000, 4096, None) == B.FQ_ERR_SHAPE
+    assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(FAKE), arr(FAKE), 1, 0x1000, 8, None) == B.FQ_ERR_SHAPE
+    assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(FAKE), arr(FAKE), 1, 0x1010, 4096, None) == B.FQ_ERR_ALIGN
+    assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(None), arr(FAKE), 1, 0x1000, 4096, None) == B.FQ_ERR_NULL
+    assert L.fq_plan_run(None, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_plan_destroy(None) == B.FQ_ERR_NULL
+    assert L.fq_layer_destroy(h) == B.FQ_OK
+    assert L.fq_layer_destroy(None) == B.FQ_ERR_NULL
+
+
+def test_entropy_validation():
+    L = fq.lib
+    assert L.fq_entropy_kl(FAKE, None, 1, 0, FAKE, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_entropy_kl(FAKE, None, -1, 8, FAKE, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_entropy_kl(None, None, 1, 8, FAKE, None, None) == B.FQ_ERR_NULL
+    assert L.fq_entropy_kl(FAKE, FAKE, 1, 8, FAKE, None, None) == B.FQ_ERR_NULL
+    assert L.fq_entropy_kl(FAKE, None, 1, 8, FAKE, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_entropy_kl(FAKE + 2, None, 1, 8, FAKE, None, None) == B.FQ_ERR_ALIGN
+    # R = 0 is valid and launches nothing
+    assert L.fq_entropy_kl(FAKE, None, 0, 8, FAKE, None, None) == B.FQ_OK
+
+
+def test_package_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2506_12024_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("no oracle", ""), os.path.join(dirpath, f)
