@@ -51,7 +51,7 @@ struct fq_layer {
 
 struct fq_plan {
     uint32_t magic;
-    int count, M, total_tiles, max_K;
+    int count, M, total_tiles, tile_rows, max_K;
     const FqLinearDesc *table_dev;
 };
 
@@ -200,9 +200,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
     fill_desc(d, layer, x_fp16, y_fp16);
     hipError_t e;
     if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
-        const int rows = fq_decode_rows_per_tile(M);
+        const int rows = fq_decode_tile_rows(layer->N, layer->K, M);
         const int tiles = (layer->N + rows - 1) / rows;
-        e = fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, layer->K, M, (hipStream_t)stream);
+        e = fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
     }
@@ -236,9 +236,18 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     if (reinterpret_cast<uintptr_t>(workspace) & 255u)
         return fail(FQ_ERR_ALIGN, "fq_plan_create: workspace must be 256-byte aligned");
     std::vector<FqLinearDesc> table((size_t)count);
-    const int rows = fq_decode_rows_per_tile(M);
-    long long tiles = 0;
+    long long tiles = 0, total_rows = 0;
     int max_K = 0;
+    for (int i = 0; i < count; i++) {
+        if (int rc = check_layer(layers[i]))
+            return rc;
+        total_rows += layers[i]->N;
+        if (layers[i]->K > max_K)
+            max_K = layers[i]->K;
+    }
+    if (max_K > MAX_DECODE_K)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create: K=%d exceeds the decode limit %d", max_K, MAX_DECODE_K);
+    const int rows = fq_decode_tile_rows(total_rows, max_K, M);
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;
@@ -277,6 +286,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     p->M = M;
     p->total_tiles = (int)tiles;
     p->max_K = max_K;
+    p->tile_rows = rows;
     p->table_dev = (const FqLinearDesc *)workspace;
     *out = p;
     return FQ_OK;
@@ -291,7 +301,7 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
     if (reinterpret_cast<uintptr_t>(bits_dev) & 3u)
         return fail(FQ_ERR_ALIGN, "fq_plan_run: bits_dev must be 4-byte aligned");
     hipError_t e = fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count,
-                                    plan->total_tiles, plan->max_K, plan->M, (hipStream_t)stream);
+                                    plan->total_tiles, plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

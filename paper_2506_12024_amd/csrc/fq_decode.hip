@@ -6,12 +6,21 @@
 // everything else (x, per-slice sums of x) in LDS.
 //
 // Work list.  A launch serves one linear (descriptor passed by value) or a
-// table of independent linears (plan).  Rows are cut into tiles of 16
-// (4 wavefronts x 4 rows); tiles of all entries are numbered consecutively and
-// workgroup b takes tiles b, b + gridDim, ...  The bit-width of an entry is a
+// table of independent linears (plan).  Rows are cut into tiles of `tile_rows`
+// (a multiple of 16: 4 wavefronts x chunks of 4 rows; small for a single linear
+// so that every CU gets work, large for a plan so that staging x is amortised);
+// tiles of all entries are numbered consecutively and workgroup b takes tiles
+// b, b + gridDim, ...  The bit-width of an entry is a
 // run-time value (host argument or device array): all three inner loops live
 // in the one kernel and the choice is a wavefront-uniform branch, so switching
 // precision per token costs a pointer select and nothing else.
+//
+// Streaming.  Inside a tile a wavefront walks items = (chunk of 4 rows, slice);
+// an item is four non-temporal 128-bit loads per lane plus the scale and zero
+// of each row's group.  The loads of item i+1 are issued before item i is
+// computed (two register sets, loop unrolled by two so no set is ever copied),
+// and the first item of a tile is issued before x is staged, so eight loads per
+// lane are in flight almost all the time.
 //
 // Inner loop, 4-bit.  A lane owns 32 consecutive codes (16 bytes) of a row:
 // slice j of the row covers k = 2048 j + 32 lane .. +31, all inside one
@@ -33,12 +42,28 @@
 
 namespace {
 
+#define FQ_GLOBAL __attribute__((address_space(1)))
+
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit load through an explicitly global pointer (global_load_dwordx4, vmcnt only).
+__device__ __forceinline__ uint4 load16_global(const void *p)
+{
+    const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 constexpr int WG_THREADS = 256;
 constexpr int WAVES = WG_THREADS / 64;
 constexpr int ROWS_PER_WAVE = 4;
-constexpr int TILE_ROWS = WAVES * ROWS_PER_WAVE;
+constexpr int TILE_ROWS_MIN = WAVES * ROWS_PER_WAVE;
+
+template <class T>
+__device__ __forceinline__ const FQ_GLOBAL T *as_global(const void *p)
+{
+    return (const FQ_GLOBAL T *)p;
+}
 
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
 {
@@ -75,14 +100,17 @@ __device__ __forceinline__ int block_pos(int b)
     return b;
 }
 
+// k covered by one wavefront slice: 64 lanes x 16 bytes of codes
+__device__ __forceinline__ int slice_span(int bits) { return bits == 4 ? 2048 : (bits == 8 ? 1024 : 512); }
+
 __device__ __forceinline__ int padded_k(int K, int bits)
 {
-    const int span = bits == 4 ? 2048 : (bits == 8 ? 1024 : 512); // k per wavefront slice
+    const int span = slice_span(bits);
     return (K + span - 1) / span * span;
 }
 
 template <int BITS>
-__device__ __forceinline__ void stage_x(const uint16_t *__restrict__ x, int K, uint4 *lds)
+__device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
 {
     const int Kp = padded_k(K, BITS);
     const int nblk = Kp >> 3;
@@ -90,7 +118,7 @@ __device__ __forceinline__ void stage_x(const uint16_t *__restrict__ x, int K, u
     for (int b = threadIdx.x; b < nblk; b += WG_THREADS) {
         uint4 v = make_uint4(0, 0, 0, 0);
         if (b * 8 < K)
-            v = reinterpret_cast<const uint4 *>(x)[b];
+            v = load16_global(x + (size_t)b * 8);
         if (BITS == 16) {
             lds[b] = v;
             continue;
@@ -131,47 +159,72 @@ __device__ __forceinline__ void stage_x(const uint16_t *__restrict__ x, int K, u
     }
 }
 
-// ---- per-wavefront row block: 4 rows x full K ---------------------------------
+// ---- items --------------------------------------------------------------------
 
-struct RowOut {
-    float acc[ROWS_PER_WAVE];
+// What one lane holds for one item: 4 rows x (16 bytes of codes, scale, zero).
+struct Loaded {
+    uint4 w[ROWS_PER_WAVE];
+    float s[ROWS_PER_WAVE];
+    uint32_t z[ROWS_PER_WAVE];
 };
 
-__device__ __forceinline__ void rows_w4(const FqLinearDesc &d, int row0, const uint4 *lds,
-                                        RowOut &out)
+// The copy of one entry selected by the call's bit-width (wavefront-uniform).
+struct Sel {
+    const uint8_t *codes; // fp16 weights for 16
+    const float *scales;
+    const uint8_t *zeros;
+    int N, K;
+};
+
+// 128-bit streaming load: the weights are read once, keep them out of the caches' way.
+__device__ __forceinline__ uint4 load16_stream(const void *p)
+{
+    const u32x4 v = __builtin_nontemporal_load((const FQ_GLOBAL u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Issue the global loads of item (rows row0..row0+3, slice j).  Rows past N and lanes
+// past K are clamped to valid addresses (their results are discarded: the row is not
+// stored, the lane's x is zero).
+template <int BITS>
+__device__ __forceinline__ void issue(const Sel &d, int row0, int j, Loaded &L)
 {
     const int lane = threadIdx.x & 63;
-    const int K = d.K, G = K >> 7;
-    const int nslice = (K + 2047) >> 11;
-    const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 4) >> 3));
-    size_t rowoff[ROWS_PER_WAVE];
+    const uint32_t K = (uint32_t)d.K, G = K >> 7;
+    constexpr int CODES = BITS == 4 ? 32 : (BITS == 8 ? 16 : 8); // per lane per slice
+    const uint32_t k0 = min((uint32_t)(j * 64 + lane) * CODES, K - CODES);
+    const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t byte0 = BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
 #pragma unroll
-    for (int r = 0; r < ROWS_PER_WAVE; r++)
-        rowoff[r] = (size_t)min(row0 + r, d.N - 1);
-    // The two exponent patterns live in VGPRs (hidden from constant folding) so that
-    // mask-and-merge is one v_and_or_b32 with the mask on the scalar bus.
-    uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
-    asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
-    for (int j = 0; j < nslice; j++) {
-        const int k0 = j * 2048 + lane * 32;
-        const int k0c = min(k0, K - 32); // lanes past K read a valid address; their x is zero
-        uint4 w[ROWS_PER_WAVE];
-        float s[ROWS_PER_WAVE];
-        uint32_t z[ROWS_PER_WAVE];
-#pragma unroll
-        for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            w[r] = *reinterpret_cast<const uint4 *>(d.codes4 + rowoff[r] * (size_t)(K >> 1) + (k0c >> 1));
-            s[r] = d.scales4[rowoff[r] * G + (k0c >> 7)];
-            z[r] = d.zeros4[rowoff[r] * G + (k0c >> 7)];
+    for (int r = 0; r < ROWS_PER_WAVE; r++) {
+        const uint32_t row = (uint32_t)min(row0 + r, d.N - 1);
+        L.w[r] = load16_stream(d.codes + (size_t)row * row_bytes + byte0);
+        if (BITS != 16) {
+            L.s[r] = as_global<float>(d.scales)[(size_t)row * G + (k0 >> 7)];
+            L.z[r] = as_global<uint8_t>(d.zeros)[(size_t)row * G + (k0 >> 7)];
         }
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void compute(int K, int j, const Loaded &L, const uint4 *lds,
+                                        float (&acc)[ROWS_PER_WAVE])
+{
+    const int lane = threadIdx.x & 63;
+    if (BITS == 4) {
+        const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 4) >> 3));
+        // The two exponent patterns live in VGPRs (hidden from constant folding) so that
+        // mask-and-merge is one v_and_or_b32 with the mask on the scalar bus.
+        uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
+        asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
         uint4 xb[4];
 #pragma unroll
         for (int i = 0; i < 4; i++)
             xb[i] = lds[(j * 4 + i) * 64 + lane];
-        const float2 cs = sums[j * 64 + lane]; // (1024 sum_even + 64 sum_odd, sum)
+        const float2 cs = sums[j * 64 + lane]; // (1024 sum_even x + 64 sum_odd x, sum x)
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            const uint32_t ww[4] = {w[r].x, w[r].y, w[r].z, w[r].w};
+            const uint32_t ww[4] = {L.w[r].x, L.w[r].y, L.w[r].z, L.w[r].w};
             float a = 0.0f;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
@@ -185,41 +238,17 @@ __device__ __forceinline__ void rows_w4(const FqLinearDesc &d, int row0, const u
                 a = dot2(t2, xb[i].z, a);
                 a = dot2(t3, xb[i].w, a);
             }
-            const float part = a - cs.x - (float)z[r] * cs.y;
-            out.acc[r] += s[r] * part;
+            const float part = a - cs.x - (float)L.z[r] * cs.y;
+            acc[r] += L.s[r] * part;
         }
-    }
-}
-
-__device__ __forceinline__ void rows_w8(const FqLinearDesc &d, int row0, const uint4 *lds,
-                                        RowOut &out)
-{
-    const int lane = threadIdx.x & 63;
-    const int K = d.K, G = K >> 7;
-    const int nslice = (K + 1023) >> 10;
-    const float *sums = reinterpret_cast<const float *>(lds + (padded_k(K, 8) >> 3));
-    size_t rowoff[ROWS_PER_WAVE];
-#pragma unroll
-    for (int r = 0; r < ROWS_PER_WAVE; r++)
-        rowoff[r] = (size_t)min(row0 + r, d.N - 1);
-    for (int j = 0; j < nslice; j++) {
-        const int k0 = j * 1024 + lane * 16;
-        const int k0c = min(k0, K - 16);
-        uint4 w[ROWS_PER_WAVE];
-        float s[ROWS_PER_WAVE];
-        uint32_t z[ROWS_PER_WAVE];
-#pragma unroll
-        for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            w[r] = *reinterpret_cast<const uint4 *>(d.codes8 + rowoff[r] * (size_t)K + k0c);
-            s[r] = d.scales8[rowoff[r] * G + (k0c >> 7)];
-            z[r] = d.zeros8[rowoff[r] * G + (k0c >> 7)];
-        }
+    } else if (BITS == 8) {
+        const float *sums = reinterpret_cast<const float *>(lds + (padded_k(K, 8) >> 3));
         const uint4 x0 = lds[(j * 2 + 0) * 64 + lane], x1 = lds[(j * 2 + 1) * 64 + lane];
         const uint32_t xx[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
         const float sx = sums[j * 64 + lane];
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            const uint32_t ww[4] = {w[r].x, w[r].y, w[r].z, w[r].w};
+            const uint32_t ww[4] = {L.w[r].x, L.w[r].y, L.w[r].z, L.w[r].w};
             float a = 0.0f;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
@@ -229,38 +258,19 @@ __device__ __forceinline__ void rows_w8(const FqLinearDesc &d, int row0, const u
                 a = dot2(lo, xx[2 * i], a);
                 a = dot2(hi, xx[2 * i + 1], a);
             }
-            const float part = a - (1024.0f + (float)z[r]) * sx;
-            out.acc[r] += s[r] * part;
+            const float part = a - (1024.0f + (float)L.z[r]) * sx;
+            acc[r] += L.s[r] * part;
         }
-    }
-}
-
-__device__ __forceinline__ void rows_w16(const FqLinearDesc &d, int row0, const uint4 *lds,
-                                         RowOut &out)
-{
-    const int lane = threadIdx.x & 63;
-    const int K = d.K;
-    const int nslice = (K + 511) >> 9;
-    size_t rowoff[ROWS_PER_WAVE];
-#pragma unroll
-    for (int r = 0; r < ROWS_PER_WAVE; r++)
-        rowoff[r] = (size_t)min(row0 + r, d.N - 1);
-    for (int j = 0; j < nslice; j++) {
-        const int k0 = j * 512 + lane * 8;
-        const int k0c = min(k0, K - 8);
-        uint4 w[ROWS_PER_WAVE];
-#pragma unroll
-        for (int r = 0; r < ROWS_PER_WAVE; r++)
-            w[r] = *reinterpret_cast<const uint4 *>(d.w16 + rowoff[r] * (size_t)K + k0c);
+    } else {
         const uint4 xv = lds[j * 64 + lane];
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            float a = out.acc[r];
-            a = dot2(w[r].x, xv.x, a);
-            a = dot2(w[r].y, xv.y, a);
-            a = dot2(w[r].z, xv.z, a);
-            a = dot2(w[r].w, xv.w, a);
-            out.acc[r] = a;
+            float a = acc[r];
+            a = dot2(L.w[r].x, xv.x, a);
+            a = dot2(L.w[r].y, xv.y, a);
+            a = dot2(L.w[r].z, xv.z, a);
+            a = dot2(L.w[r].w, xv.w, a);
+            acc[r] = a;
         }
     }
 }
@@ -270,73 +280,108 @@ __device__ __forceinline__ uint16_t to_half_bits(float f)
     return __builtin_bit_cast(uint16_t, (_Float16)f);
 }
 
+// One tile for one wavefront: rows [row_begin, row_end) in chunks of 4, all slices.
+// `need_stage`: x of this entry is not in LDS yet (uniform over the workgroup).
+template <int BITS>
+__device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16_t *y, int row_begin,
+                                         int row_end, bool need_stage, uint4 *lds)
+{
+    const int lane = threadIdx.x & 63;
+    const int nslice = (d.K + slice_span(BITS) - 1) / slice_span(BITS);
+    const int nchunk = row_end > row_begin ? (row_end - row_begin + ROWS_PER_WAVE - 1) / ROWS_PER_WAVE : 0;
+    const int nitem = nchunk * nslice;
+    Loaded A, B;
+    // weights do not depend on x: get the first item moving before the staging barrier
+    if (nitem > 0)
+        issue<BITS>(d, row_begin, 0, A);
+    if (need_stage) {
+        __syncthreads(); // every wavefront is done reading the previous x
+        stage_x<BITS>(x, d.K, lds);
+        __syncthreads();
+    }
+    float acc[ROWS_PER_WAVE] = {0.f, 0.f, 0.f, 0.f};
+    int c = 0, j = 0; // chunk and slice of the item being computed
+    auto finish = [&](int chunk) {
+        const int row0 = row_begin + chunk * ROWS_PER_WAVE;
+#pragma unroll
+        for (int r = 0; r < ROWS_PER_WAVE; r++) {
+            const float v = wave_sum(acc[r]);
+            if (lane == r && row0 + r < row_end)
+                ((FQ_GLOBAL uint16_t *)y)[row0 + r] = to_half_bits(v);
+            acc[r] = 0.0f;
+        }
+    };
+    // One step: issue item i+1 into Lnext, compute item i from Lcur.
+    auto step = [&](int i, Loaded &Lcur, Loaded &Lnext) {
+        int cn = c, jn = j + 1;
+        if (jn == nslice) {
+            jn = 0;
+            cn = c + 1;
+        }
+        if (i + 1 < nitem)
+            issue<BITS>(d, row_begin + cn * ROWS_PER_WAVE, jn, Lnext);
+        compute<BITS>(d.K, j, Lcur, lds, acc);
+        if (jn == 0)
+            finish(c);
+        c = cn;
+        j = jn;
+    };
+    for (int i = 0; i < nitem; i += 2) {
+        step(i, A, B);
+        if (i + 1 < nitem)
+            step(i + 1, B, A);
+    }
+}
+
 template <bool SINGLE>
 __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDesc single,
                                                                int bits_host,
                                                                const FqLinearDesc *__restrict__ table,
                                                                const int32_t *__restrict__ bits_dev,
-                                                               int count, int total_tiles)
+                                                               int count, int total_tiles,
+                                                               int tile_rows)
 {
     extern __shared__ uint4 lds[];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    int cur = -1; // entry whose x is staged
+    const int wave = threadIdx.x >> 6;
+    const int wave_rows = tile_rows / WAVES; // multiple of 4
     int e = 0;
+    int staged = -1; // entry whose x is in LDS
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
-        FqLinearDesc d;
+        const FqLinearDesc *dp;
         int bits;
         if (SINGLE) {
-            d = single;
+            dp = &single;
             bits = bits_host;
         } else {
             // tiles are visited in increasing order: advance the entry cursor
             while (e + 1 < count && tile >= table[e + 1].tile_begin)
                 e++;
-            d = table[e];
+            dp = &table[e];
             bits = bits_dev[e];
         }
-        const bool ok = (bits == 4 && d.codes4) || (bits == 8 && d.codes8) || (bits == 16 && d.w16);
-        if (!ok)
-            continue; // uniform: a skipped entry leaves its y untouched
-        if (cur != e) {
-            __syncthreads(); // every wavefront is done reading the previous x
-            if (bits == 4)
-                stage_x<4>(d.x, d.K, lds);
-            else if (bits == 8)
-                stage_x<8>(d.x, d.K, lds);
-            else
-                stage_x<16>(d.x, d.K, lds);
-            __syncthreads();
-            cur = e;
-        }
-        const int row0 = (tile - d.tile_begin) * TILE_ROWS + wave * ROWS_PER_WAVE;
-        if (row0 >= d.N)
-            continue; // no barrier is skipped by this: the next staging syncs all wavefronts
-        RowOut out;
-#pragma unroll
-        for (int r = 0; r < ROWS_PER_WAVE; r++)
-            out.acc[r] = 0.0f;
+        Sel d;
+        d.N = dp->N;
+        d.K = dp->K;
+        // the switch of precision: a pointer select on resident copies
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        if (!d.codes)
+            continue; // uniform: an entry without a copy at this bit-width is skipped, y untouched
+        const int row_begin = min((tile - dp->tile_begin) * tile_rows + wave * wave_rows, d.N);
+        const int row_end = min(row_begin + wave_rows, d.N);
+        const bool need_stage = staged != e;
+        staged = e;
         if (bits == 4)
-            rows_w4(d, row0, lds, out);
+            run_tile<4>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
         else if (bits == 8)
-            rows_w8(d, row0, lds, out);
+            run_tile<8>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
         else
-            rows_w16(d, row0, lds, out);
-#pragma unroll
-        for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            const float v = wave_sum(out.acc[r]);
-            if (lane == r && row0 + r < d.N)
-                d.y[row0 + r] = to_half_bits(v);
-        }
+            run_tile<16>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
     }
 }
 
 } // namespace
-
-int fq_decode_rows_per_tile(int M)
-{
-    (void)M;
-    return TILE_ROWS;
-}
 
 static size_t lds_bytes_for(int max_K)
 {
@@ -345,24 +390,56 @@ static size_t lds_bytes_for(int max_K)
     return kp * 2 + kp / 32 * 8 + 64;
 }
 
+// Workgroups that can be resident at once on the current device: a persistent grid must
+// not exceed it, or late workgroups would start a full pass late.
+static int resident_workgroups(size_t lds)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 256 * 4;
+        cus = prop.multiProcessorCount;
+    }
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_m1_kernel<false>, WG_THREADS, lds) !=
+            hipSuccess || per_cu < 1)
+        per_cu = 2;
+    return cus * per_cu;
+}
+
+int fq_decode_tile_rows(long long total_rows, int max_K, int M)
+{
+    (void)M;
+    // Largest tile (fewest x stagings) that still leaves every resident workgroup
+    // several tiles, so that the static round-robin stays balanced.
+    const long long cap = resident_workgroups(lds_bytes_for(max_K));
+    int rows = 128;
+    while (rows > TILE_ROWS_MIN && total_rows / rows < 8 * cap)
+        rows >>= 1;
+    return rows;
+}
+
 hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int max_K, int M, hipStream_t stream)
+                            int total_tiles, int tile_rows, int max_K, int M, hipStream_t stream)
 {
     (void)M;
     if (total_tiles <= 0)
         return hipSuccess;
     const size_t lds = lds_bytes_for(max_K);
-    // Persistent-style grid: enough workgroups to fill 256 CUs several times over,
-    // never more than there are tiles.
-    const int grid = total_tiles < 2048 ? total_tiles : 2048;
+    const int cap = resident_workgroups(lds);
+    const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
         decode_m1_kernel<true><<<grid, WG_THREADS, lds, stream>>>(*single, bits_host, nullptr,
-                                                                  nullptr, 1, total_tiles);
+                                                                  nullptr, 1, total_tiles, tile_rows);
     } else {
         FqLinearDesc none = {};
         decode_m1_kernel<false><<<grid, WG_THREADS, lds, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                   count, total_tiles);
+                                                                   count, total_tiles, tile_rows);
     }
     return hipGetLastError();
 }
+
+extern "C" int fq_debug_decode_grid(int max_K) { return resident_workgroups(lds_bytes_for(max_K)); }

@@ -34,8 +34,9 @@ hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, fl
 // `single` is null, else the one entry is passed by value and bits_host applies.
 hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int max_K, int M, hipStream_t stream);
-int fq_decode_rows_per_tile(int M);
+                            int total_tiles, int tile_rows, int max_K, int M, hipStream_t stream);
+// Rows per tile (multiple of 16) for a launch that covers `total_rows` output rows.
+int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 
 // Prefill-shaped dequant-GEMM on MFMA.
 hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream);
