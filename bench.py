@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+Workload (default): the Llama-7B-shaped decode stack at batch 1 -- 32 layers x
+{q,k,v,o 4096x4096; gate,up 4096->11008; down 11008->4096}, group-128 int4 and
+int8 copies of every weight resident in HBM, the bit-width of every linear drawn
+per token from {4, 8} with p = 1/2 (seeded, 128 distinct patterns), and one
+entropy + KL reduction over a 32000-entry logits pair per token.  One *step* =
+one token = all 224 linears (one plan launch, per-entry bit-widths read from
+device memory) followed by one fq_entropy_kl launch.  Attention, norms,
+embeddings, lm_head, sampling and the KV cache are not part of the path.
+
+Every tensor is synthetic and seeded (module ``synth``); weights are quantized
+on the GPU by fq_quantize.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+# HBM bytes of one plan launch of the default workload measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy (profiles/decode_m1_plan_llama7b_hbm_traffic.md);
+# reported only for that workload.
+MEASURED_TRAFFIC_BYTES = {("llama7b", 1, (4, 8)): 5004389 * 1024}
+N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
+VOCAB = 32000
+SEED = 0
+
+
+def weight_bytes(N: int, K: int, bits: int) -> int:
+    """Bytes a call must read for its weights: packed codes + fp32 scale + u8 zero per
+    group of 128 (bits = 16: the fp16 matrix)."""
+    if bits == 16:
+        return 2 * N * K
+    return N * K * bits // 8 + (N * K // 128) * 5
+
+
+class Stack:
+    """The resident multi-precision weight store of one synthetic model and a plan over it."""
+
+    def __init__(self, name: str, M: int = 1, bit_choices=(4, 8), layers: int | None = None,
+                 verbose: bool = False):
+        import torch
+        import paper_2506_12024_amd as fq
+
+        self.fq, self.torch = fq, torch
+        dev = "cuda:0"
+        n_layers, hidden, ffn, std, outl = synth.STACKS[name]
+        if layers is not None:
+            n_layers = layers
+        self.name, self.M, self.bit_choices = name, M, tuple(bit_choices)
+        self.std, self.outl = std, outl
+        self.entries = []   # (layer index, matrix name, K, N)
+        self.layers, self.xs, self.ys, self.keep = [], [], [], []
+        t0 = time.time()
+        for li in range(n_layers):
+            for mname, K, N in synth.llama_linears(hidden, ffn):
+                w = synth.weight(SEED, self.wname(li, mname), N, K, std, outlier_p=outl)
+                w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
+                layer = fq.Layer(N, K)
+                for b in self.bit_choices:
+                    if b == 16:
+                        layer.attach(16, w_dev)
+                        self.keep.append(w_dev)
+                        continue
+                    cb, sb, zb = fq.fq_packed_sizes(N, K, b)
+                    codes = torch.empty(cb, dtype=torch.uint8, device=dev)
+                    scales = torch.empty(sb // 4, dtype=torch.float32, device=dev)
+                    zeros = torch.empty(zb, dtype=torch.uint8, device=dev)
+                    fq.fq_quantize(w_dev, N, K, b, 128, codes, scales, zeros)
+                    layer.attach(b, codes, scales, zeros)
+                x = synth.activations(SEED, self.xname(li, mname), M, K)
+                self.xs.append(torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16))
+                self.ys.append(torch.zeros((M, N), dtype=torch.float16, device=dev))
+                self.layers.append(layer)
+                self.entries.append((li, mname, K, N))
+            if verbose:
+                print("  built layer %d/%d (%.1f s)" % (li + 1, n_layers, time.time() - t0),
+                      file=sys.stderr, flush=True)
+        torch.cuda.synchronize()
+        n = len(self.layers)
+        self.workspace = torch.empty(fq.Plan.workspace_bytes(n), dtype=torch.uint8, device=dev)
+        self.plan = fq.Plan(self.layers, self.xs, self.ys, M, self.workspace)
+        # per-token bit-width patterns, drawn on the host before timing
+        pats = np.stack([synth.choice(SEED, "%s/bits/step%d" % (name, s), n, self.bit_choices)
+                         for s in range(N_PATTERNS)])
+        self.patterns = pats
+        self.bits_dev = torch.from_numpy(pats).to(dev)
+        # logits pair per step
+        a, b = synth.logits_pair(SEED, "%s/logits" % name, N_PATTERNS * M, VOCAB)
+        self.logits_a = torch.from_numpy(a).to(dev)
+        self.logits_b = torch.from_numpy(b).to(dev)
+        self.logits_host = (a, b)
+        self.H = torch.zeros((N_PATTERNS, M), dtype=torch.float32, device=dev)
+        self.KL = torch.zeros((N_PATTERNS, M), dtype=torch.float32, device=dev)
+        self.build_seconds = time.time() - t0
+
+    def wname(self, li, mname):
+        return "%s/L%d/%s/w" % (self.name, li, mname)
+
+    def xname(self, li, mname):
+        return "%s/L%d/%s/x/M%d" % (self.name, li, mname, self.M)
+
+    def step_bytes(self, s: int) -> int:
+        return sum(weight_bytes(N, K, int(b)) for (_, _, K, N), b in zip(self.entries, self.patterns[s % N_PATTERNS]))
+
+    def run_linears(self, s: int):
+        self.plan.run(self.bits_dev[s % N_PATTERNS])
+
+    def run_entropy(self, s: int):
+        i, M = s % N_PATTERNS, self.M
+        self.fq.fq_entropy_kl(self.logits_a[i * M:(i + 1) * M], self.logits_b[i * M:(i + 1) * M], M, VOCAB,
+                              self.H[i], self.KL[i])
+
+    def step(self, s: int):
+        self.run_linears(s)
+        self.run_entropy(s)
+
+
+def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the
+    first `sample_layers` decoder layers of step 0 (weights regenerated from the same
+    seeds and quantized by the oracle at the drawn bit-width; only the linears and the
+    step's entropy/KL are timed), scaled to the whole stack."""
+    import oracle
+
+    n_layers = synth.STACKS[stack.name][0]
+    sample_layers = min(sample_layers, n_layers)
+    prepared = []
+    for (li, mname, K, N), b in zip(stack.entries, stack.patterns[0]):
+        if li >= sample_layers:
+            break
+        w = synth.weight(SEED, stack.wname(li, mname), N, K, stack.std, outlier_p=stack.outl)
+        x = synth.activations(SEED, stack.xname(li, mname), stack.M, K)
+        b = int(b)
+        packed = (w, None, None) if b == 16 else oracle.quantize(w, b)
+        prepared.append((x, packed, b))
+    a, bl = stack.logits_host
+    M = stack.M
+    t0 = time.perf_counter()
+    for x, (c, s, z), b in prepared:
+        oracle.linear(x, c, s, z, b)
+    t_lin = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.entropy_kl(a[:M], bl[:M])
+    t_ent = time.perf_counter() - t0
+    t_step = t_lin * (n_layers / sample_layers) + t_ent
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": M / t_step, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s, scaled x%.0f) "
+                      "+ entropy/KL of the step's logits (%.4f s)"
+                      % (sample_layers, n_layers, t_lin, n_layers / sample_layers, t_ent)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--stack", default="llama7b", choices=sorted(synth.STACKS))
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--bits", default="4,8", help="bit-widths drawn per layer per token")
+    ap.add_argument("--layers", type=int, default=None, help="truncate the stack (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed region "
+                         "(calibrates HBM byte counters when profiling)")
+    ap.add_argument("--verbose", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+                 "--gpus %d is not supported, run with --gpus 1" % args.gpus)
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    bit_choices = tuple(int(b) for b in args.bits.split(","))
+    stack = Stack(args.stack, M=args.batch, bit_choices=bit_choices, layers=args.layers,
+                  verbose=args.verbose)
+    K_steps, W = args.steps, args.warmup
+    if args.copy_mib > 0:
+        src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for s in range(W):
+        stack.step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(K_steps):
+        stack.step(W + s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    step_bytes = [stack.step_bytes(W + s) for s in range(K_steps)]
+    total_bytes = float(sum(step_bytes))
+
+    # Dominant kernel: the plan launch.  Average duration per launch from HIP events on the
+    # launch stream around K back-to-back launches of the same steps (no entropy launch between).
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for s in range(K_steps):
+        stack.run_linears(W + s)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    lin_ms = e0.elapsed_time(e1) / K_steps
+    e0.record(stream)
+    for s in range(K_steps):
+        stack.run_entropy(W + s)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ent_us = e0.elapsed_time(e1) / K_steps * 1e3
+    alg_bytes = total_bytes / K_steps
+    achieved = alg_bytes / (lin_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "effective weight GB/s + decode tokens/s, mixed W4/W8 Llama-7B-shaped linears",
+        "value": args.batch * K_steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": elapsed / K_steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s decode stack, batch %d, per-layer bits drawn from {%s} per token, "
+                               "%d linears + entropy/KL over %d logits per step"
+                               % (args.stack, args.batch, args.bits, len(stack.layers), VOCAB),
+                   "launches_per_step": 2, "build_seconds": round(stack.build_seconds, 1)},
+        "weight_GBps": total_bytes / elapsed / 1e9,
+        "weight_GB_per_step": alg_bytes / 1e9,
+        "entropy_kl_us": ent_us,
+        "roofline": {"bound": "hbm", "kernel": "decode_m1_kernel (plan launch)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.stack, args.batch, bit_choices))
+                     if args.layers is None else None,
+                     "avg_launch_ms": lin_ms, "algorithmic_bytes_per_launch": alg_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(stack)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
