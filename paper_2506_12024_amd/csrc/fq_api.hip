@@ -200,9 +200,10 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
     fill_desc(d, layer, x_fp16, y_fp16);
     hipError_t e;
     if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
-        const int rows = fq_decode_tile_rows(layer->N, layer->K, M);
+        const int rows = M == 1 ? fq_decode_tile_rows(layer->N, layer->K, M) : fq_skinny_tile_rows(layer->N, M);
         const int tiles = (layer->N + rows - 1) / rows;
-        e = fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream);
+        e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream)
+                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
     }
@@ -247,7 +248,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     }
     if (max_K > MAX_DECODE_K)
         return fail(FQ_ERR_SHAPE, "fq_plan_create: K=%d exceeds the decode limit %d", max_K, MAX_DECODE_K);
-    const int rows = fq_decode_tile_rows(total_rows, max_K, M);
+    const int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;
@@ -300,8 +301,11 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
         return fail(FQ_ERR_NULL, "fq_plan_run: bits_dev is NULL");
     if (reinterpret_cast<uintptr_t>(bits_dev) & 3u)
         return fail(FQ_ERR_ALIGN, "fq_plan_run: bits_dev must be 4-byte aligned");
-    hipError_t e = fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count,
-                                    plan->total_tiles, plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream);
+    hipError_t e = plan->M == 1
+        ? fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
+                           plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream)
+        : fq_launch_skinny(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
+                           plan->tile_rows, plan->M, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

@@ -38,6 +38,12 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
 // Rows per tile (multiple of 16) for a launch that covers `total_rows` output rows.
 int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 
+// Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 64, 128 or 256.
+hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
+                            const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
+                            int total_tiles, int tile_rows, int M, hipStream_t stream);
+int fq_skinny_tile_rows(long long total_rows, int M);
+
 // Prefill-shaped dequant-GEMM on MFMA.
 hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream);
 

@@ -1,0 +1,362 @@
+// Decode-phase weight-only quantized linear for small batches (2 <= M <= 32):
+// y[M][N] = x[M][K] . dequant(W[N][K])^T, dequant = Sec. 2.2 Eq. (3).  Still bound by
+// the weight stream (Sec. 4.1), but M multiply-adds per weight no longer fit the
+// vector ALUs, so the contraction runs on the matrix cores:
+// v_mfma_f32_16x16x32_f16 with A = x (16 batch rows x 32 k) and B = 16 weight rows x
+// 32 k, accumulating in binary32.
+//
+// Streaming side (same as the batch-1 kernel): a wavefront owns RT row tiles of 16
+// weight rows; lane (n = lane % 16, c = lane / 16) reads 16 bytes of row n per load
+// at byte offset 64 * load + 16 * c -- 32 four-bit codes, 16 eight-bit codes or 8
+// halves -- with non-temporal 128-bit loads, double buffered.  One load of a
+// wavefront covers 16 rows x 128 / 64 / 32 k, i.e. 4 / 2 / 1 MFMAs.
+//
+// Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is
+// the pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q;
+// bytes go under 0x64 with v_perm_b32), then one v_pk_add_f16 per register subtracts
+// (offset + z): the MFMA operand is the exact integer q - z.  The products are summed
+// per quantization group in a zeroed accumulator and folded into the output as
+// out += s[n][g] * acc, which is Eq. (3) with the scale factored out of the group.
+//
+// x is staged through LDS in chunks of 1024 k as 16-byte blocks of 8 halves,
+// [k block][batch row], for the 4-bit path permuted inside the block to the order the
+// unpacking produces (x0 x4 x1 x5 x2 x6 x3 x7).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+
+namespace {
+
+#define FQ_GLOBAL __attribute__((address_space(1)))
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int WG_THREADS = 256;
+constexpr int WAVES = WG_THREADS / 64;
+constexpr int KC = 1024; // k per LDS chunk
+
+__device__ __forceinline__ uint4 load16_stream(const void *p)
+{
+    const u32x4 v = __builtin_nontemporal_load((const FQ_GLOBAL u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 load16_global(const void *p)
+{
+    const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b));
+}
+
+struct Sel {
+    const uint8_t *codes;
+    const float *scales;
+    const uint8_t *zeros;
+    int N, K;
+};
+
+template <int RT>
+struct Loaded {
+    uint4 w[RT];
+    float s[RT];
+    uint32_t z[RT];
+};
+
+template <int BITS, int RT>
+__device__ __forceinline__ void issue(const Sel &d, int wave_row0, int li, Loaded<RT> &L)
+{
+    const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+    const uint32_t K = (uint32_t)d.K, G = K >> 7;
+    const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t g = BITS == 4 ? (uint32_t)li : (uint32_t)li >> 1;
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const uint32_t row = (uint32_t)min(wave_row0 + rt * 16 + n, d.N - 1);
+        L.w[rt] = load16_stream(d.codes + (size_t)row * row_bytes + (uint32_t)li * 64 + c * 16);
+        if (BITS != 16) {
+            L.s[rt] = ((const FQ_GLOBAL float *)d.scales)[(size_t)row * G + g];
+            L.z[rt] = ((const FQ_GLOBAL uint8_t *)d.zeros)[(size_t)row * G + g];
+        }
+    }
+}
+
+// Stage x[:, kc .. kc+KC) as blocks [k block][16 * MT rows].
+template <int BITS, int MT>
+__device__ __forceinline__ void stage_chunk(const uint16_t *x, int M, int K, int kc, uint4 *lds)
+{
+    constexpr int ROWS = 16 * MT, BLK = KC / 8;
+    for (int idx = threadIdx.x; idx < ROWS * BLK; idx += WG_THREADS) {
+        const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
+        const int k = kc + kb * 8;
+        if (m >= M || k >= K)
+            continue; // never read: rows past M only feed unused outputs, k past K is not visited
+        uint4 v = load16_global(x + (size_t)m * K + k);
+        if (BITS == 4) {
+            uint4 p;
+            p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u); // (x0, x4)
+            p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u); // (x1, x5)
+            p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u); // (x2, x6)
+            p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u); // (x3, x7)
+            v = p;
+        }
+        lds[kb * ROWS + m] = v;
+    }
+}
+
+__device__ __forceinline__ float4_t mfma(uint4 a, const uint32_t (&b)[4], float4_t c)
+{
+    const u32x4 av = {a.x, a.y, a.z, a.w};
+    const u32x4 bv = {b[0], b[1], b[2], b[3]};
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
+                                                  __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
+}
+
+// One load's worth of work: dequantize L, multiply with the staged x, fold finished groups.
+template <int BITS, int MT, int RT>
+__device__ __forceinline__ void compute(int li, const Loaded<RT> &L, const uint4 *lds,
+                                        float4_t (&acc)[RT][MT], float4_t (&out)[RT][MT])
+{
+    constexpr int ROWS = 16 * MT;
+    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32); // k per load
+    constexpr int NM = KPL / 32;                                 // MFMAs per load
+    const int lane = threadIdx.x & 63, m = lane & 15, c = lane >> 4;
+    const int kk = (li % (KC / KPL)) * KPL + c * (KPL / 4); // lane's first k inside the chunk
+    uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
+    asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
+
+    uint32_t b[RT][NM][4];
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const uint32_t ww[4] = {L.w[rt].x, L.w[rt].y, L.w[rt].z, L.w[rt].w};
+        if (BITS == 4) {
+            const uint32_t z = L.z[rt];
+            const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
+            const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t v = ww[i], v8 = v >> 8;
+                b[rt][i][0] = pk_add((v & 0x000F000Fu) | magic_lo, nz_lo);  // (q0 - z, q4 - z)
+                b[rt][i][1] = pk_add((v & 0x00F000F0u) | magic_hi, nz_hi);  // (q1 - z, q5 - z)
+                b[rt][i][2] = pk_add((v8 & 0x000F000Fu) | magic_lo, nz_lo); // (q2 - z, q6 - z)
+                b[rt][i][3] = pk_add((v8 & 0x00F000F0u) | magic_hi, nz_hi); // (q3 - z, q7 - z)
+            }
+        } else if (BITS == 8) {
+            const uint32_t z = L.z[rt];
+            const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t v = ww[2 * i + h];
+                    b[rt][i][2 * h + 0] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04010400u), nz);
+                    b[rt][i][2 * h + 1] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04030402u), nz);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                b[rt][0][i] = ww[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NM; i++) {
+        uint4 a[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+            a[mt] = lds[((kk >> 3) + i) * ROWS + mt * 16 + m];
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                acc[rt][mt] = mfma(a[mt], b[rt][i], acc[rt][mt]);
+    }
+    // group complete: 4-bit after every load, 8-bit after every second load
+    const bool group_end = BITS == 4 || (BITS == 8 && (li & 1));
+    if (group_end) {
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                out[rt][mt] += L.s[rt] * acc[rt][mt];
+                acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+    }
+}
+
+template <int BITS, int MT, int RT>
+__device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16_t *y, int M,
+                                         int wave_row0, uint4 *lds)
+{
+    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
+    constexpr int LPC = KC / KPL; // loads per chunk
+    const int nload = d.K / KPL;
+    const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+    float4_t acc[RT][MT], out[RT][MT];
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            out[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    Loaded<RT> A, B;
+    issue<BITS, RT>(d, wave_row0, 0, A);
+    auto step = [&](int li, Loaded<RT> &Lcur, Loaded<RT> &Lnext) {
+        if (li + 1 < nload)
+            issue<BITS, RT>(d, wave_row0, li + 1, Lnext);
+        if (li % LPC == 0) {
+            __syncthreads(); // all wavefronts are done with the previous chunk of x
+            stage_chunk<BITS, MT>(x, M, d.K, (li / LPC) * KC, lds);
+            __syncthreads();
+        }
+        compute<BITS, MT, RT>(li, Lcur, lds, acc, out);
+    };
+    for (int li = 0; li < nload; li += 2) {
+        step(li, A, B);
+        if (li + 1 < nload)
+            step(li + 1, B, A);
+    }
+    // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+        const int row = wave_row0 + rt * 16 + n;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            const float4_t v = BITS == 16 ? acc[rt][mt] : out[rt][mt];
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int m = mt * 16 + c * 4 + r;
+                if (m < M && row < d.N)
+                    ((FQ_GLOBAL uint16_t *)y)[(size_t)m * d.N + row] =
+                        __builtin_bit_cast(uint16_t, (_Float16)v[r]);
+            }
+        }
+    }
+}
+
+template <bool SINGLE, int MT, int RT>
+__global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinearDesc single,
+                                                                   int bits_host,
+                                                                   const FqLinearDesc *__restrict__ table,
+                                                                   const int32_t *__restrict__ bits_dev,
+                                                                   int count, int total_tiles, int M)
+{
+    __shared__ uint4 lds[(KC / 8) * 16 * MT];
+    constexpr int TILE_ROWS = WAVES * RT * 16;
+    const int wave = threadIdx.x >> 6;
+    int e = 0;
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+        const FqLinearDesc *dp;
+        int bits;
+        if (SINGLE) {
+            dp = &single;
+            bits = bits_host;
+        } else {
+            while (e + 1 < count && tile >= table[e + 1].tile_begin)
+                e++;
+            dp = &table[e];
+            bits = bits_dev[e];
+        }
+        Sel d;
+        d.N = dp->N;
+        d.K = dp->K;
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        if (!d.codes)
+            continue; // uniform over the workgroup
+        // All wavefronts of the workgroup run the tile (rows past N are clamped on load and
+        // masked on store) so that every one of them reaches the staging barriers.
+        const int wave_row0 = (tile - dp->tile_begin) * TILE_ROWS + wave * RT * 16;
+        if (bits == 4)
+            run_tile<4, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+        else if (bits == 8)
+            run_tile<8, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+        else
+            run_tile<16, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+    }
+}
+
+template <int MT, int RT>
+int resident(int cus)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_skinny_kernel<false, MT, RT>,
+                                                     WG_THREADS, 0) != hipSuccess || per_cu < 1)
+        per_cu = 2;
+    return cus * per_cu;
+}
+
+template <int MT, int RT>
+hipError_t launch(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
+                  const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
+                  hipStream_t stream)
+{
+    const int cap = resident<MT, RT>(cus);
+    const int grid = total_tiles < cap ? total_tiles : cap;
+    if (single) {
+        decode_skinny_kernel<true, MT, RT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr,
+                                                                           nullptr, 1, total_tiles, M);
+    } else {
+        FqLinearDesc none = {};
+        decode_skinny_kernel<false, MT, RT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev,
+                                                                            count, total_tiles, M);
+    }
+    return hipGetLastError();
+}
+
+int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 256;
+        cus = prop.multiProcessorCount;
+    }
+    return cus;
+}
+
+} // namespace
+
+// Rows per workgroup tile: 64 * RT with RT in {1, 2, 4} row tiles per wavefront; the
+// largest that still gives every CU a few tiles.
+int fq_skinny_tile_rows(long long total_rows, int M)
+{
+    (void)M;
+    const long long want = 4LL * device_cus();
+    int rt = 4;
+    while (rt > 1 && total_rows / (64 * rt) < want)
+        rt >>= 1;
+    return 64 * rt;
+}
+
+hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
+                            const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
+                            int total_tiles, int tile_rows, int M, hipStream_t stream)
+{
+    if (total_tiles <= 0)
+        return hipSuccess;
+    const int cus = device_cus();
+    const int rt = tile_rows / 64;
+    if (M <= 16) {
+        if (rt == 4)
+            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        if (rt == 2)
+            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+    }
+    if (rt == 4)
+        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+    if (rt == 2)
+        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+}

@@ -123,6 +123,74 @@ def test_linear_on_grid_weights_exact():
     assert np.array_equal(y.view(np.uint16), y_ref.view(np.uint16))
 
 
+# ------------------------------------------------------------------ linear, batch 2..32 (MFMA)
+
+@pytest.mark.parametrize("bits", [4, 8, 16])
+@pytest.mark.parametrize("M,N,K", [(2, 100, 1408), (4, 4096, 4096), (8, 530, 5120), (16, 64, 11008),
+                                   (17, 300, 2048), (32, 1000, 4096), (5, 37, 128), (32, 16, 13824)])
+def test_linear_batched_matches_oracle(bits, M, N, K):
+    w = synth.weight(0, "par/linb/%dx%d" % (N, K), N, K, 0.02, outlier_p=0.001)
+    x = synth.activations(0, "par/linb/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (bits,))
+    y = gpu_linear(layer, bits, x)
+    if bits == 16:
+        y_ref = oracle.linear(x, w, None, None, 16)
+    else:
+        c, s, z = (t.cpu().numpy() for t in packed[bits])
+        y_ref = oracle.linear(x, c, s, z, bits)
+    assert y.shape == (M, N)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+    # each batch row on its own must also be right (a row mix-up can hide in the max-abs norm)
+    for m in range(M):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_linear_batched_integer_case_exact():
+    # s = 1, z = 0 integer weights and integer x: every operation is exact, the result must
+    # equal the integer matrix product bit for bit (catches any operand-layout mistake).
+    rng = np.random.default_rng(7)
+    for bits, M, N, K in [(4, 16, 48, 1024), (8, 32, 80, 1152), (4, 3, 20, 2048)]:
+        qmax = (1 << bits) - 1
+        w = rng.integers(0, qmax + 1, size=(N, K))
+        w[:, 0::128] = 0
+        w[:, 1::128] = qmax
+        x = rng.integers(-2, 3, size=(M, K))
+        layer, packed = make_layer(w.astype(np.float16), (bits,))
+        assert torch.all(packed[bits][1] == 1.0) and torch.all(packed[bits][2] == 0)
+        y = gpu_linear(layer, bits, x.astype(np.float16))
+        expect = (x @ w.T).astype(np.float16)
+        assert np.array_equal(y.view(np.uint16), expect.view(np.uint16)), (bits, M, N, K)
+
+
+def test_plan_batched_matches_oracle():
+    shapes = [(256, 1024), (100, 1408), (512, 4096), (64, 11008)]
+    for M in (4, 32):
+        layers, xs, ys, xs_np, packs = [], [], [], [], []
+        for i, (N, K) in enumerate(shapes):
+            w = synth.weight(0, "par/planb/w%d" % i, N, K, 0.02, outlier_p=0.001)
+            layer, packed = make_layer(w, (4, 8, 16))
+            x = synth.activations(0, "par/planb/x%d/%d" % (i, M), M, K)
+            layers.append(layer)
+            packs.append((w, packed))
+            xs_np.append(x)
+            xs.append(to_dev(x))
+            ys.append(torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+        ws = torch.empty(fq.Plan.workspace_bytes(len(layers)), dtype=torch.uint8, device=DEV)
+        plan = fq.Plan(layers, xs, ys, M, ws)
+        pattern = [4, 8, 16, 4]
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        for i, b in enumerate(pattern):
+            w, packed = packs[i]
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(ys[i].cpu().numpy(), y_ref) <= TOL_Y, (M, i, b)
+
+
 # ------------------------------------------------------------------ plan (one launch, device bits)
 
 def test_plan_matches_individual_calls_and_oracle():
