@@ -318,8 +318,10 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
             jn = 0;
             cn = c + 1;
         }
-        if (i + 1 < nitem)
-            issue<BITS>(d, row_begin + cn * ROWS_PER_WAVE, jn, Lnext);
+        // Always issued (past the last item it re-reads the last chunk) so that the wait
+        // for Lcur can be a counted vmcnt with Lnext's loads still in flight.
+        const bool more = i + 1 < nitem;
+        issue<BITS>(d, row_begin + (more ? cn : c) * ROWS_PER_WAVE, more ? jn : j, Lnext);
         compute<BITS>(d.K, j, Lcur, lds, acc);
         if (jn == 0)
             finish(c);

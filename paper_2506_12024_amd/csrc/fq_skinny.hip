@@ -9,7 +9,10 @@
 // weight rows; lane (n = lane % 16, c = lane / 16) reads 16 bytes of row n per load
 // at byte offset 64 * load + 16 * c -- 32 four-bit codes, 16 eight-bit codes or 8
 // halves -- with non-temporal 128-bit loads, double buffered.  One load of a
-// wavefront covers 16 rows x 128 / 64 / 32 k, i.e. 4 / 2 / 1 MFMAs.
+// wavefront covers 16 rows x 128 / 64 / 32 k, i.e. 4 / 2 / 1 MFMAs.  Loads are issued
+// in pairs (64 * (2 i) and 64 * (2 i + 1)): a load touches only 64 bytes of each row,
+// and the two halves of a 128-byte line must be requested back to back or HBM
+// delivers the line twice.
 //
 // Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is
 // the pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q;
@@ -23,6 +26,7 @@
 // unpacking produces (x0 x4 x1 x5 x2 x6 x3 x7).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "fq_internal.h"
 
@@ -62,51 +66,67 @@ struct Sel {
     int N, K;
 };
 
+constexpr int KU = 2; // consecutive 64-byte loads per row issued together (one 128-byte line)
+
 template <int RT>
 struct Loaded {
-    uint4 w[RT];
-    float s[RT];
-    uint32_t z[RT];
+    uint4 w[RT][KU];
+    float s[RT][KU];
+    uint32_t z[RT][KU];
 };
 
+// Issue step `st`: loads 2 st and 2 st + 1 of every row tile.
 template <int BITS, int RT>
-__device__ __forceinline__ void issue(const Sel &d, int wave_row0, int li, Loaded<RT> &L)
+__device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int nload, Loaded<RT> &L)
 {
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     const uint32_t K = (uint32_t)d.K, G = K >> 7;
     const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
-    const uint32_t g = BITS == 4 ? (uint32_t)li : (uint32_t)li >> 1;
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
         const uint32_t row = (uint32_t)min(wave_row0 + rt * 16 + n, d.N - 1);
-        L.w[rt] = load16_stream(d.codes + (size_t)row * row_bytes + (uint32_t)li * 64 + c * 16);
-        if (BITS != 16) {
-            L.s[rt] = ((const FQ_GLOBAL float *)d.scales)[(size_t)row * G + g];
-            L.z[rt] = ((const FQ_GLOBAL uint8_t *)d.zeros)[(size_t)row * G + g];
+#pragma unroll
+        for (int ku = 0; ku < KU; ku++) {
+            // an odd number of loads (4-bit, K / 128 odd): the missing one re-reads the last
+            const uint32_t li = (uint32_t)min(st * KU + ku, nload - 1);
+            const uint32_t g = BITS == 4 ? li : li >> 1;
+            L.w[rt][ku] = load16_stream(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
+            if (BITS == 4 || (BITS == 8 && ku == 0)) {
+                L.s[rt][ku] = ((const FQ_GLOBAL float *)d.scales)[(size_t)row * G + g];
+                L.z[rt][ku] = ((const FQ_GLOBAL uint8_t *)d.zeros)[(size_t)row * G + g];
+            }
         }
     }
 }
 
-// Stage x[:, kc .. kc+KC) as blocks [k block][16 * MT rows].
+// Stage x[:, kc .. kc+KC) as blocks [k block][16 * MT rows].  All of a thread's global
+// loads are issued before the first LDS write so that they overlap.
 template <int BITS, int MT>
 __device__ __forceinline__ void stage_chunk(const uint16_t *x, int M, int K, int kc, uint4 *lds)
 {
-    constexpr int ROWS = 16 * MT, BLK = KC / 8;
-    for (int idx = threadIdx.x; idx < ROWS * BLK; idx += WG_THREADS) {
+    constexpr int ROWS = 16 * MT, BLK = KC / 8, PER = ROWS * BLK / WG_THREADS;
+    uint4 v[PER];
+#pragma unroll
+    for (int it = 0; it < PER; it++) {
+        const int idx = it * WG_THREADS + threadIdx.x;
         const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
-        const int k = kc + kb * 8;
-        if (m >= M || k >= K)
-            continue; // never read: rows past M only feed unused outputs, k past K is not visited
-        uint4 v = load16_global(x + (size_t)m * K + k);
+        // rows past M and k past K are clamped: those blocks only feed outputs that are
+        // never stored (rows) or are never read (k)
+        const int mc = min(m, M - 1), k = min(kc + kb * 8, K - 8);
+        v[it] = load16_global(x + (size_t)mc * K + k);
+    }
+#pragma unroll
+    for (int it = 0; it < PER; it++) {
+        const int idx = it * WG_THREADS + threadIdx.x;
+        const int m = idx / BLK, kb = idx % BLK;
+        uint4 p = v[it];
         if (BITS == 4) {
-            uint4 p;
-            p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u); // (x0, x4)
-            p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u); // (x1, x5)
-            p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u); // (x2, x6)
-            p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u); // (x3, x7)
-            v = p;
+            p.x = __builtin_amdgcn_perm(v[it].z, v[it].x, 0x05040100u); // (x0, x4)
+            p.y = __builtin_amdgcn_perm(v[it].z, v[it].x, 0x07060302u); // (x1, x5)
+            p.z = __builtin_amdgcn_perm(v[it].w, v[it].y, 0x05040100u); // (x2, x6)
+            p.w = __builtin_amdgcn_perm(v[it].w, v[it].y, 0x07060302u); // (x3, x7)
         }
-        lds[kb * ROWS + m] = v;
+        lds[kb * ROWS + m] = p;
     }
 }
 
@@ -119,10 +139,12 @@ __device__ __forceinline__ float4_t mfma(uint4 a, const uint32_t (&b)[4], float4
 }
 
 // One load's worth of work: dequantize L, multiply with the staged x, fold finished groups.
-template <int BITS, int MT, int RT>
-__device__ __forceinline__ void compute(int li, const Loaded<RT> &L, const uint4 *lds,
+template <int BITS, int MT, int RT, int ku>
+__device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4 *lds,
                                         float4_t (&acc)[RT][MT], float4_t (&out)[RT][MT])
 {
+    const int li = st * KU + ku;
+    constexpr int zk = BITS == 8 ? 0 : ku; // 8-bit: both loads of a step share one group
     constexpr int ROWS = 16 * MT;
     constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32); // k per load
     constexpr int NM = KPL / 32;                                 // MFMAs per load
@@ -131,40 +153,6 @@ __device__ __forceinline__ void compute(int li, const Loaded<RT> &L, const uint4
     uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
     asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
 
-    uint32_t b[RT][NM][4];
-#pragma unroll
-    for (int rt = 0; rt < RT; rt++) {
-        const uint32_t ww[4] = {L.w[rt].x, L.w[rt].y, L.w[rt].z, L.w[rt].w};
-        if (BITS == 4) {
-            const uint32_t z = L.z[rt];
-            const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
-            const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const uint32_t v = ww[i], v8 = v >> 8;
-                b[rt][i][0] = pk_add((v & 0x000F000Fu) | magic_lo, nz_lo);  // (q0 - z, q4 - z)
-                b[rt][i][1] = pk_add((v & 0x00F000F0u) | magic_hi, nz_hi);  // (q1 - z, q5 - z)
-                b[rt][i][2] = pk_add((v8 & 0x000F000Fu) | magic_lo, nz_lo); // (q2 - z, q6 - z)
-                b[rt][i][3] = pk_add((v8 & 0x00F000F0u) | magic_hi, nz_hi); // (q3 - z, q7 - z)
-            }
-        } else if (BITS == 8) {
-            const uint32_t z = L.z[rt];
-            const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
-#pragma unroll
-            for (int i = 0; i < 2; i++) {
-#pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    const uint32_t v = ww[2 * i + h];
-                    b[rt][i][2 * h + 0] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04010400u), nz);
-                    b[rt][i][2 * h + 1] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04030402u), nz);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-                b[rt][0][i] = ww[i];
-        }
-    }
 #pragma unroll
     for (int i = 0; i < NM; i++) {
         uint4 a[MT];
@@ -172,19 +160,45 @@ __device__ __forceinline__ void compute(int li, const Loaded<RT> &L, const uint4
         for (int mt = 0; mt < MT; mt++)
             a[mt] = lds[((kk >> 3) + i) * ROWS + mt * 16 + m];
 #pragma unroll
-        for (int rt = 0; rt < RT; rt++)
+        for (int rt = 0; rt < RT; rt++) {
+            const uint32_t ww[4] = {L.w[rt][ku].x, L.w[rt][ku].y, L.w[rt][ku].z, L.w[rt][ku].w};
+            uint32_t b[4];
+            if (BITS == 4) {
+                const uint32_t z = L.z[rt][zk];
+                const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
+                const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
+                const uint32_t v = ww[i], v8 = v >> 8;
+                b[0] = pk_add((v & 0x000F000Fu) | magic_lo, nz_lo);  // (q0 - z, q4 - z)
+                b[1] = pk_add((v & 0x00F000F0u) | magic_hi, nz_hi);  // (q1 - z, q5 - z)
+                b[2] = pk_add((v8 & 0x000F000Fu) | magic_lo, nz_lo); // (q2 - z, q6 - z)
+                b[3] = pk_add((v8 & 0x00F000F0u) | magic_hi, nz_hi); // (q3 - z, q7 - z)
+            } else if (BITS == 8) {
+                const uint32_t z = L.z[rt][zk];
+                const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t v = ww[2 * i + h];
+                    b[2 * h + 0] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04010400u), nz);
+                    b[2 * h + 1] = pk_add(__builtin_amdgcn_perm(0x64646464u, v, 0x04030402u), nz);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    b[q] = ww[q];
+            }
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
-                acc[rt][mt] = mfma(a[mt], b[rt][i], acc[rt][mt]);
+                acc[rt][mt] = mfma(a[mt], b, acc[rt][mt]);
+        }
     }
     // group complete: 4-bit after every load, 8-bit after every second load
-    const bool group_end = BITS == 4 || (BITS == 8 && (li & 1));
+    constexpr bool group_end = BITS == 4 || (BITS == 8 && ku == 1);
     if (group_end) {
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                out[rt][mt] += L.s[rt] * acc[rt][mt];
+                out[rt][mt] += L.s[rt][zk] * acc[rt][mt];
                 acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
             }
     }
@@ -195,8 +209,9 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
                                          int wave_row0, uint4 *lds)
 {
     constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
-    constexpr int LPC = KC / KPL; // loads per chunk
+    constexpr int SPC = KC / KPL / KU; // steps per chunk
     const int nload = d.K / KPL;
+    const int nstep = (nload + KU - 1) / KU;
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     float4_t acc[RT][MT], out[RT][MT];
 #pragma unroll
@@ -207,21 +222,24 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
             out[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
         }
     Loaded<RT> A, B;
-    issue<BITS, RT>(d, wave_row0, 0, A);
-    auto step = [&](int li, Loaded<RT> &Lcur, Loaded<RT> &Lnext) {
-        if (li + 1 < nload)
-            issue<BITS, RT>(d, wave_row0, li + 1, Lnext);
-        if (li % LPC == 0) {
+    issue<BITS, RT>(d, wave_row0, 0, nload, A);
+    auto step = [&](int st, Loaded<RT> &Lcur, Loaded<RT> &Lnext) {
+        // Always issued (the last step re-reads its own item) so that the wait for Lcur can
+        // be a counted vmcnt with Lnext's loads still in flight.
+        issue<BITS, RT>(d, wave_row0, min(st + 1, nstep - 1), nload, Lnext);
+        if (st % SPC == 0) {
             __syncthreads(); // all wavefronts are done with the previous chunk of x
-            stage_chunk<BITS, MT>(x, M, d.K, (li / LPC) * KC, lds);
+            stage_chunk<BITS, MT>(x, M, d.K, (st / SPC) * KC, lds);
             __syncthreads();
         }
-        compute<BITS, MT, RT>(li, Lcur, lds, acc, out);
+        compute<BITS, MT, RT, 0>(st, Lcur, lds, acc, out);
+        if (st * KU + 1 < nload)
+            compute<BITS, MT, RT, 1>(st, Lcur, lds, acc, out);
     };
-    for (int li = 0; li < nload; li += 2) {
-        step(li, A, B);
-        if (li + 1 < nload)
-            step(li + 1, B, A);
+    for (int st = 0; st < nstep; st += 2) {
+        step(st, A, B);
+        if (st + 1 < nstep)
+            step(st + 1, B, A);
     }
     // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
 #pragma unroll
@@ -334,6 +352,8 @@ int fq_skinny_tile_rows(long long total_rows, int M)
     (void)M;
     const long long want = 4LL * device_cus();
     int rt = 4;
+    if (const char *f = getenv("FQ_SKINNY_RT")) // experiment hook
+        return 64 * atoi(f);
     while (rt > 1 && total_rows / (64 * rt) < want)
         rt >>= 1;
     return 64 * rt;
