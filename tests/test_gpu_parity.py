@@ -191,6 +191,53 @@ def test_plan_batched_matches_oracle():
             assert rel_err(ys[i].cpu().numpy(), y_ref) <= TOL_Y, (M, i, b)
 
 
+# ------------------------------------------------------------------ linear, prefill-shaped (MFMA GEMM)
+
+@pytest.mark.parametrize("bits", [4, 8, 16])
+@pytest.mark.parametrize("M,N,K", [(33, 100, 1408), (128, 256, 1024), (300, 200, 2048), (257, 130, 128),
+                                   (64, 129, 4096)])
+def test_linear_prefill_matches_oracle(bits, M, N, K):
+    w = synth.weight(0, "par/pre/%dx%d" % (N, K), N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/pre/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (bits,))
+    y = gpu_linear(layer, bits, x)
+    if bits == 16:
+        y_ref = oracle.linear(x, w, None, None, 16)
+    else:
+        c, s, z = (t.cpu().numpy() for t in packed[bits])
+        y_ref = oracle.linear(x, c, s, z, bits)
+    assert y.shape == (M, N)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+    for m in (0, M // 2, M - 1):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_linear_prefill_integer_case_exact():
+    rng = np.random.default_rng(8)
+    for bits, M, N, K in [(4, 200, 150, 1024), (8, 130, 70, 640), (16, 100, 140, 256)]:
+        qmax = 15 if bits == 4 else 255 if bits == 8 else 8
+        w = rng.integers(0, qmax + 1, size=(N, K))
+        w[:, 0::128] = 0
+        w[:, 1::128] = qmax
+        x = rng.integers(-2, 3, size=(M, K))
+        layer, packed = make_layer(w.astype(np.float16), (bits,))
+        y = gpu_linear(layer, bits, x.astype(np.float16))
+        expect = (x @ w.T).astype(np.float16)
+        assert np.array_equal(y.view(np.uint16), expect.view(np.uint16)), (bits, M, N, K)
+
+
+def test_decode_call_with_large_k_takes_the_gemm_path():
+    # K beyond what the decode kernels keep in LDS: batch-1 still works (GEMM path)
+    N, K = 48, 28672
+    w = synth.weight(0, "par/bigk/w", N, K, 0.015)
+    x = synth.activations(0, "par/bigk/x", 2, K)
+    layer, packed = make_layer(w, (4,))
+    y = gpu_linear(layer, 4, x)
+    c, s, z = (t.cpu().numpy() for t in packed[4])
+    assert rel_err(y, oracle.linear(x, c, s, z, 4)) <= TOL_Y
+
+
 # ------------------------------------------------------------------ plan (one launch, device bits)
 
 def test_plan_matches_individual_calls_and_oracle():
