@@ -71,11 +71,24 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
                                   false);
 }
 
-__device__ __forceinline__ float wave_sum(float v)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_take(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        v += __shfl_xor(v, off, 64);
+    // lanes whose row is masked out, or whose source lane does not exist, read 0
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
+                                                                  ROW_MASK, 0xF, false));
+}
+
+// Sum over the 64 lanes with DPP modifiers only (no LDS crossbar): xor 1, xor 2 inside
+// quads, mirror inside 8 and 16, then row broadcasts.  The total lands in lane 63.
+__device__ __forceinline__ float wave_sum_lane63(float v)
+{
+    v += dpp_take<0xB1, 0xF>(v);  // quad_perm [1,0,3,2]
+    v += dpp_take<0x4E, 0xF>(v);  // quad_perm [2,3,0,1]
+    v += dpp_take<0x141, 0xF>(v); // row_half_mirror
+    v += dpp_take<0x140, 0xF>(v); // row_mirror: every lane of a row holds the row's sum
+    v += dpp_take<0x142, 0xA>(v); // row_bcast15 into rows 1 and 3
+    v += dpp_take<0x143, 0xC>(v); // row_bcast31 into rows 2 and 3
     return v;
 }
 
@@ -141,10 +154,10 @@ __device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
             p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u); // (x3, x7)
             lds[block_pos<4>(b)] = p;
             // slice = 4 blocks = 4 consecutive threads (b & 3 == threadIdx & 3)
-            even += __shfl_xor(even, 1, 64);
-            odd += __shfl_xor(odd, 1, 64);
-            even += __shfl_xor(even, 2, 64);
-            odd += __shfl_xor(odd, 2, 64);
+            even += dpp_take<0xB1, 0xF>(even);
+            odd += dpp_take<0xB1, 0xF>(odd);
+            even += dpp_take<0x4E, 0xF>(even);
+            odd += dpp_take<0x4E, 0xF>(odd);
             if ((b & 3) == 0) {
                 sums[(b >> 2) * 2 + 0] = 1024.0f * even + 64.0f * odd;
                 sums[(b >> 2) * 2 + 1] = even + odd;
@@ -152,7 +165,7 @@ __device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
         } else {
             lds[block_pos<8>(b)] = v;
             float s = even + odd;
-            s += __shfl_xor(s, 1, 64);
+            s += dpp_take<0xB1, 0xF>(s);
             if ((b & 1) == 0)
                 sums[b >> 1] = s;
         }
@@ -195,13 +208,18 @@ __device__ __forceinline__ void issue(const Sel &d, int row0, int j, Loaded &L)
     const uint32_t k0 = min((uint32_t)(j * 64 + lane) * CODES, K - CODES);
     const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
     const uint32_t byte0 = BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
+    const uint32_t g = k0 >> 7;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
+        // row0 is wavefront-uniform: the row bases are scalar, each lane adds a 32-bit offset
         const uint32_t row = (uint32_t)min(row0 + r, d.N - 1);
-        L.w[r] = load16_stream(d.codes + (size_t)row * row_bytes + byte0);
+        const uint8_t *rowp = d.codes + (size_t)row * row_bytes;
+        L.w[r] = load16_stream(rowp + byte0);
         if (BITS != 16) {
-            L.s[r] = as_global<float>(d.scales)[(size_t)row * G + (k0 >> 7)];
-            L.z[r] = as_global<uint8_t>(d.zeros)[(size_t)row * G + (k0 >> 7)];
+            const float *srow = d.scales + (size_t)row * G;
+            const uint8_t *zrow = d.zeros + (size_t)row * G;
+            L.s[r] = as_global<float>(srow)[g];
+            L.z[r] = as_global<uint8_t>(zrow)[g];
         }
     }
 }
@@ -305,8 +323,8 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
         const int row0 = row_begin + chunk * ROWS_PER_WAVE;
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            const float v = wave_sum(acc[r]);
-            if (lane == r && row0 + r < row_end)
+            const float v = wave_sum_lane63(acc[r]);
+            if (lane == 63 && row0 + r < row_end)
                 ((FQ_GLOBAL uint16_t *)y)[row0 + r] = to_half_bits(v);
             acc[r] = 0.0f;
         }
@@ -344,7 +362,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
                                                                int tile_rows)
 {
     extern __shared__ uint4 lds[];
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // scalar: keeps row math on the SALU
     const int wave_rows = tile_rows / WAVES; // multiple of 4
     int e = 0;
     int staged = -1; // entry whose x is in LDS
