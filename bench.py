@@ -128,6 +128,27 @@ class Stack:
         self.run_linears(s)
         self.run_entropy(s)
 
+    def build_stage_plans(self):
+        """Four plans per decoder layer (q/k/v, o, gate/up, down): the grouping a real decoder
+        allows, where only linears that share an input are independent of each other."""
+        torch, fq = self.torch, self.fq
+        groups = {"q": 0, "k": 0, "v": 0, "o": 1, "gate": 2, "up": 2, "down": 3}
+        stages = {}
+        for e, (li, mname, _, _) in enumerate(self.entries):
+            stages.setdefault((li, groups[mname]), []).append(e)
+        self.stage_plans = []
+        for key in sorted(stages):
+            idx = stages[key]
+            ws = torch.empty(fq.Plan.workspace_bytes(len(idx)), dtype=torch.uint8, device="cuda:0")
+            plan = fq.Plan([self.layers[i] for i in idx], [self.xs[i] for i in idx],
+                           [self.ys[i] for i in idx], self.M, ws)
+            self.stage_plans.append((plan, idx[0], len(idx)))
+
+    def run_linears_staged(self, s: int):
+        bits = self.bits_dev[s % N_PATTERNS]
+        for plan, first, n in self.stage_plans:
+            plan.run(bits[first:first + n])
+
 
 def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the
@@ -178,6 +199,8 @@ def main():
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(calibrates HBM byte counters when profiling)")
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--staged", action="store_true",
+                    help="also time the step as 4 dependent plan launches per layer (HIP graph)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -228,6 +251,61 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     ent_us = e0.elapsed_time(e1) / K_steps * 1e3
+
+    def time_launches(fn, n):
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(n):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    # Cost of switching: the timed mixed patterns against what the same linears cost in the
+    # fixed-precision runs (each linear charged its share, by bytes, of the all-b run).
+    switching = None
+    if set(bit_choices) == {4, 8}:
+        n = len(stack.layers)
+        fixed = {}
+        for b in (4, 8):
+            bd = torch.full((n,), b, dtype=torch.int32, device="cuda:0")
+            time_launches(lambda i: stack.plan.run(bd), 8)
+            fixed[b] = time_launches(lambda i: stack.plan.run(bd), K_steps)
+        tot = {b: sum(weight_bytes(N, K, b) for (_, _, K, N) in stack.entries) for b in (4, 8)}
+        pred = np.mean([sum(fixed[int(b)] * weight_bytes(N, K, int(b)) / tot[int(b)]
+                            for (_, _, K, N), b in zip(stack.entries, stack.patterns[(W + s) % N_PATTERNS]))
+                        for s in range(K_steps)])
+        one = stack.bits_dev[W % N_PATTERNS]
+        same_pattern = time_launches(lambda i: stack.plan.run(one), K_steps)
+        switching = {"all_w4_ms": fixed[4], "all_w8_ms": fixed[8], "mixed_ms": lin_ms,
+                     "mixed_predicted_from_fixed_ms": float(pred),
+                     "overhead": lin_ms / float(pred) - 1.0,
+                     "same_pattern_every_token_ms": same_pattern}
+
+    # The same step issued as a real decoder would have to: 4 dependent plan launches per layer
+    # (q/k/v, o, gate/up, down), captured once in a HIP graph and replayed.
+    staged_ms = None
+    if args.staged:
+        stack.build_stage_plans()
+        stack.run_linears_staged(W)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            stack.run_linears_staged(W)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                stack.run_linears_staged(W)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = max(8, K_steps // 4)
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        staged_ms = (time.perf_counter() - t0) / reps * 1e3
     alg_bytes = total_bytes / K_steps
     achieved = alg_bytes / (lin_ms * 1e-3) / 1e9
 
@@ -254,6 +332,10 @@ def main():
                      if args.layers is None else None,
                      "avg_launch_ms": lin_ms, "algorithmic_bytes_per_launch": alg_bytes},
     }
+    if switching is not None:
+        out["switching"] = switching
+    if staged_ms is not None:
+        out["staged_4_launches_per_layer_ms"] = staged_ms
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stack)
     print(json.dumps(out))

@@ -353,6 +353,105 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
     }
 }
 
+// ---- work partition of a plan ---------------------------------------------------
+// The entries of a plan cost very different amounts (rows x K x bit-width, and the
+// bit-widths are only known on the device), so a static deal of equal row tiles would
+// leave the workgroups with the expensive tiles streaming alone at the end.  Instead
+// every workgroup computes, from the table and the bit-width array, the same prefix sum
+// of costs and takes the slice [b C / G, (b + 1) C / G) of the total cost C: a
+// contiguous run of 16-row units, possibly spanning a few entries.  No atomics, no
+// tail, and x is staged once per entry a workgroup touches.
+
+struct Cut {
+    int e;       // entry the boundary falls in (count = past the end)
+    int unit;    // 16-row unit inside that entry
+};
+
+__device__ __forceinline__ long long entry_unit_cost(const FqLinearDesc &d, int bits)
+{
+    const bool ok = (bits == 4 && d.codes4) || (bits == 8 && d.codes8) || (bits == 16 && d.w16);
+    // time of 16 rows ~ bytes, with 4-bit bytes charged 10 % more: its unpack makes a
+    // workgroup's own rate, not the shared HBM rate, the limit (measured: all-W4 runs at
+    // 6.4 TB/s, all-W8 at 6.7 TB/s)
+    return ok ? (long long)(d.K >> 7) * bits * (bits == 4 ? 22 : 20) : 0;
+}
+
+// Inclusive scan over the 256 threads of the workgroup; `total` returns the sum.
+__device__ __forceinline__ long long block_scan(long long v, long long *tmp, long long &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long o = __shfl_up(v, off, 64);
+        if (lane >= off)
+            v += o;
+    }
+    __syncthreads(); // tmp may still be read from a previous call
+    if (lane == 63)
+        tmp[wave] = v;
+    __syncthreads();
+    long long before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; w++) {
+        const long long t = tmp[w];
+        all += t;
+        if (w < wave)
+            before += t;
+    }
+    total = all;
+    return v + before;
+}
+
+// Boundaries of this workgroup's slice.  Every thread returns the same values.
+__device__ __forceinline__ void partition(const FqLinearDesc *table, const int32_t *bits_dev, int count,
+                                          Cut &lo, Cut &hi)
+{
+    __shared__ long long tmp[WAVES];
+    __shared__ Cut cuts[2];
+    // pass 1: total cost
+    long long C = 0;
+    for (int base = 0; base < count; base += WG_THREADS) {
+        const int e = base + threadIdx.x;
+        long long c = 0;
+        if (e < count)
+            c = entry_unit_cost(table[e], bits_dev[e]) * ((table[e].N + 15) >> 4);
+        long long chunk;
+        block_scan(c, tmp, chunk);
+        C += chunk;
+    }
+    const long long G = gridDim.x, b = blockIdx.x;
+    const long long t_lo = b * C / G, t_hi = (b + 1) * C / G;
+    if (threadIdx.x == 0) {
+        cuts[0] = Cut{count, 0};
+        cuts[1] = Cut{count, 0};
+    }
+    // pass 2: the entries whose cost interval [P_excl, P_incl) contains the two targets
+    long long carry = 0;
+    for (int base = 0; base < count; base += WG_THREADS) {
+        const int e = base + threadIdx.x;
+        long long unit = 0, c = 0;
+        if (e < count) {
+            unit = entry_unit_cost(table[e], bits_dev[e]);
+            c = unit * ((table[e].N + 15) >> 4);
+        }
+        long long chunk;
+        const long long incl = block_scan(c, tmp, chunk) + carry; // barriers inside order the cuts[] init
+        const long long excl = incl - c;
+        if (c > 0) {
+            if (t_lo >= excl && t_lo < incl)
+                cuts[0] = Cut{e, (int)((t_lo - excl) / unit)};
+            if (t_hi >= excl && t_hi < incl)
+                cuts[1] = Cut{e, (int)((t_hi - excl) / unit)};
+        }
+        carry += chunk;
+    }
+    __syncthreads();
+    lo = cuts[0];
+    hi = cuts[1]; // t_hi == C for the last workgroup: no interval contains it, stays {count, 0}
+    if (C == 0)
+        lo = Cut{count, 0};
+}
+
 template <bool SINGLE>
 __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDesc single,
                                                                int bits_host,
@@ -363,41 +462,55 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
 {
     extern __shared__ uint4 lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // scalar: keeps row math on the SALU
-    const int wave_rows = tile_rows / WAVES; // multiple of 4
-    int e = 0;
-    int staged = -1; // entry whose x is in LDS
-    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
-        const FqLinearDesc *dp;
-        int bits;
-        if (SINGLE) {
-            dp = &single;
-            bits = bits_host;
-        } else {
-            // tiles are visited in increasing order: advance the entry cursor
-            while (e + 1 < count && tile >= table[e + 1].tile_begin)
-                e++;
-            dp = &table[e];
-            bits = bits_dev[e];
+    if (SINGLE) {
+        // one linear: equal row tiles dealt round-robin
+        const int wave_rows = tile_rows / WAVES; // multiple of 4
+        const uint8_t *codes = bits_host == 4 ? single.codes4 : bits_host == 8 ? single.codes8
+                                                                               : (const uint8_t *)single.w16;
+        Sel d = {codes, bits_host == 4 ? single.scales4 : single.scales8,
+                 bits_host == 4 ? single.zeros4 : single.zeros8, single.N, single.K};
+        bool first = true;
+        for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+            const int row_begin = min(tile * tile_rows + wave * wave_rows, d.N);
+            const int row_end = min(row_begin + wave_rows, d.N);
+            if (bits_host == 4)
+                run_tile<4>(d, single.x, single.y, row_begin, row_end, first, lds);
+            else if (bits_host == 8)
+                run_tile<8>(d, single.x, single.y, row_begin, row_end, first, lds);
+            else
+                run_tile<16>(d, single.x, single.y, row_begin, row_end, first, lds);
+            first = false;
         }
+        return;
+    }
+    Cut lo, hi;
+    partition(table, bits_dev, count, lo, hi);
+    for (int e = lo.e; e < count && e <= hi.e; e++) {
+        const FqLinearDesc *dp = &table[e];
+        const int bits = bits_dev[e];
+        const int units = (dp->N + 15) >> 4;
+        const int u0 = e == lo.e ? lo.unit : 0;
+        const int u1 = e == hi.e ? hi.unit : units;
+        if (u1 <= u0 || entry_unit_cost(*dp, bits) == 0)
+            continue; // uniform over the workgroup: nothing of this entry falls in the slice
         Sel d;
         d.N = dp->N;
         d.K = dp->K;
         // the switch of precision: a pointer select on resident copies
-        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : (const uint8_t *)dp->w16;
         d.scales = bits == 4 ? dp->scales4 : dp->scales8;
         d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
-        if (!d.codes)
-            continue; // uniform: an entry without a copy at this bit-width is skipped, y untouched
-        const int row_begin = min((tile - dp->tile_begin) * tile_rows + wave * wave_rows, d.N);
-        const int row_end = min(row_begin + wave_rows, d.N);
-        const bool need_stage = staged != e;
-        staged = e;
+        // rows [16 u0, 16 u1) split over the 4 wavefronts in multiples of 4 rows
+        const int r0 = u0 * 16, r1 = min(u1 * 16, d.N);
+        const int per_wave = ((r1 - r0 + WAVES * ROWS_PER_WAVE - 1) / (WAVES * ROWS_PER_WAVE)) * ROWS_PER_WAVE;
+        const int row_begin = min(r0 + wave * per_wave, r1);
+        const int row_end = min(row_begin + per_wave, r1);
         if (bits == 4)
-            run_tile<4>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
+            run_tile<4>(d, dp->x, dp->y, row_begin, row_end, true, lds);
         else if (bits == 8)
-            run_tile<8>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
+            run_tile<8>(d, dp->x, dp->y, row_begin, row_end, true, lds);
         else
-            run_tile<16>(d, dp->x, dp->y, row_begin, row_end, need_stage, lds);
+            run_tile<16>(d, dp->x, dp->y, row_begin, row_end, true, lds);
     }
 }
 
@@ -450,7 +563,8 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
         return hipSuccess;
     const size_t lds = lds_bytes_for(max_K);
     const int cap = resident_workgroups(lds);
-    const int grid = total_tiles < cap ? total_tiles : cap;
+    // a plan always fills the machine: its workgroups cut the total cost into equal slices
+    const int grid = single ? (total_tiles < cap ? total_tiles : cap) : cap;
     if (single) {
         decode_m1_kernel<true><<<grid, WG_THREADS, lds, stream>>>(*single, bits_host, nullptr,
                                                                   nullptr, 1, total_tiles, tile_rows);

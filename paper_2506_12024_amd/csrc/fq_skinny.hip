@@ -8,7 +8,7 @@
 // Streaming side (same as the batch-1 kernel): a wavefront owns RT row tiles of 16
 // weight rows; lane (n = lane % 16, c = lane / 16) reads 16 bytes of row n per load
 // at byte offset 64 * load + 16 * c -- 32 four-bit codes, 16 eight-bit codes or 8
-// halves -- with non-temporal 128-bit loads, double buffered.  One load of a
+// halves -- with 128-bit loads, double buffered.  One load of a
 // wavefront covers 16 rows x 128 / 64 / 32 k, i.e. 4 / 2 / 1 MFMAs.  Loads are issued
 // in pairs (64 * (2 i) and 64 * (2 i + 1)): a load touches only 64 bytes of each row,
 // and the two halves of a 128-byte line must be requested back to back or HBM
@@ -45,7 +45,9 @@ constexpr int KC = 1024; // k per LDS chunk
 
 __device__ __forceinline__ uint4 load16_stream(const void *p)
 {
-    const u32x4 v = __builtin_nontemporal_load((const FQ_GLOBAL u32x4 *)p);
+    // plain (cached) load: a wavefront load touches half of each 128-byte line, the partner
+    // load that follows should find the line in L2
+    const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ uint4 load16_global(const void *p)
