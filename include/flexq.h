@@ -139,7 +139,9 @@ int fq_plan_destroy(fq_plan *plan);
  * inputs.  -inf entries carry no mass; +inf and NaN are unspecified.
  *   logits_p, logits_q  device, f32 [R][V]     (read)
  *   entropy_out, kl_out device, f32 [R]        (written)
- * R >= 0 (R = 0 launches nothing), V >= 1.
+ * R >= 0 (R = 0 launches nothing), V >= 1.  Calls with R <= 64 combine per-row
+ * partials in a small device-resident scratch of the library: do not let two such
+ * calls overlap on different streams.
  */
 int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V,
                   float *entropy_out, float *kl_out, void *stream);

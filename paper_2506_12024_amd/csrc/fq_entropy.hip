@@ -3,7 +3,11 @@
 // entropy, Sec. 4.2 Eq. (5); the KL divergence is the layer-ranking signal of
 // Sec. 3.1 / 4.3, taken between two next-token distributions.
 //
-// One workgroup per row.  Every lane keeps an online (running-max) partial
+// One workgroup per row -- or, for a handful of rows (the decode step has one), up to 32
+// workgroups per row whose partials meet in a small static device array and are combined
+// by whichever workgroup arrives last (one launch either way; a single CU would need
+// ~8 us for the 64000 exponentials of one 32000-entry pair).
+// Every lane keeps an online (running-max) partial
 //   m  = max a_i            S  = sum e^(a_i - m)
 //   U  = sum e^(a_i - m) (a_i - m)          D = sum e^(a_i - m) (a_i - b_i)
 //   mb = max b_i            Sb = sum e^(b_i - mb)
@@ -16,6 +20,7 @@
 // the small KL of two nearly equal distributions, never passes through binary32.
 #include <hip/hip_runtime.h>
 #include <float.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "fq_internal.h"
@@ -97,17 +102,25 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// Scratch of the split mode: partials [row][split][S, U, D, Sb, m, mb] and arrival tickets.
+// Tickets are zero at load and the combining workgroup resets its row's ticket, so every
+// launch finds them zero.  Calls that use the split mode must not overlap each other.
+constexpr int MAX_SPLIT_ROWS = 64, MAX_SPLITS = 32;
+__device__ double g_part[MAX_SPLIT_ROWS][MAX_SPLITS][6];
+__device__ unsigned int g_ticket[MAX_SPLIT_ROWS];
+
 template <int THREADS, bool HAS_B, bool VEC>
 __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__restrict__ a,
                                                              const float *__restrict__ b, int V,
-                                                             float *__restrict__ H,
+                                                             int splits, float *__restrict__ H,
                                                              float *__restrict__ KL)
 {
     constexpr int WAVES = THREADS / 64;
     __shared__ float s_max[2][WAVES];
     __shared__ double s_sum[4][WAVES];
+    __shared__ unsigned int s_last;
 
-    const int r = blockIdx.x;
+    const int r = blockIdx.x / splits, sidx = blockIdx.x % splits;
     const int t = threadIdx.x;
     const float *ar = a + (size_t)r * V;
     const float *br = HAS_B ? b + (size_t)r * V : nullptr;
@@ -119,8 +132,10 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
         const float4 *a4 = reinterpret_cast<const float4 *>(ar);
         const float4 *b4 = reinterpret_cast<const float4 *>(br);
         const int nvec = V >> 2;
-        int i = t;
-        for (; i + 3 * THREADS < nvec; i += 4 * THREADS) {
+        const int per = (nvec + splits - 1) / splits;
+        const int end = min(nvec, (sidx + 1) * per);
+        int i = sidx * per + t;
+        for (; i + 3 * THREADS < end; i += 4 * THREADS) {
             const float4 a0 = a4[i], a1 = a4[i + THREADS], a2 = a4[i + 2 * THREADS],
                          a3 = a4[i + 3 * THREADS];
             float4 b0 = zero4, b1 = zero4, b2 = zero4, b3 = zero4;
@@ -135,10 +150,12 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
             add_vec<HAS_B>(p, a2, b2);
             add_vec<HAS_B>(p, a3, b3);
         }
-        for (; i < nvec; i += THREADS)
+        for (; i < end; i += THREADS)
             add_vec<HAS_B>(p, a4[i], HAS_B ? b4[i] : zero4);
     } else {
-        for (int i = t; i < V; i += THREADS) {
+        const int per = (V + splits - 1) / splits;
+        const int end = min(V, (sidx + 1) * per);
+        for (int i = sidx * per + t; i < end; i += THREADS) {
             const float av = ar[i];
             const float bv = HAS_B ? br[i] : 0.0f;
             raise_max_a(p, av);
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
         }
     }
 
-    // Row maxima.
+    // Maxima over the workgroup.
     const int wave = t >> 6, lane = t & 63;
     float gm = wave_max(p.m), gmb = wave_max(p.mb);
     if (lane == 0) {
@@ -161,7 +178,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
         gm = fmaxf(gm, s_max[0][w]);
         gmb = fmaxf(gmb, s_max[1][w]);
     }
-    // Rescale this lane's partial to the row maxima, then sum in double.
+    // Rescale this lane's partial to the maxima, then sum in double.
     double S = 0.0, U = 0.0, D = 0.0, Sb = 0.0;
     if (p.S > 0.0f) {
         const float d = p.m - gm;
@@ -185,14 +202,62 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
         s_sum[3][wave] = Sb;
     }
     __syncthreads();
-    if (t == 0) {
-        S = U = D = Sb = 0.0;
-        for (int w = 0; w < WAVES; w++) {
-            S += s_sum[0][w];
-            U += s_sum[1][w];
-            D += s_sum[2][w];
-            Sb += s_sum[3][w];
+    S = U = D = Sb = 0.0;
+#pragma unroll
+    for (int w = 0; w < WAVES; w++) {
+        S += s_sum[0][w];
+        U += s_sum[1][w];
+        D += s_sum[2][w];
+        Sb += s_sum[3][w];
+    }
+    if (splits > 1) {
+        // publish this workgroup's partial, then see whether it is the last to arrive
+        if (t == 0) {
+            double *slot = g_part[r][sidx];
+            slot[0] = S;
+            slot[1] = U;
+            slot[2] = D;
+            slot[3] = Sb;
+            slot[4] = (double)gm;
+            slot[5] = (double)gmb;
+            __threadfence();
+            s_last = atomicAdd(&g_ticket[r], 1u) == (unsigned)splits - 1 ? 1u : 0u;
         }
+        __syncthreads();
+        if (!s_last || wave != 0)
+            return;
+        __threadfence();
+        // first wavefront of the last workgroup: lane i takes partial i
+        double pm = -INFINITY, pmb = -INFINITY;
+        S = U = D = Sb = 0.0;
+        if (lane < splits) {
+            const double *slot = g_part[r][lane];
+            S = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            U = __hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            D = __hip_atomic_load(&slot[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            Sb = __hip_atomic_load(&slot[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pm = __hip_atomic_load(&slot[4], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pmb = __hip_atomic_load(&slot[5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        gm = wave_max((float)pm);
+        gmb = wave_max((float)pmb);
+        if (S > 0.0) {
+            const float d = (float)pm - gm;
+            const double c = (double)expf(d);
+            U = c * (U + (double)d * S);
+            S *= c;
+            D *= c;
+        }
+        if (Sb > 0.0)
+            Sb *= (double)expf((float)pmb - gmb);
+        S = wave_sum(S);
+        U = wave_sum(U);
+        D = wave_sum(D);
+        Sb = wave_sum(Sb);
+        if (lane == 0)
+            g_ticket[r] = 0u; // ready for the next launch
+    }
+    if (t == 0) {
         H[r] = (float)(log(S) - U / S);
         if (HAS_B)
             KL[r] = (float)(D / S + ((double)gmb - (double)gm) + log(Sb / S));
@@ -200,21 +265,21 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
 }
 
 template <int THREADS>
-hipError_t launch(const float *a, const float *b, int R, int V, float *H, float *KL,
+hipError_t launch(const float *a, const float *b, int R, int V, int splits, float *H, float *KL,
                   hipStream_t stream)
 {
     const bool vec = (V % 4 == 0) && (((uintptr_t)a & 15) == 0) && (!b || ((uintptr_t)b & 15) == 0);
-    const dim3 grid((unsigned)R), block(THREADS);
+    const dim3 grid((unsigned)R * (unsigned)splits), block(THREADS);
     if (b) {
         if (vec)
-            entropy_kl_kernel<THREADS, true, true><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+            entropy_kl_kernel<THREADS, true, true><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
         else
-            entropy_kl_kernel<THREADS, true, false><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+            entropy_kl_kernel<THREADS, true, false><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
     } else {
         if (vec)
-            entropy_kl_kernel<THREADS, false, true><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+            entropy_kl_kernel<THREADS, false, true><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
         else
-            entropy_kl_kernel<THREADS, false, false><<<grid, block, 0, stream>>>(a, b, V, H, KL);
+            entropy_kl_kernel<THREADS, false, false><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
     }
     return hipGetLastError();
 }
@@ -226,9 +291,16 @@ hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, fl
 {
     if (R == 0)
         return hipSuccess;
-    // Few rows: one large workgroup per row keeps more loads in flight for the
-    // latency-bound single-vector case; many rows: 256 threads, several rows per CU.
+    // A few rows: split every row over several workgroups (>= 1024 entries each).
+    if (R <= MAX_SPLIT_ROWS && V >= 2048) {
+        int splits = V / 1024;
+        if (splits > MAX_SPLITS)
+            splits = MAX_SPLITS;
+        return launch<256>(a, b, R, V, splits, H, KL, stream);
+    }
+    // Otherwise one workgroup per row: large ones while there are too few rows to fill the
+    // machine, 256 threads (several rows per CU) beyond that.
     if (R < 512)
-        return launch<1024>(a, b, R, V, H, KL, stream);
-    return launch<256>(a, b, R, V, H, KL, stream);
+        return launch<1024>(a, b, R, V, 1, H, KL, stream);
+    return launch<256>(a, b, R, V, 1, H, KL, stream);
 }
