@@ -21,12 +21,16 @@
 // per quantization group in a zeroed accumulator and folded into the output as
 // out += s[n][g] * acc, which is Eq. (3) with the scale factored out of the group.
 //
-// x is staged through LDS in chunks of 1024 k as 16-byte blocks of 8 halves,
-// [k block][batch row], for the 4-bit path permuted inside the block to the order the
-// unpacking produces (x0 x4 x1 x5 x2 x6 x3 x7).
+// x is staged through LDS in chunks of 1024 k (512 for more than 16 batch rows) as 16-byte
+// blocks of 8 halves, [k block][batch row], for the 4-bit path permuted inside the block to
+// the order the unpacking produces (x0 x4 x1 x5 x2 x6 x3 x7).  The scales and zeros of a
+// chunk's groups are fetched once per chunk (each lane two groups of its row) and parked in
+// a wavefront-private LDS area: fetching them per group would touch 16 cache lines per
+// instruction and, with the weights streaming through the same caches, miss every time.
+// Both x and the metadata of chunk c + 1 are prefetched into registers while chunk c is
+// computed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "fq_internal.h"
 
@@ -41,12 +45,21 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WG_THREADS = 256;
 constexpr int WAVES = WG_THREADS / 64;
-constexpr int KC = 1024; // k per LDS chunk
+constexpr int KU = 2; // consecutive 64-byte loads per row issued together (one 128-byte line)
 
-__device__ __forceinline__ uint4 load16_stream(const void *p)
+// k per LDS chunk of x: 1024 for up to 16 batch rows, 512 for up to 32 (32 KiB either way)
+template <int MT>
+struct Chunk {
+    static constexpr int KC = 1024 / MT;
+    static constexpr int GROUPS = KC / 128;  // quantization groups per chunk
+    static constexpr int GPL = GROUPS / 4;   // groups whose scale/zero one lane fetches
+    static constexpr int XPER = 16 * MT * (KC / 8) / WG_THREADS; // 16-byte x blocks per thread
+};
+
+__device__ __forceinline__ uint4 load16_weights(const void *p)
 {
     // plain (cached) load: a wavefront load touches half of each 128-byte line, the partner
-    // load that follows should find the line in L2
+    // load that follows finds the line on its way
     const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
     return make_uint4(v.x, v.y, v.z, v.w);
 }
@@ -68,13 +81,16 @@ struct Sel {
     int N, K;
 };
 
-constexpr int KU = 2; // consecutive 64-byte loads per row issued together (one 128-byte line)
-
 template <int RT>
-struct Loaded {
+struct Loaded { // one step of weights: RT row tiles x KU loads
     uint4 w[RT][KU];
-    float s[RT][KU];
-    uint32_t z[RT][KU];
+};
+
+template <int MT, int RT>
+struct Staged { // what a lane prefetches for the next chunk
+    uint4 x[Chunk<MT>::XPER];
+    float s[RT][Chunk<MT>::GPL];
+    uint32_t z[RT][Chunk<MT>::GPL];
 };
 
 // Issue step `st`: loads 2 st and 2 st + 1 of every row tile.
@@ -82,7 +98,7 @@ template <int BITS, int RT>
 __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int nload, Loaded<RT> &L)
 {
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
-    const uint32_t K = (uint32_t)d.K, G = K >> 7;
+    const uint32_t K = (uint32_t)d.K;
     const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
@@ -91,44 +107,76 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
         for (int ku = 0; ku < KU; ku++) {
             // an odd number of loads (4-bit, K / 128 odd): the missing one re-reads the last
             const uint32_t li = (uint32_t)min(st * KU + ku, nload - 1);
-            const uint32_t g = BITS == 4 ? li : li >> 1;
-            L.w[rt][ku] = load16_stream(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
-            if (BITS == 4 || (BITS == 8 && ku == 0)) {
-                L.s[rt][ku] = ((const FQ_GLOBAL float *)d.scales)[(size_t)row * G + g];
-                L.z[rt][ku] = ((const FQ_GLOBAL uint8_t *)d.zeros)[(size_t)row * G + g];
+            L.w[rt][ku] = load16_weights(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
+        }
+    }
+}
+
+// Prefetch chunk `ch` of x (this thread's blocks) and the scales / zeros of the chunk's groups
+// for this wavefront's rows: lane (n, c) fetches groups c * GPL .. of row n, so the 16 rows'
+// lines are touched once per chunk instead of once per group.
+template <int BITS, int MT, int RT>
+__device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, int M, int wave_row0,
+                                               int ch, Staged<MT, RT> &S)
+{
+    typedef Chunk<MT> C;
+    constexpr int BLK = C::KC / 8;
+    const int kc = ch * C::KC;
+#pragma unroll
+    for (int it = 0; it < C::XPER; it++) {
+        const int idx = it * WG_THREADS + threadIdx.x;
+        const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
+        // rows past M and k past K are clamped: those blocks only feed outputs that are
+        // never stored (rows) or are never read (k)
+        const int mc = min(m, M - 1), k = min(kc + kb * 8, d.K - 8);
+        S.x[it] = load16_global(x + (size_t)mc * d.K + k);
+    }
+    if (BITS != 16) {
+        const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+        const int G = d.K >> 7;
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            const size_t row = (size_t)min(wave_row0 + rt * 16 + n, d.N - 1);
+#pragma unroll
+            for (int j = 0; j < C::GPL; j++) {
+                const int g = min(ch * C::GROUPS + c * C::GPL + j, G - 1);
+                S.s[rt][j] = ((const FQ_GLOBAL float *)d.scales)[row * G + g];
+                S.z[rt][j] = ((const FQ_GLOBAL uint8_t *)d.zeros)[row * G + g];
             }
         }
     }
 }
 
-// Stage x[:, kc .. kc+KC) as blocks [k block][16 * MT rows].  All of a thread's global
-// loads are issued before the first LDS write so that they overlap.
-template <int BITS, int MT>
-__device__ __forceinline__ void stage_chunk(const uint16_t *x, int M, int K, int kc, uint4 *lds)
+// Write a prefetched chunk to LDS: x blocks [k block][16 * MT rows] (4-bit: permuted to the
+// unpack order), scales and zeros into the wavefront's own area as [row tile][group][row].
+template <int BITS, int MT, int RT>
+__device__ __forceinline__ void commit_chunk(const Staged<MT, RT> &S, uint4 *lds_x, float *ms, uint8_t *mz)
 {
-    constexpr int ROWS = 16 * MT, BLK = KC / 8, PER = ROWS * BLK / WG_THREADS;
-    uint4 v[PER];
+    typedef Chunk<MT> C;
+    constexpr int ROWS = 16 * MT, BLK = C::KC / 8;
 #pragma unroll
-    for (int it = 0; it < PER; it++) {
-        const int idx = it * WG_THREADS + threadIdx.x;
-        const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
-        // rows past M and k past K are clamped: those blocks only feed outputs that are
-        // never stored (rows) or are never read (k)
-        const int mc = min(m, M - 1), k = min(kc + kb * 8, K - 8);
-        v[it] = load16_global(x + (size_t)mc * K + k);
-    }
-#pragma unroll
-    for (int it = 0; it < PER; it++) {
+    for (int it = 0; it < C::XPER; it++) {
         const int idx = it * WG_THREADS + threadIdx.x;
         const int m = idx / BLK, kb = idx % BLK;
-        uint4 p = v[it];
+        uint4 p = S.x[it];
         if (BITS == 4) {
-            p.x = __builtin_amdgcn_perm(v[it].z, v[it].x, 0x05040100u); // (x0, x4)
-            p.y = __builtin_amdgcn_perm(v[it].z, v[it].x, 0x07060302u); // (x1, x5)
-            p.z = __builtin_amdgcn_perm(v[it].w, v[it].y, 0x05040100u); // (x2, x6)
-            p.w = __builtin_amdgcn_perm(v[it].w, v[it].y, 0x07060302u); // (x3, x7)
+            p.x = __builtin_amdgcn_perm(S.x[it].z, S.x[it].x, 0x05040100u); // (x0, x4)
+            p.y = __builtin_amdgcn_perm(S.x[it].z, S.x[it].x, 0x07060302u); // (x1, x5)
+            p.z = __builtin_amdgcn_perm(S.x[it].w, S.x[it].y, 0x05040100u); // (x2, x6)
+            p.w = __builtin_amdgcn_perm(S.x[it].w, S.x[it].y, 0x07060302u); // (x3, x7)
         }
-        lds[kb * ROWS + m] = p;
+        lds_x[kb * ROWS + m] = p;
+    }
+    if (BITS != 16) {
+        const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int j = 0; j < C::GPL; j++) {
+                const int gl = c * C::GPL + j; // group inside the chunk
+                ms[(rt * C::GROUPS + gl) * 16 + n] = S.s[rt][j];
+                mz[(rt * C::GROUPS + gl) * 16 + n] = (uint8_t)S.z[rt][j];
+            }
     }
 }
 
@@ -140,43 +188,54 @@ __device__ __forceinline__ float4_t mfma(uint4 a, const uint32_t (&b)[4], float4
                                                   __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
 }
 
-// One load's worth of work: dequantize L, multiply with the staged x, fold finished groups.
+// One load's worth of work: dequantize, multiply with the staged x, fold finished groups.
 template <int BITS, int MT, int RT, int ku>
-__device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4 *lds,
-                                        float4_t (&acc)[RT][MT], float4_t (&out)[RT][MT])
+__device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4 *lds_x, const float *ms,
+                                        const uint8_t *mz, float4_t (&acc)[RT][MT],
+                                        float4_t (&out)[RT][MT])
 {
-    const int li = st * KU + ku;
-    constexpr int zk = BITS == 8 ? 0 : ku; // 8-bit: both loads of a step share one group
+    typedef Chunk<MT> C;
     constexpr int ROWS = 16 * MT;
     constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32); // k per load
     constexpr int NM = KPL / 32;                                 // MFMAs per load
+    constexpr int LPC = C::KC / KPL;                             // loads per chunk
+    const int li = st * KU + ku;
     const int lane = threadIdx.x & 63, m = lane & 15, c = lane >> 4;
-    const int kk = (li % (KC / KPL)) * KPL + c * (KPL / 4); // lane's first k inside the chunk
+    const int lc = li % LPC;                      // load inside the chunk
+    const int kk = lc * KPL + c * (KPL / 4);      // lane's first k inside the chunk
+    const int gl = (lc * KPL) >> 7;               // group inside the chunk
     uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
     asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
 
+    float s[RT];
+    uint32_t z[RT];
+    if (BITS != 16) {
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            s[rt] = ms[(rt * C::GROUPS + gl) * 16 + m];
+            z[rt] = mz[(rt * C::GROUPS + gl) * 16 + m];
+        }
+    }
 #pragma unroll
     for (int i = 0; i < NM; i++) {
         uint4 a[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
-            a[mt] = lds[((kk >> 3) + i) * ROWS + mt * 16 + m];
+            a[mt] = lds_x[((kk >> 3) + i) * ROWS + mt * 16 + m];
 #pragma unroll
         for (int rt = 0; rt < RT; rt++) {
             const uint32_t ww[4] = {L.w[rt][ku].x, L.w[rt][ku].y, L.w[rt][ku].z, L.w[rt][ku].w};
             uint32_t b[4];
             if (BITS == 4) {
-                const uint32_t z = L.z[rt][zk];
-                const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
-                const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
+                const uint32_t nz_lo = (z[rt] | (z[rt] << 16)) | 0xE400E400u;        // -(1024 + z) twice
+                const uint32_t nz_hi = ((z[rt] << 4) | (z[rt] << 20)) | 0xD400D400u; // -(  64 + z) twice
                 const uint32_t v = ww[i], v8 = v >> 8;
                 b[0] = pk_add((v & 0x000F000Fu) | magic_lo, nz_lo);  // (q0 - z, q4 - z)
                 b[1] = pk_add((v & 0x00F000F0u) | magic_hi, nz_hi);  // (q1 - z, q5 - z)
                 b[2] = pk_add((v8 & 0x000F000Fu) | magic_lo, nz_lo); // (q2 - z, q6 - z)
                 b[3] = pk_add((v8 & 0x00F000F0u) | magic_hi, nz_hi); // (q3 - z, q7 - z)
             } else if (BITS == 8) {
-                const uint32_t z = L.z[rt][zk];
-                const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
+                const uint32_t nz = (z[rt] | (z[rt] << 16)) | 0xE400E400u;
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
                     const uint32_t v = ww[2 * i + h];
@@ -200,7 +259,7 @@ __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4
         for (int rt = 0; rt < RT; rt++)
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) {
-                out[rt][mt] += L.s[rt][zk] * acc[rt][mt];
+                out[rt][mt] += s[rt] * acc[rt][mt];
                 acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
             }
     }
@@ -208,12 +267,14 @@ __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4
 
 template <int BITS, int MT, int RT>
 __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16_t *y, int M,
-                                         int wave_row0, uint4 *lds)
+                                         int wave_row0, uint4 *lds_x, float *ms, uint8_t *mz)
 {
+    typedef Chunk<MT> C;
     constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
-    constexpr int SPC = KC / KPL / KU; // steps per chunk
+    constexpr int SPC = C::KC / KPL / KU; // steps per chunk
     const int nload = d.K / KPL;
     const int nstep = (nload + KU - 1) / KU;
+    const int nchunk = (d.K + C::KC - 1) / C::KC;
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     float4_t acc[RT][MT], out[RT][MT];
 #pragma unroll
@@ -224,19 +285,24 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
             out[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
         }
     Loaded<RT> A, B;
+    Staged<MT, RT> S;
     issue<BITS, RT>(d, wave_row0, 0, nload, A);
+    prefetch_chunk<BITS, MT, RT>(d, x, M, wave_row0, 0, S);
     auto step = [&](int st, Loaded<RT> &Lcur, Loaded<RT> &Lnext) {
         // Always issued (the last step re-reads its own item) so that the wait for Lcur can
         // be a counted vmcnt with Lnext's loads still in flight.
         issue<BITS, RT>(d, wave_row0, min(st + 1, nstep - 1), nload, Lnext);
         if (st % SPC == 0) {
+            const int ch = st / SPC;
             __syncthreads(); // all wavefronts are done with the previous chunk of x
-            stage_chunk<BITS, MT>(x, M, d.K, (st / SPC) * KC, lds);
+            commit_chunk<BITS, MT, RT>(S, lds_x, ms, mz);
             __syncthreads();
+            // next chunk's x and metadata travel while this chunk is computed
+            prefetch_chunk<BITS, MT, RT>(d, x, M, wave_row0, min(ch + 1, nchunk - 1), S);
         }
-        compute<BITS, MT, RT, 0>(st, Lcur, lds, acc, out);
+        compute<BITS, MT, RT, 0>(st, Lcur, lds_x, ms, mz, acc, out);
         if (st * KU + 1 < nload)
-            compute<BITS, MT, RT, 1>(st, Lcur, lds, acc, out);
+            compute<BITS, MT, RT, 1>(st, Lcur, lds_x, ms, mz, acc, out);
     };
     for (int st = 0; st < nstep; st += 2) {
         step(st, A, B);
@@ -268,7 +334,9 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
                                                                    const int32_t *__restrict__ bits_dev,
                                                                    int count, int total_tiles, int M)
 {
-    __shared__ uint4 lds[(KC / 8) * 16 * MT];
+    __shared__ uint4 lds_x[(Chunk<MT>::KC / 8) * 16 * MT];
+    __shared__ float lds_s[WAVES][RT * Chunk<MT>::GROUPS * 16];
+    __shared__ uint8_t lds_z[WAVES][RT * Chunk<MT>::GROUPS * 16];
     constexpr int TILE_ROWS = WAVES * RT * 16;
     const int wave = threadIdx.x >> 6;
     int e = 0;
@@ -296,11 +364,11 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
         // masked on store) so that every one of them reaches the staging barriers.
         const int wave_row0 = (tile - dp->tile_begin) * TILE_ROWS + wave * RT * 16;
         if (bits == 4)
-            run_tile<4, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+            run_tile<4, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
         else if (bits == 8)
-            run_tile<8, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+            run_tile<8, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
         else
-            run_tile<16, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds);
+            run_tile<16, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
     }
 }
 
@@ -354,8 +422,6 @@ int fq_skinny_tile_rows(long long total_rows, int M)
     (void)M;
     const long long want = 4LL * device_cus();
     int rt = 4;
-    if (const char *f = getenv("FQ_SKINNY_RT")) // experiment hook
-        return 64 * atoi(f);
     while (rt > 1 && total_rows / (64 * rt) < want)
         rt >>= 1;
     return 64 * rt;
