@@ -185,8 +185,100 @@ def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
                       % (sample_layers, n_layers, t_lin, n_layers / sample_layers, t_ent)}
 
 
+def bench_prefill(args):
+    """The prefill-shaped slice: x[2048][8192] against W 8192->28672 and x[2048][28672] against
+    W 28672->8192 (a 70B-shaped layer slice), int4 and int8, MFMA dequant-GEMM.  One step = the
+    four GEMMs.  Reports TFLOP/s against the dense fp16 MFMA peak."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev, M = "cuda:0", 2048
+    calls = []
+    for N, K in ((28672, 8192), (8192, 28672)):
+        w = synth.weight(SEED, "prefill/%dx%d/w" % (N, K), N, K, 0.015)
+        x = synth.activations(SEED, "prefill/%dx%d/x" % (N, K), M, K)
+        w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
+        x_dev = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
+        y = torch.empty((M, N), dtype=torch.float16, device=dev)
+        layer = fq.Layer(N, K)
+        for b in (4, 8):
+            cb, sb, zb = fq.fq_packed_sizes(N, K, b)
+            c = torch.empty(cb, dtype=torch.uint8, device=dev)
+            sc = torch.empty(sb // 4, dtype=torch.float32, device=dev)
+            z = torch.empty(zb, dtype=torch.uint8, device=dev)
+            fq.fq_quantize(w_dev, N, K, b, 128, c, sc, z)
+            layer.attach(b, c, sc, z)
+            calls.append((layer, b, x_dev, y))
+        del w_dev
+    flop = sum(2.0 * M * l.N * l.K for l, _, _, _ in calls)
+
+    def step():
+        for layer, b, x_dev, y in calls:
+            fq.fq_linear(layer, b, x_dev, M, y)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_launch = e0.elapsed_time(e1) / (args.steps * len(calls))
+    achieved = flop / len(calls) / (ms_launch * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "prefill dequant-GEMM throughput", "value": M * args.steps * len(calls) / elapsed,
+        "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "70B-shaped slice: M=2048, 8192->28672 and 28672->8192, W4 and W8 "
+                               "(4 GEMMs per step)"},
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": achieved, "peak": 2500.0,
+                     "unit": "TFLOP/s", "frac": achieved / 2500.0, "traffic": None,
+                     "avg_launch_ms": ms_launch, "flop_per_launch": flop / len(calls)}}))
+
+
+def bench_entropy(args):
+    """Batched entropy + KL over [2048][128256] fp32 logits pairs (HBM bound: 8 bytes per entry)."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev, R, V = "cuda:0", 2048, 128256
+    a, b = synth.logits_pair(SEED, "entropy/2048x128256", R, V)
+    a_dev, b_dev = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
+    H = torch.empty(R, device=dev)
+    KL = torch.empty(R, device=dev)
+    for _ in range(args.warmup):
+        fq.fq_entropy_kl(a_dev, b_dev, R, V, H, KL)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        fq.fq_entropy_kl(a_dev, b_dev, R, V, H, KL)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / args.steps
+    alg = 8.0 * R * V
+    achieved = alg / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "batched entropy+KL rows/s", "value": R * args.steps / elapsed, "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "config": {"workload": "entropy + KL over 2048 x 128256 fp32 logits pairs"},
+        "roofline": {"bound": "hbm", "kernel": "entropy_kl_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None, "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "entropy"],
+                    help="decode = the headline decode stack (default); prefill / entropy = the "
+                         "prefill-shaped GEMM slice and the batched entropy/KL on their own")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=16)
@@ -210,6 +302,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    if args.workload == "prefill":
+        return bench_prefill(args)
+    if args.workload == "entropy":
+        return bench_entropy(args)
     bit_choices = tuple(int(b) for b in args.bits.split(","))
     stack = Stack(args.stack, M=args.batch, bit_choices=bit_choices, layers=args.layers,
                   verbose=args.verbose)
@@ -325,7 +421,7 @@ def main():
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
         "entropy_kl_us": ent_us,
-        "roofline": {"bound": "hbm", "kernel": "decode_m1_kernel (plan launch)",
+        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else "decode_skinny_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.stack, args.batch, bit_choices))
