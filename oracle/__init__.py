@@ -132,3 +132,59 @@ def entropy_kl(a: np.ndarray, b: np.ndarray | None = None):
     if rc != 0:
         raise ValueError("orc_entropy_kl rejected its arguments")
     return (H, KL) if b is not None else (H, None)
+
+
+class Scheduler:
+    """Token-wise precision switching of Sec. 4.4 / Alg. 1 (oracle).  ``bits`` is an int32
+    array updated in place; ``events`` is the replacement order as (entry, new_bits) pairs."""
+
+    def __init__(self, bits: np.ndarray, events, window: int = 20, thre: float = 0.0,
+                 per_trigger: int = 1):
+        lib = _load()
+        lib.orc_sched_size.restype = ctypes.c_int
+        lib.orc_sched_init.restype = ctypes.c_int
+        lib.orc_sched_init.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                                       ctypes.c_void_p]
+        lib.orc_sched_step.restype = ctypes.c_int
+        lib.orc_sched_step.argtypes = [ctypes.c_void_p, ctypes.c_float]
+        lib.orc_sched_threshold_from_prefill.restype = None
+        lib.orc_sched_threshold_from_prefill.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                                         ctypes.c_int]
+        lib.orc_sched_thre.restype = ctypes.c_double
+        lib.orc_sched_thre.argtypes = [ctypes.c_void_p]
+        lib.orc_sched_last_mean.restype = ctypes.c_double
+        lib.orc_sched_last_mean.argtypes = [ctypes.c_void_p]
+        lib.orc_sched_next_event.restype = ctypes.c_int
+        lib.orc_sched_next_event.argtypes = [ctypes.c_void_p]
+        self._lib = lib
+        assert bits.dtype == np.int32 and bits.flags.c_contiguous
+        self.bits = bits
+        ev = np.asarray(events, dtype=np.int32).reshape(-1, 2)
+        self._entry = np.ascontiguousarray(ev[:, 0])
+        self._to = np.ascontiguousarray(ev[:, 1])
+        self.ev_token = np.full(len(ev), -1, dtype=np.int32)
+        self._state = ctypes.create_string_buffer(lib.orc_sched_size())
+        rc = lib.orc_sched_init(self._state, window, thre, per_trigger, _p(self._entry), _p(self._to),
+                                len(ev), _p(self.bits), _p(self.ev_token))
+        if rc != 0:
+            raise ValueError("orc_sched_init rejected its arguments")
+
+    def threshold_from_prefill(self, entropy: np.ndarray, last_n: int):
+        e = np.ascontiguousarray(entropy, dtype=np.float32)
+        self._lib.orc_sched_threshold_from_prefill(self._state, _p(e), e.size, last_n)
+
+    def step(self, entropy: float) -> int:
+        return int(self._lib.orc_sched_step(self._state, float(np.float32(entropy))))
+
+    @property
+    def thre(self) -> float:
+        return float(self._lib.orc_sched_thre(self._state))
+
+    @property
+    def last_mean(self) -> float:
+        return float(self._lib.orc_sched_last_mean(self._state))
+
+    @property
+    def next_event(self) -> int:
+        return int(self._lib.orc_sched_next_event(self._state))

@@ -268,3 +268,95 @@ int orc_entropy_kl(const float *a, const float *b, int R, int V, double *H, doub
     }
     return 0;
 }
+
+/* ---- Token-wise precision switching, Sec. 4.4 and Alg. 1 ---------------------------
+ *
+ * The steps of Alg. 1's decode loop that FlexQuant adds, in the paper's order:
+ *   PPLE <- exp(entropy(logits))                              (Sec. 4.2 Eq. (5))
+ *   push PPLE into a sliding window of `window` generated tokens (20 in the paper)
+ *   if the window is full and its average is below `thre`:
+ *       replace the weights of the next layers in the offline (KL-sorted) order by
+ *       their lower bit-width                                  (Sec. 4.3)
+ *       and wait until a full window of tokens has been generated at the new
+ *       precision before judging again                         (Sec. 4.5, last paragraph)
+ *
+ * Readings: the replacement order is an explicit list of events (entry, new bit-width)
+ * -- ascending KL for INT8 -> INT4, or a longer ladder FP16 -> INT8 -> INT4 --, a
+ * trigger applies the next `per_trigger` events, "wait for enough tokens" means the
+ * window is emptied at a switch.  PPLE and the average are taken in double; the average
+ * is the sum of the window's slots in slot order divided by `window`.
+ */
+typedef struct orc_sched {
+    double thre;
+    double last_mean;
+    int window, per_trigger, n_events, next_event, pos, count, token;
+    const int32_t *ev_entry;
+    const int32_t *ev_bits;
+    int32_t *bits;     /* per-entry bit-widths, updated in place */
+    int32_t *ev_token; /* out: token index at which each event fired (may be NULL) */
+    double ring[1024];
+} orc_sched;
+
+int orc_sched_size(void) { return (int)sizeof(orc_sched); }
+
+int orc_sched_init(orc_sched *s, int window, double thre, int per_trigger, const int32_t *ev_entry,
+                   const int32_t *ev_bits, int n_events, int32_t *bits, int32_t *ev_token)
+{
+    if (window < 1 || window > 1024 || per_trigger < 1 || n_events < 0)
+        return -1;
+    memset(s, 0, sizeof *s);
+    s->thre = thre;
+    s->window = window;
+    s->per_trigger = per_trigger;
+    s->n_events = n_events;
+    s->ev_entry = ev_entry;
+    s->ev_bits = ev_bits;
+    s->bits = bits;
+    s->ev_token = ev_token;
+    return 0;
+}
+
+/* thre <- average PPLE of the last `last_n` of R prefill positions (Alg. 1, line "thre <-") */
+void orc_sched_threshold_from_prefill(orc_sched *s, const float *entropy, int R, int last_n)
+{
+    if (last_n > R)
+        last_n = R;
+    double sum = 0.0;
+    for (int r = R - last_n; r < R; r++)
+        sum += exp((double)entropy[r]);
+    s->thre = sum / (double)last_n;
+}
+
+/* One generated token whose next-token entropy is `entropy` (nats).  Returns the number of
+ * events applied (0 if no switch happened). */
+int orc_sched_step(orc_sched *s, float entropy)
+{
+    const double pple = exp((double)entropy);
+    s->ring[s->pos] = pple;
+    s->pos = (s->pos + 1) % s->window;
+    if (s->count < s->window)
+        s->count++;
+    int applied = 0;
+    if (s->count == s->window) {
+        double sum = 0.0;
+        for (int i = 0; i < s->window; i++)
+            sum += s->ring[i];
+        s->last_mean = sum / (double)s->window;
+        if (s->last_mean < s->thre && s->next_event < s->n_events) {
+            for (int j = 0; j < s->per_trigger && s->next_event < s->n_events; j++) {
+                s->bits[s->ev_entry[s->next_event]] = s->ev_bits[s->next_event];
+                if (s->ev_token)
+                    s->ev_token[s->next_event] = s->token;
+                s->next_event++;
+                applied++;
+            }
+            s->count = 0; /* judge again only after a full window at the new precision */
+        }
+    }
+    s->token++;
+    return applied;
+}
+
+double orc_sched_thre(const orc_sched *s) { return s->thre; }
+double orc_sched_last_mean(const orc_sched *s) { return s->last_mean; }
+int orc_sched_next_event(const orc_sched *s) { return s->next_event; }
