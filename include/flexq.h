@@ -146,6 +146,37 @@ int fq_plan_destroy(fq_plan *plan);
 int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V,
                   float *entropy_out, float *kl_out, void *stream);
 
+/*
+ * Token-wise precision switching on the device (Sec. 4.4, Alg. 1).  Per generated token:
+ * PPLE = exp(entropy) enters a sliding window of `window` tokens (20 in the paper); when
+ * the window is full and its average is below `thre`, the next `per_trigger` events of
+ * the replacement order are applied -- event i sets bits[ev_entry[i]] = ev_bits[i]
+ * (ascending offline KL for INT8 -> INT4, Sec. 4.3; a FP16 -> INT8 -> INT4 ladder is a
+ * longer list) -- and the window is emptied, so the next judgement only sees tokens
+ * generated at the new precision.  `bits` is the array a plan reads (fq_plan_run), so
+ * the decode loop needs no host round trip.  All arithmetic in double.
+ *   state      device, fq_sched_state_bytes(window) bytes, 8-byte aligned, owned by the
+ *              caller, written by fq_sched_init and updated by every step
+ *   ev_entry, ev_bits  device, int32 [n_events]   (read; must outlive the state's use)
+ *   bits       device, int32 [entries]            (updated in place)
+ *   ev_token   device, int32 [n_events] or NULL   (written: index of the token at which
+ *              each event fired)
+ *   entropy    device, f32: one value (fq_sched_step: the entropy of this token's logits, as
+ *              written by fq_entropy_kl) or [R] (fq_sched_threshold_from_prefill, which sets
+ *              thre to the mean PPLE of the last min(last_n, R) of R prefill positions)
+ * 1 <= window <= 1024, per_trigger >= 1, n_events >= 0.  fq_sched_peek waits for `stream`
+ * and copies the counters back (any output may be NULL).
+ */
+size_t fq_sched_state_bytes(int window);
+int fq_sched_init(void *state, int window, double thre, int per_trigger,
+                  const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
+                  int32_t *bits, int32_t *ev_token, void *stream);
+int fq_sched_threshold_from_prefill(void *state, const float *entropy, int R, int last_n,
+                                    void *stream);
+int fq_sched_step(void *state, const float *entropy, void *stream);
+int fq_sched_peek(const void *state, int *next_event, int *tokens, double *thre,
+                  double *last_mean, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ FQ_OK, FQ_ERR_NULL, FQ_ERR_BITS, FQ_ERR_SHAPE, FQ_ERR_NOT_ATTACHED, FQ_ERR_ALIGN
 EXPORTS = [
     "fq_last_error", "fq_packed_sizes", "fq_quantize", "fq_layer_create", "fq_layer_attach",
     "fq_layer_destroy", "fq_linear", "fq_plan_workspace_bytes", "fq_plan_create", "fq_plan_run",
-    "fq_plan_destroy", "fq_entropy_kl",
+    "fq_plan_destroy", "fq_entropy_kl", "fq_sched_state_bytes", "fq_sched_init",
+    "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
 ]
 
 
@@ -66,6 +67,17 @@ def _load() -> ctypes.CDLL:
     L.fq_plan_destroy.argtypes = [vp]
     L.fq_entropy_kl.restype = ci
     L.fq_entropy_kl.argtypes = [vp, vp, ci, ci, vp, vp, vp]
+    L.fq_sched_state_bytes.restype = sz
+    L.fq_sched_state_bytes.argtypes = [ci]
+    L.fq_sched_init.restype = ci
+    L.fq_sched_init.argtypes = [vp, ci, ctypes.c_double, ci, vp, vp, ci, vp, vp, vp]
+    L.fq_sched_threshold_from_prefill.restype = ci
+    L.fq_sched_threshold_from_prefill.argtypes = [vp, vp, ci, ci, vp]
+    L.fq_sched_step.restype = ci
+    L.fq_sched_step.argtypes = [vp, vp, vp]
+    L.fq_sched_peek.restype = ci
+    L.fq_sched_peek.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_double),
+                                ctypes.POINTER(ctypes.c_double), vp]
     return L
 
 
@@ -181,3 +193,30 @@ class Plan:
 def fq_entropy_kl(logits_p, logits_q, R: int, V: int, entropy_out, kl_out, stream=None):
     _check(lib.fq_entropy_kl(_ptr(logits_p), _ptr(logits_q), R, V, _ptr(entropy_out), _ptr(kl_out),
                              _stream(stream)))
+
+
+def fq_sched_state_bytes(window: int) -> int:
+    return int(lib.fq_sched_state_bytes(window))
+
+
+def fq_sched_init(state, window: int, thre: float, per_trigger: int, ev_entry, ev_bits, n_events: int,
+                  bits, ev_token=None, stream=None):
+    _check(lib.fq_sched_init(_ptr(state), window, thre, per_trigger, _ptr(ev_entry), _ptr(ev_bits),
+                             n_events, _ptr(bits), _ptr(ev_token), _stream(stream)))
+
+
+def fq_sched_threshold_from_prefill(state, entropy, R: int, last_n: int, stream=None):
+    _check(lib.fq_sched_threshold_from_prefill(_ptr(state), _ptr(entropy), R, last_n, _stream(stream)))
+
+
+def fq_sched_step(state, entropy, stream=None):
+    _check(lib.fq_sched_step(_ptr(state), _ptr(entropy), _stream(stream)))
+
+
+def fq_sched_peek(state, stream=None):
+    """Returns (next_event, tokens, thre, last_mean) after waiting for the stream."""
+    ne, tk = ctypes.c_int(), ctypes.c_int()
+    th, lm = ctypes.c_double(), ctypes.c_double()
+    _check(lib.fq_sched_peek(_ptr(state), ctypes.byref(ne), ctypes.byref(tk), ctypes.byref(th),
+                             ctypes.byref(lm), _stream(stream)))
+    return ne.value, tk.value, th.value, lm.value

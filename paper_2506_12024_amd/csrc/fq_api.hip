@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -317,6 +318,79 @@ int fq_plan_destroy(fq_plan *plan)
         return fail(FQ_ERR_NULL, "fq_plan_destroy: plan is NULL or not valid");
     plan->magic = 0;
     delete plan;
+    return FQ_OK;
+}
+
+size_t fq_sched_state_bytes(int window)
+{
+    if (window < 1 || window > 1024)
+        return 0;
+    return (offsetof(FqSchedState, ring) + (size_t)window * sizeof(double) + 255) / 256 * 256;
+}
+
+int fq_sched_init(void *state, int window, double thre, int per_trigger, const int32_t *ev_entry,
+                  const int32_t *ev_bits, int n_events, int32_t *bits, int32_t *ev_token, void *stream)
+{
+    if (!state || !bits)
+        return fail(FQ_ERR_NULL, "fq_sched_init: state or bits is NULL");
+    if (window < 1 || window > 1024 || per_trigger < 1 || n_events < 0)
+        return fail(FQ_ERR_SHAPE, "fq_sched_init: need 1 <= window <= 1024, per_trigger >= 1, "
+                                  "n_events >= 0 (got %d, %d, %d)", window, per_trigger, n_events);
+    if (n_events > 0 && (!ev_entry || !ev_bits))
+        return fail(FQ_ERR_NULL, "fq_sched_init: ev_entry / ev_bits are NULL");
+    if ((reinterpret_cast<uintptr_t>(state) & 7u) || (reinterpret_cast<uintptr_t>(bits) & 3u) ||
+        (reinterpret_cast<uintptr_t>(ev_entry) & 3u) || (reinterpret_cast<uintptr_t>(ev_bits) & 3u) ||
+        (reinterpret_cast<uintptr_t>(ev_token) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_sched_init: state needs 8-byte, int arrays 4-byte alignment");
+    hipError_t e = fq_launch_sched_init((FqSchedState *)state, window, thre, per_trigger, ev_entry,
+                                        ev_bits, n_events, bits, ev_token, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_sched_init launch");
+    return FQ_OK;
+}
+
+int fq_sched_threshold_from_prefill(void *state, const float *entropy, int R, int last_n, void *stream)
+{
+    if (!state || !entropy)
+        return fail(FQ_ERR_NULL, "fq_sched_threshold_from_prefill: NULL argument");
+    if (R < 1 || last_n < 1)
+        return fail(FQ_ERR_SHAPE, "fq_sched_threshold_from_prefill: need R >= 1 and last_n >= 1");
+    hipError_t e = fq_launch_sched_threshold((FqSchedState *)state, entropy, R, last_n, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_sched_threshold_from_prefill launch");
+    return FQ_OK;
+}
+
+int fq_sched_step(void *state, const float *entropy, void *stream)
+{
+    if (!state || !entropy)
+        return fail(FQ_ERR_NULL, "fq_sched_step: NULL argument");
+    hipError_t e = fq_launch_sched_step((FqSchedState *)state, entropy, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_sched_step launch");
+    return FQ_OK;
+}
+
+int fq_sched_peek(const void *state, int *next_event, int *tokens, double *thre, double *last_mean,
+                  void *stream)
+{
+    if (!state)
+        return fail(FQ_ERR_NULL, "fq_sched_peek: state is NULL");
+    FqSchedState h;
+    hipError_t e = hipMemcpyAsync(&h, state, offsetof(FqSchedState, ring), hipMemcpyDeviceToHost,
+                                  (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_sched_peek copy");
+    if (next_event)
+        *next_event = h.next_event;
+    if (tokens)
+        *tokens = h.token;
+    if (thre)
+        *thre = h.thre;
+    if (last_mean)
+        *last_mean = h.last_mean;
     return FQ_OK;
 }
 

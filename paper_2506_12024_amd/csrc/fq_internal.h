@@ -44,6 +44,24 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             int total_tiles, int tile_rows, int M, hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
 
+// Device-resident state of the precision scheduler (ring of PPLE values follows the header).
+struct FqSchedState {
+    double thre;
+    double last_mean;
+    int window, per_trigger, n_events, next_event, pos, count, token, pad;
+    const int32_t *ev_entry;
+    const int32_t *ev_bits;
+    int32_t *bits;
+    int32_t *ev_token;
+    double ring[1]; // `window` slots
+};
+hipError_t fq_launch_sched_init(FqSchedState *s, int window, double thre, int per_trigger,
+                                const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
+                                int32_t *bits, int32_t *ev_token, hipStream_t stream);
+hipError_t fq_launch_sched_threshold(FqSchedState *s, const float *entropy, int R, int last_n,
+                                     hipStream_t stream);
+hipError_t fq_launch_sched_step(FqSchedState *s, const float *entropy, hipStream_t stream);
+
 // Prefill-shaped dequant-GEMM on MFMA.
 hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream);
 
