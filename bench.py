@@ -274,9 +274,80 @@ def bench_entropy(args):
                      "traffic": None, "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg}}))
 
 
+def bench_flexquant(args):
+    """Alg. 1's decode loop on the 7B-shaped stack: every linear starts at INT8; per token the
+    plan runs at the current bit-widths, fq_entropy_kl gives the entropy of the token's logits
+    and fq_sched_step (window 20) moves the next linears of a seeded replacement order to INT4
+    when the average PPLE falls below the threshold -- all on the device, three launches per
+    token.  The logits are synthetic with an entropy that falls as generation proceeds (the
+    behaviour Sec. 4.2 reports): one seeded N(0, 1) vector scaled by a growing factor."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev = "cuda:0"
+    T = max(args.steps, 64)
+    stack = Stack(args.stack, M=1, bit_choices=(4, 8), layers=args.layers, verbose=args.verbose)
+    n = len(stack.layers)
+    base = synth.normal_f32(SEED, "flexquant/logits", VOCAB, 1.0)
+    scale = (2.0 + 2.0 * np.arange(T, dtype=np.float32) / T)[:, None]
+    logits = torch.from_numpy(base[None, :] * scale).to(dev)
+    order = np.argsort(synth.normal_f32(SEED, "flexquant/order", n, 1.0)).astype(np.int32)
+    ev_entry = torch.from_numpy(order).to(dev)
+    ev_bits = torch.full((n,), 4, dtype=torch.int32, device=dev)
+    bits = torch.full((n,), 8, dtype=torch.int32, device=dev)
+    ev_token = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    H = torch.zeros(T, dtype=torch.float32, device=dev)
+    state = torch.zeros(fq.fq_sched_state_bytes(20), dtype=torch.uint8, device=dev)
+    per_trigger = max(1, n // 28)   # the whole order is walked within the run
+
+    def generate(sched: bool):
+        for t in range(T):
+            stack.plan.run(bits)
+            fq.fq_entropy_kl(logits[t], None, 1, VOCAB, H[t:t + 1], None)
+            if sched:
+                fq.fq_sched_step(state, H[t:t + 1])
+
+    # threshold: the mean PPLE of 20 "prefill" positions taken at the start of the run
+    generate(False)
+    fq.fq_sched_init(state, 20, 0.0, per_trigger, ev_entry, ev_bits, n, bits, ev_token)
+    fq.fq_sched_threshold_from_prefill(state, H, 20, 20)
+    torch.cuda.synchronize()
+    results = {}
+    for name, start, sched in (("int8", 8, False), ("int4", 4, False), ("flexquant", 8, True)):
+        bits.fill_(start)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        generate(sched)
+        torch.cuda.synchronize()
+        results[name] = T / (time.perf_counter() - t0)
+    next_event, tokens, thre, last_mean = fq.fq_sched_peek(state)
+    fired = ev_token.cpu().numpy()
+    fired = fired[fired >= 0]
+    # average bit-width over the generation, weighted by weights per entry
+    sizes = np.array([N * K for (_, _, K, N) in stack.entries], dtype=np.float64)
+    at4 = np.zeros(n)
+    tok = ev_token.cpu().numpy()
+    for i, e in enumerate(order):
+        if tok[i] >= 0:
+            at4[e] = (T - 1 - tok[i]) / T
+    avg_bits = float(((8 - 4 * at4) * sizes).sum() / sizes.sum())
+    print(json.dumps({
+        "metric": "decode tokens/s with on-device precision switching", "value": results["flexquant"],
+        "unit": "tokens/s", "n_gpus": 1, "steps": T, "warmup": 0,
+        "ms_per_step": 1e3 / results["flexquant"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s stack, batch 1, INT8 -> INT4 by the PPLE scheduler (window 20, %d "
+                               "linears per trigger), %d tokens" % (args.stack, per_trigger, T)},
+        "fixed_int8_tokens_per_s": results["int8"], "fixed_int4_tokens_per_s": results["int4"],
+        "speedup_over_int8": results["flexquant"] / results["int8"],
+        "events_fired": int(next_event), "events_total": n, "threshold_pple": thre,
+        "first_switch_token": int(fired.min()) if fired.size else None,
+        "last_switch_token": int(fired.max()) if fired.size else None,
+        "average_weight_bits": avg_bits}))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "entropy"],
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "entropy", "flexquant"],
                     help="decode = the headline decode stack (default); prefill / entropy = the "
                          "prefill-shaped GEMM slice and the batched entropy/KL on their own")
     ap.add_argument("--gpus", type=int, default=1)
@@ -306,6 +377,8 @@ def main():
         return bench_prefill(args)
     if args.workload == "entropy":
         return bench_entropy(args)
+    if args.workload == "flexquant":
+        return bench_flexquant(args)
     bit_choices = tuple(int(b) for b in args.bits.split(","))
     stack = Stack(args.stack, M=args.batch, bit_choices=bit_choices, layers=args.layers,
                   verbose=args.verbose)
