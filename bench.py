@@ -30,10 +30,10 @@ if ROOT not in sys.path:
 import synth  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
-# HBM bytes of one plan launch of the default workload measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy (profiles/decode_m1_plan_llama7b_hbm_traffic.md);
-# reported only for that workload.
-MEASURED_TRAFFIC_BYTES = {("llama7b", 1, (4, 8)): 5004389 * 1024}
+# HBM bytes per plan launch of the default workload relative to its algorithmic bytes, measured
+# with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
+# (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
+MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993230.0 / 4978290.0}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
 VOCAB = 32000
 SEED = 0
@@ -497,8 +497,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else "decode_skinny_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.stack, args.batch, bit_choices))
-                     if args.layers is None else None,
+                     "traffic": alg_bytes * MEASURED_TRAFFIC_RATIO[(args.stack, args.batch, bit_choices)]
+                     if args.layers is None and (args.stack, args.batch, bit_choices) in MEASURED_TRAFFIC_RATIO
+                     else None,
                      "avg_launch_ms": lin_ms, "algorithmic_bytes_per_launch": alg_bytes},
     }
     if switching is not None:
