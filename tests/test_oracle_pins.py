@@ -66,8 +66,12 @@ def _golden_cases():
             if not line or line.startswith("#"):
                 continue
             bits, vals, s, z, codes = [p.strip() for p in line.split(";")]
+            fill = 0.0
+            if vals.startswith("fill="):
+                first, vals = vals.split(None, 1)
+                fill = float(first[5:])
             out.append((int(bits), [float(v) for v in vals.split()], float(s), int(z),
-                        [int(c) for c in codes.split()]))
+                        [int(c) for c in codes.split()], fill))
     return out
 
 
@@ -83,8 +87,8 @@ def _unpack(codes, bits):
 
 @pytest.mark.parametrize("case", _golden_cases())
 def test_quantize_hand_cases(case):
-    bits, vals, s_exp, z_exp, codes_exp = case
-    w = np.zeros((1, G), dtype=np.float16)
+    bits, vals, s_exp, z_exp, codes_exp, fill = case
+    w = np.full((1, G), fill, dtype=np.float16)
     w[0, :len(vals)] = vals
     assert np.array_equal(w[0, :len(vals)].astype(np.float64), vals), "case values must be exact halves"
     codes, scales, zeros = oracle.quantize(w, bits, G)
@@ -93,7 +97,8 @@ def test_quantize_hand_cases(case):
     q = _unpack(codes, bits)[0]
     assert list(q[:len(vals)]) == codes_exp
     # padding zeros map to the zero point (or 0 for the all-zero group)
-    assert np.all(q[len(vals):] == z_exp)
+    if fill == 0.0:
+        assert np.all(q[len(vals):] == z_exp)
 
 
 def test_pack_bytes_hand_case():
@@ -247,17 +252,23 @@ def test_linear_on_grid_weights_exact_rational():
 
 
 def test_linear_matches_double_triple_loop_tiny():
-    w = synth.weight(6, "pins/lin", 3, 128, 0.02)
-    x = synth.activations(6, "pins/x", 2, 128)
+    # three groups per row with visibly different scales and zero points: every k must use
+    # the scale and zero of its own group
+    w = synth.weight(6, "pins/lin", 3, 384, 0.02)
+    w[:, 128:256] *= np.float16(3.0)
+    w[:, 256:384] += np.float16(0.05)
+    x = synth.activations(6, "pins/x", 2, 384)
     for bits in (4, 8):
         codes, scales, zeros = oracle.quantize(w, bits, G)
+        assert len(set(scales[0])) == 3 and len(set(zeros[0])) >= 2
         q = _unpack(codes, bits)
         y = oracle.linear(x, codes, scales, zeros, bits, G)
         for m in range(2):
             for n in range(3):
                 acc = 0.0
-                for k in range(128):
-                    w_hat = np.float32(np.float32(q[n, k] - int(zeros[n, 0])) * scales[n, 0])
+                for k in range(384):
+                    g = k // 128
+                    w_hat = np.float32(np.float32(q[n, k] - int(zeros[n, g])) * scales[n, g])
                     acc += float(x[m, k]) * float(w_hat)
                 assert y[m, n] == np.float16(acc)
 
