@@ -3,19 +3,25 @@
 // and the contraction is compute bound (Sec. 4.1) -- a dense GEMM on the matrix cores with
 // the dequantization of Sec. 2.2 Eq. (3) fused into the operand path.
 //
-// Tiling.  A workgroup (4 wavefronts, 2 x 2) owns a 128 (tokens) x 128 (weight rows) tile
-// of y and walks K in steps of 64; each wavefront owns 64 x 64 = 2 x 2 MFMA tiles of
-// v_mfma_f32_32x32x16_f16 (A = x: 32 tokens x 16 k, B = weights: 16 k x 32 rows, binary32
-// accumulators).  Per step the workgroup brings in a 128 x 64 slab of x (halves) and the
-// matching 128 x 64 slab of packed weights; the weights are unpacked in registers to the
-// exact integers q - z as halves (same bit tricks as the decode kernels) and both slabs are
-// written to LDS, from where the MFMA operands are read as 128-bit vectors.  The global
-// loads of step i+1 are issued before the MFMAs of step i (register prefetch).
+// Tiling.  A workgroup (4 wavefronts) owns a 128 (tokens) x 256 (weight rows) tile of y and
+// walks K in steps of 64.  The wavefronts split the weight rows: each owns 64 rows x all
+// 128 tokens = 4 x 2 tiles of v_mfma_f32_32x32x16_f16 (A = x: 32 tokens x 16 k, B =
+// weights: 16 k x 32 rows; 128 binary32 accumulator registers).
+//   - x goes through LDS: the 128 x 64 slab of a step is written once (double buffered,
+//     one barrier per step) and every wavefront reads its A operands from it as 128-bit
+//     vectors, 4 reads per 8 MFMAs.
+//   - the weights never touch LDS: lane (n = lane % 32, c = lane / 32) loads 16 bytes of row
+//     n straight from global memory in the MFMA's own operand layout, two steps ahead, and
+//     dequantizes them in registers.  No other wavefront needs the same rows, so nothing
+//     is unpacked twice.
 //
-// Scale.  The products of one quantization group (two steps) are summed in a zeroed
-// accumulator; at the end of the group every lane, which owns one weight row per MFMA
-// tile, folds it into the running output as out += s[n][g] * acc.  This is Eq. (3) with the
-// scale factored out of the group, in binary32, exactly as the decode kernels do.
+// Dequantization.  Codes become the exact integers q - z as halves (same bit tricks as the
+// decode kernels) and are multiplied by the group's scale rounded to half (one
+// v_pk_mul_f16 per register): the MFMA operand is half((q - z) * half(s)).  The decode
+// kernels keep the scale in binary32 outside the group sum; here that would need a second
+// set of 128 accumulator registers per wavefront and a 384-instruction fold per group, so
+// the prefill path rounds twice at 2^-11 relative instead.  The error stays well inside the
+// 2e-3 bound (about 5e-4 of the output magnitude in the worst one-group case).
 //
 // Workgroups that share a weight slab (the M tiles of one N tile) get consecutive logical
 // ids, and logical ids are dealt to the 8 XCDs in contiguous runs, so that a slab is
@@ -35,8 +41,10 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int THREADS = 256;
-constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int BM = 128, BN = 256, BK = 64;
+constexpr int WN = BN / 4;  // weight rows per wavefront (2 MFMA tiles)
 constexpr int LDK = BK + 8; // halves per LDS row: 144 bytes, keeps 128-bit reads conflict-free
+constexpr int XLD = BM * (BK / 8) / THREADS; // 16-byte pieces of the x slab per thread (4)
 
 __device__ __forceinline__ uint4 load16(const void *p)
 {
@@ -44,72 +52,126 @@ __device__ __forceinline__ uint4 load16(const void *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-__device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
+// (a + b) * s, each operation rounded to half; a + b is the exact integer q - z
+__device__ __forceinline__ uint32_t deq(uint32_t a, uint32_t b, half2_t s)
 {
-    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b));
+    return __builtin_bit_cast(uint32_t, (__builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b)) * s);
 }
 
-__device__ __forceinline__ float16_t mfma32(uint4 a, uint4 b, float16_t c)
+__device__ __forceinline__ float16_t mfma32(uint4 a, const uint32_t (&b)[4], float16_t c)
 {
     const u32x4 av = {a.x, a.y, a.z, a.w};
-    const u32x4 bv = {b.x, b.y, b.z, b.w};
+    const u32x4 bv = {b[0], b[1], b[2], b[3]};
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
                                                   __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
 }
 
-// Per-thread share of one K step.
-//   x slab: 128 rows x 64 halves = 1024 pieces of 16 bytes, 4 per thread
-//   w slab: 4-bit 128 x 32 bytes = 256 pieces (1 per thread); 8-bit 512 (2); fp16 1024 (4)
+// Packed weights of one K step for one lane: per n-tile, 16-byte loads covering 64 k.
+//   4-bit: 1 load (32 codes: k = 32 c ..), 8-bit: 2 loads (16 codes each: k = 32 h + 16 c ..),
+//   fp16: 4 loads (8 halves each: k = 16 i + 8 c ..)
 template <int BITS>
-struct Regs {
-    uint4 x[4];
-    uint4 w[BITS == 4 ? 1 : (BITS == 8 ? 2 : 4)];
-    uint32_t z;
+struct WRegs {
+    static constexpr int NL = BITS == 4 ? 1 : (BITS == 8 ? 2 : 4);
+    uint4 w[2][NL];
+    float s[2];
+    uint32_t z[2];
 };
 
 template <int BITS>
-__device__ __forceinline__ void load_step(const FqLinearDesc &d, const uint8_t *codes,
-                                          const uint8_t *zeros, int M, int m0, int n0, int k0,
-                                          Regs<BITS> &R)
+__device__ __forceinline__ void load_w(const FqLinearDesc &d, const uint8_t *codes, const float *scales,
+                                       const uint8_t *zeros, int n_wave0, int k0, WRegs<BITS> &R)
 {
-    const int t = threadIdx.x;
-    const int K = d.K;
+    const int lane = threadIdx.x & 63, n = lane & 31, c = lane >> 5;
+    const uint32_t K = (uint32_t)d.K;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int idx = i * THREADS + t, row = idx >> 3, piece = idx & 7;
-        const int m = min(m0 + row, M - 1);
-        R.x[i] = load16(d.x + (size_t)m * K + k0 + piece * 8);
-    }
-    if (BITS == 4) {
-        const int row = t >> 1, piece = t & 1; // 32 codes = 16 bytes each
-        const int n = min(n0 + row, d.N - 1);
-        R.w[0] = load16(codes + (size_t)n * (K >> 1) + (k0 >> 1) + piece * 16);
-        R.z = ((const FQ_GLOBAL uint8_t *)zeros)[(size_t)n * (K >> 7) + (k0 >> 7)];
-    } else if (BITS == 8) {
-        const int row = t >> 1, half = t & 1; // two pieces of 16 codes each
-        const int n = min(n0 + row, d.N - 1);
+    for (int j = 0; j < 2; j++) {
+        const size_t row = (size_t)min(n_wave0 + j * 32 + n, d.N - 1);
+        if (BITS == 4) {
+            R.w[j][0] = load16(codes + row * (K >> 1) + ((k0 + 32 * c) >> 1));
+        } else if (BITS == 8) {
 #pragma unroll
-        for (int i = 0; i < 2; i++)
-            R.w[i] = load16(codes + (size_t)n * K + k0 + half * 32 + i * 16);
-        R.z = ((const FQ_GLOBAL uint8_t *)zeros)[(size_t)n * (K >> 7) + (k0 >> 7)];
-    } else {
-        const int row = t >> 1, half = t & 1; // four pieces of 8 halves each
-        const int n = min(n0 + row, d.N - 1);
+            for (int h = 0; h < 2; h++)
+                R.w[j][h] = load16(codes + row * K + k0 + 32 * h + 16 * c);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            R.w[i] = load16(codes + ((size_t)n * K + k0 + half * 32 + i * 8) * 2);
+            for (int i = 0; i < 4; i++)
+                R.w[j][i] = load16(codes + (row * K + k0 + 16 * i + 8 * c) * 2);
+        }
+        if (BITS != 16) {
+            R.s[j] = ((const FQ_GLOBAL float *)scales)[row * (K >> 7) + (k0 >> 7)];
+            R.z[j] = ((const FQ_GLOBAL uint8_t *)zeros)[row * (K >> 7) + (k0 >> 7)];
+        }
     }
 }
 
-// Write the step's slabs to LDS.  4-bit: the unpacking yields each block of 8 codes in the
-// order (0 4 1 5 2 6 3 7); x is written in the same order so the MFMA sums matching pairs.
+// The B operand (8 halves) of k16-step i for n-tile j.  Which 8 k a lane supplies:
+//   4-bit: k0 + 32 c + 8 i + (0 4 1 5 2 6 3 7)   8-bit: k0 + 32 (i/2) + 16 c + 8 (i%2) + 0..7
+//   fp16:  k0 + 16 i + 8 c + 0..7
 template <int BITS>
-__device__ __forceinline__ void store_step(const Regs<BITS> &R, uint16_t *xs, uint16_t *ws)
+__device__ __forceinline__ void b_operand(const WRegs<BITS> &R, int j, int i, uint32_t (&b)[4])
 {
-    const int t = threadIdx.x;
+    if (BITS == 4) {
+        const uint32_t z = R.z[j];
+        const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
+        const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
+        const half2_t sh = {(_Float16)R.s[j], (_Float16)R.s[j]};
+        const uint32_t ww[4] = {R.w[j][0].x, R.w[j][0].y, R.w[j][0].z, R.w[j][0].w};
+        const uint32_t v = ww[i], v8 = v >> 8;
+        b[0] = deq((v & 0x000F000Fu) | 0x64006400u, nz_lo, sh);  // (q0 - z, q4 - z) * s
+        b[1] = deq((v & 0x00F000F0u) | 0x54005400u, nz_hi, sh);  // (q1 - z, q5 - z) * s
+        b[2] = deq((v8 & 0x000F000Fu) | 0x64006400u, nz_lo, sh); // (q2 - z, q6 - z) * s
+        b[3] = deq((v8 & 0x00F000F0u) | 0x54005400u, nz_hi, sh); // (q3 - z, q7 - z) * s
+    } else if (BITS == 8) {
+        const uint32_t z = R.z[j];
+        const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
+        const half2_t sh = {(_Float16)R.s[j], (_Float16)R.s[j]};
+        const uint4 q = R.w[j][i >> 1];
+        const uint32_t lo = (i & 1) ? q.z : q.x, hi = (i & 1) ? q.w : q.y;
+        b[0] = deq(__builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u), nz, sh);
+        b[1] = deq(__builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u), nz, sh);
+        b[2] = deq(__builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u), nz, sh);
+        b[3] = deq(__builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u), nz, sh);
+    } else {
+        b[0] = R.w[j][i].x;
+        b[1] = R.w[j][i].y;
+        b[2] = R.w[j][i].z;
+        b[3] = R.w[j][i].w;
+    }
+}
+
+// 16-byte block of x (8 halves, block index inside the 64-k step) that pairs with b_operand.
+template <int BITS>
+__device__ __forceinline__ int a_block(int i, int c)
+{
+    if (BITS == 4)
+        return 4 * c + i;
+    if (BITS == 8)
+        return 4 * (i >> 1) + 2 * c + (i & 1);
+    return 2 * i + c;
+}
+
+struct XRegs {
+    uint4 x[XLD];
+};
+
+__device__ __forceinline__ void load_x(const FqLinearDesc &d, int M, int m0, int k0, XRegs &R)
+{
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int idx = i * THREADS + t, row = idx >> 3, piece = idx & 7;
+    for (int i = 0; i < XLD; i++) {
+        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
+        const int m = min(m0 + row, M - 1);
+        R.x[i] = load16(d.x + (size_t)m * d.K + k0 + piece * 8);
+    }
+}
+
+// 4-bit: the unpacking yields each block of 8 codes in the order (0 4 1 5 2 6 3 7); x is
+// written in the same order so that the MFMA sums matching pairs.
+template <int BITS>
+__device__ __forceinline__ void store_x(const XRegs &R, uint16_t *xs)
+{
+#pragma unroll
+    for (int i = 0; i < XLD; i++) {
+        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
         uint4 v = R.x[i];
         if (BITS == 4) {
             uint4 p;
@@ -121,53 +183,13 @@ __device__ __forceinline__ void store_step(const Regs<BITS> &R, uint16_t *xs, ui
         }
         *reinterpret_cast<uint4 *>(xs + row * LDK + piece * 8) = v;
     }
-    if (BITS == 4) {
-        const int row = t >> 1, piece = t & 1;
-        const uint32_t z = R.z;
-        const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
-        const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
-        const uint32_t ww[4] = {R.w[0].x, R.w[0].y, R.w[0].z, R.w[0].w};
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const uint32_t v = ww[i], v8 = v >> 8;
-            uint4 o;
-            o.x = pk_add((v & 0x000F000Fu) | 0x64006400u, nz_lo);  // (q0 - z, q4 - z)
-            o.y = pk_add((v & 0x00F000F0u) | 0x54005400u, nz_hi);  // (q1 - z, q5 - z)
-            o.z = pk_add((v8 & 0x000F000Fu) | 0x64006400u, nz_lo); // (q2 - z, q6 - z)
-            o.w = pk_add((v8 & 0x00F000F0u) | 0x54005400u, nz_hi); // (q3 - z, q7 - z)
-            *reinterpret_cast<uint4 *>(ws + row * LDK + piece * 32 + i * 8) = o;
-        }
-    } else if (BITS == 8) {
-        const int row = t >> 1, half = t & 1;
-        const uint32_t z = R.z;
-        const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
-#pragma unroll
-        for (int i = 0; i < 2; i++) {
-            const uint32_t ww[4] = {R.w[i].x, R.w[i].y, R.w[i].z, R.w[i].w};
-#pragma unroll
-            for (int h = 0; h < 2; h++) {
-                uint4 o;
-                o.x = pk_add(__builtin_amdgcn_perm(0x64646464u, ww[2 * h], 0x04010400u), nz);
-                o.y = pk_add(__builtin_amdgcn_perm(0x64646464u, ww[2 * h], 0x04030402u), nz);
-                o.z = pk_add(__builtin_amdgcn_perm(0x64646464u, ww[2 * h + 1], 0x04010400u), nz);
-                o.w = pk_add(__builtin_amdgcn_perm(0x64646464u, ww[2 * h + 1], 0x04030402u), nz);
-                *reinterpret_cast<uint4 *>(ws + row * LDK + half * 32 + i * 16 + h * 8) = o;
-            }
-        }
-    } else {
-        const int row = t >> 1, half = t & 1;
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-            *reinterpret_cast<uint4 *>(ws + row * LDK + half * 32 + i * 8) = R.w[i];
-    }
 }
 
 template <int BITS>
-__global__ __launch_bounds__(THREADS) void prefill_kernel(const FqLinearDesc d, int M, int m_tiles,
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(const FqLinearDesc d, int M, int m_tiles,
                                                           int n_tiles, int per_xcd)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t xs[BM * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t ws[BN * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM * LDK];
 
     // hardware deals consecutive workgroup ids round-robin to the 8 XCDs: give each XCD a
     // contiguous run of logical tiles
@@ -181,72 +203,71 @@ __global__ __launch_bounds__(THREADS) void prefill_kernel(const FqLinearDesc d, 
     const uint8_t *zeros = BITS == 4 ? d.zeros4 : d.zeros8;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64; // wavefront's corner inside the tile
-    const int l32 = lane & 31, khalf = lane >> 5;
+    const int l32 = lane & 31, c = lane >> 5;
+    const int n_wave0 = n0 + wave * WN;
 
-    float16_t acc[2][2], out[2][2];
+    float16_t acc[4][2];
 #pragma unroll
-    for (int a = 0; a < 2; a++)
+    for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int b = 0; b < 2; b++)
+        for (int j = 0; j < 2; j++)
 #pragma unroll
-            for (int v = 0; v < 16; v++) {
-                acc[a][b][v] = 0.f;
-                out[a][b][v] = 0.f;
-            }
+            for (int v = 0; v < 16; v++)
+                acc[i][j][v] = 0.f;
 
-    const int nsteps = d.K / BK; // K is a multiple of 128: an even number of steps
-    Regs<BITS> R;
-    load_step<BITS>(d, codes, zeros, M, m0, n0, 0, R);
-    for (int s = 0; s < nsteps; s++) {
-        __syncthreads(); // everyone is done reading the previous slabs
-        store_step<BITS>(R, xs, ws);
-        __syncthreads();
-        // prefetch the next step (the last iteration re-reads its own: keeps the waits counted)
-        load_step<BITS>(d, codes, zeros, M, m0, n0, min(s + 1, nsteps - 1) * BK, R);
+    const int nsteps = d.K / BK;
+    XRegs X;
+    WRegs<BITS> W0, W1;
+    load_x(d, M, m0, 0, X);
+    load_w<BITS>(d, codes, scales, zeros, n_wave0, 0, W0);
+    store_x<BITS>(X, xs[0]);
+    load_x(d, M, m0, min(1, nsteps - 1) * BK, X);
+    load_w<BITS>(d, codes, scales, zeros, n_wave0, min(1, nsteps - 1) * BK, W1);
+    __syncthreads();
+
+    // One step: MFMAs of step s from xs[s & 1] and Wcur; meanwhile x of step s+1 goes from
+    // registers to the other LDS buffer, and the loads of step s+2 (x and weights) are issued.
+    auto step = [&](int s, WRegs<BITS> &Wcur) {
+        const uint16_t *xc = xs[s & 1];
+        store_x<BITS>(X, xs[(s + 1) & 1]); // last read in step s-1: a barrier has passed since
+        load_x(d, M, m0, min(s + 2, nsteps - 1) * BK, X);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            uint4 a[2], b[2];
+        for (int i = 0; i < 4; i++) {
+            uint4 a[4];
 #pragma unroll
-            for (int i = 0; i < 2; i++) {
-                a[i] = *reinterpret_cast<const uint4 *>(xs + (wm + i * 32 + l32) * LDK + kk + khalf * 8);
-                b[i] = *reinterpret_cast<const uint4 *>(ws + (wn + i * 32 + l32) * LDK + kk + khalf * 8);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; i++)
-#pragma unroll
-                for (int j = 0; j < 2; j++)
-                    acc[i][j] = mfma32(a[i], b[j], acc[i][j]);
-        }
-        if (BITS != 16 && (s & 1)) { // a group of 128 k is complete
-            const int g = (s * BK) >> 7;
+            for (int mt = 0; mt < 4; mt++)
+                a[mt] = *reinterpret_cast<const uint4 *>(xc + (mt * 32 + l32) * LDK + a_block<BITS>(i, c) * 8);
 #pragma unroll
             for (int j = 0; j < 2; j++) {
-                const int n = min(n0 + wn + j * 32 + l32, d.N - 1);
-                const float sc = ((const FQ_GLOBAL float *)scales)[(size_t)n * (d.K >> 7) + g];
+                uint32_t b[4];
+                b_operand<BITS>(Wcur, j, i, b);
 #pragma unroll
-                for (int i = 0; i < 2; i++) {
-                    out[i][j] += sc * acc[i][j];
-#pragma unroll
-                    for (int v = 0; v < 16; v++)
-                        acc[i][j][v] = 0.f;
-                }
+                for (int mt = 0; mt < 4; mt++)
+                    acc[mt][j] = mfma32(a[mt], b, acc[mt][j]);
             }
         }
+        // Wcur is free: refill it for step s+2 (always issued: keeps the waits counted)
+        load_w<BITS>(d, codes, scales, zeros, n_wave0, min(s + 2, nsteps - 1) * BK, Wcur);
+        __syncthreads(); // xs[(s+1)&1] complete, xs[s&1] no longer read
+    };
+    // K is a multiple of 128, so the number of steps is even: two steps per trip, straight
+    // line, each with its own register set for the weights
+    for (int s = 0; s < nsteps; s += 2) {
+        step(s, W0);
+        step(s + 1, W1);
     }
     // D layout of the 32x32 MFMA: lane holds column l32, rows 8 * (v / 4) + 4 * (lane / 32) + v % 4.
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int mt = 0; mt < 4; mt++)
 #pragma unroll
         for (int j = 0; j < 2; j++) {
-            const int n = n0 + wn + j * 32 + l32;
+            const int n = n_wave0 + j * 32 + l32;
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * khalf + (v & 3);
-                const float val = BITS == 16 ? acc[i][j][v] : out[i][j][v];
+                const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
                 if (m < M && n < d.N)
                     ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + n] =
-                        __builtin_bit_cast(uint16_t, (_Float16)val);
+                        __builtin_bit_cast(uint16_t, (_Float16)acc[mt][j][v]);
             }
         }
 }
