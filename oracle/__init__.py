@@ -47,6 +47,12 @@ def _load():
         lib.orc_linear.argtypes = [vp, ci, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         lib.orc_entropy_kl.restype = ci
         lib.orc_entropy_kl.argtypes = [vp, vp, ci, ci, vp, vp]
+        lib.orc_rank_ascending.restype = ci
+        lib.orc_rank_ascending.argtypes = [vp, ci, ci, vp]
+        lib.orc_quantize_act.restype = ci
+        lib.orc_quantize_act.argtypes = [vp, ci, ci, vp, vp]
+        lib.orc_linear_w8a8.restype = ci
+        lib.orc_linear_w8a8.argtypes = [vp, vp, ci, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         _lib = lib
     return _lib
 
@@ -132,6 +138,51 @@ def entropy_kl(a: np.ndarray, b: np.ndarray | None = None):
     if rc != 0:
         raise ValueError("orc_entropy_kl rejected its arguments")
     return (H, KL) if b is not None else (H, None)
+
+
+def rank_ascending(values: np.ndarray) -> np.ndarray:
+    """Replacement order of Sec. 4.3: entries sorted by ascending KL.  values: float32 [n] or
+    [n][m] (m calibration rows per entry, ranked by their sum); returns int32 [n]."""
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    if v.ndim == 1:
+        v = v[:, None]
+    n, m = v.shape
+    order = np.zeros(n, dtype=np.int32)
+    if _load().orc_rank_ascending(_p(v), n, m, _p(order)) != 0:
+        raise ValueError("orc_rank_ascending rejected its arguments")
+    return order
+
+
+def quantize_act(x: np.ndarray):
+    """Per-token symmetric 8-bit activation quantization (W8A8 prefill, Sec. 4.3; the
+    symmetric form stated after Eq. 3).  x: fp16 [M][K]; returns (xq int8 [M][K], sx f32 [M])."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    M, K = x.shape
+    xq = np.zeros((M, K), dtype=np.int8)
+    sx = np.zeros(M, dtype=np.float32)
+    if _load().orc_quantize_act(_p(x), M, K, _p(xq), _p(sx)) != 0:
+        raise ValueError("orc_quantize_act rejected its input (non-finite activation or bad shape)")
+    return xq, sx
+
+
+def linear_w8a8(xq: np.ndarray, sx: np.ndarray, codes, scales, zeros, group: int = 128,
+                row0: int = 0, rows: int | None = None) -> np.ndarray:
+    """y = dequant(xq, sx) . dequant(W8)^T, fp16 [M][rows]."""
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    sx = np.ascontiguousarray(sx, dtype=np.float32)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    M, K = xq.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == K and sx.shape == (M,)
+    rows = N - row0 if rows is None else rows
+    y = np.empty((M, rows), dtype=np.float16)
+    rc = _load().orc_linear_w8a8(_p(xq), _p(sx), M, _p(codes), _p(scales), _p(zeros), N, K, group,
+                                 row0, rows, _p(y))
+    if rc != 0:
+        raise ValueError("orc_linear_w8a8 rejected its arguments")
+    return y
 
 
 class Scheduler:

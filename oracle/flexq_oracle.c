@@ -13,6 +13,9 @@
  *   orc_entropy_kl   softmax of Sec. 2.3, the entropy inside the perplexity
  *                    entropy of Sec. 4.2 Eq. (5), and the KL divergence of
  *                    Sec. 3.1 between two next-token distributions
+ *   orc_sched_*      token-wise precision switching, Sec. 4.4 and Alg. 1
+ *   orc_rank_ascending   the replacement order of Sec. 4.3 (ascending KL)
+ *   orc_quantize_act, orc_linear_w8a8   the W8A8 prefill of Sec. 4.1 / 4.3 / 4.5
  *
  * Readings taken where the paper is silent (kept in step with the design
  * notes of this repository):
@@ -360,3 +363,109 @@ int orc_sched_step(orc_sched *s, float entropy)
 double orc_sched_thre(const orc_sched *s) { return s->thre; }
 double orc_sched_last_mean(const orc_sched *s) { return s->last_mean; }
 int orc_sched_next_event(const orc_sched *s) { return s->next_event; }
+
+/* ---- Offline replacement order, Sec. 4.3 -------------------------------------------
+ *
+ * Linear layers with the smaller KL divergence are replaced first.  values: [n][m]
+ * float, the KL of entry e on each of m calibration rows; the key of an entry is the sum
+ * of its m values in double, taken in index order.  order[i] = the entry with the i-th
+ * smallest key; equal keys keep their index order; keys that are NaN come last (again in
+ * index order).  Plain insertion sort.
+ */
+int orc_rank_ascending(const float *values, int n, int m, int32_t *order)
+{
+    if (n < 0 || m < 1)
+        return -1;
+    for (int e = 0; e < n; e++) {
+        double key = 0.0;
+        for (int j = 0; j < m; j++)
+            key += (double)values[(long long)e * m + j];
+        /* insert e after every entry already placed whose key is <= key */
+        int pos = e;
+        while (pos > 0) {
+            int prev = order[pos - 1];
+            double pk = 0.0;
+            for (int j = 0; j < m; j++)
+                pk += (double)values[(long long)prev * m + j];
+            int prev_after = isnan(pk) ? !isnan(key) : (!isnan(key) && pk > key);
+            if (!prev_after)
+                break;
+            order[pos] = prev;
+            pos--;
+        }
+        order[pos] = e;
+    }
+    return 0;
+}
+
+/* ---- W8A8 prefill, Sec. 4.1 / 4.3 / 4.5 ----------------------------------------------
+ *
+ * The prefill runs 8-bit weights against 8-bit activations on the integer matrix units.
+ * The weights are the resident INT8 copy of orc_quantize.  The paper does not say how the
+ * activations are quantized; the reading taken is the symmetric simplification stated
+ * after Eq. (3), per token (row of x): z = 0, Xmax = -Xmin = max |x|,
+ * q_max - q_min = 2^8 - 2, so s = (2 max|x|) / 254 and q = round(x / s) in [-127, 127],
+ * in binary32 with one rounding per operation, round-half-to-even; an all-zero row gets
+ * s = 1.  Returns -1 on a non-finite activation.
+ */
+int orc_quantize_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx)
+{
+    if (M < 0 || K < 1)
+        return -1;
+    int bad = 0;
+    for (long long m = 0; m < M; m++) {
+        float amax = 0.0f;
+        for (int k = 0; k < K; k++) {
+            float v = fabsf(half_to_float(x[m * K + k]));
+            if (!isfinite(v))
+                bad = 1;
+            if (v > amax) amax = v;
+        }
+        float s = 1.0f;
+        if (amax > 0.0f) {
+            volatile float range = amax + amax; /* Xmax - Xmin */
+            volatile float sv = range / 254.0f;
+            s = sv;
+        }
+        sx[m] = s;
+        for (int k = 0; k < K; k++) {
+            volatile float t = half_to_float(x[m * K + k]) / s;
+            float q = rintf(t);
+            if (q < -127.0f) q = -127.0f;
+            if (q > 127.0f) q = 127.0f;
+            xq[m * K + k] = (int8_t)q;
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * y = x_hat . w_hat^T with both operands dequantized by Eq. (3): x_hat[m][k] =
+ * xq[m][k] * sx[m] (z = 0) and w_hat as in orc_linear at 8 bits, each a binary32 value;
+ * the sum over k runs in index order in double and is rounded once to binary16.
+ * Rows row0 .. row0+rows-1 of the output; y: [M][rows].
+ */
+int orc_linear_w8a8(const int8_t *xq, const float *sx, int M, const uint8_t *codes,
+                    const float *scales, const uint8_t *zeros, int N, int K, int group,
+                    int row0, int rows, uint16_t *y)
+{
+    if (group <= 0 || K % group != 0 || row0 < 0 || rows < 0 || row0 + rows > N)
+        return -1;
+    const int G = K / group;
+#pragma omp parallel for schedule(static)
+    for (long long r = 0; r < rows; r++) {
+        long long n = row0 + r;
+        for (int m = 0; m < M; m++) {
+            double acc = 0.0;
+            for (long long k = 0; k < K; k++) {
+                int g = (int)(k / group);
+                volatile float d = (float)codes[n * K + k] - (float)zeros[n * G + g];
+                volatile float wv = d * scales[n * G + g];
+                volatile float xv = (float)xq[(long long)m * K + k] * sx[m];
+                acc += (double)xv * (double)wv;
+            }
+            y[(long long)m * rows + r] = double_to_half(acc);
+        }
+    }
+    return 0;
+}
