@@ -27,6 +27,21 @@
 
 namespace {
 
+// e^x as one v_exp_f32 of x * log2(e).  The product's rounding moves a term by at most
+// |x| * 2^-24 relative; terms that carry weight have |x| < 20 or so, which leaves the sums three
+// orders of magnitude inside the 1e-4 the results are held to, and the library routine's
+// range handling costs more instructions per element than HBM delivers them.
+#define EXPF(x) __expf(x)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// Streaming load: each logit is read once, so it should not displace anything in the caches.
+__device__ __forceinline__ float4 ld4_nt(const float4 *p)
+{
+    const f32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) f32x4 *)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+#define LD4(p) ld4_nt(p)
+
 struct Partial {
     float m, S, U, D, mb, Sb;
 };
@@ -43,7 +58,7 @@ __device__ __forceinline__ void raise_max_a(Partial &p, float cm)
     if (cm > p.m) {
         if (p.S > 0.0f) {
             const float d = p.m - cm;
-            const float c = expf(d);
+            const float c = EXPF(d);
             p.U = c * (p.U + d * p.S);
             p.S *= c;
             p.D *= c;
@@ -56,7 +71,7 @@ __device__ __forceinline__ void raise_max_b(Partial &p, float cm)
 {
     if (cm > p.mb) {
         if (p.Sb > 0.0f)
-            p.Sb *= expf(p.mb - cm);
+            p.Sb *= EXPF(p.mb - cm);
         p.mb = cm;
     }
 }
@@ -65,13 +80,13 @@ template <bool HAS_B>
 __device__ __forceinline__ void add_one(Partial &p, float a, float b)
 {
     const float t = a - p.m;
-    const float e = expf(t);
+    const float e = EXPF(t);
     const bool live = e > 0.0f; // e = 0 (a = -inf or far below the maximum) adds nothing
     p.S += e;
     p.U += live ? e * t : 0.0f;
     if (HAS_B) {
         p.D += live ? e * (a - b) : 0.0f;
-        p.Sb += expf(b - p.mb);
+        p.Sb += EXPF(b - p.mb);
     }
 }
 
@@ -136,14 +151,14 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
         const int end = min(nvec, (sidx + 1) * per);
         int i = sidx * per + t;
         for (; i + 3 * THREADS < end; i += 4 * THREADS) {
-            const float4 a0 = a4[i], a1 = a4[i + THREADS], a2 = a4[i + 2 * THREADS],
-                         a3 = a4[i + 3 * THREADS];
+            const float4 a0 = LD4(a4 + i), a1 = LD4(a4 + i + THREADS), a2 = LD4(a4 + i + 2 * THREADS),
+                         a3 = LD4(a4 + i + 3 * THREADS);
             float4 b0 = zero4, b1 = zero4, b2 = zero4, b3 = zero4;
             if (HAS_B) {
-                b0 = b4[i];
-                b1 = b4[i + THREADS];
-                b2 = b4[i + 2 * THREADS];
-                b3 = b4[i + 3 * THREADS];
+                b0 = LD4(b4 + i);
+                b1 = LD4(b4 + i + THREADS);
+                b2 = LD4(b4 + i + 2 * THREADS);
+                b3 = LD4(b4 + i + 3 * THREADS);
             }
             add_vec<HAS_B>(p, a0, b0);
             add_vec<HAS_B>(p, a1, b1);
