@@ -132,6 +132,33 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream);
 int fq_plan_destroy(fq_plan *plan);
 
 /*
+ * W8A8 prefill (Sec. 4.1, 4.3, 4.5): the prompt is processed with the resident INT8 weights
+ * against 8-bit activations on the integer matrix cores.
+ *
+ * fq_quantize_act quantizes activations per token with the symmetric form stated after
+ * Sec. 2.2 Eq. (3): z = 0, s_x[m] = (2 max_k |x[m][k]|) / 254, xq = round(x / s_x) in
+ * [-127, 127]; binary32, one rounding per operation, IEEE division, round-half-to-even; an
+ * all-zero row gets s_x = 1.  It also writes xsum[g][m] = sum of xq[m][k] over group g
+ * (the GEMM needs it for the weights' zero points).  Non-finite activations are unspecified.
+ *   x_fp16  device, fp16 [M][K], 16-byte aligned            (read)
+ *   xq      device, int8 [M][K], 16-byte aligned            (written)
+ *   sx      device, f32 [M]                                 (written)
+ *   xsum    device, int32 [K/128][M]  (group-major)         (written)
+ * M >= 0 (M = 0 launches nothing), K a positive multiple of 128.
+ *
+ * fq_linear_w8a8: y[m][n] = fp16( s_x[m] * sum_g s[n][g] * sum_{k in g} xq[m][k] (q[n][k] - z[n][g]) )
+ * with q, s, z the layer's 8-bit copy (FQ_ERR_NOT_ATTACHED without one): the products and the
+ * sums inside a group are exact integers, groups are accumulated in binary32.  xq, sx, xsum
+ * as written by fq_quantize_act for the same M and the layer's K.
+ *   y_fp16  device, fp16 [M][N], 2-byte aligned             (written)
+ * M >= 1.
+ */
+int fq_quantize_act(const void *x_fp16, int M, int K, void *xq, float *sx, int32_t *xsum,
+                    void *stream);
+int fq_linear_w8a8(const fq_layer *layer, const void *xq, const float *sx, const int32_t *xsum,
+                   int M, void *y_fp16, void *stream);
+
+/*
  * Per row r of [R][V] fp32 logits (natural logarithm, 0 log 0 = 0):
  *   entropy_out[r] = - sum_i p_i ln p_i,           p = softmax(logits_p[r])
  *   kl_out[r]      =   sum_i p_i (ln p_i - ln q_i), q = softmax(logits_q[r])
@@ -145,6 +172,30 @@ int fq_plan_destroy(fq_plan *plan);
  */
 int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V,
                   float *entropy_out, float *kl_out, void *stream);
+
+/*
+ * The same reduction over binary16 logits (each widened exactly to binary32 first), e.g. the
+ * fp16 output rows that fq_linear writes: the offline KL analysis of Sec. 3.1 / 4.3 compares
+ * what a layer produces at two bit-widths.
+ *   logits_p, logits_q  device, fp16 [R][V]    (read)
+ * Everything else as fq_entropy_kl.
+ */
+int fq_entropy_kl_f16(const void *logits_p, const void *logits_q, int R, int V,
+                      float *entropy_out, float *kl_out, void *stream);
+
+/*
+ * Replacement order of Sec. 4.3: linear layers with the smaller KL divergence are replaced
+ * first.  The key of entry e is the sum of values[e][0..m) in double, in index order (m
+ * calibration rows per entry); order[i] = the entry with the i-th smallest key, equal keys
+ * in index order, NaN keys last.  `order` is what fq_sched_init takes as ev_entry.
+ *   values  device, f32 [n][m]   (read)
+ *   order   device, int32 [n]    (written: a permutation of 0 .. n-1)
+ * 0 <= n <= FQ_MAX_RANK_ENTRIES (n = 0 launches nothing), 1 <= m <= FQ_MAX_RANK_ROWS.
+ * The work grows with n * n: n is the number of linears of a model.
+ */
+#define FQ_MAX_RANK_ENTRIES 65536
+#define FQ_MAX_RANK_ROWS 4096
+int fq_rank_ascending(const float *values, int n, int m, int32_t *order, void *stream);
 
 /*
  * Token-wise precision switching on the device (Sec. 4.4, Alg. 1).  Per generated token:

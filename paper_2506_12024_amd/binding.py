@@ -22,6 +22,7 @@ EXPORTS = [
     "fq_layer_destroy", "fq_linear", "fq_plan_workspace_bytes", "fq_plan_create", "fq_plan_run",
     "fq_plan_destroy", "fq_entropy_kl", "fq_sched_state_bytes", "fq_sched_init",
     "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
+    "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
 ]
 
 
@@ -67,6 +68,14 @@ def _load() -> ctypes.CDLL:
     L.fq_plan_destroy.argtypes = [vp]
     L.fq_entropy_kl.restype = ci
     L.fq_entropy_kl.argtypes = [vp, vp, ci, ci, vp, vp, vp]
+    L.fq_entropy_kl_f16.restype = ci
+    L.fq_entropy_kl_f16.argtypes = [vp, vp, ci, ci, vp, vp, vp]
+    L.fq_rank_ascending.restype = ci
+    L.fq_rank_ascending.argtypes = [vp, ci, ci, vp, vp]
+    L.fq_quantize_act.restype = ci
+    L.fq_quantize_act.argtypes = [vp, ci, ci, vp, vp, vp, vp]
+    L.fq_linear_w8a8.restype = ci
+    L.fq_linear_w8a8.argtypes = [vp, vp, vp, vp, ci, vp, vp]
     L.fq_sched_state_bytes.restype = sz
     L.fq_sched_state_bytes.argtypes = [ci]
     L.fq_sched_init.restype = ci
@@ -193,6 +202,23 @@ class Plan:
 def fq_entropy_kl(logits_p, logits_q, R: int, V: int, entropy_out, kl_out, stream=None):
     _check(lib.fq_entropy_kl(_ptr(logits_p), _ptr(logits_q), R, V, _ptr(entropy_out), _ptr(kl_out),
                              _stream(stream)))
+
+
+def fq_entropy_kl_f16(logits_p, logits_q, R: int, V: int, entropy_out, kl_out, stream=None):
+    _check(lib.fq_entropy_kl_f16(_ptr(logits_p), _ptr(logits_q), R, V, _ptr(entropy_out), _ptr(kl_out),
+                                 _stream(stream)))
+
+
+def fq_rank_ascending(values, n: int, m: int, order, stream=None):
+    _check(lib.fq_rank_ascending(_ptr(values), n, m, _ptr(order), _stream(stream)))
+
+
+def fq_quantize_act(x, M: int, K: int, xq, sx, xsum, stream=None):
+    _check(lib.fq_quantize_act(_ptr(x), M, K, _ptr(xq), _ptr(sx), _ptr(xsum), _stream(stream)))
+
+
+def fq_linear_w8a8(layer, xq, sx, xsum, M: int, y, stream=None):
+    _check(lib.fq_linear_w8a8(layer.handle, _ptr(xq), _ptr(sx), _ptr(xsum), M, _ptr(y), _stream(stream)))
 
 
 def fq_sched_state_bytes(window: int) -> int:

@@ -213,6 +213,44 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
     return FQ_OK;
 }
 
+int fq_quantize_act(const void *x_fp16, int M, int K, void *xq, float *sx, int32_t *xsum, void *stream)
+{
+    if (M < 0 || K < FQ_GROUP || K % FQ_GROUP != 0)
+        return fail(FQ_ERR_SHAPE, "fq_quantize_act: need M >= 0 and K a positive multiple of %d (got M=%d K=%d)",
+                    FQ_GROUP, M, K);
+    if (!x_fp16 || !xq || !sx || !xsum)
+        return fail(FQ_ERR_NULL, "fq_quantize_act: NULL argument");
+    if (!aligned16(x_fp16) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u) ||
+        (reinterpret_cast<uintptr_t>(xsum) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_quantize_act: x and xq need 16-byte, sx and xsum 4-byte alignment");
+    hipError_t e = fq_launch_quantize_act(x_fp16, M, K, xq, sx, xsum, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_quantize_act launch");
+    return FQ_OK;
+}
+
+int fq_linear_w8a8(const fq_layer *layer, const void *xq, const float *sx, const int32_t *xsum, int M,
+                   void *y_fp16, void *stream)
+{
+    if (int rc = check_layer(layer))
+        return rc;
+    if (!xq || !sx || !xsum || !y_fp16)
+        return fail(FQ_ERR_NULL, "fq_linear_w8a8: NULL argument");
+    if (!layer->codes[slot_of(8)])
+        return fail(FQ_ERR_NOT_ATTACHED, "fq_linear_w8a8: no 8-bit copy attached to this layer");
+    if (M < 1)
+        return fail(FQ_ERR_SHAPE, "fq_linear_w8a8: M must be >= 1 (got %d)", M);
+    if (!aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u) || (reinterpret_cast<uintptr_t>(xsum) & 3u) ||
+        (reinterpret_cast<uintptr_t>(y_fp16) & 1u))
+        return fail(FQ_ERR_ALIGN, "fq_linear_w8a8: xq needs 16-byte, sx and xsum 4-byte, y 2-byte alignment");
+    FqLinearDesc d;
+    fill_desc(d, layer, nullptr, y_fp16);
+    hipError_t e = fq_launch_w8a8(d, xq, sx, xsum, M, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_linear_w8a8 launch");
+    return FQ_OK;
+}
+
 size_t fq_plan_workspace_bytes(int count)
 {
     if (count < 1)
@@ -409,6 +447,40 @@ int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V, fl
     hipError_t e = fq_launch_entropy_kl(logits_p, logits_q, R, V, entropy_out, kl_out, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_entropy_kl launch");
+    return FQ_OK;
+}
+
+int fq_entropy_kl_f16(const void *logits_p, const void *logits_q, int R, int V, float *entropy_out,
+                      float *kl_out, void *stream)
+{
+    if (R < 0 || V < 1)
+        return fail(FQ_ERR_SHAPE, "fq_entropy_kl_f16: need R >= 0 and V >= 1 (got R=%d V=%d)", R, V);
+    if (!logits_p || !entropy_out)
+        return fail(FQ_ERR_NULL, "fq_entropy_kl_f16: logits_p or entropy_out is NULL");
+    if ((logits_q == nullptr) != (kl_out == nullptr))
+        return fail(FQ_ERR_NULL, "fq_entropy_kl_f16: logits_q and kl_out must both be given or both be NULL");
+    if ((reinterpret_cast<uintptr_t>(logits_p) & 1u) || (reinterpret_cast<uintptr_t>(logits_q) & 1u) ||
+        (reinterpret_cast<uintptr_t>(entropy_out) & 3u) || (reinterpret_cast<uintptr_t>(kl_out) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_entropy_kl_f16: logits must be 2-byte and outputs 4-byte aligned");
+    hipError_t e = fq_launch_entropy_kl_f16((const uint16_t *)logits_p, (const uint16_t *)logits_q, R, V,
+                                            entropy_out, kl_out, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_entropy_kl_f16 launch");
+    return FQ_OK;
+}
+
+int fq_rank_ascending(const float *values, int n, int m, int32_t *order, void *stream)
+{
+    if (n < 0 || n > FQ_MAX_RANK_ENTRIES || m < 1 || m > FQ_MAX_RANK_ROWS)
+        return fail(FQ_ERR_SHAPE, "fq_rank_ascending: need 0 <= n <= %d and 1 <= m <= %d (got n=%d m=%d)",
+                    FQ_MAX_RANK_ENTRIES, FQ_MAX_RANK_ROWS, n, m);
+    if (!values || !order)
+        return fail(FQ_ERR_NULL, "fq_rank_ascending: values or order is NULL");
+    if ((reinterpret_cast<uintptr_t>(values) & 3u) || (reinterpret_cast<uintptr_t>(order) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_rank_ascending: pointers must be 4-byte aligned");
+    hipError_t e = fq_launch_rank_ascending(values, n, m, order, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_rank_ascending launch");
     return FQ_OK;
 }
 

@@ -40,7 +40,17 @@ __device__ __forceinline__ float4 ld4_nt(const float4 *p)
     const f32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) f32x4 *)p);
     return make_float4(v.x, v.y, v.z, v.w);
 }
-#define LD4(p) ld4_nt(p)
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+// Vector i of a row: four consecutive logits widened to binary32 (binary16 widens exactly).
+__device__ __forceinline__ float4 load4(const float *row, int i)
+{
+    return ld4_nt(reinterpret_cast<const float4 *>(row) + i);
+}
+__device__ __forceinline__ float4 load4(const _Float16 *row, int i)
+{
+    const half4_t v = __builtin_nontemporal_load((const __attribute__((address_space(1))) half4_t *)row + i);
+    return make_float4((float)v.x, (float)v.y, (float)v.z, (float)v.w);
+}
 
 struct Partial {
     float m, S, U, D, mb, Sb;
@@ -124,9 +134,9 @@ constexpr int MAX_SPLIT_ROWS = 64, MAX_SPLITS = 32;
 __device__ double g_part[MAX_SPLIT_ROWS][MAX_SPLITS][6];
 __device__ unsigned int g_ticket[MAX_SPLIT_ROWS];
 
-template <int THREADS, bool HAS_B, bool VEC>
-__global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__restrict__ a,
-                                                             const float *__restrict__ b, int V,
+template <int THREADS, bool HAS_B, bool VEC, typename T>
+__global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict__ a,
+                                                             const T *__restrict__ b, int V,
                                                              int splits, float *__restrict__ H,
                                                              float *__restrict__ KL)
 {
@@ -137,28 +147,26 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
 
     const int r = blockIdx.x / splits, sidx = blockIdx.x % splits;
     const int t = threadIdx.x;
-    const float *ar = a + (size_t)r * V;
-    const float *br = HAS_B ? b + (size_t)r * V : nullptr;
+    const T *ar = a + (size_t)r * V;
+    const T *br = HAS_B ? b + (size_t)r * V : ar;
 
     Partial p;
     part_init(p);
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (VEC) { // V % 4 == 0 and 16-byte aligned rows
-        const float4 *a4 = reinterpret_cast<const float4 *>(ar);
-        const float4 *b4 = reinterpret_cast<const float4 *>(br);
+    if (VEC) { // V % 4 == 0 and rows aligned to four entries
         const int nvec = V >> 2;
         const int per = (nvec + splits - 1) / splits;
         const int end = min(nvec, (sidx + 1) * per);
         int i = sidx * per + t;
         for (; i + 3 * THREADS < end; i += 4 * THREADS) {
-            const float4 a0 = LD4(a4 + i), a1 = LD4(a4 + i + THREADS), a2 = LD4(a4 + i + 2 * THREADS),
-                         a3 = LD4(a4 + i + 3 * THREADS);
+            const float4 a0 = load4(ar, i), a1 = load4(ar, i + THREADS), a2 = load4(ar, i + 2 * THREADS),
+                         a3 = load4(ar, i + 3 * THREADS);
             float4 b0 = zero4, b1 = zero4, b2 = zero4, b3 = zero4;
             if (HAS_B) {
-                b0 = LD4(b4 + i);
-                b1 = LD4(b4 + i + THREADS);
-                b2 = LD4(b4 + i + 2 * THREADS);
-                b3 = LD4(b4 + i + 3 * THREADS);
+                b0 = load4(br, i);
+                b1 = load4(br, i + THREADS);
+                b2 = load4(br, i + 2 * THREADS);
+                b3 = load4(br, i + 3 * THREADS);
             }
             add_vec<HAS_B>(p, a0, b0);
             add_vec<HAS_B>(p, a1, b1);
@@ -166,13 +174,13 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
             add_vec<HAS_B>(p, a3, b3);
         }
         for (; i < end; i += THREADS)
-            add_vec<HAS_B>(p, a4[i], HAS_B ? b4[i] : zero4);
+            add_vec<HAS_B>(p, load4(ar, i), HAS_B ? load4(br, i) : zero4);
     } else {
         const int per = (V + splits - 1) / splits;
         const int end = min(V, (sidx + 1) * per);
         for (int i = sidx * per + t; i < end; i += THREADS) {
-            const float av = ar[i];
-            const float bv = HAS_B ? br[i] : 0.0f;
+            const float av = (float)ar[i];
+            const float bv = HAS_B ? (float)br[i] : 0.0f;
             raise_max_a(p, av);
             if (HAS_B)
                 raise_max_b(p, bv);
@@ -279,30 +287,29 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const float *__rest
     }
 }
 
-template <int THREADS>
-hipError_t launch(const float *a, const float *b, int R, int V, int splits, float *H, float *KL,
+template <int THREADS, typename T>
+hipError_t launch(const T *a, const T *b, int R, int V, int splits, float *H, float *KL,
                   hipStream_t stream)
 {
-    const bool vec = (V % 4 == 0) && (((uintptr_t)a & 15) == 0) && (!b || ((uintptr_t)b & 15) == 0);
+    const uintptr_t mask = 4 * sizeof(T) - 1;
+    const bool vec = (V % 4 == 0) && (((uintptr_t)a & mask) == 0) && (!b || ((uintptr_t)b & mask) == 0);
     const dim3 grid((unsigned)R * (unsigned)splits), block(THREADS);
     if (b) {
         if (vec)
-            entropy_kl_kernel<THREADS, true, true><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, true, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
         else
-            entropy_kl_kernel<THREADS, true, false><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, true, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
     } else {
         if (vec)
-            entropy_kl_kernel<THREADS, false, true><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, false, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
         else
-            entropy_kl_kernel<THREADS, false, false><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, false, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
     }
     return hipGetLastError();
 }
 
-} // namespace
-
-hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
-                                hipStream_t stream)
+template <typename T>
+hipError_t dispatch(const T *a, const T *b, int R, int V, float *H, float *KL, hipStream_t stream)
 {
     if (R == 0)
         return hipSuccess;
@@ -311,11 +318,26 @@ hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, fl
         int splits = V / 1024;
         if (splits > MAX_SPLITS)
             splits = MAX_SPLITS;
-        return launch<256>(a, b, R, V, splits, H, KL, stream);
+        return launch<256, T>(a, b, R, V, splits, H, KL, stream);
     }
     // Otherwise one workgroup per row: large ones while there are too few rows to fill the
     // machine, 256 threads (several rows per CU) beyond that.
     if (R < 512)
-        return launch<1024>(a, b, R, V, 1, H, KL, stream);
-    return launch<256>(a, b, R, V, 1, H, KL, stream);
+        return launch<1024, T>(a, b, R, V, 1, H, KL, stream);
+    return launch<256, T>(a, b, R, V, 1, H, KL, stream);
+}
+
+} // namespace
+
+hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
+                                hipStream_t stream)
+{
+    return dispatch<float>(a, b, R, V, H, KL, stream);
+}
+
+hipError_t fq_launch_entropy_kl_f16(const uint16_t *a, const uint16_t *b, int R, int V, float *H,
+                                    float *KL, hipStream_t stream)
+{
+    return dispatch<_Float16>(reinterpret_cast<const _Float16 *>(a), reinterpret_cast<const _Float16 *>(b),
+                              R, V, H, KL, stream);
 }

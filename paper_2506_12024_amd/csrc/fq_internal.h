@@ -30,6 +30,9 @@ hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, void 
 hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
                                 hipStream_t stream);
 
+hipError_t fq_launch_entropy_kl_f16(const uint16_t *a, const uint16_t *b, int R, int V, float *H,
+                                    float *KL, hipStream_t stream);
+
 // Skinny (decode) linears.  `descs` is a device table of `count` entries when
 // `single` is null, else the one entry is passed by value and bits_host applies.
 hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
@@ -62,7 +65,18 @@ hipError_t fq_launch_sched_threshold(FqSchedState *s, const float *entropy, int 
                                      hipStream_t stream);
 hipError_t fq_launch_sched_step(FqSchedState *s, const float *entropy, hipStream_t stream);
 
+hipError_t fq_launch_rank_ascending(const float *values, int n, int m, int32_t *order,
+                                    hipStream_t stream);
+
 // Prefill-shaped dequant-GEMM on MFMA.
 hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream);
+
+
+// W8A8 prefill: per-token symmetric 8-bit activation quantization (also writes the per-group
+// code sums, [K/128][M]) and the int8 MFMA GEMM against the resident 8-bit copy.
+hipError_t fq_launch_quantize_act(const void *x, int M, int K, void *xq, float *sx, int32_t *xsum,
+                                  hipStream_t stream);
+hipError_t fq_launch_w8a8(const FqLinearDesc &d, const void *xq, const float *sx, const int32_t *xsum,
+                          int M, hipStream_t stream);
 
 #endif

@@ -108,3 +108,60 @@ hipError_t fq_launch_sched_step(FqSchedState *s, const float *entropy, hipStream
     sched_step_kernel<<<1, 64, 0, stream>>>(s, entropy);
     return hipGetLastError();
 }
+
+// Replacement order of Sec. 4.3: entries sorted by ascending KL divergence.  The key of entry
+// e is the sum of its m values (KL on m calibration rows) in double, in index order.
+// Rank by counting: the place of an entry is the number of entries that come before it
+// (smaller key; equal keys in index order; NaN keys after every number), so every place is
+// written exactly once without any exchange between workgroups.  Keys are recomputed tile by
+// tile into LDS: n is the number of linears of a model, a few hundred.
+constexpr int RANK_THREADS = 256;
+
+__global__ __launch_bounds__(RANK_THREADS) void rank_ascending_kernel(const float *__restrict__ values,
+                                                                      int n, int m,
+                                                                      int32_t *__restrict__ order)
+{
+    __shared__ double s_key[RANK_THREADS];
+    const int e = blockIdx.x * RANK_THREADS + threadIdx.x;
+    auto key_of = [&](int i) {
+        double k = 0.0;
+        for (int j = 0; j < m; j++)
+            k += (double)values[(size_t)i * m + j];
+        return k;
+    };
+    const double mine = e < n ? key_of(e) : 0.0;
+    const bool mine_nan = mine != mine;
+    int before = 0;
+    for (int base = 0; base < n; base += RANK_THREADS) {
+        const int other = base + threadIdx.x;
+        __syncthreads(); // the previous tile has been read by everyone
+        s_key[threadIdx.x] = other < n ? key_of(other) : 0.0;
+        __syncthreads();
+        const int cnt = min(RANK_THREADS, n - base);
+        for (int t = 0; t < cnt; t++) {
+            const double k = s_key[t];
+            const int idx = base + t;
+            const bool k_nan = k != k;
+            bool first; // does entry idx come before entry e?
+            if (k_nan != mine_nan)
+                first = mine_nan;
+            else if (k_nan || k == mine)
+                first = idx < e;
+            else
+                first = k < mine;
+            before += first ? 1 : 0;
+        }
+    }
+    if (e < n)
+        order[before] = e;
+}
+
+hipError_t fq_launch_rank_ascending(const float *values, int n, int m, int32_t *order,
+                                    hipStream_t stream)
+{
+    if (n == 0)
+        return hipSuccess;
+    rank_ascending_kernel<<<(n + RANK_THREADS - 1) / RANK_THREADS, RANK_THREADS, 0, stream>>>(values, n, m,
+                                                                                               order);
+    return hipGetLastError();
+}

@@ -1,0 +1,226 @@
+"""GPU parity for the W8A8 prefill path (Sec. 4.1 / 4.3 / 4.5), the entropy/KL reduction over
+binary16 logits and the ascending-KL replacement order (Sec. 4.3), through the C ABI against
+the CPU oracle on identical seeded inputs.  Bars: activation codes, scales, group sums and
+the order bit-exact; fp16 outputs within 2e-3 (max-abs normalised); entropy and KL within
+1e-4 relative (absolute floor 1e-7)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2506_12024_amd as fq
+from gpu_util import DEV, make_layer, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL_Y = 2e-3
+TOL_E = 1e-4
+FLOOR_E = 1e-7
+
+
+def gpu_quantize_act(x: np.ndarray):
+    M, K = x.shape
+    x_dev = to_dev(x)
+    xq = torch.full((M, K), 99, dtype=torch.int8, device=DEV)
+    sx = torch.full((M,), float("nan"), dtype=torch.float32, device=DEV)
+    xsum = torch.full((K // 128, M), -7, dtype=torch.int32, device=DEV)
+    fq.fq_quantize_act(x_dev, M, K, xq, sx, xsum)
+    torch.cuda.synchronize()
+    return xq, sx, xsum
+
+
+# ------------------------------------------------------------------ activation quantizer
+
+@pytest.mark.parametrize("M,K", [(1, 128), (5, 1408), (33, 4096), (300, 2048), (2, 28672)])
+def test_quantize_act_bit_exact(M, K):
+    x = synth.activations(0, "par/act/%dx%d" % (M, K), M, K)
+    if M > 2:
+        x[1] *= np.float16(40.0)
+        x[2] *= np.float16(0.003)
+    xq_ref, sx_ref = oracle.quantize_act(x)
+    xq, sx, xsum = gpu_quantize_act(x)
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    sums = xq_ref.astype(np.int32).reshape(M, K // 128, 128).sum(axis=2).T
+    assert np.array_equal(xsum.cpu().numpy(), sums)
+
+
+def test_quantize_act_degenerate_rows():
+    x = np.zeros((6, 256), dtype=np.float16)
+    x[1, :8] = [127.0, 2.5, 3.5, -2.5, -3.5, 0.5, 1.5, -0.5]      # s = 1: ties to even
+    x[2, 5] = -4.0                                                 # one negative entry
+    x[3, :] = synth.normal_f16(1, "par/act/sub", 256, 1e-6)        # subnormal halves
+    x[4, 0], x[4, 1] = 65504.0, -65504.0                           # fp16 extremes
+    x[4, 2:] = np.linspace(-3e4, 3e4, 254)
+    x[5, :] = (np.resize(np.arange(-127, 128), 256) / 128.0)       # on the grid
+    xq_ref, sx_ref = oracle.quantize_act(x)
+    xq, sx, _ = gpu_quantize_act(x)
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    assert sx_ref[0] == 1.0 and not xq_ref[0].any()
+
+
+# ------------------------------------------------------------------ W8A8 linear
+
+def _w8a8(layer, x: np.ndarray):
+    M, K = x.shape
+    xq, sx, xsum = gpu_quantize_act(x)
+    y = torch.full((M, layer.N), float("nan"), dtype=torch.float16, device=DEV)
+    fq.fq_linear_w8a8(layer, xq, sx, xsum, M, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), xq.cpu().numpy(), sx.cpu().numpy()
+
+
+@pytest.mark.parametrize("M,N,K", [(33, 100, 1408), (128, 256, 1024), (300, 200, 2048), (257, 130, 128),
+                                   (64, 129, 4096), (1, 64, 256), (129, 513, 384)])
+def test_linear_w8a8_matches_oracle(M, N, K):
+    w = synth.weight(0, "par/w8a8/%dx%d" % (N, K), N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/w8a8/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (8,))
+    y, xq, sx = _w8a8(layer, x)
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    y_ref = oracle.linear_w8a8(xq, sx, c, s, z)
+    assert y.shape == (M, N)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+    for m in (0, M // 2, M - 1):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_linear_w8a8_skewed_zero_points():
+    # one-signed groups (z = 0 or 255) make the zero-point term as large as it gets
+    rng = np.random.default_rng(21)
+    N, K, M = 96, 640, 70
+    w = np.abs(synth.weight(0, "par/w8a8/skew", N, K, 0.02)).astype(np.float16)
+    w[::2] = -w[::2]
+    x = (np.abs(synth.activations(0, "par/w8a8/skew/x", M, K)) * rng.choice([1.0, 0.2], size=(M, 1))).astype(np.float16)
+    layer, packed = make_layer(w, (8,))
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    assert set(np.unique(z)) <= {0, 255}
+    y, xq, sx = _w8a8(layer, x)
+    assert rel_err(y, oracle.linear_w8a8(xq, sx, c, s, z)) <= TOL_Y
+
+
+def test_linear_w8a8_integer_case_exact():
+    # integer weights with s = 1 (each group spans 0..255) and integer activations with
+    # max 127 (s_x = 1): the result is the integer matrix product, exact in binary16
+    rng = np.random.default_rng(9)
+    M, N, K = 130, 70, 640
+    w = rng.integers(0, 3, size=(N, K))
+    w[:, 0::128] = 0
+    w[:, 1::128] = 255
+    x = rng.integers(-2, 3, size=(M, K))
+    x[:, 0] = 127                       # meets the weight 0: adds nothing
+    x[:, 1::128] = 0                    # the 255s add nothing either
+    layer, packed = make_layer(w.astype(np.float16), (8,))
+    y, xq, sx = _w8a8(layer, x.astype(np.float16))
+    assert np.all(sx == 1.0) and np.array_equal(xq.astype(np.int64), x)
+    expect = x @ w.T
+    assert np.abs(expect).max() <= 2048
+    assert np.array_equal(y.astype(np.float64), expect.astype(np.float64))
+
+
+def test_linear_w8a8_close_to_weight_only_result():
+    # the activation rounding bound of the oracle pins, on the GPU results
+    M, N, K = 64, 128, 1024
+    w = synth.weight(0, "par/w8a8/cmp", N, K, 0.015)
+    x = synth.activations(0, "par/w8a8/cmp/x", M, K)
+    layer, packed = make_layer(w, (8,))
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    y88, xq, sx = _w8a8(layer, x)
+    y816 = oracle.linear(x, c, s, z, 8).astype(np.float64)
+    w_hat = oracle.dequant(c, s, z, 8).astype(np.float64)
+    bound = 0.5 * sx[:, None].astype(np.float64) * np.abs(w_hat).sum(axis=1)[None, :]
+    slack = TOL_Y * np.abs(y816).max()
+    assert np.all(np.abs(y88.astype(np.float64) - y816) <= bound + slack)
+
+
+# ------------------------------------------------------------------ entropy / KL over fp16 logits
+
+def _check_entropy_f16(a: np.ndarray, b, skip: int = 0):
+    """`skip` leading rows are uploaded but not reduced: with an odd V the remaining rows start
+    at an address that is only 2-byte aligned."""
+    a_dev, b_dev = to_dev(a)[skip:], None if b is None else to_dev(b)[skip:]
+    a, b = a[skip:], None if b is None else b[skip:]
+    R, V = a.shape
+    H_ref, KL_ref = oracle.entropy_kl(a.astype(np.float32), None if b is None else b.astype(np.float32))
+    H = torch.full((R,), float("nan"), device=DEV)
+    KL = torch.full((R,), float("nan"), device=DEV) if b is not None else None
+    fq.fq_entropy_kl_f16(a_dev, b_dev, R, V, H, KL)
+    torch.cuda.synchronize()
+    Hn = H.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(Hn - H_ref) <= TOL_E * np.abs(H_ref) + FLOOR_E)
+    if b is not None:
+        KLn = KL.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(KLn - KL_ref) <= TOL_E * np.abs(KL_ref) + FLOOR_E)
+
+
+@pytest.mark.parametrize("R,V", [(1, 4096), (4, 11008), (16, 4096), (3, 1001), (2, 4099), (700, 1024), (2, 1)])
+def test_entropy_kl_f16_matches_oracle(R, V):
+    a, b = synth.logits_pair(0, "par/ent16/%dx%d" % (R, V), R, V)
+    a16, b16 = a.astype(np.float16), b.astype(np.float16)
+    _check_entropy_f16(a16, b16)
+    _check_entropy_f16(a16, None)
+    if R > 1 and V % 2:
+        _check_entropy_f16(a16, b16, skip=1)
+
+
+def test_entropy_kl_f16_on_linear_outputs():
+    # what the layer-ranking analysis reduces: a layer's output at 8 bits against 4 bits
+    N, K, M = 4096, 4096, 4
+    w = synth.weight(0, "par/ent16/lin/w", N, K, 0.02, outlier_p=0.001)
+    x = synth.activations(0, "par/ent16/lin/x", M, K)
+    layer, _ = make_layer(w, (4, 8))
+    x_dev = to_dev(x)
+    y8 = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    y4 = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    fq.fq_linear(layer, 8, x_dev, M, y8)
+    fq.fq_linear(layer, 4, x_dev, M, y4)
+    torch.cuda.synchronize()
+    _check_entropy_f16(y8.cpu().numpy(), y4.cpu().numpy())
+
+
+# ------------------------------------------------------------------ replacement order
+
+def _gpu_rank(v: np.ndarray) -> np.ndarray:
+    v2 = v if v.ndim == 2 else v[:, None]
+    n, m = v2.shape
+    order = torch.full((max(n, 1),), -1, dtype=torch.int32, device=DEV)
+    fq.fq_rank_ascending(to_dev(np.ascontiguousarray(v2, dtype=np.float32)), n, m, order)
+    torch.cuda.synchronize()
+    return order.cpu().numpy()[:n]
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (7, 1), (224, 1), (224, 16), (256, 3), (257, 1), (1000, 5), (5000, 1)])
+def test_rank_matches_oracle(n, m):
+    rng = np.random.default_rng(100 + n + m)
+    v = (rng.integers(0, max(2, n // 3), size=(n, m)) * 1e-3).astype(np.float32)  # plenty of ties
+    assert np.array_equal(_gpu_rank(v), oracle.rank_ascending(v))
+
+
+def test_rank_nan_and_cancellation():
+    v = np.array([2.0, np.nan, 1.0, np.nan, 0.5], dtype=np.float32)
+    assert _gpu_rank(v).tolist() == oracle.rank_ascending(v).tolist() == [4, 2, 0, 1, 3]
+    w = np.array([[1e8, 1.0, -1e8], [0.5, 0.0, 0.0], [1e8, 2.0, -1e8]], dtype=np.float32)
+    assert _gpu_rank(w).tolist() == oracle.rank_ascending(w).tolist()
+
+
+def test_rank_feeds_the_scheduler():
+    # the order written on the device is what fq_sched_init takes as its event list
+    n = 12
+    kl = synth.normal_f32(0, "par/rank/kl", n, 1.0).astype(np.float32) ** 2
+    order = torch.empty(n, dtype=torch.int32, device=DEV)
+    fq.fq_rank_ascending(to_dev(kl), n, 1, order)
+    bits = torch.full((n,), 8, dtype=torch.int32, device=DEV)
+    ev_bits = torch.full((n,), 4, dtype=torch.int32, device=DEV)
+    state = torch.zeros(fq.fq_sched_state_bytes(2), dtype=torch.uint8, device=DEV)
+    fq.fq_sched_init(state, 2, 100.0, 3, order, ev_bits, n, bits)
+    H = torch.zeros(1, dtype=torch.float32, device=DEV)      # PPLE = 1 < 100: triggers when full
+    fq.fq_sched_step(state, H)
+    fq.fq_sched_step(state, H)
+    torch.cuda.synchronize()
+    ref_order = oracle.rank_ascending(kl)
+    expect = np.full(n, 8, dtype=np.int32)
+    expect[ref_order[:3]] = 4
+    assert np.array_equal(bits.cpu().numpy(), expect)

@@ -120,3 +120,43 @@ def test_sched_validation():
     assert L.fq_sched_step(FAKE, None, None) == B.FQ_ERR_NULL
     assert L.fq_sched_threshold_from_prefill(FAKE, FAKE, 0, 3, None) == B.FQ_ERR_SHAPE
     assert L.fq_sched_peek(None, None, None, None, None, None) == B.FQ_ERR_NULL
+
+
+def test_entropy_f16_and_rank_validation():
+    L = fq.lib
+    assert L.fq_entropy_kl_f16(FAKE, None, 1, 0, FAKE, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_entropy_kl_f16(None, None, 1, 8, FAKE, None, None) == B.FQ_ERR_NULL
+    assert L.fq_entropy_kl_f16(FAKE, FAKE, 1, 8, FAKE, None, None) == B.FQ_ERR_NULL
+    assert L.fq_entropy_kl_f16(FAKE + 1, None, 1, 8, FAKE, None, None) == B.FQ_ERR_ALIGN
+    assert L.fq_entropy_kl_f16(FAKE, None, 0, 8, FAKE, None, None) == B.FQ_OK
+    assert L.fq_rank_ascending(FAKE, -1, 1, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_rank_ascending(FAKE, 4, 0, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_rank_ascending(FAKE, 1 << 20, 1, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_rank_ascending(None, 4, 1, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_rank_ascending(FAKE, 4, 1, None, None) == B.FQ_ERR_NULL
+    assert L.fq_rank_ascending(FAKE + 2, 4, 1, FAKE, None) == B.FQ_ERR_ALIGN
+    assert L.fq_rank_ascending(FAKE, 0, 1, FAKE, None) == B.FQ_OK
+
+
+def test_w8a8_validation():
+    L = fq.lib
+    assert L.fq_quantize_act(FAKE, -1, 256, FAKE, FAKE, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_quantize_act(FAKE, 4, 200, FAKE, FAKE, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_quantize_act(FAKE, 4, 0, FAKE, FAKE, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_quantize_act(None, 4, 256, FAKE, FAKE, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_quantize_act(FAKE, 4, 256, FAKE, FAKE, None, None) == B.FQ_ERR_NULL
+    assert L.fq_quantize_act(FAKE, 4, 256, FAKE + 8, FAKE, FAKE, None) == B.FQ_ERR_ALIGN
+    assert L.fq_quantize_act(FAKE, 0, 256, FAKE, FAKE, FAKE, None) == B.FQ_OK
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 16, 256, 128) == B.FQ_OK
+    assert L.fq_linear_w8a8(None, FAKE, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linear_w8a8(h, FAKE, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
+    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_linear_w8a8(h, FAKE, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
+    assert L.fq_layer_attach(h, 8, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_linear_w8a8(h, None, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linear_w8a8(h, FAKE, FAKE, None, 4, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linear_w8a8(h, FAKE, FAKE, FAKE, 0, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_linear_w8a8(h, FAKE + 4, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_ALIGN
+    assert L.fq_linear_w8a8(h, FAKE, FAKE, FAKE, 4, FAKE + 1, None) == B.FQ_ERR_ALIGN
+    assert L.fq_layer_destroy(h) == B.FQ_OK
