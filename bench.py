@@ -240,6 +240,100 @@ def bench_prefill(args):
                      "avg_launch_ms": ms_launch, "flop_per_launch": flop / len(calls)}}))
 
 
+def bench_prefill_w8a8(args):
+    """The same 70B-shaped slice in the paper's own prefill arithmetic (Sec. 4.3: W8A8 on the
+    integer matrix units): per step, each of the two GEMMs quantizes its activations per token
+    (fq_quantize_act) and multiplies them by the resident INT8 weights (fq_linear_w8a8).  Reports
+    TOP/s of the GEMM kernel against the dense int8 MFMA peak."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev, M = "cuda:0", 2048
+    calls = []
+    for N, K in ((28672, 8192), (8192, 28672)):
+        w = synth.weight(SEED, "prefill/%dx%d/w" % (N, K), N, K, 0.015)
+        x = synth.activations(SEED, "prefill/%dx%d/x" % (N, K), M, K)
+        w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
+        x_dev = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
+        layer = fq.Layer(N, K)
+        cb, sb, zb = fq.fq_packed_sizes(N, K, 8)
+        c = torch.empty(cb, dtype=torch.uint8, device=dev)
+        sc = torch.empty(sb // 4, dtype=torch.float32, device=dev)
+        z = torch.empty(zb, dtype=torch.uint8, device=dev)
+        fq.fq_quantize(w_dev, N, K, 8, 128, c, sc, z)
+        layer.attach(8, c, sc, z)
+        del w_dev
+        calls.append((layer, x_dev, torch.empty((M, K), dtype=torch.int8, device=dev),
+                      torch.empty(M, dtype=torch.float32, device=dev),
+                      torch.empty((K // 128, M), dtype=torch.int32, device=dev),
+                      torch.empty((M, N), dtype=torch.float16, device=dev)))
+    ops = sum(2.0 * M * l.N * l.K for l, *_ in calls)
+
+    def step(gemm=True, quant=True):
+        for layer, x_dev, xq, sx, xsum, y in calls:
+            if quant:
+                fq.fq_quantize_act(x_dev, M, layer.K, xq, sx, xsum)
+            if gemm:
+                fq.fq_linear_w8a8(layer, xq, sx, xsum, M, y)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    e0.record(stream)
+    for _ in range(args.steps):
+        step(quant=False)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_launch = e0.elapsed_time(e1) / (args.steps * len(calls))
+    e0.record(stream)
+    for _ in range(args.steps):
+        step(gemm=False)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_quant = e0.elapsed_time(e1) / (args.steps * len(calls))
+    achieved = ops / len(calls) / (ms_launch * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "W8A8 prefill GEMM throughput", "value": M * args.steps * len(calls) / elapsed,
+        "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "70B-shaped slice: M=2048, 8192->28672 and 28672->8192, per-token int8 "
+                               "activations x group-128 INT8 weights (2 quantize + 2 GEMM launches per step)"},
+        "roofline": {"bound": "mfma", "kernel": "w8a8_kernel", "achieved": achieved, "peak": 5000.0,
+                     "unit": "TOP/s", "frac": achieved / 5000.0, "traffic": None,
+                     "avg_launch_ms": ms_launch, "ops_per_launch": ops / len(calls)},
+        "quantize_act_avg_launch_ms": ms_quant}))
+
+
+def kl_replacement_order(stack):
+    """The offline analysis of Sec. 3.1 / 4.3, mechanics only (synthetic weights carry no
+    meaning): every linear runs once at INT8 and once at INT4 on its own seeded input, the KL
+    divergence between softmax of the two outputs is reduced per row by fq_entropy_kl_f16, and
+    fq_rank_ascending sorts the linears by it -- smaller KL is replaced first.  Everything stays
+    on the device; returns (order int32 [n], kl f32 [n][M])."""
+    import torch
+    fq = stack.fq
+    dev, n, M = "cuda:0", len(stack.layers), stack.M
+    ys4 = [torch.empty_like(y) for y in stack.ys]
+    ws = torch.empty(fq.Plan.workspace_bytes(n), dtype=torch.uint8, device=dev)
+    plan4 = fq.Plan(stack.layers, stack.xs, ys4, M, ws)
+    stack.plan.run(torch.full((n,), 8, dtype=torch.int32, device=dev))
+    plan4.run(torch.full((n,), 4, dtype=torch.int32, device=dev))
+    kl = torch.empty((n, M), dtype=torch.float32, device=dev)
+    h = torch.empty(M, dtype=torch.float32, device=dev)
+    for e, (_, _, _, N) in enumerate(stack.entries):
+        fq.fq_entropy_kl_f16(stack.ys[e], ys4[e], M, N, h, kl[e])
+    order = torch.empty(n, dtype=torch.int32, device=dev)
+    fq.fq_rank_ascending(kl, n, M, order)
+    torch.cuda.synchronize()
+    return order, kl
+
+
 def bench_entropy(args):
     """Batched entropy + KL over [2048][128256] fp32 logits pairs (HBM bound: 8 bytes per entry)."""
     import torch
@@ -277,9 +371,10 @@ def bench_entropy(args):
 def bench_flexquant(args):
     """Alg. 1's decode loop on the 7B-shaped stack: every linear starts at INT8; per token the
     plan runs at the current bit-widths, fq_entropy_kl gives the entropy of the token's logits
-    and fq_sched_step (window 20) moves the next linears of a seeded replacement order to INT4
-    when the average PPLE falls below the threshold -- all on the device, three launches per
-    token.  The logits are synthetic with an entropy that falls as generation proceeds (the
+    and fq_sched_step (window 20) moves the next linears of the replacement order (ascending KL
+    between each linear's INT8 and INT4 output, measured once before generation through the
+    library: kl_replacement_order) to INT4 when the average PPLE falls below the threshold --
+    all on the device, three launches per token.  The logits are synthetic with an entropy that falls as generation proceeds (the
     behaviour Sec. 4.2 reports): one seeded N(0, 1) vector scaled by a growing factor."""
     import torch
     import paper_2506_12024_amd as fq
@@ -290,8 +385,9 @@ def bench_flexquant(args):
     base = synth.normal_f32(SEED, "flexquant/logits", VOCAB, 1.0)
     scale = (2.0 + 2.0 * np.arange(T, dtype=np.float32) / T)[:, None]
     logits = torch.from_numpy(base[None, :] * scale).to(dev)
-    order = np.argsort(synth.normal_f32(SEED, "flexquant/order", n, 1.0)).astype(np.int32)
-    ev_entry = torch.from_numpy(order).to(dev)
+    ev_entry, kl = kl_replacement_order(stack)
+    order = ev_entry.cpu().numpy()
+    kl_host = kl.cpu().numpy().astype(np.float64).sum(axis=1)
     ev_bits = torch.full((n,), 4, dtype=torch.int32, device=dev)
     bits = torch.full((n,), 8, dtype=torch.int32, device=dev)
     ev_token = torch.full((n,), -1, dtype=torch.int32, device=dev)
@@ -342,12 +438,15 @@ def bench_flexquant(args):
         "events_fired": int(next_event), "events_total": n, "threshold_pple": thre,
         "first_switch_token": int(fired.min()) if fired.size else None,
         "last_switch_token": int(fired.max()) if fired.size else None,
-        "average_weight_bits": avg_bits}))
+        "average_weight_bits": avg_bits,
+        "kl_order": {"first": [int(e) for e in order[:4]], "last": [int(e) for e in order[-4:]],
+                     "kl_min": float(kl_host.min()), "kl_max": float(kl_host.max()),
+                     "ascending": bool(np.all(np.diff(kl_host[order]) >= 0))}}))
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "entropy", "flexquant"],
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill-w8a8", "entropy", "flexquant"],
                     help="decode = the headline decode stack (default); prefill / entropy = the "
                          "prefill-shaped GEMM slice and the batched entropy/KL on their own")
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,6 +474,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "prefill":
         return bench_prefill(args)
+    if args.workload == "prefill-w8a8":
+        return bench_prefill_w8a8(args)
     if args.workload == "entropy":
         return bench_entropy(args)
     if args.workload == "flexquant":

@@ -14,17 +14,22 @@
 //                                        - (z[n][g] - 128) * xsum[g][m] )
 // -- q - 128 is a signed byte (one XOR of the stored code), which q - z is not.  The inner
 // sum runs on v_mfma_i32_32x32x32_i8 (A = 32 tokens x 32 k, B = 32 k x 32 weight rows), four
-// of them per group of 128; it is exact, the zero-point term is added in integers, and the
-// group result is folded into a binary32 accumulator as out += s * (float)t.
+// of them per group of 128; it is exact and is folded into a binary32 accumulator as
+// out += s * (float)sum -- two vector instructions per output and group, which is what
+// bounds the kernel.  The zero-point term, sum_g (s (128 - z))[n][g] * xsum[g][m], is a
+// second, thin contraction over the groups: it runs on v_mfma_f32_32x32x2_f32 (two groups
+// per instruction) into the same accumulators rather than costing a third vector
+// instruction per output and group.
 //
-// Tiling.  A workgroup of 4 wavefronts owns 128 tokens x 256 weight rows, a wavefront
-// 128 tokens x 64 rows = 4 x 2 MFMA tiles.  The binary32 accumulators are updated by vector
-// instructions, so they must sit in the 256 architectural registers (the other half of the
-// file only feeds MFMAs and loads): 128 of them is what leaves room for the rest.  x goes
-// through LDS (128 x 128 bytes per step, double buffered, one barrier per step); a lane
-// loads its weight rows straight from global memory in the MFMA operand layout (16
-// consecutive k of row n), two steps ahead, so no weight byte is loaded twice inside a
-// workgroup.  One step = one quantization group.
+// Tiling.  A workgroup of 8 wavefronts (two per SIMD) owns 192 tokens x 256 weight rows, a
+// wavefront 96 tokens x 64 rows = 3 x 2 MFMA tiles; the 96 binary32 accumulators are
+// updated by vector instructions, so they sit in architectural registers (4 x 2 tiles would
+// need 128 and no longer fit beside the operands without spilling).  One step = one
+// quantization group: both operand slabs of a step (192 and 256 rows x 128 bytes) are fetched
+// straight into LDS by global_load_lds_dwordx4 -- no staging registers, nothing for the
+// register allocator to juggle -- double buffered, one wait and one barrier per step.
+// int8 doubles the MFMA rate and halves the bytes per operand element against the fp16
+// kernel, so the tile has to be this large to keep the L2 traffic per MFMA down.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -37,6 +42,7 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ activation quantizer
@@ -107,27 +113,14 @@ __global__ __launch_bounds__(QA_THREADS) void quantize_act_kernel(const half8 *_
 
 // ------------------------------------------------------------------ int8 GEMM
 
-constexpr int THREADS = 256;
-constexpr int BM = 128, BN = 256;
+constexpr int THREADS = 512;
+constexpr int WAVES = THREADS / 64;
+constexpr int MT = 3;            // MFMA tiles along the tokens, per wavefront (96 tokens)
+constexpr int BM = 2 * MT * 32, BN = 256;
 constexpr int BKB = 128;         // k (= bytes of a row) per step: one quantization group
-constexpr int MT = BM / 32;      // MFMA tiles along the tokens, per wavefront (4)
-constexpr int WN = BN / 4;       // weight rows per wavefront (2 MFMA tiles)
-constexpr int LDB = BKB + 16;    // bytes per LDS row of x: 144, keeps the 128-bit reads conflict-free
-constexpr int XLD = BM * (BKB / 16) / THREADS; // 16-byte pieces of the x slab per thread (4)
-
-__device__ __forceinline__ uint4 load16(const void *p)
-{
-    const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-// One step of weights for one lane: per n-tile, four 16-byte loads (k = 32 i + 16 c ..),
-// the group's scale and 128 - z.
-struct WRegs {
-    uint4 w[2][4];
-    float s[2];
-    int nzc[2];
-};
+constexpr int WN = 64;           // weight rows per wavefront (2 MFMA tiles)
+constexpr int XSLAB = BM * BKB;  // bytes of the x slab of a step (BM rows x 128 bytes)
+constexpr int WSLAB = BN * BKB;  // bytes of the weight slab
 
 struct W8A8Args {
     const uint8_t *codes;
@@ -140,54 +133,92 @@ struct W8A8Args {
     int M, N, K;
 };
 
-__device__ __forceinline__ void load_w(const W8A8Args &d, int n_wave0, int g, WRegs &R)
+// Slab layout in LDS: row r (128 bytes) holds its eight 16-byte pieces at slot
+// p ^ ((r >> 1) & 7).  A 128-bit operand read of 16 consecutive rows at one piece then
+// touches every bank once, and no padding is needed (the direct-to-LDS loads write 64
+// consecutive 16-byte chunks per instruction, lane l at chunk l: the permutation is applied
+// on the global side, where each lane is free to fetch any piece).
+__device__ __forceinline__ int slab_offset(int r, int p)
 {
-    const int lane = threadIdx.x & 63, n = lane & 31, c = lane >> 5;
-    const uint32_t K = (uint32_t)d.K, G = K >> 7;
+    return r * BKB + ((p ^ ((r >> 1) & 7)) << 4);
+}
+
+// Which 16-byte chunks a thread fetches of an operand slab (256 rows x 128 bytes of a
+// [rows][K] byte matrix): load i of wavefront w covers chunks (i * 8 + w) * 64 .. + 63, i.e.
+// rows (i * 8 + w) * 8 .. + 7; the lane takes slot (lane & 7) of row r0 + 64 i, which holds
+// piece p = slot ^ ((r >> 1) & 7) -- the same p for every i.
+struct DmaLane {
+    int r0;  // row of load 0
+    int p16; // byte offset of the piece inside the row
+};
+
+__device__ __forceinline__ DmaLane dma_lane()
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    DmaLane L;
+    L.r0 = wave * 8 + (lane >> 3);
+    L.p16 = ((lane & 7) ^ ((L.r0 >> 1) & 7)) << 4;
+    return L;
+}
+
+// Fetch one step of one operand straight into LDS: `tile` points at (first row of the tile,
+// first k of the step) and is the same for the whole workgroup; rows past `last_row` (relative
+// to the tile) are clamped to it.  Every thread issues ROWS / 64 loads of 16 bytes.
+template <int ROWS>
+__device__ __forceinline__ void dma_slab(const uint8_t *tile, const DmaLane &L, int last_row, int K,
+                                         uint8_t *slab)
+{
+    const int wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-        const size_t row = (size_t)min(n_wave0 + j * 32 + n, d.N - 1);
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-            R.w[j][i] = load16(d.codes + row * K + g * BKB + 32 * i + 16 * c);
-        R.s[j] = ((const FQ_GLOBAL float *)d.scales)[row * G + g];
-        R.nzc[j] = 128 - (int)((const FQ_GLOBAL uint8_t *)d.zeros)[row * G + g];
+    for (int i = 0; i < ROWS * 8 / THREADS; i++) {
+        // 32-bit offset from a scalar base: the load then takes the scalar-base form instead of
+        // needing a 64-bit address pair per chunk
+        const uint32_t off = (uint32_t)min(L.r0 + i * (WAVES * 8), last_row) * (uint32_t)K + L.p16;
+        __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(tile + off),
+                                         (__attribute__((address_space(3))) void *)(slab + (i * WAVES + wave) * 1024),
+                                         16, 0, 0);
     }
 }
 
-struct XRegs {
-    uint4 x[XLD];
+// Scale and zero point of this lane's two weight rows for one step, and (threads < BM) one
+// token's group sum.
+struct Meta {
+    float s[2];
+    uint32_t z[2];
     int sum;
 };
 
-__device__ __forceinline__ void load_x(const W8A8Args &d, int m0, int g, XRegs &R)
+// Lane offsets (elements) from the tile's first scale / zero / group sum, set up once.
+struct MetaOffsets {
+    uint32_t row[2]; // (row - n0) * G for the lane's two weight rows
+    uint32_t tok;    // token - m0 for the thread's group sum
+};
+
+__device__ __forceinline__ void load_meta(const float *scales_tile, const uint8_t *zeros_tile,
+                                          const int32_t *xsum_tile, const MetaOffsets &O, int g, size_t g_stride,
+                                          Meta &R)
 {
 #pragma unroll
-    for (int i = 0; i < XLD; i++) {
-        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
-        const int m = min(m0 + row, d.M - 1);
-        R.x[i] = load16(d.xq + (size_t)m * d.K + g * BKB + piece * 16);
+    for (int j = 0; j < 2; j++) {
+        R.s[j] = ((const FQ_GLOBAL float *)(scales_tile + g))[O.row[j]];
+        R.z[j] = ((const FQ_GLOBAL uint8_t *)(zeros_tile + g))[O.row[j]];
     }
-    // the first BM threads also fetch one token's group sum each
-    R.sum = ((const FQ_GLOBAL int32_t *)d.xsum)[(size_t)g * d.M + min(m0 + (int)(threadIdx.x & (BM - 1)), d.M - 1)];
+    R.sum = ((const FQ_GLOBAL int32_t *)(xsum_tile + g * g_stride))[O.tok];
 }
 
-__device__ __forceinline__ void store_x(const XRegs &R, uint8_t *xs, int32_t *xsm)
-{
-#pragma unroll
-    for (int i = 0; i < XLD; i++) {
-        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
-        *reinterpret_cast<uint4 *>(xs + row * LDB + piece * 16) = R.x[i];
-    }
-    if (threadIdx.x < BM)
-        xsm[threadIdx.x] = R.sum;
-}
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
 
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void w8a8_kernel(
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void w8a8_kernel(
     const W8A8Args d, int m_tiles, int n_tiles, int per_xcd)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t xs[2][BM * LDB];
-    __shared__ __attribute__((aligned(16))) int32_t xsm[2][BM];
+    // Four separate arrays, selected at compile time: the compiler can then tell that the
+    // operand reads of a step do not touch the slabs its direct-to-LDS loads are filling, and
+    // does not wait for those loads before the first read.
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[XSLAB], xs1[XSLAB], ws0[WSLAB], ws1[WSLAB];
+    __shared__ float xsm[2][BM];
 
     // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous run
     // of logical tiles (the M tiles of one N tile are neighbours and share the weight slab)
@@ -198,9 +229,11 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, c = lane >> 5;
-    const int n_wave0 = n0 + wave * WN;
+    const int wm = (wave & 1) * (MT * 32); // first token of this wavefront inside the tile
+    const int wn = (wave >> 1) * WN;   // first weight row
+    const int n_wave0 = n0 + wn;
 
-    float out[MT][2][16];
+    v16f out[MT][2];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
@@ -209,68 +242,145 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
             for (int v = 0; v < 16; v++)
                 out[mt][j][v] = 0.f;
 
+    // Operand reads: lane (l32, c) reads piece 2 i + c of row l32 of an MFMA tile; the slot of
+    // a piece depends on the row only through (l32 >> 1) & 7, so four byte offsets serve every
+    // tile of both operands (tiles start at multiples of 32 rows).
+    int lofs[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        lofs[i] = slab_offset(l32, 2 * i + c);
+
     const int nsteps = d.K / BKB;
-    XRegs X;
-    WRegs W0, W1;
-    load_x(d, m0, 0, X);
-    load_w(d, n_wave0, 0, W0);
-    store_x(X, xs[0], xsm[0]);
-    load_x(d, m0, min(1, nsteps - 1), X);
-    load_w(d, n_wave0, min(1, nsteps - 1), W1);
+    Meta cur, nxt;
+    const DmaLane dl = dma_lane();
+    const int x_last = d.M - 1 - m0, w_last = d.N - 1 - n0;
+    const uint8_t *x_tile = (const uint8_t *)d.xq + (size_t)m0 * d.K;
+    const uint8_t *w_tile = d.codes + (size_t)n0 * d.K;
+    const uint32_t G = (uint32_t)d.K >> 7;
+    MetaOffsets mo;
+    mo.row[0] = (uint32_t)min(wn + l32, d.N - 1 - n0) * G;
+    mo.row[1] = (uint32_t)min(wn + 32 + l32, d.N - 1 - n0) * G;
+    mo.tok = (uint32_t)min((int)min(threadIdx.x, (unsigned)BM - 1), d.M - 1 - m0);
+    const float *scales_tile = d.scales + (size_t)n0 * G;
+    const uint8_t *zeros_tile = d.zeros + (size_t)n0 * G;
+    const int32_t *xsum_tile = d.xsum + m0;
+    dma_slab<BM>(x_tile, dl, x_last, d.K, xs0);
+    dma_slab<BN>(w_tile, dl, w_last, d.K, ws0);
+    load_meta(scales_tile, zeros_tile, xsum_tile, mo, 0, (size_t)d.M, cur);
+    if (threadIdx.x < BM)
+        xsm[0][threadIdx.x] = (float)cur.sum; // |sum| <= 128 * 127: exact
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    // One step (one group): MFMAs of step s from xs[s & 1] and Wcur; meanwhile x of step s+1
-    // goes from registers to the other LDS buffer and the loads of step s+2 are issued.
-    auto step = [&](int s, WRegs &Wcur) {
-        const uint8_t *xc = xs[s & 1];
-        const int32_t *sc = xsm[s & 1];
-        store_x(X, xs[(s + 1) & 1], xsm[(s + 1) & 1]); // last read in step s-1: a barrier has passed
-        load_x(d, m0, min(s + 2, nsteps - 1), X);
+    // Zero-point term of a pair of steps (groups g, g + 1), one v_mfma_f32_32x32x2_f32 per
+    // tile: A = the tokens' group sums (lane: token l32, k = c), B = s * (128 - z) of the
+    // lane's weight row (k = c), accumulated straight into `out`.  Lanes with c = 0 use the
+    // first step's values: its group sums are still in the other LDS buffer, its s * (128 - z)
+    // is carried in bz_first.
+    float bz_first[2] = {0.f, 0.f};
+
+    // One step (one group): the slabs of step s+1 are requested first and land in the other
+    // buffer while the MFMAs of step s run; one wait and one barrier per step.
+    // PHASE 0: first step of a pair; PHASE 1: second step (adds the pair's zero-point term);
+    // PHASE 2: a last unpaired step (adds its own).
+    auto step = [&](int s, auto phase) {
+        constexpr int PHASE = decltype(phase)::value;
+        constexpr bool ODD = PHASE == 1; // steps alternate between the two buffer sets (s & 1)
+        const int sn = min(s + 1, nsteps - 1); // always issued: the last step refetches itself
+        dma_slab<BM>(x_tile + sn * BKB, dl, x_last, d.K, ODD ? xs0 : xs1); // last read in step s-1: a barrier has passed
+        dma_slab<BN>(w_tile + sn * BKB, dl, w_last, d.K, ODD ? ws0 : ws1);
+        load_meta(scales_tile, zeros_tile, xsum_tile, mo, sn, (size_t)d.M, nxt);
+        const uint8_t *xc = (ODD ? xs1 : xs0) + wm * BKB, *wc = (ODD ? ws1 : ws0) + wn * BKB;
+
         v4i b[2][4];
 #pragma unroll
         for (int j = 0; j < 2; j++)
 #pragma unroll
             for (int i = 0; i < 4; i++) { // stored code q -> signed byte q - 128
-                b[j][i].x = (int)(Wcur.w[j][i].x ^ 0x80808080u);
-                b[j][i].y = (int)(Wcur.w[j][i].y ^ 0x80808080u);
-                b[j][i].z = (int)(Wcur.w[j][i].z ^ 0x80808080u);
-                b[j][i].w = (int)(Wcur.w[j][i].w ^ 0x80808080u);
+                const v4i raw = *reinterpret_cast<const v4i *>(wc + j * 32 * BKB + lofs[i]);
+                b[j][i] = raw ^ (int)0x80808080;
             }
+        float az[MT], bz[2];
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-            v4i a[4];
+        for (int j = 0; j < 2; j++)
+            bz[j] = cur.s[j] * (float)(128 - (int)cur.z[j]);
+        if (PHASE == 0) {
+            bz_first[0] = bz[0];
+            bz_first[1] = bz[1];
+        } else {
+            // k = 1 lanes: this step; k = 0 lanes: the first step of the pair (PHASE 1) or this
+            // step with nothing on k = 1 (PHASE 2)
+            const float *sc = xsm[PHASE == 1 ? ((s & 1) ^ (c ^ 1)) : (s & 1)] + wm;
 #pragma unroll
-            for (int i = 0; i < 4; i++)
-                a[i] = *reinterpret_cast<const v4i *>(xc + (mt * 32 + l32) * LDB + 32 * i + 16 * c);
-            // group sums of the 16 tokens this lane holds results for (D layout below)
-            v4i xsv[4];
-#pragma unroll
-            for (int q = 0; q < 4; q++)
-                xsv[q] = *reinterpret_cast<const v4i *>(sc + mt * 32 + 8 * q + 4 * c);
-#pragma unroll
-            for (int j = 0; j < 2; j++) {
-                v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j][i], acc, 0, 0, 0);
-#pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    // sum x (q - z) = sum x (q - 128) + (128 - z) sum x, all in 24 bits
-                    const int t = acc[v] + __mul24(Wcur.nzc[j], xsv[v >> 2][v & 3]);
-                    out[mt][j][v] += Wcur.s[j] * (float)t;
-                }
+            for (int mt = 0; mt < MT; mt++) {
+                az[mt] = sc[mt * 32 + l32];
+                if (PHASE == 2)
+                    az[mt] = c ? 0.f : az[mt];
+            }
+            if (PHASE == 1) {
+                bz[0] = c ? bz[0] : bz_first[0];
+                bz[1] = c ? bz[1] : bz_first[1];
             }
         }
-        load_w(d, n_wave0, min(s + 2, nsteps - 1), Wcur); // always issued: keeps the waits counted
-        __syncthreads(); // xs[(s+1)&1] complete, xs[s&1] no longer read
+
+        // Tiles t = 2 mt + j.  A wavefront issues in order, and each MFMA of a tile's chain
+        // depends on the one before: a chain followed by its fold would leave the vector pipe
+        // idle during the chain and the matrix pipe idle during the fold.  So the chain of tile
+        // t+1 is interleaved with the fold of tile t, one MFMA (32 cycles in the matrix pipe) per
+        // eight vector instructions (32 cycles of issue).
+        v4i a[4];
+        v16i acc[2];
+        auto read_a = [&](int mt) {
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                a[i] = *reinterpret_cast<const v4i *>(xc + mt * 32 * BKB + lofs[i]);
+        };
+        auto chain = [&](int j) {
+            v16i r = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                r = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j][i], r, 0, 0, 0);
+            return r;
+        };
+        read_a(0);
+        acc[0] = chain(0);
+#pragma unroll
+        for (int t = 0; t < 2 * MT; t++) {
+            const int mt = t >> 1, j = t & 1;
+            if (t + 1 < 2 * MT)
+                acc[(t + 1) & 1] = chain((t + 1) & 1);
+#pragma unroll
+            for (int v = 0; v < 16; v++)
+                out[mt][j][v] += cur.s[j] * (float)acc[t & 1][v];
+            if (t + 1 < 2 * MT) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0); // eight vector instructions
+                }
+            }
+            if (j == 0 && mt + 1 < MT)
+                read_a(mt + 1); // both chains of mt are issued: fetch the next tokens' operands
+            if (PHASE != 0)
+                out[mt][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az[mt], bz[j], out[mt][j], 0, 0, 0);
+            // Pin the order across tiles: tile t is folded before the chain of tile t+2 (which
+            // reads a[0]) is issued.  Left alone the compiler issues all eight chains first and
+            // needs 96 more registers for their results.
+            asm volatile("" : "+v"(out[mt][j]), "+v"(a[0]));
+        }
+        if (threadIdx.x < BM)
+            xsm[(s + 1) & 1][threadIdx.x] = (float)nxt.sum;
+        cur = nxt;
+        __builtin_amdgcn_s_waitcnt(0); // this wavefront's direct-to-LDS loads have landed
+        __syncthreads();               // everyone's have; buffers of step s are free
     };
     int s = 0;
     for (; s + 1 < nsteps; s += 2) {
-        step(s, W0);
-        step(s + 1, W1);
+        step(s, IntC<0>());
+        step(s + 1, IntC<1>());
     }
     if (s < nsteps)
-        step(s, W0);
+        step(s, IntC<2>());
 
     // D layout of the 32x32 MFMA: lane holds column l32 (weight row), rows (tokens)
     // 8 * (v / 4) + 4 * (lane / 32) + v % 4.
@@ -278,7 +388,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
     for (int mt = 0; mt < MT; mt++) {
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-            const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
+            const int m = m0 + wm + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
             if (m < d.M) {
                 const float sxm = d.sx[m];
 #pragma unroll
