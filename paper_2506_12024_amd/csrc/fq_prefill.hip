@@ -3,23 +3,28 @@
 // and the contraction is compute bound (Sec. 4.1) -- a dense GEMM on the matrix cores with
 // the dequantization of Sec. 2.2 Eq. (3) fused into the operand path.
 //
-// Tiling.  A workgroup (4 wavefronts) owns a 128 (tokens) x 256 (weight rows) tile of y and
-// walks K in steps of 64.  The wavefronts split the weight rows: each owns 64 rows x all
-// 128 tokens = 4 x 2 tiles of v_mfma_f32_32x32x16_f16 (A = x: 32 tokens x 16 k, B =
-// weights: 16 k x 32 rows; 128 binary32 accumulator registers).
-//   - x goes through LDS: the 128 x 64 slab of a step is written once (double buffered,
-//     one barrier per step) and every wavefront reads its A operands from it as 128-bit
-//     vectors, 4 reads per 8 MFMAs.
-//   - the weights never touch LDS: lane (n = lane % 32, c = lane / 32) loads 16 bytes of row
-//     n straight from global memory in the MFMA's own operand layout, two steps ahead, and
-//     dequantizes them in registers.  No other wavefront needs the same rows, so nothing
-//     is unpacked twice.
+// Tiling.  A workgroup (8 wavefronts, two per SIMD) owns a 256 (tokens) x 256 (weight rows)
+// tile of y and walks K in steps of 64.  A wavefront owns 128 tokens x 64 rows = 4 x 2 tiles
+// of v_mfma_f32_32x32x16_f16 (A = x: 32 tokens x 16 k, B = weights: 16 k x 32 rows; 128
+// binary32 accumulator registers).  The large shared tile keeps the bytes fetched per MFMA
+// low enough that one step of compute covers the latency of the next stage's fetch.
 //
-// Dequantization.  Codes become the exact integers q - z as halves (same bit tricks as the
-// decode kernels) and are multiplied by the group's scale rounded to half (one
+// Operand path.  Both slabs of a step -- x: 128 rows x 128 bytes, packed weights: 256 rows x
+// 32 / 64 / 128 bytes for 4-bit / 8-bit / fp16 -- go from global memory straight into LDS
+// (global_load_lds_dwordx4: no staging registers, a wavefront fetches whole rows), three
+// stages deep (two for fp16 weights), one wait and one barrier per step.  Rows are stored 128 bytes apart (two 64-byte
+// or four 32-byte weight rows share such a line) with the 16-byte slots of a line XOR-ed by
+// (line >> 1) & 7, so that a 128-bit operand read of 16 consecutive rows touches every bank
+// once; the permutation is applied on the global side of the load, where each lane is free to
+// fetch any piece.  The packed weights are unpacked after the LDS read, in registers: the
+// LDS traffic of the weight operand is that of the packed codes.
+//
+// Dequantization.  Codes become the exact integers q - z as halves (bit tricks: a byte under
+// exponent 0x64 is 1024 + q, a nibble in bits 4..7 under 0x54 is 64 + q; one v_pk_add_f16
+// removes the offset and z) and are multiplied by the group's scale rounded to half (one
 // v_pk_mul_f16 per register): the MFMA operand is half((q - z) * half(s)).  The decode
 // kernels keep the scale in binary32 outside the group sum; here that would need a second
-// set of 128 accumulator registers per wavefront and a 384-instruction fold per group, so
+// set of 128 accumulator registers per wavefront and a 256-instruction fold per group, so
 // the prefill path rounds twice at 2^-11 relative instead.  The error stays well inside the
 // 2e-3 bound (about 5e-4 of the output magnitude in the worst one-group case).
 //
@@ -28,28 +33,78 @@
 // fetched into one L2 and reused there.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "fq_internal.h"
 
 namespace {
 
 #define FQ_GLOBAL __attribute__((address_space(1)))
+#define FQ_LDS __attribute__((address_space(3)))
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int THREADS = 256;
-constexpr int BM = 128, BN = 256, BK = 64;
-constexpr int WN = BN / 4;  // weight rows per wavefront (2 MFMA tiles)
-constexpr int LDK = BK + 8; // halves per LDS row: 144 bytes, keeps 128-bit reads conflict-free
-constexpr int XLD = BM * (BK / 8) / THREADS; // 16-byte pieces of the x slab per thread (4)
+constexpr int THREADS = 512;
+constexpr int WAVES = THREADS / 64;
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int WM = 128;            // tokens per wavefront (4 MFMA tiles)
+constexpr int WN = 64;             // weight rows per wavefront (2 MFMA tiles)
+constexpr int XRB = BK * 2;        // bytes of an x row per step (128)
+constexpr int XSLAB = BM * XRB;    // 32 KiB
 
-__device__ __forceinline__ uint4 load16(const void *p)
+// Byte offset of 16-byte chunk `ch` of row `r` in a slab whose rows are RB bytes long:
+// 128 / RB rows share a 128-byte line, slots XOR-ed by (line >> 1) & 7.
+template <int RB>
+__device__ __forceinline__ int slab_offset(int r, int ch)
 {
-    const u32x4 v = *(const FQ_GLOBAL u32x4 *)p;
-    return make_uint4(v.x, v.y, v.z, v.w);
+    constexpr int RPL = 128 / RB, CPR = RB / 16;
+    const int line = r / RPL;
+    return line * 128 + ((((r % RPL) * CPR + ch) ^ ((line >> 1) & 7)) << 4);
+}
+
+// Which chunks a thread fetches of a slab (ROWS rows of RB bytes).  Load i of wavefront w
+// fills LDS chunks (i * WAVES + w) * 64 .. + 63, i.e. lines (i * WAVES + w) * 8 .. + 7; the
+// lane owns slot (lane & 7) of line l0 + 8 * WAVES * i, and the piece stored there is the
+// same for every i (8 * WAVES is a multiple of 16).
+struct DmaLane {
+    int r0;      // row of load 0
+    int rstep;   // rows between consecutive loads
+    int byte0;   // byte offset of the piece inside the row
+};
+
+template <int RB>
+__device__ __forceinline__ DmaLane dma_lane()
+{
+    constexpr int RPL = 128 / RB, CPR = RB / 16;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int line = wave * 8 + (lane >> 3);
+    const int slot = (lane & 7) ^ ((line >> 1) & 7);
+    DmaLane L;
+    L.r0 = line * RPL + slot / CPR;
+    L.rstep = 8 * WAVES * RPL;
+    L.byte0 = (slot % CPR) * 16;
+    return L;
+}
+
+// Fetch one step of one operand straight into LDS.  `tile` points at (first row of the
+// tile, first byte of the step) and is the same for the whole workgroup; rows past
+// `last_row` (relative to the tile) are clamped to it; `pitch` = bytes between rows in
+// global memory.
+template <int ROWS, int RB>
+__device__ __forceinline__ void dma_slab(const uint8_t *tile, const DmaLane &L, int last_row, uint32_t pitch,
+                                         uint8_t *slab)
+{
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < ROWS * RB / 16 / THREADS; i++) {
+        const uint32_t off = (uint32_t)min(L.r0 + i * L.rstep, last_row) * pitch + L.byte0;
+        __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(tile + off),
+                                         (FQ_LDS void *)(slab + (i * WAVES + wave) * 1024), 16, 0, 0);
+    }
 }
 
 // (a + b) * s, each operation rounded to half; a + b is the exact integer q - z
@@ -58,138 +113,43 @@ __device__ __forceinline__ uint32_t deq(uint32_t a, uint32_t b, half2_t s)
     return __builtin_bit_cast(uint32_t, (__builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b)) * s);
 }
 
-__device__ __forceinline__ float16_t mfma32(uint4 a, const uint32_t (&b)[4], float16_t c)
+__device__ __forceinline__ float16_t mfma32(const u32x4 a, const uint32_t (&b)[4], float16_t c)
 {
-    const u32x4 av = {a.x, a.y, a.z, a.w};
     const u32x4 bv = {b[0], b[1], b[2], b[3]};
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av),
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
                                                   __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
 }
 
-// Packed weights of one K step for one lane: per n-tile, 16-byte loads covering 64 k.
-//   4-bit: 1 load (32 codes: k = 32 c ..), 8-bit: 2 loads (16 codes each: k = 32 h + 16 c ..),
-//   fp16: 4 loads (8 halves each: k = 16 i + 8 c ..)
+// Which 8 k of the 64-k step lane (row, c) supplies in k16-step i, as the index of the
+// 16-byte chunk of 8 halves in an x row:
+//   4-bit: a lane reads one 16-byte chunk of codes (32 codes, k = 32 c ..), word i of it holds
+//          k = 32 c + 8 i ..;   8-bit and fp16: k = 16 i + 8 c ..
 template <int BITS>
-struct WRegs {
-    static constexpr int NL = BITS == 4 ? 1 : (BITS == 8 ? 2 : 4);
-    uint4 w[2][NL];
+__device__ __forceinline__ int x_chunk(int i, int c)
+{
+    return BITS == 4 ? 4 * c + i : 2 * i + c;
+}
+
+// Scale and zero point of a lane's two weight rows for one quantization group.
+struct Meta {
     float s[2];
     uint32_t z[2];
 };
 
 template <int BITS>
-__device__ __forceinline__ void load_w(const FqLinearDesc &d, const uint8_t *codes, const float *scales,
-                                       const uint8_t *zeros, int n_wave0, int k0, WRegs<BITS> &R)
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
+    const FqLinearDesc d, int M, int m_tiles, int n_tiles, int per_xcd)
 {
-    const int lane = threadIdx.x & 63, n = lane & 31, c = lane >> 5;
-    const uint32_t K = (uint32_t)d.K;
-#pragma unroll
-    for (int j = 0; j < 2; j++) {
-        const size_t row = (size_t)min(n_wave0 + j * 32 + n, d.N - 1);
-        if (BITS == 4) {
-            R.w[j][0] = load16(codes + row * (K >> 1) + ((k0 + 32 * c) >> 1));
-        } else if (BITS == 8) {
-#pragma unroll
-            for (int h = 0; h < 2; h++)
-                R.w[j][h] = load16(codes + row * K + k0 + 32 * h + 16 * c);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-                R.w[j][i] = load16(codes + (row * K + k0 + 16 * i + 8 * c) * 2);
-        }
-        if (BITS != 16) {
-            R.s[j] = ((const FQ_GLOBAL float *)scales)[row * (K >> 7) + (k0 >> 7)];
-            R.z[j] = ((const FQ_GLOBAL uint8_t *)zeros)[row * (K >> 7) + (k0 >> 7)];
-        }
-    }
-}
-
-// The B operand (8 halves) of k16-step i for n-tile j.  Which 8 k a lane supplies:
-//   4-bit: k0 + 32 c + 8 i + (0 4 1 5 2 6 3 7)   8-bit: k0 + 32 (i/2) + 16 c + 8 (i%2) + 0..7
-//   fp16:  k0 + 16 i + 8 c + 0..7
-template <int BITS>
-__device__ __forceinline__ void b_operand(const WRegs<BITS> &R, int j, int i, uint32_t (&b)[4])
-{
-    if (BITS == 4) {
-        const uint32_t z = R.z[j];
-        const uint32_t nz_lo = (z | (z << 16)) | 0xE400E400u;        // -(1024 + z) twice
-        const uint32_t nz_hi = ((z << 4) | (z << 20)) | 0xD400D400u; // -(  64 + z) twice
-        const half2_t sh = {(_Float16)R.s[j], (_Float16)R.s[j]};
-        const uint32_t ww[4] = {R.w[j][0].x, R.w[j][0].y, R.w[j][0].z, R.w[j][0].w};
-        const uint32_t v = ww[i], v8 = v >> 8;
-        b[0] = deq((v & 0x000F000Fu) | 0x64006400u, nz_lo, sh);  // (q0 - z, q4 - z) * s
-        b[1] = deq((v & 0x00F000F0u) | 0x54005400u, nz_hi, sh);  // (q1 - z, q5 - z) * s
-        b[2] = deq((v8 & 0x000F000Fu) | 0x64006400u, nz_lo, sh); // (q2 - z, q6 - z) * s
-        b[3] = deq((v8 & 0x00F000F0u) | 0x54005400u, nz_hi, sh); // (q3 - z, q7 - z) * s
-    } else if (BITS == 8) {
-        const uint32_t z = R.z[j];
-        const uint32_t nz = (z | (z << 16)) | 0xE400E400u;
-        const half2_t sh = {(_Float16)R.s[j], (_Float16)R.s[j]};
-        const uint4 q = R.w[j][i >> 1];
-        const uint32_t lo = (i & 1) ? q.z : q.x, hi = (i & 1) ? q.w : q.y;
-        b[0] = deq(__builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u), nz, sh);
-        b[1] = deq(__builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u), nz, sh);
-        b[2] = deq(__builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u), nz, sh);
-        b[3] = deq(__builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u), nz, sh);
-    } else {
-        b[0] = R.w[j][i].x;
-        b[1] = R.w[j][i].y;
-        b[2] = R.w[j][i].z;
-        b[3] = R.w[j][i].w;
-    }
-}
-
-// 16-byte block of x (8 halves, block index inside the 64-k step) that pairs with b_operand.
-template <int BITS>
-__device__ __forceinline__ int a_block(int i, int c)
-{
-    if (BITS == 4)
-        return 4 * c + i;
-    if (BITS == 8)
-        return 4 * (i >> 1) + 2 * c + (i & 1);
-    return 2 * i + c;
-}
-
-struct XRegs {
-    uint4 x[XLD];
-};
-
-__device__ __forceinline__ void load_x(const FqLinearDesc &d, int M, int m0, int k0, XRegs &R)
-{
-#pragma unroll
-    for (int i = 0; i < XLD; i++) {
-        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
-        const int m = min(m0 + row, M - 1);
-        R.x[i] = load16(d.x + (size_t)m * d.K + k0 + piece * 8);
-    }
-}
-
-// 4-bit: the unpacking yields each block of 8 codes in the order (0 4 1 5 2 6 3 7); x is
-// written in the same order so that the MFMA sums matching pairs.
-template <int BITS>
-__device__ __forceinline__ void store_x(const XRegs &R, uint16_t *xs)
-{
-#pragma unroll
-    for (int i = 0; i < XLD; i++) {
-        const int idx = i * THREADS + threadIdx.x, row = idx >> 3, piece = idx & 7;
-        uint4 v = R.x[i];
-        if (BITS == 4) {
-            uint4 p;
-            p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u); // (x0, x4)
-            p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u); // (x1, x5)
-            p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u); // (x2, x6)
-            p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u); // (x3, x7)
-            v = p;
-        }
-        *reinterpret_cast<uint4 *>(xs + row * LDK + piece * 8) = v;
-    }
-}
-
-template <int BITS>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(const FqLinearDesc d, int M, int m_tiles,
-                                                          int n_tiles, int per_xcd)
-{
-    __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM * LDK];
+    constexpr int WRB = BK * BITS / 8;  // bytes of a packed weight row per step
+    constexpr int WSLAB = BN * WRB;
+    // Separate arrays, selected at compile time: the compiler can then tell that the operand
+    // reads of a step do not touch the slabs its direct-to-LDS loads are filling, and does not
+    // wait for those loads before the first read.
+    constexpr int NST = BITS == 16 ? 2 : 3; // stages in flight (fp16 weights: 64 KiB per stage)
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[XSLAB], xs1[XSLAB], xs2[NST == 3 ? XSLAB : 1024];
+    __shared__ __attribute__((aligned(1024))) uint8_t ws0[WSLAB], ws1[WSLAB], ws2[NST == 3 ? WSLAB : 1024];
+    __shared__ __attribute__((aligned(1024))) float smeta[BN];
+    __shared__ __attribute__((aligned(1024))) uint32_t zmeta[BN];
 
     // hardware deals consecutive workgroup ids round-robin to the 8 XCDs: give each XCD a
     // contiguous run of logical tiles
@@ -204,7 +164,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, c = lane >> 5;
-    const int n_wave0 = n0 + wave * WN;
+    const int wm = (wave & 1) * WM, wn = (wave >> 1) * WN;
 
     float16_t acc[4][2];
 #pragma unroll
@@ -215,56 +175,222 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
             for (int v = 0; v < 16; v++)
                 acc[i][j][v] = 0.f;
 
-    const int nsteps = d.K / BK;
-    XRegs X;
-    WRegs<BITS> W0, W1;
-    load_x(d, M, m0, 0, X);
-    load_w<BITS>(d, codes, scales, zeros, n_wave0, 0, W0);
-    store_x<BITS>(X, xs[0]);
-    load_x(d, M, m0, min(1, nsteps - 1) * BK, X);
-    load_w<BITS>(d, codes, scales, zeros, n_wave0, min(1, nsteps - 1) * BK, W1);
-    __syncthreads();
+    // Per-lane LDS offsets of the operand reads (tiles start at multiples of 32 rows, which
+    // leaves the slot permutation of a lane unchanged from tile to tile).
+    int aofs[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        aofs[i] = slab_offset<XRB>(l32, x_chunk<BITS>(i, c));
+    // Weights: 8-bit and fp16 rows are 64 / 128 bytes, the second n-tile (32 rows on) sits a
+    // whole number of 16-line blocks further and keeps the permutation: one offset per
+    // k16-step.  4-bit rows are 32 bytes (one read per n-tile and step): 32 rows are 8 lines,
+    // which changes the permutation, so each n-tile has its own offset.
+    constexpr int WRB_ = BK * BITS / 8;
+    int bofs[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        bofs[i] = BITS == 4 ? slab_offset<WRB_>(wn + (i & 1) * 32 + l32, c)
+                : BITS == 8 ? slab_offset<WRB_>(wn + l32, i) + 8 * c
+                            : slab_offset<WRB_>(wn + l32, 2 * i + c);
+    constexpr int BJ = 32 * WRB_; // bytes from n-tile 0 to n-tile 1 (8-bit, fp16)
 
-    // One step: MFMAs of step s from xs[s & 1] and Wcur; meanwhile x of step s+1 goes from
-    // registers to the other LDS buffer, and the loads of step s+2 (x and weights) are issued.
-    auto step = [&](int s, WRegs<BITS> &Wcur) {
-        const uint16_t *xc = xs[s & 1];
-        store_x<BITS>(X, xs[(s + 1) & 1]); // last read in step s-1: a barrier has passed since
-        load_x(d, M, m0, min(s + 2, nsteps - 1) * BK, X);
+    const uint32_t K = (uint32_t)d.K, G = K >> 7;
+    const int nsteps = d.K / BK;
+    const DmaLane xl = dma_lane<XRB>(), wl = dma_lane<WRB>();
+    const int x_last = M - 1 - m0, w_last = d.N - 1 - n0;
+    const uint32_t w_pitch = K * BITS / 8;
+    const uint8_t *x_tile = (const uint8_t *)d.x + (size_t)m0 * K * 2;
+    const uint8_t *w_tile = codes + (size_t)n0 * w_pitch;
+    const float *scales_tile = BITS == 16 ? nullptr : scales + (size_t)n0 * G;
+    const uint8_t *zeros_tile = BITS == 16 ? nullptr : zeros + (size_t)n0 * G;
+    // Scales and zero points of one quantization group for the tile's 256 weight rows also
+    // come in through direct-to-LDS loads (a dword resp. a byte per lane; either lands in the
+    // lane's dword slot, the byte zero-extended): wavefronts 0-3 fetch 64 scales each,
+    // wavefronts 4-7 64 zero points each, so every wavefront issues the same number of loads
+    // per step -- the waits below count them.  An ordinary load would do, but the compiler
+    // assumes it may overtake pending direct-to-LDS loads and waits for all of them before its
+    // first use, which would drain the fetch pipeline every other step.
+    auto fetch_meta = [&](int g) {
+        if (BITS != 16) {
+            const uint32_t row = (uint32_t)min((wave & 3) * 64 + lane, w_last) * G;
+            if (wave < 4)
+                __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(scales_tile + g + row),
+                                                 (FQ_LDS void *)(smeta + (wave & 3) * 64), 4, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(zeros_tile + g + row),
+                                                 (FQ_LDS void *)(zmeta + (wave & 3) * 64), 1, 0, 0);
+        }
+    };
+
+    Meta cur;
+    // VMEM operations a thread issues per step: these may still be in flight at the end of the
+    // step when a later stage is being filled (three stages)
+    constexpr int DMA_OPS = (BM * XRB + BN * WRB) / 16 / THREADS;
+    // s_waitcnt vmcnt(n) lgkmcnt(0) (expcnt untouched)
+    auto wait_vm = [](auto n) {
+        constexpr int N = decltype(n)::value;
+        __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | ((N >> 4) << 14));
+    };
+    // Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for
+    // every outstanding load, including the stage that is meant to stay in flight.  The waits
+    // that matter are issued explicitly before it; the empty asm statements keep the compiler
+    // from moving LDS accesses across.
+    auto barrier = [] {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    auto stage_x = [&](auto st) -> uint8_t * {
+        constexpr int ST = decltype(st)::value;
+        return ST == 0 ? xs0 : ST == 1 ? xs1 : xs2;
+    };
+    auto stage_w = [&](auto st) -> uint8_t * {
+        constexpr int ST = decltype(st)::value;
+        return ST == 0 ? ws0 : ST == 1 ? ws1 : ws2;
+    };
+    auto fetch = [&](int sf, auto st) { // step sf (clamped: always issued) into stage st
+        const int sn = min(sf, nsteps - 1);
+        dma_slab<BM, XRB>(x_tile + sn * XRB, xl, x_last, K * 2, stage_x(st));
+        dma_slab<BN, WRB>(w_tile + sn * WRB, wl, w_last, w_pitch, stage_w(st));
+    };
+    fetch(0, std::integral_constant<int, 0>());
+    if (NST == 3)
+        fetch(1, std::integral_constant<int, 1>());
+    fetch_meta(0);
+    __builtin_amdgcn_s_waitcnt(0);
+    barrier();
+
+    // One step: the slabs of step s + NST - 1 are requested first and land in the stage that
+    // was read during step s - 1, while the MFMAs of step s run on stage ST = s % NST.  A
+    // quantization group is two steps; its scales and zero points are fetched during the
+    // previous group's second (ODD) step and read into registers in its own first step.
+    auto step = [&](int s, auto st, auto odd) {
+        constexpr int ST = decltype(st)::value;
+        constexpr bool ODD = decltype(odd)::value;
+        if (!ODD && BITS != 16) {
+            // first step of a group: its scales and zero points landed during the previous step
+            // (nothing is writing smeta / zmeta now: the next request goes out a step later)
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                cur.s[j] = smeta[wn + j * 32 + l32];
+                cur.z[j] = zmeta[wn + j * 32 + l32];
+            }
+        }
+        if (ODD)
+            fetch_meta(min((s >> 1) + 1, (int)G - 1)); // the oldest request of this step
+        fetch(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>());
+        // keep the requests here, ahead of the step's MFMAs: left to itself the scheduler sinks
+        // them to the end of the step, right in front of the wait
+        __builtin_amdgcn_sched_barrier(0);
+        const uint8_t *xc = stage_x(st), *wc = stage_w(st);
+        // opaque per step: otherwise the sums of every stage's base and every offset are kept
+        // in registers across the whole loop
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            asm volatile("" : "+v"(aofs[i]), "+v"(bofs[i]));
+
+        // constants of the group for the two n-tiles
+        half2_t sh[2];
+        uint32_t nz[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            if (BITS != 16) {
+                sh[j] = half2_t{(_Float16)cur.s[j], (_Float16)cur.s[j]};
+                const uint32_t z = cur.z[j];
+                nz[j] = BITS == 8 ? ((z | (z << 16)) | 0xE400E400u)             // -(1024 + z) twice
+                                  : ((z | 0xE400u) | (((z << 4) | 0xD400u) << 16)); // -(1024 + z), -(64 + z)
+            }
+        }
+        u32x4 w4[2]; // 4-bit: the lane's 32 codes of the step, per n-tile
+        if (BITS == 4) {
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+                w4[j] = *reinterpret_cast<const u32x4 *>(wc + bofs[j]);
+        }
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            uint4 a[4];
+            u32x4 a[4];
 #pragma unroll
             for (int mt = 0; mt < 4; mt++)
-                a[mt] = *reinterpret_cast<const uint4 *>(xc + (mt * 32 + l32) * LDK + a_block<BITS>(i, c) * 8);
+                a[mt] = *reinterpret_cast<const u32x4 *>(xc + (wm + mt * 32) * XRB + aofs[i]);
 #pragma unroll
             for (int j = 0; j < 2; j++) {
                 uint32_t b[4];
-                b_operand<BITS>(Wcur, j, i, b);
+                if (BITS == 4) {
+                    // word i: nibbles q0 .. q7 of k = 32 c + 8 i ..; byte t holds (q(2t+1) q(2t)).
+                    // The byte is copied under both halves, the low nibble kept in the low half
+                    // (exponent 0x64: 1024 + q) and the high nibble in the high half (0x54: 64 + q)
+                    const uint32_t v = w4[j][i];
+                    b[0] = deq((__builtin_amdgcn_perm(0u, v, 0x0c000c00u) & 0x00F0000Fu) | 0x54006400u, nz[j], sh[j]);
+                    b[1] = deq((__builtin_amdgcn_perm(0u, v, 0x0c010c01u) & 0x00F0000Fu) | 0x54006400u, nz[j], sh[j]);
+                    b[2] = deq((__builtin_amdgcn_perm(0u, v, 0x0c020c02u) & 0x00F0000Fu) | 0x54006400u, nz[j], sh[j]);
+                    b[3] = deq((__builtin_amdgcn_perm(0u, v, 0x0c030c03u) & 0x00F0000Fu) | 0x54006400u, nz[j], sh[j]);
+                } else if (BITS == 8) {
+                    const u32x2 q = *reinterpret_cast<const u32x2 *>(wc + j * BJ + bofs[i]); // k = 16 i + 8 c ..
+                    b[0] = deq(__builtin_amdgcn_perm(0x64646464u, q.x, 0x04010400u), nz[j], sh[j]);
+                    b[1] = deq(__builtin_amdgcn_perm(0x64646464u, q.x, 0x04030402u), nz[j], sh[j]);
+                    b[2] = deq(__builtin_amdgcn_perm(0x64646464u, q.y, 0x04010400u), nz[j], sh[j]);
+                    b[3] = deq(__builtin_amdgcn_perm(0x64646464u, q.y, 0x04030402u), nz[j], sh[j]);
+                } else {
+                    const u32x4 q = *reinterpret_cast<const u32x4 *>(wc + j * BJ + bofs[i]);
+                    b[0] = q.x;
+                    b[1] = q.y;
+                    b[2] = q.z;
+                    b[3] = q.w;
+                }
 #pragma unroll
                 for (int mt = 0; mt < 4; mt++)
                     acc[mt][j] = mfma32(a[mt], b, acc[mt][j]);
             }
         }
-        // Wcur is free: refill it for step s+2 (always issued: keeps the waits counted)
-        load_w<BITS>(d, codes, scales, zeros, n_wave0, min(s + 2, nsteps - 1) * BK, Wcur);
-        __syncthreads(); // xs[(s+1)&1] complete, xs[s&1] no longer read
+        // Stage s + 1 must have landed (it was requested one step earlier when there are three
+        // stages, so this step's own requests -- the last DMA_OPS operations issued -- may stay
+        // in flight), and this wavefront's LDS reads of stage ST must be done before anyone
+        // refills it.
+        if (NST == 3)
+            wait_vm(std::integral_constant<int, DMA_OPS>());
+        else
+            wait_vm(std::integral_constant<int, 0>());
+        barrier();
     };
-    // K is a multiple of 128, so the number of steps is even: two steps per trip, straight
-    // line, each with its own register set for the weights
-    for (int s = 0; s < nsteps; s += 2) {
-        step(s, W0);
-        step(s + 1, W1);
+    // K is a multiple of 128, so the number of steps is even.  Stages and group halves repeat
+    // with period 6 (three stages) or 2 (two stages).
+    int s = 0;
+    if (NST == 3) {
+        for (; s + 6 <= nsteps; s += 6) {
+            step(s, std::integral_constant<int, 0>(), std::false_type());
+            step(s + 1, std::integral_constant<int, 1>(), std::true_type());
+            step(s + 2, std::integral_constant<int, 2>(), std::false_type());
+            step(s + 3, std::integral_constant<int, 0>(), std::true_type());
+            step(s + 4, std::integral_constant<int, 1>(), std::false_type());
+            step(s + 5, std::integral_constant<int, 2>(), std::true_type());
+        }
+        if (s + 2 <= nsteps) {
+            step(s, std::integral_constant<int, 0>(), std::false_type());
+            step(s + 1, std::integral_constant<int, 1>(), std::true_type());
+            s += 2;
+        }
+        if (s + 2 <= nsteps) {
+            step(s, std::integral_constant<int, 2>(), std::false_type());
+            step(s + 1, std::integral_constant<int, 0>(), std::true_type());
+            s += 2;
+        }
+    } else {
+        for (; s < nsteps; s += 2) {
+            step(s, std::integral_constant<int, 0>(), std::false_type());
+            step(s + 1, std::integral_constant<int, 1>(), std::true_type());
+        }
     }
+    __builtin_amdgcn_s_waitcnt(0); // nothing of this kernel's is in flight past this point
     // D layout of the 32x32 MFMA: lane holds column l32, rows 8 * (v / 4) + 4 * (lane / 32) + v % 4.
 #pragma unroll
     for (int mt = 0; mt < 4; mt++)
 #pragma unroll
         for (int j = 0; j < 2; j++) {
-            const int n = n_wave0 + j * 32 + l32;
+            const int n = n0 + wn + j * 32 + l32;
 #pragma unroll
             for (int v = 0; v < 16; v++) {
-                const int m = m0 + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
+                const int m = m0 + wm + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
                 if (m < M && n < d.N)
                     ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + n] =
                         __builtin_bit_cast(uint16_t, (_Float16)acc[mt][j][v]);
