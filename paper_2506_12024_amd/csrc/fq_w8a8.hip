@@ -275,9 +275,12 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // Zero-point term of a pair of steps (groups g, g + 1), one v_mfma_f32_32x32x2_f32 per
     // tile: A = the tokens' group sums (lane: token l32, k = c), B = s * (128 - z) of the
     // lane's weight row (k = c), accumulated straight into `out`.  Lanes with c = 0 use the
-    // first step's values: its group sums are still in the other LDS buffer, its s * (128 - z)
-    // is carried in bz_first.
-    float bz_first[2] = {0.f, 0.f};
+    // first step's values, carried in az_first / bz_first (the first step's LDS copy of the
+    // group sums is being overwritten with the next step's by the time the second step runs).
+    float az_first[MT], bz_first[2] = {0.f, 0.f};
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+        az_first[mt] = 0.f;
 
     // One step (one group): the slabs of step s+1 are requested first and land in the other
     // buffer while the MFMAs of step s run; one wait and one barrier per step.
@@ -304,23 +307,28 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int j = 0; j < 2; j++)
             bz[j] = cur.s[j] * (float)(128 - (int)cur.z[j]);
+        // group sums of this step for the wavefront's tokens: only xsm[s & 1] is read during
+        // step s (the other buffer receives step s + 1's values at the end of the step)
+        const float *sc = xsm[s & 1] + wm;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+            az[mt] = sc[mt * 32 + l32];
         if (PHASE == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                az_first[mt] = az[mt];
             bz_first[0] = bz[0];
             bz_first[1] = bz[1];
-        } else {
-            // k = 1 lanes: this step; k = 0 lanes: the first step of the pair (PHASE 1) or this
-            // step with nothing on k = 1 (PHASE 2)
-            const float *sc = xsm[PHASE == 1 ? ((s & 1) ^ (c ^ 1)) : (s & 1)] + wm;
+        } else if (PHASE == 1) { // k = 1 lanes: this step; k = 0 lanes: the first step of the pair
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-                az[mt] = sc[mt * 32 + l32];
-                if (PHASE == 2)
-                    az[mt] = c ? 0.f : az[mt];
-            }
-            if (PHASE == 1) {
-                bz[0] = c ? bz[0] : bz_first[0];
-                bz[1] = c ? bz[1] : bz_first[1];
-            }
+            for (int mt = 0; mt < MT; mt++)
+                az[mt] = c ? az[mt] : az_first[mt];
+            bz[0] = c ? bz[0] : bz_first[0];
+            bz[1] = c ? bz[1] : bz_first[1];
+        } else { // a last unpaired step: nothing on k = 1
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                az[mt] = c ? 0.f : az[mt];
         }
 
         // Tiles t = 2 mt + j.  A wavefront issues in order, and each MFMA of a tile's chain

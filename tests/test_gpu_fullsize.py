@@ -126,3 +126,41 @@ def test_batched_entropy_kl_full_size_sampled_rows():
     KLn = KL.cpu().numpy().astype(np.float64)[rows]
     assert np.all(np.abs(Hn - H_ref) <= 1e-4 * np.abs(H_ref) + 1e-7)
     assert np.all(np.abs(KLn - KL_ref) <= 1e-4 * np.abs(KL_ref) + 1e-7)
+
+
+@pytest.mark.parametrize("N,K", [(28672, 8192), (8192, 28672)])
+def test_w8a8_slice_sampled_outputs(N, K):
+    """The W8A8 prefill at the benchmark's shapes: activation codes and scales of sampled tokens
+    bit-exact, group sums exact everywhere, sampled outputs against the oracle."""
+    M = 2048
+    name = "full/prefill/%dx%d" % (N, K)
+    w = synth.weight(0, name + "/w", N, K, 0.015)
+    x = synth.activations(0, name + "/x", M, K)
+    w_dev, x_dev = to_dev(w), to_dev(x)
+    cb, sb, zb = fq.fq_packed_sizes(N, K, 8)
+    c = torch.empty(cb, dtype=torch.uint8, device=DEV)
+    s = torch.empty(sb // 4, dtype=torch.float32, device=DEV)
+    z = torch.empty(zb, dtype=torch.uint8, device=DEV)
+    fq.fq_quantize(w_dev, N, K, 8, 128, c, s, z)
+    layer = fq.Layer(N, K).attach(8, c, s, z)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    xsum = torch.empty((K // 128, M), dtype=torch.int32, device=DEV)
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+    fq.fq_quantize_act(x_dev, M, K, xq, sx, xsum)
+    fq.fq_linear_w8a8(layer, xq, sx, xsum, M, y)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    rng = np.random.default_rng(5)
+    ms = [0, M - 1] + list(rng.integers(0, M, size=6))
+    xq_ref, sx_ref = oracle.quantize_act(x[ms])
+    assert np.array_equal(xq[ms].cpu().numpy(), xq_ref)
+    assert np.array_equal(sx[ms].cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    sums = xq.view(M, K // 128, 128).sum(dim=2, dtype=torch.int32).t()
+    assert torch.equal(xsum, sums)
+    ymax = float(y.float().abs().max())
+    for n in [0, N - 1] + list(rng.integers(0, N, size=10)):
+        cr, sr, zr = oracle.quantize(w[n:n + 1], 8)
+        y_ref = oracle.linear_w8a8(xq_ref, sx_ref, cr, sr, zr)[:, 0].astype(np.float64)
+        got = y[ms, int(n)].cpu().numpy().astype(np.float64)
+        assert np.abs(got - y_ref).max() <= TOL_Y * ymax, n
