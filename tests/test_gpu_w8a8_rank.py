@@ -224,3 +224,43 @@ def test_rank_feeds_the_scheduler():
     expect = np.full(n, 8, dtype=np.int32)
     expect[ref_order[:3]] = 4
     assert np.array_equal(bits.cpu().numpy(), expect)
+
+
+def test_prefill_paths_repeatable_on_a_large_tile_grid():
+    # Several workgroup tiles per CU and many steps: repeated launches must agree bit for bit
+    # (a wavefront reading a buffer another one is already refilling shows up here), and a
+    # sample of columns from every part of a workgroup tile must match the oracle.
+    M, N, K = 600, 1024, 4096
+    w = synth.weight(0, "par/rep/w", N, K, 0.015)
+    x = synth.activations(0, "par/rep/x", M, K)
+    layer, packed = make_layer(w, (4, 8))
+    x_dev = to_dev(x)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    xsum = torch.empty((K // 128, M), dtype=torch.int32, device=DEV)
+    fq.fq_quantize_act(x_dev, M, K, xq, sx, xsum)
+    runs = {"w4": [], "w8": [], "w8a8": []}
+    for _ in range(3):
+        for key, fn in (("w4", lambda y: fq.fq_linear(layer, 4, x_dev, M, y)),
+                        ("w8", lambda y: fq.fq_linear(layer, 8, x_dev, M, y)),
+                        ("w8a8", lambda y: fq.fq_linear_w8a8(layer, xq, sx, xsum, M, y))):
+            y = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+            fn(y)
+            runs[key].append(y)
+    torch.cuda.synchronize()
+    for key, ys in runs.items():
+        assert torch.equal(ys[0].view(torch.int16), ys[1].view(torch.int16)), key
+        assert torch.equal(ys[0].view(torch.int16), ys[2].view(torch.int16)), key
+    cols = [0, 31, 32, 63, 64, 127, 128, 129, 191, 192, 255, 256, 511, 700, 1023]
+    ms = [0, 95, 96, 191, 192, 255, 256, 599]
+    xq_h, sx_h = xq.cpu().numpy(), sx.cpu().numpy()
+    for key, bits in (("w4", 4), ("w8", 8), ("w8a8", 8)):
+        c, s, z = (t.cpu().numpy() for t in packed[bits])
+        y = runs[key][0].cpu().numpy()
+        for n in cols:
+            if key == "w8a8":
+                ref = oracle.linear_w8a8(xq_h[ms], sx_h[ms], c[n:n + 1], s[n:n + 1], z[n:n + 1])
+            else:
+                ref = oracle.linear(x[ms], c[n:n + 1], s[n:n + 1], z[n:n + 1], bits)
+            got = y[ms, n].astype(np.float64)
+            assert np.abs(got - ref[:, 0].astype(np.float64)).max() <= TOL_Y * np.abs(y.astype(np.float64)).max(), (key, n)
