@@ -1,0 +1,687 @@
+// Decode-phase weight-only quantized linear for small batches (2 <= M <= 16), streaming
+// kernel for launches with many 256-row tiles: y[M][N] = x[M][K] . dequant(W[N][K])^T,
+// dequant = Sec. 2.2 Eq. (3).  The phase is bound by the weight stream (Sec. 4.1); the
+// contraction runs on v_mfma_f32_16x16x32_f16 (A = x: 16 batch rows x 32 k, B = 16 weight
+// rows x 32 k, binary32 accumulation).  Launches with few or narrow tiles and batches above
+// 16 stay with the register-fed small-batch kernel.
+//
+// Work split.  A workgroup owns a tile of 256 weight rows and has ten wavefronts: eight
+// consumers (two per SIMD, so that one computes while the other waits), 32 rows = 2 MFMA row
+// tiles each, and two loaders.
+//
+// Weight stream.  A stage is one 128-byte line of each of the consumer's 32 rows (256 / 128 /
+// 64 k at 4 / 8 / 16 bits); a load instruction covers 8 rows x 128 bytes, whole lines only
+// (halves of a line requested apart are fetched from HBM twice more often than not), marked
+// non-temporal (read once).  Stages go from global memory straight into a wavefront-private
+// LDS ring of two slots with direct-to-LDS loads (global_load_lds_dwordx4): no register
+// staging, and the only synchronisation the stream needs is a counted s_waitcnt vmcnt(n) of
+// the wavefront on its own loads.  A step waits for its stage, copies it to registers together
+// with the x blocks and the scales / zero points it needs, and at once requests the stage two
+// steps ahead into the slot it has just emptied: two stages per consumer, 64 KiB per CU, are
+// in flight while the step computes (three measured the same: the memory system is the limit,
+// not the depth).  These LDS reads are inline assembly: the compiler cannot tell a read of a
+// run-time slot from the slots being filled and would wait for every outstanding load first.
+//
+// Loaders.  x and the metadata are what the stream cannot carry: a scale or zero-point fetch
+// per stage touches one cache line per row (64 tiny requests per instruction, more than the
+// weights themselves need), and the 4-bit path wants x permuted.  Two more wavefronts fetch
+// them with ordinary loads -- their own vmcnt, nobody else waits -- in chunks of 512 k, each
+// loader every other chunk, requested two chunk periods before they are due: x as 16-byte
+// blocks of 8 halves, one request of 1 KiB per batch row and chunk, stored [k block][batch
+// row] with the rows of k block kb XOR-ed by kb % 16 (conflict free for the writer, whose
+// lanes are k blocks, and for the readers, whose lanes are batch rows), zero past K, for the
+// 4-bit path permuted inside the block to the order the unpacking produces (x0 x4 x1 x5 x2 x6
+// x3 x7); scales and zero points for a pair of chunks at a time (8 units: 32 + 8 contiguous
+// bytes per row), stored [consumer][row][row tile][unit].  One barrier per chunk hands a
+// chunk over.
+//
+// Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is the
+// pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q; bytes go
+// under 0x64 with v_perm_b32).  The offsets and the zero point are not subtracted per weight:
+// a second MFMA per operand multiplies the same x block by the constant -(offset + z), so
+// that the accumulator holds sum x (q - z) over the stage (every product is exact in
+// binary32), which is folded as out += s * acc -- Eq. (3) with the scale factored out of the
+// group.  The vector ALUs are left with the unpacking (5 instructions per 8 four-bit weights).
+//
+// LDS layout of a weight stage: per row tile 16 lines of 128 bytes, the eight 16-byte slots of
+// line n XOR-ed by (n >> 1) & 7 -- a 128-bit read of the 16 rows at one piece is conflict
+// free; the permutation is applied on the global side of the load.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+
+namespace {
+
+#define FQ_GLOBAL __attribute__((address_space(1)))
+#define FQ_LDS __attribute__((address_space(3)))
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int CONSUMERS = 8;
+constexpr int LOADERS = 2;
+constexpr int THREADS = (CONSUMERS + LOADERS) * 64;
+constexpr int RT = 2;                         // MFMA row tiles (16 rows) per consumer
+constexpr int TILE_ROWS = CONSUMERS * RT * 16;
+constexpr int NS = 2;                         // ring slots per consumer (3 measured the same)
+constexpr int STAGE_BYTES = RT * 16 * 128;    // 4 KiB of weights per stage
+constexpr int SOPS = STAGE_BYTES / 1024;      // direct-to-LDS loads per lane and stage
+constexpr int KC = 512;                       // k per chunk of x: one 16-byte block per loader lane and batch row
+constexpr int UC = KC / 128;                  // units (quantization groups) per chunk
+constexpr int UP = 2 * UC;                    // units per metadata fetch: a pair of chunks
+constexpr int XBYTES = 16 * KC * 2;           // one x buffer (16 batch rows)
+
+// Workgroup barrier without the fence of __syncthreads() (which would wait for every
+// outstanding load, i.e. drain the rings); the waits that matter are issued explicitly.
+__device__ __forceinline__ void barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ float4_t mfma(const u32x4 a, const u32x4 b, float4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c,
+                                                  0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const FQ_LDS void *)p;
+}
+
+struct Sel {
+    const uint8_t *codes;
+    const float *scales;
+    const uint8_t *zeros;
+    const uint16_t *x;
+    uint16_t *y;
+    int N, K;
+};
+
+// The workgroup's LDS.  x and metadata buffers come in pairs (chunk parity).
+struct Lds {
+    uint8_t *ring;    // [CONSUMERS][NS][STAGE_BYTES]
+    uint8_t *x[2];    // [KC / 8][16] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 16)
+    float *ms[2];     // [CONSUMERS][16 rows][RT][UP] scales of a pair of chunks
+    uint8_t *mz[2];   // same order, zero points
+};
+
+// What a step holds in registers: the stage's weights (pieces c and c + 4 of the lane's line in
+// each row tile), the scales and zero points of the lane's row in each row tile for the stage's
+// units, and the x blocks the lane supplies to the stage's MFMAs (8 / 4 / 2 at 4 / 8 / 16 bits).
+struct Stage {
+    u32x4 w[RT][2];
+    float s[RT][2]; // [row tile][unit of the stage] (8 bits: one unit)
+    uint32_t z;     // byte 2 * rt + unit
+    u32x4 a[8];
+};
+
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// Wait until at most ALLOW of the wavefront's loads are outstanding (the stage of this step is
+// older than those), then copy the slot, the metadata and the stage's x blocks to registers.
+// `wa`, `wb`: LDS byte addresses of the lane's two pieces in row tile 0 of the slot; `sa`, `za`:
+// of the lane's scales and zero points for row tile 0 (row tile 1: UP entries further); `xa`:
+// of the lane's x blocks.  All of it is inline assembly on purpose: the compiler cannot tell
+// these reads from the slots being filled and would wait for every outstanding load first.
+template <int BITS, int ALLOW>
+__device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint32_t za, const uint32_t (&xa)[4],
+                                     Stage &st)
+{
+    if constexpr (BITS == 4) {
+        float2_t s0, s1;
+        uint32_t z0, z1;
+        asm volatile("s_waitcnt vmcnt(%24)\n\t"
+                     "ds_read_b128 %0, %16\n\t"
+                     "ds_read_b128 %1, %17\n\t"
+                     "ds_read_b128 %2, %16 offset:2048\n\t"
+                     "ds_read_b128 %3, %17 offset:2048\n\t"
+                     "ds_read_b64 %4, %18\n\t"
+                     "ds_read_b64 %5, %18 offset:32\n\t"
+                     "ds_read_u16 %6, %19\n\t"
+                     "ds_read_u16 %7, %19 offset:8\n\t"
+                     "ds_read_b128 %8, %20\n\t"
+                     "ds_read_b128 %9, %21\n\t"
+                     "ds_read_b128 %10, %22\n\t"
+                     "ds_read_b128 %11, %23\n\t"
+                     "ds_read_b128 %12, %20 offset:4096\n\t"
+                     "ds_read_b128 %13, %21 offset:4096\n\t"
+                     "ds_read_b128 %14, %22 offset:4096\n\t"
+                     "ds_read_b128 %15, %23 offset:4096\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(s0), "=&v"(s1),
+                       "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3]),
+                       "=&v"(st.a[4]), "=&v"(st.a[5]), "=&v"(st.a[6]), "=&v"(st.a[7])
+                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW)
+                     : "memory");
+        st.s[0][0] = s0.x, st.s[0][1] = s0.y, st.s[1][0] = s1.x, st.s[1][1] = s1.y;
+        st.z = z0 | (z1 << 16);
+    } else if constexpr (BITS == 8) {
+        uint32_t z0, z1;
+        asm volatile("s_waitcnt vmcnt(%20)\n\t"
+                     "ds_read_b128 %0, %12\n\t"
+                     "ds_read_b128 %1, %13\n\t"
+                     "ds_read_b128 %2, %12 offset:2048\n\t"
+                     "ds_read_b128 %3, %13 offset:2048\n\t"
+                     "ds_read_b32 %4, %14\n\t"
+                     "ds_read_b32 %5, %14 offset:32\n\t"
+                     "ds_read_u8 %6, %15\n\t"
+                     "ds_read_u8 %7, %15 offset:8\n\t"
+                     "ds_read_b128 %8, %16\n\t"
+                     "ds_read_b128 %9, %17\n\t"
+                     "ds_read_b128 %10, %18\n\t"
+                     "ds_read_b128 %11, %19\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.s[0][0]),
+                       "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]),
+                       "=&v"(st.a[3])
+                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW)
+                     : "memory");
+        st.z = z0 | (z1 << 16);
+    } else {
+        asm volatile("s_waitcnt vmcnt(%10)\n\t"
+                     "ds_read_b128 %0, %6\n\t"
+                     "ds_read_b128 %1, %7\n\t"
+                     "ds_read_b128 %2, %6 offset:2048\n\t"
+                     "ds_read_b128 %3, %7 offset:2048\n\t"
+                     "ds_read_b128 %4, %8\n\t"
+                     "ds_read_b128 %5, %9\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
+                       "=&v"(st.a[1])
+                     : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
+                     : "memory");
+    }
+}
+
+template <int BITS>
+struct Cfg {
+    static constexpr int KPS = 128 * 8 / BITS; // k per stage: 256 / 128 / 64
+    static constexpr int SPC = KC / KPS;       // steps per chunk: 2 / 4 / 8
+};
+
+// ------------------------------------------------------------------ consumer wavefronts
+template <int BITS>
+struct Consumer {
+    typedef Cfg<BITS> C;
+    const Sel &d;
+    const Lds &L;
+    const int M, wave, lane, n, c, row0;
+    const int row_bytes;  // a multiple of 64
+    const int nchunks;
+    int T;                // steps: 128-byte lines of a row (the last may be half a line at 4 bits)
+    uint8_t *ring;        // this wavefront's NS slots
+    const uint8_t *gbase; // first byte of the wavefront's first row (wave-uniform)
+    // per-lane constants of the weight loads: load i of a stage covers rows 8 i .. 8 i + 7, lane
+    // -> row lane / 8 of those, LDS slot lane % 8, i.e. piece slot ^ ((row % 16) >> 1) of the line
+    uint32_t ld_off[SOPS]; // byte offset of the lane's row from the first row, plus its piece
+    uint32_t ld_hi;        // 64 if the lane's piece in even loads lies in the upper half of the line (odd: the other)
+    uint32_t wa0, wb0;     // LDS addresses for take(): the lane's pieces c and c + 4 in slot 0
+    uint32_t ml;           // wave * 16 + n: the lane's place in the metadata of a pair of chunks
+    // byte offsets of the lane's x blocks inside a stage's blocks (block kb holds batch row n at
+    // place n ^ (kb % 16)).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
+    // 16 bits: blocks 4 h + c of an even stage, 8 + 4 h + c of an odd one
+    uint32_t xq[4];
+    float4_t acc[RT], out[RT];
+
+    __device__ __forceinline__ Consumer(const Sel &d_, const Lds &L_, int M_, int tile_row0, int wave_)
+        : d(d_), L(L_), M(M_), wave(wave_), lane(threadIdx.x & 63), n(lane & 15), c(lane >> 4),
+          row0(tile_row0 + wave_ * RT * 16), row_bytes(d_.K * BITS / 8), nchunks((d_.K + KC - 1) / KC)
+    {
+        T = (row_bytes + 127) / 128;
+        ring = L.ring + wave * NS * STAGE_BYTES;
+        // the wavefront's rows span at most 32 * row_bytes < 4 GiB: 32-bit lane offsets from a uniform base
+        const int first_row = min(row0, d.N - 1);
+        gbase = d.codes + (size_t)first_row * (size_t)row_bytes;
+        const int r = lane >> 3, slot = lane & 7;
+#pragma unroll
+        for (int i = 0; i < SOPS; i++) {
+            const int rl = 8 * i + r; // row inside the wavefront's 32
+            const int piece = slot ^ (((rl & 15) >> 1) & 7);
+            const int row = min(row0 + rl, d.N - 1);
+            ld_off[i] = (uint32_t)(row - first_row) * (uint32_t)row_bytes + (uint32_t)piece * 16;
+        }
+        ld_hi = ((slot ^ (r >> 1)) & 4) * 16; // bit 2 of the piece flips with the parity of i
+        wa0 = lds_addr(ring) + n * 128 + ((c ^ ((n >> 1) & 7)) * 16);
+        wb0 = wa0 ^ 64; // piece c + 4
+        ml = wave * 16 + n;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int kb = BITS == 4 ? 4 * c + i : BITS == 8 ? 8 * (i >> 1) + 2 * c + (i & 1) : 4 * i + c;
+            xq[i] = (uint32_t)(kb * 256 + ((n ^ (kb & 15)) * 16));
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            out[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    // Request step q (line q of every row) into ring slot `slot`.  A 4-bit row may end with
+    // half a line: the lanes of the missing half re-read the present one (their x is zero).
+    __device__ __forceinline__ void fetch(int q, int slot)
+    {
+        const uint8_t *base = gbase + (size_t)q * 128;
+        uint8_t *dst = ring + slot * STAGE_BYTES;
+        const bool half_line = BITS == 4 && q * 128 + 64 >= row_bytes;
+        const uint32_t back_even = half_line ? ld_hi : 0u, back_odd = half_line ? 64u - ld_hi : 0u;
+#pragma unroll
+        for (int i = 0; i < SOPS; i++) {
+            uint32_t off = ld_off[i];
+            if (BITS == 4)
+                off -= (i & 1) ? back_odd : back_even; // pieces 4..7 -> 0..3
+            __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(base + off), (FQ_LDS void *)(dst + i * 1024), 16,
+                                             0, 2 /* nt: the weights are read once */);
+        }
+    }
+
+    __device__ __forceinline__ void compute(const Stage &st)
+    {
+        if (BITS == 4) {
+            uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
+            asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
+            const uint32_t z4 = (st.z << 4) & 0xF0F0F0F0u;
+#pragma unroll
+            for (int h = 0; h < 2; h++) { // the line's two units
+                u32x4 nz[RT];
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++) {
+                    const uint32_t by = (uint32_t)(2 * rt + h), sel = 0x04000400u | by | (by << 16);
+                    const uint32_t lo = __builtin_amdgcn_perm(0xE4E4E4E4u, st.z, sel); // -(1024 + z) twice
+                    const uint32_t hi = __builtin_amdgcn_perm(0xD4D4D4D4u, z4, sel);   // -(  64 + z) twice
+                    nz[rt] = u32x4{lo, hi, lo, hi};
+                }
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const u32x4 a = st.a[4 * h + i];
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) {
+                        const uint32_t w = st.w[rt][h][i], w8 = w >> 8;
+                        u32x4 b;
+                        b.x = (w & 0x000F000Fu) | magic_lo;  // (1024 + q0, 1024 + q4)
+                        b.y = (w & 0x00F000F0u) | magic_hi;  // (  64 + q1,   64 + q5)
+                        b.z = (w8 & 0x000F000Fu) | magic_lo; // (1024 + q2, 1024 + q6)
+                        b.w = (w8 & 0x00F000F0u) | magic_hi; // (  64 + q3,   64 + q7)
+                        acc[rt] = mfma(a, b, acc[rt]);
+                    }
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++)
+                        acc[rt] = mfma(a, nz[rt], acc[rt]);
+                }
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++) {
+                    out[rt] += st.s[rt][h] * acc[rt];
+                    acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        } else if (BITS == 8) {
+            u32x4 nz[RT];
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++) {
+                const uint32_t by = (uint32_t)(2 * rt), sel = 0x04000400u | by | (by << 16);
+                const uint32_t v = __builtin_amdgcn_perm(0xE4E4E4E4u, st.z, sel); // -(1024 + z) twice
+                nz[rt] = u32x4{v, v, v, v};
+            }
+#pragma unroll
+            for (int h = 0; h < 2; h++)
+#pragma unroll
+                for (int i = 0; i < 2; i++) {
+                    const u32x4 a = st.a[2 * h + i];
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++) {
+                        const uint32_t v0 = st.w[rt][h][2 * i], v1 = st.w[rt][h][2 * i + 1];
+                        u32x4 b;
+                        b.x = __builtin_amdgcn_perm(0x64646464u, v0, 0x04010400u);
+                        b.y = __builtin_amdgcn_perm(0x64646464u, v0, 0x04030402u);
+                        b.z = __builtin_amdgcn_perm(0x64646464u, v1, 0x04010400u);
+                        b.w = __builtin_amdgcn_perm(0x64646464u, v1, 0x04030402u);
+                        acc[rt] = mfma(a, b, acc[rt]);
+                    }
+#pragma unroll
+                    for (int rt = 0; rt < RT; rt++)
+                        acc[rt] = mfma(a, nz[rt], acc[rt]);
+                }
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++) {
+                out[rt] += st.s[rt][0] * acc[rt];
+                acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; h++)
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++)
+                    acc[rt] = mfma(st.a[h], st.w[rt][h], acc[rt]);
+        }
+    }
+
+    // Chunk ch, whose x and metadata are in the buffers of parity XB.
+    template <int XB>
+    __device__ __forceinline__ void chunk(int ch, int &fq, int &slot)
+    {
+        barrier(); // the loader has written chunk ch; everybody is done with chunk ch - 1
+        // metadata: buffer of the pair of chunks, the chunk's half of it, the lane's row
+        const uint32_t mo = ml * (RT * UP) + (ch & 1) * UC;
+        const uint32_t sbase = lds_addr((ch & 2) ? L.ms[1] : L.ms[0]) + mo * 4,
+                       zbase = lds_addr((ch & 2) ? L.mz[1] : L.mz[0]) + mo;
+        uint32_t xbase = lds_addr(L.x[XB]);
+        asm volatile("" : "+s"(xbase)); // opaque: or every stage's x addresses are hoisted out of the tile and spill
+#pragma unroll
+        for (int j = 0; j < C::SPC; j++) {
+            const int q = ch * C::SPC + j;
+            if (q >= T)
+                break;
+            // where the stage sits inside the chunk: its first unit, its x blocks
+            const int unit = j * C::KPS / 128;
+            const uint32_t wa = wa0 + slot * STAGE_BYTES, wb = wb0 + slot * STAGE_BYTES, sa = sbase + unit * 4,
+                           za = zbase + unit;
+            uint32_t xa[4];
+            if (BITS == 4) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    xa[i] = xbase + j * 8192 + xq[i];
+            } else if (BITS == 8) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    xa[i] = xbase + j * 4096 + xq[i];
+            } else {
+                xa[0] = xbase + (j >> 1) * 4096 + xq[2 * (j & 1)];
+                xa[1] = xbase + (j >> 1) * 4096 + xq[2 * (j & 1) + 1];
+                xa[2] = xa[3] = 0;
+            }
+            Stage st;
+            const int pend = __builtin_amdgcn_readfirstlane(fq - 1 - q); // younger stages in flight
+            if (NS > 2 && pend >= 2)
+                take<BITS, 2 * SOPS>(wa, wb, sa, za, xa, st);
+            else if (pend == 1)
+                take<BITS, SOPS>(wa, wb, sa, za, xa, st);
+            else
+                take<BITS, 0>(wa, wb, sa, za, xa, st);
+            if (fq < T) { // the stage NS steps ahead, into the slot just emptied
+                fetch(fq, slot);
+                fq++;
+            }
+            __builtin_amdgcn_sched_barrier(0); // keep the requests here: the scheduler sinks them otherwise
+            compute(st);
+            slot = slot == NS - 1 ? 0 : slot + 1;
+        }
+    }
+
+    __device__ __forceinline__ void run()
+    {
+        int fq = 0, slot = 0;
+        for (int s = 0; s < NS; s++)
+            if (fq < T) {
+                fetch(fq, s);
+                fq++;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        for (int ch = 0; ch < nchunks; ch += 2) {
+            chunk<0>(ch, fq, slot);
+            if (ch + 1 < nchunks)
+                chunk<1>(ch + 1, fq, slot);
+        }
+        // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            const int row = row0 + rt * 16 + n;
+            const float4_t v = BITS == 16 ? acc[rt] : out[rt];
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int m = c * 4 + r;
+                if (m < M && row < d.N)
+                    ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + row] = __builtin_bit_cast(uint16_t, (_Float16)v[r]);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        barrier(); // the loader may refill the buffers for the next tile
+    }
+};
+
+// ------------------------------------------------------------------ loader wavefront
+// (One code path for the three bit-widths: instantiated per width, the register allocator sees
+// three sets of staging registers live across the tile loop.)
+template <int LI>
+struct Loader {
+    const Sel &d;
+    const Lds &L;
+    const int M, lane, tile_row0, G, nchunks, BITS;
+    static constexpr int li = LI;
+    u32x4 xr[16];        // the chunk's block `lane` of every batch row: one 1 KiB request per row
+    // metadata of a pair of chunks (UP units): scales as 16 bytes = 4 units per lane, two lanes to
+    // a row, 32 rows to an instruction; zero points as 8 bytes per lane, one lane to a row
+    float4_t sr[TILE_ROWS / 32];
+    uint32_t zr[TILE_ROWS / 64][2];
+
+    __device__ __forceinline__ Loader(const Sel &d_, const Lds &L_, int M_, int tile_row0_, int bits)
+        : d(d_), L(L_), M(M_), lane(threadIdx.x & 63), tile_row0(tile_row0_), G(d_.K >> 7),
+          nchunks((d_.K + KC - 1) / KC), BITS(bits)
+    {
+    }
+
+    __device__ __forceinline__ void load_x(int ch)
+    {
+        const int k = ch * KC + lane * 8;
+
+#pragma unroll
+        for (int m = 0; m < 16; m++) {
+            // batch rows past M feed outputs that are never stored; k past K meets re-read weights
+            // (the missing half of a last line): x is zero there
+            const int mm = min(m, M - 1);
+            xr[m] = k < d.K ? *(const FQ_GLOBAL u32x4 *)(d.x + (size_t)mm * d.K + k) : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+
+    __device__ __forceinline__ void store_x(int b)
+    {
+        u32x4 *xb = reinterpret_cast<u32x4 *>(b ? L.x[1] : L.x[0]);
+#pragma unroll
+        for (int m = 0; m < 16; m++) {
+            u32x4 p = xr[m];
+            if (BITS == 4) { // (x0 .. x7) -> (x0 x4 x1 x5 x2 x6 x3 x7), the unpack order
+                p.x = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x05040100u);
+                p.y = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x07060302u);
+                p.z = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x05040100u);
+                p.w = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x07060302u);
+            }
+            xb[lane * 16 + (m ^ (lane & 15))] = p; // conflict free for the writer and for the readers
+        }
+    }
+
+    // Metadata of the pair of chunks cp: units UP * cp ...  Past G (a last, partial pair) the
+    // unit index is clamped, and then every unit is fetched on its own.  Addresses are a uniform
+    // base plus a 32-bit lane offset, recomputed per call (kept opaque: hoisted out of the tile
+    // they would cost a register each).
+    __device__ __forceinline__ void load_meta(int cp)
+    {
+        typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+        typedef uint32_t u32_a1 __attribute__((aligned(1)));
+        const int u0 = cp * UP;
+        const bool whole = u0 + UP <= G;
+        int last = d.N - 1 - tile_row0; // rows of the tile past N repeat row N - 1
+        asm volatile("" : "+s"(last));
+        const float *sbase = d.scales + (size_t)tile_row0 * (size_t)G;
+        const uint8_t *zbase = d.zeros + (size_t)tile_row0 * (size_t)G;
+#pragma unroll
+        for (int i = 0; i < TILE_ROWS / 32; i++) {
+            const uint32_t row = (uint32_t)min(32 * i + (lane >> 1), last);
+            const int u = u0 + 4 * (lane & 1);
+            if (whole) {
+                sr[i] = *(const FQ_GLOBAL f32x4_a4 *)(sbase + (row * (uint32_t)G + (uint32_t)u));
+            } else {
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    sr[i][g] = ((const FQ_GLOBAL float *)sbase)[row * (uint32_t)G + (uint32_t)min(u + g, G - 1)];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TILE_ROWS / 64; j++) {
+            const uint32_t row = (uint32_t)min(64 * j + lane, last);
+            if (whole) {
+                zr[j][0] = *(const FQ_GLOBAL u32_a1 *)(zbase + (row * (uint32_t)G + (uint32_t)u0));
+                zr[j][1] = *(const FQ_GLOBAL u32_a1 *)(zbase + (row * (uint32_t)G + (uint32_t)u0 + 4u));
+            } else {
+                zr[j][0] = zr[j][1] = 0;
+#pragma unroll
+                for (int g = 0; g < UP; g++)
+                    zr[j][g >> 2] |= (uint32_t)((const FQ_GLOBAL uint8_t *)zbase)[row * (uint32_t)G + (uint32_t)min(u0 + g, G - 1)]
+                                     << (8 * (g & 3));
+            }
+        }
+    }
+
+    // [consumer][row % 16][row tile][unit]
+    __device__ __forceinline__ void store_meta(int b)
+    {
+        float *ms = b ? L.ms[1] : L.ms[0];
+        uint8_t *mz = b ? L.mz[1] : L.mz[0];
+#pragma unroll
+        for (int i = 0; i < TILE_ROWS / 32; i++) {
+            // row 32 i + lane / 2 of the tile: consumer i, row tile lane / 32, row (lane / 2) % 16
+            const int idx = ((i * 16 + ((lane >> 1) & 15)) * RT + (lane >> 5)) * UP + 4 * (lane & 1);
+            *reinterpret_cast<float4_t *>(ms + idx) = sr[i];
+        }
+#pragma unroll
+        for (int j = 0; j < TILE_ROWS / 64; j++) {
+            // row 64 j + lane: consumer 2 j + lane / 32, row tile (lane / 16) % 2, row lane % 16
+            const int idx = (((2 * j + (lane >> 5)) * 16 + (lane & 15)) * RT + ((lane >> 4) & 1)) * UP;
+            *reinterpret_cast<uint2 *>(mz + idx) = make_uint2(zr[j][0], zr[j][1]);
+        }
+    }
+
+    __device__ __forceinline__ void load(int ch)
+    {
+        load_x(ch);
+        if (BITS != 16 && (ch & 1) == 0)
+            load_meta(ch >> 1);
+    }
+    __device__ __forceinline__ void store(int ch)
+    {
+        store_x(ch & 1);
+        if (BITS != 16 && (ch & 1) == 0)
+            store_meta((ch >> 1) & 1);
+    }
+
+    // Loader li owns the chunks of parity li (loader 0 with them the metadata, whose pairs start
+    // at even chunks).  Chunk g + 1 is written while the consumers work on chunk g, and the
+    // owner then requests chunk g + 3 at once: two chunk periods ahead of its own deadline,
+    // because a request joins the queue of everything the consumers have in flight on this CU
+    // and takes that long to come back.
+    __device__ __forceinline__ void run()
+    {
+        if (li < nchunks)
+            load(li);
+        if (li == 0) {
+            store(0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (2 < nchunks)
+                load(2);
+        }
+        for (int g = 0; g < nchunks; g++) {
+            __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): this wavefront's LDS writes are done
+            barrier();
+            if (g + 1 < nchunks && ((g + 1) & 1) == li) {
+                store(g + 1);
+                __builtin_amdgcn_sched_barrier(0); // the registers are reused: no load before the last write
+                if (g + 3 < nchunks)
+                    load(g + 3);
+            }
+        }
+        barrier(); // the consumers have stored the tile
+    }
+};
+
+// The tiles of one workgroup, as seen by its loader (LOADER) or by one of its consumers: the two
+// roles walk the same tiles in separate loops so that neither carries the other's registers.
+template <bool SINGLE, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
+__device__ __forceinline__ void run_tiles(const FqLinearDesc &single, int bits_host, const FqLinearDesc *table,
+                                          const int32_t *bits_dev, int count, int total_tiles, int M, const Lds &L,
+                                          int wave)
+{
+    const int grid = gridDim.x;
+    const int first = blockIdx.x;
+    int e = 0;
+    for (int tile = first; tile < total_tiles; tile += grid) {
+        const FqLinearDesc *dp;
+        int bits;
+        if (SINGLE) {
+            dp = &single;
+            bits = bits_host;
+        } else {
+            while (e + 1 < count && tile >= table[e + 1].tile_begin)
+                e++;
+            dp = &table[e];
+            bits = bits_dev[e];
+        }
+        Sel d;
+        d.N = dp->N;
+        d.K = dp->K;
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.x = dp->x;
+        d.y = dp->y;
+        if (!d.codes)
+            continue; // uniform over the workgroup
+        // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
+        // that every one of them reaches the barriers: one per chunk and one at the end.
+        const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
+        if (ROLE > 0) {
+            constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
+            Loader<LI>(d, L, M, tile_row0, bits).run();
+        } else {
+            if (bits == 4)
+                Consumer<4>(d, L, M, tile_row0, wave).run();
+            else if (bits == 8)
+                Consumer<8>(d, L, M, tile_row0, wave).run();
+            else
+                Consumer<16>(d, L, M, tile_row0, wave).run();
+        }
+    }
+}
+
+template <bool SINGLE>
+__global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc single, int bits_host,
+                                                                const FqLinearDesc *__restrict__ table,
+                                                                const int32_t *__restrict__ bits_dev, int count,
+                                                                int total_tiles, int M)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t ring[CONSUMERS * NS * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t x0[XBYTES], x1[XBYTES];
+    __shared__ __attribute__((aligned(256))) float ms0[UP * TILE_ROWS], ms1[UP * TILE_ROWS];
+    __shared__ __attribute__((aligned(256))) uint8_t mz0[UP * TILE_ROWS], mz1[UP * TILE_ROWS];
+    Lds L;
+    L.ring = ring;
+    L.x[0] = x0, L.x[1] = x1;
+    L.ms[0] = ms0, L.ms[1] = ms1;
+    L.mz[0] = mz0, L.mz[1] = mz1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave == CONSUMERS)
+        run_tiles<SINGLE, 1>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+    else if (wave > CONSUMERS)
+        run_tiles<SINGLE, 2>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+    else
+        run_tiles<SINGLE, 0>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+}
+
+} // namespace
+
+// Same contract as fq_launch_skinny for 2 <= M <= 16 and tiles of 256 rows.
+hipError_t fq_launch_skinny_stream(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
+                                   const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
+                                   hipStream_t stream)
+{
+    // one workgroup per CU (LDS): persistent over the tiles
+    const int grid = total_tiles < cus ? total_tiles : cus;
+    if (single) {
+        decode_stream_kernel<true><<<grid, THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1, total_tiles, M);
+    } else {
+        FqLinearDesc none = {};
+        decode_stream_kernel<false><<<grid, THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count, total_tiles, M);
+    }
+    return hipGetLastError();
+}

@@ -1,0 +1,94 @@
+"""Parity of the streaming small-batch kernel (2 <= M <= 16, launches with at least a thousand
+256-row tiles) with the CPU oracle, element by element.  The plan below is the smallest that
+takes that path: many linears of modest K, whose shapes cover a single quantization group
+(half a 128-byte line at 4 bits), odd and even group counts, a last chunk of x that is not full,
+and row counts that end inside a tile and inside an MFMA row tile."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2506_12024_amd as fq
+from gpu_util import DEV, make_layer, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL_Y = 2e-3
+NS = [6656, 6600, 4100, 7000, 5000]
+KS = [128, 384, 640, 1152, 256]
+MIN_ROWS = 1024 * 256  # what the dispatcher asks for before it uses 256-row tiles
+
+
+def _build(M, tag, weight_fn):
+    shapes, rows, i = [], 0, 0
+    while rows < MIN_ROWS + 256:
+        shapes.append((NS[i % 5], KS[(i + i // 5) % 5]))
+        rows += shapes[-1][0]
+        i += 1
+    layers, packs, xs_np, xs, ys = [], [], [], [], []
+    for i, (N, K) in enumerate(shapes):
+        w = weight_fn(i, N, K)
+        layer, packed = make_layer(w, (4, 8, 16))
+        x = synth.activations(0, "%s/x%d/%d" % (tag, i, M), M, K)
+        layers.append(layer)
+        packs.append((w, packed))
+        xs_np.append(x)
+        xs.append(to_dev(x))
+        ys.append(torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+    ws = torch.empty(fq.Plan.workspace_bytes(len(layers)), dtype=torch.uint8, device=DEV)
+    return shapes, layers, packs, xs_np, xs, ys, fq.Plan(layers, xs, ys, M, ws)
+
+
+@pytest.mark.parametrize("M,every", [(16, 1), (5, 3), (2, 4)])
+def test_streaming_plan_matches_oracle(M, every):
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(
+        M, "par/stream", lambda i, N, K: synth.weight(0, "par/stream/w%d" % i, N, K, 0.02, outlier_p=0.001))
+    for shift in (0, 1):
+        pattern = [(4, 8, 16)[(i + shift) % 3] for i in range(len(layers))]
+        for y in ys:
+            y.fill_(float("nan"))
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        for i, b in enumerate(pattern):
+            y = ys[i].cpu().numpy()
+            assert np.isfinite(y.astype(np.float32)).all(), (M, i, b, shapes[i])
+            if (i + shift) % every:
+                continue
+            w, packed = packs[i]
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(y, y_ref) <= TOL_Y, (M, i, b, shapes[i])
+
+
+def test_streaming_plan_integer_case_exact():
+    # integer activations, weights on the quantization grid with s = 1 and z = 0 (every group
+    # spans 0 .. 2^b - 1): every product and every partial sum is an integer below 2^24, so the
+    # kernel's offset trick (x times 1024 + q, then x times -(1024 + z)) must cancel exactly
+    M = 16
+    rng = np.random.default_rng(3)
+
+    def weights(i, N, K):
+        w = rng.integers(0, 16, size=(N, K)).astype(np.float16)
+        w[:, 0::128] = 0
+        w[:, 1::128] = 15
+        return w
+
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(M, "par/stream/int", weights)
+    for i, (N, K) in enumerate(shapes):  # integer x in place of the generator's
+        xi = (rng.integers(-1, 2, size=(M, K)) * (rng.random((M, K)) < 0.3)).astype(np.float16)
+        xs_np[i] = xi
+        xs[i].copy_(to_dev(xi))
+    pattern = [(4, 16, 4, 16, 4)[i % 5] for i in range(len(layers))]
+    plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    for i in range(0, len(layers), 2):
+        w, packed = packs[i]
+        if pattern[i] == 4:
+            assert torch.all(packed[4][1] == 1.0) and torch.all(packed[4][2] == 0)
+        expect = (xs_np[i].astype(np.float64) @ w.astype(np.float64).T)
+        assert np.abs(expect).max() < 2048
+        assert np.array_equal(ys[i].cpu().numpy().astype(np.float64), expect), (i, pattern[i], shapes[i])
