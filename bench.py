@@ -33,7 +33,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per plan launch of the default workload relative to its algorithmic bytes, measured
 # with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
-MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993230.0 / 4978290.0}
+MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993230.0 / 4978290.0,
+                          # profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md
+                          ("llama7b", 16, (4, 8, 16)): 8.438 / 7.857}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
 VOCAB = 32000
 SEED = 0
@@ -595,7 +597,9 @@ def main():
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
         "entropy_kl_us": ent_us,
-        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else "decode_skinny_kernel"),
+        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else
+                                                                  "decode_stream_kernel" if args.batch <= 16 else
+                                                                  "decode_skinny_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": alg_bytes * MEASURED_TRAFFIC_RATIO[(args.stack, args.batch, bit_choices)]

@@ -597,26 +597,18 @@ struct Loader {
 
 // The tiles of one workgroup, as seen by its loader (LOADER) or by one of its consumers: the two
 // roles walk the same tiles in separate loops so that neither carries the other's registers.
-template <bool SINGLE, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
-__device__ __forceinline__ void run_tiles(const FqLinearDesc &single, int bits_host, const FqLinearDesc *table,
-                                          const int32_t *bits_dev, int count, int total_tiles, int M, const Lds &L,
-                                          int wave)
+template <int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
+__device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
+                                          int total_tiles, int M, const Lds &L, int wave)
 {
     const int grid = gridDim.x;
     const int first = blockIdx.x;
     int e = 0;
     for (int tile = first; tile < total_tiles; tile += grid) {
-        const FqLinearDesc *dp;
-        int bits;
-        if (SINGLE) {
-            dp = &single;
-            bits = bits_host;
-        } else {
-            while (e + 1 < count && tile >= table[e + 1].tile_begin)
-                e++;
-            dp = &table[e];
-            bits = bits_dev[e];
-        }
+        while (e + 1 < count && tile >= table[e + 1].tile_begin)
+            e++;
+        const FqLinearDesc *dp = &table[e];
+        const int bits = bits_dev[e];
         Sel d;
         d.N = dp->N;
         d.K = dp->K;
@@ -644,9 +636,7 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc &single, int bits_h
     }
 }
 
-template <bool SINGLE>
-__global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc single, int bits_host,
-                                                                const FqLinearDesc *__restrict__ table,
+__global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev, int count,
                                                                 int total_tiles, int M)
 {
@@ -661,27 +651,22 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
     L.mz[0] = mz0, L.mz[1] = mz1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave == CONSUMERS)
-        run_tiles<SINGLE, 1>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<1>(table, bits_dev, count, total_tiles, M, L, wave);
     else if (wave > CONSUMERS)
-        run_tiles<SINGLE, 2>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<2>(table, bits_dev, count, total_tiles, M, L, wave);
     else
-        run_tiles<SINGLE, 0>(single, bits_host, table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<0>(table, bits_dev, count, total_tiles, M, L, wave);
 }
 
 } // namespace
 
-// Same contract as fq_launch_skinny for 2 <= M <= 16 and tiles of 256 rows.
-hipError_t fq_launch_skinny_stream(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
-                                   const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
-                                   hipStream_t stream)
+// A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 16 and
+// tiles of 256 rows.
+hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
+                                   int M, int cus, hipStream_t stream)
 {
     // one workgroup per CU (LDS): persistent over the tiles
     const int grid = total_tiles < cus ? total_tiles : cus;
-    if (single) {
-        decode_stream_kernel<true><<<grid, THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1, total_tiles, M);
-    } else {
-        FqLinearDesc none = {};
-        decode_stream_kernel<false><<<grid, THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count, total_tiles, M);
-    }
+    decode_stream_kernel<<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
     return hipGetLastError();
 }
