@@ -46,7 +46,7 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
                             int total_tiles, int tile_rows, int M, hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
-// Streaming variant for plan launches with 2 <= M <= 16 and tiles of 256 rows (fq_launch_skinny
+// Streaming variant for plan launches with 2 <= M <= 32 and tiles of 256 rows (fq_launch_skinny
 // hands those to it).
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
                                    int total_tiles, int M, int cus, hipStream_t stream);

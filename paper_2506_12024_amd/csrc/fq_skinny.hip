@@ -435,7 +435,7 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
         return hipSuccess;
     const int cus = device_cus();
     const int rt = tile_rows / 64;
-    if (!single && M <= 16 && tile_rows == 256)
+    if (!single && tile_rows == 256)
         return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, stream);
     if (M <= 16) {
         if (rt == 4)

@@ -1,9 +1,9 @@
-// Decode-phase weight-only quantized linear for small batches (2 <= M <= 16), streaming
+// Decode-phase weight-only quantized linear for small batches (2 <= M <= 32), streaming
 // kernel for launches with many 256-row tiles: y[M][N] = x[M][K] . dequant(W[N][K])^T,
 // dequant = Sec. 2.2 Eq. (3).  The phase is bound by the weight stream (Sec. 4.1); the
 // contraction runs on v_mfma_f32_16x16x32_f16 (A = x: 16 batch rows x 32 k, B = 16 weight
-// rows x 32 k, binary32 accumulation).  Launches with few or narrow tiles and batches above
-// 16 stay with the register-fed small-batch kernel.
+// rows x 32 k, binary32 accumulation; two batch tiles above 16 rows).  Launches with few or
+// narrow tiles and single calls stay with the register-fed small-batch kernel.
 //
 // Work split.  A workgroup owns a tile of 256 weight rows and has ten wavefronts: eight
 // consumers (two per SIMD, so that one computes while the other waits), 32 rows = 2 MFMA row
@@ -71,7 +71,7 @@ constexpr int SOPS = STAGE_BYTES / 1024;      // direct-to-LDS loads per lane an
 constexpr int KC = 512;                       // k per chunk of x: one 16-byte block per loader lane and batch row
 constexpr int UC = KC / 128;                  // units (quantization groups) per chunk
 constexpr int UP = 2 * UC;                    // units per metadata fetch: a pair of chunks
-constexpr int XBYTES = 16 * KC * 2;           // one x buffer (16 batch rows)
+// MT below: batch tiles of 16 rows (1 for M <= 16, 2 for M <= 32); an x buffer is 16 * MT * KC halves
 
 // Workgroup barrier without the fence of __syncthreads() (which would wait for every
 // outstanding load, i.e. drain the rings); the waits that matter are issued explicitly.
@@ -105,14 +105,15 @@ struct Sel {
 // The workgroup's LDS.  x and metadata buffers come in pairs (chunk parity).
 struct Lds {
     uint8_t *ring;    // [CONSUMERS][NS][STAGE_BYTES]
-    uint8_t *x[2];    // [KC / 8][16] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 16)
+    uint8_t *x[2];    // [KC / 8][16 * MT] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 16)
     float *ms[2];     // [CONSUMERS][16 rows][RT][UP] scales of a pair of chunks
     uint8_t *mz[2];   // same order, zero points
 };
 
 // What a step holds in registers: the stage's weights (pieces c and c + 4 of the lane's line in
 // each row tile), the scales and zero points of the lane's row in each row tile for the stage's
-// units, and the x blocks the lane supplies to the stage's MFMAs (8 / 4 / 2 at 4 / 8 / 16 bits).
+// units, and x blocks the lane supplies to the stage's MFMAs: 8 / 4 / 2 per batch tile at 4 / 8 /
+// 16 bits; with two batch tiles the 4-bit stage takes its 16 in two rounds, one per unit.
 struct Stage {
     u32x4 w[RT][2];
     float s[RT][2]; // [row tile][unit of the stage] (8 bits: one unit)
@@ -128,7 +129,9 @@ typedef float float2_t __attribute__((ext_vector_type(2)));
 // of the lane's scales and zero points for row tile 0 (row tile 1: UP entries further); `xa`:
 // of the lane's x blocks.  All of it is inline assembly on purpose: the compiler cannot tell
 // these reads from the slots being filled and would wait for every outstanding load first.
-template <int BITS, int ALLOW>
+// Which x blocks land in st.a: 4 bits, MT = 1: [unit][i]; 4 bits, MT = 2: [batch tile][i] of
+// unit 0 (unit 1 follows with more_x); 8 bits: [batch tile][half][i]; 16 bits: [batch tile][half].
+template <int BITS, int MT, int ALLOW>
 __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint32_t za, const uint32_t (&xa)[4],
                                      Stage &st)
 {
@@ -148,54 +151,119 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                      "ds_read_b128 %9, %21\n\t"
                      "ds_read_b128 %10, %22\n\t"
                      "ds_read_b128 %11, %23\n\t"
-                     "ds_read_b128 %12, %20 offset:4096\n\t"
-                     "ds_read_b128 %13, %21 offset:4096\n\t"
-                     "ds_read_b128 %14, %22 offset:4096\n\t"
-                     "ds_read_b128 %15, %23 offset:4096\n\t"
+                     "ds_read_b128 %12, %20 offset:%25\n\t"
+                     "ds_read_b128 %13, %21 offset:%25\n\t"
+                     "ds_read_b128 %14, %22 offset:%25\n\t"
+                     "ds_read_b128 %15, %23 offset:%25\n\t"
                      "s_waitcnt lgkmcnt(0)"
                      : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(s0), "=&v"(s1),
                        "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3]),
                        "=&v"(st.a[4]), "=&v"(st.a[5]), "=&v"(st.a[6]), "=&v"(st.a[7])
-                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW)
+                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW),
+                       "n"(MT == 1 ? 4096 : 256) // the second unit, or the second batch tile of the first unit
                      : "memory");
         st.s[0][0] = s0.x, st.s[0][1] = s0.y, st.s[1][0] = s1.x, st.s[1][1] = s1.y;
         st.z = z0 | (z1 << 16);
     } else if constexpr (BITS == 8) {
         uint32_t z0, z1;
-        asm volatile("s_waitcnt vmcnt(%20)\n\t"
-                     "ds_read_b128 %0, %12\n\t"
-                     "ds_read_b128 %1, %13\n\t"
-                     "ds_read_b128 %2, %12 offset:2048\n\t"
-                     "ds_read_b128 %3, %13 offset:2048\n\t"
-                     "ds_read_b32 %4, %14\n\t"
-                     "ds_read_b32 %5, %14 offset:32\n\t"
-                     "ds_read_u8 %6, %15\n\t"
-                     "ds_read_u8 %7, %15 offset:8\n\t"
-                     "ds_read_b128 %8, %16\n\t"
-                     "ds_read_b128 %9, %17\n\t"
-                     "ds_read_b128 %10, %18\n\t"
-                     "ds_read_b128 %11, %19\n\t"
-                     "s_waitcnt lgkmcnt(0)"
-                     : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.s[0][0]),
-                       "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]),
-                       "=&v"(st.a[3])
-                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW)
-                     : "memory");
+        if constexpr (MT == 1) {
+            asm volatile("s_waitcnt vmcnt(%20)\n\t"
+                         "ds_read_b128 %0, %12\n\t"
+                         "ds_read_b128 %1, %13\n\t"
+                         "ds_read_b128 %2, %12 offset:2048\n\t"
+                         "ds_read_b128 %3, %13 offset:2048\n\t"
+                         "ds_read_b32 %4, %14\n\t"
+                         "ds_read_b32 %5, %14 offset:32\n\t"
+                         "ds_read_u8 %6, %15\n\t"
+                         "ds_read_u8 %7, %15 offset:8\n\t"
+                         "ds_read_b128 %8, %16\n\t"
+                         "ds_read_b128 %9, %17\n\t"
+                         "ds_read_b128 %10, %18\n\t"
+                         "ds_read_b128 %11, %19\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]),
+                           "=&v"(st.s[0][0]), "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]),
+                           "=&v"(st.a[2]), "=&v"(st.a[3])
+                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]),
+                           "n"(ALLOW)
+                         : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(%24)\n\t"
+                         "ds_read_b128 %0, %16\n\t"
+                         "ds_read_b128 %1, %17\n\t"
+                         "ds_read_b128 %2, %16 offset:2048\n\t"
+                         "ds_read_b128 %3, %17 offset:2048\n\t"
+                         "ds_read_b32 %4, %18\n\t"
+                         "ds_read_b32 %5, %18 offset:32\n\t"
+                         "ds_read_u8 %6, %19\n\t"
+                         "ds_read_u8 %7, %19 offset:8\n\t"
+                         "ds_read_b128 %8, %20\n\t"
+                         "ds_read_b128 %9, %21\n\t"
+                         "ds_read_b128 %10, %22\n\t"
+                         "ds_read_b128 %11, %23\n\t"
+                         "ds_read_b128 %12, %20 offset:256\n\t"
+                         "ds_read_b128 %13, %21 offset:256\n\t"
+                         "ds_read_b128 %14, %22 offset:256\n\t"
+                         "ds_read_b128 %15, %23 offset:256\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]),
+                           "=&v"(st.s[0][0]), "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]),
+                           "=&v"(st.a[2]), "=&v"(st.a[3]), "=&v"(st.a[4]), "=&v"(st.a[5]), "=&v"(st.a[6]),
+                           "=&v"(st.a[7])
+                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]),
+                           "n"(ALLOW)
+                         : "memory");
+        }
         st.z = z0 | (z1 << 16);
     } else {
-        asm volatile("s_waitcnt vmcnt(%10)\n\t"
-                     "ds_read_b128 %0, %6\n\t"
-                     "ds_read_b128 %1, %7\n\t"
-                     "ds_read_b128 %2, %6 offset:2048\n\t"
-                     "ds_read_b128 %3, %7 offset:2048\n\t"
-                     "ds_read_b128 %4, %8\n\t"
-                     "ds_read_b128 %5, %9\n\t"
-                     "s_waitcnt lgkmcnt(0)"
-                     : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
-                       "=&v"(st.a[1])
-                     : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
-                     : "memory");
+        if constexpr (MT == 1) {
+            asm volatile("s_waitcnt vmcnt(%10)\n\t"
+                         "ds_read_b128 %0, %6\n\t"
+                         "ds_read_b128 %1, %7\n\t"
+                         "ds_read_b128 %2, %6 offset:2048\n\t"
+                         "ds_read_b128 %3, %7 offset:2048\n\t"
+                         "ds_read_b128 %4, %8\n\t"
+                         "ds_read_b128 %5, %9\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
+                           "=&v"(st.a[1])
+                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
+                         : "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(%12)\n\t"
+                         "ds_read_b128 %0, %8\n\t"
+                         "ds_read_b128 %1, %9\n\t"
+                         "ds_read_b128 %2, %8 offset:2048\n\t"
+                         "ds_read_b128 %3, %9 offset:2048\n\t"
+                         "ds_read_b128 %4, %10\n\t"
+                         "ds_read_b128 %5, %11\n\t"
+                         "ds_read_b128 %6, %10 offset:256\n\t"
+                         "ds_read_b128 %7, %11 offset:256\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
+                           "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3])
+                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
+                         : "memory");
+        }
     }
+}
+
+// The x blocks of the second unit of a 4-bit stage with two batch tiles: [batch tile][i].
+__device__ __forceinline__ void more_x(uint32_t xa0, uint32_t xa1, uint32_t xa2, uint32_t xa3, Stage &st)
+{
+    asm volatile("ds_read_b128 %0, %8 offset:8192\n\t"
+                 "ds_read_b128 %1, %9 offset:8192\n\t"
+                 "ds_read_b128 %2, %10 offset:8192\n\t"
+                 "ds_read_b128 %3, %11 offset:8192\n\t"
+                 "ds_read_b128 %4, %8 offset:8448\n\t"
+                 "ds_read_b128 %5, %9 offset:8448\n\t"
+                 "ds_read_b128 %6, %10 offset:8448\n\t"
+                 "ds_read_b128 %7, %11 offset:8448\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3]), "=&v"(st.a[4]), "=&v"(st.a[5]),
+                   "=&v"(st.a[6]), "=&v"(st.a[7])
+                 : "v"(xa0), "v"(xa1), "v"(xa2), "v"(xa3)
+                 : "memory");
 }
 
 template <int BITS>
@@ -205,7 +273,7 @@ struct Cfg {
 };
 
 // ------------------------------------------------------------------ consumer wavefronts
-template <int BITS>
+template <int BITS, int MT>
 struct Consumer {
     typedef Cfg<BITS> C;
     const Sel &d;
@@ -226,7 +294,7 @@ struct Consumer {
     // place n ^ (kb % 16)).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
     // 16 bits: blocks 4 h + c of an even stage, 8 + 4 h + c of an odd one
     uint32_t xq[4];
-    float4_t acc[RT], out[RT];
+    float4_t acc[RT][MT], out[RT][MT];
 
     __device__ __forceinline__ Consumer(const Sel &d_, const Lds &L_, int M_, int tile_row0, int wave_)
         : d(d_), L(L_), M(M_), wave(wave_), lane(threadIdx.x & 63), n(lane & 15), c(lane >> 4),
@@ -252,13 +320,15 @@ struct Consumer {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const int kb = BITS == 4 ? 4 * c + i : BITS == 8 ? 8 * (i >> 1) + 2 * c + (i & 1) : 4 * i + c;
-            xq[i] = (uint32_t)(kb * 256 + ((n ^ (kb & 15)) * 16));
+            xq[i] = (uint32_t)(kb * (256 * MT) + ((n ^ (kb & 15)) * 16));
         }
 #pragma unroll
-        for (int rt = 0; rt < RT; rt++) {
-            acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
-            out[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
-        }
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+                out[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
     }
 
     // Request step q (line q of every row) into ring slot `slot`.  A 4-bit row may end with
@@ -279,44 +349,63 @@ struct Consumer {
         }
     }
 
-    __device__ __forceinline__ void compute(const Stage &st)
+    // One unit (128 k) of a 4-bit stage: half h of the line, x blocks a[mt * AM + i].
+    template <int AM, int H>
+    __device__ __forceinline__ void unit4(const Stage &st, const u32x4 *a)
+    {
+        constexpr int h = H;
+        uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
+        asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
+        const uint32_t z4 = (st.z << 4) & 0xF0F0F0F0u;
+        u32x4 nz[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            const uint32_t by = (uint32_t)(2 * rt + h), sel = 0x04000400u | by | (by << 16);
+            const uint32_t lo = __builtin_amdgcn_perm(0xE4E4E4E4u, st.z, sel); // -(1024 + z) twice
+            const uint32_t hi = __builtin_amdgcn_perm(0xD4D4D4D4u, z4, sel);   // -(  64 + z) twice
+            nz[rt] = u32x4{lo, hi, lo, hi};
+        }
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++) {
+                const uint32_t w = st.w[rt][h][i], w8 = w >> 8;
+                u32x4 b;
+                b.x = (w & 0x000F000Fu) | magic_lo;  // (1024 + q0, 1024 + q4)
+                b.y = (w & 0x00F000F0u) | magic_hi;  // (  64 + q1,   64 + q5)
+                b.z = (w8 & 0x000F000Fu) | magic_lo; // (1024 + q2, 1024 + q6)
+                b.w = (w8 & 0x00F000F0u) | magic_hi; // (  64 + q3,   64 + q7)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    acc[rt][mt] = mfma(a[mt * AM + i], b, acc[rt][mt]);
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    acc[rt][mt] = mfma(a[mt * AM + i], nz[rt], acc[rt][mt]);
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                out[rt][mt] += st.s[rt][h] * acc[rt][mt];
+                acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+    }
+
+    // The stage in `st` (for 4 bits and two batch tiles: its second unit is fetched here, xa as
+    // given to take()).
+    __device__ __forceinline__ void compute(Stage &st, uint32_t xa0, uint32_t xa1, uint32_t xa2, uint32_t xa3)
     {
         if (BITS == 4) {
-            uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
-            asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
-            const uint32_t z4 = (st.z << 4) & 0xF0F0F0F0u;
-#pragma unroll
-            for (int h = 0; h < 2; h++) { // the line's two units
-                u32x4 nz[RT];
-#pragma unroll
-                for (int rt = 0; rt < RT; rt++) {
-                    const uint32_t by = (uint32_t)(2 * rt + h), sel = 0x04000400u | by | (by << 16);
-                    const uint32_t lo = __builtin_amdgcn_perm(0xE4E4E4E4u, st.z, sel); // -(1024 + z) twice
-                    const uint32_t hi = __builtin_amdgcn_perm(0xD4D4D4D4u, z4, sel);   // -(  64 + z) twice
-                    nz[rt] = u32x4{lo, hi, lo, hi};
-                }
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const u32x4 a = st.a[4 * h + i];
-#pragma unroll
-                    for (int rt = 0; rt < RT; rt++) {
-                        const uint32_t w = st.w[rt][h][i], w8 = w >> 8;
-                        u32x4 b;
-                        b.x = (w & 0x000F000Fu) | magic_lo;  // (1024 + q0, 1024 + q4)
-                        b.y = (w & 0x00F000F0u) | magic_hi;  // (  64 + q1,   64 + q5)
-                        b.z = (w8 & 0x000F000Fu) | magic_lo; // (1024 + q2, 1024 + q6)
-                        b.w = (w8 & 0x00F000F0u) | magic_hi; // (  64 + q3,   64 + q7)
-                        acc[rt] = mfma(a, b, acc[rt]);
-                    }
-#pragma unroll
-                    for (int rt = 0; rt < RT; rt++)
-                        acc[rt] = mfma(a, nz[rt], acc[rt]);
-                }
-#pragma unroll
-                for (int rt = 0; rt < RT; rt++) {
-                    out[rt] += st.s[rt][h] * acc[rt];
-                    acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
-                }
+            if (MT == 1) {
+                unit4<0, 0>(st, st.a);
+                unit4<0, 1>(st, st.a + 4);
+            } else {
+                unit4<4, 0>(st, st.a);
+                more_x(xa0, xa1, xa2, xa3, st);
+                unit4<4, 1>(st, st.a);
             }
         } else if (BITS == 8) {
             u32x4 nz[RT];
@@ -330,7 +419,6 @@ struct Consumer {
             for (int h = 0; h < 2; h++)
 #pragma unroll
                 for (int i = 0; i < 2; i++) {
-                    const u32x4 a = st.a[2 * h + i];
 #pragma unroll
                     for (int rt = 0; rt < RT; rt++) {
                         const uint32_t v0 = st.w[rt][h][2 * i], v1 = st.w[rt][h][2 * i + 1];
@@ -339,23 +427,31 @@ struct Consumer {
                         b.y = __builtin_amdgcn_perm(0x64646464u, v0, 0x04030402u);
                         b.z = __builtin_amdgcn_perm(0x64646464u, v1, 0x04010400u);
                         b.w = __builtin_amdgcn_perm(0x64646464u, v1, 0x04030402u);
-                        acc[rt] = mfma(a, b, acc[rt]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++)
+                            acc[rt][mt] = mfma(st.a[mt * 4 + 2 * h + i], b, acc[rt][mt]);
                     }
 #pragma unroll
                     for (int rt = 0; rt < RT; rt++)
-                        acc[rt] = mfma(a, nz[rt], acc[rt]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++)
+                            acc[rt][mt] = mfma(st.a[mt * 4 + 2 * h + i], nz[rt], acc[rt][mt]);
                 }
 #pragma unroll
-            for (int rt = 0; rt < RT; rt++) {
-                out[rt] += st.s[rt][0] * acc[rt];
-                acc[rt] = float4_t{0.f, 0.f, 0.f, 0.f};
-            }
+            for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) {
+                    out[rt][mt] += st.s[rt][0] * acc[rt][mt];
+                    acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+                }
         } else {
 #pragma unroll
             for (int h = 0; h < 2; h++)
 #pragma unroll
                 for (int rt = 0; rt < RT; rt++)
-                    acc[rt] = mfma(st.a[h], st.w[rt][h], acc[rt]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++)
+                        acc[rt][mt] = mfma(st.a[mt * 2 + h], st.w[rt][h], acc[rt][mt]);
         }
     }
 
@@ -363,7 +459,7 @@ struct Consumer {
     template <int XB>
     __device__ __forceinline__ void chunk(int ch, int &fq, int &slot)
     {
-        barrier(); // the loader has written chunk ch; everybody is done with chunk ch - 1
+        barrier(); // the loaders have written chunk ch; everybody is done with chunk ch - 1
         // metadata: buffer of the pair of chunks, the chunk's half of it, the lane's row
         const uint32_t mo = ml * (RT * UP) + (ch & 1) * UC;
         const uint32_t sbase = lds_addr((ch & 2) ? L.ms[1] : L.ms[0]) + mo * 4,
@@ -383,30 +479,30 @@ struct Consumer {
             if (BITS == 4) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    xa[i] = xbase + j * 8192 + xq[i];
+                    xa[i] = xbase + j * (8192 * MT) + xq[i];
             } else if (BITS == 8) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    xa[i] = xbase + j * 4096 + xq[i];
+                    xa[i] = xbase + j * (4096 * MT) + xq[i];
             } else {
-                xa[0] = xbase + (j >> 1) * 4096 + xq[2 * (j & 1)];
-                xa[1] = xbase + (j >> 1) * 4096 + xq[2 * (j & 1) + 1];
+                xa[0] = xbase + (j >> 1) * (4096 * MT) + xq[2 * (j & 1)];
+                xa[1] = xbase + (j >> 1) * (4096 * MT) + xq[2 * (j & 1) + 1];
                 xa[2] = xa[3] = 0;
             }
             Stage st;
             const int pend = __builtin_amdgcn_readfirstlane(fq - 1 - q); // younger stages in flight
             if (NS > 2 && pend >= 2)
-                take<BITS, 2 * SOPS>(wa, wb, sa, za, xa, st);
+                take<BITS, MT, 2 * SOPS>(wa, wb, sa, za, xa, st);
             else if (pend == 1)
-                take<BITS, SOPS>(wa, wb, sa, za, xa, st);
+                take<BITS, MT, SOPS>(wa, wb, sa, za, xa, st);
             else
-                take<BITS, 0>(wa, wb, sa, za, xa, st);
+                take<BITS, MT, 0>(wa, wb, sa, za, xa, st);
             if (fq < T) { // the stage NS steps ahead, into the slot just emptied
                 fetch(fq, slot);
                 fq++;
             }
             __builtin_amdgcn_sched_barrier(0); // keep the requests here: the scheduler sinks them otherwise
-            compute(st);
+            compute(st, xa[0], xa[1], xa[2], xa[3]);
             slot = slot == NS - 1 ? 0 : slot + 1;
         }
     }
@@ -429,29 +525,35 @@ struct Consumer {
 #pragma unroll
         for (int rt = 0; rt < RT; rt++) {
             const int row = row0 + rt * 16 + n;
-            const float4_t v = BITS == 16 ? acc[rt] : out[rt];
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const int m = c * 4 + r;
-                if (m < M && row < d.N)
-                    ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + row] = __builtin_bit_cast(uint16_t, (_Float16)v[r]);
+            for (int mt = 0; mt < MT; mt++) {
+                const float4_t v = BITS == 16 ? acc[rt][mt] : out[rt][mt];
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const int m = mt * 16 + c * 4 + r;
+                    if (m < M && row < d.N)
+                        ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + row] =
+                            __builtin_bit_cast(uint16_t, (_Float16)v[r]);
+                }
             }
         }
         __builtin_amdgcn_s_waitcnt(0);
-        barrier(); // the loader may refill the buffers for the next tile
+        barrier(); // the loaders may refill the buffers for the next tile
     }
 };
 
 // ------------------------------------------------------------------ loader wavefront
 // (One code path for the three bit-widths: instantiated per width, the register allocator sees
 // three sets of staging registers live across the tile loop.)
-template <int LI>
+template <int MT, int LI>
 struct Loader {
     const Sel &d;
     const Lds &L;
     const int M, lane, tile_row0, G, nchunks, BITS;
     static constexpr int li = LI;
-    u32x4 xr[16];        // the chunk's block `lane` of every batch row: one 1 KiB request per row
+    // the chunk's block `lane` of 16 batch rows (with two batch tiles: loader li takes tile li):
+    // one 1 KiB request per row
+    u32x4 xr[16];
     // metadata of a pair of chunks (UP units): scales as 16 bytes = 4 units per lane, two lanes to
     // a row, 32 rows to an instruction; zero points as 8 bytes per lane, one lane to a row
     float4_t sr[TILE_ROWS / 32];
@@ -471,7 +573,7 @@ struct Loader {
         for (int m = 0; m < 16; m++) {
             // batch rows past M feed outputs that are never stored; k past K meets re-read weights
             // (the missing half of a last line): x is zero there
-            const int mm = min(m, M - 1);
+            const int mm = min((MT == 2 ? 16 * LI : 0) + m, M - 1);
             xr[m] = k < d.K ? *(const FQ_GLOBAL u32x4 *)(d.x + (size_t)mm * d.K + k) : u32x4{0u, 0u, 0u, 0u};
         }
     }
@@ -488,7 +590,8 @@ struct Loader {
                 p.z = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x05040100u);
                 p.w = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x07060302u);
             }
-            xb[lane * 16 + (m ^ (lane & 15))] = p; // conflict free for the writer and for the readers
+            // conflict free for the writer and for the readers
+            xb[lane * (16 * MT) + (MT == 2 ? 16 * LI : 0) + (m ^ (lane & 15))] = p;
         }
     }
 
@@ -556,39 +659,40 @@ struct Loader {
     __device__ __forceinline__ void load(int ch)
     {
         load_x(ch);
-        if (BITS != 16 && (ch & 1) == 0)
+        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
             load_meta(ch >> 1);
     }
     __device__ __forceinline__ void store(int ch)
     {
         store_x(ch & 1);
-        if (BITS != 16 && (ch & 1) == 0)
+        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
             store_meta((ch >> 1) & 1);
     }
 
-    // Loader li owns the chunks of parity li (loader 0 with them the metadata, whose pairs start
-    // at even chunks).  Chunk g + 1 is written while the consumers work on chunk g, and the
-    // owner then requests chunk g + 3 at once: two chunk periods ahead of its own deadline,
-    // because a request joins the queue of everything the consumers have in flight on this CU
-    // and takes that long to come back.
+    // One batch tile: loader li owns the chunks of parity li (loader 0 with them the metadata,
+    // whose pairs start at even chunks).  Chunk g + 1 is written while the consumers work on chunk
+    // g, and the owner then requests chunk g + 3 at once.  Two batch tiles: each loader owns one
+    // of them in every chunk and requests chunk g + 2 after writing chunk g + 1.
     __device__ __forceinline__ void run()
     {
-        if (li < nchunks)
-            load(li);
-        if (li == 0) {
+        constexpr int STEP = MT == 1 ? 2 : 1; // distance between the chunks of one loader
+        const int c0 = MT == 1 ? li : 0;
+        if (c0 < nchunks)
+            load(c0);
+        if (c0 == 0) {
             store(0);
             __builtin_amdgcn_sched_barrier(0);
-            if (2 < nchunks)
-                load(2);
+            if (STEP < nchunks)
+                load(STEP);
         }
         for (int g = 0; g < nchunks; g++) {
             __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): this wavefront's LDS writes are done
             barrier();
-            if (g + 1 < nchunks && ((g + 1) & 1) == li) {
+            if (g + 1 < nchunks && (MT == 2 || ((g + 1) & 1) == li)) {
                 store(g + 1);
                 __builtin_amdgcn_sched_barrier(0); // the registers are reused: no load before the last write
-                if (g + 3 < nchunks)
-                    load(g + 3);
+                if (g + 1 + STEP < nchunks)
+                    load(g + 1 + STEP);
             }
         }
         barrier(); // the consumers have stored the tile
@@ -597,7 +701,7 @@ struct Loader {
 
 // The tiles of one workgroup, as seen by its loader (LOADER) or by one of its consumers: the two
 // roles walk the same tiles in separate loops so that neither carries the other's registers.
-template <int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
+template <int MT, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
 __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
                                           int total_tiles, int M, const Lds &L, int wave)
 {
@@ -624,24 +728,25 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
         const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
         if (ROLE > 0) {
             constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
-            Loader<LI>(d, L, M, tile_row0, bits).run();
+            Loader<MT, LI>(d, L, M, tile_row0, bits).run();
         } else {
             if (bits == 4)
-                Consumer<4>(d, L, M, tile_row0, wave).run();
+                Consumer<4, MT>(d, L, M, tile_row0, wave).run();
             else if (bits == 8)
-                Consumer<8>(d, L, M, tile_row0, wave).run();
+                Consumer<8, MT>(d, L, M, tile_row0, wave).run();
             else
-                Consumer<16>(d, L, M, tile_row0, wave).run();
+                Consumer<16, MT>(d, L, M, tile_row0, wave).run();
         }
     }
 }
 
+template <int MT>
 __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev, int count,
                                                                 int total_tiles, int M)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t ring[CONSUMERS * NS * STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t x0[XBYTES], x1[XBYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t x0[16 * MT * KC * 2], x1[16 * MT * KC * 2];
     __shared__ __attribute__((aligned(256))) float ms0[UP * TILE_ROWS], ms1[UP * TILE_ROWS];
     __shared__ __attribute__((aligned(256))) uint8_t mz0[UP * TILE_ROWS], mz1[UP * TILE_ROWS];
     Lds L;
@@ -651,22 +756,25 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
     L.mz[0] = mz0, L.mz[1] = mz1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave == CONSUMERS)
-        run_tiles<1>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave);
     else if (wave > CONSUMERS)
-        run_tiles<2>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave);
     else
-        run_tiles<0>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave);
 }
 
 } // namespace
 
-// A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 16 and
+// A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
 // tiles of 256 rows.
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
                                    int M, int cus, hipStream_t stream)
 {
     // one workgroup per CU (LDS): persistent over the tiles
     const int grid = total_tiles < cus ? total_tiles : cus;
-    decode_stream_kernel<<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
+    if (M <= 16)
+        decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
+    else
+        decode_stream_kernel<2><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
     return hipGetLastError();
 }
