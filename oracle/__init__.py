@@ -41,6 +41,10 @@ def _load():
         lib.orc_double_to_half.argtypes = [ctypes.c_double]
         lib.orc_quantize.restype = ci
         lib.orc_quantize.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+        lib.orc_quantize_sym.restype = ci
+        lib.orc_quantize_sym.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+        lib.orc_fake_quantize.restype = ci
+        lib.orc_fake_quantize.argtypes = [vp, ci, ci, ci, ci, ci, vp]
         lib.orc_dequant.restype = None
         lib.orc_dequant.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp]
         lib.orc_linear.restype = ci
@@ -83,6 +87,37 @@ def quantize(w: np.ndarray, bits: int, group: int = 128):
     if rc != 0:
         raise ValueError("orc_quantize rejected its input (non-finite weight or bad shape)")
     return codes, scales, zeros
+
+
+def quantize_sym(w: np.ndarray, bits: int, group: int = 128):
+    """Symmetric variant stated after Sec. 2.2 Eq. 3 (z = 0, Xmax = -Xmin = max |X|, 2^n - 2
+    levels), written in the layout of quantize(): stored code = q + 2^(n-1), stored zero point
+    = 2^(n-1), so that dequant() and linear() apply unchanged."""
+    w = np.ascontiguousarray(w, dtype=np.float16)
+    N, K = w.shape
+    if bits not in (4, 8) or group <= 0 or K % group:
+        raise ValueError("bad bits/group")
+    codes = np.zeros((N, K * bits // 8), dtype=np.uint8)
+    scales = np.zeros((N, K // group), dtype=np.float32)
+    zeros = np.zeros((N, K // group), dtype=np.uint8)
+    rc = _load().orc_quantize_sym(_p(w), N, K, bits, group, _p(codes), _p(scales), _p(zeros))
+    if rc != 0:
+        raise ValueError("orc_quantize_sym rejected its input (non-finite weight or bad shape)")
+    return codes, scales, zeros
+
+
+def fake_quantize(w: np.ndarray, bits: int, group: int = 128, sym: bool = False) -> np.ndarray:
+    """Quantize and dequantize (Sec. 2.2 Eq. 2 then Eq. 3) at 2 .. 8 bits, rounded to fp16: how the
+    paper simulated its 2- to 4-bit models (Sec. 5.1, Table 1).  fp16 [N][K]."""
+    w = np.ascontiguousarray(w, dtype=np.float16)
+    N, K = w.shape
+    if not 2 <= bits <= 8 or group <= 0 or K % group:
+        raise ValueError("bad bits/group")
+    out = np.zeros((N, K), dtype=np.float16)
+    rc = _load().orc_fake_quantize(_p(w), N, K, bits, group, 1 if sym else 0, _p(out))
+    if rc != 0:
+        raise ValueError("orc_fake_quantize rejected its input (non-finite weight or bad shape)")
+    return out
 
 
 def dequant(codes, scales, zeros, bits: int, group: int = 128) -> np.ndarray:

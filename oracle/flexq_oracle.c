@@ -169,6 +169,142 @@ int orc_quantize(const uint16_t *w, int N, int K, int bits, int group,
     return bad ? -1 : 0;
 }
 
+/*
+ * Symmetric variant, stated after Sec. 2.2 Eq. (3): z = 0, Xmax = -Xmin = max |X|, and the range
+ * Qmax - Qmin = 2^n - 2, i.e. integers -(2^(n-1) - 1) .. 2^(n-1) - 1.  Per group:
+ * s = (2 max|w|) / (2^n - 2), q = clamp(rint(w / s)).  The result is written in the layout of
+ * orc_quantize -- stored code = q + 2^(n-1), stored zero point = 2^(n-1) for every group -- so that
+ * Eq. (3), s * (code - zero), gives s * q and orc_dequant / orc_linear apply unchanged.
+ * An all-zero group takes s = 1.  Binary32, one rounding per operation.
+ */
+static float sym_scale(const uint16_t *wg, int group, int bits, int *bad)
+{
+    float amax = 0.0f;
+    for (int i = 0; i < group; i++) {
+        float v = half_to_float(wg[i]);
+        if (!isfinite(v))
+            *bad |= 1;
+        float a = fabsf(v);
+        if (a > amax) amax = a;
+    }
+    if (amax == 0.0f)
+        return 1.0f;
+    const float levels = (float)((1 << bits) - 2);
+    volatile float range = amax + amax;
+    volatile float sv = range / levels;
+    return sv;
+}
+
+static float sym_code(float v, float s, int bits)
+{
+    const float lim = (float)((1 << (bits - 1)) - 1);
+    volatile float t = v / s;
+    float q = rintf(t);
+    if (q < -lim) q = -lim;
+    if (q > lim) q = lim;
+    return q;
+}
+
+int orc_quantize_sym(const uint16_t *w, int N, int K, int bits, int group,
+                     uint8_t *codes, float *scales, uint8_t *zeros)
+{
+    if ((bits != 4 && bits != 8) || group <= 0 || (group & 1) || K % group != 0)
+        return -1;
+    const int G = K / group;
+    const int offset = 1 << (bits - 1);
+    int bad = 0;
+    if (bits == 4)
+        memset(codes, 0, (size_t)N * K / 2);
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long long n = 0; n < N; n++) {
+        for (int g = 0; g < G; g++) {
+            const uint16_t *wg = w + n * K + (long long)g * group;
+            int b = 0;
+            const float s = sym_scale(wg, group, bits, &b);
+            bad |= b;
+            scales[n * G + g] = s;
+            zeros[n * G + g] = (uint8_t)offset;
+            for (int i = 0; i < group; i++) {
+                int q = (int)sym_code(half_to_float(wg[i]), s, bits) + offset;
+                long long k = (long long)g * group + i;
+                if (bits == 8)
+                    codes[n * K + k] = (uint8_t)q;
+                else
+                    codes[(n * K + k) / 2] |= (uint8_t)((unsigned)q << ((k & 1) ? 4 : 0));
+            }
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * Quantize and dequantize in one go, the way the paper obtained its 2-, 3- and 4-bit results
+ * (Sec. 5.1: those widths were simulated, Table 1): w_hat = half(s * (q - z)) per Eq. (2) and
+ * Eq. (3), bits = 2 .. 8, asymmetric (sym = 0: s, z and q exactly as in orc_quantize) or the
+ * symmetric variant (sym = 1: as in orc_quantize_sym).  w_hat: [N][K] binary16 bit patterns.
+ */
+int orc_fake_quantize(const uint16_t *w, int N, int K, int bits, int group, int sym, uint16_t *w_hat)
+{
+    if (bits < 2 || bits > 8 || group <= 0 || K % group != 0)
+        return -1;
+    const int G = K / group;
+    const float qmax = (float)((1 << bits) - 1);
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (long long n = 0; n < N; n++) {
+        for (int g = 0; g < G; g++) {
+            const uint16_t *wg = w + n * K + (long long)g * group;
+            uint16_t *og = w_hat + n * K + (long long)g * group;
+            if (sym) {
+                int b = 0;
+                const float s = sym_scale(wg, group, bits, &b);
+                bad |= b;
+                for (int i = 0; i < group; i++) {
+                    const int q = (int)sym_code(half_to_float(wg[i]), s, bits); /* an integer code: no -0 */
+                    volatile float d = (float)q * s;
+                    og[i] = double_to_half((double)d);
+                }
+                continue;
+            }
+            float lo = 0.0f, hi = 0.0f; /* range always contains 0 */
+            for (int i = 0; i < group; i++) {
+                float v = half_to_float(wg[i]);
+                if (!isfinite(v))
+                    bad |= 1;
+                if (v < lo) lo = v;
+                if (v > hi) hi = v;
+            }
+            float s, zf;
+            if (hi == lo) {
+                s = 1.0f;
+                zf = 0.0f;
+            } else {
+                volatile float range = hi - lo;
+                volatile float sv = range / qmax;
+                s = sv;
+                volatile float neg = -lo;
+                volatile float zq = neg / s;
+                zf = rintf(zq);
+                if (zf < 0.0f) zf = 0.0f;
+                if (zf > qmax) zf = qmax;
+            }
+            for (int i = 0; i < group; i++) {
+                float v = half_to_float(wg[i]);
+                volatile float t = v / s;
+                volatile float u = t + zf;
+                float q = rintf(u);
+                if (q < 0.0f) q = 0.0f;
+                if (q > qmax) q = qmax;
+                const int code = (int)q; /* what orc_quantize stores: an integer, no -0 */
+                volatile float dq = (float)code - zf;
+                volatile float d = dq * s;
+                og[i] = double_to_half((double)d);
+            }
+        }
+    }
+    return bad ? -1 : 0;
+}
+
 /* ---- Eq. (3): dequantize to float, [N][K] ---- */
 
 void orc_dequant(const uint8_t *codes, const float *scales, const uint8_t *zeros,
