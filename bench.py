@@ -370,6 +370,71 @@ def bench_entropy(args):
                      "traffic": None, "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg}}))
 
 
+def bench_quantize(args):
+    """The quantizers on one 7B-shaped weight (11008 x 4096 fp16): fq_quantize and fq_quantize_sym
+    at 4 and 8 bits (read 2 bytes, write bits / 8 + 5 / 128 bytes per weight) and fq_fake_quantize
+    at 2 bits (read 2, write 2).  A step is the five calls; the roofline object is the 2-bit
+    quantize-dequantize, the others are listed beside it.  HBM bound."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev, N, K = "cuda:0", 11008, 4096
+    w = synth.weight(SEED, "quantize/w", N, K, 0.02, outlier_p=0.001)
+    w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
+    bufs = {}
+    for b in (4, 8):
+        cb, sb, zb = fq.fq_packed_sizes(N, K, b, 128)
+        bufs[b] = (torch.empty(cb, dtype=torch.uint8, device=dev), torch.empty(sb // 4, device=dev),
+                   torch.empty(zb, dtype=torch.uint8, device=dev))
+    w_hat = torch.empty_like(w_dev)
+    calls = [("fq_quantize 4-bit", lambda: fq.fq_quantize(w_dev, N, K, 4, 128, *bufs[4]), 2 + 0.5 + 5 / 128),
+             ("fq_quantize 8-bit", lambda: fq.fq_quantize(w_dev, N, K, 8, 128, *bufs[8]), 2 + 1 + 5 / 128),
+             ("fq_quantize_sym 4-bit", lambda: fq.fq_quantize_sym(w_dev, N, K, 4, 128, *bufs[4]), 2 + 0.5 + 5 / 128),
+             ("fq_quantize_sym 8-bit", lambda: fq.fq_quantize_sym(w_dev, N, K, 8, 128, *bufs[8]), 2 + 1 + 5 / 128),
+             ("fq_fake_quantize 2-bit", lambda: fq.fq_fake_quantize(w_dev, N, K, 2, 128, False, w_hat), 4.0)]
+    stream = torch.cuda.current_stream()
+    per_call = {}
+    for name, fn, bytes_per_weight in calls:
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        per_call[name] = {"ms": ms, "GBps": bytes_per_weight * N * K / (ms * 1e-3) / 1e9}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for _, fn, _ in calls:
+            fn()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fake = per_call["fq_fake_quantize 2-bit"]
+    out = {
+        "metric": "quantizer weights/s (five calls per step)", "value": 5.0 * N * K * args.steps / elapsed,
+        "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "quantizers on one 11008 x 4096 fp16 weight, group 128"},
+        "per_call": per_call,
+        "roofline": {"bound": "hbm", "kernel": "fake_quantize_kernel", "achieved": fake["GBps"],
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": fake["GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "avg_launch_ms": fake["ms"], "algorithmic_bytes_per_launch": 4.0 * N * K}}
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = 1024
+        t0 = time.perf_counter()
+        oracle.fake_quantize(w[:rows], 2)
+        oracle.quantize_sym(w[:rows], 4)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * K / dt, "unit": "weights/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+                               "sample": "fake_quantize (2-bit) and quantize_sym (4-bit) on the first %d rows" % rows}
+    print(json.dumps(out))
+
+
 def bench_flexquant(args):
     """Alg. 1's decode loop on the 7B-shaped stack: every linear starts at INT8; per token the
     plan runs at the current bit-widths, fq_entropy_kl gives the entropy of the token's logits
@@ -448,7 +513,7 @@ def bench_flexquant(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill-w8a8", "entropy", "flexquant"],
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill-w8a8", "entropy", "flexquant", "quantize"],
                     help="decode = the headline decode stack (default); prefill / entropy = the "
                          "prefill-shaped GEMM slice and the batched entropy/KL on their own")
     ap.add_argument("--gpus", type=int, default=1)
@@ -480,6 +545,8 @@ def main():
         return bench_prefill_w8a8(args)
     if args.workload == "entropy":
         return bench_entropy(args)
+    if args.workload == "quantize":
+        return bench_quantize(args)
     if args.workload == "flexquant":
         return bench_flexquant(args)
     bit_choices = tuple(int(b) for b in args.bits.split(","))

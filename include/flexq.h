@@ -4,6 +4,8 @@
  *
  * What the calls compute is defined by the paper:
  *   fq_quantize     asymmetric uniform quantization, Sec. 2.2 Eq. (2)
+ *                   (fq_quantize_sym: the symmetric variant; fq_fake_quantize:
+ *                   quantize-dequantize at 2..8 bits as in Sec. 5.1)
  *   fq_linear       the weight-only quantized linear layer of the decode phase
  *                   (Sec. 4.1), weights dequantized on the fly by Eq. (3), the
  *                   bit-width of every layer chosen per generated token from
@@ -82,6 +84,31 @@ int fq_packed_sizes(int N, int K, int bits, int group,
  */
 int fq_quantize(const void *w_fp16, int N, int K, int bits, int group,
                 void *codes, void *scales, void *zeros, void *stream);
+
+/*
+ * The symmetric variant stated after Sec. 2.2 Eq. (3): z = 0, Xmax = -Xmin = max |w| of the
+ * group, 2^bits - 2 steps.  Per (row, group): s = (2 max|w|) / (2^bits - 2),
+ * q = clamp(round(w / s)) in -(2^(bits-1) - 1) .. 2^(bits-1) - 1, binary32, one rounding per
+ * operation, round-half-to-even; an all-zero group gets s = 1.  Written in the packed layout of
+ * fq_quantize with stored code = q + 2^(bits-1) and stored zero point = 2^(bits-1) in every group,
+ * so that Eq. (3), s * (code - zero), is s * q and fq_layer_attach / fq_linear / fq_plan_* take
+ * the result as they take fq_quantize's.  Arguments, alignment and errors as fq_quantize.
+ */
+int fq_quantize_sym(const void *w_fp16, int N, int K, int bits, int group,
+                    void *codes, void *scales, void *zeros, void *stream);
+
+/*
+ * Quantize and dequantize in one pass, w_hat = fp16(s * (q - z)) with s, z, q of Eq. (2) exactly
+ * as fq_quantize (symmetric = 0) or fq_quantize_sym (symmetric != 0) compute them, at any width
+ * from 2 to 8 bits.  This is how the paper evaluates its 2- to 4-bit models (Sec. 5.1: those
+ * widths are simulated; Table 1); the result is an fp16 weight for fq_layer_attach(layer, 16, ...).
+ *   w_fp16      device, fp16 [N][K], 16-byte aligned   (read)
+ *   w_hat_fp16  device, fp16 [N][K], 16-byte aligned   (written; may be w_fp16 itself)
+ * bits in 2..8; group = FQ_GROUP; K a multiple of group.  Non-finite weights give unspecified
+ * results.
+ */
+int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int symmetric,
+                     void *w_hat_fp16, void *stream);
 
 /*
  * A layer handle: a small host object naming the resident copies of one

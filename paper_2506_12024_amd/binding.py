@@ -23,6 +23,7 @@ EXPORTS = [
     "fq_plan_destroy", "fq_entropy_kl", "fq_sched_state_bytes", "fq_sched_init",
     "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
     "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
+    "fq_quantize_sym", "fq_fake_quantize",
 ]
 
 
@@ -72,6 +73,10 @@ def _load() -> ctypes.CDLL:
     L.fq_entropy_kl_f16.argtypes = [vp, vp, ci, ci, vp, vp, vp]
     L.fq_rank_ascending.restype = ci
     L.fq_rank_ascending.argtypes = [vp, ci, ci, vp, vp]
+    L.fq_quantize_sym.restype = ci
+    L.fq_quantize_sym.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    L.fq_fake_quantize.restype = ci
+    L.fq_fake_quantize.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
     L.fq_quantize_act.restype = ci
     L.fq_quantize_act.argtypes = [vp, ci, ci, vp, vp, vp, vp]
     L.fq_linear_w8a8.restype = ci
@@ -131,6 +136,16 @@ def fq_packed_sizes(N: int, K: int, bits: int, group: int = FQ_GROUP):
 def fq_quantize(w_fp16, N: int, K: int, bits: int, group: int, codes, scales, zeros, stream=None):
     _check(lib.fq_quantize(_ptr(w_fp16), N, K, bits, group, _ptr(codes), _ptr(scales), _ptr(zeros),
                            _stream(stream)))
+
+
+def fq_quantize_sym(w_fp16, N: int, K: int, bits: int, group: int, codes, scales, zeros, stream=None):
+    _check(lib.fq_quantize_sym(_ptr(w_fp16), N, K, bits, group, _ptr(codes), _ptr(scales), _ptr(zeros),
+                               _stream(stream)))
+
+
+def fq_fake_quantize(w_fp16, N: int, K: int, bits: int, group: int, symmetric: bool, w_hat_fp16, stream=None):
+    _check(lib.fq_fake_quantize(_ptr(w_fp16), N, K, bits, group, 1 if symmetric else 0, _ptr(w_hat_fp16),
+                                _stream(stream)))
 
 
 class Layer:

@@ -117,21 +117,51 @@ int fq_packed_sizes(int N, int K, int bits, int group, size_t *codes_bytes, size
     return FQ_OK;
 }
 
-int fq_quantize(const void *w_fp16, int N, int K, int bits, int group, void *codes, void *scales,
-                void *zeros, void *stream)
+static int quantize_any(const char *who, bool symmetric, const void *w_fp16, int N, int K, int bits, int group,
+                        void *codes, void *scales, void *zeros, void *stream)
 {
     if (!w_fp16 || !codes || !scales || !zeros)
-        return fail(FQ_ERR_NULL, "fq_quantize: NULL tensor pointer");
+        return fail(FQ_ERR_NULL, "%s: NULL tensor pointer", who);
     if (bits != 4 && bits != 8)
-        return fail(FQ_ERR_BITS, "fq_quantize: bits must be 4 or 8 (got %d)", bits);
+        return fail(FQ_ERR_BITS, "%s: bits must be 4 or 8 (got %d)", who, bits);
     if (int rc = check_shape(N, K, group))
         return rc;
     if (!aligned16(w_fp16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u))
-        return fail(FQ_ERR_ALIGN, "fq_quantize: w and codes need 16-byte, scales 4-byte alignment");
+        return fail(FQ_ERR_ALIGN, "%s: w and codes need 16-byte, scales 4-byte alignment", who);
     const long long n_groups = (long long)N * (K / group);
-    hipError_t e = fq_launch_quantize(w_fp16, n_groups, bits, codes, scales, zeros, (hipStream_t)stream);
+    hipError_t e = fq_launch_quantize(w_fp16, n_groups, bits, symmetric, codes, scales, zeros, (hipStream_t)stream);
     if (e != hipSuccess)
-        return hip_fail(e, "fq_quantize launch");
+        return hip_fail(e, "quantize launch");
+    return FQ_OK;
+}
+
+int fq_quantize(const void *w_fp16, int N, int K, int bits, int group, void *codes, void *scales,
+                void *zeros, void *stream)
+{
+    return quantize_any("fq_quantize", false, w_fp16, N, K, bits, group, codes, scales, zeros, stream);
+}
+
+int fq_quantize_sym(const void *w_fp16, int N, int K, int bits, int group, void *codes, void *scales,
+                    void *zeros, void *stream)
+{
+    return quantize_any("fq_quantize_sym", true, w_fp16, N, K, bits, group, codes, scales, zeros, stream);
+}
+
+int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int symmetric, void *w_hat_fp16,
+                     void *stream)
+{
+    if (!w_fp16 || !w_hat_fp16)
+        return fail(FQ_ERR_NULL, "fq_fake_quantize: NULL tensor pointer");
+    if (bits < 2 || bits > 8)
+        return fail(FQ_ERR_BITS, "fq_fake_quantize: bits must be 2..8 (got %d)", bits);
+    if (int rc = check_shape(N, K, group))
+        return rc;
+    if (!aligned16(w_fp16) || !aligned16(w_hat_fp16))
+        return fail(FQ_ERR_ALIGN, "fq_fake_quantize: w and w_hat need 16-byte alignment");
+    const long long n_groups = (long long)N * (K / group);
+    hipError_t e = fq_launch_fake_quantize(w_fp16, n_groups, bits, symmetric != 0, w_hat_fp16, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_fake_quantize launch");
     return FQ_OK;
 }
 

@@ -24,8 +24,10 @@ struct FqLinearDesc {
     int pad;
 };
 
-hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, void *codes,
+hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
                               void *scales, void *zeros, hipStream_t stream);
+hipError_t fq_launch_fake_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *w_hat,
+                                   hipStream_t stream);
 
 hipError_t fq_launch_entropy_kl(const float *a, const float *b, int R, int V, float *H, float *KL,
                                 hipStream_t stream);

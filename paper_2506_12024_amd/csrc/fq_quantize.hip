@@ -1,4 +1,5 @@
-// Group-wise asymmetric quantize-and-pack, Sec. 2.2 Eq. (2), for gfx950.
+// Group-wise quantize-and-pack, Sec. 2.2 Eq. (2), for gfx950: the asymmetric form, the symmetric
+// variant stated after Eq. (3), and quantize-dequantize to fp16 at 2..8 bits (Sec. 5.1).
 //
 // One 16-lane segment of a wavefront owns one group of 128 consecutive k of
 // one row: every lane loads 8 halves (one 128-bit load, fully coalesced: a
@@ -34,7 +35,41 @@ __device__ __forceinline__ float seg16_max(float v)
     return v;
 }
 
-template <int BITS>
+// Scale, zero point and code limits of a group from its range (every lane of the segment
+// computes the same).  Asymmetric: the range always contains 0.  Symmetric: max |w| on the last of
+// 2^(bits-1) - 1 levels either side; codes are stored offset by 2^(bits-1), which is also the
+// stored zero point, so that Eq. (3) applies unchanged.
+struct GroupParams {
+    float s, z, qlo, qhi;
+};
+template <bool SYM>
+__device__ __forceinline__ GroupParams group_params(float lo, float hi, int bits)
+{
+#pragma clang fp contract(off)
+    GroupParams p;
+    if (SYM) {
+        const float amax = fmaxf(-lo, hi);
+        const float lim = (float)((1 << (bits - 1)) - 1);
+        p.s = amax == 0.0f ? 1.0f : __fdiv_rn(__fadd_rn(amax, amax), (float)((1 << bits) - 2));
+        p.z = 0.0f;
+        p.qlo = -lim;
+        p.qhi = lim;
+    } else {
+        const float qmax = (float)((1 << bits) - 1);
+        if (hi == lo) { // all-zero group
+            p.s = 1.0f;
+            p.z = 0.0f;
+        } else {
+            p.s = __fdiv_rn(__fsub_rn(hi, lo), qmax);
+            p.z = fminf(fmaxf(rintf(__fdiv_rn(-lo, p.s)), 0.0f), qmax);
+        }
+        p.qlo = 0.0f;
+        p.qhi = qmax;
+    }
+    return p;
+}
+
+template <int BITS, bool SYM>
 __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__ w,
                                                        long long n_groups, // N * K / 128
                                                        uint8_t *__restrict__ codes,
@@ -60,22 +95,15 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
     lo = seg16_min(lo);
     hi = seg16_max(hi);
 
-    const float qmax = (float)((1 << BITS) - 1);
-    float s, z;
-    if (hi == lo) { // all-zero group
-        s = 1.0f;
-        z = 0.0f;
-    } else {
-        s = __fdiv_rn(__fsub_rn(hi, lo), qmax);
-        z = rintf(__fdiv_rn(-lo, s));
-        z = fminf(fmaxf(z, 0.0f), qmax);
-    }
+    const GroupParams p = group_params<SYM>(lo, hi, BITS);
+    const float s = p.s;
+    const float z = SYM ? (float)(1 << (BITS - 1)) : p.z; // what is stored
     uint32_t q[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
-        float t = rintf(__fadd_rn(__fdiv_rn(f[i], s), z));
-        t = fminf(fmaxf(t, 0.0f), qmax);
-        q[i] = (uint32_t)t;
+        float t = rintf(__fadd_rn(__fdiv_rn(f[i], s), p.z));
+        t = fminf(fmaxf(t, p.qlo), p.qhi);
+        q[i] = (uint32_t)(int)(SYM ? t + z : t);
     }
     if (BITS == 4) {
         uint32_t word = 0;
@@ -95,20 +123,77 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
     }
 }
 
+// Eq. (2) then Eq. (3), rounded to fp16: w_hat = half(s * (q - z)).
+template <bool SYM>
+__global__ __launch_bounds__(256) void fake_quantize_kernel(const half8 *__restrict__ w, long long n_groups, int bits,
+                                                            half8 *__restrict__ w_hat)
+{
+#pragma clang fp contract(off)
+    const long long seg = ((long long)blockIdx.x * 256 + threadIdx.x) >> 4;
+    const int sub = threadIdx.x & 15;
+    if (seg >= n_groups)
+        return;
+    const half8 v = w[seg * 16 + sub];
+    float f[8];
+    float lo = 0.0f, hi = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        f[i] = (float)v[i];
+        lo = fminf(lo, f[i]);
+        hi = fmaxf(hi, f[i]);
+    }
+    lo = seg16_min(lo);
+    hi = seg16_max(hi);
+    const GroupParams p = group_params<SYM>(lo, hi, bits);
+    half8 out;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        float t = rintf(__fadd_rn(__fdiv_rn(f[i], p.s), p.z));
+        t = fminf(fmaxf(t, p.qlo), p.qhi);
+        const float code = (float)(int)t; // the stored code is an integer: -0 becomes 0
+        float d = __fmul_rn(__fsub_rn(code, p.z), p.s);
+        // two roundings, binary32 then binary16, as Eq. (3) in binary32 followed by a store to
+        // fp16: kept apart from the conversion, which the compiler otherwise fuses with the
+        // product into one mixed-precision instruction with a single rounding
+        asm volatile("" : "+v"(d));
+        out[i] = (_Float16)d;
+    }
+    w_hat[seg * 16 + sub] = out;
+}
+
 } // namespace
 
-hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, void *codes,
+hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
                               void *scales, void *zeros, hipStream_t stream)
 {
     const long long threads = n_groups * 16;
     const unsigned blocks = (unsigned)((threads + 255) / 256);
     if (blocks == 0)
         return hipSuccess;
-    if (bits == 4)
-        quantize_kernel<4><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, (uint8_t *)codes,
-                                                      (float *)scales, (uint8_t *)zeros);
+    const half8 *wp = (const half8 *)w;
+    uint8_t *cp = (uint8_t *)codes, *zp = (uint8_t *)zeros;
+    float *sp = (float *)scales;
+    if (bits == 4 && !symmetric)
+        quantize_kernel<4, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (bits == 4)
+        quantize_kernel<4, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (!symmetric)
+        quantize_kernel<8, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
     else
-        quantize_kernel<8><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, (uint8_t *)codes,
-                                                      (float *)scales, (uint8_t *)zeros);
+        quantize_kernel<8, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    return hipGetLastError();
+}
+
+hipError_t fq_launch_fake_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *w_hat,
+                                   hipStream_t stream)
+{
+    const long long threads = n_groups * 16;
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (blocks == 0)
+        return hipSuccess;
+    if (symmetric)
+        fake_quantize_kernel<true><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, bits, (half8 *)w_hat);
+    else
+        fake_quantize_kernel<false><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, bits, (half8 *)w_hat);
     return hipGetLastError();
 }

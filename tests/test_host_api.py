@@ -160,3 +160,18 @@ def test_w8a8_validation():
     assert L.fq_linear_w8a8(h, FAKE + 4, FAKE, FAKE, 4, FAKE, None) == B.FQ_ERR_ALIGN
     assert L.fq_linear_w8a8(h, FAKE, FAKE, FAKE, 4, FAKE + 1, None) == B.FQ_ERR_ALIGN
     assert L.fq_layer_destroy(h) == B.FQ_OK
+
+
+def test_sym_and_fake_quantize_validation():
+    L, vp = fq.lib, ctypes.c_void_p
+    ok = vp(FAKE)
+    assert L.fq_quantize_sym(None, 4, 128, 4, 128, ok, ok, ok, None) == B.FQ_ERR_NULL
+    assert L.fq_quantize_sym(ok, 4, 128, 3, 128, ok, ok, ok, None) == B.FQ_ERR_BITS
+    assert L.fq_quantize_sym(ok, 4, 100, 4, 128, ok, ok, ok, None) == B.FQ_ERR_SHAPE
+    assert L.fq_quantize_sym(vp(FAKE + 8), 4, 128, 4, 128, ok, ok, ok, None) == B.FQ_ERR_ALIGN
+    assert L.fq_fake_quantize(ok, 4, 128, 1, 128, 0, ok, None) == B.FQ_ERR_BITS
+    assert L.fq_fake_quantize(ok, 4, 128, 9, 128, 0, ok, None) == B.FQ_ERR_BITS
+    assert L.fq_fake_quantize(ok, 4, 128, 3, 128, 0, None, None) == B.FQ_ERR_NULL
+    assert L.fq_fake_quantize(ok, 4, 128, 3, 64, 0, ok, None) == B.FQ_ERR_SHAPE
+    assert L.fq_fake_quantize(ok, 4, 128, 3, 128, 1, vp(FAKE + 8), None) == B.FQ_ERR_ALIGN
+    assert "fq_fake_quantize" in fq.fq_last_error()
