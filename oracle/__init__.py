@@ -45,6 +45,8 @@ def _load():
         lib.orc_quantize_sym.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
         lib.orc_fake_quantize.restype = ci
         lib.orc_fake_quantize.argtypes = [vp, ci, ci, ci, ci, ci, vp]
+        lib.orc_lm_head_entropy.restype = ci
+        lib.orc_lm_head_entropy.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp]
         lib.orc_dequant.restype = None
         lib.orc_dequant.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp]
         lib.orc_linear.restype = ci
@@ -173,6 +175,23 @@ def entropy_kl(a: np.ndarray, b: np.ndarray | None = None):
     if rc != 0:
         raise ValueError("orc_entropy_kl rejected its arguments")
     return (H, KL) if b is not None else (H, None)
+
+
+def lm_head_entropy(x: np.ndarray, w: np.ndarray):
+    """Output layer + what Alg. 1 takes from its logits: x fp16 [M][K], w fp16 [V][K] ->
+    (logits f64 [M][V], H f64 [M], argmax int32 [M]); entropy as in Sec. 4.2 Eq. 5."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    w = np.ascontiguousarray(w, dtype=np.float16)
+    M, K = x.shape
+    V, K2 = w.shape
+    if K != K2:
+        raise ValueError("x and w disagree on K")
+    logits = np.zeros((M, V), dtype=np.float64)
+    H = np.zeros(M, dtype=np.float64)
+    am = np.zeros(M, dtype=np.int32)
+    if _load().orc_lm_head_entropy(_p(x), _p(w), M, V, K, _p(logits), _p(H), _p(am)) != 0:
+        raise ValueError("orc_lm_head_entropy rejected its input")
+    return logits, H, am
 
 
 def rank_ascending(values: np.ndarray) -> np.ndarray:

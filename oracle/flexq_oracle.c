@@ -38,6 +38,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ---- binary16 <-> binary32/64, written out (no compiler half type) ---- */
@@ -499,6 +500,56 @@ int orc_sched_step(orc_sched *s, float entropy)
 double orc_sched_thre(const orc_sched *s) { return s->thre; }
 double orc_sched_last_mean(const orc_sched *s) { return s->last_mean; }
 int orc_sched_next_event(const orc_sched *s) { return s->next_event; }
+
+/*
+ * The output layer followed by what Alg. 1 takes from its logits in every decode step: the
+ * next token (argmax) and the entropy behind PPLE (Sec. 4.2 Eq. 5; softmax as in Sec. 2.3).
+ * x: [M][K] half bits; w: [V][K] half bits (the fp16 output-layer weight).
+ * logits[m][v] = sum_k x[m][k] * w[v][k] in double (optional output, may be NULL),
+ * H[m] = -sum_v p ln p with p = softmax(logits[m]), argmax[m] = the smallest v that attains the
+ * maximum logit.
+ */
+int orc_lm_head_entropy(const uint16_t *x, const uint16_t *w, int M, int V, int K, double *logits,
+                        double *H, int32_t *argmax)
+{
+    if (M < 0 || V < 1 || K < 1)
+        return -1;
+    for (int m = 0; m < M; m++) {
+        double *row = logits ? logits + (long long)m * V : (double *)malloc(sizeof(double) * (size_t)V);
+        if (!row)
+            return -1;
+#pragma omp parallel for schedule(static)
+        for (long long v = 0; v < V; v++) {
+            double acc = 0.0;
+            for (int k = 0; k < K; k++)
+                acc += (double)half_to_float(x[(long long)m * K + k]) * (double)half_to_float(w[v * K + k]);
+            row[v] = acc;
+        }
+        double mx = -INFINITY;
+        int best = 0;
+        for (int v = 0; v < V; v++)
+            if (row[v] > mx) {
+                mx = row[v];
+                best = v;
+            }
+        double S = 0.0;
+        for (int v = 0; v < V; v++)
+            S += exp(row[v] - mx);
+        const double lse = mx + log(S);
+        double h = 0.0;
+        for (int v = 0; v < V; v++) {
+            double p = exp(row[v] - mx) / S;
+            if (p != 0.0)
+                h -= p * (row[v] - lse);
+        }
+        H[m] = h;
+        if (argmax)
+            argmax[m] = best;
+        if (!logits)
+            free(row);
+    }
+    return 0;
+}
 
 /* ---- Offline replacement order, Sec. 4.3 -------------------------------------------
  *
