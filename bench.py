@@ -435,6 +435,71 @@ def bench_quantize(args):
     print(json.dumps(out))
 
 
+def bench_lm_head(args):
+    """The output layer of a 7B-shaped model (32000 x 4096 fp16) fused with the entropy and argmax
+    of its logits (fq_lm_head_entropy, batch 1), against the same done in two launches through
+    fq_linear (fp16 passthrough) and fq_entropy_kl_f16.  HBM bound: 2 bytes per weight."""
+    import torch
+    import paper_2506_12024_amd as fq
+    dev, V, K, M = "cuda:0", VOCAB, 4096, 1
+    w = synth.weight(SEED, "lm_head/w", V, K, 0.02)
+    x = synth.activations(SEED, "lm_head/x", M, K)
+    w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
+    x_dev = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
+    H = torch.empty(M, device=dev)
+    am = torch.empty(M, dtype=torch.int32, device=dev)
+    layer = fq.Layer(V, K)
+    layer.attach(16, w_dev)
+    y = torch.empty((M, V), dtype=torch.float16, device=dev)
+    H2 = torch.empty(M, device=dev)
+
+    def fused():
+        fq.fq_lm_head_entropy(x_dev, w_dev, M, V, K, None, H, am)
+
+    def separate():
+        fq.fq_linear(layer, 16, x_dev, M, y)
+        fq.fq_entropy_kl_f16(y, None, M, V, H2, None)
+
+    stream = torch.cuda.current_stream()
+    ms = {}
+    for name, fn in (("fused", fused), ("separate", separate)):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms[name] = e0.elapsed_time(e1) / args.steps
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fused()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    alg = 2.0 * V * K
+    achieved = alg / (ms["fused"] * 1e-3) / 1e9
+    out = {
+        "metric": "output layer + entropy + argmax, tokens/s", "value": M * args.steps / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "fp16 output layer 32000 x 4096, batch 1, fused with entropy and argmax"},
+        "two_launches_ms": ms["separate"],
+        "roofline": {"bound": "hbm", "kernel": "lm_head_entropy_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "avg_launch_ms": ms["fused"],
+                     "algorithmic_bytes_per_launch": alg}}
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = 8000
+        t0 = time.perf_counter()
+        oracle.lm_head_entropy(x, w[:rows])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": M * (rows / V) / dt, "unit": "tokens/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+                               "sample": "the first %d of %d vocabulary rows, scaled" % (rows, V)}
+    print(json.dumps(out))
+
+
 def bench_flexquant(args):
     """Alg. 1's decode loop on the 7B-shaped stack: every linear starts at INT8; per token the
     plan runs at the current bit-widths, fq_entropy_kl gives the entropy of the token's logits
@@ -513,7 +578,7 @@ def bench_flexquant(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill-w8a8", "entropy", "flexquant", "quantize"],
+    ap.add_argument("--workload", default="decode", choices=["decode", "prefill", "prefill-w8a8", "entropy", "flexquant", "quantize", "lm-head"],
                     help="decode = the headline decode stack (default); prefill / entropy = the "
                          "prefill-shaped GEMM slice and the batched entropy/KL on their own")
     ap.add_argument("--gpus", type=int, default=1)
@@ -547,6 +612,8 @@ def main():
         return bench_entropy(args)
     if args.workload == "quantize":
         return bench_quantize(args)
+    if args.workload == "lm-head":
+        return bench_lm_head(args)
     if args.workload == "flexquant":
         return bench_flexquant(args)
     bit_choices = tuple(int(b) for b in args.bits.split(","))

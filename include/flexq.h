@@ -59,6 +59,7 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 
 #define FQ_GROUP 128      /* the only group size the kernels are built for */
 #define FQ_MAX_DECODE_M 32 /* rows of x served by the skinny (decode) kernels */
+#define FQ_MAX_LM_HEAD_M 4 /* rows of x served by fq_lm_head_entropy */
 
 /* Message describing the calling thread's most recent error ("" if none). */
 const char *fq_last_error(void);
@@ -223,6 +224,26 @@ int fq_entropy_kl_f16(const void *logits_p, const void *logits_q, int R, int V,
 #define FQ_MAX_RANK_ENTRIES 65536
 #define FQ_MAX_RANK_ROWS 4096
 int fq_rank_ascending(const float *values, int n, int m, int32_t *order, void *stream);
+
+/*
+ * The output layer fused with what Alg. 1 takes from its logits in every decode step: the next
+ * token (argmax) and the entropy behind PPLE (Sec. 4.2 Eq. (5); softmax as in Sec. 2.3).
+ *   logits[m][v] = sum_k x[m][k] * w[v][k]   (fp16 operands, binary32 accumulation)
+ *   H[m] = -sum_v p ln p, p = softmax(logits[m]);  argmax[m] = the smallest v with the largest logit
+ * The logits do not pass through HBM unless asked for.  Two launches on `stream`: the weight
+ * stream with per-workgroup partial results, and a one-workgroup merge.
+ *   x_fp16  device, fp16 [M][K], 16-byte aligned      (read)
+ *   w_fp16  device, fp16 [V][K], 16-byte aligned      (read; the fp16 output-layer weight)
+ *   logits  device, f32 [M][V], or NULL               (written if not NULL)
+ *   H       device, f32 [M]                           (written)
+ *   argmax  device, int32 [M], or NULL                (written if not NULL)
+ * 1 <= M <= FQ_MAX_LM_HEAD_M; K a multiple of 512 with M * K <= 32768; V >= 1.  Two logits that
+ * differ by less than the rounding of a binary32 sum of K products may swap places in argmax.
+ * Uses a static device array for the partial results of its workgroups: calls must not overlap
+ * each other on one device (same-stream order is enough).
+ */
+int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int K,
+                       float *logits, float *H, int32_t *argmax, void *stream);
 
 /*
  * Token-wise precision switching on the device (Sec. 4.4, Alg. 1).  Per generated token:

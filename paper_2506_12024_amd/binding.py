@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libflexq.so")
 
 FQ_GROUP = 128
 FQ_MAX_DECODE_M = 32
+FQ_MAX_LM_HEAD_M = 4
 FQ_OK, FQ_ERR_NULL, FQ_ERR_BITS, FQ_ERR_SHAPE, FQ_ERR_NOT_ATTACHED, FQ_ERR_ALIGN, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
 
@@ -23,7 +24,7 @@ EXPORTS = [
     "fq_plan_destroy", "fq_entropy_kl", "fq_sched_state_bytes", "fq_sched_init",
     "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
     "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
-    "fq_quantize_sym", "fq_fake_quantize",
+    "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy",
 ]
 
 
@@ -77,6 +78,8 @@ def _load() -> ctypes.CDLL:
     L.fq_quantize_sym.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
     L.fq_fake_quantize.restype = ci
     L.fq_fake_quantize.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+    L.fq_lm_head_entropy.restype = ci
+    L.fq_lm_head_entropy.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
     L.fq_quantize_act.restype = ci
     L.fq_quantize_act.argtypes = [vp, ci, ci, vp, vp, vp, vp]
     L.fq_linear_w8a8.restype = ci
@@ -226,6 +229,10 @@ def fq_entropy_kl_f16(logits_p, logits_q, R: int, V: int, entropy_out, kl_out, s
 
 def fq_rank_ascending(values, n: int, m: int, order, stream=None):
     _check(lib.fq_rank_ascending(_ptr(values), n, m, _ptr(order), _stream(stream)))
+
+
+def fq_lm_head_entropy(x, w, M: int, V: int, K: int, logits, H, argmax=None, stream=None):
+    _check(lib.fq_lm_head_entropy(_ptr(x), _ptr(w), M, V, K, _ptr(logits), _ptr(H), _ptr(argmax), _stream(stream)))
 
 
 def fq_quantize_act(x, M: int, K: int, xq, sx, xsum, stream=None):

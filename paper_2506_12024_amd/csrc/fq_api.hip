@@ -165,6 +165,26 @@ int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int 
     return FQ_OK;
 }
 
+int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int K, float *logits, float *H,
+                       int32_t *argmax, void *stream)
+{
+    if (M < 1 || M > FQ_MAX_LM_HEAD_M)
+        return fail(FQ_ERR_SHAPE, "fq_lm_head_entropy: M must be 1..%d (got %d)", FQ_MAX_LM_HEAD_M, M);
+    if (V < 1 || K < 512 || K % 512 != 0 || (long long)M * K > 32768)
+        return fail(FQ_ERR_SHAPE,
+                    "fq_lm_head_entropy: need V >= 1, K a positive multiple of 512 and M * K <= 32768 (got V=%d K=%d M=%d)",
+                    V, K, M);
+    if (!x_fp16 || !w_fp16 || !H)
+        return fail(FQ_ERR_NULL, "fq_lm_head_entropy: NULL argument");
+    if (!aligned16(x_fp16) || !aligned16(w_fp16) || (reinterpret_cast<uintptr_t>(H) & 3u) ||
+        (reinterpret_cast<uintptr_t>(logits) & 3u) || (reinterpret_cast<uintptr_t>(argmax) & 3u))
+        return fail(FQ_ERR_ALIGN, "fq_lm_head_entropy: x and w need 16-byte, the outputs 4-byte alignment");
+    hipError_t e = fq_launch_lm_head_entropy(x_fp16, w_fp16, M, V, K, logits, H, argmax, (hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_lm_head_entropy launch");
+    return FQ_OK;
+}
+
 int fq_layer_create(fq_layer **out, int N, int K, int group)
 {
     if (!out)

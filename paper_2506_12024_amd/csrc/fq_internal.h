@@ -85,4 +85,8 @@ hipError_t fq_launch_quantize_act(const void *x, int M, int K, void *xq, float *
 hipError_t fq_launch_w8a8(const FqLinearDesc &d, const void *xq, const float *sx, const int32_t *xsum,
                           int M, hipStream_t stream);
 
+// Output layer (fp16 weight [V][K], 1 <= M <= 4 rows of x) fused with entropy and argmax of its logits.
+hipError_t fq_launch_lm_head_entropy(const void *x, const void *w, int M, int V, int K, float *logits, float *H,
+                                     int32_t *argmax, hipStream_t stream);
+
 #endif

@@ -175,3 +175,17 @@ def test_sym_and_fake_quantize_validation():
     assert L.fq_fake_quantize(ok, 4, 128, 3, 64, 0, ok, None) == B.FQ_ERR_SHAPE
     assert L.fq_fake_quantize(ok, 4, 128, 3, 128, 1, vp(FAKE + 8), None) == B.FQ_ERR_ALIGN
     assert "fq_fake_quantize" in fq.fq_last_error()
+
+
+def test_lm_head_entropy_validation():
+    L, vp = fq.lib, ctypes.c_void_p
+    ok = vp(FAKE)
+    assert L.fq_lm_head_entropy(ok, ok, 0, 100, 512, None, ok, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_lm_head_entropy(ok, ok, 5, 100, 512, None, ok, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_lm_head_entropy(ok, ok, 1, 100, 500, None, ok, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_lm_head_entropy(ok, ok, 4, 100, 16384, None, ok, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_lm_head_entropy(ok, ok, 1, 0, 512, None, ok, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_lm_head_entropy(ok, None, 1, 100, 512, None, ok, None, None) == B.FQ_ERR_NULL
+    assert L.fq_lm_head_entropy(ok, ok, 1, 100, 512, None, None, None, None) == B.FQ_ERR_NULL
+    assert L.fq_lm_head_entropy(vp(FAKE + 8), ok, 1, 100, 512, None, ok, None, None) == B.FQ_ERR_ALIGN
+    assert "fq_lm_head_entropy" in fq.fq_last_error()
