@@ -350,6 +350,9 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
                         layers[i]->K, MAX_DECODE_K);
         if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2])
             return fail(FQ_ERR_NOT_ATTACHED, "fq_plan_create: entry %d has no copy attached", i);
+        if ((long long)M * layers[i]->N >= (1LL << 30)) // the kernels address y with 32-bit byte offsets
+            return fail(FQ_ERR_SHAPE, "fq_plan_create: entry %d: M * N = %lld is 2^30 or more", i,
+                        (long long)M * layers[i]->N);
         fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
         table[(size_t)i].tile_begin = (int)tiles;
         tiles += (layers[i]->N + rows - 1) / rows;

@@ -20,8 +20,13 @@ KS = [128, 384, 640, 1152, 256]
 MIN_ROWS = 1024 * 256  # what the dispatcher asks for before it uses 256-row tiles
 
 
-def _build(M, tag, weight_fn):
-    shapes, rows, i = [], 0, 0
+# rows longer than one block of scales (32 units): two and three whole blocks, a block and one
+# unit, one and a half, and a chunk count that is odd (the last pair of chunks is a single one)
+LONG = [(600, 8192), (300, 12288), (520, 4224), (700, 6144), (280, 4608)]
+
+
+def _build(M, tag, weight_fn, extra=()):
+    shapes, rows, i = list(extra), sum(n for n, _ in extra), 0
     while rows < MIN_ROWS + 256:
         shapes.append((NS[i % 5], KS[(i + i // 5) % 5]))
         rows += shapes[-1][0]
@@ -62,6 +67,26 @@ def test_streaming_plan_matches_oracle(M, every):
                 c, s, z = (t.cpu().numpy() for t in packed[b])
                 y_ref = oracle.linear(xs_np[i], c, s, z, b)
             assert rel_err(y, y_ref) <= TOL_Y, (M, i, b, shapes[i])
+
+
+@pytest.mark.parametrize("M", [16, 27])
+def test_streaming_plan_long_rows(M):
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(
+        M, "par/stream/long", lambda i, N, K: synth.weight(0, "par/stream/long/w%d" % i, N, K, 0.02, outlier_p=0.001),
+        extra=LONG)
+    for shift in (0, 1, 2):
+        pattern = [(4, 8, 16)[(i + shift) % 3] for i in range(len(layers))]
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        for i in list(range(len(LONG))) + [len(LONG) + 3 * shift, len(layers) - 1 - shift]:
+            b = pattern[i]
+            w, packed = packs[i]
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(ys[i].cpu().numpy(), y_ref) <= TOL_Y, (M, i, b, shapes[i])
 
 
 @pytest.mark.parametrize("M", [16, 32])
