@@ -34,8 +34,11 @@
 // them with ordinary loads -- their own vmcnt, nobody else waits.  Two fetch x in chunks of
 // 512 k, each every other chunk, requested two chunk periods before they are due: 16-byte
 // blocks of 8 halves, one request of 1 KiB per batch row and chunk, stored [k block][batch
-// row] with the rows of k block kb XOR-ed by kb % 16 (conflict free for the writer, whose
-// lanes are k blocks, and for the readers, whose lanes are batch rows), zero past K, for the
+// row] with the rows of k block kb XOR-ed by kb % 8 + 8 (kb / 32) -- conflict free for the
+// writer, whose lanes are k blocks (a 128-bit LDS write goes eight lanes at a time), and for the
+// readers, whose lanes are batch rows (a 128-bit read pairs eight lanes of the lower half of
+// the wavefront with eight of the upper: measured, batch rows 0 .. 7 and 8 .. 15 must stay in
+// different halves of the 256 bytes whatever the k block) -- zero past K, for the
 // 4-bit path permuted inside the block to the order the unpacking produces (x0 x4 x1 x5 x2 x6
 // x3 x7).  Two fetch scales and zero points, half the tile's rows each, 32 units (4096 k) of a
 // row at a time -- a whole line of scales where rows start on one -- keep them in registers
@@ -113,7 +116,7 @@ struct Sel {
 // The workgroup's LDS.  x and metadata buffers come in pairs (chunk parity).
 struct Lds {
     uint8_t *ring;    // [CONSUMERS][NS][STAGE_BYTES]
-    uint8_t *x[2];    // [KC / 8][16 * MT] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 16)
+    uint8_t *x[2];    // [KC / 8][16 * MT] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 8 + 8 (kb / 32))
     float *ms[2];     // [CONSUMERS][16 rows][RT][UP] scales of a pair of chunks
     uint8_t *mz[2];   // same order, zero points
 };
@@ -485,8 +488,8 @@ struct Consumer {
     const int lane, n, c;
     uint32_t wa0, wb0; // LDS addresses for take(): the lane's pieces c and c + 4 in slot 0
     uint32_t ml;       // wave * 16 + n: the lane's place in the metadata of a pair of chunks
-    // byte offsets of the lane's x blocks inside a stage's blocks (block kb holds batch row n at
-    // place n ^ (kb % 16)).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
+    // byte offsets of the lane's x blocks inside a stage's blocks (block kb of the chunk holds
+    // batch row n at place n ^ (kb % 8 + 8 (kb / 32))).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
     // 16 bits: blocks 4 h + c of an even stage, 8 + 4 h + c of an odd one
     uint32_t xq[4];
     float4_t acc[RT][MT], out[RT][MT];
@@ -500,7 +503,7 @@ struct Consumer {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             const int kb = BITS == 4 ? 4 * c + i : BITS == 8 ? 8 * (i >> 1) + 2 * c + (i & 1) : 4 * i + c;
-            xq[i] = (uint32_t)(kb * (256 * MT) + ((n ^ (kb & 15)) * 16));
+            xq[i] = (uint32_t)(kb * (256 * MT) + ((n ^ (kb & 7)) * 16));
         }
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
@@ -636,17 +639,18 @@ struct Consumer {
             const uint32_t wa = wa0 + S.rslot * STAGE_BYTES, wb = wb0 + S.rslot * STAGE_BYTES, sa = sbase + unit * 4,
                            za = zbase + unit;
             uint32_t xa[4];
+            // (k blocks 32 .. 63 of the chunk keep their batch rows in the other half of the places)
             if (BITS == 4) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    xa[i] = xbase + j * (8192 * MT) + xq[i];
+                    xa[i] = xbase + j * (8192 * MT) + (xq[i] ^ (j ? 128u : 0u));
             } else if (BITS == 8) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
-                    xa[i] = xbase + j * (4096 * MT) + xq[i];
+                    xa[i] = xbase + j * (4096 * MT) + (xq[i] ^ ((j >> 1) ? 128u : 0u));
             } else {
-                xa[0] = xbase + (j >> 1) * (4096 * MT) + xq[2 * (j & 1)];
-                xa[1] = xbase + (j >> 1) * (4096 * MT) + xq[2 * (j & 1) + 1];
+                xa[0] = xbase + (j >> 1) * (4096 * MT) + (xq[2 * (j & 1)] ^ ((j >> 2) ? 128u : 0u));
+                xa[1] = xbase + (j >> 1) * (4096 * MT) + (xq[2 * (j & 1) + 1] ^ ((j >> 2) ? 128u : 0u));
                 xa[2] = xa[3] = 0;
             }
             Stage st;
@@ -760,7 +764,7 @@ struct Loader {
                 p.w = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x07060302u);
             }
             // conflict free for the writer and for the readers
-            xb[lane * (16 * MT) + (MT == 2 ? 16 * LI : 0) + (m ^ (lane & 15))] = p;
+            xb[lane * (16 * MT) + (MT == 2 ? 16 * LI : 0) + (m ^ ((lane & 7) | ((lane >> 2) & 8)))] = p;
         }
     }
 
