@@ -36,9 +36,9 @@
 // blocks of 8 halves, one request of 1 KiB per batch row and chunk, stored [k block][batch
 // row] with the rows of k block kb XOR-ed by kb % 8 + 8 (kb / 32) -- conflict free for the
 // writer, whose lanes are k blocks (a 128-bit LDS write goes eight lanes at a time), and for the
-// readers, whose lanes are batch rows (a 128-bit read pairs eight lanes of the lower half of
-// the wavefront with eight of the upper: measured, batch rows 0 .. 7 and 8 .. 15 must stay in
-// different halves of the 256 bytes whatever the k block) -- zero past K, for the
+// readers, whose lanes are batch rows (measured: a 128-bit read runs at full rate only if lanes
+// 0 .. 7 and 8 .. 15 of every group of 16 lanes use different halves of the 256 bytes and the
+// same ones in all four groups, i.e. whatever the k block) -- zero past K, for the
 // 4-bit path permuted inside the block to the order the unpacking produces (x0 x4 x1 x5 x2 x6
 // x3 x7).  Two fetch scales and zero points, half the tile's rows each, 32 units (4096 k) of a
 // row at a time -- a whole line of scales where rows start on one -- keep them in registers
