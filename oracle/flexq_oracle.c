@@ -101,29 +101,44 @@ uint16_t orc_double_to_half(double d) { return double_to_half(d); }
 
 /* ---- Eq. (2): quantize one matrix, group-wise along the input dimension ---- */
 
+/* Packed codes: 8 bits one per byte; 4 bits two per byte, the even k in the low nibble; 2 bits
+ * four per byte, k % 4 = 0 in bits 0..1 up to k % 4 = 3 in bits 6..7.  Rows follow each other. */
 static int code_of(const uint8_t *codes, int bits, long long row_elems, long long n, long long k)
 {
     if (bits == 8)
         return codes[n * row_elems + k];
+    if (bits == 2)
+        return (codes[(n * row_elems + k) / 4] >> (2 * (k & 3))) & 3;
     uint8_t byte = codes[(n * row_elems + k) / 2];
     return (k & 1) ? (byte >> 4) : (byte & 0xF);
+}
+
+static void put_code(uint8_t *codes, int bits, long long row_elems, long long n, long long k, unsigned q)
+{
+    if (bits == 8)
+        codes[n * row_elems + k] = (uint8_t)q;
+    else if (bits == 2)
+        codes[(n * row_elems + k) / 4] |= (uint8_t)(q << (2 * (k & 3)));
+    else
+        codes[(n * row_elems + k) / 2] |= (uint8_t)(q << ((k & 1) ? 4 : 0));
 }
 
 /*
  * w: [N][K] binary16 bit patterns.  codes: N*K*bits/8 bytes.  scales: [N][K/group]
  * float.  zeros: [N][K/group] bytes.  Returns 0, or -1 on a bad argument
- * (bits not 4 or 8, K not a multiple of group, odd group) or a non-finite weight.
+ * (bits not 2, 4 or 8, K not a multiple of group, an odd group, at 2 bits a group that is not a
+ * multiple of 4) or a non-finite weight.
  */
 int orc_quantize(const uint16_t *w, int N, int K, int bits, int group,
                  uint8_t *codes, float *scales, uint8_t *zeros)
 {
-    if ((bits != 4 && bits != 8) || group <= 0 || (group & 1) || K % group != 0)
+    if ((bits != 2 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) || K % group != 0)
         return -1;
     const int G = K / group;
     const float qmax = (float)((1 << bits) - 1);
     int bad = 0;
-    if (bits == 4)
-        memset(codes, 0, (size_t)N * K / 2);
+    if (bits != 8)
+        memset(codes, 0, (size_t)N * K * bits / 8);
 #pragma omp parallel for schedule(static) reduction(| : bad)
     for (long long n = 0; n < N; n++) {
         for (int g = 0; g < G; g++) {
@@ -159,11 +174,7 @@ int orc_quantize(const uint16_t *w, int N, int K, int bits, int group,
                 float q = rintf(u);
                 if (q < 0.0f) q = 0.0f;
                 if (q > qmax) q = qmax;
-                long long k = (long long)g * group + i;
-                if (bits == 8)
-                    codes[n * K + k] = (uint8_t)q;
-                else
-                    codes[(n * K + k) / 2] |= (uint8_t)((unsigned)q << ((k & 1) ? 4 : 0));
+                put_code(codes, bits, K, n, (long long)g * group + i, (unsigned)q);
             }
         }
     }
@@ -209,13 +220,13 @@ static float sym_code(float v, float s, int bits)
 int orc_quantize_sym(const uint16_t *w, int N, int K, int bits, int group,
                      uint8_t *codes, float *scales, uint8_t *zeros)
 {
-    if ((bits != 4 && bits != 8) || group <= 0 || (group & 1) || K % group != 0)
+    if ((bits != 2 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) || K % group != 0)
         return -1;
     const int G = K / group;
     const int offset = 1 << (bits - 1);
     int bad = 0;
-    if (bits == 4)
-        memset(codes, 0, (size_t)N * K / 2);
+    if (bits != 8)
+        memset(codes, 0, (size_t)N * K * bits / 8);
 #pragma omp parallel for schedule(static) reduction(| : bad)
     for (long long n = 0; n < N; n++) {
         for (int g = 0; g < G; g++) {
@@ -227,11 +238,7 @@ int orc_quantize_sym(const uint16_t *w, int N, int K, int bits, int group,
             zeros[n * G + g] = (uint8_t)offset;
             for (int i = 0; i < group; i++) {
                 int q = (int)sym_code(half_to_float(wg[i]), s, bits) + offset;
-                long long k = (long long)g * group + i;
-                if (bits == 8)
-                    codes[n * K + k] = (uint8_t)q;
-                else
-                    codes[(n * K + k) / 2] |= (uint8_t)((unsigned)q << ((k & 1) ? 4 : 0));
+                put_code(codes, bits, K, n, (long long)g * group + i, (unsigned)q);
             }
         }
     }
@@ -323,7 +330,7 @@ void orc_dequant(const uint8_t *codes, const float *scales, const uint8_t *zeros
 }
 
 /*
- * Weight-only quantized linear.  x: [M][K] half bits.  bits 4/8: codes, scales,
+ * Weight-only quantized linear.  x: [M][K] half bits.  bits 2/4/8: codes, scales,
  * zeros as written by orc_quantize; bits 16: `codes` holds [N][K] half weights,
  * scales/zeros unused.  Rows row0 .. row0+rows-1 of the output are computed
  * (rows = N, row0 = 0 for all); y: [M][rows] half bits, y[m][n-row0].
@@ -334,7 +341,7 @@ int orc_linear(const uint16_t *x, int M, const uint8_t *codes, const float *scal
                const uint8_t *zeros, int N, int K, int bits, int group,
                int row0, int rows, uint16_t *y)
 {
-    if (bits != 4 && bits != 8 && bits != 16)
+    if (bits != 2 && bits != 4 && bits != 8 && bits != 16)
         return -1;
     if (bits != 16 && (group <= 0 || K % group != 0))
         return -1;
