@@ -30,6 +30,9 @@
  * kernels stream directly -- a switch of bit-width never repacks anything):
  *   codes, bits = 8 : u8  [N][K]      byte k of row n is the code of W[n][k]
  *   codes, bits = 4 : u8  [N][K/2]    byte j of row n = code(2j) | code(2j+1) << 4
+ *   codes, bits = 2 : u8  [N][K/4]    byte j of row n = code(4j) | code(4j+1) << 2 |
+ *                                     code(4j+2) << 4 | code(4j+3) << 6
+ *                                     (Table 1's lowest width; served at M = 1 only)
  *   scales          : f32 [N][K/group]
  *   zeros           : u8  [N][K/group]
  *   bits = 16       : the fp16 weights W[N][K] themselves, no scales/zeros
@@ -65,7 +68,7 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 const char *fq_last_error(void);
 
 /*
- * Bytes of the three packed buffers for an N x K weight at `bits` (4 or 8).
+ * Bytes of the three packed buffers for an N x K weight at `bits` (2, 4 or 8).
  * Any of the three outputs may be NULL.  Host-only; launches nothing.
  */
 int fq_packed_sizes(int N, int K, int bits, int group,
@@ -80,7 +83,7 @@ int fq_packed_sizes(int N, int K, int bits, int group,
  *   codes   device, fq_packed_sizes bytes, 16-byte aligned (written)
  *   scales  device, f32 [N][K/group]                   (written)
  *   zeros   device, u8  [N][K/group]                   (written)
- * bits in {4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
+ * bits in {2, 4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
  * Non-finite weights give unspecified codes.
  */
 int fq_quantize(const void *w_fp16, int N, int K, int bits, int group,
@@ -114,7 +117,7 @@ int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int 
 /*
  * A layer handle: a small host object naming the resident copies of one
  * linear's weight.  fq_layer_attach records (does not copy) the buffers for one
- * bit-width; any subset of {4, 8, 16} may be attached, each at most once per
+ * bit-width; any subset of {2, 4, 8, 16} may be attached, each at most once per
  * value (attaching again replaces the pointers).  For bits = 16 pass the fp16
  * weights as `codes` and NULL scales/zeros.  Buffers must be 16-byte aligned.
  * Launches nothing.
@@ -128,7 +131,8 @@ int fq_layer_destroy(fq_layer *layer);
  * Decode-phase linear (Sec. 4.1, Eq. (3)):
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
- * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.
+ * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 2 is
+ * served at M = 1 (token-by-token decoding) only: FQ_ERR_BITS otherwise.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)
  * 1 <= M <= FQ_MAX_DECODE_M selects the memory-bound skinny kernels; larger M
@@ -148,9 +152,10 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *   workspace  device memory of fq_plan_workspace_bytes(count) bytes, 256-byte
  *              aligned, owned by the caller, must outlive the plan; the
  *              descriptor table is copied into it on `stream` by fq_plan_create
- *   bits_dev   device, int32 [count], each 4, 8 or 16 and attached to its layer;
+ *   bits_dev   device, int32 [count], each 2, 4, 8 or 16 and attached to its layer;
  *              an entry whose value is anything else is skipped by the kernel
- *              and its y is left untouched
+ *              and its y is left untouched.  Plans with M > 1 do not take layers
+ *              that have a 2-bit copy attached (FQ_ERR_BITS from fq_plan_create)
  */
 size_t fq_plan_workspace_bytes(int count);
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers,

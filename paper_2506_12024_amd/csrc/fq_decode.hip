@@ -100,12 +100,15 @@ __device__ __forceinline__ float wave_sum_lane63(float v)
 // After the blocks come the per-slice sums of x.
 //
 //   bits  codes/lane/slice  blocks/lane  block position
+//    2        64               8         ((b >> 9) * 8 + (b & 7)) * 64 + ((b >> 3) & 63), pairs of blocks interleaved
 //    4        32               4         ((b >> 8) * 4 + (b & 3)) * 64 + ((b >> 2) & 63)
 //    8        16               2         ((b >> 7) * 2 + (b & 1)) * 64 + ((b >> 1) & 63)
 //   16         8               1         b
 template <int BITS>
 __device__ __forceinline__ int block_pos(int b)
 {
+    if (BITS == 2)
+        return ((b >> 9) * 8 + (b & 7)) * 64 + ((b >> 3) & 63);
     if (BITS == 4)
         return ((b >> 8) * 4 + (b & 3)) * 64 + ((b >> 2) & 63);
     if (BITS == 8)
@@ -114,7 +117,7 @@ __device__ __forceinline__ int block_pos(int b)
 }
 
 // k covered by one wavefront slice: 64 lanes x 16 bytes of codes
-__device__ __forceinline__ int slice_span(int bits) { return bits == 4 ? 2048 : (bits == 8 ? 1024 : 512); }
+__device__ __forceinline__ int slice_span(int bits) { return bits == 2 ? 4096 : bits == 4 ? 2048 : (bits == 8 ? 1024 : 512); }
 
 __device__ __forceinline__ int padded_k(int K, int bits)
 {
@@ -122,9 +125,61 @@ __device__ __forceinline__ int padded_k(int K, int bits)
     return (K + span - 1) / span * span;
 }
 
+// 2 bits.  A 32-bit word of codes holds 16 consecutive k: code i in bits 2 i .. 2 i + 1.  The
+// unpacking pairs code i of the low half-word with code 8 + i of the high one, so the two x blocks
+// of those 16 k, A = x[0..7] and B = x[8..15], are stored interleaved: (A0 B0 A1 B1 A2 B2 A3 B3),
+// (A4 B4 .. A7 B7).  A code keeps its bit position, which fixes its offset: 1024 / 256 / 64 / 16
+// for i % 4 = 0 / 1 / 2 / 3.  A thread stages one such pair of blocks; the four threads of a lane's
+// slice (64 k) add up its two sums.
+__device__ __forceinline__ void stage_x2(const uint16_t *x, int K, uint4 *lds)
+{
+    const int Kp = padded_k(K, 2);
+    const int npair = Kp >> 4; // a multiple of 256: every thread makes the same number of trips
+    float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3)); // per lane slice: (sum off(k) x, sum x)
+    for (int pb = threadIdx.x; pb < npair; pb += WG_THREADS) {
+        uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
+        if (pb * 16 < K) { // K is a multiple of 128: both blocks or neither
+            va = load16_global(x + (size_t)pb * 16);
+            vb = load16_global(x + (size_t)pb * 16 + 8);
+        }
+        float p[4] = {0.f, 0.f, 0.f, 0.f}; // sums of the x whose code sits at position i % 4
+        const uint32_t w[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const half2_t h = __builtin_bit_cast(half2_t, w[i]); // halves 2 i, 2 i + 1 of their block
+            p[(2 * i) & 3] += (float)h[0];
+            p[(2 * i + 1) & 3] += (float)h[1];
+        }
+        uint4 o0, o1;
+        o0.x = __builtin_amdgcn_perm(vb.x, va.x, 0x05040100u); // (A0, B0)
+        o0.y = __builtin_amdgcn_perm(vb.x, va.x, 0x07060302u); // (A1, B1)
+        o0.z = __builtin_amdgcn_perm(vb.y, va.y, 0x05040100u); // (A2, B2)
+        o0.w = __builtin_amdgcn_perm(vb.y, va.y, 0x07060302u); // (A3, B3)
+        o1.x = __builtin_amdgcn_perm(vb.z, va.z, 0x05040100u); // (A4, B4)
+        o1.y = __builtin_amdgcn_perm(vb.z, va.z, 0x07060302u);
+        o1.z = __builtin_amdgcn_perm(vb.w, va.w, 0x05040100u);
+        o1.w = __builtin_amdgcn_perm(vb.w, va.w, 0x07060302u); // (A7, B7)
+        lds[block_pos<2>(2 * pb)] = o0;
+        lds[block_pos<2>(2 * pb + 1)] = o1;
+        float c = 1024.0f * p[0] + 256.0f * p[1] + 64.0f * p[2] + 16.0f * p[3];
+        float t = (p[0] + p[1]) + (p[2] + p[3]);
+        // slice = 4 pairs = 4 consecutive threads
+        c += dpp_take<0xB1, 0xF>(c);
+        t += dpp_take<0xB1, 0xF>(t);
+        c += dpp_take<0x4E, 0xF>(c);
+        t += dpp_take<0x4E, 0xF>(t);
+        if ((pb & 3) == 0)
+            sums[pb >> 2] = make_float2(c, t);
+    }
+}
+
 template <int BITS>
 __device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
 {
+    if (BITS == 2) {
+        stage_x2(x, K, lds);
+        return;
+    }
     const int Kp = padded_k(K, BITS);
     const int nblk = Kp >> 3;
     float *sums = reinterpret_cast<float *>(lds + nblk); // [slices][2] for 4-bit, [slices] for 8-bit
@@ -204,10 +259,10 @@ __device__ __forceinline__ void issue(const Sel &d, int row0, int j, Loaded &L)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t K = (uint32_t)d.K, G = K >> 7;
-    constexpr int CODES = BITS == 4 ? 32 : (BITS == 8 ? 16 : 8); // per lane per slice
+    constexpr int CODES = 128 / BITS; // per lane per slice: 16 bytes
     const uint32_t k0 = min((uint32_t)(j * 64 + lane) * CODES, K - CODES);
-    const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
-    const uint32_t byte0 = BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
+    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t byte0 = BITS == 2 ? (k0 >> 2) : BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
     const uint32_t g = k0 >> 7;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
@@ -229,7 +284,42 @@ __device__ __forceinline__ void compute(int K, int j, const Loaded &L, const uin
                                         float (&acc)[ROWS_PER_WAVE])
 {
     const int lane = threadIdx.x & 63;
-    if (BITS == 4) {
+    if (BITS == 2) {
+        const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 2) >> 3));
+        // exponent patterns under which a 2-bit field at bits 0, 2, 4, 6 of a half reads as
+        // 1024 + q, 256 + q, 64 + q, 16 + q (kept in VGPRs as for 4 bits)
+        uint32_t m0 = 0x64006400u, m1 = 0x5C005C00u, m2 = 0x54005400u, m3 = 0x4C004C00u;
+        asm volatile("" : "+v"(m0), "+v"(m1), "+v"(m2), "+v"(m3));
+        const float2 cs = sums[j * 64 + lane]; // (sum off(k) x, sum x) over the lane's 64 k
+        float a[ROWS_PER_WAVE] = {0.f, 0.f, 0.f, 0.f};
+        // two rounds of two code words each: the x blocks of a round are all that is held at once
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            uint4 xb[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                xb[i] = lds[(j * 8 + 4 * h + i) * 64 + lane];
+#pragma unroll
+            for (int r = 0; r < ROWS_PER_WAVE; r++) {
+                const uint32_t ww[2] = {h ? L.w[r].z : L.w[r].x, h ? L.w[r].w : L.w[r].y};
+#pragma unroll
+                for (int i = 0; i < 2; i++) {
+                    const uint32_t v = ww[i], v8 = v >> 8;
+                    a[r] = dot2((v & 0x00030003u) | m0, xb[2 * i].x, a[r]);      // codes 0, 8
+                    a[r] = dot2((v & 0x000C000Cu) | m1, xb[2 * i].y, a[r]);      // codes 1, 9
+                    a[r] = dot2((v & 0x00300030u) | m2, xb[2 * i].z, a[r]);      // codes 2, 10
+                    a[r] = dot2((v & 0x00C000C0u) | m3, xb[2 * i].w, a[r]);      // codes 3, 11
+                    a[r] = dot2((v8 & 0x00030003u) | m0, xb[2 * i + 1].x, a[r]); // codes 4, 12
+                    a[r] = dot2((v8 & 0x000C000Cu) | m1, xb[2 * i + 1].y, a[r]);
+                    a[r] = dot2((v8 & 0x00300030u) | m2, xb[2 * i + 1].z, a[r]);
+                    a[r] = dot2((v8 & 0x00C000C0u) | m3, xb[2 * i + 1].w, a[r]); // codes 7, 15
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < ROWS_PER_WAVE; r++)
+            acc[r] += L.s[r] * (a[r] - cs.x - (float)L.z[r] * cs.y);
+    } else if (BITS == 4) {
         const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 4) >> 3));
         // The two exponent patterns live in VGPRs (hidden from constant folding) so that
         // mask-and-merge is one v_and_or_b32 with the mask on the scalar bus.
@@ -369,6 +459,8 @@ struct Cut {
 
 __device__ __forceinline__ long long entry_unit_cost(const FqLinearDesc &d, int bits)
 {
+    if (bits == 2) // bound by the unpacking, not by the bytes: measured 0.72 of the time of 4 bits (88 per group)
+        return d.codes2 ? (long long)(d.K >> 7) * 63 : 0;
     const bool ok = (bits == 4 && d.codes4) || (bits == 8 && d.codes8) || (bits == 16 && d.w16);
     // time of 16 rows ~ bytes, with 4-bit bytes charged 10 % more: its unpack makes a
     // workgroup's own rate, not the shared HBM rate, the limit (measured: all-W4 runs at
@@ -465,15 +557,19 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
     if (SINGLE) {
         // one linear: equal row tiles dealt round-robin
         const int wave_rows = tile_rows / WAVES; // multiple of 4
-        const uint8_t *codes = bits_host == 4 ? single.codes4 : bits_host == 8 ? single.codes8
-                                                                               : (const uint8_t *)single.w16;
-        Sel d = {codes, bits_host == 4 ? single.scales4 : single.scales8,
-                 bits_host == 4 ? single.zeros4 : single.zeros8, single.N, single.K};
+        const uint8_t *codes = bits_host == 2   ? single.codes2
+                               : bits_host == 4 ? single.codes4
+                               : bits_host == 8 ? single.codes8
+                                                : (const uint8_t *)single.w16;
+        Sel d = {codes, bits_host == 2 ? single.scales2 : bits_host == 4 ? single.scales4 : single.scales8,
+                 bits_host == 2 ? single.zeros2 : bits_host == 4 ? single.zeros4 : single.zeros8, single.N, single.K};
         bool first = true;
         for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
             const int row_begin = min(tile * tile_rows + wave * wave_rows, d.N);
             const int row_end = min(row_begin + wave_rows, d.N);
-            if (bits_host == 4)
+            if (bits_host == 2)
+                run_tile<2>(d, single.x, single.y, row_begin, row_end, first, lds);
+            else if (bits_host == 4)
                 run_tile<4>(d, single.x, single.y, row_begin, row_end, first, lds);
             else if (bits_host == 8)
                 run_tile<8>(d, single.x, single.y, row_begin, row_end, first, lds);
@@ -497,15 +593,17 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
         d.N = dp->N;
         d.K = dp->K;
         // the switch of precision: a pointer select on resident copies
-        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : (const uint8_t *)dp->w16;
-        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.codes = bits == 2 ? dp->codes2 : bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : (const uint8_t *)dp->w16;
+        d.scales = bits == 2 ? dp->scales2 : bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 2 ? dp->zeros2 : bits == 4 ? dp->zeros4 : dp->zeros8;
         // rows [16 u0, 16 u1) split over the 4 wavefronts in multiples of 4 rows
         const int r0 = u0 * 16, r1 = min(u1 * 16, d.N);
         const int per_wave = ((r1 - r0 + WAVES * ROWS_PER_WAVE - 1) / (WAVES * ROWS_PER_WAVE)) * ROWS_PER_WAVE;
         const int row_begin = min(r0 + wave * per_wave, r1);
         const int row_end = min(row_begin + per_wave, r1);
-        if (bits == 4)
+        if (bits == 2)
+            run_tile<2>(d, dp->x, dp->y, row_begin, row_end, true, lds);
+        else if (bits == 4)
             run_tile<4>(d, dp->x, dp->y, row_begin, row_end, true, lds);
         else if (bits == 8)
             run_tile<8>(d, dp->x, dp->y, row_begin, row_end, true, lds);
@@ -518,9 +616,11 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
 
 static size_t lds_bytes_for(int max_K)
 {
-    // worst case over the three bit-widths: 4-bit pads K to 2048 and adds 8 bytes per 32 k
-    const size_t kp = ((size_t)max_K + 2047) / 2048 * 2048;
-    return kp * 2 + kp / 32 * 8 + 64;
+    // worst case over the bit-widths: 4-bit pads K to 2048 and adds 8 bytes per 32 k, 2-bit pads
+    // to 4096 and adds 8 bytes per 64 k
+    const size_t kp4 = ((size_t)max_K + 2047) / 2048 * 2048, kp2 = ((size_t)max_K + 4095) / 4096 * 4096;
+    const size_t b4 = kp4 * 2 + kp4 / 32 * 8, b2 = kp2 * 2 + kp2 / 64 * 8;
+    return (b4 > b2 ? b4 : b2) + 64;
 }
 
 // Workgroups that can be resident at once on the current device: a persistent grid must

@@ -16,6 +16,9 @@ struct FqLinearDesc {
     const float *scales8;
     const uint8_t *zeros8;
     const uint16_t *w16;    // fp16 [N][K] or null
+    const uint8_t *codes2;  // [N][K/4] or null (served by the M = 1 kernel only)
+    const float *scales2;
+    const uint8_t *zeros2;
     const uint16_t *x;      // fp16 [M][K]
     uint16_t *y;            // fp16 [M][N]
     int N;

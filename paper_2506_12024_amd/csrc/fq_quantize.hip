@@ -5,7 +5,7 @@
 // one row: every lane loads 8 halves (one 128-bit load, fully coalesced: a
 // wavefront reads 1 KiB = 4 groups), the segment reduces min/max with DPP
 // row shifts, every lane then derives the same s and z and writes its 8 codes
-// with one 32-bit (4-bit codes) or 64-bit (8-bit codes) store.
+// with one 16-bit (2-bit codes), 32-bit (4-bit codes) or 64-bit (8-bit codes) store.
 //
 // The arithmetic is pinned so that codes, scales and zeros are bit-exact
 // against a binary32 evaluation with one rounding per operation: IEEE
@@ -105,7 +105,13 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
         t = fminf(fmaxf(t, p.qlo), p.qhi);
         q[i] = (uint32_t)(int)(SYM ? t + z : t);
     }
-    if (BITS == 4) {
+    if (BITS == 2) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            word |= q[i] << (2 * i); // byte j = code(4j) | code(4j+1) << 2 | code(4j+2) << 4 | code(4j+3) << 6
+        reinterpret_cast<uint16_t *>(codes)[seg * 16 + sub] = (uint16_t)word;
+    } else if (BITS == 4) {
         uint32_t word = 0;
 #pragma unroll
         for (int i = 0; i < 8; i++)
@@ -173,7 +179,11 @@ hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool 
     const half8 *wp = (const half8 *)w;
     uint8_t *cp = (uint8_t *)codes, *zp = (uint8_t *)zeros;
     float *sp = (float *)scales;
-    if (bits == 4 && !symmetric)
+    if (bits == 2 && !symmetric)
+        quantize_kernel<2, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (bits == 2)
+        quantize_kernel<2, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (bits == 4 && !symmetric)
         quantize_kernel<4, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
     else if (bits == 4)
         quantize_kernel<4, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);

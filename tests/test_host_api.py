@@ -162,6 +162,19 @@ def test_w8a8_validation():
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
 
+def test_2bit_copy_limits():
+    L = fq.lib
+    assert fq.fq_packed_sizes(4096, 4096, 2) == (4096 * 4096 // 4, 4096 * 32 * 4, 4096 * 32)
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 64, 256, 128) == B.FQ_OK
+    assert L.fq_layer_attach(h, 2, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_layer_attach(h, 2, FAKE, None, FAKE) == B.FQ_ERR_NULL
+    assert L.fq_linear(h, 2, FAKE, 2, FAKE, None) == B.FQ_ERR_BITS  # served at M = 1 only
+    assert "M = 1" in fq.fq_last_error()
+    assert L.fq_linear(h, 4, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
+    assert L.fq_layer_destroy(h) == B.FQ_OK
+
+
 def test_sym_and_fake_quantize_validation():
     L, vp = fq.lib, ctypes.c_void_p
     ok = vp(FAKE)
