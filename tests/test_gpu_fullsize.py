@@ -70,6 +70,11 @@ def test_llama7b_stack_batch1_mixed_w4_w8():
     _check_stack(st, steps=(0, 77), n_entries=28, rows_per_entry=6, rng=np.random.default_rng(0))
 
 
+def test_llama7b_stack_batch1_bits_2_4_8():
+    st = bench.Stack("llama7b", M=1, bit_choices=(2, 4, 8))
+    _check_stack(st, steps=(11,), n_entries=28, rows_per_entry=5, rng=np.random.default_rng(3))
+
+
 def test_llama7b_stack_batch16_bits_4_8_16():
     st = bench.Stack("llama7b", M=16, bit_choices=(4, 8, 16))
     _check_stack(st, steps=(3,), n_entries=21, rows_per_entry=4, rng=np.random.default_rng(1))
