@@ -22,11 +22,10 @@
 // stage two steps ahead into the slot it has just emptied: two stages per consumer, 64 KiB per
 // CU, are in flight while the step computes (three measured the same: the memory system is the
 // limit, not the depth).  When a tile's stages have all been requested the requests go on with
-// the first stages of the workgroup's next tile, so that it starts with its ring full; the
-// outputs of a tile are stored with a fixed number of buffer stores (lanes with nothing to
-// store point past the end of the buffer), which the counted waits of the next tile's first
-// steps allow for.  The LDS reads are inline assembly: the compiler cannot tell a read of a
-// run-time slot from the slots being filled and would wait for every outstanding load first.
+// the first stages of the workgroup's next tile, so that it starts with its ring full (the
+// counted waits of its first steps do not allow for the stores of the tile before: those have
+// to be through as well).  The LDS reads are inline assembly: the compiler cannot tell a read of
+// a run-time slot from the slots being filled and would wait for every outstanding load first.
 //
 // Loaders.  x and the metadata are what the stream cannot carry: a scale or zero-point fetch
 // per stage touches one cache line per row (64 tiny requests per instruction, more than the
@@ -134,20 +133,15 @@ struct Stage {
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
-// Wait until at most n of the wavefront's vector memory operations are outstanding (they
-// complete in order; n is rounded down to a value that has an instruction here).  NST: the
-// stores of a tile's outputs, which may sit between the stages in flight.
-template <int NST>
+// Wait until at most n of the wavefront's vector memory operations are outstanding (n is rounded
+// down to a value that has an instruction here).  n counts the loads of the stages requested
+// after the one waited for; loads complete in order among themselves.  The stores of a tile's
+// outputs, which may sit between the stages in flight, are never allowed for: whatever their
+// order of completion relative to the loads, the stage waited for has then arrived.
 __device__ __forceinline__ void wait_vm(int n)
 {
     n = __builtin_amdgcn_readfirstlane(n);
-    if (NS > 2 && n >= NST + 2 * SOPS)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NST + 2 * SOPS) : "memory");
-    else if (n >= NST + SOPS)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NST + SOPS) : "memory");
-    else if (n >= NST)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NST) : "memory");
-    else if (NS > 2 && n >= 2 * SOPS)
+    if (NS > 2 && n >= 2 * SOPS)
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * SOPS) : "memory");
     else if (n >= SOPS)
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SOPS) : "memory");
@@ -407,7 +401,6 @@ struct Stream {
     uint8_t *ring;    // this wavefront's NS slots
     int rslot, wslot; // slot of the oldest stage in flight; slot of the next request
     int infl;         // stages in flight
-    int old;          // of those, the ones requested before the wavefront's latest output stores
     Rows cur, nxt;    // the tile being computed, the one after it
     int fq, nfq;      // stages requested so far of either
     // per-lane constants of the weight loads: load i of a stage covers rows 8 i .. 8 i + 7 of the
@@ -420,7 +413,7 @@ struct Stream {
     {
         const uint32_t lane = threadIdx.x & 63;
         ring = L.ring + wave * NS * STAGE_BYTES;
-        rslot = wslot = infl = old = fq = nfq = 0;
+        rslot = wslot = infl = fq = nfq = 0;
         r = lane >> 3;
         pc16 = ((lane & 7) ^ (r >> 1)) * 16;
         cur.none(), nxt.none();
@@ -456,16 +449,14 @@ struct Stream {
         }
     }
 
-    // How many vector memory operations younger than the oldest stage may be outstanding when it
-    // has arrived: the other stages in flight and, if it was requested before them, NST stores.
-    __device__ __forceinline__ int younger(int nst) const { return (infl - 1) * SOPS + (old > 0 ? nst : 0); }
+    // Loads younger than those of the oldest stage in flight.
+    __device__ __forceinline__ int younger() const { return (infl - 1) * SOPS; }
 
     // The oldest stage has been copied out of its slot.
     __device__ __forceinline__ void taken()
     {
         rslot = rslot == NS - 1 ? 0 : rslot + 1;
         infl--;
-        old -= old > 0;
     }
 
     // The current tile is done and its outputs have been stored: go on to the next.
@@ -474,7 +465,6 @@ struct Stream {
         cur = nxt;
         fq = nfq;
         nfq = 0;
-        old = infl;
         nxt.none();
     }
 };
@@ -482,7 +472,6 @@ struct Stream {
 template <int BITS, int MT>
 struct Consumer {
     typedef Cfg<BITS> C;
-    static constexpr int NST = RT * MT * 4; // store instructions of a tile's outputs
     Stream &S;
     const Lds &L;
     const int lane, n, c;
@@ -654,7 +643,7 @@ struct Consumer {
                 xa[2] = xa[3] = 0;
             }
             Stage st;
-            wait_vm<NST>(S.younger(NST));
+            wait_vm(S.younger());
             take<BITS, MT>(wa, wb, sa, za, xa, st);
             S.taken();
             S.request(); // into the slot just emptied: the stage NS steps ahead
@@ -663,9 +652,9 @@ struct Consumer {
         }
     }
 
-    // The tile at w (its first chunk).  Exactly NST store instructions, whatever M and N: lanes
-    // with nothing to store point past the end of the buffer, where the hardware drops the write
-    // (the count is what wait_vm relies on).
+    // The tile at w (its first chunk).  The outputs leave through buffer stores: lanes with
+    // nothing to store (batch rows past M, rows past N) point past the end of the buffer, where
+    // the hardware drops the write -- no branches around the stores.
     __device__ __forceinline__ void run(const Walk &w, int M, int wave)
     {
         for (int ch = 0; ch < w.nchunks; ch++)
