@@ -182,9 +182,9 @@ def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
     t_step = t_lin * (n_layers / sample_layers) + t_ent
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": M / t_step, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s, scaled x%.0f) "
-                      "+ entropy/KL of the step's logits (%.4f s)"
-                      % (sample_layers, n_layers, t_lin, n_layers / sample_layers, t_ent)}
+            "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s on %d threads = %.0f core-seconds, "
+                      "scaled x%.0f) + entropy/KL of the step's logits (%.4f s)"
+                      % (sample_layers, n_layers, t_lin, threads, t_lin * threads, n_layers / sample_layers, t_ent)}
 
 
 def bench_prefill(args):
