@@ -457,15 +457,27 @@ struct Cut {
     int unit;    // 16-row unit inside that entry
 };
 
+// Relative time of one quantization group (128 k) of one row at each width, a byte of 8-bit codes
+// costing 200.  8 and 16 bits stream at the shared HBM rate: cost ~ bytes.  The unpacking of 4 and
+// 2 bits makes a workgroup's own rate the limit, so their bytes are charged more: measured on the
+// 7B stack, the mixed {4, 8} step takes 0.811 / 0.792 / 0.776 / 0.765 / 0.761 / 0.762 / 0.769 ms
+// with a 4-bit byte charged 200 / 210 / 220 / 225 / 230 / 235 / 240, and a 2-bit group charged
+// 0.64 / 0.68 / 0.72 / 0.76 / 0.80 of a 4-bit one gives 0.470 / 0.462 / 0.459 / 0.455 / 0.461 ms
+// for bits from {2, 4} and 0.633 / 0.628 / 0.629 / 0.632 / 0.634 ms for {2, 4, 8}.
+constexpr int W4_COST = 230;     // per byte
+constexpr int W2_PER_MILLE = 730; // of the cost of a 4-bit group
 __device__ __forceinline__ long long entry_unit_cost(const FqLinearDesc &d, int bits)
 {
-    if (bits == 2) // bound by the unpacking, not by the bytes: measured 0.72 of the time of 4 bits (88 per group)
-        return d.codes2 ? (long long)(d.K >> 7) * 63 : 0;
-    const bool ok = (bits == 4 && d.codes4) || (bits == 8 && d.codes8) || (bits == 16 && d.w16);
-    // time of 16 rows ~ bytes, with 4-bit bytes charged 10 % more: its unpack makes a
-    // workgroup's own rate, not the shared HBM rate, the limit (measured: all-W4 runs at
-    // 6.4 TB/s, all-W8 at 6.7 TB/s)
-    return ok ? (long long)(d.K >> 7) * bits * (bits == 4 ? 22 : 20) : 0;
+    const long long groups = d.K >> 7;
+    if (bits == 2)
+        return d.codes2 ? groups * (64 * W4_COST * W2_PER_MILLE / 1000) : 0;
+    if (bits == 4)
+        return d.codes4 ? groups * (64 * W4_COST) : 0;
+    if (bits == 8)
+        return d.codes8 ? groups * (128 * 200) : 0;
+    if (bits == 16)
+        return d.w16 ? groups * (256 * 200) : 0;
+    return 0;
 }
 
 // Inclusive scan over the 256 threads of the workgroup; `total` returns the sum.
