@@ -683,8 +683,9 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
     const int cap = resident_workgroups(lds);
     // A plan cuts its total cost into one equal slice per workgroup.  Two workgroups per CU
     // (8 wavefronts, each with eight 128-bit loads per lane in flight) stream measurably
-    // faster than four: fewer concurrent streams, better DRAM page locality (measured
-    // 0.774 vs 0.803 ms on the mixed 7B step).
+    // faster than four: fewer concurrent streams, better DRAM page locality (measured on the
+    // mixed 7B step: 0.867 / 0.763 / 0.788 / 0.795 ms with 1 / 2 / 3 / 4 workgroups per CU; a
+    // third register set, i.e. twelve loads per lane in flight, made it slower too: 0.780 ms).
     const int plan_grid = cap < 2 * device_cus() ? cap : 2 * device_cus();
     const int grid = single ? (total_tiles < cap ? total_tiles : cap) : plan_grid;
     if (single) {
