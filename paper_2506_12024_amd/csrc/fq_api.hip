@@ -359,9 +359,6 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         if (M != 1 && layers[i]->codes[3]) // a device-side width of 2 could not be served, nor refused, at launch
             return fail(FQ_ERR_BITS, "fq_plan_create: entry %d has a 2-bit copy, which is served at M = 1 only (M=%d)",
                         i, M);
-        if ((long long)M * layers[i]->N >= (1LL << 30)) // the kernels address y with 32-bit byte offsets
-            return fail(FQ_ERR_SHAPE, "fq_plan_create: entry %d: M * N = %lld is 2^30 or more", i,
-                        (long long)M * layers[i]->N);
         fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
         table[(size_t)i].tile_begin = (int)tiles;
         tiles += (layers[i]->N + rows - 1) / rows;

@@ -5,11 +5,9 @@
 // rows x 32 k, binary32 accumulation; two batch tiles above 16 rows).  Launches with few or
 // narrow tiles and single calls stay with the register-fed small-batch kernel.
 //
-// Work split.  A workgroup owns a tile of 256 weight rows at a time and has twelve wavefronts,
-// three per SIMD: eight consumers (two per SIMD, so that one computes while the other waits),
-// 32 rows = 2 MFMA row tiles each, and four loaders.  A workgroup's tiles (blockIdx.x,
-// + gridDim.x, ...) and the 512-k chunks of each form one list that every wavefront walks on
-// its own; one barrier per chunk is where they meet, and there is none between tiles.
+// Work split.  A workgroup owns a tile of 256 weight rows and has ten wavefronts: eight
+// consumers (two per SIMD, so that one computes while the other waits), 32 rows = 2 MFMA row
+// tiles each, and two loaders.
 //
 // Weight stream.  A stage is one 128-byte line of each of the consumer's 32 rows (256 / 128 /
 // 64 k at 4 / 8 / 16 bits); a load instruction covers 8 rows x 128 bytes, whole lines only
@@ -17,21 +15,18 @@
 // non-temporal (read once).  Stages go from global memory straight into a wavefront-private
 // LDS ring of two slots with direct-to-LDS loads (global_load_lds_dwordx4): no register
 // staging, and the only synchronisation the stream needs is a counted s_waitcnt vmcnt(n) of
-// the wavefront on its own operations.  A step waits for its stage, copies it to registers
-// together with the x blocks and the scales / zero points it needs, and at once requests the
-// stage two steps ahead into the slot it has just emptied: two stages per consumer, 64 KiB per
-// CU, are in flight while the step computes (three measured the same: the memory system is the
-// limit, not the depth).  When a tile's stages have all been requested the requests go on with
-// the first stages of the workgroup's next tile, so that it starts with its ring full (the
-// counted waits of its first steps do not allow for the stores of the tile before: those have
-// to be through as well).  The LDS reads are inline assembly: the compiler cannot tell a read of
-// a run-time slot from the slots being filled and would wait for every outstanding load first.
+// the wavefront on its own loads.  A step waits for its stage, copies it to registers together
+// with the x blocks and the scales / zero points it needs, and at once requests the stage two
+// steps ahead into the slot it has just emptied: two stages per consumer, 64 KiB per CU, are
+// in flight while the step computes (three measured the same: the memory system is the limit,
+// not the depth).  These LDS reads are inline assembly: the compiler cannot tell a read of a
+// run-time slot from the slots being filled and would wait for every outstanding load first.
 //
 // Loaders.  x and the metadata are what the stream cannot carry: a scale or zero-point fetch
 // per stage touches one cache line per row (64 tiny requests per instruction, more than the
-// weights themselves need), and the 4-bit path wants x permuted.  Four more wavefronts fetch
-// them with ordinary loads -- their own vmcnt, nobody else waits.  Two fetch x in chunks of
-// 512 k, each every other chunk, requested two chunk periods before they are due: 16-byte
+// weights themselves need), and the 4-bit path wants x permuted.  Two more wavefronts fetch
+// them with ordinary loads -- their own vmcnt, nobody else waits -- in chunks of 512 k, each
+// loader every other chunk, requested two chunk periods before they are due: x as 16-byte
 // blocks of 8 halves, one request of 1 KiB per batch row and chunk, stored [k block][batch
 // row] with the rows of k block kb XOR-ed by kb % 8 + 8 (kb / 32) -- conflict free for the
 // writer, whose lanes are k blocks (a 128-bit LDS write goes eight lanes at a time), and for the
@@ -39,11 +34,9 @@
 // 0 .. 7 and 8 .. 15 of every group of 16 lanes use different halves of the 256 bytes and the
 // same ones in all four groups, i.e. whatever the k block) -- zero past K, for the
 // 4-bit path permuted inside the block to the order the unpacking produces (x0 x4 x1 x5 x2 x6
-// x3 x7).  Two fetch scales and zero points, half the tile's rows each, 32 units (4096 k) of a
-// row at a time -- a whole line of scales where rows start on one -- keep them in registers
-// and write them to LDS a pair of chunks (8 units) at a time, stored [consumer][row][row
-// tile][unit].  The loaders run ahead through the list: the first chunks of a tile are in LDS
-// before the consumers have finished the one before.
+// x3 x7); scales and zero points for a pair of chunks at a time (8 units: 32 + 8 contiguous
+// bytes per row), stored [consumer][row][row tile][unit].  One barrier per chunk hands a
+// chunk over.
 //
 // Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is the
 // pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q; bytes go
@@ -71,7 +64,7 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CONSUMERS = 8;
-constexpr int LOADERS = 4;                     // two for x, two for the scales and zero points
+constexpr int LOADERS = 2;
 constexpr int THREADS = (CONSUMERS + LOADERS) * 64;
 constexpr int RT = 2;                         // MFMA row tiles (16 rows) per consumer
 constexpr int TILE_ROWS = CONSUMERS * RT * 16;
@@ -133,38 +126,23 @@ struct Stage {
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
-// Wait until at most n of the wavefront's vector memory operations are outstanding (n is rounded
-// down to a value that has an instruction here).  n counts the loads of the stages requested
-// after the one waited for; loads complete in order among themselves.  The stores of a tile's
-// outputs, which may sit between the stages in flight, are never allowed for: whatever their
-// order of completion relative to the loads, the stage waited for has then arrived.
-__device__ __forceinline__ void wait_vm(int n)
-{
-    n = __builtin_amdgcn_readfirstlane(n);
-    if (NS > 2 && n >= 2 * SOPS)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * SOPS) : "memory");
-    else if (n >= SOPS)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SOPS) : "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
-// Copy a ring slot, the metadata and the stage's x blocks to registers (after wait_vm for the
-// slot's stage).  `wa`, `wb`: LDS byte addresses of the lane's two pieces in row tile 0 of the
-// slot; `sa`, `za`: of the lane's scales and zero points for row tile 0 (row tile 1: UP entries
-// further); `xa`: of the lane's x blocks.  All of it is inline assembly on purpose: the compiler
-// cannot tell these reads from the slots being filled and would wait for every outstanding load
-// first.
+// Wait until at most ALLOW of the wavefront's loads are outstanding (the stage of this step is
+// older than those), then copy the slot, the metadata and the stage's x blocks to registers.
+// `wa`, `wb`: LDS byte addresses of the lane's two pieces in row tile 0 of the slot; `sa`, `za`:
+// of the lane's scales and zero points for row tile 0 (row tile 1: UP entries further); `xa`:
+// of the lane's x blocks.  All of it is inline assembly on purpose: the compiler cannot tell
+// these reads from the slots being filled and would wait for every outstanding load first.
 // Which x blocks land in st.a: 4 bits, MT = 1: [unit][i]; 4 bits, MT = 2: [batch tile][i] of
 // unit 0 (unit 1 follows with more_x); 8 bits: [batch tile][half][i]; 16 bits: [batch tile][half].
-template <int BITS, int MT>
+template <int BITS, int MT, int ALLOW>
 __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint32_t za, const uint32_t (&xa)[4],
                                      Stage &st)
 {
     if constexpr (BITS == 4) {
         float2_t s0, s1;
         uint32_t z0, z1;
-        asm volatile("ds_read_b128 %0, %16\n\t"
+        asm volatile("s_waitcnt vmcnt(%24)\n\t"
+                     "ds_read_b128 %0, %16\n\t"
                      "ds_read_b128 %1, %17\n\t"
                      "ds_read_b128 %2, %16 offset:2048\n\t"
                      "ds_read_b128 %3, %17 offset:2048\n\t"
@@ -176,15 +154,15 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                      "ds_read_b128 %9, %21\n\t"
                      "ds_read_b128 %10, %22\n\t"
                      "ds_read_b128 %11, %23\n\t"
-                     "ds_read_b128 %12, %20 offset:%24\n\t"
-                     "ds_read_b128 %13, %21 offset:%24\n\t"
-                     "ds_read_b128 %14, %22 offset:%24\n\t"
-                     "ds_read_b128 %15, %23 offset:%24\n\t"
+                     "ds_read_b128 %12, %20 offset:%25\n\t"
+                     "ds_read_b128 %13, %21 offset:%25\n\t"
+                     "ds_read_b128 %14, %22 offset:%25\n\t"
+                     "ds_read_b128 %15, %23 offset:%25\n\t"
                      "s_waitcnt lgkmcnt(0)"
                      : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(s0), "=&v"(s1),
                        "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3]),
                        "=&v"(st.a[4]), "=&v"(st.a[5]), "=&v"(st.a[6]), "=&v"(st.a[7])
-                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]),
+                     : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(ALLOW),
                        "n"(MT == 1 ? 4096 : 256) // the second unit, or the second batch tile of the first unit
                      : "memory");
         st.s[0][0] = s0.x, st.s[0][1] = s0.y, st.s[1][0] = s1.x, st.s[1][1] = s1.y;
@@ -192,7 +170,8 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
     } else if constexpr (BITS == 8) {
         uint32_t z0, z1;
         if constexpr (MT == 1) {
-            asm volatile("ds_read_b128 %0, %12\n\t"
+            asm volatile("s_waitcnt vmcnt(%20)\n\t"
+                         "ds_read_b128 %0, %12\n\t"
                          "ds_read_b128 %1, %13\n\t"
                          "ds_read_b128 %2, %12 offset:2048\n\t"
                          "ds_read_b128 %3, %13 offset:2048\n\t"
@@ -208,10 +187,12 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                          : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]),
                            "=&v"(st.s[0][0]), "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]),
                            "=&v"(st.a[2]), "=&v"(st.a[3])
-                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3])
+                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]),
+                           "n"(ALLOW)
                          : "memory");
         } else {
-            asm volatile("ds_read_b128 %0, %16\n\t"
+            asm volatile("s_waitcnt vmcnt(%24)\n\t"
+                         "ds_read_b128 %0, %16\n\t"
                          "ds_read_b128 %1, %17\n\t"
                          "ds_read_b128 %2, %16 offset:2048\n\t"
                          "ds_read_b128 %3, %17 offset:2048\n\t"
@@ -232,13 +213,15 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                            "=&v"(st.s[0][0]), "=&v"(st.s[1][0]), "=&v"(z0), "=&v"(z1), "=&v"(st.a[0]), "=&v"(st.a[1]),
                            "=&v"(st.a[2]), "=&v"(st.a[3]), "=&v"(st.a[4]), "=&v"(st.a[5]), "=&v"(st.a[6]),
                            "=&v"(st.a[7])
-                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3])
+                         : "v"(wa), "v"(wb), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]),
+                           "n"(ALLOW)
                          : "memory");
         }
         st.z = z0 | (z1 << 16);
     } else {
         if constexpr (MT == 1) {
-            asm volatile("ds_read_b128 %0, %6\n\t"
+            asm volatile("s_waitcnt vmcnt(%10)\n\t"
+                         "ds_read_b128 %0, %6\n\t"
                          "ds_read_b128 %1, %7\n\t"
                          "ds_read_b128 %2, %6 offset:2048\n\t"
                          "ds_read_b128 %3, %7 offset:2048\n\t"
@@ -247,10 +230,11 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                          "s_waitcnt lgkmcnt(0)"
                          : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
                            "=&v"(st.a[1])
-                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1])
+                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
                          : "memory");
         } else {
-            asm volatile("ds_read_b128 %0, %8\n\t"
+            asm volatile("s_waitcnt vmcnt(%12)\n\t"
+                         "ds_read_b128 %0, %8\n\t"
                          "ds_read_b128 %1, %9\n\t"
                          "ds_read_b128 %2, %8 offset:2048\n\t"
                          "ds_read_b128 %3, %9 offset:2048\n\t"
@@ -261,7 +245,7 @@ __device__ __forceinline__ void take(uint32_t wa, uint32_t wb, uint32_t sa, uint
                          "s_waitcnt lgkmcnt(0)"
                          : "=&v"(st.w[0][0]), "=&v"(st.w[0][1]), "=&v"(st.w[1][0]), "=&v"(st.w[1][1]), "=&v"(st.a[0]),
                            "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3])
-                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1])
+                         : "v"(wa), "v"(wb), "v"(xa[0]), "v"(xa[1]), "n"(ALLOW)
                          : "memory");
         }
     }
@@ -291,202 +275,49 @@ struct Cfg {
     static constexpr int SPC = KC / KPS;       // steps per chunk: 2 / 4 / 8
 };
 
-// ------------------------------------------------------------------ the workgroup's work list
-// The tiles of a workgroup (blockIdx.x, + gridDim.x, ...; entries whose selected width is not
-// attached are passed over) and the chunks of each, numbered through: every wavefront of the
-// workgroup walks the same list on its own, at its own distance ahead, and meets the others at
-// one barrier per chunk.  All of it is wave-uniform.
-struct Walk {
-    const FqLinearDesc *table;
-    const int32_t *bits_dev;
-    int count, total_tiles;
-    int tile, e; // tile >= total_tiles: the list has ended
-    Sel d;
-    int bits, tile_row0, nchunks;
-    int ch; // chunk inside the tile
-    int g;  // chunks before it in the list: its parity names the x buffer
-    int p;  // pairs of chunks before its pair (pairs do not span tiles): parity of the metadata buffer
-
-    __device__ __forceinline__ bool valid() const { return tile < total_tiles; }
-
-    __device__ __forceinline__ void seek()
-    {
-        const int grid = gridDim.x;
-        for (; tile < total_tiles; tile += grid) {
-            while (e + 1 < count && tile >= table[e + 1].tile_begin)
-                e++;
-            const FqLinearDesc *dp = &table[e];
-            bits = bits_dev[e];
-            d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-            if (!d.codes)
-                continue;
-            d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-            d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
-            d.x = dp->x;
-            d.y = dp->y;
-            d.N = dp->N;
-            d.K = dp->K;
-            tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
-            nchunks = (d.K + KC - 1) / KC;
-            return;
-        }
-    }
-
-    __device__ __forceinline__ void start(const FqLinearDesc *table_, const int32_t *bits_dev_, int count_,
-                                          int total_tiles_)
-    {
-        table = table_, bits_dev = bits_dev_, count = count_, total_tiles = total_tiles_;
-        tile = blockIdx.x, e = 0, ch = 0, g = 0, p = 0;
-        bits = 0, tile_row0 = 0, nchunks = 0;
-        d = Sel{nullptr, nullptr, nullptr, nullptr, nullptr, 1, 0};
-        seek();
-    }
-
-    __device__ __forceinline__ void next_tile()
-    {
-        tile += gridDim.x;
-        ch = 0;
-        seek();
-    }
-
-    __device__ __forceinline__ void next_chunk()
-    {
-        g++;
-        if (ch + 1 >= nchunks) {
-            p++;
-            next_tile();
-        } else {
-            ch++;
-            p += (ch & 1) == 0;
-        }
-    }
-
-    // From the first chunk of a tile to the first chunk of the next one.
-    __device__ __forceinline__ void skip_tile()
-    {
-        g += nchunks;
-        p += (nchunks + 1) >> 1;
-        next_tile();
-    }
-};
-
 // ------------------------------------------------------------------ consumer wavefronts
-// Where a consumer's 32 rows of a tile lie in the code array (wave-uniform).
-struct Rows {
-    const uint8_t *gbase; // first byte of the first row
-    uint32_t row_bytes;   // a multiple of 64
-    int T;                // steps: 128-byte lines of a row (the last may be half a line at 4 bits); 0: no tile
-    int lastrel;          // rows past N repeat row N - 1: the last row's distance from the first
-    bool four;            // 4-bit codes
-
-    __device__ __forceinline__ void set(const Walk &w, int wave)
-    {
-        row_bytes = (uint32_t)(w.d.K * w.bits) >> 3;
-        T = (int)((row_bytes + 127) >> 7);
-        // the wavefront's rows span at most 32 * row_bytes < 4 GiB: 32-bit lane offsets from a uniform base
-        const int first = min(w.tile_row0 + wave * RT * 16, w.d.N - 1);
-        gbase = w.d.codes + (size_t)first * (size_t)row_bytes;
-        lastrel = w.d.N - 1 - first;
-        four = w.bits == 4;
-    }
-    __device__ __forceinline__ void none()
-    {
-        gbase = nullptr, row_bytes = 0, T = 0, lastrel = 0, four = false;
-    }
-};
-
-// A consumer's weight stream: the ring and the requests, which run on from a tile into the first
-// stages of the next one, so that a new tile starts with its ring full.
-struct Stream {
-    uint8_t *ring;    // this wavefront's NS slots
-    int rslot, wslot; // slot of the oldest stage in flight; slot of the next request
-    int infl;         // stages in flight
-    Rows cur, nxt;    // the tile being computed, the one after it
-    int fq, nfq;      // stages requested so far of either
-    // per-lane constants of the weight loads: load i of a stage covers rows 8 i .. 8 i + 7 of the
-    // wavefront's 32, lane -> row lane / 8 of those, LDS slot lane % 8, i.e. piece
-    // slot ^ ((row % 16) >> 1) of the line
-    uint32_t r;    // lane / 8
-    uint32_t pc16; // 16 * piece in even loads; odd loads: the piece 4 further, 16 * piece ^ 64
-
-    __device__ __forceinline__ Stream(const Lds &L, int wave)
-    {
-        const uint32_t lane = threadIdx.x & 63;
-        ring = L.ring + wave * NS * STAGE_BYTES;
-        rslot = wslot = infl = fq = nfq = 0;
-        r = lane >> 3;
-        pc16 = ((lane & 7) ^ (r >> 1)) * 16;
-        cur.none(), nxt.none();
-    }
-
-    // Request stages, of the current tile and then of the next, while a slot is free (one per
-    // step in the steady state).  A 4-bit row may end with half a line: the lanes of the missing
-    // half re-read the present one (their x is zero).
-    __device__ __forceinline__ void request()
-    {
-#pragma nounroll
-        while (infl < NS) {
-            const bool c = fq < cur.T;
-            if (!c && nfq >= nxt.T)
-                break;
-            const int q = c ? fq : nfq;
-            const uint32_t row_bytes = c ? cur.row_bytes : nxt.row_bytes;
-            const int lastrel = c ? cur.lastrel : nxt.lastrel;
-            const bool four = c ? cur.four : nxt.four;
-            const uint8_t *base = (c ? cur.gbase : nxt.gbase) + (size_t)q * 128;
-            uint8_t *dst = ring + wslot * STAGE_BYTES;
-            const uint32_t keep = four && (uint32_t)q * 128 + 64 >= row_bytes ? ~64u : ~0u; // pieces 4..7 -> 0..3
-#pragma unroll
-            for (int i = 0; i < SOPS; i++) {
-                const uint32_t rel = (uint32_t)min((int)(8 * i + r), lastrel);
-                const uint32_t off = rel * row_bytes + ((pc16 ^ (64u * (i & 1))) & keep);
-                __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(base + off), (FQ_LDS void *)(dst + i * 1024),
-                                                 16, 0, 2 /* nt: the weights are read once */);
-            }
-            fq += c, nfq += !c;
-            wslot = wslot == NS - 1 ? 0 : wslot + 1;
-            infl++;
-        }
-    }
-
-    // Loads younger than those of the oldest stage in flight.
-    __device__ __forceinline__ int younger() const { return (infl - 1) * SOPS; }
-
-    // The oldest stage has been copied out of its slot.
-    __device__ __forceinline__ void taken()
-    {
-        rslot = rslot == NS - 1 ? 0 : rslot + 1;
-        infl--;
-    }
-
-    // The current tile is done and its outputs have been stored: go on to the next.
-    __device__ __forceinline__ void advance()
-    {
-        cur = nxt;
-        fq = nfq;
-        nfq = 0;
-        nxt.none();
-    }
-};
-
 template <int BITS, int MT>
 struct Consumer {
     typedef Cfg<BITS> C;
-    Stream &S;
+    const Sel &d;
     const Lds &L;
-    const int lane, n, c;
-    uint32_t wa0, wb0; // LDS addresses for take(): the lane's pieces c and c + 4 in slot 0
-    uint32_t ml;       // wave * 16 + n: the lane's place in the metadata of a pair of chunks
+    const int M, wave, lane, n, c, row0;
+    const int row_bytes;  // a multiple of 64
+    const int nchunks;
+    int T;                // steps: 128-byte lines of a row (the last may be half a line at 4 bits)
+    uint8_t *ring;        // this wavefront's NS slots
+    const uint8_t *gbase; // first byte of the wavefront's first row (wave-uniform)
+    // per-lane constants of the weight loads: load i of a stage covers rows 8 i .. 8 i + 7, lane
+    // -> row lane / 8 of those, LDS slot lane % 8, i.e. piece slot ^ ((row % 16) >> 1) of the line
+    uint32_t ld_off[SOPS]; // byte offset of the lane's row from the first row, plus its piece
+    uint32_t ld_hi;        // 64 if the lane's piece in even loads lies in the upper half of the line (odd: the other)
+    uint32_t wa0, wb0;     // LDS addresses for take(): the lane's pieces c and c + 4 in slot 0
+    uint32_t ml;           // wave * 16 + n: the lane's place in the metadata of a pair of chunks
     // byte offsets of the lane's x blocks inside a stage's blocks (block kb of the chunk holds
     // batch row n at place n ^ (kb % 8 + 8 (kb / 32))).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
     // 16 bits: blocks 4 h + c of an even stage, 8 + 4 h + c of an odd one
     uint32_t xq[4];
     float4_t acc[RT][MT], out[RT][MT];
 
-    __device__ __forceinline__ Consumer(Stream &S_, const Lds &L_, int wave)
-        : S(S_), L(L_), lane(threadIdx.x & 63), n(lane & 15), c(lane >> 4)
+    __device__ __forceinline__ Consumer(const Sel &d_, const Lds &L_, int M_, int tile_row0, int wave_)
+        : d(d_), L(L_), M(M_), wave(wave_), lane(threadIdx.x & 63), n(lane & 15), c(lane >> 4),
+          row0(tile_row0 + wave_ * RT * 16), row_bytes(d_.K * BITS / 8), nchunks((d_.K + KC - 1) / KC)
     {
-        wa0 = lds_addr(S.ring) + n * 128 + ((c ^ ((n >> 1) & 7)) * 16);
+        T = (row_bytes + 127) / 128;
+        ring = L.ring + wave * NS * STAGE_BYTES;
+        // the wavefront's rows span at most 32 * row_bytes < 4 GiB: 32-bit lane offsets from a uniform base
+        const int first_row = min(row0, d.N - 1);
+        gbase = d.codes + (size_t)first_row * (size_t)row_bytes;
+        const int r = lane >> 3, slot = lane & 7;
+#pragma unroll
+        for (int i = 0; i < SOPS; i++) {
+            const int rl = 8 * i + r; // row inside the wavefront's 32
+            const int piece = slot ^ (((rl & 15) >> 1) & 7);
+            const int row = min(row0 + rl, d.N - 1);
+            ld_off[i] = (uint32_t)(row - first_row) * (uint32_t)row_bytes + (uint32_t)piece * 16;
+        }
+        ld_hi = ((slot ^ (r >> 1)) & 4) * 16; // bit 2 of the piece flips with the parity of i
+        wa0 = lds_addr(ring) + n * 128 + ((c ^ ((n >> 1) & 7)) * 16);
         wb0 = wa0 ^ 64; // piece c + 4
         ml = wave * 16 + n;
 #pragma unroll
@@ -501,6 +332,24 @@ struct Consumer {
                 acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
                 out[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
             }
+    }
+
+    // Request step q (line q of every row) into ring slot `slot`.  A 4-bit row may end with
+    // half a line: the lanes of the missing half re-read the present one (their x is zero).
+    __device__ __forceinline__ void fetch(int q, int slot)
+    {
+        const uint8_t *base = gbase + (size_t)q * 128;
+        uint8_t *dst = ring + slot * STAGE_BYTES;
+        const bool half_line = BITS == 4 && q * 128 + 64 >= row_bytes;
+        const uint32_t back_even = half_line ? ld_hi : 0u, back_odd = half_line ? 64u - ld_hi : 0u;
+#pragma unroll
+        for (int i = 0; i < SOPS; i++) {
+            uint32_t off = ld_off[i];
+            if (BITS == 4)
+                off -= (i & 1) ? back_odd : back_even; // pieces 4..7 -> 0..3
+            __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(base + off), (FQ_LDS void *)(dst + i * 1024), 16,
+                                             0, 2 /* nt: the weights are read once */);
+        }
     }
 
     // One unit (128 k) of a 4-bit stage: half h of the line, x blocks a[mt * AM + i].
@@ -609,26 +458,27 @@ struct Consumer {
         }
     }
 
-    // Chunk ch of the tile, whose x is in buffer xb and whose metadata is in buffer mb.
-    __device__ __forceinline__ void chunk(int ch, int xb, int mb)
+    // Chunk ch, whose x and metadata are in the buffers of parity XB.
+    template <int XB>
+    __device__ __forceinline__ void chunk(int ch, int &fq, int &slot)
     {
-        barrier(); // the loaders have written the chunk; everybody is done with the one before
+        barrier(); // the loaders have written chunk ch; everybody is done with chunk ch - 1
         // metadata: buffer of the pair of chunks, the chunk's half of it, the lane's row
         const uint32_t mo = ml * (RT * UP) + (ch & 1) * UC;
-        const uint32_t sbase = lds_addr(mb ? L.ms[1] : L.ms[0]) + mo * 4, zbase = lds_addr(mb ? L.mz[1] : L.mz[0]) + mo;
-        uint32_t xbase = lds_addr(xb ? L.x[1] : L.x[0]);
+        const uint32_t sbase = lds_addr((ch & 2) ? L.ms[1] : L.ms[0]) + mo * 4,
+                       zbase = lds_addr((ch & 2) ? L.mz[1] : L.mz[0]) + mo;
+        uint32_t xbase = lds_addr(L.x[XB]);
         asm volatile("" : "+s"(xbase)); // opaque: or every stage's x addresses are hoisted out of the tile and spill
 #pragma unroll
         for (int j = 0; j < C::SPC; j++) {
             const int q = ch * C::SPC + j;
-            if (q >= S.cur.T)
+            if (q >= T)
                 break;
             // where the stage sits inside the chunk: its first unit, its x blocks
             const int unit = j * C::KPS / 128;
-            const uint32_t wa = wa0 + S.rslot * STAGE_BYTES, wb = wb0 + S.rslot * STAGE_BYTES, sa = sbase + unit * 4,
+            const uint32_t wa = wa0 + slot * STAGE_BYTES, wb = wb0 + slot * STAGE_BYTES, sa = sbase + unit * 4,
                            za = zbase + unit;
             uint32_t xa[4];
-            // (k blocks 32 .. 63 of the chunk keep their batch rows in the other half of the places)
             if (BITS == 4) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
@@ -643,27 +493,38 @@ struct Consumer {
                 xa[2] = xa[3] = 0;
             }
             Stage st;
-            wait_vm(S.younger());
-            take<BITS, MT>(wa, wb, sa, za, xa, st);
-            S.taken();
-            S.request(); // into the slot just emptied: the stage NS steps ahead
+            const int pend = __builtin_amdgcn_readfirstlane(fq - 1 - q); // younger stages in flight
+            if (NS > 2 && pend >= 2)
+                take<BITS, MT, 2 * SOPS>(wa, wb, sa, za, xa, st);
+            else if (pend == 1)
+                take<BITS, MT, SOPS>(wa, wb, sa, za, xa, st);
+            else
+                take<BITS, MT, 0>(wa, wb, sa, za, xa, st);
+            if (fq < T) { // the stage NS steps ahead, into the slot just emptied
+                fetch(fq, slot);
+                fq++;
+            }
             __builtin_amdgcn_sched_barrier(0); // keep the requests here: the scheduler sinks them otherwise
             compute(st, xa[0], xa[1], xa[2], xa[3]);
+            slot = slot == NS - 1 ? 0 : slot + 1;
         }
     }
 
-    // The tile at w (its first chunk).  The outputs leave through buffer stores: lanes with
-    // nothing to store (batch rows past M, rows past N) point past the end of the buffer, where
-    // the hardware drops the write -- no branches around the stores.
-    __device__ __forceinline__ void run(const Walk &w, int M, int wave)
+    __device__ __forceinline__ void run()
     {
-        for (int ch = 0; ch < w.nchunks; ch++)
-            chunk(ch, (w.g + ch) & 1, (w.p + (ch >> 1)) & 1);
+        int fq = 0, slot = 0;
+        for (int s = 0; s < NS; s++)
+            if (fq < T) {
+                fetch(fq, s);
+                fq++;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        for (int ch = 0; ch < nchunks; ch += 2) {
+            chunk<0>(ch, fq, slot);
+            if (ch + 1 < nchunks)
+                chunk<1>(ch + 1, fq, slot);
+        }
         // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
-        const int N = w.d.N;
-        const int row0 = w.tile_row0 + wave * RT * 16;
-        const __amdgpu_buffer_rsrc_t yb =
-            __builtin_amdgcn_make_buffer_rsrc((void *)w.d.y, 0, M * N * 2, 0x00020000 /* raw, 32-bit format */);
 #pragma unroll
         for (int rt = 0; rt < RT; rt++) {
             const int row = row0 + rt * 16 + n;
@@ -673,61 +534,41 @@ struct Consumer {
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const int m = mt * 16 + c * 4 + r;
-                    const int off = (m < M && row < N) ? (m * N + row) * 2 : (int)0x80000000u;
-                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, (_Float16)v[r]), yb, off, 0, 0);
+                    if (m < M && row < d.N)
+                        ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + row] =
+                            __builtin_bit_cast(uint16_t, (_Float16)v[r]);
                 }
             }
         }
-        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0);
+        barrier(); // the loaders may refill the buffers for the next tile
     }
 };
 
-template <int MT>
-__device__ __forceinline__ void consume(Walk w, const Lds &L, int M, int wave)
-{
-    Stream S(L, wave);
-    S.cur.set(w, wave);
-    bool first = true;
-    while (w.valid()) {
-        {
-            Walk t = w; // look ahead: the tile after this one
-            t.skip_tile();
-            if (t.valid())
-                S.nxt.set(t, wave);
-        }
-        if (first) {
-            S.request();
-            __builtin_amdgcn_sched_barrier(0);
-            first = false;
-        }
-        if (w.bits == 4)
-            Consumer<4, MT>(S, L, wave).run(w, M, wave);
-        else if (w.bits == 8)
-            Consumer<8, MT>(S, L, wave).run(w, M, wave);
-        else
-            Consumer<16, MT>(S, L, wave).run(w, M, wave);
-        S.advance();
-        w.skip_tile();
-    }
-}
-
-// ------------------------------------------------------------------ loader wavefronts
+// ------------------------------------------------------------------ loader wavefront
 // (One code path for the three bit-widths: instantiated per width, the register allocator sees
-// three sets of staging registers live across the loop.)
+// three sets of staging registers live across the tile loop.)
 template <int MT, int LI>
 struct Loader {
+    const Sel &d;
     const Lds &L;
-    const int M, lane;
-    // a chunk's block `lane` of 16 batch rows (with two batch tiles: loader LI takes tile LI):
+    const int M, lane, tile_row0, G, nchunks, BITS;
+    static constexpr int li = LI;
+    // the chunk's block `lane` of 16 batch rows (with two batch tiles: loader li takes tile li):
     // one 1 KiB request per row
     u32x4 xr[16];
-    // what the registers hold: chunk h_g of the list (-1: nothing), of an entry of h_bits bits,
-    // for x buffer h_xb
-    int h_g, h_bits, h_xb;
+    // metadata of a pair of chunks (UP units): scales as 16 bytes = 4 units per lane, two lanes to
+    // a row, 32 rows to an instruction; zero points as 8 bytes per lane, one lane to a row
+    float4_t sr[TILE_ROWS / 32];
+    uint32_t zr[TILE_ROWS / 64][2];
 
-    __device__ __forceinline__ Loader(const Lds &L_, int M_) : L(L_), M(M_), lane(threadIdx.x & 63), h_g(-1) {}
+    __device__ __forceinline__ Loader(const Sel &d_, const Lds &L_, int M_, int tile_row0_, int bits)
+        : d(d_), L(L_), M(M_), lane(threadIdx.x & 63), tile_row0(tile_row0_), G(d_.K >> 7),
+          nchunks((d_.K + KC - 1) / KC), BITS(bits)
+    {
+    }
 
-    __device__ __forceinline__ void load_x(const Sel &d, int ch)
+    __device__ __forceinline__ void load_x(int ch)
     {
         const int k = ch * KC + lane * 8;
 
@@ -740,13 +581,13 @@ struct Loader {
         }
     }
 
-    __device__ __forceinline__ void store_x()
+    __device__ __forceinline__ void store_x(int b)
     {
-        u32x4 *xb = reinterpret_cast<u32x4 *>(h_xb ? L.x[1] : L.x[0]);
+        u32x4 *xb = reinterpret_cast<u32x4 *>(b ? L.x[1] : L.x[0]);
 #pragma unroll
         for (int m = 0; m < 16; m++) {
             u32x4 p = xr[m];
-            if (h_bits == 4) { // (x0 .. x7) -> (x0 x4 x1 x5 x2 x6 x3 x7), the unpack order
+            if (BITS == 4) { // (x0 .. x7) -> (x0 x4 x1 x5 x2 x6 x3 x7), the unpack order
                 p.x = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x05040100u);
                 p.y = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x07060302u);
                 p.z = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x05040100u);
@@ -757,179 +598,160 @@ struct Loader {
         }
     }
 
-    // Request the chunk at w.
-    __device__ __forceinline__ void load(const Walk &w)
-    {
-        load_x(w.d, w.ch);
-        h_g = w.g, h_bits = w.bits, h_xb = w.g & 1;
-    }
-
-    // w: this loader's next chunk.  Write what the registers hold, then request the loader's
-    // next chunk (the registers are reused: no load before the last write).
-    __device__ __forceinline__ void hand_over(Walk &w)
-    {
-        constexpr int STEP = MT == 1 ? 2 : 1; // distance between the chunks of one loader
-        store_x();
-        __builtin_amdgcn_sched_barrier(0);
-        h_g = -1;
-#pragma unroll
-        for (int s = 0; s < STEP; s++)
-            if (w.valid())
-                w.next_chunk();
-        if (w.valid())
-            load(w);
-    }
-
-    // One batch tile: loader LI owns the chunks of parity LI in the list.  Chunk g + 1 is written
-    // while the consumers work on chunk g, and the owner then requests chunk g + 3 at once.  Two
-    // batch tiles: each loader owns one of them in every chunk and requests chunk g + 2 after
-    // writing chunk g + 1.  The list runs through the tiles: the first chunks of a tile are
-    // requested and written while the consumers are still in the one before.
-    __device__ __forceinline__ void run(Walk w)
-    {
-        Walk b = w; // the chunk of the next barrier
-        if (MT == 1 && LI == 1 && w.valid())
-            w.next_chunk();
-        if (w.valid())
-            load(w);
-        if (h_g == 0)
-            hand_over(w);
-        while (b.valid()) {
-            __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): this wavefront's LDS writes are done
-            barrier();
-            if (h_g == b.g + 1)
-                hand_over(w);
-            b.next_chunk();
-        }
-    }
-};
-
-// ------------------------------------------------------------------ metadata loader wavefronts
-// Scales and zero points of rows 128 ML .. 128 ML + 127 of a tile.  They are fetched a block of
-// 32 units (4096 k, eight chunks) at a time: 128 bytes of scales and 32 of zero points per row,
-// i.e. whole lines of the scale array where a row starts on one -- fetched in smaller pieces, the
-// pieces of a line arrive chunk periods apart and the line comes from HBM more than once.  The
-// block stays in registers and is handed to the consumers a pair of chunks (UP units) at a time,
-// in LDS as [consumer][row % 16][row tile][unit].  The next block (of this tile or the next) is
-// requested when the last pair of the block has been written: two chunk periods before it is due.
-template <int ML>
-struct MetaLoader {
-    static constexpr int BU = 32;        // units per block
-    static constexpr int ROWS = TILE_ROWS / 2;
-    const Lds &L;
-    const int lane;
-    float4_t sr[ROWS / 8]; // load i: rows 8 i + lane / 8, units 4 (lane % 8) .. + 3 of the block
-    u32x4 zr[ROWS / 32];   // load j: rows 32 j + lane / 2, units 16 (lane % 2) .. + 15 of the block
-    int h_tile, h_blk;     // the block in the registers (h_tile < 0: none)
-
-    __device__ __forceinline__ MetaLoader(const Lds &L_) : L(L_), lane(threadIdx.x & 63), h_tile(-1), h_blk(0) {}
-
-    // The block of the chunk at w.  Units past G (a last, partial block) repeat unit G - 1 (they
-    // meet x = 0, so they must be finite), and rows past N repeat row N - 1.
-    __device__ __forceinline__ void load(const Walk &w)
+    // Metadata of the pair of chunks cp: units UP * cp ...  Past G (a last, partial pair) the
+    // unit index is clamped, and then every unit is fetched on its own.  Addresses are a uniform
+    // base plus a 32-bit lane offset, recomputed per call (kept opaque: hoisted out of the tile
+    // they would cost a register each).
+    __device__ __forceinline__ void load_meta(int cp)
     {
         typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
-        typedef uint32_t u32x4_a1 __attribute__((ext_vector_type(4), aligned(1)));
-        const Sel &d = w.d;
-        const int G = d.K >> 7;
-        h_tile = w.tile, h_blk = w.ch / (BU / UC);
-        const int ub = h_blk * BU;
-        const int row_base = w.tile_row0 + ROWS * ML;
-        int last = d.N - 1;
+        typedef uint32_t u32_a1 __attribute__((aligned(1)));
+        const int u0 = cp * UP;
+        const bool whole = u0 + UP <= G;
+        int last = d.N - 1 - tile_row0; // rows of the tile past N repeat row N - 1
         asm volatile("" : "+s"(last));
-        const FQ_GLOBAL float *sc = (const FQ_GLOBAL float *)d.scales;
-        const FQ_GLOBAL uint8_t *zp = (const FQ_GLOBAL uint8_t *)d.zeros;
-        {
-            const int u = ub + 4 * (lane & 7);
-            const bool inside = u + 4 <= G;
+        const float *sbase = d.scales + (size_t)tile_row0 * (size_t)G;
+        const uint8_t *zbase = d.zeros + (size_t)tile_row0 * (size_t)G;
 #pragma unroll
-            for (int i = 0; i < ROWS / 8; i++) {
-                const uint32_t row = (uint32_t)min(row_base + 8 * i + (lane >> 3), last);
-                if (inside) {
-                    sr[i] = *(const FQ_GLOBAL f32x4_a4 *)(sc + (row * (uint32_t)G + (uint32_t)u));
-                } else {
+        for (int i = 0; i < TILE_ROWS / 32; i++) {
+            const uint32_t row = (uint32_t)min(32 * i + (lane >> 1), last);
+            const int u = u0 + 4 * (lane & 1);
+            if (whole) {
+                sr[i] = *(const FQ_GLOBAL f32x4_a4 *)(sbase + (row * (uint32_t)G + (uint32_t)u));
+            } else {
 #pragma unroll
-                    for (int g = 0; g < 4; g++)
-                        sr[i][g] = sc[row * (uint32_t)G + (uint32_t)min(u + g, G - 1)];
-                }
+                for (int g = 0; g < 4; g++)
+                    sr[i][g] = ((const FQ_GLOBAL float *)sbase)[row * (uint32_t)G + (uint32_t)min(u + g, G - 1)];
             }
         }
-        {
-            const int u = ub + 16 * (lane & 1);
-            const bool inside = u + 16 <= G;
 #pragma unroll
-            for (int j = 0; j < ROWS / 32; j++) {
-                const uint32_t row = (uint32_t)min(row_base + 32 * j + (lane >> 1), last);
-                if (inside) {
-                    zr[j] = *(const FQ_GLOBAL u32x4_a1 *)(zp + (row * (uint32_t)G + (uint32_t)u));
-                } else {
-                    uint32_t v[4] = {0u, 0u, 0u, 0u};
+        for (int j = 0; j < TILE_ROWS / 64; j++) {
+            const uint32_t row = (uint32_t)min(64 * j + lane, last);
+            if (whole) {
+                zr[j][0] = *(const FQ_GLOBAL u32_a1 *)(zbase + (row * (uint32_t)G + (uint32_t)u0));
+                zr[j][1] = *(const FQ_GLOBAL u32_a1 *)(zbase + (row * (uint32_t)G + (uint32_t)u0 + 4u));
+            } else {
+                zr[j][0] = zr[j][1] = 0;
 #pragma unroll
-                    for (int g = 0; g < 16; g++)
-                        v[g >> 2] |= (uint32_t)zp[row * (uint32_t)G + (uint32_t)min(u + g, G - 1)] << (8 * (g & 3));
-                    zr[j] = u32x4{v[0], v[1], v[2], v[3]};
-                }
+                for (int g = 0; g < UP; g++)
+                    zr[j][g >> 2] |= (uint32_t)((const FQ_GLOBAL uint8_t *)zbase)[row * (uint32_t)G + (uint32_t)min(u0 + g, G - 1)]
+                                     << (8 * (g & 3));
             }
         }
     }
 
-    // Write the pair of chunks that starts at w (w.ch even), which lies in the block held.
-    __device__ __forceinline__ void store(const Walk &w)
+    // [consumer][row % 16][row tile][unit]
+    __device__ __forceinline__ void store_meta(int b)
     {
-        float *ms = (w.p & 1) ? L.ms[1] : L.ms[0];
-        uint8_t *mz = (w.p & 1) ? L.mz[1] : L.mz[0];
-        const int cp = (w.ch / 2) % (BU / UP); // the pair inside the block: units 8 cp .. 8 cp + 7
-        if (((lane & 7) >> 1) == cp) {
+        float *ms = b ? L.ms[1] : L.ms[0];
+        uint8_t *mz = b ? L.mz[1] : L.mz[0];
 #pragma unroll
-            for (int i = 0; i < ROWS / 8; i++) {
-                const int rl = ROWS * ML + 8 * i + (lane >> 3); // row of the tile: consumer rl / 32, row tile (rl / 16) % 2
-                const int idx = (((rl >> 5) * 16 + (rl & 15)) * RT + ((rl >> 4) & 1)) * UP + 4 * (lane & 1);
-                *reinterpret_cast<float4_t *>(ms + idx) = sr[i];
-            }
+        for (int i = 0; i < TILE_ROWS / 32; i++) {
+            // row 32 i + lane / 2 of the tile: consumer i, row tile lane / 32, row (lane / 2) % 16
+            const int idx = ((i * 16 + ((lane >> 1) & 15)) * RT + (lane >> 5)) * UP + 4 * (lane & 1);
+            *reinterpret_cast<float4_t *>(ms + idx) = sr[i];
         }
-        if ((lane & 1) == (cp >> 1)) {
 #pragma unroll
-            for (int j = 0; j < ROWS / 32; j++) {
-                const int rl = ROWS * ML + 32 * j + (lane >> 1);
-                const int idx = (((rl >> 5) * 16 + (rl & 15)) * RT + ((rl >> 4) & 1)) * UP;
-                const uint32_t a = (cp & 1) ? zr[j].z : zr[j].x, b = (cp & 1) ? zr[j].w : zr[j].y;
-                *reinterpret_cast<uint2 *>(mz + idx) = make_uint2(a, b);
-            }
+        for (int j = 0; j < TILE_ROWS / 64; j++) {
+            // row 64 j + lane: consumer 2 j + lane / 32, row tile (lane / 16) % 2, row lane % 16
+            const int idx = (((2 * j + (lane >> 5)) * 16 + (lane & 15)) * RT + ((lane >> 4) & 1)) * UP;
+            *reinterpret_cast<uint2 *>(mz + idx) = make_uint2(zr[j][0], zr[j][1]);
         }
     }
 
-    // w: the first chunk of the next pair to write.  Write it, go on to the next pair, and
-    // request its block if that is another one (the registers are reused: no load before the
-    // last write).
-    __device__ __forceinline__ void hand_over(Walk &w)
+    __device__ __forceinline__ void load(int ch)
     {
-        if (w.bits != 16)
-            store(w);
-        __builtin_amdgcn_sched_barrier(0);
-        w.next_chunk();
-        if (w.valid() && (w.ch & 1))
-            w.next_chunk();
-        if (w.valid() && w.bits != 16 && (w.tile != h_tile || w.ch / (BU / UC) != h_blk))
-            load(w);
+        load_x(ch);
+        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
+            load_meta(ch >> 1);
+    }
+    __device__ __forceinline__ void store(int ch)
+    {
+        store_x(ch & 1);
+        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
+            store_meta((ch >> 1) & 1);
     }
 
-    __device__ __forceinline__ void run(Walk w)
+    // One batch tile: loader li owns the chunks of parity li (loader 0 with them the metadata,
+    // whose pairs start at even chunks).  Chunk g + 1 is written while the consumers work on chunk
+    // g, and the owner then requests chunk g + 3 at once.  Two batch tiles: each loader owns one
+    // of them in every chunk and requests chunk g + 2 after writing chunk g + 1.
+    __device__ __forceinline__ void run()
     {
-        Walk b = w; // the chunk of the next barrier
-        if (w.valid()) {
-            if (w.bits != 16)
-                load(w);
-            hand_over(w); // the first pair is due at the first barrier
+        constexpr int STEP = MT == 1 ? 2 : 1; // distance between the chunks of one loader
+        const int c0 = MT == 1 ? li : 0;
+        if (c0 < nchunks)
+            load(c0);
+        if (c0 == 0) {
+            store(0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (STEP < nchunks)
+                load(STEP);
         }
-        while (b.valid()) {
+        for (int g = 0; g < nchunks; g++) {
             __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): this wavefront's LDS writes are done
             barrier();
-            if (w.valid() && w.g == b.g + 1)
-                hand_over(w);
-            b.next_chunk();
+            if (g + 1 < nchunks && (MT == 2 || ((g + 1) & 1) == li)) {
+                store(g + 1);
+                __builtin_amdgcn_sched_barrier(0); // the registers are reused: no load before the last write
+                if (g + 1 + STEP < nchunks)
+                    load(g + 1 + STEP);
+            }
         }
+        barrier(); // the consumers have stored the tile
     }
 };
+
+// The tiles of one workgroup, as seen by its loader (LOADER) or by one of its consumers: the two
+// roles walk the same tiles in separate loops so that neither carries the other's registers.
+template <int MT, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
+__device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
+                                          int total_tiles, int M, const Lds &L, int wave)
+{
+    const int grid = gridDim.x;
+    // Workgroups are dealt to the 8 XCDs in turn.  Tiles are handed out so that an XCD takes runs
+    // of XCD_RUN consecutive tiles: the x of a linear is then fetched into a few L2s rather than
+    // into all eight, while a linear's weight rows are still spread over several XCDs (measured
+    // on the mixed 7B step at batch 16: 1.362 / 1.347 / 1.348 / 1.349 / 1.351 ms for runs of
+    // 1 / 4 / 8 / 16 / 32; 8 is also the best for each single width).
+    constexpr int XCD_RUN = 8;
+    int first = blockIdx.x;
+    if (grid % (8 * XCD_RUN) == 0) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        first = ((slot / XCD_RUN) * 8 + xcd) * XCD_RUN + slot % XCD_RUN;
+    }
+    int e = 0;
+    for (int tile = first; tile < total_tiles; tile += grid) {
+        while (e + 1 < count && tile >= table[e + 1].tile_begin)
+            e++;
+        const FqLinearDesc *dp = &table[e];
+        const int bits = bits_dev[e];
+        Sel d;
+        d.N = dp->N;
+        d.K = dp->K;
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.x = dp->x;
+        d.y = dp->y;
+        if (!d.codes)
+            continue; // uniform over the workgroup
+        // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
+        // that every one of them reaches the barriers: one per chunk and one at the end.
+        const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
+        if (ROLE > 0) {
+            constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
+            Loader<MT, LI>(d, L, M, tile_row0, bits).run();
+        } else {
+            if (bits == 4)
+                Consumer<4, MT>(d, L, M, tile_row0, wave).run();
+            else if (bits == 8)
+                Consumer<8, MT>(d, L, M, tile_row0, wave).run();
+            else
+                Consumer<16, MT>(d, L, M, tile_row0, wave).run();
+        }
+    }
+}
 
 template <int MT>
 __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc *__restrict__ table,
@@ -946,24 +768,18 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
     L.ms[0] = ms0, L.ms[1] = ms1;
     L.mz[0] = mz0, L.mz[1] = mz1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    Walk w;
-    w.start(table, bits_dev, count, total_tiles);
-    if (wave < CONSUMERS)
-        consume<MT>(w, L, M, wave);
-    else if (wave == CONSUMERS)
-        Loader<MT, 0>(L, M).run(w);
-    else if (wave == CONSUMERS + 1)
-        Loader<MT, 1>(L, M).run(w);
-    else if (wave == CONSUMERS + 2)
-        MetaLoader<0>(L).run(w);
+    if (wave == CONSUMERS)
+        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave);
+    else if (wave > CONSUMERS)
+        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave);
     else
-        MetaLoader<1>(L).run(w);
+        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave);
 }
 
 } // namespace
 
 // A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
-// tiles of 256 rows (M * N < 2^30 for every entry: the outputs are stored through 32-bit offsets).
+// tiles of 256 rows.
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
                                    int M, int cus, hipStream_t stream)
 {
