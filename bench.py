@@ -731,7 +731,9 @@ def main():
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
         "entropy_kl_us": ent_us,
-        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else "decode_stream_kernel"),
+        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else
+                                                                      "decode_skinny_kernel" if 2 in bit_choices
+                                                                      else "decode_stream_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": alg_bytes * MEASURED_TRAFFIC_RATIO[(args.stack, args.batch, bit_choices)]

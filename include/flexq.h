@@ -32,7 +32,8 @@
  *   codes, bits = 4 : u8  [N][K/2]    byte j of row n = code(2j) | code(2j+1) << 4
  *   codes, bits = 2 : u8  [N][K/4]    byte j of row n = code(4j) | code(4j+1) << 2 |
  *                                     code(4j+2) << 4 | code(4j+3) << 6
- *                                     (Table 1's lowest width; served at M = 1 only)
+ *                                     (Table 1's lowest width; served by the decode kernels,
+ *                                     M <= FQ_MAX_DECODE_M)
  *   scales          : f32 [N][K/group]
  *   zeros           : u8  [N][K/group]
  *   bits = 16       : the fp16 weights W[N][K] themselves, no scales/zeros
@@ -132,7 +133,8 @@ int fq_layer_destroy(fq_layer *layer);
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
  * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 2 is
- * served at M = 1 (token-by-token decoding) only: FQ_ERR_BITS otherwise.
+ * served in the decode phase only (M <= FQ_MAX_DECODE_M and K within the decode kernels' limit):
+ * FQ_ERR_BITS otherwise.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)
  * 1 <= M <= FQ_MAX_DECODE_M selects the memory-bound skinny kernels; larger M
@@ -154,8 +156,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *              descriptor table is copied into it on `stream` by fq_plan_create
  *   bits_dev   device, int32 [count], each 2, 4, 8 or 16 and attached to its layer;
  *              an entry whose value is anything else is skipped by the kernel
- *              and its y is left untouched.  Plans with M > 1 do not take layers
- *              that have a 2-bit copy attached (FQ_ERR_BITS from fq_plan_create)
+ *              and its y is left untouched.  A plan with M > 1 whose layers carry a
+ *              2-bit copy runs on the register-fed batch kernel (the streaming one for
+ *              large plans takes 4, 8 and 16 bits)
  */
 size_t fq_plan_workspace_bytes(int count);
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers,

@@ -248,9 +248,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
         return fail(FQ_ERR_NOT_ATTACHED, "fq_linear: no %d-bit copy attached to this layer", bits);
     if (M < 1)
         return fail(FQ_ERR_SHAPE, "fq_linear: M must be >= 1 (got %d)", M);
-    if (bits == 2 && (M != 1 || layer->K > MAX_DECODE_K))
-        return fail(FQ_ERR_BITS, "fq_linear: the 2-bit copy is served at M = 1 and K <= %d only (got M=%d K=%d)",
-                    MAX_DECODE_K, M, layer->K);
+    if (bits == 2 && (M > FQ_MAX_DECODE_M || layer->K > MAX_DECODE_K))
+        return fail(FQ_ERR_BITS, "fq_linear: the 2-bit copy is served by the decode kernels only, M <= %d and K <= %d (got M=%d K=%d)",
+                    FQ_MAX_DECODE_M, MAX_DECODE_K, M, layer->K);
     if (!aligned16(x_fp16) || (reinterpret_cast<uintptr_t>(y_fp16) & 1u))
         return fail(FQ_ERR_ALIGN, "fq_linear: x needs 16-byte and y 2-byte alignment");
     FqLinearDesc d;
@@ -343,7 +343,14 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     }
     if (max_K > MAX_DECODE_K)
         return fail(FQ_ERR_SHAPE, "fq_plan_create: K=%d exceeds the decode limit %d", max_K, MAX_DECODE_K);
-    const int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
+    int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
+    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits: a plan that holds a
+    // 2-bit copy, whose entries may be switched to it at any token, stays with the register-fed kernel.
+    bool has2 = false;
+    for (int i = 0; i < count; i++)
+        has2 = has2 || layers[i]->codes[3] != nullptr;
+    if (M > 1 && has2 && rows > 128)
+        rows = 128;
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;
@@ -356,9 +363,6 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
                         layers[i]->K, MAX_DECODE_K);
         if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2] && !layers[i]->codes[3])
             return fail(FQ_ERR_NOT_ATTACHED, "fq_plan_create: entry %d has no copy attached", i);
-        if (M != 1 && layers[i]->codes[3]) // a device-side width of 2 could not be served, nor refused, at launch
-            return fail(FQ_ERR_BITS, "fq_plan_create: entry %d has a 2-bit copy, which is served at M = 1 only (M=%d)",
-                        i, M);
         fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
         table[(size_t)i].tile_begin = (int)tiles;
         tiles += (layers[i]->N + rows - 1) / rows;

@@ -99,7 +99,7 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
 {
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     const uint32_t K = (uint32_t)d.K;
-    const uint32_t row_bytes = BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
         const uint32_t row = (uint32_t)min(wave_row0 + rt * 16 + n, d.N - 1);
@@ -107,7 +107,19 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
         for (int ku = 0; ku < KU; ku++) {
             // an odd number of loads (4-bit, K / 128 odd): the missing one re-reads the last
             const uint32_t li = (uint32_t)min(st * KU + ku, nload - 1);
-            L.w[rt][ku] = load16_weights(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
+            if (BITS == 2) {
+                // 64 bytes of a row are two quantization groups: the lane takes 8 bytes (32 codes) of
+                // either, so that the four lanes of a row supply whole groups to the MFMAs.  A row
+                // may end after the first group (K / 128 odd): the second piece then re-reads the
+                // first (its x is zero).
+                const uint8_t *p = d.codes + (size_t)row * row_bytes + li * 64 + c * 8;
+                const uint32_t second = li * 64 + 32 < row_bytes ? 32u : 0u;
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 a = *(const FQ_GLOBAL u32x2 *)p, b = *(const FQ_GLOBAL u32x2 *)(p + second);
+                L.w[rt][ku] = make_uint4(a.x, a.y, b.x, b.y);
+            } else {
+                L.w[rt][ku] = load16_weights(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
+            }
         }
     }
 }
@@ -130,6 +142,8 @@ __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, 
         // never stored (rows) or are never read (k)
         const int mc = min(m, M - 1), k = min(kc + kb * 8, d.K - 8);
         S.x[it] = load16_global(x + (size_t)mc * d.K + k);
+        if (BITS == 2 && kc + kb * 8 >= d.K) // 2 bits: the second group of a last load may lie past K
+            S.x[it] = make_uint4(0, 0, 0, 0);
     }
     if (BITS != 16) {
         const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
@@ -159,6 +173,21 @@ __device__ __forceinline__ void commit_chunk(const Staged<MT, RT> &S, uint4 *lds
         const int idx = it * WG_THREADS + threadIdx.x;
         const int m = idx / BLK, kb = idx % BLK;
         uint4 p = S.x[it];
+        if (BITS == 2) {
+            // Blocks kb (A = x0..7) and kb + 1 (B = x8..15) of 16 consecutive k, held by
+            // neighbouring lanes, are stored interleaved -- (A0 B0 A1 B1 A2 B2 A3 B3) at kb,
+            // (A4 B4 .. A7 B7) at kb + 1 -- the order in which a word of 16 two-bit codes unpacks.
+            const bool odd = kb & 1;
+            const uint32_t give0 = odd ? S.x[it].x : S.x[it].z, give1 = odd ? S.x[it].y : S.x[it].w;
+            const uint32_t got0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give0, 0xB1, 0xF, 0xF, false);
+            const uint32_t got1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)give1, 0xB1, 0xF, 0xF, false);
+            const uint32_t a0 = odd ? got0 : S.x[it].x, a1 = odd ? got1 : S.x[it].y; // words of A
+            const uint32_t b0 = odd ? S.x[it].z : got0, b1 = odd ? S.x[it].w : got1; // words of B
+            p.x = __builtin_amdgcn_perm(b0, a0, 0x05040100u);
+            p.y = __builtin_amdgcn_perm(b0, a0, 0x07060302u);
+            p.z = __builtin_amdgcn_perm(b1, a1, 0x05040100u);
+            p.w = __builtin_amdgcn_perm(b1, a1, 0x07060302u);
+        }
         if (BITS == 4) {
             p.x = __builtin_amdgcn_perm(S.x[it].z, S.x[it].x, 0x05040100u); // (x0, x4)
             p.y = __builtin_amdgcn_perm(S.x[it].z, S.x[it].x, 0x07060302u); // (x1, x5)
@@ -186,6 +215,71 @@ __device__ __forceinline__ float4_t mfma(uint4 a, const uint32_t (&b)[4], float4
     const u32x4 bv = {b[0], b[1], b[2], b[3]};
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
                                                   __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
+}
+
+// 2 bits: one load's worth of work.  The lane holds 32 codes of each of the load's two groups
+// (words 0, 1 and words 2, 3); a word of 16 codes unpacks into two MFMA operands, (q0 q8 q1 q9 q2
+// q10 q3 q11) and (q4 q12 .. q7 q15): a 2-bit field at bits 0 / 2 / 4 / 6 of a half reads as 1024 + q
+// / 256 + q / 64 + q / 16 + q under the exponents 0x64 / 0x5C / 0x54 / 0x4C, and one v_pk_add_f16 per
+// register removes offset and zero point.  x is staged in the matching interleaved order.
+template <int MT, int RT, int ku>
+__device__ __forceinline__ void compute2(int st, const Loaded<RT> &L, const uint4 *lds_x, const float *ms,
+                                         const uint8_t *mz, float4_t (&acc)[RT][MT], float4_t (&out)[RT][MT])
+{
+    typedef Chunk<MT> C;
+    constexpr int ROWS = 16 * MT;
+    constexpr int KPL = 256, LPC = C::KC / KPL;
+    const int li = st * KU + ku;
+    const int lane = threadIdx.x & 63, m = lane & 15, c = lane >> 4;
+    const int lc = li % LPC; // load inside the chunk
+    uint32_t m0 = 0x64006400u, m1 = 0x5C005C00u, m2 = 0x54005400u, m3 = 0x4C004C00u;
+    asm volatile("" : "+v"(m0), "+v"(m1), "+v"(m2), "+v"(m3));
+#pragma unroll
+    for (int g2 = 0; g2 < 2; g2++) { // the load's two groups
+        const int gl = lc * 2 + g2;  // group inside the chunk
+        const int kk = gl * 128 + c * 32; // lane's first k of it inside the chunk
+        float s[RT];
+        uint32_t nz[RT][4];
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            s[rt] = ms[(rt * C::GROUPS + gl) * 16 + m];
+            const uint32_t z = mz[(rt * C::GROUPS + gl) * 16 + m]; // 0 .. 3
+            const uint32_t zz = z | (z << 16);
+            nz[rt][0] = zz | 0xE400E400u;        // -(1024 + z) twice
+            nz[rt][1] = (zz << 2) | 0xDC00DC00u; // -( 256 + z)
+            nz[rt][2] = (zz << 4) | 0xD400D400u; // -(  64 + z)
+            nz[rt][3] = (zz << 6) | 0xCC00CC00u; // -(  16 + z)
+        }
+#pragma unroll
+        for (int i = 0; i < 2; i++)     // word of the group
+#pragma unroll
+            for (int h = 0; h < 2; h++) { // codes 0..3 + 8..11, or 4..7 + 12..15 of the word
+                uint4 a[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    a[mt] = lds_x[((kk >> 3) + 2 * i + h) * ROWS + mt * 16 + m];
+#pragma unroll
+                for (int rt = 0; rt < RT; rt++) {
+                    const uint32_t ww[4] = {L.w[rt][ku].x, L.w[rt][ku].y, L.w[rt][ku].z, L.w[rt][ku].w};
+                    const uint32_t v = h ? (ww[2 * g2 + i] >> 8) : ww[2 * g2 + i];
+                    uint32_t b[4];
+                    b[0] = pk_add((v & 0x00030003u) | m0, nz[rt][0]);
+                    b[1] = pk_add((v & 0x000C000Cu) | m1, nz[rt][1]);
+                    b[2] = pk_add((v & 0x00300030u) | m2, nz[rt][2]);
+                    b[3] = pk_add((v & 0x00C000C0u) | m3, nz[rt][3]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++)
+                        acc[rt][mt] = mfma(a[mt], b, acc[rt][mt]);
+                }
+            }
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                out[rt][mt] += s[rt] * acc[rt][mt];
+                acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+            }
+    }
 }
 
 // One load's worth of work: dequantize, multiply with the staged x, fold finished groups.
@@ -270,9 +364,9 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
                                          int wave_row0, uint4 *lds_x, float *ms, uint8_t *mz)
 {
     typedef Chunk<MT> C;
-    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
+    constexpr int KPL = BITS == 2 ? 256 : BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
     constexpr int SPC = C::KC / KPL / KU; // steps per chunk
-    const int nload = d.K / KPL;
+    const int nload = (d.K + KPL - 1) / KPL; // 2 bits: a last load may hold one group only
     const int nstep = (nload + KU - 1) / KU;
     const int nchunk = (d.K + C::KC - 1) / C::KC;
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
@@ -300,9 +394,15 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
             // next chunk's x and metadata travel while this chunk is computed
             prefetch_chunk<BITS, MT, RT>(d, x, M, wave_row0, min(ch + 1, nchunk - 1), S);
         }
-        compute<BITS, MT, RT, 0>(st, Lcur, lds_x, ms, mz, acc, out);
-        if (st * KU + 1 < nload)
-            compute<BITS, MT, RT, 1>(st, Lcur, lds_x, ms, mz, acc, out);
+        if (BITS == 2) {
+            compute2<MT, RT, 0>(st, Lcur, lds_x, ms, mz, acc, out);
+            if (st * KU + 1 < nload)
+                compute2<MT, RT, 1>(st, Lcur, lds_x, ms, mz, acc, out);
+        } else {
+            compute<BITS, MT, RT, 0>(st, Lcur, lds_x, ms, mz, acc, out);
+            if (st * KU + 1 < nload)
+                compute<BITS, MT, RT, 1>(st, Lcur, lds_x, ms, mz, acc, out);
+        }
     };
     for (int st = 0; st < nstep; st += 2) {
         step(st, A, B);
@@ -355,15 +455,21 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
         Sel d;
         d.N = dp->N;
         d.K = dp->K;
-        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.codes = bits == 2    ? dp->codes2
+                  : bits == 4  ? dp->codes4
+                  : bits == 8  ? dp->codes8
+                  : bits == 16 ? (const uint8_t *)dp->w16
+                               : nullptr;
+        d.scales = bits == 2 ? dp->scales2 : bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 2 ? dp->zeros2 : bits == 4 ? dp->zeros4 : dp->zeros8;
         if (!d.codes)
             continue; // uniform over the workgroup
         // All wavefronts of the workgroup run the tile (rows past N are clamped on load and
         // masked on store) so that every one of them reaches the staging barriers.
         const int wave_row0 = (tile - dp->tile_begin) * TILE_ROWS + wave * RT * 16;
-        if (bits == 4)
+        if (bits == 2)
+            run_tile<2, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
+        else if (bits == 4)
             run_tile<4, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
         else if (bits == 8)
             run_tile<8, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);

@@ -162,19 +162,6 @@ def test_w8a8_validation():
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
 
-def test_plan_limits_checked_before_any_launch():
-    # a 2-bit copy cannot be part of a batched plan: refused before the table is copied to the device
-    L = fq.lib
-    p, arr = ctypes.c_void_p(), (ctypes.c_void_p * 1)
-    h = ctypes.c_void_p()
-    assert L.fq_layer_create(ctypes.byref(h), 64, 256, 128) == B.FQ_OK
-    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
-    assert L.fq_layer_attach(h, 2, FAKE, FAKE, FAKE) == B.FQ_OK
-    assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(FAKE), arr(FAKE), 4, 0x1000, 4096, None) == B.FQ_ERR_BITS
-    assert "2-bit" in fq.fq_last_error()
-    assert L.fq_layer_destroy(h) == B.FQ_OK
-
-
 def test_2bit_copy_limits():
     L = fq.lib
     assert fq.fq_packed_sizes(4096, 4096, 2) == (4096 * 4096 // 4, 4096 * 32 * 4, 4096 * 32)
@@ -182,8 +169,8 @@ def test_2bit_copy_limits():
     assert L.fq_layer_create(ctypes.byref(h), 64, 256, 128) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, FAKE, FAKE) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, None, FAKE) == B.FQ_ERR_NULL
-    assert L.fq_linear(h, 2, FAKE, 2, FAKE, None) == B.FQ_ERR_BITS  # served at M = 1 only
-    assert "M = 1" in fq.fq_last_error()
+    assert L.fq_linear(h, 2, FAKE, 33, FAKE, None) == B.FQ_ERR_BITS  # decode phase only
+    assert "decode" in fq.fq_last_error()
     assert L.fq_linear(h, 4, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
