@@ -257,7 +257,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
     fill_desc(d, layer, x_fp16, y_fp16);
     hipError_t e;
     if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
-        const int rows = M == 1 ? fq_decode_tile_rows(layer->N, layer->K, M) : fq_skinny_tile_rows(layer->N, M);
+        int rows = M == 1 ? fq_decode_tile_rows(layer->N, layer->K, M) : fq_skinny_tile_rows(layer->N, M);
+        if (M > 1 && bits == 2 && rows == 16) // the K-split kernel takes 4, 8 and 16 bits
+            rows = 64;
         const int tiles = (layer->N + rows - 1) / rows;
         e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream)
                    : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, (hipStream_t)stream);
@@ -351,6 +353,8 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         has2 = has2 || layers[i]->codes[3] != nullptr;
     if (M > 1 && has2 && rows > 128)
         rows = 128;
+    if (M > 1 && has2 && rows == 16) // nor does the K-split kernel for launches with few rows
+        rows = 64;
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;

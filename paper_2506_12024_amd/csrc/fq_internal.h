@@ -46,7 +46,7 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
 // Rows per tile (multiple of 16) for a launch that covers `total_rows` output rows.
 int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 
-// Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 64, 128 or 256.
+// Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 16 (K split), 64, 128 or 256.
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
                             int total_tiles, int tile_rows, int M, hipStream_t stream);

@@ -29,6 +29,9 @@
 // instruction and, with the weights streaming through the same caches, miss every time.
 // Both x and the metadata of chunk c + 1 are prefetched into registers while chunk c is
 // computed.
+//
+// Launches with few rows (a single linear of a few thousand rows) use a second kernel further
+// down, in which the four wavefronts of a workgroup share one row tile and split K.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -47,13 +50,16 @@ constexpr int WG_THREADS = 256;
 constexpr int WAVES = WG_THREADS / 64;
 constexpr int KU = 2; // consecutive 64-byte loads per row issued together (one 128-byte line)
 
-// k per LDS chunk of x: 1024 for up to 16 batch rows, 512 for up to 32 (32 KiB either way)
-template <int MT>
+// k per LDS chunk of x: 1024 for up to 16 batch rows, 512 for up to 32 (32 KiB either way), staged
+// by the whole workgroup.  SK (K split, below): 256 k, staged by one wavefront for itself.
+template <int MT, bool SK = false>
 struct Chunk {
-    static constexpr int KC = 1024 / MT;
-    static constexpr int GROUPS = KC / 128;  // quantization groups per chunk
-    static constexpr int GPL = GROUPS / 4;   // groups whose scale/zero one lane fetches
-    static constexpr int XPER = 16 * MT * (KC / 8) / WG_THREADS; // 16-byte x blocks per thread
+    static constexpr int KC = SK ? 256 : 1024 / MT;
+    static constexpr int STAGERS = SK ? 64 : WG_THREADS; // threads that stage one chunk
+    static constexpr int GROUPS = KC / 128;              // quantization groups per chunk
+    static constexpr int GPL = GROUPS >= 4 ? GROUPS / 4 : 1; // groups whose scale/zero one lane fetches
+    static constexpr int XPER = 16 * MT * (KC / 8) / STAGERS; // 16-byte x blocks per thread
+    static __device__ __forceinline__ int tid() { return SK ? (int)(threadIdx.x & 63) : (int)threadIdx.x; }
 };
 
 __device__ __forceinline__ uint4 load16_weights(const void *p)
@@ -86,11 +92,11 @@ struct Loaded { // one step of weights: RT row tiles x KU loads
     uint4 w[RT][KU];
 };
 
-template <int MT, int RT>
+template <int MT, int RT, class C = Chunk<MT>>
 struct Staged { // what a lane prefetches for the next chunk
-    uint4 x[Chunk<MT>::XPER];
-    float s[RT][Chunk<MT>::GPL];
-    uint32_t z[RT][Chunk<MT>::GPL];
+    uint4 x[C::XPER];
+    float s[RT][C::GPL];
+    uint32_t z[RT][C::GPL];
 };
 
 // Issue step `st`: loads 2 st and 2 st + 1 of every row tile.
@@ -127,16 +133,15 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
 // Prefetch chunk `ch` of x (this thread's blocks) and the scales / zeros of the chunk's groups
 // for this wavefront's rows: lane (n, c) fetches groups c * GPL .. of row n, so the 16 rows'
 // lines are touched once per chunk instead of once per group.
-template <int BITS, int MT, int RT>
+template <int BITS, int MT, int RT, class C = Chunk<MT>>
 __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, int M, int wave_row0,
-                                               int ch, Staged<MT, RT> &S)
+                                               int ch, Staged<MT, RT, C> &S)
 {
-    typedef Chunk<MT> C;
     constexpr int BLK = C::KC / 8;
     const int kc = ch * C::KC;
 #pragma unroll
     for (int it = 0; it < C::XPER; it++) {
-        const int idx = it * WG_THREADS + threadIdx.x;
+        const int idx = it * C::STAGERS + C::tid();
         const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
         // rows past M and k past K are clamped: those blocks only feed outputs that are
         // never stored (rows) or are never read (k)
@@ -153,7 +158,8 @@ __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, 
             const size_t row = (size_t)min(wave_row0 + rt * 16 + n, d.N - 1);
 #pragma unroll
             for (int j = 0; j < C::GPL; j++) {
-                const int g = min(ch * C::GROUPS + c * C::GPL + j, G - 1);
+                // (fewer than four groups in a chunk: the lanes past them fetch the last one again)
+                const int g = min(ch * C::GROUPS + min(c * C::GPL + j, C::GROUPS - 1), G - 1);
                 S.s[rt][j] = ((const FQ_GLOBAL float *)d.scales)[row * G + g];
                 S.z[rt][j] = ((const FQ_GLOBAL uint8_t *)d.zeros)[row * G + g];
             }
@@ -163,14 +169,13 @@ __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, 
 
 // Write a prefetched chunk to LDS: x blocks [k block][16 * MT rows] (4-bit: permuted to the
 // unpack order), scales and zeros into the wavefront's own area as [row tile][group][row].
-template <int BITS, int MT, int RT>
-__device__ __forceinline__ void commit_chunk(const Staged<MT, RT> &S, uint4 *lds_x, float *ms, uint8_t *mz)
+template <int BITS, int MT, int RT, class C = Chunk<MT>>
+__device__ __forceinline__ void commit_chunk(const Staged<MT, RT, C> &S, uint4 *lds_x, float *ms, uint8_t *mz)
 {
-    typedef Chunk<MT> C;
     constexpr int ROWS = 16 * MT, BLK = C::KC / 8;
 #pragma unroll
     for (int it = 0; it < C::XPER; it++) {
-        const int idx = it * WG_THREADS + threadIdx.x;
+        const int idx = it * C::STAGERS + C::tid();
         const int m = idx / BLK, kb = idx % BLK;
         uint4 p = S.x[it];
         if (BITS == 2) {
@@ -203,8 +208,10 @@ __device__ __forceinline__ void commit_chunk(const Staged<MT, RT> &S, uint4 *lds
 #pragma unroll
             for (int j = 0; j < C::GPL; j++) {
                 const int gl = c * C::GPL + j; // group inside the chunk
-                ms[(rt * C::GROUPS + gl) * 16 + n] = S.s[rt][j];
-                mz[(rt * C::GROUPS + gl) * 16 + n] = (uint8_t)S.z[rt][j];
+                if (gl < C::GROUPS) {
+                    ms[(rt * C::GROUPS + gl) * 16 + n] = S.s[rt][j];
+                    mz[(rt * C::GROUPS + gl) * 16 + n] = (uint8_t)S.z[rt][j];
+                }
             }
     }
 }
@@ -283,12 +290,11 @@ __device__ __forceinline__ void compute2(int st, const Loaded<RT> &L, const uint
 }
 
 // One load's worth of work: dequantize, multiply with the staged x, fold finished groups.
-template <int BITS, int MT, int RT, int ku>
+template <int BITS, int MT, int RT, int ku, class C = Chunk<MT>>
 __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4 *lds_x, const float *ms,
                                         const uint8_t *mz, float4_t (&acc)[RT][MT],
                                         float4_t (&out)[RT][MT])
 {
-    typedef Chunk<MT> C;
     constexpr int ROWS = 16 * MT;
     constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32); // k per load
     constexpr int NM = KPL / 32;                                 // MFMAs per load
@@ -427,6 +433,144 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
     }
 }
 
+// ---- K split: launches with few rows ------------------------------------------------------
+// A single linear has only N / 64 tiles of the kind above, far too few wavefronts to keep HBM busy
+// (4096 rows: 64 workgroups).  Here a workgroup owns one row tile of 16 rows and its four
+// wavefronts split K between them: wavefront w takes the chunks of 256 k with index w, w + 4, ...,
+// stages its own x and metadata in its own part of LDS (ordered by the wavefront's own instruction
+// stream: no workgroup barrier), and the four partial results meet in LDS at the end.  4, 8 and 16
+// bits (a 2-bit step is 512 k: those launches use the tiles above).
+template <int BITS, int MT>
+__device__ __forceinline__ void run_tile_sk(const Sel &d, const uint16_t *x, uint16_t *y, int M, int row0,
+                                            int wave, uint4 *lds_x, float *ms, uint8_t *mz, float4_t *red)
+{
+    typedef Chunk<MT, true> C;
+    constexpr int RT = 1;
+    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
+    constexpr int SPC = C::KC / KPL / KU; // steps per chunk: 1 / 2 / 4
+    const int nload = d.K / KPL;
+    const int nstep = (nload + KU - 1) / KU;
+    const int nchunk = (d.K + C::KC - 1) / C::KC;
+    const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+    float4_t acc[RT][MT], out[RT][MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        acc[0][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        out[0][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    Loaded<RT> A, B;
+    Staged<MT, RT, C> S;
+    int ch = wave, j = 0; // the wavefront's current chunk and step inside it
+    if (ch < nchunk) {
+        issue<BITS, RT>(d, row0, ch * SPC, nload, A);
+        prefetch_chunk<BITS, MT, RT, C>(d, x, M, row0, ch, S);
+    }
+    // One step; returns false after the wavefront's last one.
+    auto step = [&](Loaded<RT> &Lcur, Loaded<RT> &Lnext) -> bool {
+        const int st = ch * SPC + j;
+        int nch = ch, nj = j + 1;
+        if (nj == SPC || ch * SPC + nj >= nstep) {
+            nch = ch + WAVES;
+            nj = 0;
+        }
+        const bool more = nch < nchunk;
+        // Always issued (after the last step it re-reads its own item) so that the wait for Lcur
+        // can be a counted vmcnt with Lnext's loads still in flight.
+        issue<BITS, RT>(d, row0, more ? nch * SPC + nj : st, nload, Lnext);
+        if (j == 0) {
+            // the wavefront's LDS accesses execute in order: its reads of the previous chunk are
+            // done before these writes, and the reads below see them
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            commit_chunk<BITS, MT, RT, C>(S, lds_x, ms, mz);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            prefetch_chunk<BITS, MT, RT, C>(d, x, M, row0, min(ch + WAVES, nchunk - 1), S);
+        }
+        compute<BITS, MT, RT, 0, C>(st, Lcur, lds_x, ms, mz, acc, out);
+        if (st * KU + 1 < nload)
+            compute<BITS, MT, RT, 1, C>(st, Lcur, lds_x, ms, mz, acc, out);
+        ch = nch;
+        j = nj;
+        return more;
+    };
+    if (ch < nchunk) {
+        for (;;) {
+            if (!step(A, B))
+                break;
+            if (!step(B, A))
+                break;
+        }
+    }
+    // the four partial results: wavefronts 1..3 park theirs, wavefront 0 adds them up and stores
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const float4_t v = BITS == 16 ? acc[0][mt] : out[0][mt];
+        if (wave > 0)
+            red[((wave - 1) * MT + mt) * 64 + lane] = v;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
+        const int row = row0 + n;
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            float4_t v = BITS == 16 ? acc[0][mt] : out[0][mt];
+#pragma unroll
+            for (int w = 0; w < WAVES - 1; w++)
+                v += red[(w * MT + mt) * 64 + lane];
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int m = mt * 16 + c * 4 + r;
+                if (m < M && row < d.N)
+                    ((FQ_GLOBAL uint16_t *)y)[(size_t)m * d.N + row] = __builtin_bit_cast(uint16_t, (_Float16)v[r]);
+            }
+        }
+    }
+    __syncthreads(); // `red` is free again
+}
+
+template <bool SINGLE, int MT>
+__global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLinearDesc single, int bits_host,
+                                                                      const FqLinearDesc *__restrict__ table,
+                                                                      const int32_t *__restrict__ bits_dev,
+                                                                      int count, int total_tiles, int M)
+{
+    typedef Chunk<MT, true> C;
+    __shared__ uint4 lds_x[WAVES][(C::KC / 8) * 16 * MT];
+    __shared__ float lds_s[WAVES][C::GROUPS * 16];
+    __shared__ uint8_t lds_z[WAVES][C::GROUPS * 16];
+    __shared__ float4_t red[(WAVES - 1) * MT * 64];
+    const int wave = threadIdx.x >> 6;
+    int e = 0;
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+        const FqLinearDesc *dp;
+        int bits;
+        if (SINGLE) {
+            dp = &single;
+            bits = bits_host;
+        } else {
+            while (e + 1 < count && tile >= table[e + 1].tile_begin)
+                e++;
+            dp = &table[e];
+            bits = bits_dev[e];
+        }
+        Sel d;
+        d.N = dp->N;
+        d.K = dp->K;
+        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        if (!d.codes)
+            continue; // uniform over the workgroup
+        const int row0 = (tile - dp->tile_begin) * 16;
+        if (bits == 4)
+            run_tile_sk<4, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
+        else if (bits == 8)
+            run_tile_sk<8, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
+        else
+            run_tile_sk<16, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
+    }
+}
+
 template <bool SINGLE, int MT, int RT>
 __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinearDesc single,
                                                                    int bits_host,
@@ -506,6 +650,27 @@ hipError_t launch(const FqLinearDesc *single, int bits_host, const FqLinearDesc 
     return hipGetLastError();
 }
 
+template <int MT>
+hipError_t launch_sk(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
+                     const int32_t *bits_dev, int count, int total_tiles, int M, int cus, hipStream_t stream)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_skinny_sk_kernel<false, MT>, WG_THREADS, 0) !=
+            hipSuccess || per_cu < 1)
+        per_cu = 2;
+    const int cap = cus * per_cu;
+    const int grid = total_tiles < cap ? total_tiles : cap;
+    if (single) {
+        decode_skinny_sk_kernel<true, MT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1,
+                                                                        total_tiles, M);
+    } else {
+        FqLinearDesc none = {};
+        decode_skinny_sk_kernel<false, MT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count,
+                                                                         total_tiles, M);
+    }
+    return hipGetLastError();
+}
+
 int device_cus()
 {
     static int cus = 0;
@@ -521,8 +686,9 @@ int device_cus()
 
 } // namespace
 
-// Rows per workgroup tile: 64 * RT with RT in {1, 2, 4} row tiles per wavefront; the
-// largest that still gives every CU a few tiles.
+// Rows per workgroup tile: 64 * RT with RT in {1, 2, 4} row tiles per wavefront, the largest that
+// still gives every CU a few tiles; 16 (the K-split kernel) where even 64-row tiles would leave
+// CUs without work.
 int fq_skinny_tile_rows(long long total_rows, int M)
 {
     (void)M;
@@ -530,6 +696,9 @@ int fq_skinny_tile_rows(long long total_rows, int M)
     int rt = 4;
     while (rt > 1 && total_rows / (64 * rt) < want)
         rt >>= 1;
+    // (measured at M = 16: 4096 rows 16 -> 8 us with the K split, 11008 rows 16.7 -> 17.3 us)
+    if (rt == 1 && total_rows / 64 < device_cus() / 2)
+        return 16;
     return 64 * rt;
 }
 
@@ -543,6 +712,9 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
     const int rt = tile_rows / 64;
     if (!single && tile_rows == 256)
         return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+    if (tile_rows == 16)
+        return M <= 16 ? launch_sk<1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream)
+                       : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
     if (M <= 16) {
         if (rt == 4)
             return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
