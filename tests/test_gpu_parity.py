@@ -127,7 +127,9 @@ def test_linear_on_grid_weights_exact():
 
 @pytest.mark.parametrize("bits", [4, 8, 16])
 @pytest.mark.parametrize("M,N,K", [(2, 100, 1408), (4, 4096, 4096), (8, 530, 5120), (16, 64, 11008),
-                                   (17, 300, 2048), (32, 1000, 4096), (5, 37, 128), (32, 16, 13824)])
+                                   (17, 300, 2048), (32, 1000, 4096), (5, 37, 128), (32, 16, 13824),
+                                   # enough rows for the 64-row tiles (fewer rows take the K-split kernel)
+                                   (16, 11008, 1024), (24, 9000, 640)])
 def test_linear_batched_matches_oracle(bits, M, N, K):
     w = synth.weight(0, "par/linb/%dx%d" % (N, K), N, K, 0.02, outlier_p=0.001)
     x = synth.activations(0, "par/linb/x/%dx%d" % (M, K), M, K)
