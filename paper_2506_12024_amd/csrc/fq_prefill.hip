@@ -30,7 +30,8 @@
 //
 // Workgroups that share a weight slab (the M tiles of one N tile) get consecutive logical
 // ids, and logical ids are dealt to the 8 XCDs in contiguous runs, so that a slab is
-// fetched into one L2 and reused there.
+// fetched into one L2 and reused there.  The tiles an XCD has left for a last round that would
+// fill at most half of its CUs run as half tiles (128 tokens) in a second launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -50,11 +51,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int THREADS = 512;
 constexpr int WAVES = THREADS / 64;
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int WM = 128;            // tokens per wavefront (4 MFMA tiles)
+constexpr int BM_FULL = 256, BN = 256, BK = 64;
 constexpr int WN = 64;             // weight rows per wavefront (2 MFMA tiles)
 constexpr int XRB = BK * 2;        // bytes of an x row per step (128)
-constexpr int XSLAB = BM * XRB;    // 32 KiB
 
 // Byte offset of 16-byte chunk `ch` of row `r` in a slab whose rows are RB bytes long:
 // 128 / RB rows share a 128-byte line, slots XOR-ed by (line >> 1) & 7.
@@ -136,10 +135,18 @@ struct Meta {
     uint32_t z[2];
 };
 
-template <int BITS>
+// HALF: the workgroup takes half a tile, 128 tokens x 256 weight rows (a wavefront 64 tokens x 64
+// rows): the tiles left over after the last full round of workgroups are cut in two, so that they
+// keep twice as many CUs busy for half as long.  `skip`: first tile of this launch inside an XCD's
+// run of `per_xcd` tiles.
+template <int BITS, bool HALF>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
-    const FqLinearDesc d, int M, int m_tiles, int n_tiles, int per_xcd)
+    const FqLinearDesc d, int M, int m_tiles, int n_tiles, int per_xcd, int skip)
 {
+    constexpr int BM = HALF ? BM_FULL / 2 : BM_FULL; // tokens per workgroup
+    constexpr int WM = BM / 2;                       // tokens per wavefront
+    constexpr int MTL = WM / 32;                     // MFMA tiles of a wavefront along the tokens (4 or 2)
+    constexpr int XSLAB = BM * XRB;                  // 32 or 16 KiB
     constexpr int WRB = BK * BITS / 8;  // bytes of a packed weight row per step
     constexpr int WSLAB = BN * WRB;
     // Separate arrays, selected at compile time: the compiler can then tell that the operand
@@ -153,10 +160,14 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     // hardware deals consecutive workgroup ids round-robin to the 8 XCDs: give each XCD a
     // contiguous run of logical tiles
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= m_tiles * n_tiles)
+    const int in_run = skip + (HALF ? (int)(blockIdx.x >> 4) : (int)(blockIdx.x >> 3));
+    const int logical = (blockIdx.x & 7) * per_xcd + in_run;
+    if (in_run >= per_xcd || logical >= m_tiles * n_tiles)
         return;
-    const int m0 = (logical % m_tiles) * BM, n0 = (logical / m_tiles) * BN;
+    const int m0 = (logical % m_tiles) * BM_FULL + (HALF ? (int)((blockIdx.x >> 3) & 1) * BM : 0);
+    const int n0 = (logical / m_tiles) * BN;
+    if (m0 >= M)
+        return; // the second half of a last, partly filled tile
 
     const uint8_t *codes = BITS == 4 ? d.codes4 : BITS == 8 ? d.codes8 : (const uint8_t *)d.w16;
     const float *scales = BITS == 4 ? d.scales4 : d.scales8;
@@ -166,9 +177,9 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int l32 = lane & 31, c = lane >> 5;
     const int wm = (wave & 1) * WM, wn = (wave >> 1) * WN;
 
-    float16_t acc[4][2];
+    float16_t acc[MTL][2];
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < MTL; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++)
 #pragma unroll
@@ -309,9 +320,9 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            u32x4 a[4];
+            u32x4 a[MTL];
 #pragma unroll
-            for (int mt = 0; mt < 4; mt++)
+            for (int mt = 0; mt < MTL; mt++)
                 a[mt] = *reinterpret_cast<const u32x4 *>(xc + (wm + mt * 32) * XRB + aofs[i]);
 #pragma unroll
             for (int j = 0; j < 2; j++) {
@@ -339,7 +350,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     b[3] = q.w;
                 }
 #pragma unroll
-                for (int mt = 0; mt < 4; mt++)
+                for (int mt = 0; mt < MTL; mt++)
                     acc[mt][j] = mfma32(a[mt], b, acc[mt][j]);
             }
         }
@@ -384,7 +395,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     __builtin_amdgcn_s_waitcnt(0); // nothing of this kernel's is in flight past this point
     // D layout of the 32x32 MFMA: lane holds column l32, rows 8 * (v / 4) + 4 * (lane / 32) + v % 4.
 #pragma unroll
-    for (int mt = 0; mt < 4; mt++)
+    for (int mt = 0; mt < MTL; mt++)
 #pragma unroll
         for (int j = 0; j < 2; j++) {
             const int n = n0 + wn + j * 32 + l32;
@@ -400,19 +411,42 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 } // namespace
 
+template <bool HALF>
+static hipError_t launch_prefill(const FqLinearDesc &d, int bits, int M, int m_tiles, int n_tiles, int per_xcd,
+                                 int skip, int per_launch, hipStream_t stream)
+{
+    if (per_launch <= 0)
+        return hipSuccess;
+    const unsigned grid = (unsigned)per_launch * (HALF ? 16u : 8u);
+    if (bits == 4)
+        prefill_kernel<4, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);
+    else if (bits == 8)
+        prefill_kernel<8, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);
+    else
+        prefill_kernel<16, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);
+    return hipGetLastError();
+}
+
 hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t stream)
 {
-    const int m_tiles = (M + BM - 1) / BM, n_tiles = (d.N + BN - 1) / BN;
+    const int m_tiles = (M + BM_FULL - 1) / BM_FULL, n_tiles = (d.N + BN - 1) / BN;
     const long long total = (long long)m_tiles * n_tiles;
     if (total > 0x3fffffffLL)
         return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
-    const unsigned grid = (unsigned)per_xcd * 8;
-    if (bits == 4)
-        prefill_kernel<4><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd);
-    else if (bits == 8)
-        prefill_kernel<8><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd);
-    else
-        prefill_kernel<16><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd);
-    return hipGetLastError();
+    // One workgroup per CU at a time: an XCD works through its run of tiles in rounds of its CU
+    // count.  What is left for the last round, if it would fill at most half the CUs, runs as half
+    // tiles in a second launch (2048 x 28672: 112 tiles per XCD = 3 rounds of 32 + 16 tiles, which
+    // then take half a round instead of a whole one).
+    int cus = 256, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+        cus = prop.multiProcessorCount;
+    const int per_round = cus / 8 > 0 ? cus / 8 : 1;
+    const int rest = per_xcd % per_round;
+    const int tail = rest > 0 && 2 * rest <= per_round ? rest : 0;
+    hipError_t e = launch_prefill<false>(d, bits, M, m_tiles, n_tiles, per_xcd, 0, per_xcd - tail, stream);
+    if (e != hipSuccess)
+        return e;
+    return launch_prefill<true>(d, bits, M, m_tiles, n_tiles, per_xcd, per_xcd - tail, tail, stream);
 }
