@@ -35,7 +35,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
 MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993230.0 / 4978290.0,
                           # profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md
-                          ("llama7b", 16, (4, 8, 16)): 8.066 / 7.857}
+                          ("llama7b", 16, (4, 8, 16)): 8.052 / 7.857}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
 VOCAB = 32000
 SEED = 0

@@ -54,6 +54,7 @@ struct fq_plan {
     uint32_t magic;
     int count, M, total_tiles, tile_rows, max_K;
     const FqLinearDesc *table_dev;
+    int *queue_dev; // nine ints after the table: per-XCD tile cursors and a count of finished workgroups
 };
 
 namespace {
@@ -262,7 +263,7 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
             rows = 64;
         const int tiles = (layer->N + rows - 1) / rows;
         e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream)
-                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, (hipStream_t)stream);
+                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, nullptr, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
     }
@@ -313,7 +314,8 @@ size_t fq_plan_workspace_bytes(int count)
 {
     if (count < 1)
         return 0;
-    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256;
+    // the descriptor table, then 256 bytes for the tile queue of the streaming batch kernel
+    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256;
 }
 
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, const void *const *xs,
@@ -380,8 +382,11 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         return fail(FQ_ERR_HIP, "fq_plan_create: out of host memory");
     // The table is small; a synchronous-with-respect-to-host copy keeps the host vector's
     // lifetime trivial (hipMemcpyAsync from pageable memory returns after staging the source).
+    const size_t table_bytes = ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256;
     hipError_t e = hipMemcpyAsync(workspace, table.data(), (size_t)count * sizeof(FqLinearDesc),
                                   hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess) // the queue starts at zero; the kernel that uses it leaves it at zero
+        e = hipMemsetAsync((char *)workspace + table_bytes, 0, 256, (hipStream_t)stream);
     if (e == hipSuccess)
         e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) {
@@ -395,6 +400,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     p->max_K = max_K;
     p->tile_rows = rows;
     p->table_dev = (const FqLinearDesc *)workspace;
+    p->queue_dev = (int *)((char *)workspace + table_bytes);
     *out = p;
     return FQ_OK;
 }
@@ -411,7 +417,7 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
         ? fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
                            plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream)
         : fq_launch_skinny(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
-                           plan->tile_rows, plan->M, (hipStream_t)stream);
+                           plan->tile_rows, plan->M, plan->queue_dev, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

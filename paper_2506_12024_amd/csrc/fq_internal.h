@@ -49,12 +49,12 @@ int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 // Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 16 (K split), 64, 128 or 256.
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int M, hipStream_t stream);
+                            int total_tiles, int tile_rows, int M, int *queue, hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
 // Streaming variant for plan launches with 2 <= M <= 32 and tiles of 256 rows (fq_launch_skinny
 // hands those to it).
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                                   int total_tiles, int M, int cus, hipStream_t stream);
+                                   int total_tiles, int M, int cus, int *queue, hipStream_t stream);
 
 // Device-resident state of the precision scheduler (ring of PPLE values follows the header).
 struct FqSchedState {

@@ -704,14 +704,14 @@ int fq_skinny_tile_rows(long long total_rows, int M)
 
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int M, hipStream_t stream)
+                            int total_tiles, int tile_rows, int M, int *queue, hipStream_t stream)
 {
     if (total_tiles <= 0)
         return hipSuccess;
     const int cus = device_cus();
     const int rt = tile_rows / 64;
     if (!single && tile_rows == 256)
-        return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, queue, stream);
     if (tile_rows == 16)
         return M <= 16 ? launch_sk<1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream)
                        : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);

@@ -676,7 +676,10 @@ struct Loader {
     // whose pairs start at even chunks).  Chunk g + 1 is written while the consumers work on chunk
     // g, and the owner then requests chunk g + 3 at once.  Two batch tiles: each loader owns one
     // of them in every chunk and requests chunk g + 2 after writing chunk g + 1.
-    __device__ __forceinline__ void run()
+    // `after_first(lane)` is called once, after the barrier that hands over the first chunk and
+    // after this wavefront's work that follows it: the place where a loader has time to spare.
+    template <class F>
+    __device__ __forceinline__ void run(F after_first)
     {
         constexpr int STEP = MT == 1 ? 2 : 1; // distance between the chunks of one loader
         const int c0 = MT == 1 ? li : 0;
@@ -697,58 +700,109 @@ struct Loader {
                 if (g + 1 + STEP < nchunks)
                     load(g + 1 + STEP);
             }
+            if (g == 0)
+                after_first(lane);
         }
         barrier(); // the consumers have stored the tile
     }
 };
 
-// The tiles of one workgroup, as seen by its loader (LOADER) or by one of its consumers: the two
-// roles walk the same tiles in separate loops so that neither carries the other's registers.
+// One tile, as seen by a loader (ROLE = 1 + li) or by a consumer (ROLE = 0).  Returns false if the
+// entry's selected width is not attached (uniform over the workgroup: nothing is run, no barrier).
+// Loader 1 calls `after_first` (see Loader::run).
+template <int MT, int ROLE, class F>
+__device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_t *bits_dev, int count, int tile,
+                                         int &e, int M, const Lds &L, int wave, F after_first)
+{
+    while (e + 1 < count && tile >= table[e + 1].tile_begin)
+        e++;
+    const FqLinearDesc *dp = &table[e];
+    const int bits = bits_dev[e];
+    Sel d;
+    d.N = dp->N;
+    d.K = dp->K;
+    d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+    d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+    d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+    d.x = dp->x;
+    d.y = dp->y;
+    if (!d.codes)
+        return false;
+    // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
+    // that every one of them reaches the barriers: one per chunk and one at the end.
+    const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
+    if (ROLE > 0) {
+        constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
+        if constexpr (LI == 1)
+            Loader<MT, LI>(d, L, M, tile_row0, bits).run(after_first);
+        else
+            Loader<MT, LI>(d, L, M, tile_row0, bits).run([](int) {});
+    } else {
+        if (bits == 4)
+            Consumer<4, MT>(d, L, M, tile_row0, wave).run();
+        else if (bits == 8)
+            Consumer<8, MT>(d, L, M, tile_row0, wave).run();
+        else
+            Consumer<16, MT>(d, L, M, tile_row0, wave).run();
+    }
+    return true;
+}
+
+// The tiles of one workgroup: the roles walk the same tiles in separate loops so that neither
+// carries the other's registers.
+//
+// Workgroups are dealt to the 8 XCDs in turn.  Tiles are handed out so that an XCD takes runs of
+// XCD_RUN consecutive tiles: the x of a linear is then fetched into a few L2s rather than into all
+// eight, while a linear's weight rows are still spread over several XCDs (measured on the mixed 7B
+// step at batch 16: 1.362 / 1.347 / 1.348 / 1.349 / 1.351 ms for runs of 1 / 4 / 8 / 16 / 32; 8 is
+// also the best for each single width).  Within an XCD the workgroups draw their tiles from a
+// queue (`queue[xcd]`, a cursor in device memory): tiles take very different times (a fp16 tile
+// four times as long as a 4-bit one) and a fixed deal leaves the workgroups with the long ones
+// running alone at the end.  Loader 1 draws the next tile while the current one runs, at a point
+// where it would otherwise wait for the consumers (the round trip of the atomic is not hidden
+// anywhere on the way into a tile), and leaves it in LDS (`mail`): everybody reads it at the top
+// of a tile, it is replaced after the tile's first chunk barrier, and read again after the
+// barrier that ends the tile.  The last workgroup to finish (`queue[8]` counts them) puts the
+// cursors back to zero for the next launch.
 template <int MT, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
 __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
-                                          int total_tiles, int M, const Lds &L, int wave)
+                                          int total_tiles, int M, const Lds &L, int wave, int *queue, int *mail)
 {
-    const int grid = gridDim.x;
-    // Workgroups are dealt to the 8 XCDs in turn.  Tiles are handed out so that an XCD takes runs
-    // of XCD_RUN consecutive tiles: the x of a linear is then fetched into a few L2s rather than
-    // into all eight, while a linear's weight rows are still spread over several XCDs (measured
-    // on the mixed 7B step at batch 16: 1.362 / 1.347 / 1.348 / 1.349 / 1.351 ms for runs of
-    // 1 / 4 / 8 / 16 / 32; 8 is also the best for each single width).
     constexpr int XCD_RUN = 8;
-    int first = blockIdx.x;
-    if (grid % (8 * XCD_RUN) == 0) {
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        first = ((slot / XCD_RUN) * 8 + xcd) * XCD_RUN + slot % XCD_RUN;
-    }
+    const int grid = gridDim.x;
     int e = 0;
-    for (int tile = first; tile < total_tiles; tile += grid) {
-        while (e + 1 < count && tile >= table[e + 1].tile_begin)
-            e++;
-        const FqLinearDesc *dp = &table[e];
-        const int bits = bits_dev[e];
-        Sel d;
-        d.N = dp->N;
-        d.K = dp->K;
-        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
-        d.x = dp->x;
-        d.y = dp->y;
-        if (!d.codes)
-            continue; // uniform over the workgroup
-        // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
-        // that every one of them reaches the barriers: one per chunk and one at the end.
-        const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
-        if (ROLE > 0) {
-            constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
-            Loader<MT, LI>(d, L, M, tile_row0, bits).run();
-        } else {
-            if (bits == 4)
-                Consumer<4, MT>(d, L, M, tile_row0, wave).run();
-            else if (bits == 8)
-                Consumer<8, MT>(d, L, M, tile_row0, wave).run();
-            else
-                Consumer<16, MT>(d, L, M, tile_row0, wave).run();
+    if (!queue || grid % (8 * XCD_RUN) != 0) { // no queue: a fixed deal
+        for (int tile = blockIdx.x; tile < total_tiles; tile += grid)
+            run_tile<MT, ROLE>(table, bits_dev, count, tile, e, M, L, wave, [](int) {});
+        return;
+    }
+    const int xcd = blockIdx.x & 7;
+    auto draw = [&](int lane) { // the XCD's next tile: its q-th is tile q % XCD_RUN of its run number q / XCD_RUN
+        if (lane == 0) {
+            const int q = __hip_atomic_fetch_add(&queue[xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *(volatile int *)mail = ((q / XCD_RUN) * 8 + xcd) * XCD_RUN + q % XCD_RUN;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): written before this wavefront's next barrier
+    };
+    if (ROLE == 2)
+        draw(threadIdx.x & 63);
+    __syncthreads();
+    for (;;) {
+        const int tile = __builtin_amdgcn_readfirstlane(*(volatile int *)mail);
+        if (tile >= total_tiles)
+            break;
+        if (!run_tile<MT, ROLE>(table, bits_dev, count, tile, e, M, L, wave, draw)) {
+            __syncthreads(); // a tile that is passed over: everybody has read, then the next one is drawn
+            if (ROLE == 2)
+                draw(threadIdx.x & 63);
+            __syncthreads();
+        }
+    }
+    if (ROLE == 2 && (threadIdx.x & 63) == 0) {
+        const int done = __hip_atomic_fetch_add(&queue[8], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == grid - 1) { // every workgroup has drawn its last tile
+            for (int i = 0; i <= 8; i++)
+                __hip_atomic_store(&queue[i], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -756,8 +810,9 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
 template <int MT>
 __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev, int count,
-                                                                int total_tiles, int M)
+                                                                int total_tiles, int M, int *queue)
 {
+    __shared__ int mail[1];
     __shared__ __attribute__((aligned(1024))) uint8_t ring[CONSUMERS * NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t x0[16 * MT * KC * 2], x1[16 * MT * KC * 2];
     __shared__ __attribute__((aligned(256))) float ms0[UP * TILE_ROWS], ms1[UP * TILE_ROWS];
@@ -769,25 +824,26 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
     L.mz[0] = mz0, L.mz[1] = mz1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave == CONSUMERS)
-        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
     else if (wave > CONSUMERS)
-        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
     else
-        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave);
+        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
 }
 
 } // namespace
 
 // A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
-// tiles of 256 rows.
+// tiles of 256 rows.  `queue`: nine zeroed ints in device memory that belong to the plan (the
+// kernel leaves them zeroed), or null for a fixed deal of the tiles.
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
-                                   int M, int cus, hipStream_t stream)
+                                   int M, int cus, int *queue, hipStream_t stream)
 {
     // one workgroup per CU (LDS): persistent over the tiles
     const int grid = total_tiles < cus ? total_tiles : cus;
     if (M <= 16)
-        decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
+        decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue);
     else
-        decode_stream_kernel<2><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M);
+        decode_stream_kernel<2><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue);
     return hipGetLastError();
 }

@@ -119,3 +119,41 @@ def test_streaming_plan_integer_case_exact(M):
         expect = (xs_np[i].astype(np.float64) @ w.astype(np.float64).T)
         assert np.abs(expect).max() < 2048
         assert np.array_equal(ys[i].cpu().numpy().astype(np.float64), expect), (i, pattern[i], shapes[i])
+
+
+def test_streaming_plan_skipped_entries_and_repeated_runs():
+    # entries whose bit-width is none of the attached ones are passed over (y untouched) and the
+    # tiles after them still run; launches follow one another without anything being reset by
+    # the host in between (the kernel hands out its tiles from a queue it leaves at zero)
+    M = 16
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(
+        M, "par/stream/skip", lambda i, N, K: synth.weight(0, "par/stream/skip/w%d" % i, N, K, 0.02))
+    n = len(layers)
+    patterns = [
+        [0 if i % 5 == 0 or i == n - 1 else (4, 8, 16)[i % 3] for i in range(n)],
+        [0] * n,
+        [3 if i % 2 else (16, 4, 8)[i % 3] for i in range(n)],
+        [(8, 16, 4)[i % 3] for i in range(n)],
+    ]
+    for p, pattern in enumerate(patterns):
+        for y in ys:
+            y.fill_(7.0)
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        checked = 0
+        for i, b in enumerate(pattern):
+            y = ys[i].cpu().numpy()
+            if b not in (4, 8, 16):
+                assert np.all(y == np.float16(7.0)), (p, i, b)
+                continue
+            assert np.isfinite(y.astype(np.float32)).all(), (p, i, b)
+            if checked >= 6 and i < n - 3:
+                continue
+            checked += 1
+            w, packed = packs[i]
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(y, y_ref) <= TOL_Y, (p, i, b, shapes[i])
