@@ -68,7 +68,7 @@ class Stack:
         self.layers, self.xs, self.ys, self.keep = [], [], [], []
         t0 = time.time()
         for li in range(n_layers):
-            for mname, K, N in synth.llama_linears(hidden, ffn):
+            for mname, K, N in synth.llama_linears(hidden, ffn, synth.KV_WIDTH.get(name)):
                 w = synth.weight(SEED, self.wname(li, mname), N, K, std, outlier_p=outl)
                 w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
                 layer = fq.Layer(N, K)

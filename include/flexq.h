@@ -63,6 +63,7 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 
 #define FQ_GROUP 128      /* the only group size the kernels are built for */
 #define FQ_MAX_DECODE_M 32 /* rows of x served by the skinny (decode) kernels */
+#define FQ_MAX_DECODE_K 32768 /* longest row they take (a row of x stays in LDS at M = 1) */
 #define FQ_MAX_LM_HEAD_M 4 /* rows of x served by fq_lm_head_entropy */
 
 /* Message describing the calling thread's most recent error ("" if none). */
@@ -133,12 +134,12 @@ int fq_layer_destroy(fq_layer *layer);
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
  * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 2 is
- * served in the decode phase only (M <= FQ_MAX_DECODE_M and K within the decode kernels' limit):
+ * served in the decode phase only (M <= FQ_MAX_DECODE_M and K <= FQ_MAX_DECODE_K):
  * FQ_ERR_BITS otherwise.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)
- * 1 <= M <= FQ_MAX_DECODE_M selects the memory-bound skinny kernels; larger M
- * (prefill-shaped, any M >= 1) runs the MFMA dequant-GEMM.
+ * 1 <= M <= FQ_MAX_DECODE_M with K <= FQ_MAX_DECODE_K selects the memory-bound skinny
+ * kernels; anything else (prefill-shaped, any M >= 1) runs the MFMA dequant-GEMM.
  */
 int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
               void *y_fp16, void *stream);
@@ -146,7 +147,7 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
 /*
  * A plan runs `count` linears with ONE launch: entry i computes
  * ys[i] = linear(layers[i], bits[i], xs[i]) with the same M (1..FQ_MAX_DECODE_M)
- * for all.  The entries must be independent of each other within one run (no
+ * for all and every K <= FQ_MAX_DECODE_K (FQ_ERR_SHAPE otherwise).  The entries must be independent of each other within one run (no
  * ys[i] may alias an xs[j]).  The bit-width of every entry is read by the kernel
  * from DEVICE memory at run time, so the per-token precision pattern of
  * Sec. 4.4 / Alg. 1 can be written by another kernel or a small copy and the

@@ -33,8 +33,9 @@ int hip_fail(hipError_t e, const char *what)
 
 constexpr uint32_t LAYER_MAGIC = 0x46514C59u; // "FQLY"
 constexpr uint32_t PLAN_MAGIC = 0x4651504Cu;  // "FQPL"
-// The decode kernels keep one row of x (plus its slice sums) in LDS.
-constexpr int MAX_DECODE_K = 24576;
+// The batch-1 decode kernel keeps one row of x (plus its slice sums) in LDS: 72 KiB at this K, two
+// workgroups per CU.  The widest row of the models the paper runs is 28672 (Llama-70B's FFN).
+constexpr int MAX_DECODE_K = FQ_MAX_DECODE_K;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

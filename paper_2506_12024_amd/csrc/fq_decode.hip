@@ -38,6 +38,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/flexq.h"
 #include "fq_internal.h"
 
 namespace {
@@ -680,6 +681,24 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
     if (total_tiles <= 0)
         return hipSuccess;
     const size_t lds = lds_bytes_for(max_K);
+    if (lds > 48 * 1024) { // above the default limit of dynamic LDS: raised once per device
+        static bool raised[64];
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess)
+            return e;
+        if (dev < 0 || dev >= 64 || !raised[dev]) {
+            const int most = (int)lds_bytes_for(FQ_MAX_DECODE_K);
+            e = hipFuncSetAttribute((const void *)decode_m1_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute((const void *)decode_m1_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        most);
+            if (e != hipSuccess)
+                return e;
+            if (dev >= 0 && dev < 64)
+                raised[dev] = true;
+        }
+    }
     const int cap = resident_workgroups(lds);
     // A plan cuts its total cost into one equal slice per workgroup.  Two workgroups per CU
     // (8 wavefronts, each with eight 128-bit loads per lane in flight) stream measurably

@@ -104,9 +104,11 @@ def choice(seed: int, name: str, count: int, choices, *, first: int = 0) -> np.n
 # Workload recipes (shapes only; no arithmetic of the method).
 # ---------------------------------------------------------------------------
 
-def llama_linears(hidden: int, ffn: int):
-    """(name, K, N) of the seven linears of one Llama-style decoder layer."""
-    return [("q", hidden, hidden), ("k", hidden, hidden), ("v", hidden, hidden),
+def llama_linears(hidden: int, ffn: int, kv: int | None = None):
+    """(name, K, N) of the seven linears of one Llama-style decoder layer; `kv`: width of the key
+    and value projections where it is smaller than the hidden size (grouped-query attention)."""
+    kv = hidden if kv is None else kv
+    return [("q", hidden, hidden), ("k", hidden, kv), ("v", hidden, kv),
             ("o", hidden, hidden), ("gate", hidden, ffn), ("up", hidden, ffn),
             ("down", ffn, hidden)]
 
@@ -115,7 +117,9 @@ STACKS = {
     # name: (layers, hidden, ffn, weight std, outlier probability)
     "llama7b": (32, 4096, 11008, 0.02, 0.0),
     "llama13b": (40, 5120, 13824, 0.02, 0.001),
+    "llama70b": (80, 8192, 28672, 0.015, 0.0),
 }
+KV_WIDTH = {"llama70b": 1024}  # grouped-query attention: 8 key/value heads of 128
 
 
 def weight(seed: int, name: str, N: int, K: int, std: float, outlier_p: float = 0.0,

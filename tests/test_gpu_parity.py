@@ -229,9 +229,58 @@ def test_linear_prefill_integer_case_exact():
         assert np.array_equal(y.view(np.uint16), expect.view(np.uint16)), (bits, M, N, K)
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+@pytest.mark.parametrize("M,N,K", [(1, 200, 28672), (1, 70, 32768), (1, 33, 24704), (4, 100, 28672), (16, 300, 32768),
+                                   (32, 64, 28672), (16, 4200, 28672)])
+def test_linear_wide_rows_match_oracle(bits, M, N, K):
+    # the widest rows the decode kernels take (Llama-70B's FFN is 28672 wide; the limit is 32768):
+    # at batch 1 the whole row of x sits in LDS, above the default limit of dynamic LDS
+    w = synth.weight(0, "par/wide/%dx%d" % (N, K), N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/wide/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (bits,))
+    y = gpu_linear(layer, bits, x)
+    if bits == 16:
+        y_ref = oracle.linear(x, w, None, None, 16)
+    else:
+        c, s, z = (t.cpu().numpy() for t in packed[bits])
+        y_ref = oracle.linear(x, c, s, z, bits)
+    assert not np.isnan(y.astype(np.float32)).any()
+    for m in range(M):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_plan_wide_rows_match_oracle():
+    shapes = [(300, 28672), (128, 4096), (90, 32768), (520, 28672), (64, 128)]
+    pattern = [4, 8, 16, 8, 4]
+    for M in (1, 8):
+        layers, packs, xs_np, xs, ys = [], [], [], [], []
+        for i, (N, K) in enumerate(shapes):
+            w = synth.weight(0, "par/wideplan/w%d" % i, N, K, 0.015, outlier_p=0.001)
+            layer, packed = make_layer(w, (4, 8, 16))
+            layers.append(layer)
+            packs.append((w, packed))
+            xs_np.append(synth.activations(0, "par/wideplan/x%d/%d" % (i, M), M, K))
+            xs.append(to_dev(xs_np[-1]))
+            ys.append(torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV))
+        ws = torch.empty(fq.Plan.workspace_bytes(len(layers)), dtype=torch.uint8, device=DEV)
+        plan = fq.Plan(layers, xs, ys, M, ws)
+        for shift in range(3):
+            bits = [pattern[(i + shift) % 5] for i in range(5)]
+            plan.run(torch.tensor(bits, dtype=torch.int32, device=DEV))
+            torch.cuda.synchronize()
+            for i, b in enumerate(bits):
+                w, packed = packs[i]
+                if b == 16:
+                    y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+                else:
+                    c, s, z = (t.cpu().numpy() for t in packed[b])
+                    y_ref = oracle.linear(xs_np[i], c, s, z, b)
+                assert rel_err(ys[i].cpu().numpy(), y_ref) <= TOL_Y, (M, shift, i, b)
+
+
 def test_decode_call_with_large_k_takes_the_gemm_path():
-    # K beyond what the decode kernels keep in LDS: batch-1 still works (GEMM path)
-    N, K = 48, 28672
+    # K beyond what the decode kernels take: batch-1 still works (GEMM path)
+    N, K = 48, 32768 + 128
     w = synth.weight(0, "par/bigk/w", N, K, 0.015)
     x = synth.activations(0, "par/bigk/x", 2, K)
     layer, packed = make_layer(w, (4,))

@@ -22,7 +22,7 @@ MIN_ROWS = 1024 * 256  # what the dispatcher asks for before it uses 256-row til
 
 # rows longer than one block of scales (32 units): two and three whole blocks, a block and one
 # unit, one and a half, and a chunk count that is odd (the last pair of chunks is a single one)
-LONG = [(600, 8192), (300, 12288), (520, 4224), (700, 6144), (280, 4608)]
+LONG = [(600, 8192), (300, 12288), (520, 4224), (700, 6144), (280, 4608), (300, 28672), (270, 32768)]
 
 
 def _build(M, tag, weight_fn, extra=()):
