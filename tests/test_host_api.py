@@ -85,6 +85,24 @@ def test_layer_and_linear_validation():
     assert L.fq_layer_destroy(None) == B.FQ_ERR_NULL
 
 
+def test_plan_refuses_rows_beyond_the_decode_limit():
+    text = open(os.path.join(ROOT, "include", "flexq.h")).read()
+    limit = int(re.search(r"#define\s+FQ_MAX_DECODE_K\s+(\d+)", text).group(1))
+    assert limit == 32768
+    L, FAKE = fq.lib, 0x1000
+    arr = (ctypes.c_void_p * 1)
+    for K, want in ((limit, B.FQ_OK), (limit + 128, B.FQ_ERR_SHAPE)):
+        h, p = ctypes.c_void_p(), ctypes.c_void_p()
+        assert L.fq_layer_create(ctypes.byref(h), 64, K, 128) == B.FQ_OK
+        assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
+        if want == B.FQ_OK:  # creating the plan would copy its table to the device
+            assert L.fq_layer_destroy(h) == B.FQ_OK
+            continue
+        assert L.fq_plan_create(ctypes.byref(p), 1, arr(h), arr(FAKE), arr(FAKE), 1, 0x1000, 4096, None) == want
+        assert "decode limit" in fq.fq_last_error()
+        assert L.fq_layer_destroy(h) == B.FQ_OK
+
+
 def test_entropy_validation():
     L = fq.lib
     assert L.fq_entropy_kl(FAKE, None, 1, 0, FAKE, None, None) == B.FQ_ERR_SHAPE
