@@ -727,13 +727,13 @@ def main():
         "config": {"workload": "%s decode stack, batch %d, per-layer bits drawn from {%s} per token, "
                                "%d linears + entropy/KL over %d logits per step"
                                % (args.stack, args.batch, args.bits, len(stack.layers), VOCAB),
-                   "launches_per_step": 2, "build_seconds": round(stack.build_seconds, 1)},
+                   "launches_per_step": 2 if args.batch == 1 else (4 if 2 in bit_choices else 3), "build_seconds": round(stack.build_seconds, 1)},
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
         "entropy_kl_us": ent_us,
         "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else
-                                                                      "decode_skinny_kernel" if 2 in bit_choices
-                                                                      else "decode_stream_kernel"),
+                                                                      "decode_stream_kernel + decode_skinny_kernel"
+                                                                      if 2 in bit_choices else "decode_stream_kernel"),
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": alg_bytes * MEASURED_TRAFFIC_RATIO[(args.stack, args.batch, bit_choices)]

@@ -154,15 +154,16 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  * same plan (and a HIP graph holding it) serves every pattern.
  *   workspace  device memory of fq_plan_workspace_bytes(count) bytes, 256-byte
  *              aligned, owned by the caller, must outlive the plan; the
- *              descriptor table is copied into it on `stream` by fq_plan_create.  Its last
- *              256 bytes are the tile queue of the streaming batch kernel, zeroed by
- *              fq_plan_create and left zeroed by every run: runs of one plan must not
- *              overlap in time (they would share the queue, and they write the same ys)
+ *              descriptor table is copied into it on `stream` by fq_plan_create.  After the
+ *              table come the tile queue of the streaming batch kernel, zeroed by
+ *              fq_plan_create and left zeroed by every run, and the lists of entries a run
+ *              draws up for its bit-widths: runs of one plan must not overlap in time
+ *              (they would share these, and they write the same ys)
  *   bits_dev   device, int32 [count], each 2, 4, 8 or 16 and attached to its layer;
  *              an entry whose value is anything else is skipped by the kernel
- *              and its y is left untouched.  A plan with M > 1 whose layers carry a
- *              2-bit copy runs on the register-fed batch kernel (the streaming one for
- *              large plans takes 4, 8 and 16 bits)
+ *              and its y is left untouched.  A large plan with M > 1 whose layers carry
+ *              2-bit copies runs as two kernels (the streaming batch kernel takes 4, 8 and
+ *              16 bits; the entries that are at 2 bits follow on the register-fed one)
  */
 size_t fq_plan_workspace_bytes(int count);
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers,

@@ -54,8 +54,10 @@ struct fq_layer {
 struct fq_plan {
     uint32_t magic;
     int count, M, total_tiles, tile_rows, max_K;
+    int total_tiles2; // 128-row tiles of the second pass of a split batched plan, else 0
     const FqLinearDesc *table_dev;
-    int *queue_dev; // nine ints after the table: per-XCD tile cursors and a count of finished workgroups
+    int *queue_dev;  // after the table: per-XCD tile cursors, a count of finished workgroups, list totals
+    void *order_dev; // after the queue: two lists of two ints per entry
 };
 
 namespace {
@@ -264,7 +266,7 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
             rows = 64;
         const int tiles = (layer->N + rows - 1) / rows;
         e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream)
-                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, nullptr, (hipStream_t)stream);
+                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, nullptr, nullptr, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
     }
@@ -315,8 +317,9 @@ size_t fq_plan_workspace_bytes(int count)
 {
     if (count < 1)
         return 0;
-    // the descriptor table, then 256 bytes for the tile queue of the streaming batch kernel
-    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256;
+    // the descriptor table, then 256 bytes for the tile queue of the streaming batch kernel and two
+    // lists of 8 bytes per entry: what a launch runs under its bit-widths
+    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256 + ((size_t)count * 16 + 255) / 256 * 256;
 }
 
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, const void *const *xs,
@@ -349,15 +352,17 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     if (max_K > MAX_DECODE_K)
         return fail(FQ_ERR_SHAPE, "fq_plan_create: K=%d exceeds the decode limit %d", max_K, MAX_DECODE_K);
     int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
-    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits: a plan that holds a
-    // 2-bit copy, whose entries may be switched to it at any token, stays with the register-fed kernel.
+    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits and passes over
+    // every entry at another width: a plan of its size that holds a 2-bit copy, whose entries may be
+    // switched to it at any token, runs in two launches, the second one the register-fed kernel over
+    // the entries that are at 2 bits, in 128-row tiles of a numbering of their own.
     bool has2 = false;
     for (int i = 0; i < count; i++)
         has2 = has2 || layers[i]->codes[3] != nullptr;
-    if (M > 1 && has2 && rows > 128)
-        rows = 128;
-    if (M > 1 && has2 && rows == 16) // nor does the K-split kernel for launches with few rows
+    const bool split = M > 1 && has2 && rows == 256;
+    if (M > 1 && has2 && rows == 16) // the K-split kernel for launches with few rows has no 2-bit path
         rows = 64;
+    long long tiles2 = 0;
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;
@@ -373,9 +378,11 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
         table[(size_t)i].tile_begin = (int)tiles;
         tiles += (layers[i]->N + rows - 1) / rows;
+        if (split)
+            tiles2 += (layers[i]->N + 127) / 128;
         if (layers[i]->K > max_K)
             max_K = layers[i]->K;
-        if (tiles > 0x7fffffffLL)
+        if (tiles > 0x7fffffffLL || tiles2 > 0x7fffffffLL)
             return fail(FQ_ERR_SHAPE, "fq_plan_create: too many row tiles");
     }
     fq_plan *p = new (std::nothrow) fq_plan();
@@ -398,10 +405,12 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     p->count = count;
     p->M = M;
     p->total_tiles = (int)tiles;
+    p->total_tiles2 = (int)tiles2;
     p->max_K = max_K;
     p->tile_rows = rows;
     p->table_dev = (const FqLinearDesc *)workspace;
     p->queue_dev = (int *)((char *)workspace + table_bytes);
+    p->order_dev = (char *)workspace + table_bytes + 256;
     *out = p;
     return FQ_OK;
 }
@@ -418,7 +427,10 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
         ? fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
                            plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream)
         : fq_launch_skinny(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
-                           plan->tile_rows, plan->M, plan->queue_dev, (hipStream_t)stream);
+                           plan->tile_rows, plan->M, plan->queue_dev, plan->order_dev, (hipStream_t)stream);
+    if (e == hipSuccess && plan->total_tiles2 > 0)
+        e = fq_launch_skinny_second(plan->table_dev, bits_dev, plan->count, plan->total_tiles2, plan->M,
+                                    plan->queue_dev, plan->order_dev, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

@@ -16,7 +16,7 @@ struct FqLinearDesc {
     const float *scales8;
     const uint8_t *zeros8;
     const uint16_t *w16;    // fp16 [N][K] or null
-    const uint8_t *codes2;  // [N][K/4] or null (served by the M = 1 kernel only)
+    const uint8_t *codes2;  // [N][K/4] or null (not served by the streaming batch kernel and the GEMM)
     const float *scales2;
     const uint8_t *zeros2;
     const uint16_t *x;      // fp16 [M][K]
@@ -49,12 +49,21 @@ int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 // Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 16 (K split), 64, 128 or 256.
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int M, int *queue, hipStream_t stream);
+                            int total_tiles, int tile_rows, int M, int *queue, void *order, hipStream_t stream);
+// Second pass of a split batched plan: the entries whose bit-width is 2, in 128-row tiles, as
+// listed by plan_order_kernel in the launch of the streaming kernel before it (`queue`, `order`:
+// the plan's; total_tiles2: the most there can be).
+hipError_t fq_launch_skinny_second(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
+                                   int total_tiles2, int M, const int *queue, const void *order, hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
 // Streaming variant for plan launches with 2 <= M <= 32 and tiles of 256 rows (fq_launch_skinny
 // hands those to it).
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                                   int total_tiles, int M, int cus, int *queue, hipStream_t stream);
+                                   int total_tiles, int M, int cus, int *queue, void *order, hipStream_t stream);
+// The plan's queue words (ints): a tile cursor per XCD, the count of workgroups that have finished,
+// then what plan_order_kernel leaves for the launches that follow it: tiles and entries of the
+// streaming kernel's list, tiles and entries of the second pass's list.
+constexpr int FQ_Q_DONE = 8, FQ_Q_TILES = 9, FQ_Q_ENTRIES = 10;
 
 // Device-resident state of the precision scheduler (ring of PPLE values follows the header).
 struct FqSchedState {

@@ -707,15 +707,14 @@ struct Loader {
     }
 };
 
-// One tile, as seen by a loader (ROLE = 1 + li) or by a consumer (ROLE = 0).  Returns false if the
-// entry's selected width is not attached (uniform over the workgroup: nothing is run, no barrier).
-// Loader 1 calls `after_first` (see Loader::run).
+// One tile (rows 256 t .. of entry e), as seen by a loader (ROLE = 1 + li) or by a consumer
+// (ROLE = 0).  Returns false if the entry's selected width is not one of this kernel's or not
+// attached (uniform over the workgroup: nothing is run, no barrier).  Loader 1 calls
+// `after_first` (see Loader::run).
 template <int MT, int ROLE, class F>
-__device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_t *bits_dev, int count, int tile,
-                                         int &e, int M, const Lds &L, int wave, F after_first)
+__device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_t *bits_dev, int e, int t, int M,
+                                         const Lds &L, int wave, F after_first)
 {
-    while (e + 1 < count && tile >= table[e + 1].tile_begin)
-        e++;
     const FqLinearDesc *dp = &table[e];
     const int bits = bits_dev[e];
     Sel d;
@@ -730,7 +729,7 @@ __device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_
         return false;
     // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
     // that every one of them reaches the barriers: one per chunk and one at the end.
-    const int tile_row0 = (tile - dp->tile_begin) * TILE_ROWS;
+    const int tile_row0 = t * TILE_ROWS;
     if (ROLE > 0) {
         constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
         if constexpr (LI == 1)
@@ -758,29 +757,56 @@ __device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_
 // also the best for each single width).  Within an XCD the workgroups draw their tiles from a
 // queue (`queue[xcd]`, a cursor in device memory): tiles take very different times (a fp16 tile
 // four times as long as a 4-bit one) and a fixed deal leaves the workgroups with the long ones
-// running alone at the end.  Loader 1 draws the next tile while the current one runs, at a point
-// where it would otherwise wait for the consumers (the round trip of the atomic is not hidden
-// anywhere on the way into a tile), and leaves it in LDS (`mail`): everybody reads it at the top
-// of a tile, it is replaced after the tile's first chunk barrier, and read again after the
-// barrier that ends the tile.  The last workgroup to finish (`queue[8]` counts them) puts the
-// cursors back to zero for the next launch.
+// running alone at the end.  The queue runs over the tiles of the entries this kernel serves at
+// this launch's bit-widths, in table order, as listed by plan_order_kernel just before the launch
+// (entries at a width that is not attached, or at 2 bits, which another kernel runs, cost
+// nothing).  Loader 1 draws the next tile while the current one runs, at a point where it would
+// otherwise wait for the consumers (the round trip of the atomic is not hidden anywhere on the
+// way into a tile), looks up its entry, and leaves both in LDS (`mail`): everybody reads them at
+// the top of a tile, they are replaced after the tile's first chunk barrier, and read again
+// after the barrier that ends the tile.  The last workgroup to finish puts the cursors back to
+// zero for the next launch.
 template <int MT, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
 __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
-                                          int total_tiles, int M, const Lds &L, int wave, int *queue, int *mail)
+                                          int total_tiles, int M, const Lds &L, int wave, int *queue,
+                                          const int2 *order, int *mail)
 {
     constexpr int XCD_RUN = 8;
     const int grid = gridDim.x;
-    int e = 0;
-    if (!queue || grid % (8 * XCD_RUN) != 0) { // no queue: a fixed deal
-        for (int tile = blockIdx.x; tile < total_tiles; tile += grid)
-            run_tile<MT, ROLE>(table, bits_dev, count, tile, e, M, L, wave, [](int) {});
+    if (!queue) { // no queue: a fixed deal in the order of the table
+        int e = 0;
+        for (int tile = blockIdx.x; tile < total_tiles; tile += grid) {
+            while (e + 1 < count && tile >= table[e + 1].tile_begin)
+                e++;
+            run_tile<MT, ROLE>(table, bits_dev, e, tile - table[e].tile_begin, M, L, wave, [](int) {});
+        }
         return;
     }
     const int xcd = blockIdx.x & 7;
-    auto draw = [&](int lane) { // the XCD's next tile: its q-th is tile q % XCD_RUN of its run number q / XCD_RUN
-        if (lane == 0) {
-            const int q = __hip_atomic_fetch_add(&queue[xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            *(volatile int *)mail = ((q / XCD_RUN) * 8 + xcd) * XCD_RUN + q % XCD_RUN;
+    const int listed_tiles = queue[FQ_Q_TILES], entries = queue[FQ_Q_ENTRIES];
+    auto draw = [&](int lane) { // whole wavefront
+        int q = 0;
+        if (lane == 0)
+            q = __hip_atomic_fetch_add(&queue[xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        q = __builtin_amdgcn_readfirstlane(q);
+        // the XCD's q-th tile: tile q % XCD_RUN of its run number q / XCD_RUN
+        const int v = ((q / XCD_RUN) * 8 + xcd) * XCD_RUN + q % XCD_RUN;
+        if (v >= listed_tiles) {
+            if (lane == 0)
+                *(volatile int *)mail = -1;
+        } else {
+            for (int base = 0; base < entries; base += 64) { // the entry whose tiles [first, next first) hold v
+                const int r = base + lane;
+                const int2 o = r < entries ? order[r] : make_int2(0x7fffffff, 0);
+                const int next = r + 1 < entries ? order[r + 1].x : listed_tiles;
+                const bool hit = r < entries && o.x <= v && v < next;
+                if (hit) {
+                    ((volatile int *)mail)[0] = o.y;
+                    ((volatile int *)mail)[1] = v - o.x;
+                }
+                if (__ballot(hit))
+                    break;
+            }
         }
         __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): written before this wavefront's next barrier
     };
@@ -788,10 +814,11 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
         draw(threadIdx.x & 63);
     __syncthreads();
     for (;;) {
-        const int tile = __builtin_amdgcn_readfirstlane(*(volatile int *)mail);
-        if (tile >= total_tiles)
+        const int e = __builtin_amdgcn_readfirstlane(((volatile int *)mail)[0]);
+        const int t = __builtin_amdgcn_readfirstlane(((volatile int *)mail)[1]);
+        if (e < 0)
             break;
-        if (!run_tile<MT, ROLE>(table, bits_dev, count, tile, e, M, L, wave, draw)) {
+        if (!run_tile<MT, ROLE>(table, bits_dev, e, t, M, L, wave, draw)) {
             __syncthreads(); // a tile that is passed over: everybody has read, then the next one is drawn
             if (ROLE == 2)
                 draw(threadIdx.x & 63);
@@ -799,20 +826,90 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
         }
     }
     if (ROLE == 2 && (threadIdx.x & 63) == 0) {
-        const int done = __hip_atomic_fetch_add(&queue[8], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int done = __hip_atomic_fetch_add(&queue[FQ_Q_DONE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (done == grid - 1) { // every workgroup has drawn its last tile
-            for (int i = 0; i <= 8; i++)
+            for (int i = 0; i <= FQ_Q_DONE; i++)
                 __hip_atomic_store(&queue[i], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+}
+
+// Inclusive scan over the 256 threads of plan_order_kernel; `total` returns the sum.
+__device__ __forceinline__ int scan256(int v, int *tmp, int &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off, 64);
+        if (lane >= off)
+            v += o;
+    }
+    __syncthreads(); // tmp may still be read from a previous call
+    if (lane == 63)
+        tmp[wave] = v;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        all += tmp[w];
+        if (w < wave)
+            before += tmp[w];
+    }
+    total = all;
+    return v + before;
+}
+
+// What a batched plan launch runs under this launch's bit-widths, in table order: list 0 the entries
+// at 4, 8 or 16 bits whose copy is attached, in 256-row tiles (the streaming kernel's), list 1 the
+// entries at 2 bits, in 128-row tiles (the register-fed kernel's second pass).  order[l][r] = (first
+// tile of the list's r-th entry, entry); queue[FQ_Q_TILES + 2 l] = tiles of the list,
+// queue[FQ_Q_ENTRIES + 2 l] = its entries.  One workgroup.
+__global__ __launch_bounds__(256) void plan_order_kernel(const FqLinearDesc *__restrict__ table,
+                                                         const int32_t *__restrict__ bits_dev, int count, int *queue,
+                                                         int2 *order0, int2 *order1)
+{
+    __shared__ int tmp[4];
+    int first_tile[2] = {0, 0}, first_rank[2] = {0, 0};
+    for (int base = 0; base < count; base += 256) {
+        const int e = base + threadIdx.x;
+        int list = -1, tiles = 0;
+        if (e < count) {
+            const FqLinearDesc &d = table[e];
+            const int bits = bits_dev[e];
+            if ((bits == 16 && d.w16) || (bits == 8 && d.codes8) || (bits == 4 && d.codes4)) {
+                list = 0;
+                tiles = (d.N + TILE_ROWS - 1) / TILE_ROWS;
+            } else if (bits == 2 && d.codes2) {
+                list = 1;
+                tiles = (d.N + 127) / 128;
+            }
+        }
+#pragma unroll
+        for (int l = 0; l < 2; l++) {
+            int sum_t, sum_e;
+            const int incl_t = scan256(list == l ? tiles : 0, tmp, sum_t);
+            const int incl_e = scan256(list == l ? 1 : 0, tmp, sum_e);
+            if (list == l)
+                (l ? order1 : order0)[first_rank[l] + incl_e - 1] = make_int2(first_tile[l] + incl_t - tiles, e);
+            first_tile[l] += sum_t;
+            first_rank[l] += sum_e;
+        }
+    }
+    if (threadIdx.x == 0) {
+        queue[FQ_Q_TILES] = first_tile[0];
+        queue[FQ_Q_ENTRIES] = first_rank[0];
+        queue[FQ_Q_TILES + 2] = first_tile[1];
+        queue[FQ_Q_ENTRIES + 2] = first_rank[1];
     }
 }
 
 template <int MT>
 __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev, int count,
-                                                                int total_tiles, int M, int *queue)
+                                                                int total_tiles, int M, int *queue,
+                                                                const int2 *__restrict__ order)
 {
-    __shared__ int mail[1];
+    __shared__ int mail[2];
     __shared__ __attribute__((aligned(1024))) uint8_t ring[CONSUMERS * NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t x0[16 * MT * KC * 2], x1[16 * MT * KC * 2];
     __shared__ __attribute__((aligned(256))) float ms0[UP * TILE_ROWS], ms1[UP * TILE_ROWS];
@@ -824,26 +921,34 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
     L.mz[0] = mz0, L.mz[1] = mz1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave == CONSUMERS)
-        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
+        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
     else if (wave > CONSUMERS)
-        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
+        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
     else
-        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave, queue, mail);
+        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
 }
 
 } // namespace
 
 // A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
-// tiles of 256 rows.  `queue`: nine zeroed ints in device memory that belong to the plan (the
-// kernel leaves them zeroed), or null for a fixed deal of the tiles.
+// tiles of 256 rows.  `queue`: 16 ints in device memory that belong to the plan, zeroed once (the
+// kernel leaves the cursors zeroed), and `order`: 2 x `count` pairs of ints of the plan's; or null
+// for a fixed deal of the tiles.
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
-                                   int M, int cus, int *queue, hipStream_t stream)
+                                   int M, int cus, int *queue, void *order, hipStream_t stream)
 {
     // one workgroup per CU (LDS): persistent over the tiles
     const int grid = total_tiles < cus ? total_tiles : cus;
+    if (queue && order) // what this launch runs, under its bit-widths (a second pass reads its list too)
+        plan_order_kernel<<<1, 256, 0, stream>>>(descs_dev, bits_dev, count, queue, (int2 *)order,
+                                                 (int2 *)order + count);
+    if (!order || grid % 64 != 0) // the queue hands out runs of 8 tiles to 8 XCDs
+        queue = nullptr;
     if (M <= 16)
-        decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue);
+        decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue,
+                                                              (const int2 *)order);
     else
-        decode_stream_kernel<2><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue);
+        decode_stream_kernel<2><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue,
+                                                              (const int2 *)order);
     return hipGetLastError();
 }

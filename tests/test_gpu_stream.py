@@ -25,7 +25,7 @@ MIN_ROWS = 1024 * 256  # what the dispatcher asks for before it uses 256-row til
 LONG = [(600, 8192), (300, 12288), (520, 4224), (700, 6144), (280, 4608), (300, 28672), (270, 32768)]
 
 
-def _build(M, tag, weight_fn, extra=()):
+def _build(M, tag, weight_fn, extra=(), widths=(4, 8, 16)):
     shapes, rows, i = list(extra), sum(n for n, _ in extra), 0
     while rows < MIN_ROWS + 256:
         shapes.append((NS[i % 5], KS[(i + i // 5) % 5]))
@@ -34,7 +34,7 @@ def _build(M, tag, weight_fn, extra=()):
     layers, packs, xs_np, xs, ys = [], [], [], [], []
     for i, (N, K) in enumerate(shapes):
         w = weight_fn(i, N, K)
-        layer, packed = make_layer(w, (4, 8, 16))
+        layer, packed = make_layer(w, widths)
         x = synth.activations(0, "%s/x%d/%d" % (tag, i, M), M, K)
         layers.append(layer)
         packs.append((w, packed))
@@ -157,3 +157,36 @@ def test_streaming_plan_skipped_entries_and_repeated_runs():
                 c, s, z = (t.cpu().numpy() for t in packed[b])
                 y_ref = oracle.linear(xs_np[i], c, s, z, b)
             assert rel_err(y, y_ref) <= TOL_Y, (p, i, b, shapes[i])
+
+
+@pytest.mark.parametrize("M", [16, 23])
+def test_streaming_plan_with_2bit_copies(M):
+    # a plan of the streaming kernel's size whose layers also hold 2-bit copies runs in two
+    # launches: the streaming kernel passes over the entries that are at 2 bits, the register-fed
+    # kernel runs exactly those
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(
+        M, "par/stream/w2", lambda i, N, K: synth.weight(0, "par/stream/w2/w%d" % i, N, K, 0.02, outlier_p=0.001),
+        widths=(2, 4, 8, 16))
+    n = len(layers)
+    patterns = [[(2, 4, 8, 16)[(i + s) % 4] for i in range(n)] for s in range(2)] + [[2] * n, [(8, 16, 4)[i % 3] for i in range(n)],
+                                                                                       [0 if i % 3 == 0 else 2 for i in range(n)]]
+    for p, pattern in enumerate(patterns):
+        for y in ys:
+            y.fill_(5.0)
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        for i, b in enumerate(pattern):
+            y = ys[i].cpu().numpy()
+            if b == 0:
+                assert np.all(y == np.float16(5.0)), (p, i)
+                continue
+            assert np.isfinite(y.astype(np.float32)).all(), (p, i, b)
+            if (i + p) % 4 and i < n - 2:
+                continue
+            w, packed = packs[i]
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(y, y_ref) <= TOL_Y, (M, p, i, b, shapes[i])
