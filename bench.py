@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per plan launch of the default workload relative to its algorithmic bytes, measured
 # with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
-MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993230.0 / 4978290.0,
+MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993151.0 / 4978290.0,
                           # profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md
                           ("llama7b", 16, (4, 8, 16)): 8.052 / 7.857}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
