@@ -80,6 +80,19 @@ def test_llama7b_stack_batch16_bits_4_8_16():
     _check_stack(st, steps=(3,), n_entries=21, rows_per_entry=4, rng=np.random.default_rng(1))
 
 
+@pytest.mark.parametrize("M", [4, 32])
+def test_llama7b_stack_batch_sweep_bits_4_8_16(M):
+    # the other batch sizes of the sweep (one and two batch tiles of the streaming kernel)
+    st = bench.Stack("llama7b", M=M, bit_choices=(4, 8, 16))
+    _check_stack(st, steps=(9,), n_entries=14, rows_per_entry=3, rng=np.random.default_rng(10 + M))
+
+
+def test_llama7b_stack_batch16_bits_2_4_8():
+    # a plan of the streaming kernel's size whose layers hold 2-bit copies: two kernels per launch
+    st = bench.Stack("llama7b", M=16, bit_choices=(2, 4, 8))
+    _check_stack(st, steps=(2,), n_entries=21, rows_per_entry=3, rng=np.random.default_rng(5))
+
+
 def test_llama13b_stack_batch8_outliers():
     st = bench.Stack("llama13b", M=8, bit_choices=(4, 8))
     _check_stack(st, steps=(5,), n_entries=21, rows_per_entry=4, rng=np.random.default_rng(2))
