@@ -190,3 +190,47 @@ def test_streaming_plan_with_2bit_copies(M):
                 c, s, z = (t.cpu().numpy() for t in packed[b])
                 y_ref = oracle.linear(xs_np[i], c, s, z, b)
             assert rel_err(y, y_ref) <= TOL_Y, (M, p, i, b, shapes[i])
+
+
+def test_streaming_plan_with_more_than_256_entries():
+    # the per-launch entry lists are drawn up 256 entries at a time
+    M, n = 16, 330
+    rng = np.random.default_rng(7)
+    shapes = [(820 + 13 * (i % 9), (128, 256, 384)[i % 3]) for i in range(n)]
+    assert sum(N for N, _ in shapes) >= MIN_ROWS + 256
+    layers, packs, xs_np, xs, ys = [], [], [], [], []
+    for i, (N, K) in enumerate(shapes):
+        w = synth.weight(0, "par/stream/many/w%d" % i, N, K, 0.02)
+        layer, packed = make_layer(w, (2, 4, 8) if i % 2 else (4, 8, 16))
+        layers.append(layer)
+        packs.append((w, packed))
+        xs_np.append(synth.activations(0, "par/stream/many/x%d" % i, M, K))
+        xs.append(to_dev(xs_np[-1]))
+        ys.append(torch.empty((M, N), dtype=torch.float16, device=DEV))
+    ws = torch.empty(fq.Plan.workspace_bytes(n), dtype=torch.uint8, device=DEV)
+    plan = fq.Plan(layers, xs, ys, M, ws)
+    for p in range(2):
+        # widths that some layers do not hold: those entries are passed over
+        pattern = [int(rng.choice((2, 4, 8, 16))) for _ in range(n)]
+        for y in ys:
+            y.fill_(9.0)
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        checked = 0
+        for i, b in enumerate(pattern):
+            y = ys[i].cpu().numpy()
+            w, packed = packs[i]
+            if b not in packed:
+                assert np.all(y == np.float16(9.0)), (p, i, b)
+                continue
+            assert np.isfinite(y.astype(np.float32)).all(), (p, i, b)
+            if i % 23 and i not in (255, 256, 257, n - 1):
+                continue
+            checked += 1
+            if b == 16:
+                y_ref = oracle.linear(xs_np[i], w, None, None, 16)
+            else:
+                c, s, z = (t.cpu().numpy() for t in packed[b])
+                y_ref = oracle.linear(xs_np[i], c, s, z, b)
+            assert rel_err(y, y_ref) <= TOL_Y, (p, i, b, shapes[i])
+        assert checked >= 8
