@@ -92,15 +92,19 @@ def test_token_loop_graph_matches_direct_calls():
     assert fq.fq_sched_peek(direct.state) == fq.fq_sched_peek(replayed.state)
 
 
-def test_streaming_plan_graph_replays():
+@pytest.mark.parametrize("widths", [(4, 8, 16), (2, 4, 8, 16)])
+def test_streaming_plan_graph_replays(widths):
     # the batched streaming kernel hands out its tiles from a queue in the plan's workspace and
-    # leaves it zeroed: replays need no memset node and follow each other directly
+    # leaves it zeroed: replays need no memset node and follow each other directly (with 2-bit
+    # copies a launch is three kernels: the entry lists, the streaming kernel, the 2-bit pass)
     M = 16
     shapes, layers, packs, xs_np, xs, ys, plan = _build(
-        M, "graph/stream", lambda i, N, K: synth.weight(0, "graph/stream/w%d" % i, N, K, 0.02))
+        M, "graph/stream", lambda i, N, K: synth.weight(0, "graph/stream/w%d" % i, N, K, 0.02), widths=widths)
     n = len(layers)
     bits = torch.zeros(n, dtype=torch.int32, device=DEV)
-    patterns = [[(4, 8, 16)[(i + s) % 3] for i in range(n)] for s in range(3)] + [[4] * n, [0 if i % 2 else 16 for i in range(n)]]
+    k = len(widths)
+    patterns = [[widths[(i + s) % k] for i in range(n)] for s in range(3)] + [[widths[0]] * n,
+                                                                              [0 if i % 2 else 16 for i in range(n)]]
     expect = []
     for p in patterns:
         bits.copy_(torch.tensor(p, dtype=torch.int32))
