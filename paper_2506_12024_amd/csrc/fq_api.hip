@@ -53,8 +53,7 @@ struct fq_layer {
 
 struct fq_plan {
     uint32_t magic;
-    int count, M, total_tiles, tile_rows, max_K;
-    int total_tiles2; // 128-row tiles of the second pass of a split batched plan, else 0
+    FqPlanGeom geom;
     const FqLinearDesc *table_dev;
     int *queue_dev;  // after the table: per-XCD tile cursors, a count of finished workgroups, list totals
     void *order_dev; // after the queue: two lists of two ints per entry
@@ -322,6 +321,89 @@ size_t fq_plan_workspace_bytes(int count)
     return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256 + ((size_t)count * 16 + 255) / 256 * 256;
 }
 
+} // extern "C"
+
+int fq_fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Checks the arguments of a plan (every check that needs no HIP call first, then the device facts
+// that size the tiles) and writes its descriptor table and geometry.
+int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, const void *const *xs,
+                   void *const *ys, int M, FqLinearDesc *table, FqPlanGeom *geom)
+{
+    if (!layers || !xs || !ys)
+        return fail(FQ_ERR_NULL, "%s: NULL argument", who);
+    if (count < 1)
+        return fail(FQ_ERR_SHAPE, "%s: count must be >= 1 (got %d)", who, count);
+    if (M < 1 || M > FQ_MAX_DECODE_M)
+        return fail(FQ_ERR_SHAPE, "%s: M must be in 1..%d (got %d)", who, FQ_MAX_DECODE_M, M);
+    long long total_rows = 0;
+    int max_K = 0;
+    bool has2 = false;
+    for (int i = 0; i < count; i++) {
+        if (int rc = check_layer(layers[i]))
+            return rc;
+        if (!xs[i] || !ys[i])
+            return fail(FQ_ERR_NULL, "%s: x or y of entry %d is NULL", who, i);
+        if (!aligned16(xs[i]) || (reinterpret_cast<uintptr_t>(ys[i]) & 1u))
+            return fail(FQ_ERR_ALIGN, "%s: entry %d: x needs 16-byte, y 2-byte alignment", who, i);
+        if (layers[i]->K > MAX_DECODE_K)
+            return fail(FQ_ERR_SHAPE, "%s: entry %d: K=%d exceeds the decode limit %d", who, i, layers[i]->K,
+                        MAX_DECODE_K);
+        if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2] && !layers[i]->codes[3])
+            return fail(FQ_ERR_NOT_ATTACHED, "%s: entry %d has no copy attached", who, i);
+        total_rows += layers[i]->N;
+        if (layers[i]->K > max_K)
+            max_K = layers[i]->K;
+        has2 = has2 || layers[i]->codes[3] != nullptr;
+    }
+    int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
+    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits and passes over
+    // every entry at another width: a plan of its size that holds a 2-bit copy, whose entries may be
+    // switched to it at any token, runs in two launches, the second one the register-fed kernel over
+    // the entries that are at 2 bits, in 128-row tiles of a numbering of their own.
+    const bool split = M > 1 && has2 && rows == 256;
+    if (M > 1 && has2 && rows == 16) // the K-split kernel for launches with few rows has no 2-bit path
+        rows = 64;
+    long long tiles = 0, tiles2 = 0;
+    for (int i = 0; i < count; i++) {
+        fill_desc(table[i], layers[i], xs[i], ys[i]);
+        table[i].tile_begin = (int)tiles;
+        tiles += (layers[i]->N + rows - 1) / rows;
+        if (split)
+            tiles2 += (layers[i]->N + 127) / 128;
+        if (tiles > 0x7fffffffLL || tiles2 > 0x7fffffffLL)
+            return fail(FQ_ERR_SHAPE, "%s: too many row tiles", who);
+    }
+    geom->count = count;
+    geom->M = M;
+    geom->total_tiles = (int)tiles;
+    geom->total_tiles2 = (int)tiles2;
+    geom->max_K = max_K;
+    geom->tile_rows = rows;
+    return FQ_OK;
+}
+
+hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, int *queue_dev, void *order_dev,
+                          const int32_t *bits_dev, hipStream_t stream)
+{
+    hipError_t e = g.M == 1
+        ? fq_launch_decode(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.max_K, g.M, stream)
+        : fq_launch_skinny(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.M, queue_dev,
+                           order_dev, stream);
+    if (e == hipSuccess && g.total_tiles2 > 0)
+        e = fq_launch_skinny_second(table_dev, bits_dev, g.count, g.total_tiles2, g.M, queue_dev, order_dev, stream);
+    return e;
+}
+
+extern "C" {
+
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, const void *const *xs,
                    void *const *ys, int M, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -332,59 +414,15 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         return fail(FQ_ERR_NULL, "fq_plan_create: NULL argument");
     if (count < 1)
         return fail(FQ_ERR_SHAPE, "fq_plan_create: count must be >= 1 (got %d)", count);
-    if (M < 1 || M > FQ_MAX_DECODE_M)
-        return fail(FQ_ERR_SHAPE, "fq_plan_create: M must be in 1..%d (got %d)", FQ_MAX_DECODE_M, M);
     if (workspace_bytes < fq_plan_workspace_bytes(count))
         return fail(FQ_ERR_SHAPE, "fq_plan_create: workspace too small (%zu < %zu bytes)",
                     workspace_bytes, fq_plan_workspace_bytes(count));
     if (reinterpret_cast<uintptr_t>(workspace) & 255u)
         return fail(FQ_ERR_ALIGN, "fq_plan_create: workspace must be 256-byte aligned");
     std::vector<FqLinearDesc> table((size_t)count);
-    long long tiles = 0, total_rows = 0;
-    int max_K = 0;
-    for (int i = 0; i < count; i++) {
-        if (int rc = check_layer(layers[i]))
-            return rc;
-        total_rows += layers[i]->N;
-        if (layers[i]->K > max_K)
-            max_K = layers[i]->K;
-    }
-    if (max_K > MAX_DECODE_K)
-        return fail(FQ_ERR_SHAPE, "fq_plan_create: K=%d exceeds the decode limit %d", max_K, MAX_DECODE_K);
-    int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
-    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits and passes over
-    // every entry at another width: a plan of its size that holds a 2-bit copy, whose entries may be
-    // switched to it at any token, runs in two launches, the second one the register-fed kernel over
-    // the entries that are at 2 bits, in 128-row tiles of a numbering of their own.
-    bool has2 = false;
-    for (int i = 0; i < count; i++)
-        has2 = has2 || layers[i]->codes[3] != nullptr;
-    const bool split = M > 1 && has2 && rows == 256;
-    if (M > 1 && has2 && rows == 16) // the K-split kernel for launches with few rows has no 2-bit path
-        rows = 64;
-    long long tiles2 = 0;
-    for (int i = 0; i < count; i++) {
-        if (int rc = check_layer(layers[i]))
-            return rc;
-        if (!xs[i] || !ys[i])
-            return fail(FQ_ERR_NULL, "fq_plan_create: x or y of entry %d is NULL", i);
-        if (!aligned16(xs[i]) || (reinterpret_cast<uintptr_t>(ys[i]) & 1u))
-            return fail(FQ_ERR_ALIGN, "fq_plan_create: entry %d: x needs 16-byte, y 2-byte alignment", i);
-        if (layers[i]->K > MAX_DECODE_K)
-            return fail(FQ_ERR_SHAPE, "fq_plan_create: entry %d: K=%d exceeds the decode limit %d", i,
-                        layers[i]->K, MAX_DECODE_K);
-        if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2] && !layers[i]->codes[3])
-            return fail(FQ_ERR_NOT_ATTACHED, "fq_plan_create: entry %d has no copy attached", i);
-        fill_desc(table[(size_t)i], layers[i], xs[i], ys[i]);
-        table[(size_t)i].tile_begin = (int)tiles;
-        tiles += (layers[i]->N + rows - 1) / rows;
-        if (split)
-            tiles2 += (layers[i]->N + 127) / 128;
-        if (layers[i]->K > max_K)
-            max_K = layers[i]->K;
-        if (tiles > 0x7fffffffLL || tiles2 > 0x7fffffffLL)
-            return fail(FQ_ERR_SHAPE, "fq_plan_create: too many row tiles");
-    }
+    FqPlanGeom geom;
+    if (int rc = fq_plan_layout("fq_plan_create", count, layers, xs, ys, M, table.data(), &geom))
+        return rc;
     fq_plan *p = new (std::nothrow) fq_plan();
     if (!p)
         return fail(FQ_ERR_HIP, "fq_plan_create: out of host memory");
@@ -402,12 +440,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
         return hip_fail(e, "fq_plan_create table copy");
     }
     p->magic = PLAN_MAGIC;
-    p->count = count;
-    p->M = M;
-    p->total_tiles = (int)tiles;
-    p->total_tiles2 = (int)tiles2;
-    p->max_K = max_K;
-    p->tile_rows = rows;
+    p->geom = geom;
     p->table_dev = (const FqLinearDesc *)workspace;
     p->queue_dev = (int *)((char *)workspace + table_bytes);
     p->order_dev = (char *)workspace + table_bytes + 256;
@@ -423,14 +456,8 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
         return fail(FQ_ERR_NULL, "fq_plan_run: bits_dev is NULL");
     if (reinterpret_cast<uintptr_t>(bits_dev) & 3u)
         return fail(FQ_ERR_ALIGN, "fq_plan_run: bits_dev must be 4-byte aligned");
-    hipError_t e = plan->M == 1
-        ? fq_launch_decode(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
-                           plan->tile_rows, plan->max_K, plan->M, (hipStream_t)stream)
-        : fq_launch_skinny(nullptr, 0, plan->table_dev, bits_dev, plan->count, plan->total_tiles,
-                           plan->tile_rows, plan->M, plan->queue_dev, plan->order_dev, (hipStream_t)stream);
-    if (e == hipSuccess && plan->total_tiles2 > 0)
-        e = fq_launch_skinny_second(plan->table_dev, bits_dev, plan->count, plan->total_tiles2, plan->M,
-                                    plan->queue_dev, plan->order_dev, (hipStream_t)stream);
+    hipError_t e = fq_plan_launch(plan->geom, plan->table_dev, plan->queue_dev, plan->order_dev, bits_dev,
+                                  (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

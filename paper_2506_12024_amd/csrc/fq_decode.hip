@@ -638,27 +638,9 @@ static size_t lds_bytes_for(int max_K)
 
 // Workgroups that can be resident at once on the current device: a persistent grid must
 // not exceed it, or late workgroups would start a full pass late.
-static int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return 256;
-        cus = prop.multiProcessorCount;
-    }
-    return cus;
-}
-
 static int resident_workgroups(size_t lds)
 {
-    const int cus = device_cus();
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_m1_kernel<false>, WG_THREADS, lds) !=
-            hipSuccess || per_cu < 1)
-        per_cu = 2;
-    return cus * per_cu;
+    return fq_device_cus() * fq_workgroups_per_cu((const void *)decode_m1_kernel<false>, WG_THREADS, lds, 2);
 }
 
 int fq_decode_tile_rows(long long total_rows, int max_K, int M)
@@ -682,22 +664,12 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
         return hipSuccess;
     const size_t lds = lds_bytes_for(max_K);
     if (lds > 48 * 1024) { // above the default limit of dynamic LDS: raised once per device
-        static bool raised[64];
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
+        const size_t most = lds_bytes_for(FQ_MAX_DECODE_K);
+        hipError_t e = fq_raise_dynamic_lds((const void *)decode_m1_kernel<true>, most);
+        if (e == hipSuccess)
+            e = fq_raise_dynamic_lds((const void *)decode_m1_kernel<false>, most);
         if (e != hipSuccess)
             return e;
-        if (dev < 0 || dev >= 64 || !raised[dev]) {
-            const int most = (int)lds_bytes_for(FQ_MAX_DECODE_K);
-            e = hipFuncSetAttribute((const void *)decode_m1_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, most);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute((const void *)decode_m1_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        most);
-            if (e != hipSuccess)
-                return e;
-            if (dev >= 0 && dev < 64)
-                raised[dev] = true;
-        }
     }
     const int cap = resident_workgroups(lds);
     // A plan cuts its total cost into one equal slice per workgroup.  Two workgroups per CU
@@ -705,7 +677,7 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
     // faster than four: fewer concurrent streams, better DRAM page locality (measured on the
     // mixed 7B step: 0.867 / 0.763 / 0.788 / 0.795 ms with 1 / 2 / 3 / 4 workgroups per CU; a
     // third register set, i.e. twelve loads per lane in flight, made it slower too: 0.780 ms).
-    const int plan_grid = cap < 2 * device_cus() ? cap : 2 * device_cus();
+    const int plan_grid = cap < 2 * fq_device_cus() ? cap : 2 * fq_device_cus();
     const int grid = single ? (total_tiles < cap ? total_tiles : cap) : plan_grid;
     if (single) {
         decode_m1_kernel<true><<<grid, WG_THREADS, lds, stream>>>(*single, bits_host, nullptr,

@@ -27,6 +27,30 @@ struct FqLinearDesc {
     int pad;
 };
 
+// Geometry of a plan: how its entries are cut into row tiles for the kernel that serves its M.
+struct FqPlanGeom {
+    int count, M, total_tiles, tile_rows, max_K;
+    int total_tiles2; // 128-row tiles of the second pass of a split batched plan, else 0
+};
+struct fq_layer;
+// Records a message for fq_last_error() on the calling thread and returns `code`.
+int fq_fail(int code, const char *fmt, ...);
+// Argument checks and layout shared by the entry points that run a list of linears with one launch:
+// fills table[count] and *geom, or returns a negative fq_status with the message recorded.
+int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, const void *const *xs,
+                   void *const *ys, int M, FqLinearDesc *table, FqPlanGeom *geom);
+// The launch (or two) of a laid-out plan whose table, queue words and entry lists are in device memory.
+hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, int *queue_dev, void *order_dev,
+                          const int32_t *bits_dev, hipStream_t stream);
+
+// Facts about the current device, asked of the runtime once per device and cached (thread-safe):
+// its compute units; the workgroups of `func` (launched with `threads` threads and `lds` bytes of
+// dynamic LDS) that fit on one of them, `fallback` if the runtime cannot say; and a kernel's
+// dynamic LDS limit raised to at least `bytes` (a no-op once done).
+int fq_device_cus();
+int fq_workgroups_per_cu(const void *func, int threads, size_t lds, int fallback);
+hipError_t fq_raise_dynamic_lds(const void *func, size_t bytes);
+
 hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
                               void *scales, void *zeros, hipStream_t stream);
 hipError_t fq_launch_fake_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *w_hat,

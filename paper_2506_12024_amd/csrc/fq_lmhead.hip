@@ -285,18 +285,7 @@ __global__ __launch_bounds__(MAX_WGS) void lm_head_combine_kernel(int parts, flo
     }
 }
 
-int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return 256;
-        cus = prop.multiProcessorCount;
-    }
-    return cus;
-}
+int device_cus() { return fq_device_cus(); }
 
 template <int M>
 hipError_t launch(const uint16_t *x, const uint16_t *w, int V, int K, float *logits, float *H, int32_t *argmax,
@@ -304,8 +293,7 @@ hipError_t launch(const uint16_t *x, const uint16_t *w, int V, int K, float *log
 {
     const size_t lds = (size_t)M * K * 2;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)lm_head_entropy_kernel<M>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = fq_raise_dynamic_lds((const void *)lm_head_entropy_kernel<M>, 64 * 1024);
         if (e != hipSuccess)
             return e;
     }

@@ -438,10 +438,7 @@ hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t
     // count.  What is left for the last round, if it would fill at most half the CUs, runs as half
     // tiles in a second launch (2048 x 28672: 112 tiles per XCD = 3 rounds of 32 + 16 tiles, which
     // then take half a round instead of a whole one).
-    int cus = 256, dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-        cus = prop.multiProcessorCount;
+    const int cus = fq_device_cus();
     const int per_round = cus / 8 > 0 ? cus / 8 : 1;
     const int rest = per_xcd % per_round;
     const int tail = rest > 0 && 2 * rest <= per_round ? rest : 0;

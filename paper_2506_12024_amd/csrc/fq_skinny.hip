@@ -644,11 +644,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
 template <int MT, int RT>
 int resident(int cus)
 {
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_skinny_kernel<false, MT, RT>,
-                                                     WG_THREADS, 0) != hipSuccess || per_cu < 1)
-        per_cu = 2;
-    return cus * per_cu;
+    return cus * fq_workgroups_per_cu((const void *)decode_skinny_kernel<false, MT, RT>, WG_THREADS, 0, 2);
 }
 
 template <int MT, int RT>
@@ -673,11 +669,7 @@ template <int MT>
 hipError_t launch_sk(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
                      const int32_t *bits_dev, int count, int total_tiles, int M, int cus, hipStream_t stream)
 {
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_skinny_sk_kernel<false, MT>, WG_THREADS, 0) !=
-            hipSuccess || per_cu < 1)
-        per_cu = 2;
-    const int cap = cus * per_cu;
+    const int cap = cus * fq_workgroups_per_cu((const void *)decode_skinny_sk_kernel<false, MT>, WG_THREADS, 0, 2);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
         decode_skinny_sk_kernel<true, MT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1,
@@ -690,18 +682,7 @@ hipError_t launch_sk(const FqLinearDesc *single, int bits_host, const FqLinearDe
     return hipGetLastError();
 }
 
-int device_cus()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return 256;
-        cus = prop.multiProcessorCount;
-    }
-    return cus;
-}
+int device_cus() { return fq_device_cus(); }
 
 } // namespace
 

@@ -57,7 +57,9 @@ def test_quantize_degenerate_groups(bits):
 # ------------------------------------------------------------------ linear, batch 1
 
 @pytest.mark.parametrize("bits", [4, 8, 16])
-@pytest.mark.parametrize("N,K", [(4096, 4096), (100, 1408), (37, 128), (16, 11008), (530, 5120)])
+@pytest.mark.parametrize("N,K", [(4096, 4096), (100, 1408), (37, 128), (16, 11008), (530, 5120),
+                                 # the 13B-shaped stack's long row and its wide FFN, at batch 1
+                                 (200, 13824), (13824, 5120)])
 def test_linear_m1_matches_oracle(bits, N, K):
     w = synth.weight(0, "par/lin/%dx%d" % (N, K), N, K, 0.02, outlier_p=0.001)
     x = synth.activations(0, "par/lin/x/%d" % K, 1, K)
