@@ -173,6 +173,23 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream);
 int fq_plan_destroy(fq_plan *plan);
 
 /*
+ * For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): what fq_plan_create + fq_plan_run + fq_plan_destroy do, in one call that
+ * takes no workspace, creates no object, copies nothing from host memory and never synchronises.
+ * Entry i computes ys[i] = linear(layers[i], bits_dev[i], xs[i]); arguments, limits, alignment and
+ * errors as for fq_plan_create and fq_plan_run; count <= FQ_STATIC_MAX_ENTRIES (FQ_ERR_SHAPE
+ * beyond).  The descriptor table, the tile queue and the entry lists live in a static device array
+ * of the library (about 65 KiB, held on every device the library runs on until the process ends);
+ * the table is written there by small kernels that carry it in their arguments, one launch per 32
+ * entries, ahead of the launch that computes.  Every call on a device shares that array: calls that
+ * overlap in time on one device race (calls on one stream, or ordered by events, do not).  The
+ * host-side handles in `layers` are read during the call only.
+ */
+#define FQ_STATIC_MAX_ENTRIES 512
+int fq_linears_static(int count, const fq_layer *const *layers, const void *const *xs, void *const *ys,
+                      int M, const int32_t *bits_dev, void *stream);
+
+/*
  * W8A8 prefill (Sec. 4.1, 4.3, 4.5): the prompt is processed with the resident INT8 weights
  * against 8-bit activations on the integer matrix cores.
  *

@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libflexq.so")
 FQ_GROUP = 128
 FQ_MAX_DECODE_M = 32
 FQ_MAX_LM_HEAD_M = 4
+FQ_STATIC_MAX_ENTRIES = 512
 FQ_OK, FQ_ERR_NULL, FQ_ERR_BITS, FQ_ERR_SHAPE, FQ_ERR_NOT_ATTACHED, FQ_ERR_ALIGN, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
 
@@ -24,7 +25,7 @@ EXPORTS = [
     "fq_plan_destroy", "fq_entropy_kl", "fq_sched_state_bytes", "fq_sched_init",
     "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
     "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
-    "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy",
+    "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy", "fq_linears_static",
 ]
 
 
@@ -68,6 +69,8 @@ def _load() -> ctypes.CDLL:
     L.fq_plan_run.argtypes = [vp, vp, vp]
     L.fq_plan_destroy.restype = ci
     L.fq_plan_destroy.argtypes = [vp]
+    L.fq_linears_static.restype = ci
+    L.fq_linears_static.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, vp]
     L.fq_entropy_kl.restype = ci
     L.fq_entropy_kl.argtypes = [vp, vp, ci, ci, vp, vp, vp]
     L.fq_entropy_kl_f16.restype = ci
@@ -215,6 +218,13 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def fq_linears_static(layers, xs, ys, M: int, bits_dev, stream=None):
+    n = len(layers)
+    arr = ctypes.c_void_p * max(n, 1)
+    _check(lib.fq_linears_static(n, arr(*[l.handle for l in layers]), arr(*[_ptr(x) for x in xs]),
+                                 arr(*[_ptr(y) for y in ys]), M, _ptr(bits_dev), _stream(stream)))
 
 
 def fq_entropy_kl(logits_p, logits_q, R: int, V: int, entropy_out, kl_out, stream=None):

@@ -220,3 +220,26 @@ def test_lm_head_entropy_validation():
     assert L.fq_lm_head_entropy(ok, ok, 1, 100, 512, None, None, None, None) == B.FQ_ERR_NULL
     assert L.fq_lm_head_entropy(vp(FAKE + 8), ok, 1, 100, 512, None, ok, None, None) == B.FQ_ERR_ALIGN
     assert "fq_lm_head_entropy" in fq.fq_last_error()
+
+
+def test_linears_static_validation():
+    # the entry point that allocates nothing rejects bad arguments, and sizes beyond its static
+    # workspace, before any HIP call
+    L = fq.lib
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 16, 256, 128) == B.FQ_OK
+    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
+    arr = (ctypes.c_void_p * 1)
+    assert L.fq_linears_static(1, arr(h), arr(FAKE), arr(FAKE), 1, None, None) == B.FQ_ERR_NULL
+    assert L.fq_linears_static(1, arr(h), arr(FAKE), arr(FAKE), 1, FAKE + 2, None) == B.FQ_ERR_ALIGN
+    assert L.fq_linears_static(0, arr(h), arr(FAKE), arr(FAKE), 1, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_linears_static(1, arr(h), arr(FAKE), arr(FAKE), 33, FAKE, None) == B.FQ_ERR_SHAPE
+    assert L.fq_linears_static(1, None, arr(FAKE), arr(FAKE), 1, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linears_static(1, arr(h), arr(None), arr(FAKE), 1, FAKE, None) == B.FQ_ERR_NULL
+    assert L.fq_linears_static(1, arr(h), arr(FAKE + 4), arr(FAKE), 1, FAKE, None) == B.FQ_ERR_ALIGN
+    n = B.FQ_STATIC_MAX_ENTRIES + 1
+    many = (ctypes.c_void_p * n)
+    assert L.fq_linears_static(n, many(*[h.value] * n), many(*[FAKE] * n), many(*[FAKE] * n), 1, FAKE,
+                               None) == B.FQ_ERR_SHAPE
+    assert b"FQ_STATIC_MAX_ENTRIES" in L.fq_last_error()
+    assert L.fq_layer_destroy(h) == B.FQ_OK
