@@ -146,6 +146,20 @@ class Stack:
                            [self.ys[i] for i in idx], self.M, ws)
             self.stage_plans.append((plan, idx[0], len(idx)))
 
+    def build_staged_plan(self):
+        """The same stages in ONE stage-ordered plan: a single persistent launch walks them in order."""
+        torch, fq = self.torch, self.fq
+        groups = {"q": 0, "k": 0, "v": 0, "o": 1, "gate": 2, "up": 2, "down": 3}
+        stage = [4 * li + groups[mname] for (li, mname, _, _) in self.entries]
+        assert all(b >= a for a, b in zip(stage, stage[1:])), "entries are listed in stage order"
+        self.staged_ws = torch.empty(fq.StagedPlan.workspace_bytes(len(stage), max(stage) + 1), dtype=torch.uint8,
+                                     device="cuda:0")
+        self.staged_plan = fq.StagedPlan(self.layers, self.xs, self.ys, stage, self.M, self.staged_ws)
+        self.n_stages = max(stage) + 1
+
+    def run_linears_one_launch_staged(self, s: int):
+        self.staged_plan.run(self.bits_dev[s % N_PATTERNS])
+
     def run_linears_staged(self, s: int):
         bits = self.bits_dev[s % N_PATTERNS]
         for plan, first, n in self.stage_plans:
@@ -712,6 +726,12 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         staged_ms = (time.perf_counter() - t0) / reps * 1e3
+        stack.build_staged_plan()
+        for i in range(8):
+            stack.run_linears_one_launch_staged(W + i)
+        one_launch_ms = time_launches(lambda i: stack.run_linears_one_launch_staged(W + i), K_steps)
+        print("one-launch staged plan: %.4f ms per step, status %r" % (one_launch_ms, stack.staged_plan.status()),
+              file=sys.stderr, flush=True)
     alg_bytes = total_bytes / K_steps
     achieved = alg_bytes / (lin_ms * 1e-3) / 1e9
 

@@ -173,6 +173,40 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream);
 int fq_plan_destroy(fq_plan *plan);
 
 /*
+ * A stage-ordered plan: the decode step of Alg. 1 in the order a decoder must issue it (Sec. 4.1:
+ * each of these linears is bound by loading its weights, so the step is one long weight stream
+ * with dependencies in it).  Entry i belongs to stage `stage[i]`; the entries of a stage are
+ * independent of each other, and an entry may read (as x) what an entry of an EARLIER stage writes
+ * (as y).  fq_plan_run runs all stages in order with ONE launch of a persistent kernel: a grid-wide
+ * barrier stands between two stages, and the weights of the next stage are already being fetched
+ * while it is crossed.  Results are bit-identical to the same stages run as separate plans.
+ *   stage      HOST, int32 [count]: stage[0] = 0, never decreasing, rising by at most 1;
+ *              at most FQ_MAX_STAGE_ENTRIES entries per stage
+ *   workspace  device, fq_plan_staged_workspace_bytes(count, number of stages) bytes, 256-byte
+ *              aligned, owned by the caller, must outlive the plan
+ *   M          must be 1; every K <= FQ_MAX_DECODE_K, and the table of stages plus one row of x
+ *              must fit the LDS of a compute unit (FQ_ERR_SHAPE otherwise: about 1000 stages at
+ *              K = 11008, 1500 at 4096)
+ * Everything else as fq_plan_create (which also copies the tables and waits for that copy).
+ * The kernel's workgroups wait for each other, so the launch needs the device to itself: while
+ * another kernel holds compute units the waits may run out.  A wait is bounded (about a second
+ * by default, fq_plan_set_wait_limit sets the number of polls): a launch that gives up leaves y
+ * incomplete, every workgroup still exits, the barrier's counters are put back, and the next
+ * launch starts clean.  fq_plan_status waits for `stream` and reports
+ *   gave_up  launches of this plan that gave up so far (never reset)
+ *   flags    bit 0: an entry's bit-width was not 2, 4, 8 or 16 or had no copy attached (its y was
+ *            left untouched); bit 1: a workgroup's share of a stage exceeded 8192 rows (skipped)
+ * Either output may be NULL.  Runs of one plan must not overlap in time.
+ */
+#define FQ_MAX_STAGE_ENTRIES 32
+size_t fq_plan_staged_workspace_bytes(int count, int n_stages);
+int fq_plan_create_staged(fq_plan **out, int count, const fq_layer *const *layers,
+                          const void *const *xs, void *const *ys, const int32_t *stage, int M,
+                          void *workspace, size_t workspace_bytes, void *stream);
+int fq_plan_set_wait_limit(fq_plan *plan, long long polls);
+int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *stream);
+
+/*
  * For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc): what fq_plan_create + fq_plan_run + fq_plan_destroy do, in one call that
  * takes no workspace, creates no object, copies nothing from host memory and never synchronises.

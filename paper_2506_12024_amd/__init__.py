@@ -6,7 +6,7 @@ first use of any name below loads the library and raises if it has not been buil
 (``python -m paper_2506_12024_amd.build``).
 """
 _EXPORTS = (
-    "FQ_GROUP", "FQ_MAX_DECODE_M", "FlexqError", "Layer", "Plan", "fq_entropy_kl", "fq_entropy_kl_f16",
+    "FQ_GROUP", "FQ_MAX_DECODE_M", "FlexqError", "Layer", "Plan", "StagedPlan", "fq_entropy_kl", "fq_entropy_kl_f16",
     "fq_last_error", "fq_linear", "fq_linear_w8a8", "fq_packed_sizes", "fq_quantize", "fq_quantize_act",
     "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy", "FQ_MAX_LM_HEAD_M",
     "fq_linears_static", "FQ_STATIC_MAX_ENTRIES",

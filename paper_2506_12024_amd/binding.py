@@ -26,6 +26,7 @@ EXPORTS = [
     "fq_sched_threshold_from_prefill", "fq_sched_step", "fq_sched_peek",
     "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
     "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy", "fq_linears_static",
+    "fq_plan_staged_workspace_bytes", "fq_plan_create_staged", "fq_plan_set_wait_limit", "fq_plan_status",
 ]
 
 
@@ -69,6 +70,15 @@ def _load() -> ctypes.CDLL:
     L.fq_plan_run.argtypes = [vp, vp, vp]
     L.fq_plan_destroy.restype = ci
     L.fq_plan_destroy.argtypes = [vp]
+    L.fq_plan_staged_workspace_bytes.restype = sz
+    L.fq_plan_staged_workspace_bytes.argtypes = [ci, ci]
+    L.fq_plan_create_staged.restype = ci
+    L.fq_plan_create_staged.argtypes = [ctypes.POINTER(vp), ci, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                        ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_int32), ci, vp, sz, vp]
+    L.fq_plan_set_wait_limit.restype = ci
+    L.fq_plan_set_wait_limit.argtypes = [vp, ctypes.c_longlong]
+    L.fq_plan_status.restype = ci
+    L.fq_plan_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
     L.fq_linears_static.restype = ci
     L.fq_linears_static.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, vp]
     L.fq_entropy_kl.restype = ci
@@ -218,6 +228,37 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+class StagedPlan(Plan):
+    """Owns a stage-ordered ``fq_plan``: entry i belongs to stage ``stage[i]`` (host ints, never
+    decreasing); one launch runs the stages in order."""
+
+    def __init__(self, layers, xs, ys, stage, M: int, workspace, stream=None):
+        n = len(layers)
+        arr = ctypes.c_void_p * max(n, 1)
+        st = (ctypes.c_int32 * max(n, 1))(*[int(v) for v in stage])
+        self._keep = (list(layers), list(xs), list(ys), workspace)
+        h = ctypes.c_void_p()
+        ws_bytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else 0
+        _check(lib.fq_plan_create_staged(
+            ctypes.byref(h), n, arr(*[l.handle for l in layers]), arr(*[_ptr(x) for x in xs]),
+            arr(*[_ptr(y) for y in ys]), st, M, _ptr(workspace), ws_bytes, _stream(stream)))
+        self.handle = h
+        self.count = n
+
+    @staticmethod
+    def workspace_bytes(count: int, n_stages: int) -> int:
+        return int(lib.fq_plan_staged_workspace_bytes(count, n_stages))
+
+    def set_wait_limit(self, polls: int):
+        _check(lib.fq_plan_set_wait_limit(self.handle, polls))
+
+    def status(self, stream=None):
+        """Returns (gave_up, flags) after waiting for the stream."""
+        g, f = ctypes.c_int32(), ctypes.c_int32()
+        _check(lib.fq_plan_status(self.handle, ctypes.byref(g), ctypes.byref(f), _stream(stream)))
+        return g.value, f.value
 
 
 def fq_linears_static(layers, xs, ys, M: int, bits_dev, stream=None):

@@ -14,8 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexq.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["fq_api.hip", "fq_device.hip", "fq_noalloc.hip", "fq_quantize.hip", "fq_entropy.hip", "fq_decode.hip", "fq_skinny.hip", "fq_stream.hip", "fq_prefill.hip", "fq_w8a8.hip", "fq_sched.hip", "fq_lmhead.hip"]
-HEADERS = [os.path.join(CSRC, "fq_internal.h"),
+SOURCES = ["fq_api.hip", "fq_device.hip", "fq_noalloc.hip", "fq_quantize.hip", "fq_entropy.hip", "fq_decode.hip", "fq_staged.hip", "fq_skinny.hip", "fq_stream.hip", "fq_prefill.hip", "fq_w8a8.hip", "fq_sched.hip", "fq_lmhead.hip"]
+HEADERS = [os.path.join(CSRC, "fq_internal.h"), os.path.join(CSRC, "fq_gemv.h"),
            os.path.join(os.path.dirname(HERE), "include", "flexq.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          # packed fp32 ops are kept off for device code (the host pass warns it does not know the feature)

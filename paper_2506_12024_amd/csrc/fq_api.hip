@@ -54,6 +54,11 @@ struct fq_layer {
 struct fq_plan {
     uint32_t magic;
     FqPlanGeom geom;
+    // stage-ordered plans (fq_plan_create_staged): n_stages > 0
+    int n_stages;
+    const int32_t *stage_begin_dev; // int32 [n_stages + 1], after the table
+    int *sync_dev;                  // the barrier's counters and the status words, after that
+    long long wait_limit;           // polls a workgroup spends on one stage boundary before it gives up
     const FqLinearDesc *table_dev;
     int *queue_dev;  // after the table: per-XCD tile cursors, a count of finished workgroups, list totals
     void *order_dev; // after the queue: two lists of two ints per entry
@@ -448,6 +453,130 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
     return FQ_OK;
 }
 
+// Layout of a stage-ordered plan's workspace: table | stage_begin | sync words.
+static size_t staged_table_bytes(int count) { return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256; }
+static size_t staged_begin_bytes(int n_stages) { return ((size_t)(n_stages + 1) * 4 + 255) / 256 * 256; }
+constexpr size_t STAGED_SYNC_BYTES = 2048;
+constexpr int STAGED_RES_CHUNKS = 2048; // 4-row chunks of one stage a workgroup can hold results for
+constexpr long long STAGED_WAIT_LIMIT = 1LL << 21; // about a second of polling
+
+size_t fq_plan_staged_workspace_bytes(int count, int n_stages)
+{
+    if (count < 1 || n_stages < 1 || n_stages > count)
+        return 0;
+    return staged_table_bytes(count) + staged_begin_bytes(n_stages) + STAGED_SYNC_BYTES;
+}
+
+int fq_plan_create_staged(fq_plan **out, int count, const fq_layer *const *layers, const void *const *xs,
+                          void *const *ys, const int32_t *stage, int M, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    if (!out)
+        return fail(FQ_ERR_NULL, "fq_plan_create_staged: out is NULL");
+    *out = nullptr;
+    if (!layers || !xs || !ys || !stage || !workspace)
+        return fail(FQ_ERR_NULL, "fq_plan_create_staged: NULL argument");
+    if (count < 1)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: count must be >= 1 (got %d)", count);
+    if (M != 1)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: the stage-ordered kernel serves M = 1 (got %d)", M);
+    if (stage[0] != 0)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: stage[0] must be 0 (got %d)", stage[0]);
+    std::vector<int32_t> begin;
+    begin.push_back(0);
+    for (int i = 1; i < count; i++) {
+        if (stage[i] != stage[i - 1] && stage[i] != stage[i - 1] + 1)
+            return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: stage numbers must not decrease and must rise by "
+                                      "at most one (entry %d: %d after %d)", i, stage[i], stage[i - 1]);
+        if (stage[i] != stage[i - 1])
+            begin.push_back(i);
+        if (i + 1 - begin.back() > FQ_MAX_STAGE_ENTRIES)
+            return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: stage %d has more than %d entries", stage[i],
+                        FQ_MAX_STAGE_ENTRIES);
+    }
+    const int n_stages = (int)begin.size();
+    begin.push_back(count);
+    if (workspace_bytes < fq_plan_staged_workspace_bytes(count, n_stages))
+        return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: workspace too small (%zu < %zu bytes)", workspace_bytes,
+                    fq_plan_staged_workspace_bytes(count, n_stages));
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+        return fail(FQ_ERR_ALIGN, "fq_plan_create_staged: workspace must be 256-byte aligned");
+    std::vector<FqLinearDesc> table((size_t)count);
+    FqPlanGeom geom;
+    if (int rc = fq_plan_layout("fq_plan_create_staged", count, layers, xs, ys, M, table.data(), &geom))
+        return rc;
+    for (int a = 0; a < count; a++) // a later stage may read what an earlier one writes, never the reverse
+        for (int b = 0; b < count; b++)
+            if (stage[a] <= stage[b] && xs[a] == ys[b])
+                return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: x of entry %d (stage %d) is y of entry %d (stage %d)",
+                            a, stage[a], b, stage[b]);
+    const size_t lds = fq_staged_lds_bytes(n_stages, geom.max_K, STAGED_RES_CHUNKS);
+    if (lds > 160 * 1024)
+        return fail(FQ_ERR_SHAPE, "fq_plan_create_staged: %d stages with rows of up to %d inputs need %zu bytes of "
+                                  "LDS (160 KiB at most)", n_stages, geom.max_K, lds);
+    if (fq_staged_grid(lds) < 1)
+        return fail(FQ_ERR_HIP, "fq_plan_create_staged: the stage-ordered kernel does not fit this device");
+    fq_plan *p = new (std::nothrow) fq_plan();
+    if (!p)
+        return fail(FQ_ERR_HIP, "fq_plan_create_staged: out of host memory");
+    char *ws = (char *)workspace;
+    const size_t tb = staged_table_bytes(count), bb = staged_begin_bytes(n_stages);
+    hipError_t e = hipMemcpyAsync(ws, table.data(), (size_t)count * sizeof(FqLinearDesc), hipMemcpyHostToDevice,
+                                  (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ws + tb, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess) // counters and status words start at zero; every launch leaves the counters at zero
+        e = hipMemsetAsync(ws + tb + bb, 0, STAGED_SYNC_BYTES, (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) {
+        delete p;
+        return hip_fail(e, "fq_plan_create_staged table copy");
+    }
+    p->magic = PLAN_MAGIC;
+    p->geom = geom;
+    p->table_dev = (const FqLinearDesc *)ws;
+    p->queue_dev = nullptr;
+    p->order_dev = nullptr;
+    p->n_stages = n_stages;
+    p->stage_begin_dev = (const int32_t *)(ws + tb);
+    p->sync_dev = (int *)(ws + tb + bb);
+    p->wait_limit = STAGED_WAIT_LIMIT;
+    *out = p;
+    return FQ_OK;
+}
+
+int fq_plan_set_wait_limit(fq_plan *plan, long long polls)
+{
+    if (!plan || plan->magic != PLAN_MAGIC)
+        return fail(FQ_ERR_NULL, "fq_plan_set_wait_limit: plan is NULL or not valid");
+    if (plan->n_stages < 1)
+        return fail(FQ_ERR_SHAPE, "fq_plan_set_wait_limit: not a stage-ordered plan");
+    if (polls < 0)
+        return fail(FQ_ERR_SHAPE, "fq_plan_set_wait_limit: polls must be >= 0");
+    plan->wait_limit = polls;
+    return FQ_OK;
+}
+
+int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *stream)
+{
+    if (!plan || plan->magic != PLAN_MAGIC)
+        return fail(FQ_ERR_NULL, "fq_plan_status: plan is NULL or not valid");
+    if (plan->n_stages < 1)
+        return fail(FQ_ERR_SHAPE, "fq_plan_status: not a stage-ordered plan");
+    int32_t words[2] = {0, 0}; // the sticky count of launches that gave up, then the flags
+    hipError_t e = hipMemcpyAsync(words, plan->sync_dev + 257, sizeof words, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess)
+        return hip_fail(e, "fq_plan_status copy");
+    if (gave_up)
+        *gave_up = words[0];
+    if (flags)
+        *flags = words[1];
+    return FQ_OK;
+}
+
 int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
 {
     if (!plan || plan->magic != PLAN_MAGIC)
@@ -456,8 +585,11 @@ int fq_plan_run(const fq_plan *plan, const int32_t *bits_dev, void *stream)
         return fail(FQ_ERR_NULL, "fq_plan_run: bits_dev is NULL");
     if (reinterpret_cast<uintptr_t>(bits_dev) & 3u)
         return fail(FQ_ERR_ALIGN, "fq_plan_run: bits_dev must be 4-byte aligned");
-    hipError_t e = fq_plan_launch(plan->geom, plan->table_dev, plan->queue_dev, plan->order_dev, bits_dev,
-                                  (hipStream_t)stream);
+    hipError_t e = plan->n_stages > 0
+        ? fq_launch_decode_staged(plan->table_dev, bits_dev, plan->stage_begin_dev, plan->n_stages, plan->geom.max_K,
+                                  STAGED_RES_CHUNKS, plan->sync_dev, plan->wait_limit, (hipStream_t)stream)
+        : fq_plan_launch(plan->geom, plan->table_dev, plan->queue_dev, plan->order_dev, bits_dev,
+                         (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_plan_run launch");
     return FQ_OK;

@@ -70,6 +70,16 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
 // Rows per tile (multiple of 16) for a launch that covers `total_rows` output rows.
 int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 
+// Stage-ordered plan at M = 1 in one persistent launch: entries [stage_begin[s], stage_begin[s + 1])
+// form stage s; `sync_dev` holds the barrier's counters and status words (zero before the first
+// launch).  fq_staged_lds_bytes: dynamic LDS the kernel needs; fq_staged_grid: workgroups it is
+// launched with (0 = does not fit the current device).
+size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks);
+int fq_staged_grid(size_t lds_bytes);
+hipError_t fq_launch_decode_staged(const FqLinearDesc *table_dev, const int32_t *bits_dev,
+                                   const int32_t *stage_begin_dev, int n_stages, int max_K, int res_chunks,
+                                   int *sync_dev, long long wait_limit, hipStream_t stream);
+
 // Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 16 (K split), 64, 128 or 256.
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,

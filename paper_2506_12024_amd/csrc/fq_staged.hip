@@ -1,0 +1,493 @@
+// A decode step in the order a decoder must issue it, in ONE launch (batch 1).
+//
+// A token's linears are not independent: the output projection needs the attention's result, the
+// down projection needs gate and up (Alg. 1's decode loop walks them in order).  Issued as one
+// launch per dependent group, a 7B-shaped step is 128 launches of 2 to 14 microseconds of weight
+// streaming each (Sec. 4.1: the decode phase is bound by loading the weights), and the gaps, ramps
+// and tails between them cost more than the streaming.  This kernel keeps one persistent grid
+// resident for the whole step: the plan's entries carry a stage number, stages run in order, and
+// between two stages stands a grid-wide barrier instead of a kernel boundary.  What makes that pay
+// is that the weights never depend on x: a wavefront keeps several items of weights in flight in
+// registers at all times, across the barrier too, so the weight stream of stage s + 1 is already
+// landing while stage s is being finished and the barrier is being crossed.
+//
+// Roles.  A workgroup (one per compute unit) has CW compute wavefronts and one service wavefront.
+//   compute   walks its items -- (4 rows, one slice of K), as in the one-launch kernel -- through
+//             all stages with two cursors: the issue cursor runs P items ahead of the compute
+//             cursor and only touches weights, scales and zero points; the compute cursor needs
+//             the stage's x in LDS and therefore stops at every stage boundary.  Finished rows go
+//             to LDS, not to memory: a compute wavefront never stores and never waits for
+//             vmcnt(0), its loads stay in flight across every barrier.
+//   service   per stage: writes the workgroup's finished rows to y with write-through stores,
+//             waits for them, announces the workgroup's arrival, waits until every workgroup has
+//             arrived, invalidates the caches and stages the next stage's x into LDS.
+//
+// Shares.  In a stage every workgroup serves exactly one entry: the workgroups are dealt to the
+// stage's entries in proportion to their cost (rows x K x bit-width, from the device-side
+// bit-width array), and an entry's 4-row chunks are dealt evenly to its workgroups.  So a stage
+// needs one x per workgroup, staged once, right after the barrier.
+//
+// Barrier.  Eight arrival counters on lines of their own (workgroup b adds to counter b % 8) count
+// up through the launch: after stage s counter l holds (s + 1) * (workgroups with b % 8 = l).  A
+// ninth word is the abort flag.  The wait is bounded: a service wavefront that has polled
+// `wait_limit` times sets the abort flag and a sticky count; every waiter sees the flag at its next
+// poll and every workgroup leaves the kernel.  The last workgroup out (a tenth counter) puts the
+// counters and the flag back to zero, so that the next launch, and a replayed HIP graph, find them
+// clean.  All workgroups must be resident together (the host launches at most as many as fit).
+//
+// Arithmetic: the item code of the one-launch kernel (fq_gemv.h), rows handled whole by one
+// wavefront in the same slice order, hence bit-identical results.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/flexq.h"
+#include "fq_internal.h"
+#include "fq_gemv.h"
+
+namespace {
+
+constexpr int CW = 8;                  // compute wavefronts per workgroup
+constexpr int THREADS = (CW + 1) * 64; // + the service wavefront
+constexpr int P = 4;                   // items in flight per compute wavefront (register sets)
+constexpr int XU = 24;                 // 16-byte blocks of x a service lane fetches before it places them
+
+// What a workgroup does in one stage.  64 bytes, kept in LDS for every stage of the plan.
+struct Share {
+    const uint8_t *codes; // the copy selected by the entry's bit-width (fp16 weights for 16)
+    const float *scales;
+    const uint8_t *zeros;
+    const uint16_t *x;
+    uint16_t *y;
+    int N, K;
+    int c0, c1; // this workgroup's 4-row chunks of the entry
+    int bits;   // 0: nothing to do in this stage
+    int pad;
+};
+static_assert(sizeof(Share) == 64, "Share is read from LDS as four 16-byte pieces");
+
+// Relative cost of one row of one quantization group at each width (the one-launch kernel's table).
+__device__ __forceinline__ long long group_cost(const FqLinearDesc &d, int bits)
+{
+    if (bits == 2)
+        return d.codes2 ? 64 * 230 * 730 / 1000 : 0;
+    if (bits == 4)
+        return d.codes4 ? 64 * 230 : 0;
+    if (bits == 8)
+        return d.codes8 ? 128 * 200 : 0;
+    if (bits == 16)
+        return d.w16 ? 256 * 200 : 0;
+    return 0;
+}
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <class T>
+__device__ __forceinline__ T *uni_ptr(T *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = (uint32_t)uni((int)(uint32_t)v), hi = (uint32_t)uni((int)(uint32_t)(v >> 32));
+    return (T *)(((uint64_t)hi << 32) | lo);
+}
+
+// Workgroup barrier that leaves vector memory loads in flight: LDS traffic of this wavefront done,
+// then s_barrier (no fence: __syncthreads() would wait for vmcnt(0)).
+__device__ __forceinline__ void wg_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// The loads of item (rows row0 .. row0 + 3, slice j) with the bit-width a run-time value: always
+// four 128-bit loads, four scales, four zero points, so that the count of loads in flight is the
+// same on every path.  For 16 bits scales and zeros alias the weights (loaded, never used).
+__device__ __forceinline__ void issue_any(const uint8_t *codes, const float *scales, const uint8_t *zeros, int N,
+                                          int K, int bits, int row0, int j, Loaded &L)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t Ku = (uint32_t)K, G = Ku >> 7;
+    const int csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3; // log2(codes per lane and slice)
+    const int rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0; // bytes = (2 k) >> rsh
+    const uint32_t k0 = min((uint32_t)(j * 64 + lane) << csh, Ku - (1u << csh));
+    const uint32_t row_bytes = (2 * Ku) >> rsh, byte0 = (2 * k0) >> rsh, g = k0 >> 7;
+#pragma unroll
+    for (int r = 0; r < ROWS_PER_WAVE; r++) {
+        const uint32_t row = (uint32_t)min(row0 + r, N - 1);
+        L.w[r] = load16_stream(codes + (size_t)row * row_bytes + byte0);
+        L.s[r] = as_global<float>(scales + (size_t)row * G)[g];
+        L.z[r] = as_global<uint8_t>(zeros + (size_t)row * G)[g];
+    }
+    // the loads stay here: without this the compiler sinks the scale and zero-point loads to just
+    // before their first use, three steps later, where their latency is no longer hidden
+    asm volatile("" ::: "memory");
+}
+
+// One walker over a compute wavefront's items: stage by stage, inside a stage the wavefront's
+// chunks in order, inside a chunk the slices in order.  Uniform over the wavefront.
+struct Cursor {
+    const uint8_t *codes;
+    const float *scales;
+    const uint8_t *zeros;
+    int N, K, bits;
+    int s;              // stage
+    int chunk, end;     // this wavefront's chunks [chunk, end) still to do in stage s
+    int j, nslice;
+    int wg_c0;          // first chunk of the workgroup's share (results are indexed from it)
+};
+
+__device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int s, int wave)
+{
+    const Share *sh = &shares[s];
+    c.s = s;
+    c.bits = uni(sh->bits);
+    c.codes = uni_ptr(sh->codes);
+    c.scales = uni_ptr(sh->scales);
+    c.zeros = uni_ptr(sh->zeros);
+    c.N = uni(sh->N);
+    c.K = uni(sh->K);
+    const int c0 = uni(sh->c0), c1 = uni(sh->c1);
+    const int n = c.bits ? c1 - c0 : 0;
+    c.wg_c0 = c0;
+    c.chunk = c0 + (int)((long long)n * wave / CW);
+    c.end = c0 + (int)((long long)n * (wave + 1) / CW);
+    c.j = 0;
+    c.nslice = c.bits ? (c.K + slice_span(c.bits) - 1) / slice_span(c.bits) : 1;
+}
+
+// ---- service wavefront ------------------------------------------------------------------------
+
+// x of one entry into LDS in the layout of its bit-width: up to XU blocks per lane are requested
+// before the first is placed, so that a row of up to 12288 inputs costs one memory round trip.
+template <int BITS>
+__device__ __forceinline__ void stage_x_batched(const uint16_t *x, int K, uint4 *lds)
+{
+    const int lane = threadIdx.x & 63;
+    const int Kp = padded_k(K, BITS);
+    if (BITS == 2) {
+        const int npair = Kp >> 4;
+        float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3));
+        constexpr int U = XU / 2;
+        for (int base = 0; base < npair; base += 64 * U) {
+            uint4 va[U], vb[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int pb = base + u * 64 + lane;
+                va[u] = make_uint4(0, 0, 0, 0);
+                vb[u] = make_uint4(0, 0, 0, 0);
+                if (pb < npair && pb * 16 < K) {
+                    va[u] = load16_global(x + (size_t)pb * 16);
+                    vb[u] = load16_global(x + (size_t)pb * 16 + 8);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int pb = base + u * 64 + lane;
+                if (base + u * 64 < npair) // uniform: npair is a multiple of 64
+                    place_pair2(pb, va[u], vb[u], lds, sums);
+            }
+        }
+        return;
+    }
+    const int nblk = Kp >> 3;
+    float *sums = reinterpret_cast<float *>(lds + nblk);
+    for (int base = 0; base < nblk; base += 64 * XU) {
+        uint4 v[XU];
+#pragma unroll
+        for (int u = 0; u < XU; u++) {
+            const int b = base + u * 64 + lane;
+            v[u] = make_uint4(0, 0, 0, 0);
+            if (b < nblk && b * 8 < K)
+                v[u] = load16_global(x + (size_t)b * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < XU; u++) {
+            const int b = base + u * 64 + lane;
+            if (base + u * 64 < nblk) // uniform: nblk is a multiple of 64
+                place_block<BITS>(b, v[u], lds, sums);
+        }
+    }
+}
+
+__device__ __forceinline__ void stage_share_x(const Share *sh, uint4 *xbuf)
+{
+    const int bits = uni(sh->bits);
+    if (bits == 0 || uni(sh->c1) <= uni(sh->c0))
+        return;
+    const uint16_t *x = uni_ptr(sh->x);
+    const int K = uni(sh->K);
+    if (bits == 2)
+        stage_x_batched<2>(x, K, xbuf);
+    else if (bits == 4)
+        stage_x_batched<4>(x, K, xbuf);
+    else if (bits == 8)
+        stage_x_batched<8>(x, K, xbuf);
+    else
+        stage_x_batched<16>(x, K, xbuf);
+}
+
+// Rows finished in this stage, LDS -> y, with stores that write through to memory (visible to the
+// other XCDs' caches once acknowledged).
+__device__ __forceinline__ void store_share_y(const Share *sh, const uint16_t *res)
+{
+    const int lane = threadIdx.x & 63;
+    const int bits = uni(sh->bits), c0 = uni(sh->c0), c1 = uni(sh->c1), N = uni(sh->N);
+    if (bits == 0 || c1 <= c0)
+        return;
+    uint16_t *y = uni_ptr(sh->y);
+    const int row0 = c0 * ROWS_PER_WAVE, rows = min(c1 * ROWS_PER_WAVE, N) - row0;
+    for (int i = lane; i < rows; i += 64) {
+        const uint32_t v = res[i];
+        uint16_t *p = y + row0 + i;
+        asm volatile("global_store_short %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+    }
+}
+
+// Layout of the plan's sync words (ints): counter l at 32 l (l = 0 .. 7), the abort flag at 256,
+// the sticky count of launches that gave up at 257, flags at 258 (bit 0: an entry's bit-width is
+// not attached to its layer, its y was left untouched), the count of finished workgroups at 288.
+constexpr int SY_ABORT = 256, SY_GAVE_UP = 257, SY_FLAGS = 258, SY_DONE = 288;
+
+// Waits until every workgroup has arrived at the end of stage s.  False: the launch is aborted.
+__device__ __forceinline__ bool wait_stage(int *sync, int s, int G, long long wait_limit)
+{
+    const int lane = threadIdx.x & 63;
+    const int mine = lane < 8 ? (s + 1) * ((G - lane + 7) >> 3) : 0;
+    for (long long it = 0;; it++) {
+        int v = 0;
+        if (lane < 8)
+            v = __hip_atomic_load(&sync[32 * lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else if (lane == 8)
+            v = __hip_atomic_load(&sync[SY_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int aborted = __builtin_amdgcn_readlane(v, 8);
+        if (aborted)
+            return false;
+        if (__builtin_amdgcn_ballot_w64(lane >= 8 || v >= mine) == ~0ull)
+            return true;
+        if (it >= wait_limit) {
+            // the first to give up in this launch raises the flag and counts the launch
+            if (lane == 0 &&
+                __hip_atomic_exchange(&sync[SY_ABORT], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0)
+                __hip_atomic_fetch_add(&sync[SY_GAVE_UP], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
+__global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDesc *__restrict__ table,
+                                                                const int32_t *__restrict__ bits_dev,
+                                                                const int32_t *__restrict__ stage_begin,
+                                                                int n_stages, int *sync, long long wait_limit,
+                                                                int res_chunks)
+{
+    extern __shared__ uint4 lds[];
+    Share *shares = reinterpret_cast<Share *>(lds);                       // [n_stages]
+    uint16_t *res = reinterpret_cast<uint16_t *>(lds + 4 * n_stages);     // [res_chunks][4] halves
+    int *flags = reinterpret_cast<int *>(lds + 4 * n_stages + res_chunks / 2); // [0]: abort
+    uint4 *xbuf = lds + 4 * n_stages + res_chunks / 2 + 4;
+    const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int G = gridDim.x, b = blockIdx.x;
+
+    // ---- every workgroup's share of every stage -------------------------------------------
+    bool too_large = false, unattached = false;
+    for (int s = threadIdx.x; s < n_stages; s += THREADS) {
+        const int e0 = stage_begin[s], e1 = stage_begin[s + 1];
+        long long C = 0;
+        for (int e = e0; e < e1; e++) {
+            const long long gc = group_cost(table[e], bits_dev[e]);
+            unattached = unattached || gc == 0;
+            C += gc * (table[e].K >> 7) * ((table[e].N + 3) >> 2);
+        }
+        Share sh = {};
+        if (C > 0) {
+            const long long avail = G - (e1 - e0);
+            long long prefix = 0;
+            for (int e = e0; e < e1; e++) {
+                const FqLinearDesc d = table[e];
+                const int bits = bits_dev[e];
+                const int chunks = (d.N + 3) >> 2;
+                const long long cost = group_cost(d, bits) * (d.K >> 7) * chunks;
+                const int g_lo = (e - e0) + (int)(avail * prefix / C);
+                prefix += cost;
+                const int g_hi = (e - e0 + 1) + (int)(avail * prefix / C);
+                if (b >= g_lo && b < g_hi && cost > 0) {
+                    const long long idx = b - g_lo, n = g_hi - g_lo;
+                    sh.codes = bits == 2 ? d.codes2 : bits == 4 ? d.codes4 : bits == 8 ? d.codes8 : (const uint8_t *)d.w16;
+                    sh.scales = bits == 2 ? d.scales2 : bits == 4 ? d.scales4 : bits == 8 ? d.scales8 : (const float *)d.w16;
+                    sh.zeros = bits == 2 ? d.zeros2 : bits == 4 ? d.zeros4 : bits == 8 ? d.zeros8 : (const uint8_t *)d.w16;
+                    sh.x = d.x;
+                    sh.y = d.y;
+                    sh.N = d.N;
+                    sh.K = d.K;
+                    sh.c0 = (int)(chunks * idx / n);
+                    sh.c1 = (int)(chunks * (idx + 1) / n);
+                    sh.bits = bits;
+                    if (sh.c1 - sh.c0 > res_chunks) { // more rows than the results buffer holds: refuse
+                        too_large = true;
+                        sh.bits = 0;
+                    }
+                }
+            }
+        }
+        shares[s] = sh;
+    }
+    if (threadIdx.x == 0)
+        flags[0] = 0;
+    if (unattached && b == 0)
+        __hip_atomic_fetch_or(&sync[SY_FLAGS], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (too_large)
+        __hip_atomic_fetch_or(&sync[SY_FLAGS], 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+
+    if (wave == CW) {
+        // ---- service wavefront ------------------------------------------------------------
+        stage_share_x(&shares[0], xbuf);
+        wg_barrier(); // x of stage 0 is in LDS
+        bool aborted = false;
+        for (int s = 0; s < n_stages; s++) {
+            wg_barrier(); // the compute wavefronts' rows of stage s are in LDS
+            store_share_y(&shares[s], res);
+            if (s + 1 == n_stages)
+                break;
+            __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): the stores are acknowledged
+            if (lane == 0)
+                __hip_atomic_fetch_add(&sync[32 * (b & 7)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            aborted = !wait_stage(sync, s, G, wait_limit);
+            if (aborted) {
+                if (lane == 0)
+                    flags[0] = 1;
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // what the other workgroups wrote is now read
+                stage_share_x(&shares[s + 1], xbuf);
+            }
+            wg_barrier(); // x of stage s + 1 is in LDS (or the abort flag is)
+            if (aborted)
+                break;
+        }
+        // last workgroup out puts the counters back
+        if (lane == 0) {
+            const int done = __hip_atomic_fetch_add(&sync[SY_DONE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == G - 1) {
+                for (int l = 0; l < 8; l++)
+                    __hip_atomic_store(&sync[32 * l], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&sync[SY_ABORT], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&sync[SY_DONE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        return;
+    }
+
+    // ---- compute wavefronts ---------------------------------------------------------------
+    Cursor ic, cc;
+    enter_stage(ic, shares, 0, wave);
+    enter_stage(cc, shares, 0, wave);
+    bool more = true; // the issue cursor still has items
+    Loaded L[P];
+    // Next item of the issue cursor into L (past the last item: the last item again, discarded).
+    auto issue_next = [&](Loaded &dst) {
+        while (more && ic.chunk >= ic.end) {
+            if (ic.s + 1 >= n_stages)
+                more = false;
+            else
+                enter_stage(ic, shares, ic.s + 1, wave);
+        }
+        const bool valid = more && ic.bits != 0;
+        // a wavefront without items (or past its last one) re-reads the head of the table: valid memory
+        const uint8_t *codes = valid ? ic.codes : (const uint8_t *)table;
+        const float *scales = valid ? ic.scales : (const float *)table;
+        const uint8_t *zeros = valid ? ic.zeros : (const uint8_t *)table;
+        issue_any(codes, scales, zeros, valid ? ic.N : 1, valid ? ic.K : 128, valid ? ic.bits : 16,
+                  valid ? ic.chunk * ROWS_PER_WAVE : 0, valid ? ic.j : 0, dst);
+        if (valid && ++ic.j == ic.nslice) {
+            ic.j = 0;
+            ic.chunk++;
+        }
+    };
+#pragma unroll
+    for (int p = 0; p < P; p++)
+        issue_next(L[p]);
+    wg_barrier(); // x of stage 0 is in LDS
+    float acc[ROWS_PER_WAVE] = {0.f, 0.f, 0.f, 0.f};
+    // The loop is left at its bottom only.  The compiler counts the loads in flight per path, and it
+    // routes every exit of a loop through the loop's latch: with a way out from the middle, each
+    // step would have to wait as if its set had been requested last.  So a wavefront that is done
+    // in step p idles through the rest of the round (requesting loads that are discarded).
+    bool finished = false;
+    do {
+#pragma unroll
+        for (int p = 0; p < P; p++) {
+            // bring the compute cursor to its next item, crossing stage boundaries on the way
+            while (!finished && cc.chunk >= cc.end) {
+                wg_barrier(); // this wavefront's rows of stage cc.s are in LDS
+                if (cc.s + 1 >= n_stages) {
+                    finished = true;
+                } else {
+                    wg_barrier(); // x of the next stage is in LDS
+                    if (uni(flags[0]))
+                        finished = true;
+                    else
+                        enter_stage(cc, shares, cc.s + 1, wave);
+                }
+            }
+            if (!finished) {
+                if (cc.bits == 2)
+                    compute<2>(cc.K, cc.j, L[p], xbuf, acc);
+                else if (cc.bits == 4)
+                    compute<4>(cc.K, cc.j, L[p], xbuf, acc);
+                else if (cc.bits == 8)
+                    compute<8>(cc.K, cc.j, L[p], xbuf, acc);
+                else
+                    compute<16>(cc.K, cc.j, L[p], xbuf, acc);
+                if (++cc.j == cc.nslice) {
+                    // the chunk's four rows: reduce over the wavefront, lane 63 leaves them in LDS
+                    uint32_t h[ROWS_PER_WAVE];
+#pragma unroll
+                    for (int r = 0; r < ROWS_PER_WAVE; r++) {
+                        h[r] = to_half_bits(wave_sum_lane63(acc[r]));
+                        acc[r] = 0.0f;
+                    }
+                    if (lane == 63)
+                        *reinterpret_cast<uint2 *>(res + (size_t)(cc.chunk - cc.wg_c0) * ROWS_PER_WAVE) =
+                            make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                    cc.j = 0;
+                    cc.chunk++;
+                }
+            }
+            issue_next(L[p]);
+        }
+    } while (!finished);
+}
+
+} // namespace
+
+size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks)
+{
+    const size_t kp4 = ((size_t)max_K + 2047) / 2048 * 2048, kp2 = ((size_t)max_K + 4095) / 4096 * 4096;
+    const size_t b4 = kp4 * 2 + kp4 / 32 * 8, b2 = kp2 * 2 + kp2 / 64 * 8;
+    return (size_t)n_stages * sizeof(Share) + (size_t)res_chunks * 8 + 64 + (b4 > b2 ? b4 : b2) + 64;
+}
+
+// Workgroups of the staged kernel: one per compute unit, and never more than fit at once (they
+// wait for each other).  0: the kernel does not fit with this much LDS.
+int fq_staged_grid(size_t lds_bytes)
+{
+    if (lds_bytes > 48 * 1024 &&
+        fq_raise_dynamic_lds((const void *)decode_staged_kernel, 160 * 1024) != hipSuccess)
+        return 0;
+    const int per_cu = fq_workgroups_per_cu((const void *)decode_staged_kernel, THREADS, lds_bytes, 0);
+    return per_cu < 1 ? 0 : fq_device_cus();
+}
+
+hipError_t fq_launch_decode_staged(const FqLinearDesc *table_dev, const int32_t *bits_dev,
+                                   const int32_t *stage_begin_dev, int n_stages, int max_K, int res_chunks,
+                                   int *sync_dev, long long wait_limit, hipStream_t stream)
+{
+    const size_t lds = fq_staged_lds_bytes(n_stages, max_K, res_chunks);
+    const int grid = fq_staged_grid(lds);
+    if (grid < 1)
+        return hipErrorInvalidConfiguration;
+    decode_staged_kernel<<<grid, THREADS, lds, stream>>>(table_dev, bits_dev, stage_begin_dev, n_stages, sync_dev,
+                                                         wait_limit, res_chunks);
+    return hipGetLastError();
+}

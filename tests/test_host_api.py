@@ -243,3 +243,37 @@ def test_linears_static_validation():
                                None) == B.FQ_ERR_SHAPE
     assert b"FQ_STATIC_MAX_ENTRIES" in L.fq_last_error()
     assert L.fq_layer_destroy(h) == B.FQ_OK
+
+
+def test_staged_plan_validation():
+    # every rejection of a stage-ordered plan happens before a HIP call
+    L = fq.lib
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 16, 256, 128) == B.FQ_OK
+    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_OK
+    p = ctypes.c_void_p()
+    arr3 = (ctypes.c_void_p * 3)
+    st = (ctypes.c_int32 * 3)
+    hs = arr3(h.value, h.value, h.value)
+    xs, ys = arr3(FAKE, FAKE, FAKE), arr3(FAKE + 0x100, FAKE + 0x200, FAKE + 0x300)
+    assert L.fq_plan_staged_workspace_bytes(0, 1) == 0 and L.fq_plan_staged_workspace_bytes(3, 4) == 0
+    ws = L.fq_plan_staged_workspace_bytes(3, 2)
+    assert ws % 256 == 0 and ws >= 3 * 64 + 12 + 1156
+
+    def create(stage, M=1, workspace=0x10000, bytes_=1 << 20, xs_=xs, ys_=ys):
+        return L.fq_plan_create_staged(ctypes.byref(p), 3, hs, xs_, ys_, st(*stage), M, workspace, bytes_, None)
+
+    assert create([1, 1, 2]) == B.FQ_ERR_SHAPE             # must start at 0
+    assert create([0, 2, 2]) == B.FQ_ERR_SHAPE             # rises by more than one
+    assert create([0, 1, 0]) == B.FQ_ERR_SHAPE             # decreases
+    assert create([0, 0, 1], M=2) == B.FQ_ERR_SHAPE        # batch 1 only
+    assert create([0, 0, 1], bytes_=64) == B.FQ_ERR_SHAPE  # workspace too small
+    assert create([0, 0, 1], workspace=0x10010) == B.FQ_ERR_ALIGN
+    assert L.fq_plan_create_staged(ctypes.byref(p), 3, hs, xs, ys, None, 1, 0x10000, 1 << 20, None) == B.FQ_ERR_NULL
+    # an entry may read what an EARLIER stage wrote, not what its own or a later stage writes
+    assert create([0, 0, 1], xs_=arr3(FAKE, FAKE + 0x100, FAKE)) == B.FQ_ERR_SHAPE   # x1 = y0, same stage
+    assert create([0, 1, 1], xs_=arr3(FAKE + 0x300, FAKE, FAKE)) == B.FQ_ERR_SHAPE   # x0 = y2, later stage
+    assert b"stage" in L.fq_last_error()
+    assert L.fq_plan_set_wait_limit(None, 5) == B.FQ_ERR_NULL
+    assert L.fq_plan_status(None, None, None, None) == B.FQ_ERR_NULL
+    assert L.fq_layer_destroy(h) == B.FQ_OK
