@@ -6,8 +6,11 @@ Workload (default): the Llama-7B-shaped decode stack at batch 1 -- 32 layers x
 int8 copies of every weight resident in HBM, the bit-width of every linear drawn
 per token from {4, 8} with p = 1/2 (seeded, 128 distinct patterns), and one
 entropy + KL reduction over a 32000-entry logits pair per token.  One *step* =
-one token = all 224 linears (one plan launch, per-entry bit-widths read from
-device memory) followed by one fq_entropy_kl launch.  Attention, norms,
+one token = all 224 linears in the order a decoder must issue them (q/k/v, o,
+gate/up, down, layer after layer: 128 dependent stages in ONE launch of the
+stage-ordered plan, per-entry bit-widths read from device memory) followed by
+one fq_entropy_kl launch.  The same linears as one plan of independent entries
+are timed beside it (`independent_order`).  Attention, norms,
 embeddings, lm_head, sampling and the KV cache are not part of the path.
 
 Every tensor is synthetic and seeded (module ``synth``); weights are quantized
@@ -34,8 +37,10 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
 MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993151.0 / 4978290.0,
-                          # profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md
                           ("llama7b", 16, (4, 8, 16)): 8.052 / 7.857}
+# where those ratios come from (a constant carried from a profile, not counters read in this run)
+TRAFFIC_SOURCE = {("llama7b", 1, (4, 8)): "profiles/decode_m1_plan_llama7b_hbm_traffic.md (rocprofv3 --pmc, scaled by a 1 GiB copy)",
+                  ("llama7b", 16, (4, 8, 16)): "profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md (rocprofv3 --pmc)"}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
 VOCAB = 32000
 SEED = 0
@@ -166,15 +171,23 @@ class Stack:
             plan.run(bits[first:first + n])
 
 
-def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: the
-    first `sample_layers` decoder layers of step 0 (weights regenerated from the same
-    seeds and quantized by the oracle at the drawn bit-width; only the linears and the
-    step's entropy/KL are timed), scaled to the whole stack."""
+def _set_omp_threads(n: int) -> bool:
+    """Number of threads of the OpenMP runtime the oracle's library runs on (the oracle itself is
+    untouched: this is the call OMP_NUM_THREADS would make at start-up)."""
+    import ctypes
+    try:
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+        return True
+    except OSError:
+        return False
+
+
+def _oracle_step_seconds(stack: Stack, sample_layers: int):
+    """Seconds the oracle takes for the linears of the first `sample_layers` decoder layers of step
+    0 (weights regenerated from the same seeds and quantized by the oracle at the drawn bit-width
+    before the clock starts) and for the step's entropy/KL."""
     import oracle
 
-    n_layers = synth.STACKS[stack.name][0]
-    sample_layers = min(sample_layers, n_layers)
     prepared = []
     for (li, mname, K, N), b in zip(stack.entries, stack.patterns[0]):
         if li >= sample_layers:
@@ -193,12 +206,32 @@ def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
     t0 = time.perf_counter()
     oracle.entropy_kl(a[:M], bl[:M])
     t_ent = time.perf_counter() - t0
-    t_step = t_lin * (n_layers / sample_layers) + t_ent
+    return t_lin, t_ent
+
+
+def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
+    """The CPU oracle, as it stands, on a bounded sample of the same workload, scaled to the whole
+    stack: on all the host threads it is given (its OpenMP loops run over output rows) and on one
+    thread (a smaller sample)."""
+    n_layers = synth.STACKS[stack.name][0]
+    sample_layers = min(sample_layers, n_layers)
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": M / t_step, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s on %d threads = %.0f core-seconds, "
-                      "scaled x%.0f) + entropy/KL of the step's logits (%.4f s)"
-                      % (sample_layers, n_layers, t_lin, threads, t_lin * threads, n_layers / sample_layers, t_ent)}
+    M = stack.M
+    t_lin, t_ent = _oracle_step_seconds(stack, sample_layers)
+    t_step = t_lin * (n_layers / sample_layers) + t_ent
+    out = {"value": M / t_step, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+           "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s on %d threads = %.0f core-seconds, "
+                     "scaled x%.0f) + entropy/KL of the step's logits (%.4f s)"
+                     % (sample_layers, n_layers, t_lin, threads, t_lin * threads, n_layers / sample_layers, t_ent)}
+    if threads > 1 and _set_omp_threads(1):
+        one = max(1, sample_layers // 8)
+        t_lin1, t_ent1 = _oracle_step_seconds(stack, one)
+        _set_omp_threads(threads)
+        out["single_thread"] = {"value": M / (t_lin1 * (n_layers / one) + t_ent1), "unit": "tokens/s", "cores": 1,
+                                "sample": "step 0: linears of the first %d of %d decoder layers (%.2f s on one thread, "
+                                          "scaled x%.0f) + entropy/KL (%.4f s)"
+                                          % (one, n_layers, t_lin1, n_layers / one, t_ent1)}
+    return out
 
 
 def bench_prefill(args):
@@ -607,8 +640,11 @@ def main():
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(calibrates HBM byte counters when profiling)")
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--order", default="dependent", choices=["dependent", "independent"],
+                    help="batch 1: the step's linears in the order a decoder must issue them (one launch of "
+                         "the stage-ordered plan; default) or as one plan of independent entries")
     ap.add_argument("--staged", action="store_true",
-                    help="also time the step as 4 dependent plan launches per layer (HIP graph)")
+                    help="also time the dependent order as 4 separate plan launches per layer (HIP graph)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -634,6 +670,22 @@ def main():
     stack = Stack(args.stack, M=args.batch, bit_choices=bit_choices, layers=args.layers,
                   verbose=args.verbose)
     K_steps, W = args.steps, args.warmup
+    fq = stack.fq
+    # Order of the linears inside a step.  "dependent": the order a decoder must issue them in --
+    # q/k/v, then o, then gate/up, then down, layer after layer, every group waiting for the one
+    # before it (4 stages per decoder layer) -- as ONE launch of the stage-ordered plan.
+    # "independent": all linears of the step as one plan of mutually independent entries (every
+    # entry has its own seeded x in this workload, so both orders compute the same numbers); it is
+    # the kernel-level figure for the weight stream.  Batches above 1 are served in the independent
+    # order only.
+    order = args.order if args.batch == 1 else "independent"
+    if order == "dependent":
+        stack.build_staged_plan()
+        run_linears = stack.run_linears_one_launch_staged
+        plan_of_step = stack.staged_plan
+    else:
+        run_linears = stack.run_linears
+        plan_of_step = stack.plan
     if args.copy_mib > 0:
         src = torch.ones(args.copy_mib << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
@@ -642,37 +694,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def step(s):
+        run_linears(s)
+        stack.run_entropy(s)
+
     for s in range(W):
-        stack.step(s)
+        step(s)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(K_steps):
-        stack.step(W + s)
+        step(W + s)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
     step_bytes = [stack.step_bytes(W + s) for s in range(K_steps)]
     total_bytes = float(sum(step_bytes))
+    alg_bytes = total_bytes / K_steps
 
-    # Dominant kernel: the plan launch.  Average duration per launch from HIP events on the
-    # launch stream around K back-to-back launches of the same steps (no entropy launch between).
     stream = torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record(stream)
-    for s in range(K_steps):
-        stack.run_linears(W + s)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    lin_ms = e0.elapsed_time(e1) / K_steps
-    e0.record(stream)
-    for s in range(K_steps):
-        stack.run_entropy(W + s)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ent_us = e0.elapsed_time(e1) / K_steps * 1e3
 
     def time_launches(fn, n):
+        """Mean duration of n back-to-back calls, from HIP events on the launch stream."""
         torch.cuda.synchronize()
         e0.record(stream)
         for i in range(n):
@@ -681,59 +724,56 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    # Cost of switching: the timed mixed patterns against what the same linears cost in the
-    # fixed-precision runs (each linear charged its share, by bytes, of the all-b run).
-    switching = None
-    if set(bit_choices) == {4, 8}:
+    # Dominant kernel of the timed step: the plan launch.
+    lin_ms = time_launches(lambda i: run_linears(W + i), K_steps)
+    ent_us = time_launches(lambda i: stack.run_entropy(W + i), K_steps) * 1e3
+
+    def switching_cost(plan, mixed_ms):
+        """The timed mixed patterns against what the same linears cost in the fixed-precision runs
+        (each linear charged its share, by bytes, of the all-b run)."""
         n = len(stack.layers)
         fixed = {}
         for b in (4, 8):
             bd = torch.full((n,), b, dtype=torch.int32, device="cuda:0")
-            time_launches(lambda i: stack.plan.run(bd), 8)
-            fixed[b] = time_launches(lambda i: stack.plan.run(bd), K_steps)
+            time_launches(lambda i: plan.run(bd), 8)
+            fixed[b] = time_launches(lambda i: plan.run(bd), K_steps)
         tot = {b: sum(weight_bytes(N, K, b) for (_, _, K, N) in stack.entries) for b in (4, 8)}
         pred = np.mean([sum(fixed[int(b)] * weight_bytes(N, K, int(b)) / tot[int(b)]
                             for (_, _, K, N), b in zip(stack.entries, stack.patterns[(W + s) % N_PATTERNS]))
                         for s in range(K_steps)])
         one = stack.bits_dev[W % N_PATTERNS]
-        same_pattern = time_launches(lambda i: stack.plan.run(one), K_steps)
-        switching = {"all_w4_ms": fixed[4], "all_w8_ms": fixed[8], "mixed_ms": lin_ms,
-                     "mixed_predicted_from_fixed_ms": float(pred),
-                     "overhead": lin_ms / float(pred) - 1.0,
-                     "same_pattern_every_token_ms": same_pattern}
+        same_pattern = time_launches(lambda i: plan.run(one), K_steps)
+        return {"all_w4_ms": fixed[4], "all_w8_ms": fixed[8], "mixed_ms": mixed_ms,
+                "mixed_predicted_from_fixed_ms": float(pred), "overhead": mixed_ms / float(pred) - 1.0,
+                "same_pattern_every_token_ms": same_pattern}
 
-    # The same step issued as a real decoder would have to: 4 dependent plan launches per layer
-    # (q/k/v, o, gate/up, down), captured once in a HIP graph and replayed.
-    staged_ms = None
-    if args.staged:
-        stack.build_stage_plans()
-        stack.run_linears_staged(W)
-        torch.cuda.synchronize()
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            stack.run_linears_staged(W)
-            side.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                stack.run_linears_staged(W)
-        torch.cuda.synchronize()
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        reps = max(8, K_steps // 4)
-        for _ in range(reps):
-            graph.replay()
-        torch.cuda.synchronize()
-        staged_ms = (time.perf_counter() - t0) / reps * 1e3
-        stack.build_staged_plan()
-        for i in range(8):
-            stack.run_linears_one_launch_staged(W + i)
-        one_launch_ms = time_launches(lambda i: stack.run_linears_one_launch_staged(W + i), K_steps)
-        print("one-launch staged plan: %.4f ms per step, status %r" % (one_launch_ms, stack.staged_plan.status()),
-              file=sys.stderr, flush=True)
-    alg_bytes = total_bytes / K_steps
-    achieved = alg_bytes / (lin_ms * 1e-3) / 1e9
+    switching = switching_cost(plan_of_step, lin_ms) if set(bit_choices) == {4, 8} else None
+
+    # What this machine gives a kernel that only reads (same access pattern as the decode kernels).
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    probe.fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    time_launches(lambda i: fq.fq_stream_read(probe, probe.numel(), sink), 3)
+    stream_gbps = probe.numel() / (time_launches(lambda i: fq.fq_stream_read(probe, probe.numel(), sink), 20) * 1e-3) / 1e9
+    del probe
+
+    traffic_key = (args.stack, args.batch, bit_choices)
+    kernel_of = {"dependent": "decode_staged_kernel (one launch: %d stages)" % getattr(stack, "n_stages", 0),
+                 "independent": "decode_m1_kernel (plan launch)" if args.batch == 1 else
+                                "decode_stream_kernel + decode_skinny_kernel" if 2 in bit_choices else
+                                "decode_stream_kernel"}
+
+    def roofline(kernel, ms, traffic=None, traffic_source=None):
+        achieved = alg_bytes / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "frac_of_measured_stream": achieved / stream_gbps,
+                "traffic": traffic, "traffic_source": traffic_source,
+                "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg_bytes}
+
+    def measured_traffic():
+        if args.layers is None and traffic_key in MEASURED_TRAFFIC_RATIO:
+            return alg_bytes * MEASURED_TRAFFIC_RATIO[traffic_key], TRAFFIC_SOURCE[traffic_key]
+        return None, None
 
     out = {
         "metric": "effective weight GB/s + decode tokens/s, mixed W4/W8 Llama-7B-shaped linears",
@@ -742,29 +782,61 @@ def main():
         "n_gpus": 1, "steps": K_steps, "warmup": W,
         "ms_per_step": elapsed / K_steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f16 x int%s -> f32" % "/int".join(str(b) for b in bit_choices if b != 16)
+                 + (" (+ f16 x f16)" if 16 in bit_choices else ""),
         "data": "synthetic",
         "config": {"workload": "%s decode stack, batch %d, per-layer bits drawn from {%s} per token, "
                                "%d linears + entropy/KL over %d logits per step"
                                % (args.stack, args.batch, args.bits, len(stack.layers), VOCAB),
-                   "launches_per_step": 2 if args.batch == 1 else (4 if 2 in bit_choices else 3), "build_seconds": round(stack.build_seconds, 1)},
+                   "order": order,
+                   "launches_per_step": 2 if args.batch == 1 else (4 if 2 in bit_choices else 3),
+                   "build_seconds": round(stack.build_seconds, 1)},
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
         "entropy_kl_us": ent_us,
-        "roofline": {"bound": "hbm", "kernel": "%s (plan launch)" % ("decode_m1_kernel" if args.batch == 1 else
-                                                                      "decode_stream_kernel + decode_skinny_kernel"
-                                                                      if 2 in bit_choices else "decode_stream_kernel"),
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": alg_bytes * MEASURED_TRAFFIC_RATIO[(args.stack, args.batch, bit_choices)]
-                     if args.layers is None and (args.stack, args.batch, bit_choices) in MEASURED_TRAFFIC_RATIO
-                     else None,
-                     "avg_launch_ms": lin_ms, "algorithmic_bytes_per_launch": alg_bytes},
+        "stream_read_GBps": stream_gbps,
     }
+    if order == "dependent":
+        out["roofline"] = roofline(kernel_of["dependent"], lin_ms)
+        gave_up, flags = stack.staged_plan.status()
+        out["staged_plan_status"] = {"gave_up": gave_up, "flags": flags}
+        # beside it: the same linears as one plan of independent entries (the weight stream alone)
+        for i in range(8):
+            stack.run_linears(W + i)
+        ind_ms = time_launches(lambda i: stack.run_linears(W + i), K_steps)
+        traffic, source = measured_traffic()
+        ind = {"ms_per_step": ind_ms + ent_us * 1e-3, "tokens_per_s": 1e3 / (ind_ms + ent_us * 1e-3),
+               "roofline": roofline(kernel_of["independent"], ind_ms, traffic, source)}
+        if set(bit_choices) == {4, 8}:
+            ind["switching"] = switching_cost(stack.plan, ind_ms)
+        out["independent_order"] = ind
+        if args.staged:
+            # the dependent order as separate launches: 4 plan launches per layer, captured in a HIP graph
+            stack.build_stage_plans()
+            stack.run_linears_staged(W)
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                stack.run_linears_staged(W)
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    stack.run_linears_staged(W)
+            torch.cuda.synchronize()
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = max(8, K_steps // 4)
+            for _ in range(reps):
+                graph.replay()
+            torch.cuda.synchronize()
+            out["dependent_order_as_%d_launches_ms" % len(stack.stage_plans)] = (time.perf_counter() - t0) / reps * 1e3
+    else:
+        traffic, source = measured_traffic()
+        out["roofline"] = roofline(kernel_of["independent"], lin_ms, traffic, source)
     if switching is not None:
         out["switching"] = switching
-    if staged_ms is not None:
-        out["staged_4_launches_per_layer_ms"] = staged_ms
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(stack)
     print(json.dumps(out))

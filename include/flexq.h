@@ -224,6 +224,16 @@ int fq_linears_static(int count, const fq_layer *const *layers, const void *cons
                       int M, const int32_t *bits_dev, void *stream);
 
 /*
+ * Measurement aid: reads `bytes` bytes (rounded down to a multiple of 16) once, with the access
+ * pattern of the decode kernels and nothing else -- the rate a benchmark may set the weight stream
+ * of Sec. 4.1 against, next to the published peak.  `sink` receives a word only if the data
+ * happen to xor to one particular value.
+ *   src   device, 16-byte aligned   (read)
+ *   sink  device, u32 [1]           (hardly ever written)
+ */
+int fq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
+/*
  * W8A8 prefill (Sec. 4.1, 4.3, 4.5): the prompt is processed with the resident INT8 weights
  * against 8-bit activations on the integer matrix cores.
  *

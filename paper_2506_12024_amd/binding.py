@@ -27,6 +27,7 @@ EXPORTS = [
     "fq_entropy_kl_f16", "fq_rank_ascending", "fq_quantize_act", "fq_linear_w8a8",
     "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy", "fq_linears_static",
     "fq_plan_staged_workspace_bytes", "fq_plan_create_staged", "fq_plan_set_wait_limit", "fq_plan_status",
+    "fq_stream_read",
 ]
 
 
@@ -45,6 +46,12 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             "libflexq.so is not built: run `python -m paper_2506_12024_amd.build` "
             "(there is no fallback path)")
+    try:
+        # PyTorch-ROCm carries its own HIP runtime; loaded first, the library binds to that one
+        # instead of bringing a second runtime (with no devices set up) into the process
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(_LIB_PATH)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     L.fq_last_error.restype = ctypes.c_char_p
@@ -79,6 +86,8 @@ def _load() -> ctypes.CDLL:
     L.fq_plan_set_wait_limit.argtypes = [vp, ctypes.c_longlong]
     L.fq_plan_status.restype = ci
     L.fq_plan_status.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), vp]
+    L.fq_stream_read.restype = ci
+    L.fq_stream_read.argtypes = [vp, sz, vp, vp]
     L.fq_linears_static.restype = ci
     L.fq_linears_static.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, vp]
     L.fq_entropy_kl.restype = ci
@@ -259,6 +268,10 @@ class StagedPlan(Plan):
         g, f = ctypes.c_int32(), ctypes.c_int32()
         _check(lib.fq_plan_status(self.handle, ctypes.byref(g), ctypes.byref(f), _stream(stream)))
         return g.value, f.value
+
+
+def fq_stream_read(src, nbytes: int, sink, stream=None):
+    _check(lib.fq_stream_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)))
 
 
 def fq_linears_static(layers, xs, ys, M: int, bits_dev, stream=None):

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexq.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["fq_api.hip", "fq_device.hip", "fq_noalloc.hip", "fq_quantize.hip", "fq_entropy.hip", "fq_decode.hip", "fq_staged.hip", "fq_skinny.hip", "fq_stream.hip", "fq_prefill.hip", "fq_w8a8.hip", "fq_sched.hip", "fq_lmhead.hip"]
+SOURCES = ["fq_api.hip", "fq_device.hip", "fq_noalloc.hip", "fq_probe.hip", "fq_quantize.hip", "fq_entropy.hip", "fq_decode.hip", "fq_staged.hip", "fq_skinny.hip", "fq_stream.hip", "fq_prefill.hip", "fq_w8a8.hip", "fq_sched.hip", "fq_lmhead.hip"]
 HEADERS = [os.path.join(CSRC, "fq_internal.h"), os.path.join(CSRC, "fq_gemv.h"),
            os.path.join(os.path.dirname(HERE), "include", "flexq.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

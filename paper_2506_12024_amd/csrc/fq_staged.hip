@@ -16,29 +16,42 @@
 //             all stages with two cursors: the issue cursor runs P items ahead of the compute
 //             cursor and only touches weights, scales and zero points; the compute cursor needs
 //             the stage's x in LDS and therefore stops at every stage boundary.  Finished rows go
-//             to LDS, not to memory: a compute wavefront never stores and never waits for
-//             vmcnt(0), its loads stay in flight across every barrier.
+//             to LDS, not to memory: a compute wavefront never stores, and between two stage
+//             boundaries it never waits for more than the item it is about to use.
 //   service   per stage: writes the workgroup's finished rows to y with write-through stores,
-//             waits for them, announces the workgroup's arrival, waits until every workgroup has
-//             arrived, invalidates the caches and stages the next stage's x into LDS.
+//             waits for them, announces the workgroup's arrival and waits until every workgroup
+//             has arrived.
+// After that all wavefronts stage the next stage's x into LDS together (one 16-byte block or a few
+// per thread, read at agent scope so that no cache of this XCD can answer with an older use of the
+// buffer).
 //
 // Shares.  In a stage every workgroup serves exactly one entry: the workgroups are dealt to the
 // stage's entries in proportion to their cost (rows x K x bit-width, from the device-side
 // bit-width array), and an entry's 4-row chunks are dealt evenly to its workgroups.  So a stage
 // needs one x per workgroup, staged once, right after the barrier.
 //
-// Barrier.  Eight arrival counters on lines of their own (workgroup b adds to counter b % 8) count
-// up through the launch: after stage s counter l holds (s + 1) * (workgroups with b % 8 = l).  A
-// ninth word is the abort flag.  The wait is bounded: a service wavefront that has polled
-// `wait_limit` times sets the abort flag and a sticky count; every waiter sees the flag at its next
-// poll and every workgroup leaves the kernel.  The last workgroup out (a tenth counter) puts the
-// counters and the flag back to zero, so that the next launch, and a replayed HIP graph, find them
-// clean.  All workgroups must be resident together (the host launches at most as many as fit).
+// Barrier.  NC arrival counters on lines of their own (workgroup b adds to counter b % NC: adds to
+// one address are served one after the other, with 32 workgroups behind one counter they alone
+// took 2 to 3 microseconds) count up through the launch: after stage s counter l holds (s + 1) *
+// (workgroups with b % NC = l).  One more word is the abort flag.  The wait is bounded: a service
+// wavefront that has polled `wait_limit` times raises the abort flag and, if it is the first, adds
+// one to a sticky count; every waiter sees the flag at its next poll and every workgroup leaves the
+// kernel.  The last workgroup out (one more counter) puts the counters and the flag back to zero,
+// so that the next launch, and a replayed HIP graph, find them clean.  All workgroups must be
+// resident together (the host launches at most as many as fit).
+//
+// What a stage costs (7B-shaped stack, bits from {4, 8}, time stamps of every workgroup): the
+// compute wavefronts' part 8.9 us (the arithmetic and the requests of 5 items per wavefront: with
+// the weights prefetched this part is bound by the vector ALUs, not by memory), stores and their
+// acknowledgement 0.5, the wait for the other workgroups 3.7 (of which 1.1 is the median spread of
+// the arrivals, 2.3 the way of the last arrival to the pollers), x 0.9.
 //
 // Arithmetic: the item code of the one-launch kernel (fq_gemv.h), rows handled whole by one
 // wavefront in the same slice order, hence bit-identical results.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "../../include/flexq.h"
 #include "fq_internal.h"
@@ -46,10 +59,11 @@
 
 namespace {
 
-constexpr int CW = 8;                  // compute wavefronts per workgroup
-constexpr int THREADS = (CW + 1) * 64; // + the service wavefront
-constexpr int P = 4;                   // items in flight per compute wavefront (register sets)
-constexpr int XU = 24;                 // 16-byte blocks of x a service lane fetches before it places them
+constexpr int CW = 7;                  // compute wavefronts per workgroup
+constexpr int THREADS = (CW + 1) * 64; // + the service wavefront: two wavefronts per SIMD, 256 registers each
+constexpr int P = 7;                   // items in flight per compute wavefront (register sets): 8 loads each,
+                                       // 56 of the 63 loads a wavefront can have outstanding
+constexpr int XU = 3;                  // 16-byte blocks of x a thread fetches before it places them
 
 // What a workgroup does in one stage.  64 bytes, kept in LDS for every stage of the plan.
 struct Share {
@@ -99,28 +113,68 @@ __device__ __forceinline__ void wg_barrier()
     asm volatile("" ::: "memory");
 }
 
-// The loads of item (rows row0 .. row0 + 3, slice j) with the bit-width a run-time value: always
-// four 128-bit loads, four scales, four zero points, so that the count of loads in flight is the
-// same on every path.  For 16 bits scales and zeros alias the weights (loaded, never used).
+// What one lane holds for one item in flight: 16 bytes of codes of each of the 4 rows, and its part
+// of the item's scales and zero points, which are fetched TRANSPOSED: a slice touches GS = 32 / 16 /
+// 8 groups of a row (2 / 4 / 8 bits), so (4 rows x GS groups) fit one or two loads of the wavefront
+// -- lane l fetches row l / GS, group l % GS -- instead of one load per row and lane.  Eight load
+// instructions and 20 registers per item; the lanes pick their rows' values out of the other lanes
+// (ds_bpermute) when the item is computed.
+struct Item {
+    uint4 w[ROWS_PER_WAVE];
+    float s[2];
+    uint8_t z[2]; // kept as bytes: widened where used, so that nothing touches a register while its load is in flight
+};
+
+// The loads of item (rows row0 .. row0 + 3, slice j) with the bit-width a run-time value: the same
+// eight load instructions on every path, so that the count of loads in flight is the same whatever
+// the widths of the items are.  For 16 bits scales and zeros alias the weights (loaded, never used).
 __device__ __forceinline__ void issue_any(const uint8_t *codes, const float *scales, const uint8_t *zeros, int N,
-                                          int K, int bits, int row0, int j, Loaded &L)
+                                          int K, int bits, int row0, int j, Item &L)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t Ku = (uint32_t)K, G = Ku >> 7;
     const int csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3; // log2(codes per lane and slice)
     const int rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0; // bytes = (2 k) >> rsh
     const uint32_t k0 = min((uint32_t)(j * 64 + lane) << csh, Ku - (1u << csh));
-    const uint32_t row_bytes = (2 * Ku) >> rsh, byte0 = (2 * k0) >> rsh, g = k0 >> 7;
+    const uint32_t row_bytes = (2 * Ku) >> rsh, byte0 = (2 * k0) >> rsh;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
         const uint32_t row = (uint32_t)min(row0 + r, N - 1);
         L.w[r] = load16_stream(codes + (size_t)row * row_bytes + byte0);
-        L.s[r] = as_global<float>(scales + (size_t)row * G)[g];
-        L.z[r] = as_global<uint8_t>(zeros + (size_t)row * G)[g];
     }
-    // the loads stay here: without this the compiler sinks the scale and zero-point loads to just
-    // before their first use, three steps later, where their latency is no longer hidden
+    // scales and zero points: lane l -> (row l >> gsh, group l & (GS - 1)) of the slice; at 2 bits the
+    // second pair of loads takes rows 2 and 3, at the other widths it repeats the first
+    const int gsh = csh - 1; // log2(GS): 5, 4, 3 (2 for fp16: unused)
+    const uint32_t g = min((uint32_t)(j << gsh) + (uint32_t)(lane & ((1 << gsh) - 1)), G - 1);
+    const int rr = (lane >> gsh) & 3;
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const uint32_t row = (uint32_t)min(row0 + (bits == 2 ? rr + 2 * h : rr), N - 1);
+        L.s[h] = as_global<float>(scales + (size_t)row * G)[g];
+        L.z[h] = as_global<uint8_t>(zeros + (size_t)row * G)[g];
+    }
+    // the loads stay here: the compiler would otherwise sink some of them towards their first use,
+    // steps later, where their latency is no longer hidden
     asm volatile("" ::: "memory");
+}
+
+// The item as the shared arithmetic takes it: every lane gets the scale and zero point of its own
+// group for each of the four rows from the lane that fetched them.
+__device__ __forceinline__ void expand(const Item &I, int K, int bits, int j, Loaded &L)
+{
+    const int lane = threadIdx.x & 63;
+    const int csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3, gsh = csh - 1;
+    const uint32_t Ku = (uint32_t)K;
+    const uint32_t k0 = min((uint32_t)(j * 64 + lane) << csh, Ku - (1u << csh));
+    const int gi = (int)(k0 >> 7) - (j << gsh); // my group's place among the slice's groups
+#pragma unroll
+    for (int r = 0; r < ROWS_PER_WAVE; r++) {
+        L.w[r] = I.w[r];
+        const int h = bits == 2 ? r >> 1 : 0;
+        const int src = ((bits == 2 ? r & 1 : r) << gsh) + gi;
+        L.s[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, h ? I.s[1] : I.s[0])));
+        L.z[r] = (uint8_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)(h ? I.z[1] : I.z[0]));
+    }
 }
 
 // One walker over a compute wavefront's items: stage by stage, inside a stage the wavefront's
@@ -157,53 +211,64 @@ __device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int 
 
 // ---- service wavefront ------------------------------------------------------------------------
 
-// x of one entry into LDS in the layout of its bit-width: up to XU blocks per lane are requested
-// before the first is placed, so that a row of up to 12288 inputs costs one memory round trip.
-template <int BITS>
-__device__ __forceinline__ void stage_x_batched(const uint16_t *x, int K, uint4 *lds)
+// 16 bytes of x, read at agent scope (two 64-bit relaxed atomic loads: they are served where the
+// other XCDs' write-through stores have arrived, whatever this XCD's caches still hold of an
+// earlier use of the buffer).
+__device__ __forceinline__ uint4 load16_coherent(const uint16_t *p)
 {
-    const int lane = threadIdx.x & 63;
+    const FQ_GLOBAL uint64_t *q = (const FQ_GLOBAL uint64_t *)p;
+    const uint64_t lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint64_t hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
+// x of one entry into LDS in the layout of its bit-width, by all THREADS threads of the workgroup:
+// XU blocks per thread are requested before the first is placed, so a row of up to 12288 inputs
+// costs one memory round trip and three blocks' worth of placing per thread.
+template <int BITS>
+__device__ __forceinline__ void stage_x_all(const uint16_t *x, int K, uint4 *lds)
+{
+    const int tid = threadIdx.x;
     const int Kp = padded_k(K, BITS);
     if (BITS == 2) {
-        const int npair = Kp >> 4;
+        const int npair = Kp >> 4; // a multiple of 256
         float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3));
-        constexpr int U = XU / 2;
-        for (int base = 0; base < npair; base += 64 * U) {
-            uint4 va[U], vb[U];
+        for (int base = 0; base < npair; base += THREADS * XU) {
+            uint4 va[XU], vb[XU];
 #pragma unroll
-            for (int u = 0; u < U; u++) {
-                const int pb = base + u * 64 + lane;
+            for (int u = 0; u < XU; u++) {
+                const int pb = base + u * THREADS + tid;
                 va[u] = make_uint4(0, 0, 0, 0);
                 vb[u] = make_uint4(0, 0, 0, 0);
                 if (pb < npair && pb * 16 < K) {
-                    va[u] = load16_global(x + (size_t)pb * 16);
-                    vb[u] = load16_global(x + (size_t)pb * 16 + 8);
+                    va[u] = load16_coherent(x + (size_t)pb * 16);
+                    vb[u] = load16_coherent(x + (size_t)pb * 16 + 8);
                 }
             }
 #pragma unroll
-            for (int u = 0; u < U; u++) {
-                const int pb = base + u * 64 + lane;
-                if (base + u * 64 < npair) // uniform: npair is a multiple of 64
+            for (int u = 0; u < XU; u++) {
+                const int pb = base + u * THREADS + tid;
+                if (((base + u * THREADS + tid) & ~63) < npair) // uniform over the wavefront: npair is a multiple of 64
                     place_pair2(pb, va[u], vb[u], lds, sums);
             }
         }
         return;
     }
-    const int nblk = Kp >> 3;
+    const int nblk = Kp >> 3; // a multiple of 64
     float *sums = reinterpret_cast<float *>(lds + nblk);
-    for (int base = 0; base < nblk; base += 64 * XU) {
+    for (int base = 0; base < nblk; base += THREADS * XU) {
         uint4 v[XU];
 #pragma unroll
         for (int u = 0; u < XU; u++) {
-            const int b = base + u * 64 + lane;
+            const int b = base + u * THREADS + tid;
             v[u] = make_uint4(0, 0, 0, 0);
             if (b < nblk && b * 8 < K)
-                v[u] = load16_global(x + (size_t)b * 8);
+                v[u] = load16_coherent(x + (size_t)b * 8);
         }
 #pragma unroll
         for (int u = 0; u < XU; u++) {
-            const int b = base + u * 64 + lane;
-            if (base + u * 64 < nblk) // uniform: nblk is a multiple of 64
+            const int b = base + u * THREADS + tid;
+            if ((b & ~63) < nblk) // uniform over the wavefront
                 place_block<BITS>(b, v[u], lds, sums);
         }
     }
@@ -217,13 +282,13 @@ __device__ __forceinline__ void stage_share_x(const Share *sh, uint4 *xbuf)
     const uint16_t *x = uni_ptr(sh->x);
     const int K = uni(sh->K);
     if (bits == 2)
-        stage_x_batched<2>(x, K, xbuf);
+        stage_x_all<2>(x, K, xbuf);
     else if (bits == 4)
-        stage_x_batched<4>(x, K, xbuf);
+        stage_x_all<4>(x, K, xbuf);
     else if (bits == 8)
-        stage_x_batched<8>(x, K, xbuf);
+        stage_x_all<8>(x, K, xbuf);
     else
-        stage_x_batched<16>(x, K, xbuf);
+        stage_x_all<16>(x, K, xbuf);
 }
 
 // Rows finished in this stage, LDS -> y, with stores that write through to memory (visible to the
@@ -243,27 +308,43 @@ __device__ __forceinline__ void store_share_y(const Share *sh, const uint16_t *r
     }
 }
 
-// Layout of the plan's sync words (ints): counter l at 32 l (l = 0 .. 7), the abort flag at 256,
-// the sticky count of launches that gave up at 257, flags at 258 (bit 0: an entry's bit-width is
-// not attached to its layer, its y was left untouched), the count of finished workgroups at 288.
-constexpr int SY_ABORT = 256, SY_GAVE_UP = 257, SY_FLAGS = 258, SY_DONE = 288;
+// Layout of the plan's sync words (ints): counter l at 32 l (l = 0 .. NC - 1), then the abort flag,
+// the sticky count of launches that gave up, flags (bit 0: an entry's bit-width is not attached to
+// its layer, its y was left untouched; bit 1: a share too large for the results buffer), and on the
+// next line the count of finished workgroups.
+constexpr int NC = 32; // arrival counters
+constexpr int SY_ABORT = 32 * NC, SY_GAVE_UP = SY_ABORT + 1, SY_FLAGS = SY_ABORT + 2, SY_DONE = SY_ABORT + 32;
 
 // Waits until every workgroup has arrived at the end of stage s.  False: the launch is aborted.
+// Lanes 0 .. NC - 1 watch one counter each, lane NC the abort flag.  A poll is a round trip to memory of a
+// microsecond or more, so four are kept in flight, a fraction of that apart: the arrival of the last
+// workgroup is seen one round trip after it happened, not up to two.
 __device__ __forceinline__ bool wait_stage(int *sync, int s, int G, long long wait_limit)
 {
     const int lane = threadIdx.x & 63;
-    const int mine = lane < 8 ? (s + 1) * ((G - lane + 7) >> 3) : 0;
-    for (long long it = 0;; it++) {
-        int v = 0;
-        if (lane < 8)
-            v = __hip_atomic_load(&sync[32 * lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else if (lane == 8)
-            v = __hip_atomic_load(&sync[SY_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int aborted = __builtin_amdgcn_readlane(v, 8);
-        if (aborted)
-            return false;
-        if (__builtin_amdgcn_ballot_w64(lane >= 8 || v >= mine) == ~0ull)
-            return true;
+    const int mine = lane < NC ? (s + 1) * ((G - lane + NC - 1) / NC) : 0;
+    const int *word = &sync[lane < NC ? 32 * lane : SY_ABORT];
+    auto poll = [&]() -> int {
+        return lane <= NC ? __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    };
+    constexpr int Q = 4;
+    int v[Q];
+#pragma unroll
+    for (int q = 0; q + 1 < Q; q++) {
+        v[q] = poll();
+        __builtin_amdgcn_s_sleep(4);
+    }
+    for (long long it = 0;; it += Q) {
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            v[(q + Q - 1) % Q] = poll();
+            const int got = v[q]; // the oldest of the polls in flight
+            if (__builtin_amdgcn_readlane(got, NC))
+                return false;
+            if (__builtin_amdgcn_ballot_w64(lane >= NC || got >= mine) == ~0ull)
+                return true;
+            __builtin_amdgcn_s_sleep(4);
+        }
         if (it >= wait_limit) {
             // the first to give up in this launch raises the flag and counts the launch
             if (lane == 0 &&
@@ -271,9 +352,19 @@ __device__ __forceinline__ bool wait_stage(int *sync, int s, int G, long long wa
                 __hip_atomic_fetch_add(&sync[SY_GAVE_UP], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return false;
         }
-        __builtin_amdgcn_s_sleep(2);
     }
 }
+
+#ifdef FQ_STAGED_PROBE
+__device__ long long g_probe[256][160][8];
+#define PROBE(slot)                                                                                           \
+    do {                                                                                                      \
+        if (lane == 0 && b < 256 && s < 160)                                                                  \
+            g_probe[b][s][slot] = (long long)wall_clock64();                                                  \
+    } while (0)
+#else
+#define PROBE(slot)
+#endif
 
 __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev,
@@ -340,36 +431,42 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
         __hip_atomic_fetch_or(&sync[SY_FLAGS], 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
 
+    // x of stage 0: by everyone, before anything else is requested
+    stage_share_x(&shares[0], xbuf);
+
     if (wave == CW) {
         // ---- service wavefront ------------------------------------------------------------
-        stage_share_x(&shares[0], xbuf);
         wg_barrier(); // x of stage 0 is in LDS
-        bool aborted = false;
         for (int s = 0; s < n_stages; s++) {
+            PROBE(0);
             wg_barrier(); // the compute wavefronts' rows of stage s are in LDS
+            PROBE(1);
             store_share_y(&shares[s], res);
             if (s + 1 == n_stages)
                 break;
             __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): the stores are acknowledged
+            PROBE(2);
             if (lane == 0)
-                __hip_atomic_fetch_add(&sync[32 * (b & 7)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            aborted = !wait_stage(sync, s, G, wait_limit);
-            if (aborted) {
-                if (lane == 0)
-                    flags[0] = 1;
-            } else {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); // what the other workgroups wrote is now read
-                stage_share_x(&shares[s + 1], xbuf);
-            }
-            wg_barrier(); // x of stage s + 1 is in LDS (or the abort flag is)
+                __hip_atomic_fetch_add(&sync[32 * (b % NC)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool aborted = !wait_stage(sync, s, G, wait_limit);
+            PROBE(3);
+            if (aborted && lane == 0)
+                flags[0] = 1;
+            wg_barrier(); // every workgroup has arrived (or the abort flag is up)
             if (aborted)
                 break;
+            PROBE(4);
+            stage_share_x(&shares[s + 1], xbuf); // with the compute wavefronts
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            PROBE(5);
+            wg_barrier(); // x of stage s + 1 is in LDS
+            PROBE(6);
         }
         // last workgroup out puts the counters back
         if (lane == 0) {
             const int done = __hip_atomic_fetch_add(&sync[SY_DONE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (done == G - 1) {
-                for (int l = 0; l < 8; l++)
+                for (int l = 0; l < NC; l++)
                     __hip_atomic_store(&sync[32 * l], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(&sync[SY_ABORT], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(&sync[SY_DONE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -383,9 +480,12 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
     enter_stage(ic, shares, 0, wave);
     enter_stage(cc, shares, 0, wave);
     bool more = true; // the issue cursor still has items
-    Loaded L[P];
-    // Next item of the issue cursor into L (past the last item: the last item again, discarded).
-    auto issue_next = [&](Loaded &dst) {
+    Item L[P];
+    // Next item of the issue cursor into dst.  Past the last item: the same eight load instructions
+    // on the head of the table (cached, discarded) -- the compiler counts the loads in flight per
+    // path, and only with the same count on every path does it let a set's loads stay in flight
+    // until the set is used.
+    auto issue_next = [&](Item &dst) __attribute__((always_inline)) {
         while (more && ic.chunk >= ic.end) {
             if (ic.s + 1 >= n_stages)
                 more = false;
@@ -414,52 +514,76 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
     // step would have to wait as if its set had been requested last.  So a wavefront that is done
     // in step p idles through the rest of the round (requesting loads that are discarded).
     bool finished = false;
-    do {
-#pragma unroll
-        for (int p = 0; p < P; p++) {
-            // bring the compute cursor to its next item, crossing stage boundaries on the way
-            while (!finished && cc.chunk >= cc.end) {
-                wg_barrier(); // this wavefront's rows of stage cc.s are in LDS
-                if (cc.s + 1 >= n_stages) {
+    // One step of the round on set p (a compile-time index: the sets must stay in registers).
+    auto step = [&](auto pc) __attribute__((always_inline)) {
+        constexpr int p = decltype(pc)::value;
+        // bring the compute cursor to its next item, crossing stage boundaries on the way
+        while (!finished && cc.chunk >= cc.end) {
+            wg_barrier(); // this wavefront's rows of stage cc.s are in LDS
+            if (cc.s + 1 >= n_stages) {
+                finished = true;
+            } else {
+                wg_barrier(); // every workgroup has arrived (or the abort flag is up)
+                if (uni(flags[0])) {
                     finished = true;
                 } else {
+                    // x of the next stage, with the service wavefront.  This waits for every load of
+                    // this wavefront (returns are in order); they were all requested before the
+                    // barrier was entered, microseconds ago.
+                    stage_share_x(&shares[cc.s + 1], xbuf);
                     wg_barrier(); // x of the next stage is in LDS
-                    if (uni(flags[0]))
-                        finished = true;
-                    else
-                        enter_stage(cc, shares, cc.s + 1, wave);
+                    enter_stage(cc, shares, cc.s + 1, wave);
                 }
             }
-            if (!finished) {
-                if (cc.bits == 2)
-                    compute<2>(cc.K, cc.j, L[p], xbuf, acc);
-                else if (cc.bits == 4)
-                    compute<4>(cc.K, cc.j, L[p], xbuf, acc);
-                else if (cc.bits == 8)
-                    compute<8>(cc.K, cc.j, L[p], xbuf, acc);
-                else
-                    compute<16>(cc.K, cc.j, L[p], xbuf, acc);
-                if (++cc.j == cc.nslice) {
-                    // the chunk's four rows: reduce over the wavefront, lane 63 leaves them in LDS
-                    uint32_t h[ROWS_PER_WAVE];
-#pragma unroll
-                    for (int r = 0; r < ROWS_PER_WAVE; r++) {
-                        h[r] = to_half_bits(wave_sum_lane63(acc[r]));
-                        acc[r] = 0.0f;
-                    }
-                    if (lane == 63)
-                        *reinterpret_cast<uint2 *>(res + (size_t)(cc.chunk - cc.wg_c0) * ROWS_PER_WAVE) =
-                            make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                    cc.j = 0;
-                    cc.chunk++;
-                }
-            }
-            issue_next(L[p]);
         }
+        if (!finished) {
+            Loaded T;
+            expand(L[p], cc.K, cc.bits, cc.j, T);
+            if (cc.bits == 2)
+                compute<2>(cc.K, cc.j, T, xbuf, acc);
+            else if (cc.bits == 4)
+                compute<4>(cc.K, cc.j, T, xbuf, acc);
+            else if (cc.bits == 8)
+                compute<8>(cc.K, cc.j, T, xbuf, acc);
+            else
+                compute<16>(cc.K, cc.j, T, xbuf, acc);
+            if (++cc.j == cc.nslice) {
+                // the chunk's four rows: reduce over the wavefront, lane 63 leaves them in LDS
+                uint32_t h[ROWS_PER_WAVE];
+#pragma unroll
+                for (int r = 0; r < ROWS_PER_WAVE; r++) {
+                    h[r] = to_half_bits(wave_sum_lane63(acc[r]));
+                    acc[r] = 0.0f;
+                }
+                if (lane == 63)
+                    *reinterpret_cast<uint2 *>(res + (size_t)(cc.chunk - cc.wg_c0) * ROWS_PER_WAVE) =
+                        make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                cc.j = 0;
+                cc.chunk++;
+            }
+        }
+        issue_next(L[p]);
+    };
+    static_assert(P == 7, "the round is written out");
+    do {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 5>{});
+        step(std::integral_constant<int, 6>{});
     } while (!finished);
 }
 
 } // namespace
+
+#ifdef FQ_STAGED_PROBE
+extern "C" int fq_staged_probe_read(long long *out) // host: [256][160][8]
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_probe), sizeof(long long) * 256 * 160 * 8);
+}
+#endif
 
 size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks)
 {

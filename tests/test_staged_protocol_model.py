@@ -1,8 +1,8 @@
 """A thread-per-workgroup model of the stage-ordered kernel's barrier protocol (CPU only).
 
 The kernel (csrc/fq_staged.hip) separates two stages by a grid-wide barrier built from plain
-device-scope atomics: eight arrival counters that count up through the launch (workgroup b adds to
-counter b % 8; after stage s counter l must hold (s + 1) * |{b : b % 8 = l}|), an abort flag, a
+device-scope atomics: 32 arrival counters that count up through the launch (workgroup b adds to
+counter b % 32; after stage s counter l must hold (s + 1) * |{b : b % 32 = l}|), an abort flag, a
 sticky count of launches that gave up, and a count of finished workgroups whose last arrival puts
 counters and flag back to zero.  This model runs the same steps with one Python thread per
 workgroup and checks what the kernel relies on:
@@ -16,7 +16,7 @@ import time
 
 import pytest
 
-N_COUNTERS = 8
+N_COUNTERS = 32
 
 
 class SyncWords:
@@ -46,6 +46,12 @@ class SyncWords:
             setattr(self, name, v)
             return old
 
+    def snapshot(self):
+        """What one poll of the wavefront sees: every counter and the flag (the lanes' loads are
+        issued together; each word is read atomically, and the protocol does not rely on more)."""
+        with self.lock:
+            return list(self.counter), self.abort
+
     def load(self, name, idx=None):
         with self.lock:
             return getattr(self, name) if idx is None else getattr(self, name)[idx]
@@ -59,14 +65,14 @@ class SyncWords:
 
 
 def members(G, l):
-    return (G - l + 7) >> 3
+    return (G - l + N_COUNTERS - 1) // N_COUNTERS
 
 
 def wait_stage(sync, s, G, wait_limit):
     it = 0
     while True:
-        vals = [sync.load("counter", l) for l in range(N_COUNTERS)]
-        if sync.load("abort"):
+        vals, aborted = sync.snapshot()
+        if aborted:
             return False
         if all(vals[l] >= (s + 1) * members(G, l) for l in range(N_COUNTERS)):
             return True
@@ -75,7 +81,7 @@ def wait_stage(sync, s, G, wait_limit):
                 sync.add("gave_up")
             return False
         it += 1
-        time.sleep(0)
+        time.sleep(0.0001)
 
 
 def workgroup(b, G, n_stages, sync, wait_limit, written, violations, delay, start_gate=None):
@@ -123,7 +129,7 @@ def clean(sync):
     return sync.counter == [0] * N_COUNTERS and sync.abort == 0 and sync.done == 0
 
 
-@pytest.mark.parametrize("G,n_stages", [(1, 5), (7, 9), (8, 4), (13, 21), (24, 9)])
+@pytest.mark.parametrize("G,n_stages", [(1, 5), (7, 9), (32, 4), (45, 6)])
 def test_stages_are_ordered_and_words_end_clean(G, n_stages):
     sync = SyncWords()
     for _ in range(3):                             # replays on the same words, as a HIP graph would
@@ -135,10 +141,10 @@ def test_stages_are_ordered_and_words_end_clean(G, n_stages):
 
 
 def test_counter_targets_cover_every_workgroup():
-    for G in range(1, 70):
+    for G in range(1, 300):
         assert sum(members(G, l) for l in range(N_COUNTERS)) == G
         for l in range(N_COUNTERS):
-            assert members(G, l) == len([b for b in range(G) if b % 8 == l])
+            assert members(G, l) == len([b for b in range(G) if b % N_COUNTERS == l])
 
 
 def test_a_wait_that_runs_out_lets_everyone_leave_and_the_next_launch_is_clean():
