@@ -179,7 +179,8 @@ int fq_plan_destroy(fq_plan *plan);
  * independent of each other, and an entry may read (as x) what an entry of an EARLIER stage writes
  * (as y).  fq_plan_run runs all stages in order with ONE launch of a persistent kernel: a grid-wide
  * barrier stands between two stages, and the weights of the next stage are already being fetched
- * while it is crossed.  Results are bit-identical to the same stages run as separate plans.
+ * while it is crossed.  Results are bit-identical to the same stages run as separate stage-ordered
+ * plans (against fq_plan_create's kernel a row may be summed in a different order).
  *   stage      HOST, int32 [count]: stage[0] = 0, never decreasing, rising by at most 1;
  *              at most FQ_MAX_STAGE_ENTRIES entries per stage
  *   workspace  device, fq_plan_staged_workspace_bytes(count, number of stages) bytes, 256-byte
@@ -195,7 +196,7 @@ int fq_plan_destroy(fq_plan *plan);
  * launch starts clean.  fq_plan_status waits for `stream` and reports
  *   gave_up  launches of this plan that gave up so far (never reset)
  *   flags    bit 0: an entry's bit-width was not 2, 4, 8 or 16 or had no copy attached (its y was
- *            left untouched); bit 1: a workgroup's share of a stage exceeded 8192 rows (skipped)
+ *            left untouched); bit 1: a workgroup's share of a stage exceeded 4096 rows (skipped)
  * Either output may be NULL.  Runs of one plan must not overlap in time.
  */
 #define FQ_MAX_STAGE_ENTRIES 32

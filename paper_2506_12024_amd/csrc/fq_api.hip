@@ -457,7 +457,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
 static size_t staged_table_bytes(int count) { return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256; }
 static size_t staged_begin_bytes(int n_stages) { return ((size_t)(n_stages + 1) * 4 + 255) / 256 * 256; }
 constexpr size_t STAGED_SYNC_BYTES = 8192; // 32 counters on lines of their own, then the status words
-constexpr int STAGED_RES_CHUNKS = 2048; // 4-row chunks of one stage a workgroup can hold results for
+constexpr int STAGED_RES_CHUNKS = 1024; // 4-row chunks of one stage a workgroup can hold results for
 constexpr long long STAGED_WAIT_LIMIT = 1LL << 21; // about a second of polling
 
 size_t fq_plan_staged_workspace_bytes(int count, int n_stages)

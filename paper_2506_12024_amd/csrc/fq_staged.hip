@@ -52,6 +52,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "../../include/flexq.h"
 #include "fq_internal.h"
@@ -59,9 +60,13 @@
 
 namespace {
 
-constexpr int CW = 7;                  // compute wavefronts per workgroup
+#ifndef FQ_CW
+#define FQ_CW 8
+#define FQ_P 4
+#endif
+constexpr int CW = FQ_CW;                  // compute wavefronts per workgroup
 constexpr int THREADS = (CW + 1) * 64; // + the service wavefront: two wavefronts per SIMD, 256 registers each
-constexpr int P = 7;                   // items in flight per compute wavefront (register sets): 8 loads each,
+constexpr int P = FQ_P;                   // items in flight per compute wavefront (register sets): 8 loads each,
                                        // 56 of the 63 loads a wavefront can have outstanding
 constexpr int XU = 3;                  // 16-byte blocks of x a thread fetches before it places them
 
@@ -78,6 +83,7 @@ struct Share {
     int pad;
 };
 static_assert(sizeof(Share) == 64, "Share is read from LDS as four 16-byte pieces");
+static_assert(CW <= 15, "one word of the flags line per compute wavefront");
 
 // Relative cost of one row of one quantization group at each width (the one-launch kernel's table).
 __device__ __forceinline__ long long group_cost(const FqLinearDesc &d, int bits)
@@ -101,6 +107,13 @@ __device__ __forceinline__ T *uni_ptr(T *p)
     const uint64_t v = (uint64_t)p;
     const uint32_t lo = (uint32_t)uni((int)(uint32_t)v), hi = (uint32_t)uni((int)(uint32_t)(v >> 32));
     return (T *)(((uint64_t)hi << 32) | lo);
+}
+
+// f(0), f(1), ... with the index a compile-time constant.
+template <class F, int... I>
+__device__ __forceinline__ void for_each_index(F &f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
 }
 
 // Workgroup barrier that leaves vector memory loads in flight: LDS traffic of this wavefront done,
@@ -177,17 +190,21 @@ __device__ __forceinline__ void expand(const Item &I, int K, int bits, int j, Lo
     }
 }
 
-// One walker over a compute wavefront's items: stage by stage, inside a stage the wavefront's
-// chunks in order, inside a chunk the slices in order.  Uniform over the wavefront.
+// One walker over a compute wavefront's items: stage by stage; inside a stage the workgroup's
+// items -- its chunks in order, inside a chunk the slices in order -- are cut into CW equal runs,
+// one per compute wavefront, so a chunk's slices may be shared by neighbouring wavefronts (a stage
+// often gives a workgroup fewer chunks than it has wavefronts).  Uniform over the wavefront.
 struct Cursor {
     const uint8_t *codes;
     const float *scales;
     const uint8_t *zeros;
     int N, K, bits;
     int s;              // stage
-    int chunk, end;     // this wavefront's chunks [chunk, end) still to do in stage s
-    int j, nslice;
-    int wg_c0;          // first chunk of the workgroup's share (results are indexed from it)
+    int item, end;      // this wavefront's items [item, end) still to do in stage s, counted from the share's first
+    int chunk, j;       // chunk (absolute) and slice of `item`
+    int nslice;
+    int first;          // chunk (relative to the share's first) this wavefront's run begins in
+    int wg_c0;          // the share's first chunk
 };
 
 __device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int s, int wave)
@@ -201,15 +218,15 @@ __device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int 
     c.N = uni(sh->N);
     c.K = uni(sh->K);
     const int c0 = uni(sh->c0), c1 = uni(sh->c1);
-    const int n = c.bits ? c1 - c0 : 0;
-    c.wg_c0 = c0;
-    c.chunk = c0 + (int)((long long)n * wave / CW);
-    c.end = c0 + (int)((long long)n * (wave + 1) / CW);
-    c.j = 0;
     c.nslice = c.bits ? (c.K + slice_span(c.bits) - 1) / slice_span(c.bits) : 1;
+    const int n = c.bits ? (c1 - c0) * c.nslice : 0;
+    c.wg_c0 = c0;
+    c.item = n * wave / CW; // (at most 1024 chunks x 64 slices x CW: no overflow)
+    c.end = n * (wave + 1) / CW;
+    c.first = c.item / c.nslice;
+    c.chunk = c0 + c.first;
+    c.j = c.item - c.first * c.nslice;
 }
-
-// ---- service wavefront ------------------------------------------------------------------------
 
 // 16 bytes of x, read at agent scope (two 64-bit relaxed atomic loads: they are served where the
 // other XCDs' write-through stores have arrived, whatever this XCD's caches still hold of an
@@ -291,20 +308,31 @@ __device__ __forceinline__ void stage_share_x(const Share *sh, uint4 *xbuf)
         stage_x_all<16>(x, K, xbuf);
 }
 
-// Rows finished in this stage, LDS -> y, with stores that write through to memory (visible to the
-// other XCDs' caches once acknowledged).
-__device__ __forceinline__ void store_share_y(const Share *sh, const uint16_t *res)
+// Rows finished in this stage, LDS -> y.  A row's value is the sum, in wavefront order, of the
+// partial sums of the wavefronts that shared its chunk (mostly one).  The stores write through to
+// memory (visible to the other XCDs' caches once acknowledged).
+__device__ __forceinline__ void store_share_y(const Share *sh, const float *part, int PK, const int *firsts)
 {
     const int lane = threadIdx.x & 63;
-    const int bits = uni(sh->bits), c0 = uni(sh->c0), c1 = uni(sh->c1), N = uni(sh->N);
+    const int bits = uni(sh->bits), c0 = uni(sh->c0), c1 = uni(sh->c1), N = uni(sh->N), K = uni(sh->K);
     if (bits == 0 || c1 <= c0)
         return;
     uint16_t *y = uni_ptr(sh->y);
+    const int nslice = (K + slice_span(bits) - 1) / slice_span(bits);
+    const int n = (c1 - c0) * nslice; // items of the share (at most 1024 chunks x 64 slices)
     const int row0 = c0 * ROWS_PER_WAVE, rows = min(c1 * ROWS_PER_WAVE, N) - row0;
     for (int i = lane; i < rows; i += 64) {
-        const uint32_t v = res[i];
+        const int c = i / ROWS_PER_WAVE, r = i % ROWS_PER_WAVE; // chunk relative to the share's first
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < CW; w++) {
+            const int i0 = n * w / CW, i1 = n * (w + 1) / CW; // wavefront w's run of items
+            if (i1 > i0 && i0 < (c + 1) * nslice && i1 > c * nslice)
+                v += part[(w * PK + (c - firsts[w])) * ROWS_PER_WAVE + r]; // firsts[w] = i0 / nslice, left by wavefront w
+        }
+        const uint32_t h = to_half_bits(v);
         uint16_t *p = y + row0 + i;
-        asm volatile("global_store_short %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+        asm volatile("global_store_short %0, %1, off sc0 sc1" ::"v"(p), "v"(h) : "memory");
     }
 }
 
@@ -373,10 +401,11 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                                                                 int res_chunks)
 {
     extern __shared__ uint4 lds[];
-    Share *shares = reinterpret_cast<Share *>(lds);                       // [n_stages]
-    uint16_t *res = reinterpret_cast<uint16_t *>(lds + 4 * n_stages);     // [res_chunks][4] halves
-    int *flags = reinterpret_cast<int *>(lds + 4 * n_stages + res_chunks / 2); // [0]: abort
-    uint4 *xbuf = lds + 4 * n_stages + res_chunks / 2 + 4;
+    const int PK = res_chunks / CW + 2; // chunks one wavefront can have a hand in per stage
+    Share *shares = reinterpret_cast<Share *>(lds);                  // [n_stages]
+    float *part = reinterpret_cast<float *>(lds + 4 * n_stages);     // [CW][PK][4] partial rows
+    int *flags = reinterpret_cast<int *>(lds + 4 * n_stages + CW * PK); // [0]: abort; [1 + w]: first chunk of wavefront w's run
+    uint4 *xbuf = lds + 4 * n_stages + CW * PK + 4;
     const int wave = uni(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int G = gridDim.x, b = blockIdx.x;
 
@@ -441,14 +470,18 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
             PROBE(0);
             wg_barrier(); // the compute wavefronts' rows of stage s are in LDS
             PROBE(1);
-            store_share_y(&shares[s], res);
+            store_share_y(&shares[s], part, PK, flags + 1);
             if (s + 1 == n_stages)
                 break;
             __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): the stores are acknowledged
             PROBE(2);
             if (lane == 0)
                 __hip_atomic_fetch_add(&sync[32 * (b % NC)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef FQ_NO_WAIT
+            const bool aborted = false;
+#else
             const bool aborted = !wait_stage(sync, s, G, wait_limit);
+#endif
             PROBE(3);
             if (aborted && lane == 0)
                 flags[0] = 1;
@@ -479,6 +512,8 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
     Cursor ic, cc;
     enter_stage(ic, shares, 0, wave);
     enter_stage(cc, shares, 0, wave);
+    if (lane == 0)
+        flags[1 + wave] = cc.first;
     bool more = true; // the issue cursor still has items
     Item L[P];
     // Next item of the issue cursor into dst.  Past the last item: the same eight load instructions
@@ -486,7 +521,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
     // path, and only with the same count on every path does it let a set's loads stay in flight
     // until the set is used.
     auto issue_next = [&](Item &dst) __attribute__((always_inline)) {
-        while (more && ic.chunk >= ic.end) {
+        while (more && ic.item >= ic.end) {
             if (ic.s + 1 >= n_stages)
                 more = false;
             else
@@ -499,9 +534,12 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
         const uint8_t *zeros = valid ? ic.zeros : (const uint8_t *)table;
         issue_any(codes, scales, zeros, valid ? ic.N : 1, valid ? ic.K : 128, valid ? ic.bits : 16,
                   valid ? ic.chunk * ROWS_PER_WAVE : 0, valid ? ic.j : 0, dst);
-        if (valid && ++ic.j == ic.nslice) {
-            ic.j = 0;
-            ic.chunk++;
+        if (valid) {
+            ic.item++;
+            if (++ic.j == ic.nslice) {
+                ic.j = 0;
+                ic.chunk++;
+            }
         }
     };
 #pragma unroll
@@ -518,7 +556,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
     auto step = [&](auto pc) __attribute__((always_inline)) {
         constexpr int p = decltype(pc)::value;
         // bring the compute cursor to its next item, crossing stage boundaries on the way
-        while (!finished && cc.chunk >= cc.end) {
+        while (!finished && cc.item >= cc.end) {
             wg_barrier(); // this wavefront's rows of stage cc.s are in LDS
             if (cc.s + 1 >= n_stages) {
                 finished = true;
@@ -533,12 +571,18 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                     stage_share_x(&shares[cc.s + 1], xbuf);
                     wg_barrier(); // x of the next stage is in LDS
                     enter_stage(cc, shares, cc.s + 1, wave);
+                    if (lane == 0)
+                        flags[1 + wave] = cc.first;
                 }
             }
         }
         if (!finished) {
             Loaded T;
             expand(L[p], cc.K, cc.bits, cc.j, T);
+#ifdef FQ_NO_COMPUTE
+            acc[0] += T.s[0] + (float)T.w[0].x + (float)T.w[1].y + (float)T.w[2].z + (float)T.w[3].w + (float)T.z[3];
+            if (false)
+#endif
             if (cc.bits == 2)
                 compute<2>(cc.K, cc.j, T, xbuf, acc);
             else if (cc.bits == 4)
@@ -547,32 +591,30 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                 compute<8>(cc.K, cc.j, T, xbuf, acc);
             else
                 compute<16>(cc.K, cc.j, T, xbuf, acc);
-            if (++cc.j == cc.nslice) {
-                // the chunk's four rows: reduce over the wavefront, lane 63 leaves them in LDS
-                uint32_t h[ROWS_PER_WAVE];
+            cc.item++;
+            cc.j++;
+            if (cc.j == cc.nslice || cc.item == cc.end) {
+                // this wavefront's part of the chunk's four rows: reduce over the lanes, lane 63
+                // leaves the sums in LDS
+                float v[ROWS_PER_WAVE];
 #pragma unroll
                 for (int r = 0; r < ROWS_PER_WAVE; r++) {
-                    h[r] = to_half_bits(wave_sum_lane63(acc[r]));
+                    v[r] = wave_sum_lane63(acc[r]);
                     acc[r] = 0.0f;
                 }
                 if (lane == 63)
-                    *reinterpret_cast<uint2 *>(res + (size_t)(cc.chunk - cc.wg_c0) * ROWS_PER_WAVE) =
-                        make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                cc.j = 0;
-                cc.chunk++;
+                    *reinterpret_cast<float4 *>(part + ((size_t)wave * PK + (cc.chunk - cc.wg_c0 - cc.first)) * ROWS_PER_WAVE) =
+                        make_float4(v[0], v[1], v[2], v[3]);
+                if (cc.j == cc.nslice) {
+                    cc.j = 0;
+                    cc.chunk++;
+                }
             }
         }
         issue_next(L[p]);
     };
-    static_assert(P == 7, "the round is written out");
     do {
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
-        step(std::integral_constant<int, 4>{});
-        step(std::integral_constant<int, 5>{});
-        step(std::integral_constant<int, 6>{});
+        for_each_index(step, std::make_integer_sequence<int, P>{});
     } while (!finished);
 }
 
@@ -589,7 +631,7 @@ size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks)
 {
     const size_t kp4 = ((size_t)max_K + 2047) / 2048 * 2048, kp2 = ((size_t)max_K + 4095) / 4096 * 4096;
     const size_t b4 = kp4 * 2 + kp4 / 32 * 8, b2 = kp2 * 2 + kp2 / 64 * 8;
-    return (size_t)n_stages * sizeof(Share) + (size_t)res_chunks * 8 + 64 + (b4 > b2 ? b4 : b2) + 64;
+    return (size_t)n_stages * sizeof(Share) + (size_t)CW * (res_chunks / CW + 2) * 16 + 64 + (b4 > b2 ? b4 : b2) + 64;
 }
 
 // Workgroups of the staged kernel: one per compute unit, and never more than fit at once (they
