@@ -37,9 +37,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
 MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993151.0 / 4978290.0,
+                          ("llama7b", 1, (4, 8), "dependent"): 5020670.0 / 4978290.0,
                           ("llama7b", 16, (4, 8, 16)): 8.052 / 7.857}
 # where those ratios come from (a constant carried from a profile, not counters read in this run)
 TRAFFIC_SOURCE = {("llama7b", 1, (4, 8)): "profiles/decode_m1_plan_llama7b_hbm_traffic.md (rocprofv3 --pmc, scaled by a 1 GiB copy)",
+                  ("llama7b", 1, (4, 8), "dependent"): "profiles/decode_staged_plan_llama7b_hbm_traffic.md (rocprofv3 --pmc, scaled by a 1 GiB read)",
                   ("llama7b", 16, (4, 8, 16)): "profiles/decode_stream_plan_llama7b_batch16_kernel_trace.md (rocprofv3 --pmc)"}
 N_PATTERNS = 128        # decode steps with distinct per-layer bit patterns
 VOCAB = 32000
@@ -770,9 +772,9 @@ def main():
                 "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_ms": ms, "algorithmic_bytes_per_launch": alg_bytes}
 
-    def measured_traffic():
-        if args.layers is None and traffic_key in MEASURED_TRAFFIC_RATIO:
-            return alg_bytes * MEASURED_TRAFFIC_RATIO[traffic_key], TRAFFIC_SOURCE[traffic_key]
+    def measured_traffic(key=traffic_key):
+        if args.layers is None and key in MEASURED_TRAFFIC_RATIO:
+            return alg_bytes * MEASURED_TRAFFIC_RATIO[key], TRAFFIC_SOURCE[key]
         return None, None
 
     out = {
@@ -797,7 +799,7 @@ def main():
         "stream_read_GBps": stream_gbps,
     }
     if order == "dependent":
-        out["roofline"] = roofline(kernel_of["dependent"], lin_ms)
+        out["roofline"] = roofline(kernel_of["dependent"], lin_ms, *measured_traffic(traffic_key + ("dependent",)))
         gave_up, flags = stack.staged_plan.status()
         out["staged_plan_status"] = {"gave_up": gave_up, "flags": flags}
         # beside it: the same linears as one plan of independent entries (the weight stream alone)
