@@ -40,14 +40,18 @@
 // so that the next launch, and a replayed HIP graph, find them clean.  All workgroups must be
 // resident together (the host launches at most as many as fit).
 //
-// What a stage costs (7B-shaped stack, bits from {4, 8}, time stamps of every workgroup): the
-// compute wavefronts' part 8.9 us (the arithmetic and the requests of 5 items per wavefront: with
-// the weights prefetched this part is bound by the vector ALUs, not by memory), stores and their
-// acknowledgement 0.5, the wait for the other workgroups 3.7 (of which 1.1 is the median spread of
-// the arrivals, 2.3 the way of the last arrival to the pollers), x 0.9.
+// What a stage costs (7B-shaped stack, bits from {4, 8}, time stamps of every workgroup, 12.4 us
+// per stage in all): the compute wavefronts' part 6.1 us; the workgroup's rows summed, stored and
+// acknowledged 1.5; the wait for the other workgroups 3.8 (of which 1.0 is the median spread of the
+// arrivals, 2.0 the way of the last arrival to the pollers); x 0.8.  In the compute part a wavefront
+// hardly ever waits for an item's data (35 ns per item); it spends 1.1 us per item computing and 0.7
+// requesting the next -- and with the arithmetic taken out, 0.2 and 1.8: the requests are accepted
+// at the rate memory serves them, so the compute part is the stage's bytes at memory speed, and it
+// does not overlap with the 6 us of the boundary, during which nothing is requested.
 //
-// Arithmetic: the item code of the one-launch kernel (fq_gemv.h), rows handled whole by one
-// wavefront in the same slice order, hence bit-identical results.
+// Arithmetic: the item code of the one-launch kernel (fq_gemv.h).  A row whose slices are shared
+// by two wavefronts is the sum, in wavefront order, of their partial sums: deterministic, the same
+// whether the stage runs alone or after others, but not the one-launch kernel's order of additions.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -60,14 +64,12 @@
 
 namespace {
 
-#ifndef FQ_CW
-#define FQ_CW 8
-#define FQ_P 4
-#endif
-constexpr int CW = FQ_CW;                  // compute wavefronts per workgroup
-constexpr int THREADS = (CW + 1) * 64; // + the service wavefront: two wavefronts per SIMD, 256 registers each
-constexpr int P = FQ_P;                   // items in flight per compute wavefront (register sets): 8 loads each,
-                                       // 56 of the 63 loads a wavefront can have outstanding
+constexpr int CW = 8;                  // compute wavefronts per workgroup
+constexpr int THREADS = (CW + 1) * 64; // + the service wavefront: up to three wavefronts per SIMD, 168 registers each
+constexpr int P = 4;                   // items in flight per compute wavefront (register sets), 8 loads each.
+                                       // Measured on the 7B-shaped step (ms, bits from {4,8} / all 4 / all 8):
+                                       // CW 7, P 7: 1.86 / 1.57 / 2.05;  CW 8, P 4: 1.77 / 1.50 / 1.97;
+                                       // CW 7, P 5: 1.84 / 1.54 / 2.03;  CW 11, P 3: 1.79 / 1.52 / 2.05
 constexpr int XU = 3;                  // 16-byte blocks of x a thread fetches before it places them
 
 // What a workgroup does in one stage.  64 bytes, kept in LDS for every stage of the plan.
@@ -138,33 +140,111 @@ struct Item {
     uint8_t z[2]; // kept as bytes: widened where used, so that nothing touches a register while its load is in flight
 };
 
-// The loads of item (rows row0 .. row0 + 3, slice j) with the bit-width a run-time value: the same
-// eight load instructions on every path, so that the count of loads in flight is the same whatever
-// the widths of the items are.  For 16 bits scales and zeros alias the weights (loaded, never used).
-__device__ __forceinline__ void issue_any(const uint8_t *codes, const float *scales, const uint8_t *zeros, int N,
-                                          int K, int bits, int row0, int j, Item &L)
+// One walker over a compute wavefront's items: stage by stage; inside a stage the workgroup's
+// items -- its chunks in order, inside a chunk the slices in order -- are cut into CW equal runs,
+// one per compute wavefront, so a chunk's slices may be shared by neighbouring wavefronts (a stage
+// often gives a workgroup fewer chunks than it has wavefronts).  Uniform over the wavefront.  What
+// an item's addresses need is kept per stage and per chunk, so that an item costs a handful of
+// instructions: the wavefronts issue a few hundred instructions per 4 KiB of weights, and at five
+// items per wavefront and stage that, not memory, is what a stage's compute part is made of.
+struct Cursor {
+    // per stage
+    const uint8_t *codes;
+    const float *scales;
+    const uint8_t *zeros;
+    int N, K, bits;
+    int s;              // stage
+    int item, end;      // this wavefront's items [item, end) still to do in stage s, counted from the share's first
+    int nslice;
+    int first;          // chunk (relative to the share's first) this wavefront's run begins in
+    int wg_c0;          // the share's first chunk
+    int csh, rsh, gsh;  // log2(codes per lane and slice); bytes = (2 k) >> rsh; log2(groups per slice)
+    uint32_t row_bytes, G, kmax;
+    // per chunk
+    int chunk, j;       // chunk (absolute) and slice of `item`
+    const uint8_t *crow; // codes of the chunk's first row
+    const float *srow;
+    const uint8_t *zrow;
+    int last;           // rows of the chunk that exist, minus one (3 but for the matrix's last chunk)
+};
+
+__device__ __forceinline__ void set_chunk(Cursor &c)
+{
+    const int row0 = c.chunk * ROWS_PER_WAVE;
+    c.last = min(ROWS_PER_WAVE - 1, c.N - 1 - row0);
+    c.crow = c.codes + (size_t)row0 * c.row_bytes;
+    c.srow = c.scales + (size_t)row0 * c.G;
+    c.zrow = c.zeros + (size_t)row0 * c.G;
+}
+
+// A stage's constants for an entry of `bits` bits with rows of K inputs.
+__device__ __forceinline__ void set_width(Cursor &c, int bits, int K)
+{
+    c.bits = bits;
+    c.K = K;
+    c.csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3;
+    c.rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0;
+    c.gsh = c.csh - 1; // 32 / 16 / 8 groups per slice (fp16: unused)
+    c.row_bytes = (2u * (uint32_t)K) >> c.rsh;
+    c.G = (uint32_t)K >> 7;
+    c.kmax = (uint32_t)K - (1u << c.csh);
+}
+
+__device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int s, int wave)
+{
+    const Share *sh = &shares[s];
+    c.s = s;
+    const int bits = uni(sh->bits);
+    c.codes = uni_ptr(sh->codes);
+    c.scales = uni_ptr(sh->scales);
+    c.zeros = uni_ptr(sh->zeros);
+    c.N = uni(sh->N);
+    set_width(c, bits, uni(sh->K));
+    const int c0 = uni(sh->c0), c1 = uni(sh->c1);
+    c.nslice = bits ? (c.K + slice_span(bits) - 1) / slice_span(bits) : 1;
+    const int n = bits ? (c1 - c0) * c.nslice : 0;
+    c.wg_c0 = c0;
+    c.item = n * wave / CW; // (at most 1024 chunks x 64 slices x CW: no overflow)
+    c.end = n * (wave + 1) / CW;
+    c.first = c.item / c.nslice;
+    c.chunk = c0 + c.first;
+    c.j = c.item - c.first * c.nslice;
+    if (c.item < c.end)
+        set_chunk(c);
+}
+
+// The cursor's item is done (or requested): on to the next one of the run.
+__device__ __forceinline__ void advance(Cursor &c)
+{
+    c.item++;
+    if (++c.j == c.nslice) {
+        c.j = 0;
+        c.chunk++;
+        if (c.item < c.end)
+            set_chunk(c);
+    }
+}
+
+// The loads of the cursor's item: the same eight load instructions whatever the bit-width (a
+// run-time value), so that the count of loads in flight is the same on every path.  For 16 bits
+// scales and zeros alias the weights (loaded, never used).
+__device__ __forceinline__ void issue_item(const Cursor &c, Item &L)
 {
     const int lane = threadIdx.x & 63;
-    const uint32_t Ku = (uint32_t)K, G = Ku >> 7;
-    const int csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3; // log2(codes per lane and slice)
-    const int rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0; // bytes = (2 k) >> rsh
-    const uint32_t k0 = min((uint32_t)(j * 64 + lane) << csh, Ku - (1u << csh));
-    const uint32_t row_bytes = (2 * Ku) >> rsh, byte0 = (2 * k0) >> rsh;
+    const uint32_t k0 = min((uint32_t)(c.j * 64 + lane) << c.csh, c.kmax);
+    const uint32_t byte0 = (2 * k0) >> c.rsh;
 #pragma unroll
-    for (int r = 0; r < ROWS_PER_WAVE; r++) {
-        const uint32_t row = (uint32_t)min(row0 + r, N - 1);
-        L.w[r] = load16_stream(codes + (size_t)row * row_bytes + byte0);
-    }
+    for (int r = 0; r < ROWS_PER_WAVE; r++) // a row past the matrix's last repeats the last (discarded)
+        L.w[r] = load16_stream(c.crow + (byte0 + (uint32_t)min(r, c.last) * c.row_bytes));
     // scales and zero points: lane l -> (row l >> gsh, group l & (GS - 1)) of the slice; at 2 bits the
     // second pair of loads takes rows 2 and 3, at the other widths it repeats the first
-    const int gsh = csh - 1; // log2(GS): 5, 4, 3 (2 for fp16: unused)
-    const uint32_t g = min((uint32_t)(j << gsh) + (uint32_t)(lane & ((1 << gsh) - 1)), G - 1);
-    const int rr = (lane >> gsh) & 3;
+    const uint32_t g = min(((uint32_t)c.j << c.gsh) + (uint32_t)(lane & ((1 << c.gsh) - 1)), c.G - 1);
+    const int rr = (lane >> c.gsh) & 3;
 #pragma unroll
     for (int h = 0; h < 2; h++) {
-        const uint32_t row = (uint32_t)min(row0 + (bits == 2 ? rr + 2 * h : rr), N - 1);
-        L.s[h] = as_global<float>(scales + (size_t)row * G)[g];
-        L.z[h] = as_global<uint8_t>(zeros + (size_t)row * G)[g];
+        const uint32_t idx = (uint32_t)min(c.bits == 2 ? rr + 2 * h : rr, c.last) * c.G + g;
+        L.s[h] = as_global<float>(c.srow)[idx];
+        L.z[h] = as_global<uint8_t>(c.zrow)[idx];
     }
     // the loads stay here: the compiler would otherwise sink some of them towards their first use,
     // steps later, where their latency is no longer hidden
@@ -173,59 +253,20 @@ __device__ __forceinline__ void issue_any(const uint8_t *codes, const float *sca
 
 // The item as the shared arithmetic takes it: every lane gets the scale and zero point of its own
 // group for each of the four rows from the lane that fetched them.
-__device__ __forceinline__ void expand(const Item &I, int K, int bits, int j, Loaded &L)
+__device__ __forceinline__ void expand(const Item &I, const Cursor &c, Loaded &L)
 {
     const int lane = threadIdx.x & 63;
-    const int csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3, gsh = csh - 1;
-    const uint32_t Ku = (uint32_t)K;
-    const uint32_t k0 = min((uint32_t)(j * 64 + lane) << csh, Ku - (1u << csh));
-    const int gi = (int)(k0 >> 7) - (j << gsh); // my group's place among the slice's groups
+    const uint32_t k0 = min((uint32_t)(c.j * 64 + lane) << c.csh, c.kmax);
+    const int gi = (int)(k0 >> 7) - (c.j << c.gsh); // my group's place among the slice's groups
+    const bool two = c.bits == 2;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
         L.w[r] = I.w[r];
-        const int h = bits == 2 ? r >> 1 : 0;
-        const int src = ((bits == 2 ? r & 1 : r) << gsh) + gi;
-        L.s[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, h ? I.s[1] : I.s[0])));
-        L.z[r] = (uint8_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)(h ? I.z[1] : I.z[0]));
+        const int src = (((two ? r & 1 : r) << c.gsh) + gi) << 2;
+        const bool h = two && r >= 2;
+        L.s[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, h ? I.s[1] : I.s[0])));
+        L.z[r] = (uint8_t)__builtin_amdgcn_ds_bpermute(src, (int)(h ? I.z[1] : I.z[0]));
     }
-}
-
-// One walker over a compute wavefront's items: stage by stage; inside a stage the workgroup's
-// items -- its chunks in order, inside a chunk the slices in order -- are cut into CW equal runs,
-// one per compute wavefront, so a chunk's slices may be shared by neighbouring wavefronts (a stage
-// often gives a workgroup fewer chunks than it has wavefronts).  Uniform over the wavefront.
-struct Cursor {
-    const uint8_t *codes;
-    const float *scales;
-    const uint8_t *zeros;
-    int N, K, bits;
-    int s;              // stage
-    int item, end;      // this wavefront's items [item, end) still to do in stage s, counted from the share's first
-    int chunk, j;       // chunk (absolute) and slice of `item`
-    int nslice;
-    int first;          // chunk (relative to the share's first) this wavefront's run begins in
-    int wg_c0;          // the share's first chunk
-};
-
-__device__ __forceinline__ void enter_stage(Cursor &c, const Share *shares, int s, int wave)
-{
-    const Share *sh = &shares[s];
-    c.s = s;
-    c.bits = uni(sh->bits);
-    c.codes = uni_ptr(sh->codes);
-    c.scales = uni_ptr(sh->scales);
-    c.zeros = uni_ptr(sh->zeros);
-    c.N = uni(sh->N);
-    c.K = uni(sh->K);
-    const int c0 = uni(sh->c0), c1 = uni(sh->c1);
-    c.nslice = c.bits ? (c.K + slice_span(c.bits) - 1) / slice_span(c.bits) : 1;
-    const int n = c.bits ? (c1 - c0) * c.nslice : 0;
-    c.wg_c0 = c0;
-    c.item = n * wave / CW; // (at most 1024 chunks x 64 slices x CW: no overflow)
-    c.end = n * (wave + 1) / CW;
-    c.first = c.item / c.nslice;
-    c.chunk = c0 + c.first;
-    c.j = c.item - c.first * c.nslice;
 }
 
 // 16 bytes of x, read at agent scope (two 64-bit relaxed atomic loads: they are served where the
@@ -383,16 +424,6 @@ __device__ __forceinline__ bool wait_stage(int *sync, int s, int G, long long wa
     }
 }
 
-#ifdef FQ_STAGED_PROBE
-__device__ long long g_probe[256][160][8];
-#define PROBE(slot)                                                                                           \
-    do {                                                                                                      \
-        if (lane == 0 && b < 256 && s < 160)                                                                  \
-            g_probe[b][s][slot] = (long long)wall_clock64();                                                  \
-    } while (0)
-#else
-#define PROBE(slot)
-#endif
 
 __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDesc *__restrict__ table,
                                                                 const int32_t *__restrict__ bits_dev,
@@ -467,33 +498,22 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
         // ---- service wavefront ------------------------------------------------------------
         wg_barrier(); // x of stage 0 is in LDS
         for (int s = 0; s < n_stages; s++) {
-            PROBE(0);
             wg_barrier(); // the compute wavefronts' rows of stage s are in LDS
-            PROBE(1);
             store_share_y(&shares[s], part, PK, flags + 1);
             if (s + 1 == n_stages)
                 break;
             __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): the stores are acknowledged
-            PROBE(2);
             if (lane == 0)
                 __hip_atomic_fetch_add(&sync[32 * (b % NC)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#ifdef FQ_NO_WAIT
-            const bool aborted = false;
-#else
             const bool aborted = !wait_stage(sync, s, G, wait_limit);
-#endif
-            PROBE(3);
             if (aborted && lane == 0)
                 flags[0] = 1;
             wg_barrier(); // every workgroup has arrived (or the abort flag is up)
             if (aborted)
                 break;
-            PROBE(4);
             stage_share_x(&shares[s + 1], xbuf); // with the compute wavefronts
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            PROBE(5);
             wg_barrier(); // x of stage s + 1 is in LDS
-            PROBE(6);
         }
         // last workgroup out puts the counters back
         if (lane == 0) {
@@ -516,31 +536,31 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
         flags[1 + wave] = cc.first;
     bool more = true; // the issue cursor still has items
     Item L[P];
-    // Next item of the issue cursor into dst.  Past the last item: the same eight load instructions
-    // on the head of the table (cached, discarded) -- the compiler counts the loads in flight per
-    // path, and only with the same count on every path does it let a set's loads stay in flight
-    // until the set is used.
+    // Next item of the issue cursor into dst.  Past its last item the cursor is parked on the head of
+    // the table (cached, the result discarded): the same eight load instructions -- the compiler
+    // counts the loads in flight per path, and only with the same count on every path does it let
+    // a set's loads stay in flight until the set is used.
+    auto park = [&]() __attribute__((always_inline)) {
+        more = false;
+        ic.codes = (const uint8_t *)table;
+        ic.scales = (const float *)table;
+        ic.zeros = (const uint8_t *)table;
+        ic.N = 1;
+        set_width(ic, 16, 128);
+        ic.chunk = 0;
+        ic.j = 0;
+        set_chunk(ic);
+    };
     auto issue_next = [&](Item &dst) __attribute__((always_inline)) {
         while (more && ic.item >= ic.end) {
             if (ic.s + 1 >= n_stages)
-                more = false;
+                park();
             else
                 enter_stage(ic, shares, ic.s + 1, wave);
         }
-        const bool valid = more && ic.bits != 0;
-        // a wavefront without items (or past its last one) re-reads the head of the table: valid memory
-        const uint8_t *codes = valid ? ic.codes : (const uint8_t *)table;
-        const float *scales = valid ? ic.scales : (const float *)table;
-        const uint8_t *zeros = valid ? ic.zeros : (const uint8_t *)table;
-        issue_any(codes, scales, zeros, valid ? ic.N : 1, valid ? ic.K : 128, valid ? ic.bits : 16,
-                  valid ? ic.chunk * ROWS_PER_WAVE : 0, valid ? ic.j : 0, dst);
-        if (valid) {
-            ic.item++;
-            if (++ic.j == ic.nslice) {
-                ic.j = 0;
-                ic.chunk++;
-            }
-        }
+        issue_item(ic, dst);
+        if (more)
+            advance(ic);
     };
 #pragma unroll
     for (int p = 0; p < P; p++)
@@ -578,11 +598,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
         }
         if (!finished) {
             Loaded T;
-            expand(L[p], cc.K, cc.bits, cc.j, T);
-#ifdef FQ_NO_COMPUTE
-            acc[0] += T.s[0] + (float)T.w[0].x + (float)T.w[1].y + (float)T.w[2].z + (float)T.w[3].w + (float)T.z[3];
-            if (false)
-#endif
+            expand(L[p], cc, T);
             if (cc.bits == 2)
                 compute<2>(cc.K, cc.j, T, xbuf, acc);
             else if (cc.bits == 4)
@@ -591,9 +607,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                 compute<8>(cc.K, cc.j, T, xbuf, acc);
             else
                 compute<16>(cc.K, cc.j, T, xbuf, acc);
-            cc.item++;
-            cc.j++;
-            if (cc.j == cc.nslice || cc.item == cc.end) {
+            if (cc.j + 1 == cc.nslice || cc.item + 1 == cc.end) {
                 // this wavefront's part of the chunk's four rows: reduce over the lanes, lane 63
                 // leaves the sums in LDS
                 float v[ROWS_PER_WAVE];
@@ -605,11 +619,8 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                 if (lane == 63)
                     *reinterpret_cast<float4 *>(part + ((size_t)wave * PK + (cc.chunk - cc.wg_c0 - cc.first)) * ROWS_PER_WAVE) =
                         make_float4(v[0], v[1], v[2], v[3]);
-                if (cc.j == cc.nslice) {
-                    cc.j = 0;
-                    cc.chunk++;
-                }
             }
+            advance(cc);
         }
         issue_next(L[p]);
     };
@@ -620,12 +631,6 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
 
 } // namespace
 
-#ifdef FQ_STAGED_PROBE
-extern "C" int fq_staged_probe_read(long long *out) // host: [256][160][8]
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_probe), sizeof(long long) * 256 * 160 * 8);
-}
-#endif
 
 size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks)
 {
