@@ -17,9 +17,14 @@
  * Conventions.
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, who keeps it
  *     alive until the work enqueued on `stream` has finished.  The library never
- *     allocates, frees or copies tensor memory and never synchronises.
+ *     allocates, frees or copies tensor memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Work is enqueued in order on it; a call returns without waiting.
+ *     Work is enqueued in order on it; a call returns without waiting.  Four calls
+ *     do wait for `stream`, and say so where they are declared: fq_plan_create and
+ *     fq_plan_create_staged (they copy their small tables from host memory and
+ *     wait for that copy, so they cannot be called under stream capture: create
+ *     plans before capturing), fq_plan_status and fq_sched_peek (they read words
+ *     back to the host).
  *   - Every function returns FQ_OK (0) or a negative fq_status.  Arguments are
  *     validated before anything is launched; on an error nothing was enqueued.
  *     fq_last_error() returns a message for the calling thread's last failure.
@@ -66,11 +71,13 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 #define FQ_MAX_DECODE_K 32768 /* longest row they take (a row of x stays in LDS at M = 1) */
 #define FQ_MAX_LM_HEAD_M 4 /* rows of x served by fq_lm_head_entropy */
 
-/* Message describing the calling thread's most recent error ("" if none). */
+/* Message describing the calling thread's most recent error ("" if none).  (Interface only: the
+ * paper defines no error model.) */
 const char *fq_last_error(void);
 
 /*
- * Bytes of the three packed buffers for an N x K weight at `bits` (2, 4 or 8).
+ * Bytes of the three packed buffers for an N x K weight at `bits` (2, 4 or 8): what Eq. (2) of
+ * Sec. 2.2 produces per weight (an n-bit code) and per group (s, z), in the layout above.
  * Any of the three outputs may be NULL.  Host-only; launches nothing.
  */
 int fq_packed_sizes(int N, int K, int bits, int group,
@@ -118,11 +125,13 @@ int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int 
 
 /*
  * A layer handle: a small host object naming the resident copies of one
- * linear's weight.  fq_layer_attach records (does not copy) the buffers for one
+ * linear's weight -- Sec. 4.3: every linear is kept in several formats at once, all resident in
+ * HBM, and a switch of precision selects among them.  fq_layer_attach records (does not copy) the buffers for one
  * bit-width; any subset of {2, 4, 8, 16} may be attached, each at most once per
  * value (attaching again replaces the pointers).  For bits = 16 pass the fp16
  * weights as `codes` and NULL scales/zeros.  Buffers must be 16-byte aligned.
- * Launches nothing.
+ * Launches nothing and takes no stream: the kernels stream the packed layout as it is, so there is
+ * nothing to re-tile when a copy is attached.
  */
 int fq_layer_create(fq_layer **out, int N, int K, int group);
 int fq_layer_attach(fq_layer *layer, int bits, const void *codes,
@@ -154,7 +163,8 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  * same plan (and a HIP graph holding it) serves every pattern.
  *   workspace  device memory of fq_plan_workspace_bytes(count) bytes, 256-byte
  *              aligned, owned by the caller, must outlive the plan; the
- *              descriptor table is copied into it on `stream` by fq_plan_create.  After the
+ *              descriptor table is copied into it on `stream` by fq_plan_create, which waits for
+ *              that copy (the only work it enqueues).  After the
  *              table come the tile queue of the streaming batch kernel, zeroed by
  *              fq_plan_create and left zeroed by every run, and the lists of entries a run
  *              draws up for its bit-widths: runs of one plan must not overlap in time
