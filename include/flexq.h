@@ -343,8 +343,10 @@ int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int
  *              caller, written by fq_sched_init and updated by every step
  *   ev_entry, ev_bits  device, int32 [n_events]   (read; must outlive the state's use)
  *   bits       device, int32 [entries]            (updated in place)
+ *   entries    length of `bits`: an event whose entry is outside 0 .. entries - 1, or whose
+ *              bit-width is not 2, 4, 8 or 16, is passed over when its turn comes
  *   ev_token   device, int32 [n_events] or NULL   (written: index of the token at which
- *              each event fired)
+ *              each event fired; -2 for an event that was passed over)
  *   entropy    device, f32: one value (fq_sched_step: the entropy of this token's logits, as
  *              written by fq_entropy_kl) or [R] (fq_sched_threshold_from_prefill, which sets
  *              thre to the mean PPLE of the last min(last_n, R) of R prefill positions)
@@ -354,7 +356,7 @@ int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int
 size_t fq_sched_state_bytes(int window);
 int fq_sched_init(void *state, int window, double thre, int per_trigger,
                   const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
-                  int32_t *bits, int32_t *ev_token, void *stream);
+                  int32_t *bits, int entries, int32_t *ev_token, void *stream);
 int fq_sched_threshold_from_prefill(void *state, const float *entropy, int R, int last_n,
                                     void *stream);
 int fq_sched_step(void *state, const float *entropy, void *stream);

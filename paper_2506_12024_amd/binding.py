@@ -109,7 +109,7 @@ def _load() -> ctypes.CDLL:
     L.fq_sched_state_bytes.restype = sz
     L.fq_sched_state_bytes.argtypes = [ci]
     L.fq_sched_init.restype = ci
-    L.fq_sched_init.argtypes = [vp, ci, ctypes.c_double, ci, vp, vp, ci, vp, vp, vp]
+    L.fq_sched_init.argtypes = [vp, ci, ctypes.c_double, ci, vp, vp, ci, vp, ci, vp, vp]
     L.fq_sched_threshold_from_prefill.restype = ci
     L.fq_sched_threshold_from_prefill.argtypes = [vp, vp, ci, ci, vp]
     L.fq_sched_step.restype = ci
@@ -312,9 +312,12 @@ def fq_sched_state_bytes(window: int) -> int:
 
 
 def fq_sched_init(state, window: int, thre: float, per_trigger: int, ev_entry, ev_bits, n_events: int,
-                  bits, ev_token=None, stream=None):
+                  bits, ev_token=None, stream=None, entries: int | None = None):
+    """`entries` defaults to the length of the `bits` tensor."""
+    if entries is None:
+        entries = bits.numel()
     _check(lib.fq_sched_init(_ptr(state), window, thre, per_trigger, _ptr(ev_entry), _ptr(ev_bits),
-                             n_events, _ptr(bits), _ptr(ev_token), _stream(stream)))
+                             n_events, _ptr(bits), entries, _ptr(ev_token), _stream(stream)))
 
 
 def fq_sched_threshold_from_prefill(state, entropy, R: int, last_n: int, stream=None):

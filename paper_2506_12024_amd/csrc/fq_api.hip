@@ -612,13 +612,14 @@ size_t fq_sched_state_bytes(int window)
 }
 
 int fq_sched_init(void *state, int window, double thre, int per_trigger, const int32_t *ev_entry,
-                  const int32_t *ev_bits, int n_events, int32_t *bits, int32_t *ev_token, void *stream)
+                  const int32_t *ev_bits, int n_events, int32_t *bits, int entries, int32_t *ev_token, void *stream)
 {
     if (!state || !bits)
         return fail(FQ_ERR_NULL, "fq_sched_init: state or bits is NULL");
-    if (window < 1 || window > 1024 || per_trigger < 1 || n_events < 0)
+    if (window < 1 || window > 1024 || per_trigger < 1 || n_events < 0 || entries < 1)
         return fail(FQ_ERR_SHAPE, "fq_sched_init: need 1 <= window <= 1024, per_trigger >= 1, "
-                                  "n_events >= 0 (got %d, %d, %d)", window, per_trigger, n_events);
+                                  "n_events >= 0, entries >= 1 (got %d, %d, %d, %d)", window, per_trigger, n_events,
+                    entries);
     if (n_events > 0 && (!ev_entry || !ev_bits))
         return fail(FQ_ERR_NULL, "fq_sched_init: ev_entry / ev_bits are NULL");
     if ((reinterpret_cast<uintptr_t>(state) & 7u) || (reinterpret_cast<uintptr_t>(bits) & 3u) ||
@@ -626,7 +627,7 @@ int fq_sched_init(void *state, int window, double thre, int per_trigger, const i
         (reinterpret_cast<uintptr_t>(ev_token) & 3u))
         return fail(FQ_ERR_ALIGN, "fq_sched_init: state needs 8-byte, int arrays 4-byte alignment");
     hipError_t e = fq_launch_sched_init((FqSchedState *)state, window, thre, per_trigger, ev_entry,
-                                        ev_bits, n_events, bits, ev_token, (hipStream_t)stream);
+                                        ev_bits, n_events, bits, entries, ev_token, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_sched_init launch");
     return FQ_OK;

@@ -103,7 +103,7 @@ constexpr int FQ_Q_DONE = 8, FQ_Q_TILES = 9, FQ_Q_ENTRIES = 10;
 struct FqSchedState {
     double thre;
     double last_mean;
-    int window, per_trigger, n_events, next_event, pos, count, token, pad;
+    int window, per_trigger, n_events, next_event, pos, count, token, entries;
     const int32_t *ev_entry;
     const int32_t *ev_bits;
     int32_t *bits;
@@ -112,7 +112,7 @@ struct FqSchedState {
 };
 hipError_t fq_launch_sched_init(FqSchedState *s, int window, double thre, int per_trigger,
                                 const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
-                                int32_t *bits, int32_t *ev_token, hipStream_t stream);
+                                int32_t *bits, int entries, int32_t *ev_token, hipStream_t stream);
 hipError_t fq_launch_sched_threshold(FqSchedState *s, const float *entropy, int R, int last_n,
                                      hipStream_t stream);
 hipError_t fq_launch_sched_step(FqSchedState *s, const float *entropy, hipStream_t stream);

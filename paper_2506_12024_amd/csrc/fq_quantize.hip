@@ -131,8 +131,9 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
 
 // Eq. (2) then Eq. (3), rounded to fp16: w_hat = half(s * (q - z)).
 template <bool SYM>
-__global__ __launch_bounds__(256) void fake_quantize_kernel(const half8 *__restrict__ w, long long n_groups, int bits,
-                                                            half8 *__restrict__ w_hat)
+// (w_hat may be w itself: no __restrict__; a lane reads its eight weights before it writes them)
+__global__ __launch_bounds__(256) void fake_quantize_kernel(const half8 *w, long long n_groups, int bits,
+                                                            half8 *w_hat)
 {
 #pragma clang fp contract(off)
     const long long seg = ((long long)blockIdx.x * 256 + threadIdx.x) >> 4;

@@ -18,7 +18,7 @@
 
 __global__ void sched_init_kernel(FqSchedState *s, int window, double thre, int per_trigger,
                                   const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
-                                  int32_t *bits, int32_t *ev_token)
+                                  int32_t *bits, int entries, int32_t *ev_token)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0)
         return;
@@ -31,7 +31,7 @@ __global__ void sched_init_kernel(FqSchedState *s, int window, double thre, int 
     s->pos = 0;
     s->count = 0;
     s->token = 0;
-    s->pad = 0;
+    s->entries = entries;
     s->ev_entry = ev_entry;
     s->ev_bits = ev_bits;
     s->bits = bits;
@@ -73,9 +73,15 @@ __global__ void sched_step_kernel(FqSchedState *s, const float *entropy)
         int next = s->next_event;
         if (mean < s->thre && next < s->n_events) {
             for (int j = 0; j < s->per_trigger && next < s->n_events; j++) {
-                s->bits[s->ev_entry[next]] = s->ev_bits[next];
+                // an event that names no entry of the array, or no bit-width, is passed over (a
+                // replacement order ranked over another number of linears must not write beside
+                // the array the plan reads)
+                const int e = s->ev_entry[next], b = s->ev_bits[next];
+                const bool ok = e >= 0 && e < s->entries && (b == 2 || b == 4 || b == 8 || b == 16);
+                if (ok)
+                    s->bits[e] = b;
                 if (s->ev_token)
-                    s->ev_token[next] = s->token;
+                    s->ev_token[next] = ok ? s->token : -2;
                 next++;
             }
             s->next_event = next;
@@ -89,10 +95,10 @@ __global__ void sched_step_kernel(FqSchedState *s, const float *entropy)
 
 hipError_t fq_launch_sched_init(FqSchedState *s, int window, double thre, int per_trigger,
                                 const int32_t *ev_entry, const int32_t *ev_bits, int n_events,
-                                int32_t *bits, int32_t *ev_token, hipStream_t stream)
+                                int32_t *bits, int entries, int32_t *ev_token, hipStream_t stream)
 {
     sched_init_kernel<<<1, 64, 0, stream>>>(s, window, thre, per_trigger, ev_entry, ev_bits, n_events,
-                                           bits, ev_token);
+                                           bits, entries, ev_token);
     return hipGetLastError();
 }
 

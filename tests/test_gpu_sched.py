@@ -130,3 +130,26 @@ def test_scheduler_drives_a_plan_without_host_round_trip():
         assert abs(H_dev[t].item() - H_ref[t]) <= 1e-4 * abs(H_ref[t]) + 1e-7
         switched += ref.step(float(H_ref[t]))
     assert switched == 3 and np.array_equal(bits.cpu().numpy(), ref_bits)
+
+
+def test_events_outside_the_array_are_passed_over():
+    # a replacement order ranked over more linears than the plan has, and an event with no valid
+    # bit-width: neither may write anything; the guard words around the array stay as they were
+    pple = [1.0] * 12
+    H = np.log(np.array(pple, dtype=np.float64)).astype(np.float32)
+    n = 4
+    guard = torch.full((n + 8,), 77, dtype=torch.int32, device=DEV)
+    bits = guard[4:4 + n]
+    bits.fill_(8)
+    ev = np.array([(1, 4), (9, 4), (-3, 4), (2, 5), (3, 4)], dtype=np.int32)
+    ev_entry, ev_bits = to_dev(np.ascontiguousarray(ev[:, 0])), to_dev(np.ascontiguousarray(ev[:, 1]))
+    ev_token = torch.full((len(ev),), -1, dtype=torch.int32, device=DEV)
+    state = torch.zeros(fq.fq_sched_state_bytes(2), dtype=torch.uint8, device=DEV)
+    fq.fq_sched_init(state, 2, 5.0, 1, ev_entry, ev_bits, len(ev), bits, ev_token, entries=n)
+    H_dev = to_dev(H)
+    for t in range(len(H)):
+        fq.fq_sched_step(state, H_dev[t:t + 1])
+    next_event, tokens, _, _ = fq.fq_sched_peek(state)
+    assert next_event == len(ev) and tokens == len(pple)
+    assert guard.cpu().tolist() == [77] * 4 + [8, 4, 8, 4] + [77] * 4
+    assert ev_token.cpu().tolist() == [1, -2, -2, -2, 9]

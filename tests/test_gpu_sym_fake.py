@@ -82,3 +82,13 @@ def test_two_bit_model_through_the_fp16_path():
     y = gpu_linear(layer, 16, x)
     y_ref = oracle.linear(x, oracle.fake_quantize(w, 2), None, None, 16)
     assert rel_err(y, y_ref) <= 2e-3
+
+
+def test_fake_quantize_in_place():
+    # w_hat may be w itself
+    w = synth.weight(0, "sym/inplace/w", 64, 1024, 0.02, outlier_p=0.001)
+    ref = oracle.fake_quantize(w, 3)
+    w_dev = to_dev(w)
+    fq.fq_fake_quantize(w_dev, 64, 1024, 3, 128, False, w_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(w_dev.cpu().numpy().view(np.uint16), ref.view(np.uint16))

@@ -128,12 +128,13 @@ def test_sched_validation():
     L = fq.lib
     assert L.fq_sched_state_bytes(0) == 0 and L.fq_sched_state_bytes(1025) == 0
     assert L.fq_sched_state_bytes(20) >= 64 + 20 * 8 and L.fq_sched_state_bytes(20) % 256 == 0
-    assert L.fq_sched_init(None, 20, 2.0, 1, FAKE, FAKE, 4, FAKE, None, None) == B.FQ_ERR_NULL
-    assert L.fq_sched_init(FAKE, 20, 2.0, 1, FAKE, FAKE, 4, None, None, None) == B.FQ_ERR_NULL
-    assert L.fq_sched_init(FAKE, 0, 2.0, 1, FAKE, FAKE, 4, FAKE, None, None) == B.FQ_ERR_SHAPE
-    assert L.fq_sched_init(FAKE, 20, 2.0, 0, FAKE, FAKE, 4, FAKE, None, None) == B.FQ_ERR_SHAPE
-    assert L.fq_sched_init(FAKE, 20, 2.0, 1, None, FAKE, 4, FAKE, None, None) == B.FQ_ERR_NULL
-    assert L.fq_sched_init(FAKE + 4, 20, 2.0, 1, FAKE, FAKE, 4, FAKE, None, None) == B.FQ_ERR_ALIGN
+    assert L.fq_sched_init(None, 20, 2.0, 1, FAKE, FAKE, 4, FAKE, 8, None, None) == B.FQ_ERR_NULL
+    assert L.fq_sched_init(FAKE, 20, 2.0, 1, FAKE, FAKE, 4, None, 8, None, None) == B.FQ_ERR_NULL
+    assert L.fq_sched_init(FAKE, 0, 2.0, 1, FAKE, FAKE, 4, FAKE, 8, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_sched_init(FAKE, 20, 2.0, 0, FAKE, FAKE, 4, FAKE, 8, None, None) == B.FQ_ERR_SHAPE
+    assert L.fq_sched_init(FAKE, 20, 2.0, 1, None, FAKE, 4, FAKE, 8, None, None) == B.FQ_ERR_NULL
+    assert L.fq_sched_init(FAKE + 4, 20, 2.0, 1, FAKE, FAKE, 4, FAKE, 8, None, None) == B.FQ_ERR_ALIGN
+    assert L.fq_sched_init(FAKE, 20, 2.0, 1, FAKE, FAKE, 4, FAKE, 0, None, None) == B.FQ_ERR_SHAPE
     assert L.fq_sched_step(None, FAKE, None) == B.FQ_ERR_NULL
     assert L.fq_sched_step(FAKE, None, None) == B.FQ_ERR_NULL
     assert L.fq_sched_threshold_from_prefill(FAKE, FAKE, 0, 3, None) == B.FQ_ERR_SHAPE
