@@ -80,7 +80,7 @@ def quantize(w: np.ndarray, bits: int, group: int = 128):
     zeros u8 [N][K/group]) in the canonical packed layout (Sec. 2.2 Eq. 2)."""
     w = np.ascontiguousarray(w, dtype=np.float16)
     N, K = w.shape
-    if bits not in (2, 4, 8) or group <= 0 or K % group:
+    if bits not in (2, 3, 4, 8) or group <= 0 or K % group:
         raise ValueError("bad bits/group")
     codes = np.zeros((N, K * bits // 8), dtype=np.uint8)
     scales = np.zeros((N, K // group), dtype=np.float32)
@@ -97,7 +97,7 @@ def quantize_sym(w: np.ndarray, bits: int, group: int = 128):
     = 2^(n-1), so that dequant() and linear() apply unchanged."""
     w = np.ascontiguousarray(w, dtype=np.float16)
     N, K = w.shape
-    if bits not in (2, 4, 8) or group <= 0 or K % group:
+    if bits not in (2, 3, 4, 8) or group <= 0 or K % group:
         raise ValueError("bad bits/group")
     codes = np.zeros((N, K * bits // 8), dtype=np.uint8)
     scales = np.zeros((N, K // group), dtype=np.float32)

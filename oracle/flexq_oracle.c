@@ -102,9 +102,23 @@ uint16_t orc_double_to_half(double d) { return double_to_half(d); }
 /* ---- Eq. (2): quantize one matrix, group-wise along the input dimension ---- */
 
 /* Packed codes: 8 bits one per byte; 4 bits two per byte, the even k in the low nibble; 2 bits
- * four per byte, k % 4 = 0 in bits 0..1 up to k % 4 = 3 in bits 6..7.  Rows follow each other. */
+ * four per byte, k % 4 = 0 in bits 0..1 up to k % 4 = 3 in bits 6..7.  Rows follow each other.
+ * 3 bits (the paper names no format for its 3-bit models; this is the repository's): a row is
+ * K / 32 blocks of 12 bytes, block b holding k = 32 b .. 32 b + 31; bytes 0..7 of a block are the
+ * two low bits of the 32 codes in the 2-bit order (byte j: codes 4j .. 4j+3); bytes 8..11 are one
+ * little-endian 32-bit word of the codes' high bits, code i at bit
+ * (i % 8) + 16 * ((i / 8) % 2) + 8 * (i / 16): codes 0..7, 16..23, 8..15, 24..31 from bit 0 up. */
+static int high_bit_place3(int i) { return (i & 7) + 16 * ((i >> 3) & 1) + 8 * (i >> 4); }
+
 static int code_of(const uint8_t *codes, int bits, long long row_elems, long long n, long long k)
 {
+    if (bits == 3) {
+        const uint8_t *blk = codes + n * (row_elems * 3 / 8) + (k / 32) * 12;
+        const int i = (int)(k % 32), hp = high_bit_place3(i);
+        const int lo = (blk[i / 4] >> (2 * (i & 3))) & 3;
+        const int hi = (blk[8 + hp / 8] >> (hp & 7)) & 1;
+        return lo | (hi << 2);
+    }
     if (bits == 8)
         return codes[n * row_elems + k];
     if (bits == 2)
@@ -115,6 +129,13 @@ static int code_of(const uint8_t *codes, int bits, long long row_elems, long lon
 
 static void put_code(uint8_t *codes, int bits, long long row_elems, long long n, long long k, unsigned q)
 {
+    if (bits == 3) {
+        uint8_t *blk = codes + n * (row_elems * 3 / 8) + (k / 32) * 12;
+        const int i = (int)(k % 32), hp = high_bit_place3(i);
+        blk[i / 4] |= (uint8_t)((q & 3u) << (2 * (i & 3)));
+        blk[8 + hp / 8] |= (uint8_t)(((q >> 2) & 1u) << (hp & 7));
+        return;
+    }
     if (bits == 8)
         codes[n * row_elems + k] = (uint8_t)q;
     else if (bits == 2)
@@ -126,13 +147,14 @@ static void put_code(uint8_t *codes, int bits, long long row_elems, long long n,
 /*
  * w: [N][K] binary16 bit patterns.  codes: N*K*bits/8 bytes.  scales: [N][K/group]
  * float.  zeros: [N][K/group] bytes.  Returns 0, or -1 on a bad argument
- * (bits not 2, 4 or 8, K not a multiple of group, an odd group, at 2 bits a group that is not a
- * multiple of 4) or a non-finite weight.
+ * (bits not 2, 3, 4 or 8, K not a multiple of group, an odd group, at 2 bits a group that is not a
+ * multiple of 4, at 3 bits one that is not a multiple of 32) or a non-finite weight.
  */
 int orc_quantize(const uint16_t *w, int N, int K, int bits, int group,
                  uint8_t *codes, float *scales, uint8_t *zeros)
 {
-    if ((bits != 2 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) || K % group != 0)
+    if ((bits != 2 && bits != 3 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) ||
+        (bits == 3 && (group & 31)) || K % group != 0)
         return -1;
     const int G = K / group;
     const float qmax = (float)((1 << bits) - 1);
@@ -220,7 +242,8 @@ static float sym_code(float v, float s, int bits)
 int orc_quantize_sym(const uint16_t *w, int N, int K, int bits, int group,
                      uint8_t *codes, float *scales, uint8_t *zeros)
 {
-    if ((bits != 2 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) || K % group != 0)
+    if ((bits != 2 && bits != 3 && bits != 4 && bits != 8) || group <= 0 || (group & 1) || (bits == 2 && (group & 3)) ||
+        (bits == 3 && (group & 31)) || K % group != 0)
         return -1;
     const int G = K / group;
     const int offset = 1 << (bits - 1);
@@ -341,7 +364,7 @@ int orc_linear(const uint16_t *x, int M, const uint8_t *codes, const float *scal
                const uint8_t *zeros, int N, int K, int bits, int group,
                int row0, int rows, uint16_t *y)
 {
-    if (bits != 2 && bits != 4 && bits != 8 && bits != 16)
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8 && bits != 16)
         return -1;
     if (bits != 16 && (group <= 0 || K % group != 0))
         return -1;
