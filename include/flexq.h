@@ -39,6 +39,14 @@
  *                                     code(4j+2) << 4 | code(4j+3) << 6
  *                                     (Table 1's lowest width; served by the decode kernels,
  *                                     M <= FQ_MAX_DECODE_M)
+ *   codes, bits = 3 : u8  [N][K/32][12]  a block of 12 bytes holds 32 consecutive codes c(0..31):
+ *                                     bytes 0..7 their low two bits in the 2-bit order above
+ *                                     (byte j = sum over i < 4 of (c(4j+i) & 3) << 2i), bytes
+ *                                     8..11 a little-endian word of their high bits, c(i) >> 2 at
+ *                                     bit (i % 8) + 16 ((i / 8) % 2) + 8 (i / 16).  The paper runs
+ *                                     3-bit models (Table 1, Sec. 5.1) without fixing a packing:
+ *                                     this one is this library's, chosen so that a lane's 12 bytes
+ *                                     unpack with the 2-bit path's masks.  Served at M = 1.
  *   scales          : f32 [N][K/group]
  *   zeros           : u8  [N][K/group]
  *   bits = 16       : the fp16 weights W[N][K] themselves, no scales/zeros
@@ -76,7 +84,7 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 const char *fq_last_error(void);
 
 /*
- * Bytes of the three packed buffers for an N x K weight at `bits` (2, 4 or 8): what Eq. (2) of
+ * Bytes of the three packed buffers for an N x K weight at `bits` (2, 3, 4 or 8): what Eq. (2) of
  * Sec. 2.2 produces per weight (an n-bit code) and per group (s, z), in the layout above.
  * Any of the three outputs may be NULL.  Host-only; launches nothing.
  */
@@ -92,7 +100,7 @@ int fq_packed_sizes(int N, int K, int bits, int group,
  *   codes   device, fq_packed_sizes bytes, 16-byte aligned (written)
  *   scales  device, f32 [N][K/group]                   (written)
  *   zeros   device, u8  [N][K/group]                   (written)
- * bits in {2, 4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
+ * bits in {2, 3, 4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
  * Non-finite weights give unspecified codes.
  */
 int fq_quantize(const void *w_fp16, int N, int K, int bits, int group,
@@ -127,7 +135,7 @@ int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int 
  * A layer handle: a small host object naming the resident copies of one
  * linear's weight -- Sec. 4.3: every linear is kept in several formats at once, all resident in
  * HBM, and a switch of precision selects among them.  fq_layer_attach records (does not copy) the buffers for one
- * bit-width; any subset of {2, 4, 8, 16} may be attached, each at most once per
+ * bit-width; any subset of {2, 3, 4, 8, 16} may be attached, each at most once per
  * value (attaching again replaces the pointers).  For bits = 16 pass the fp16
  * weights as `codes` and NULL scales/zeros.  Buffers must be 16-byte aligned.
  * Launches nothing and takes no stream: the kernels stream the packed layout as it is, so there is
@@ -143,8 +151,8 @@ int fq_layer_destroy(fq_layer *layer);
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
  * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 2 is
- * served in the decode phase only (M <= FQ_MAX_DECODE_M and K <= FQ_MAX_DECODE_K):
- * FQ_ERR_BITS otherwise.
+ * served in the decode phase only (M <= FQ_MAX_DECODE_M and K <= FQ_MAX_DECODE_K), bits = 3 at
+ * M = 1 only (K <= FQ_MAX_DECODE_K): FQ_ERR_BITS otherwise.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)
  * 1 <= M <= FQ_MAX_DECODE_M with K <= FQ_MAX_DECODE_K selects the memory-bound skinny
@@ -169,9 +177,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *              fq_plan_create and left zeroed by every run, and the lists of entries a run
  *              draws up for its bit-widths: runs of one plan must not overlap in time
  *              (they would share these, and they write the same ys)
- *   bits_dev   device, int32 [count], each 2, 4, 8 or 16 and attached to its layer;
- *              an entry whose value is anything else is skipped by the kernel
- *              and its y is left untouched.  A large plan with M > 1 whose layers carry
+ *   bits_dev   device, int32 [count], each 2, 3, 4, 8 or 16 and attached to its layer;
+ *              an entry whose value is anything else (or 3 in a plan with M > 1) is skipped
+ *              by the kernel and its y is left untouched.  A large plan with M > 1 whose layers carry
  *              2-bit copies runs as two kernels (the streaming batch kernel takes 4, 8 and
  *              16 bits; the entries that are at 2 bits follow on the register-fed one)
  */
@@ -205,7 +213,7 @@ int fq_plan_destroy(fq_plan *plan);
  * incomplete, every workgroup still exits, the barrier's counters are put back, and the next
  * launch starts clean.  fq_plan_status waits for `stream` and reports
  *   gave_up  launches of this plan that gave up so far (never reset)
- *   flags    bit 0: an entry's bit-width was not 2, 4, 8 or 16 or had no copy attached (its y was
+ *   flags    bit 0: an entry's bit-width was not 2, 3, 4, 8 or 16 or had no copy attached (its y was
  *            left untouched); bit 1: a workgroup's share of a stage exceeded 4096 rows (skipped)
  * Either output may be NULL.  Runs of one plan must not overlap in time.
  */
@@ -344,7 +352,7 @@ int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int
  *   ev_entry, ev_bits  device, int32 [n_events]   (read; must outlive the state's use)
  *   bits       device, int32 [entries]            (updated in place)
  *   entries    length of `bits`: an event whose entry is outside 0 .. entries - 1, or whose
- *              bit-width is not 2, 4, 8 or 16, is passed over when its turn comes
+ *              bit-width is not 2, 3, 4, 8 or 16, is passed over when its turn comes
  *   ev_token   device, int32 [n_events] or NULL   (written: index of the token at which
  *              each event fired; -2 for an event that was passed over)
  *   entropy    device, f32: one value (fq_sched_step: the entropy of this token's logits, as

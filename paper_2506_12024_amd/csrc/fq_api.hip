@@ -39,16 +39,16 @@ constexpr int MAX_DECODE_K = FQ_MAX_DECODE_K;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int slot_of(int bits) { return bits == 4 ? 0 : bits == 8 ? 1 : bits == 16 ? 2 : bits == 2 ? 3 : -1; }
+int slot_of(int bits) { return bits == 4 ? 0 : bits == 8 ? 1 : bits == 16 ? 2 : bits == 2 ? 3 : bits == 3 ? 4 : -1; }
 
 } // namespace
 
 struct fq_layer {
     uint32_t magic;
     int N, K, group;
-    const void *codes[4]; // by slot_of(bits)
-    const void *scales[4];
-    const void *zeros[4];
+    const void *codes[5]; // by slot_of(bits)
+    const void *scales[5];
+    const void *zeros[5];
 };
 
 struct fq_plan {
@@ -88,6 +88,9 @@ void fill_desc(FqLinearDesc &d, const fq_layer *l, const void *x, void *y)
     d.codes2 = (const uint8_t *)l->codes[3];
     d.scales2 = (const float *)l->scales[3];
     d.zeros2 = (const uint8_t *)l->zeros[3];
+    d.codes3 = (const uint8_t *)l->codes[4];
+    d.scales3 = (const float *)l->scales[4];
+    d.zeros3 = (const uint8_t *)l->zeros[4];
     d.x = (const uint16_t *)x;
     d.y = (uint16_t *)y;
     d.N = l->N;
@@ -114,8 +117,8 @@ const char *fq_last_error(void) { return g_err; }
 int fq_packed_sizes(int N, int K, int bits, int group, size_t *codes_bytes, size_t *scales_bytes,
                     size_t *zeros_bytes)
 {
-    if (bits != 2 && bits != 4 && bits != 8)
-        return fail(FQ_ERR_BITS, "fq_packed_sizes: bits must be 2, 4 or 8 (got %d)", bits);
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8)
+        return fail(FQ_ERR_BITS, "fq_packed_sizes: bits must be 2, 3, 4 or 8 (got %d)", bits);
     if (int rc = check_shape(N, K, group))
         return rc;
     const size_t groups = (size_t)N * (size_t)(K / group);
@@ -133,8 +136,8 @@ static int quantize_any(const char *who, bool symmetric, const void *w_fp16, int
 {
     if (!w_fp16 || !codes || !scales || !zeros)
         return fail(FQ_ERR_NULL, "%s: NULL tensor pointer", who);
-    if (bits != 2 && bits != 4 && bits != 8)
-        return fail(FQ_ERR_BITS, "%s: bits must be 2, 4 or 8 (got %d)", who, bits);
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8)
+        return fail(FQ_ERR_BITS, "%s: bits must be 2, 3, 4 or 8 (got %d)", who, bits);
     if (int rc = check_shape(N, K, group))
         return rc;
     if (!aligned16(w_fp16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u))
@@ -221,7 +224,7 @@ int fq_layer_attach(fq_layer *layer, int bits, const void *codes, const void *sc
         return rc;
     const int slot = slot_of(bits);
     if (slot < 0)
-        return fail(FQ_ERR_BITS, "fq_layer_attach: bits must be 2, 4, 8 or 16 (got %d)", bits);
+        return fail(FQ_ERR_BITS, "fq_layer_attach: bits must be 2, 3, 4, 8 or 16 (got %d)", bits);
     if (!codes)
         return fail(FQ_ERR_NULL, "fq_layer_attach: codes is NULL");
     if (bits != 16 && (!scales || !zeros))
@@ -251,11 +254,14 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
         return fail(FQ_ERR_NULL, "fq_linear: x or y is NULL");
     const int slot = slot_of(bits);
     if (slot < 0)
-        return fail(FQ_ERR_BITS, "fq_linear: bits must be 2, 4, 8 or 16 (got %d)", bits);
+        return fail(FQ_ERR_BITS, "fq_linear: bits must be 2, 3, 4, 8 or 16 (got %d)", bits);
     if (!layer->codes[slot])
         return fail(FQ_ERR_NOT_ATTACHED, "fq_linear: no %d-bit copy attached to this layer", bits);
     if (M < 1)
         return fail(FQ_ERR_SHAPE, "fq_linear: M must be >= 1 (got %d)", M);
+    if (bits == 3 && (M != 1 || layer->K > MAX_DECODE_K))
+        return fail(FQ_ERR_BITS, "fq_linear: the 3-bit copy is served by the batch-1 decode kernel only, M = 1 and K <= %d (got M=%d K=%d)",
+                    MAX_DECODE_K, M, layer->K);
     if (bits == 2 && (M > FQ_MAX_DECODE_M || layer->K > MAX_DECODE_K))
         return fail(FQ_ERR_BITS, "fq_linear: the 2-bit copy is served by the decode kernels only, M <= %d and K <= %d (got M=%d K=%d)",
                     FQ_MAX_DECODE_M, MAX_DECODE_K, M, layer->K);
@@ -361,7 +367,8 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
         if (layers[i]->K > MAX_DECODE_K)
             return fail(FQ_ERR_SHAPE, "%s: entry %d: K=%d exceeds the decode limit %d", who, i, layers[i]->K,
                         MAX_DECODE_K);
-        if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2] && !layers[i]->codes[3])
+        if (!layers[i]->codes[0] && !layers[i]->codes[1] && !layers[i]->codes[2] && !layers[i]->codes[3] &&
+            !layers[i]->codes[4])
             return fail(FQ_ERR_NOT_ATTACHED, "%s: entry %d has no copy attached", who, i);
         total_rows += layers[i]->N;
         if (layers[i]->K > max_K)

@@ -126,11 +126,14 @@ struct Cut {
 // for bits from {2, 4} and 0.633 / 0.628 / 0.629 / 0.632 / 0.634 ms for {2, 4, 8}.
 constexpr int W4_COST = 230;     // per byte
 constexpr int W2_PER_MILLE = 730; // of the cost of a 4-bit group
+constexpr int W3_PER_MILLE = 850; // a 3-bit group: three quarters of the bytes, the same unpacking work
 __device__ __forceinline__ long long entry_unit_cost(const FqLinearDesc &d, int bits)
 {
     const long long groups = d.K >> 7;
     if (bits == 2)
         return d.codes2 ? groups * (64 * W4_COST * W2_PER_MILLE / 1000) : 0;
+    if (bits == 3)
+        return d.codes3 ? groups * (64 * W4_COST * W3_PER_MILLE / 1000) : 0;
     if (bits == 4)
         return d.codes4 ? groups * (64 * W4_COST) : 0;
     if (bits == 8)
@@ -229,24 +232,26 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
     if (SINGLE) {
         // one linear: equal row tiles dealt round-robin
         const int wave_rows = tile_rows / WAVES; // multiple of 4
-        const uint8_t *codes = bits_host == 2   ? single.codes2
-                               : bits_host == 4 ? single.codes4
-                               : bits_host == 8 ? single.codes8
-                                                : (const uint8_t *)single.w16;
-        Sel d = {codes, bits_host == 2 ? single.scales2 : bits_host == 4 ? single.scales4 : single.scales8,
-                 bits_host == 2 ? single.zeros2 : bits_host == 4 ? single.zeros4 : single.zeros8, single.N, single.K};
         bool first = true;
         for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
-            const int row_begin = min(tile * tile_rows + wave * wave_rows, d.N);
-            const int row_end = min(row_begin + wave_rows, d.N);
-            if (bits_host == 2)
+            const int row_begin = min(tile * tile_rows + wave * wave_rows, single.N);
+            const int row_end = min(row_begin + wave_rows, single.N);
+            if (bits_host == 2) {
+                const Sel d = {single.codes2, single.scales2, single.zeros2, single.N, single.K};
                 run_tile<2>(d, single.x, single.y, row_begin, row_end, first, lds);
-            else if (bits_host == 4)
+            } else if (bits_host == 3) {
+                const Sel d = {single.codes3, single.scales3, single.zeros3, single.N, single.K};
+                run_tile<3>(d, single.x, single.y, row_begin, row_end, first, lds);
+            } else if (bits_host == 4) {
+                const Sel d = {single.codes4, single.scales4, single.zeros4, single.N, single.K};
                 run_tile<4>(d, single.x, single.y, row_begin, row_end, first, lds);
-            else if (bits_host == 8)
+            } else if (bits_host == 8) {
+                const Sel d = {single.codes8, single.scales8, single.zeros8, single.N, single.K};
                 run_tile<8>(d, single.x, single.y, row_begin, row_end, first, lds);
-            else
+            } else {
+                const Sel d = {(const uint8_t *)single.w16, nullptr, nullptr, single.N, single.K};
                 run_tile<16>(d, single.x, single.y, row_begin, row_end, first, lds);
+            }
             first = false;
         }
         return;
@@ -261,26 +266,29 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
         const int u1 = e == hi.e ? hi.unit : units;
         if (u1 <= u0 || entry_unit_cost(*dp, bits) == 0)
             continue; // uniform over the workgroup: nothing of this entry falls in the slice
-        Sel d;
-        d.N = dp->N;
-        d.K = dp->K;
-        // the switch of precision: a pointer select on resident copies
-        d.codes = bits == 2 ? dp->codes2 : bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : (const uint8_t *)dp->w16;
-        d.scales = bits == 2 ? dp->scales2 : bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 2 ? dp->zeros2 : bits == 4 ? dp->zeros4 : dp->zeros8;
         // rows [16 u0, 16 u1) split over the 4 wavefronts in multiples of 4 rows
-        const int r0 = u0 * 16, r1 = min(u1 * 16, d.N);
+        const int r0 = u0 * 16, r1 = min(u1 * 16, dp->N);
         const int per_wave = ((r1 - r0 + WAVES * ROWS_PER_WAVE - 1) / (WAVES * ROWS_PER_WAVE)) * ROWS_PER_WAVE;
         const int row_begin = min(r0 + wave * per_wave, r1);
         const int row_end = min(row_begin + per_wave, r1);
-        if (bits == 2)
+        // the switch of precision: a pointer select on resident copies (each width names its own
+        // copy inside its own branch: nothing is selected ahead of the branch)
+        if (bits == 2) {
+            const Sel d = {dp->codes2, dp->scales2, dp->zeros2, dp->N, dp->K};
             run_tile<2>(d, dp->x, dp->y, row_begin, row_end, true, lds);
-        else if (bits == 4)
+        } else if (bits == 3) {
+            const Sel d = {dp->codes3, dp->scales3, dp->zeros3, dp->N, dp->K};
+            run_tile<3>(d, dp->x, dp->y, row_begin, row_end, true, lds);
+        } else if (bits == 4) {
+            const Sel d = {dp->codes4, dp->scales4, dp->zeros4, dp->N, dp->K};
             run_tile<4>(d, dp->x, dp->y, row_begin, row_end, true, lds);
-        else if (bits == 8)
+        } else if (bits == 8) {
+            const Sel d = {dp->codes8, dp->scales8, dp->zeros8, dp->N, dp->K};
             run_tile<8>(d, dp->x, dp->y, row_begin, row_end, true, lds);
-        else
+        } else {
+            const Sel d = {(const uint8_t *)dp->w16, nullptr, nullptr, dp->N, dp->K};
             run_tile<16>(d, dp->x, dp->y, row_begin, row_end, true, lds);
+        }
     }
 }
 

@@ -67,6 +67,7 @@ __device__ __forceinline__ float wave_sum_lane63(float v)
 //
 //   bits  codes/lane/slice  blocks/lane  block position
 //    2        64               8         ((b >> 9) * 8 + (b & 7)) * 64 + ((b >> 3) & 63), pairs of blocks interleaved
+//    3        32               4         as for 4 bits, pairs of blocks interleaved as for 2 bits
 //    4        32               4         ((b >> 8) * 4 + (b & 3)) * 64 + ((b >> 2) & 63)
 //    8        16               2         ((b >> 7) * 2 + (b & 1)) * 64 + ((b >> 1) & 63)
 //   16         8               1         b
@@ -75,7 +76,7 @@ __device__ __forceinline__ int block_pos(int b)
 {
     if (BITS == 2)
         return ((b >> 9) * 8 + (b & 7)) * 64 + ((b >> 3) & 63);
-    if (BITS == 4)
+    if (BITS == 4 || BITS == 3)
         return ((b >> 8) * 4 + (b & 3)) * 64 + ((b >> 2) & 63);
     if (BITS == 8)
         return ((b >> 7) * 2 + (b & 1)) * 64 + ((b >> 1) & 63);
@@ -83,7 +84,7 @@ __device__ __forceinline__ int block_pos(int b)
 }
 
 // k covered by one wavefront slice: 64 lanes x 16 bytes of codes
-__device__ __forceinline__ int slice_span(int bits) { return bits == 2 ? 4096 : bits == 4 ? 2048 : (bits == 8 ? 1024 : 512); }
+__device__ __forceinline__ int slice_span(int bits) { return bits == 2 ? 4096 : bits == 4 || bits == 3 ? 2048 : (bits == 8 ? 1024 : 512); }
 
 __device__ __forceinline__ int padded_k(int K, int bits)
 {
@@ -130,6 +131,46 @@ __device__ __forceinline__ void place_pair2(int pb, uint4 va, uint4 vb, uint4 *l
     t += dpp_take<0x4E, 0xF>(t);
     if ((pb & 3) == 0)
         sums[pb >> 2] = make_float2(c, t);
+}
+
+// 3 bits.  A lane's 12 bytes hold 32 codes: two words of low bit pairs in the 2-bit order and one
+// word of high bits.  The low words are unpacked like 2-bit codes, so the x blocks of every 16 k
+// are interleaved as for 2 bits -- the high word's bits are laid out to pair up the same way (bit
+// i of its low half with bit i of its high half: codes i and 8 + i, after a shift by 8 codes 16 + i
+// and 24 + i).  A low bit pair keeps its place in its byte (offsets 1024 / 256 / 64 / 16 for
+// i % 4 = 0 .. 3), a high bit its place among eight (offset 1024 >> (i % 8), the bit itself worth
+// 1; the caller adds the high part four times).  A thread stages one pair of blocks; the two
+// threads of a lane's slice (32 k) add up its two sums: sum (off_low + 4 off_high)(k) x_k and sum x_k.
+__device__ __forceinline__ void place_pair3(int pb, uint4 va, uint4 vb, uint4 *lds, float2 *sums)
+{
+    float p[4] = {0.f, 0.f, 0.f, 0.f}; // sums of the x whose code sits at position i % 4 of its byte
+    float c_high = 0.f;                // sum of 2^-(i % 8) x_k
+    const uint32_t w[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[i]); // halves 2 i, 2 i + 1 of their block (k % 8 = 2 (i % 4), + 1)
+        p[(2 * i) & 3] += (float)h[0];
+        p[(2 * i + 1) & 3] += (float)h[1];
+        c_high += (float)h[0] * (1.0f / (float)(1 << ((2 * i) & 7))) + (float)h[1] * (1.0f / (float)(1 << ((2 * i + 1) & 7)));
+    }
+    uint4 o0, o1;
+    o0.x = __builtin_amdgcn_perm(vb.x, va.x, 0x05040100u); // (A0, B0)
+    o0.y = __builtin_amdgcn_perm(vb.x, va.x, 0x07060302u); // (A1, B1)
+    o0.z = __builtin_amdgcn_perm(vb.y, va.y, 0x05040100u); // (A2, B2)
+    o0.w = __builtin_amdgcn_perm(vb.y, va.y, 0x07060302u); // (A3, B3)
+    o1.x = __builtin_amdgcn_perm(vb.z, va.z, 0x05040100u); // (A4, B4)
+    o1.y = __builtin_amdgcn_perm(vb.z, va.z, 0x07060302u);
+    o1.z = __builtin_amdgcn_perm(vb.w, va.w, 0x05040100u);
+    o1.w = __builtin_amdgcn_perm(vb.w, va.w, 0x07060302u); // (A7, B7)
+    lds[block_pos<3>(2 * pb)] = o0;
+    lds[block_pos<3>(2 * pb + 1)] = o1;
+    float c = 1024.0f * p[0] + 256.0f * p[1] + 64.0f * p[2] + 16.0f * p[3] + 4096.0f * c_high;
+    float t = (p[0] + p[1]) + (p[2] + p[3]);
+    // slice = 2 pairs = 2 consecutive threads
+    c += dpp_take<0xB1, 0xF>(c);
+    t += dpp_take<0xB1, 0xF>(t);
+    if ((pb & 1) == 0)
+        sums[pb >> 1] = make_float2(c, t);
 }
 
 // Places block b (k = 8 b .. 8 b + 7; v as loaded, zeros past K) for 4, 8 or 16 bits and the sums
@@ -181,6 +222,19 @@ template <int BITS, int THREADS>
 __device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
 {
     const int Kp = padded_k(K, BITS);
+    if (BITS == 3) {
+        const int npair = Kp >> 4; // a multiple of 128
+        float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3)); // per lane slice: (sum off(k) x, sum x)
+        for (int pb = threadIdx.x % THREADS; pb < npair; pb += THREADS) {
+            uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
+            if (pb * 16 < K) {
+                va = load16_global(x + (size_t)pb * 16);
+                vb = load16_global(x + (size_t)pb * 16 + 8);
+            }
+            place_pair3(pb, va, vb, lds, sums);
+        }
+        return;
+    }
     if (BITS == 2) {
         const int npair = Kp >> 4; // a multiple of 256: every thread makes the same number of trips
         float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3)); // per lane slice: (sum off(k) x, sum x)
@@ -228,6 +282,23 @@ __device__ __forceinline__ uint4 load16_stream(const void *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// The same from an address that is only 4-byte aligned (one instruction all the same).
+__device__ __forceinline__ uint4 load16_stream_a4(const void *p)
+{
+    typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+    const u32x4 v = __builtin_nontemporal_load((const FQ_GLOBAL u32x4_a4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// 96-bit streaming load (a 3-bit block: 4-byte aligned); .w is left 0.
+__device__ __forceinline__ uint4 load12_stream(const void *p)
+{
+    typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+    typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
+    const u32x3 v = __builtin_nontemporal_load((const FQ_GLOBAL u32x3_a4 *)p);
+    return make_uint4(v.x, v.y, v.z, 0u);
+}
+
 // Issue the global loads of item (rows row0..row0+3, slice j).  Rows past N and lanes
 // past K are clamped to valid addresses (their results are discarded: the row is not
 // stored, the lane's x is zero).
@@ -236,17 +307,17 @@ __device__ __forceinline__ void issue(const Sel &d, int row0, int j, Loaded &L)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t K = (uint32_t)d.K, G = K >> 7;
-    constexpr int CODES = 128 / BITS; // per lane per slice: 16 bytes
+    constexpr int CODES = BITS == 3 ? 32 : 128 / BITS; // per lane per slice: 16 bytes (3 bits: a block of 12)
     const uint32_t k0 = min((uint32_t)(j * 64 + lane) * CODES, K - CODES);
-    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
-    const uint32_t byte0 = BITS == 2 ? (k0 >> 2) : BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
+    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 3 ? (K >> 3) * 3 : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t byte0 = BITS == 2 ? (k0 >> 2) : BITS == 3 ? (k0 >> 5) * 12 : BITS == 4 ? (k0 >> 1) : (BITS == 8 ? k0 : 2 * k0);
     const uint32_t g = k0 >> 7;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
         // row0 is wavefront-uniform: the row bases are scalar, each lane adds a 32-bit offset
         const uint32_t row = (uint32_t)min(row0 + r, d.N - 1);
         const uint8_t *rowp = d.codes + (size_t)row * row_bytes;
-        L.w[r] = load16_stream(rowp + byte0);
+        L.w[r] = BITS == 3 ? load12_stream(rowp + byte0) : load16_stream(rowp + byte0);
         if (BITS != 16) {
             const float *srow = d.scales + (size_t)row * G;
             const uint8_t *zrow = d.zeros + (size_t)row * G;
@@ -296,6 +367,47 @@ __device__ __forceinline__ void compute(int K, int j, const Loaded &L, const uin
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++)
             acc[r] += L.s[r] * (a[r] - cs.x - (float)L.z[r] * cs.y);
+    } else if (BITS == 3) {
+        const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 3) >> 3));
+        // exponent patterns under which bit i of a half reads as (1024 >> i) + bit: the low bit pairs
+        // sit at bits 0, 2, 4, 6 (m[0], m[2], m[4], m[6]: 1024 + q, 256 + q, 64 + q, 16 + q as at 2
+        // bits), the high bits at bits 0 .. 7
+        uint32_t m[8] = {0x64006400u, 0x60006000u, 0x5C005C00u, 0x58005800u,
+                         0x54005400u, 0x50005000u, 0x4C004C00u, 0x48004800u};
+        asm volatile("" : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "+v"(m[4]), "+v"(m[5]), "+v"(m[6]), "+v"(m[7]));
+        uint4 xb[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            xb[i] = lds[(j * 4 + i) * 64 + lane];
+        const float2 cs = sums[j * 64 + lane]; // (sum (off_low + 4 off_high)(k) x, sum x) over the lane's 32 k
+#pragma unroll
+        for (int r = 0; r < ROWS_PER_WAVE; r++) {
+            const uint32_t lw[2] = {L.w[r].x, L.w[r].y};
+            const uint32_t hw[2] = {L.w[r].z, L.w[r].z >> 8};
+            float a_low = 0.0f, a_high = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 2; i++) { // 16 codes: x blocks 2 i (pairs 0 .. 3) and 2 i + 1 (pairs 4 .. 7)
+                const uint32_t v = lw[i], v8 = v >> 8, h = hw[i];
+                a_low = dot2((v & 0x00030003u) | m[0], xb[2 * i].x, a_low);      // codes 0, 8
+                a_low = dot2((v & 0x000C000Cu) | m[2], xb[2 * i].y, a_low);      // codes 1, 9
+                a_low = dot2((v & 0x00300030u) | m[4], xb[2 * i].z, a_low);      // codes 2, 10
+                a_low = dot2((v & 0x00C000C0u) | m[6], xb[2 * i].w, a_low);      // codes 3, 11
+                a_low = dot2((v8 & 0x00030003u) | m[0], xb[2 * i + 1].x, a_low); // codes 4, 12
+                a_low = dot2((v8 & 0x000C000Cu) | m[2], xb[2 * i + 1].y, a_low);
+                a_low = dot2((v8 & 0x00300030u) | m[4], xb[2 * i + 1].z, a_low);
+                a_low = dot2((v8 & 0x00C000C0u) | m[6], xb[2 * i + 1].w, a_low); // codes 7, 15
+                a_high = dot2((h & 0x00010001u) | m[0], xb[2 * i].x, a_high);
+                a_high = dot2((h & 0x00020002u) | m[1], xb[2 * i].y, a_high);
+                a_high = dot2((h & 0x00040004u) | m[2], xb[2 * i].z, a_high);
+                a_high = dot2((h & 0x00080008u) | m[3], xb[2 * i].w, a_high);
+                a_high = dot2((h & 0x00100010u) | m[4], xb[2 * i + 1].x, a_high);
+                a_high = dot2((h & 0x00200020u) | m[5], xb[2 * i + 1].y, a_high);
+                a_high = dot2((h & 0x00400040u) | m[6], xb[2 * i + 1].z, a_high);
+                a_high = dot2((h & 0x00800080u) | m[7], xb[2 * i + 1].w, a_high);
+            }
+            const float part = a_low + 4.0f * a_high - cs.x - (float)L.z[r] * cs.y;
+            acc[r] += L.s[r] * part;
+        }
     } else if (BITS == 4) {
         const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 4) >> 3));
         // The two exponent patterns live in VGPRs (hidden from constant folding) so that

@@ -19,6 +19,9 @@ struct FqLinearDesc {
     const uint8_t *codes2;  // [N][K/4] or null (not served by the streaming batch kernel and the GEMM)
     const float *scales2;
     const uint8_t *zeros2;
+    const uint8_t *codes3;  // [N][K/32] blocks of 12 bytes, or null (served at M = 1 only)
+    const float *scales3;
+    const uint8_t *zeros3;
     const uint16_t *x;      // fp16 [M][K]
     uint16_t *y;            // fp16 [M][N]
     int N;

@@ -27,7 +27,7 @@ static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
 
 namespace {
 
-constexpr int BATCH = 32; // descriptors per fill launch: 3584 bytes of kernel arguments
+constexpr int BATCH = 24; // descriptors per fill launch: 3264 bytes of kernel arguments
 
 struct DescBatch {
     FqLinearDesc d[BATCH];

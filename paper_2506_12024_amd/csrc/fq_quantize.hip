@@ -111,6 +111,20 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
         for (int i = 0; i < 8; i++)
             word |= q[i] << (2 * i); // byte j = code(4j) | code(4j+1) << 2 | code(4j+2) << 4 | code(4j+3) << 6
         reinterpret_cast<uint16_t *>(codes)[seg * 16 + sub] = (uint16_t)word;
+    } else if (BITS == 3) {
+        // a block of 12 bytes holds 32 codes, this lane's 8 are its quarter t: two bytes of low bit
+        // pairs (the 2-bit order), one byte of high bits -- quarters 0, 2, 1, 3 from the low end
+        // of the block's high word
+        const int t = sub & 3;
+        uint32_t low = 0, high = 0;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            low |= (q[i] & 3u) << (2 * i);
+            high |= (q[i] >> 2) << i;
+        }
+        uint8_t *blk = codes + (seg * 4 + (sub >> 2)) * 12;
+        *reinterpret_cast<uint16_t *>(blk + 2 * t) = (uint16_t)low;
+        blk[8 + ((t & 1) << 1) + (t >> 1)] = (uint8_t)high;
     } else if (BITS == 4) {
         uint32_t word = 0;
 #pragma unroll
@@ -184,6 +198,10 @@ hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool 
         quantize_kernel<2, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
     else if (bits == 2)
         quantize_kernel<2, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (bits == 3 && !symmetric)
+        quantize_kernel<3, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
+    else if (bits == 3)
+        quantize_kernel<3, true><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
     else if (bits == 4 && !symmetric)
         quantize_kernel<4, false><<<blocks, 256, 0, stream>>>(wp, n_groups, cp, sp, zp);
     else if (bits == 4)

@@ -77,7 +77,7 @@ __global__ void sched_step_kernel(FqSchedState *s, const float *entropy)
                 // replacement order ranked over another number of linears must not write beside
                 // the array the plan reads)
                 const int e = s->ev_entry[next], b = s->ev_bits[next];
-                const bool ok = e >= 0 && e < s->entries && (b == 2 || b == 4 || b == 8 || b == 16);
+                const bool ok = e >= 0 && e < s->entries && (b == 2 || b == 3 || b == 4 || b == 8 || b == 16);
                 if (ok)
                     s->bits[e] = b;
                 if (s->ev_token)

@@ -92,6 +92,8 @@ __device__ __forceinline__ long long group_cost(const FqLinearDesc &d, int bits)
 {
     if (bits == 2)
         return d.codes2 ? 64 * 230 * 730 / 1000 : 0;
+    if (bits == 3)
+        return d.codes3 ? 64 * 230 * 850 / 1000 : 0;
     if (bits == 4)
         return d.codes4 ? 64 * 230 : 0;
     if (bits == 8)
@@ -182,10 +184,10 @@ __device__ __forceinline__ void set_width(Cursor &c, int bits, int K)
 {
     c.bits = bits;
     c.K = K;
-    c.csh = bits == 2 ? 6 : bits == 4 ? 5 : bits == 8 ? 4 : 3;
-    c.rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0;
+    c.csh = bits == 2 ? 6 : bits == 4 || bits == 3 ? 5 : bits == 8 ? 4 : 3;
+    c.rsh = bits == 2 ? 3 : bits == 4 ? 2 : bits == 8 ? 1 : 0; // (3 bits: unused)
     c.gsh = c.csh - 1; // 32 / 16 / 8 groups per slice (fp16: unused)
-    c.row_bytes = (2u * (uint32_t)K) >> c.rsh;
+    c.row_bytes = bits == 3 ? ((uint32_t)K >> 3) * 3u : (2u * (uint32_t)K) >> c.rsh;
     c.G = (uint32_t)K >> 7;
     c.kmax = (uint32_t)K - (1u << c.csh);
 }
@@ -232,10 +234,14 @@ __device__ __forceinline__ void issue_item(const Cursor &c, Item &L)
 {
     const int lane = threadIdx.x & 63;
     const uint32_t k0 = min((uint32_t)(c.j * 64 + lane) << c.csh, c.kmax);
-    const uint32_t byte0 = (2 * k0) >> c.rsh;
+    // 3 bits: the lane's block of 12 bytes comes with 4 bytes of a neighbour, the next block's
+    // first for an even block, the previous block's last for an odd one (a row holds an even
+    // number of blocks, so the 16 bytes never leave the row)
+    const uint32_t blk = k0 >> 5;
+    const uint32_t byte0 = c.bits == 3 ? blk * 12u - ((blk & 1u) << 2) : (2 * k0) >> c.rsh;
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) // a row past the matrix's last repeats the last (discarded)
-        L.w[r] = load16_stream(c.crow + (byte0 + (uint32_t)min(r, c.last) * c.row_bytes));
+        L.w[r] = load16_stream_a4(c.crow + (byte0 + (uint32_t)min(r, c.last) * c.row_bytes)); // (3 bits: 8-byte aligned)
     // scales and zero points: lane l -> (row l >> gsh, group l & (GS - 1)) of the slice; at 2 bits the
     // second pair of loads takes rows 2 and 3, at the other widths it repeats the first
     const uint32_t g = min(((uint32_t)c.j << c.gsh) + (uint32_t)(lane & ((1 << c.gsh) - 1)), c.G - 1);
@@ -259,9 +265,12 @@ __device__ __forceinline__ void expand(const Item &I, const Cursor &c, Loaded &L
     const uint32_t k0 = min((uint32_t)(c.j * 64 + lane) << c.csh, c.kmax);
     const int gi = (int)(k0 >> 7) - (c.j << c.gsh); // my group's place among the slice's groups
     const bool two = c.bits == 2;
+    const bool odd3 = c.bits == 3 && ((k0 >> 5) & 1u); // a 3-bit block that sits in the last 12 of its 16 bytes
 #pragma unroll
     for (int r = 0; r < ROWS_PER_WAVE; r++) {
         L.w[r] = I.w[r];
+        if (odd3)
+            L.w[r] = make_uint4(I.w[r].y, I.w[r].z, I.w[r].w, 0u);
         const int src = (((two ? r & 1 : r) << c.gsh) + gi) << 2;
         const bool h = two && r >= 2;
         L.s[r] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, h ? I.s[1] : I.s[0])));
@@ -288,8 +297,8 @@ __device__ __forceinline__ void stage_x_all(const uint16_t *x, int K, uint4 *lds
 {
     const int tid = threadIdx.x;
     const int Kp = padded_k(K, BITS);
-    if (BITS == 2) {
-        const int npair = Kp >> 4; // a multiple of 256
+    if (BITS == 2 || BITS == 3) {
+        const int npair = Kp >> 4; // a multiple of 256 (3 bits: of 128)
         float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3));
         for (int base = 0; base < npair; base += THREADS * XU) {
             uint4 va[XU], vb[XU];
@@ -306,8 +315,12 @@ __device__ __forceinline__ void stage_x_all(const uint16_t *x, int K, uint4 *lds
 #pragma unroll
             for (int u = 0; u < XU; u++) {
                 const int pb = base + u * THREADS + tid;
-                if (((base + u * THREADS + tid) & ~63) < npair) // uniform over the wavefront: npair is a multiple of 64
-                    place_pair2(pb, va[u], vb[u], lds, sums);
+                if (((base + u * THREADS + tid) & ~63) < npair) { // uniform over the wavefront: npair is a multiple of 64
+                    if (BITS == 2)
+                        place_pair2(pb, va[u], vb[u], lds, sums);
+                    else
+                        place_pair3(pb, va[u], vb[u], lds, sums);
+                }
             }
         }
         return;
@@ -341,6 +354,8 @@ __device__ __forceinline__ void stage_share_x(const Share *sh, uint4 *xbuf)
     const int K = uni(sh->K);
     if (bits == 2)
         stage_x_all<2>(x, K, xbuf);
+    else if (bits == 3)
+        stage_x_all<3>(x, K, xbuf);
     else if (bits == 4)
         stage_x_all<4>(x, K, xbuf);
     else if (bits == 8)
@@ -464,9 +479,21 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                 const int g_hi = (e - e0 + 1) + (int)(avail * prefix / C);
                 if (b >= g_lo && b < g_hi && cost > 0) {
                     const long long idx = b - g_lo, n = g_hi - g_lo;
-                    sh.codes = bits == 2 ? d.codes2 : bits == 4 ? d.codes4 : bits == 8 ? d.codes8 : (const uint8_t *)d.w16;
-                    sh.scales = bits == 2 ? d.scales2 : bits == 4 ? d.scales4 : bits == 8 ? d.scales8 : (const float *)d.w16;
-                    sh.zeros = bits == 2 ? d.zeros2 : bits == 4 ? d.zeros4 : bits == 8 ? d.zeros8 : (const uint8_t *)d.w16;
+                    sh.codes = bits == 2   ? d.codes2
+                               : bits == 3 ? d.codes3
+                               : bits == 4 ? d.codes4
+                               : bits == 8 ? d.codes8
+                                           : (const uint8_t *)d.w16;
+                    sh.scales = bits == 2   ? d.scales2
+                                : bits == 3 ? d.scales3
+                                : bits == 4 ? d.scales4
+                                : bits == 8 ? d.scales8
+                                            : (const float *)d.w16;
+                    sh.zeros = bits == 2   ? d.zeros2
+                               : bits == 3 ? d.zeros3
+                               : bits == 4 ? d.zeros4
+                               : bits == 8 ? d.zeros8
+                                           : (const uint8_t *)d.w16;
                     sh.x = d.x;
                     sh.y = d.y;
                     sh.N = d.N;
@@ -601,6 +628,8 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
             expand(L[p], cc, T);
             if (cc.bits == 2)
                 compute<2>(cc.K, cc.j, T, xbuf, acc);
+            else if (cc.bits == 3)
+                compute<3>(cc.K, cc.j, T, xbuf, acc);
             else if (cc.bits == 4)
                 compute<4>(cc.K, cc.j, T, xbuf, acc);
             else if (cc.bits == 8)

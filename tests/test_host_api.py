@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol():
 def test_packed_sizes():
     assert fq.fq_packed_sizes(4096, 4096, 4) == (4096 * 4096 // 2, 4096 * 32 * 4, 4096 * 32)
     assert fq.fq_packed_sizes(11008, 4096, 8) == (11008 * 4096, 11008 * 32 * 4, 11008 * 32)
-    for args, code in [((4096, 4096, 3, 128), B.FQ_ERR_BITS), ((4096, 4000, 4, 128), B.FQ_ERR_SHAPE),
+    assert fq.fq_packed_sizes(256, 4096, 3) == (256 * 4096 * 3 // 8, 256 * 32 * 4, 256 * 32)
+    for args, code in [((4096, 4096, 5, 128), B.FQ_ERR_BITS), ((4096, 4000, 4, 128), B.FQ_ERR_SHAPE),
                        ((0, 4096, 4, 128), B.FQ_ERR_SHAPE), ((16, 256, 4, 64), B.FQ_ERR_SHAPE)]:
         with pytest.raises(fq.FlexqError) as ei:
             fq.fq_packed_sizes(*args)
@@ -54,7 +55,7 @@ def test_layer_and_linear_validation():
     assert L.fq_layer_create(ctypes.byref(h), 16, 200, 128) == B.FQ_ERR_SHAPE
     assert L.fq_layer_create(None, 16, 256, 128) == B.FQ_ERR_NULL
     assert L.fq_layer_create(ctypes.byref(h), 16, 256, 128) == B.FQ_OK
-    assert L.fq_layer_attach(h, 3, FAKE, FAKE, FAKE) == B.FQ_ERR_BITS
+    assert L.fq_layer_attach(h, 5, FAKE, FAKE, FAKE) == B.FQ_ERR_BITS
     assert L.fq_layer_attach(h, 4, None, FAKE, FAKE) == B.FQ_ERR_NULL
     assert L.fq_layer_attach(h, 4, FAKE, None, FAKE) == B.FQ_ERR_NULL
     assert L.fq_layer_attach(h, 4, FAKE + 8, FAKE, FAKE) == B.FQ_ERR_ALIGN
@@ -198,7 +199,7 @@ def test_sym_and_fake_quantize_validation():
     L, vp = fq.lib, ctypes.c_void_p
     ok = vp(FAKE)
     assert L.fq_quantize_sym(None, 4, 128, 4, 128, ok, ok, ok, None) == B.FQ_ERR_NULL
-    assert L.fq_quantize_sym(ok, 4, 128, 3, 128, ok, ok, ok, None) == B.FQ_ERR_BITS
+    assert L.fq_quantize_sym(ok, 4, 128, 5, 128, ok, ok, ok, None) == B.FQ_ERR_BITS
     assert L.fq_quantize_sym(ok, 4, 100, 4, 128, ok, ok, ok, None) == B.FQ_ERR_SHAPE
     assert L.fq_quantize_sym(vp(FAKE + 8), 4, 128, 4, 128, ok, ok, ok, None) == B.FQ_ERR_ALIGN
     assert L.fq_fake_quantize(ok, 4, 128, 1, 128, 0, ok, None) == B.FQ_ERR_BITS

@@ -200,7 +200,7 @@ def test_quantize_groups_are_independent():
 def test_quantize_rejects_bad_input():
     w = np.zeros((2, 256), dtype=np.float16)
     with pytest.raises(ValueError):
-        oracle.quantize(w, 3, G)
+        oracle.quantize(w, 5, G)
     with pytest.raises(ValueError):
         oracle.quantize(np.zeros((2, 200), dtype=np.float16), 4, G)
     w[1, 5] = np.inf
