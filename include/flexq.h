@@ -39,14 +39,15 @@
  *                                     code(4j+2) << 4 | code(4j+3) << 6
  *                                     (Table 1's lowest width; served by the decode kernels,
  *                                     M <= FQ_MAX_DECODE_M)
- *   codes, bits = 3 : u8  [N][K/32][12]  a block of 12 bytes holds 32 consecutive codes c(0..31):
- *                                     bytes 0..7 their low two bits in the 2-bit order above
- *                                     (byte j = sum over i < 4 of (c(4j+i) & 3) << 2i), bytes
- *                                     8..11 a little-endian word of their high bits, c(i) >> 2 at
- *                                     bit (i % 8) + 16 ((i / 8) % 2) + 8 (i / 16).  The paper runs
- *                                     3-bit models (Table 1, Sec. 5.1) without fixing a packing:
- *                                     this one is this library's, chosen so that a lane's 12 bytes
- *                                     unpack with the 2-bit path's masks.  Served at M = 1.
+ *   codes, bits = 3 : u8  [N][K/32][12]  a block of 12 bytes holds 32 consecutive codes c(0..31)
+ *                                     as three little-endian 32-bit words: word j holds c(10j) ..
+ *                                     c(10j+9) whole, c(10j + 5h + p) (h = 0, 1; p = 0 .. 4) in
+ *                                     bits 16h + 3p .. 16h + 3p + 2; bit 15 of word t is bit t
+ *                                     of c(30), bit 31 of word t is bit t of c(31).  The paper
+ *                                     runs 3-bit models (Table 1, Sec. 5.1) without fixing a
+ *                                     packing: this one is this library's, chosen so that ten
+ *                                     codes of a word unpack with one mask-and-merge and one
+ *                                     dot product per pair.  Served at M = 1.
  *   scales          : f32 [N][K/group]
  *   zeros           : u8  [N][K/group]
  *   bits = 16       : the fp16 weights W[N][K] themselves, no scales/zeros

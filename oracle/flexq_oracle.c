@@ -104,20 +104,27 @@ uint16_t orc_double_to_half(double d) { return double_to_half(d); }
 /* Packed codes: 8 bits one per byte; 4 bits two per byte, the even k in the low nibble; 2 bits
  * four per byte, k % 4 = 0 in bits 0..1 up to k % 4 = 3 in bits 6..7.  Rows follow each other.
  * 3 bits (the paper names no format for its 3-bit models; this is the repository's): a row is
- * K / 32 blocks of 12 bytes, block b holding k = 32 b .. 32 b + 31; bytes 0..7 of a block are the
- * two low bits of the 32 codes in the 2-bit order (byte j: codes 4j .. 4j+3); bytes 8..11 are one
- * little-endian 32-bit word of the codes' high bits, code i at bit
- * (i % 8) + 16 * ((i / 8) % 2) + 8 * (i / 16): codes 0..7, 16..23, 8..15, 24..31 from bit 0 up. */
-static int high_bit_place3(int i) { return (i & 7) + 16 * ((i >> 3) & 1) + 8 * (i >> 4); }
+ * K / 32 blocks of 12 bytes, block b holding k = 32 b .. 32 b + 31, read as three little-endian
+ * 32-bit words.  Word j holds codes 10 j .. 10 j + 9 whole: code 10 j + 5 h + p (h = 0, 1;
+ * p = 0 .. 4) in bits 16 h + 3 p .. 16 h + 3 p + 2.  That leaves bit 15 and bit 31 of every word:
+ * bit 15 of word t is bit t of code 30, bit 31 of word t is bit t of code 31. */
+static int bit_place3(int i, int t) /* where bit t of code i of a block sits among the block's 96 bits */
+{
+    if (i < 30)
+        return 32 * (i / 10) + 16 * ((i % 10) / 5) + 3 * (i % 5) + t;
+    return 32 * t + 15 + 16 * (i - 30);
+}
 
 static int code_of(const uint8_t *codes, int bits, long long row_elems, long long n, long long k)
 {
     if (bits == 3) {
         const uint8_t *blk = codes + n * (row_elems * 3 / 8) + (k / 32) * 12;
-        const int i = (int)(k % 32), hp = high_bit_place3(i);
-        const int lo = (blk[i / 4] >> (2 * (i & 3))) & 3;
-        const int hi = (blk[8 + hp / 8] >> (hp & 7)) & 1;
-        return lo | (hi << 2);
+        int q = 0;
+        for (int t = 0; t < 3; t++) {
+            const int place = bit_place3((int)(k % 32), t);
+            q |= ((blk[place / 8] >> (place % 8)) & 1) << t;
+        }
+        return q;
     }
     if (bits == 8)
         return codes[n * row_elems + k];
@@ -131,9 +138,10 @@ static void put_code(uint8_t *codes, int bits, long long row_elems, long long n,
 {
     if (bits == 3) {
         uint8_t *blk = codes + n * (row_elems * 3 / 8) + (k / 32) * 12;
-        const int i = (int)(k % 32), hp = high_bit_place3(i);
-        blk[i / 4] |= (uint8_t)((q & 3u) << (2 * (i & 3)));
-        blk[8 + hp / 8] |= (uint8_t)(((q >> 2) & 1u) << (hp & 7));
+        for (int t = 0; t < 3; t++) {
+            const int place = bit_place3((int)(k % 32), t);
+            blk[place / 8] |= (uint8_t)(((q >> t) & 1u) << (place % 8));
+        }
         return;
     }
     if (bits == 8)

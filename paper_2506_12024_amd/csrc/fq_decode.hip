@@ -126,7 +126,7 @@ struct Cut {
 // for bits from {2, 4} and 0.633 / 0.628 / 0.629 / 0.632 / 0.634 ms for {2, 4, 8}.
 constexpr int W4_COST = 230;     // per byte
 constexpr int W2_PER_MILLE = 730; // of the cost of a 4-bit group
-constexpr int W3_PER_MILLE = 850; // a 3-bit group: three quarters of the bytes, the same unpacking work
+constexpr int W3_PER_MILLE = 950; // a 3-bit group: three quarters of the bytes, a third more unpacking (0.511 ms against 0.539 ms for the 7B stack all at 3 or all at 4 bits)
 __device__ __forceinline__ long long entry_unit_cost(const FqLinearDesc &d, int bits)
 {
     const long long groups = d.K >> 7;

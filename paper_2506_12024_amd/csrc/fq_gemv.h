@@ -67,7 +67,7 @@ __device__ __forceinline__ float wave_sum_lane63(float v)
 //
 //   bits  codes/lane/slice  blocks/lane  block position
 //    2        64               8         ((b >> 9) * 8 + (b & 7)) * 64 + ((b >> 3) & 63), pairs of blocks interleaved
-//    3        32               4         as for 4 bits, pairs of blocks interleaved as for 2 bits
+//    3        32               4         as for 4 bits (the lane's 32 x regrouped into the pairs its three code words meet)
 //    4        32               4         ((b >> 8) * 4 + (b & 3)) * 64 + ((b >> 2) & 63)
 //    8        16               2         ((b >> 7) * 2 + (b & 1)) * 64 + ((b >> 1) & 63)
 //   16         8               1         b
@@ -133,44 +133,43 @@ __device__ __forceinline__ void place_pair2(int pb, uint4 va, uint4 vb, uint4 *l
         sums[pb >> 2] = make_float2(c, t);
 }
 
-// 3 bits.  A lane's 12 bytes hold 32 codes: two words of low bit pairs in the 2-bit order and one
-// word of high bits.  The low words are unpacked like 2-bit codes, so the x blocks of every 16 k
-// are interleaved as for 2 bits -- the high word's bits are laid out to pair up the same way (bit
-// i of its low half with bit i of its high half: codes i and 8 + i, after a shift by 8 codes 16 + i
-// and 24 + i).  A low bit pair keeps its place in its byte (offsets 1024 / 256 / 64 / 16 for
-// i % 4 = 0 .. 3), a high bit its place among eight (offset 1024 >> (i % 8), the bit itself worth
-// 1; the caller adds the high part four times).  A thread stages one pair of blocks; the two
-// threads of a lane's slice (32 k) add up its two sums: sum (off_low + 4 off_high)(k) x_k and sum x_k.
-__device__ __forceinline__ void place_pair3(int pb, uint4 va, uint4 vb, uint4 *lds, float2 *sums)
+// 3 bits.  A lane's 12 bytes = three words hold 32 codes: word j the codes 10 j + 5 h + p (h = 0,
+// 1: the word's halves; p = 0 .. 4: bits 3 p .. 3 p + 2 of the half), the words' bits 15 and 31 the
+// codes 30 and 31, bit j of each in word j.  The unpacking pairs the two halves of a word, so the
+// lane's 32 x are stored as 16 pairs in the order it meets them: pair 5 j + p = (x[10 j + p],
+// x[10 j + 5 + p]), pair 15 = (x[30], x[31]).  A whole code keeps its place in its half, which
+// fixes its offset: 1024 / 128 / 16 for p = 0 / 1 / 2 and again, after a shift by 9 bits, 1024 /
+// 128 for p = 3 / 4; a bit of the last two codes is read at bit 6 after that shift, under 16 / 32
+// / 64 in words 0 / 1 / 2, where it is worth 1 / 2 / 4: offset 112 in all.
+__device__ __forceinline__ constexpr float offset3(int i)
 {
-    float p[4] = {0.f, 0.f, 0.f, 0.f}; // sums of the x whose code sits at position i % 4 of its byte
-    float c_high = 0.f;                // sum of 2^-(i % 8) x_k
-    const uint32_t w[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+    return i >= 30 ? 112.0f : (i % 5 == 0 || i % 5 == 3) ? 1024.0f : (i % 5 == 1 || i % 5 == 4) ? 128.0f : 16.0f;
+}
+
+// Places the x of lane slice ls (k = 32 ls .. 32 ls + 31; v = its four blocks as loaded, zeros
+// past K) and the slice's two sums: sum offset(k) x_k and sum x_k.
+__device__ __forceinline__ void place_slice3(int ls, const uint4 (&v)[4], uint4 *lds, float2 *sums)
+{
+    const uint32_t w[16] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w,
+                            v[2].x, v[2].y, v[2].z, v[2].w, v[3].x, v[3].y, v[3].z, v[3].w};
+    float c = 0.f, t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const half2_t h = __builtin_bit_cast(half2_t, w[i]); // halves 2 i, 2 i + 1 of their block (k % 8 = 2 (i % 4), + 1)
-        p[(2 * i) & 3] += (float)h[0];
-        p[(2 * i + 1) & 3] += (float)h[1];
-        c_high += (float)h[0] * (1.0f / (float)(1 << ((2 * i) & 7))) + (float)h[1] * (1.0f / (float)(1 << ((2 * i + 1) & 7)));
+    for (int d = 0; d < 16; d++) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[d]); // x[2 d], x[2 d + 1]
+        c += offset3(2 * d) * (float)h[0] + offset3(2 * d + 1) * (float)h[1];
+        t += (float)h[0] + (float)h[1];
     }
-    uint4 o0, o1;
-    o0.x = __builtin_amdgcn_perm(vb.x, va.x, 0x05040100u); // (A0, B0)
-    o0.y = __builtin_amdgcn_perm(vb.x, va.x, 0x07060302u); // (A1, B1)
-    o0.z = __builtin_amdgcn_perm(vb.y, va.y, 0x05040100u); // (A2, B2)
-    o0.w = __builtin_amdgcn_perm(vb.y, va.y, 0x07060302u); // (A3, B3)
-    o1.x = __builtin_amdgcn_perm(vb.z, va.z, 0x05040100u); // (A4, B4)
-    o1.y = __builtin_amdgcn_perm(vb.z, va.z, 0x07060302u);
-    o1.z = __builtin_amdgcn_perm(vb.w, va.w, 0x05040100u);
-    o1.w = __builtin_amdgcn_perm(vb.w, va.w, 0x07060302u); // (A7, B7)
-    lds[block_pos<3>(2 * pb)] = o0;
-    lds[block_pos<3>(2 * pb + 1)] = o1;
-    float c = 1024.0f * p[0] + 256.0f * p[1] + 64.0f * p[2] + 16.0f * p[3] + 4096.0f * c_high;
-    float t = (p[0] + p[1]) + (p[2] + p[3]);
-    // slice = 2 pairs = 2 consecutive threads
-    c += dpp_take<0xB1, 0xF>(c);
-    t += dpp_take<0xB1, 0xF>(t);
-    if ((pb & 1) == 0)
-        sums[pb >> 1] = make_float2(c, t);
+    uint32_t o[16];
+#pragma unroll
+    for (int u = 0; u < 16; u++) {
+        const int a = u < 15 ? 10 * (u / 5) + u % 5 : 30, b = u < 15 ? a + 5 : 31; // the pair (x[a], x[b])
+        const uint32_t sel = ((b & 1) ? 0x07060000u : 0x05040000u) | ((a & 1) ? 0x0302u : 0x0100u);
+        o[u] = __builtin_amdgcn_perm(w[b >> 1], w[a >> 1], sel);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        lds[((ls >> 6) * 4 + i) * 64 + (ls & 63)] = make_uint4(o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]);
+    sums[ls] = make_float2(c, t);
 }
 
 // Places block b (k = 8 b .. 8 b + 7; v as loaded, zeros past K) for 4, 8 or 16 bits and the sums
@@ -223,15 +222,14 @@ __device__ __forceinline__ void stage_x(const uint16_t *x, int K, uint4 *lds)
 {
     const int Kp = padded_k(K, BITS);
     if (BITS == 3) {
-        const int npair = Kp >> 4; // a multiple of 128
+        const int nls = Kp >> 5; // lane slices of 32 k: a thread stages a whole one
         float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3)); // per lane slice: (sum off(k) x, sum x)
-        for (int pb = threadIdx.x % THREADS; pb < npair; pb += THREADS) {
-            uint4 va = make_uint4(0, 0, 0, 0), vb = make_uint4(0, 0, 0, 0);
-            if (pb * 16 < K) {
-                va = load16_global(x + (size_t)pb * 16);
-                vb = load16_global(x + (size_t)pb * 16 + 8);
-            }
-            place_pair3(pb, va, vb, lds, sums);
+        for (int ls = threadIdx.x % THREADS; ls < nls; ls += THREADS) {
+            uint4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) // K is a multiple of 128: all four blocks or none
+                v[i] = ls * 32 < K ? load16_global(x + (size_t)ls * 32 + 8 * i) : make_uint4(0, 0, 0, 0);
+            place_slice3(ls, v, lds, sums);
         }
         return;
     }
@@ -369,43 +367,33 @@ __device__ __forceinline__ void compute(int K, int j, const Loaded &L, const uin
             acc[r] += L.s[r] * (a[r] - cs.x - (float)L.z[r] * cs.y);
     } else if (BITS == 3) {
         const float2 *sums = reinterpret_cast<const float2 *>(lds + (padded_k(K, 3) >> 3));
-        // exponent patterns under which bit i of a half reads as (1024 >> i) + bit: the low bit pairs
-        // sit at bits 0, 2, 4, 6 (m[0], m[2], m[4], m[6]: 1024 + q, 256 + q, 64 + q, 16 + q as at 2
-        // bits), the high bits at bits 0 .. 7
-        uint32_t m[8] = {0x64006400u, 0x60006000u, 0x5C005C00u, 0x58005800u,
-                         0x54005400u, 0x50005000u, 0x4C004C00u, 0x48004800u};
-        asm volatile("" : "+v"(m[0]), "+v"(m[1]), "+v"(m[2]), "+v"(m[3]), "+v"(m[4]), "+v"(m[5]), "+v"(m[6]), "+v"(m[7]));
+        // exponent patterns under which a field of a half reads as offset + code: 1024 for a field
+        // at bit 0, 128 at bit 3, 16 at bit 6; a single bit at bit 6 reads as 32 + 2 b under the
+        // pattern of 32 and as 64 + 4 b under that of 64 (kept in VGPRs as for 4 bits)
+        uint32_t m0 = 0x64006400u, m1 = 0x58005800u, m2 = 0x4C004C00u, m3 = 0x50005000u, m4 = 0x54005400u;
+        asm volatile("" : "+v"(m0), "+v"(m1), "+v"(m2), "+v"(m3), "+v"(m4));
         uint4 xb[4];
 #pragma unroll
         for (int i = 0; i < 4; i++)
             xb[i] = lds[(j * 4 + i) * 64 + lane];
-        const float2 cs = sums[j * 64 + lane]; // (sum (off_low + 4 off_high)(k) x, sum x) over the lane's 32 k
+        const uint32_t xx[16] = {xb[0].x, xb[0].y, xb[0].z, xb[0].w, xb[1].x, xb[1].y, xb[1].z, xb[1].w,
+                                 xb[2].x, xb[2].y, xb[2].z, xb[2].w, xb[3].x, xb[3].y, xb[3].z, xb[3].w};
+        const float2 cs = sums[j * 64 + lane]; // (sum offset(k) x, sum x) over the lane's 32 k
 #pragma unroll
         for (int r = 0; r < ROWS_PER_WAVE; r++) {
-            const uint32_t lw[2] = {L.w[r].x, L.w[r].y};
-            const uint32_t hw[2] = {L.w[r].z, L.w[r].z >> 8};
-            float a_low = 0.0f, a_high = 0.0f;
+            const uint32_t ww[3] = {L.w[r].x, L.w[r].y, L.w[r].z};
+            float a = 0.0f;
 #pragma unroll
-            for (int i = 0; i < 2; i++) { // 16 codes: x blocks 2 i (pairs 0 .. 3) and 2 i + 1 (pairs 4 .. 7)
-                const uint32_t v = lw[i], v8 = v >> 8, h = hw[i];
-                a_low = dot2((v & 0x00030003u) | m[0], xb[2 * i].x, a_low);      // codes 0, 8
-                a_low = dot2((v & 0x000C000Cu) | m[2], xb[2 * i].y, a_low);      // codes 1, 9
-                a_low = dot2((v & 0x00300030u) | m[4], xb[2 * i].z, a_low);      // codes 2, 10
-                a_low = dot2((v & 0x00C000C0u) | m[6], xb[2 * i].w, a_low);      // codes 3, 11
-                a_low = dot2((v8 & 0x00030003u) | m[0], xb[2 * i + 1].x, a_low); // codes 4, 12
-                a_low = dot2((v8 & 0x000C000Cu) | m[2], xb[2 * i + 1].y, a_low);
-                a_low = dot2((v8 & 0x00300030u) | m[4], xb[2 * i + 1].z, a_low);
-                a_low = dot2((v8 & 0x00C000C0u) | m[6], xb[2 * i + 1].w, a_low); // codes 7, 15
-                a_high = dot2((h & 0x00010001u) | m[0], xb[2 * i].x, a_high);
-                a_high = dot2((h & 0x00020002u) | m[1], xb[2 * i].y, a_high);
-                a_high = dot2((h & 0x00040004u) | m[2], xb[2 * i].z, a_high);
-                a_high = dot2((h & 0x00080008u) | m[3], xb[2 * i].w, a_high);
-                a_high = dot2((h & 0x00100010u) | m[4], xb[2 * i + 1].x, a_high);
-                a_high = dot2((h & 0x00200020u) | m[5], xb[2 * i + 1].y, a_high);
-                a_high = dot2((h & 0x00400040u) | m[6], xb[2 * i + 1].z, a_high);
-                a_high = dot2((h & 0x00800080u) | m[7], xb[2 * i + 1].w, a_high);
+            for (int i = 0; i < 3; i++) {
+                const uint32_t v = ww[i], v9 = v >> 9;
+                a = dot2((v & 0x00070007u) | m0, xx[5 * i + 0], a);  // codes 10 i + 0, 10 i + 5
+                a = dot2((v & 0x00380038u) | m1, xx[5 * i + 1], a);  // codes 10 i + 1, 10 i + 6
+                a = dot2((v & 0x01C001C0u) | m2, xx[5 * i + 2], a);  // codes 10 i + 2, 10 i + 7
+                a = dot2((v9 & 0x00070007u) | m0, xx[5 * i + 3], a); // codes 10 i + 3, 10 i + 8
+                a = dot2((v9 & 0x00380038u) | m1, xx[5 * i + 4], a); // codes 10 i + 4, 10 i + 9
+                a = dot2((v9 & 0x00400040u) | (i == 0 ? m2 : i == 1 ? m3 : m4), xx[15], a); // bit i of codes 30, 31
             }
-            const float part = a_low + 4.0f * a_high - cs.x - (float)L.z[r] * cs.y;
+            const float part = a - cs.x - (float)L.z[r] * cs.y;
             acc[r] += L.s[r] * part;
         }
     } else if (BITS == 4) {

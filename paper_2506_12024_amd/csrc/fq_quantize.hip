@@ -5,7 +5,8 @@
 // one row: every lane loads 8 halves (one 128-bit load, fully coalesced: a
 // wavefront reads 1 KiB = 4 groups), the segment reduces min/max with DPP
 // row shifts, every lane then derives the same s and z and writes its 8 codes
-// with one 16-bit (2-bit codes), 32-bit (4-bit codes) or 64-bit (8-bit codes) store.
+// with one 16-bit (2-bit codes), 32-bit (4-bit codes) or 64-bit (8-bit codes) store (3-bit
+// codes: four lanes put a block of three words together).
 //
 // The arithmetic is pinned so that codes, scales and zeros are bit-exact
 // against a binary32 evaluation with one rounding per operation: IEEE
@@ -112,19 +113,35 @@ __global__ __launch_bounds__(256) void quantize_kernel(const half8 *__restrict__
             word |= q[i] << (2 * i); // byte j = code(4j) | code(4j+1) << 2 | code(4j+2) << 4 | code(4j+3) << 6
         reinterpret_cast<uint16_t *>(codes)[seg * 16 + sub] = (uint16_t)word;
     } else if (BITS == 3) {
-        // a block of 12 bytes holds 32 codes, this lane's 8 are its quarter t: two bytes of low bit
-        // pairs (the 2-bit order), one byte of high bits -- quarters 0, 2, 1, 3 from the low end
-        // of the block's high word
+        // A block of 12 bytes = three words holds 32 codes: word j the codes 10 j .. 10 j + 9 whole
+        // (code 10 j + 5 h + p in bits 16 h + 3 p .. + 2), the words' bits 15 and 31 the three bits
+        // of codes 30 and 31.  The four lanes of a block place their eight codes each, the words
+        // are OR-ed across the four, and lane t < 3 stores word t.
         const int t = sub & 3;
-        uint32_t low = 0, high = 0;
+        uint32_t c[3] = {0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            low |= (q[i] & 3u) << (2 * i);
-            high |= (q[i] >> 2) << i;
+        for (int e = 0; e < 8; e++) {
+            const int i = 8 * t + e;
+            if (i < 30) {
+                const int j = i / 10, r = i - 10 * j;
+                const uint32_t v = q[e] << (r >= 5 ? 16 + 3 * (r - 5) : 3 * r);
+#pragma unroll
+                for (int jj = 0; jj < 3; jj++)
+                    c[jj] |= j == jj ? v : 0u;
+            } else {
+                const int sh = 15 + 16 * (i - 30);
+#pragma unroll
+                for (int jj = 0; jj < 3; jj++)
+                    c[jj] |= ((q[e] >> jj) & 1u) << sh;
+            }
         }
-        uint8_t *blk = codes + (seg * 4 + (sub >> 2)) * 12;
-        *reinterpret_cast<uint16_t *>(blk + 2 * t) = (uint16_t)low;
-        blk[8 + ((t & 1) << 1) + (t >> 1)] = (uint8_t)high;
+#pragma unroll
+        for (int jj = 0; jj < 3; jj++) {
+            c[jj] |= (uint32_t)__shfl_xor((int)c[jj], 1, 64);
+            c[jj] |= (uint32_t)__shfl_xor((int)c[jj], 2, 64);
+        }
+        if (t < 3)
+            reinterpret_cast<uint32_t *>(codes)[(seg * 4 + (sub >> 2)) * 3 + t] = t == 0 ? c[0] : t == 1 ? c[1] : c[2];
     } else if (BITS == 4) {
         uint32_t word = 0;
 #pragma unroll

@@ -93,7 +93,7 @@ __device__ __forceinline__ long long group_cost(const FqLinearDesc &d, int bits)
     if (bits == 2)
         return d.codes2 ? 64 * 230 * 730 / 1000 : 0;
     if (bits == 3)
-        return d.codes3 ? 64 * 230 * 850 / 1000 : 0;
+        return d.codes3 ? 64 * 230 * 950 / 1000 : 0;
     if (bits == 4)
         return d.codes4 ? 64 * 230 : 0;
     if (bits == 8)
@@ -297,8 +297,20 @@ __device__ __forceinline__ void stage_x_all(const uint16_t *x, int K, uint4 *lds
 {
     const int tid = threadIdx.x;
     const int Kp = padded_k(K, BITS);
-    if (BITS == 2 || BITS == 3) {
-        const int npair = Kp >> 4; // a multiple of 256 (3 bits: of 128)
+    if (BITS == 3) {
+        const int nls = Kp >> 5; // lane slices of 32 k, one per thread and trip
+        float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3));
+        for (int ls = tid; ls < nls; ls += THREADS) {
+            uint4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                v[i] = ls * 32 < K ? load16_coherent(x + (size_t)ls * 32 + 8 * i) : make_uint4(0, 0, 0, 0);
+            place_slice3(ls, v, lds, sums);
+        }
+        return;
+    }
+    if (BITS == 2) {
+        const int npair = Kp >> 4; // a multiple of 256
         float2 *sums = reinterpret_cast<float2 *>(lds + (Kp >> 3));
         for (int base = 0; base < npair; base += THREADS * XU) {
             uint4 va[XU], vb[XU];
@@ -315,12 +327,8 @@ __device__ __forceinline__ void stage_x_all(const uint16_t *x, int K, uint4 *lds
 #pragma unroll
             for (int u = 0; u < XU; u++) {
                 const int pb = base + u * THREADS + tid;
-                if (((base + u * THREADS + tid) & ~63) < npair) { // uniform over the wavefront: npair is a multiple of 64
-                    if (BITS == 2)
-                        place_pair2(pb, va[u], vb[u], lds, sums);
-                    else
-                        place_pair3(pb, va[u], vb[u], lds, sums);
-                }
+                if (((base + u * THREADS + tid) & ~63) < npair) // uniform over the wavefront: npair is a multiple of 64
+                    place_pair2(pb, va[u], vb[u], lds, sums);
             }
         }
         return;

@@ -1,9 +1,9 @@
 """Pins for the 3-bit path of the CPU oracle (Table 1 lists 2-, 3- and 4-bit models; Sec. 2.2
 Eq. (2) and (3) with n = 3): hand-worked cases, the byte layout (blocks of 12 bytes for 32 codes:
-8 bytes of low bit pairs, one 32-bit word of high bits), invariants, brute force, and agreement
-with routines of the oracle that are written separately (the quantize-dequantize routine) or that a
-library provides (integer matmul).  The unpacking below is written from the statement of the
-format, not taken from the oracle."""
+three little-endian words of ten whole codes each, the two last codes spread over the words' bits
+15 and 31), invariants, brute force, and agreement with routines of the oracle that are written
+separately (the quantize-dequantize routine) or that a library provides (integer matmul).  The
+unpacking below is written from the statement of the format, not taken from the oracle."""
 import os
 
 import numpy as np
@@ -16,9 +16,17 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 G = 128
 
 
-def _high_bit_place(i):
-    # codes 0..7, 16..23, 8..15, 24..31 of a block from bit 0 of the word up
-    return (i % 8) + 16 * ((i // 8) % 2) + 8 * (i // 16)
+def _bit_place(i, t):
+    """Bit t of code i of a block, counted over the block's 96 bits (byte b holds bits 8 b .. 8 b + 7)."""
+    if i < 30:
+        word, r = divmod(i, 10)
+        half, p = divmod(r, 5)
+        return 32 * word + 16 * half + 3 * p + t
+    return 32 * t + 15 + 16 * (i - 30)
+
+
+def _block_int(blk):
+    return sum(int(b) << (8 * j) for j, b in enumerate(blk))
 
 
 def _unpack3(codes):
@@ -26,13 +34,11 @@ def _unpack3(codes):
     rows, nbytes = codes.shape
     K = nbytes * 8 // 3
     out = np.zeros((rows, K), dtype=np.int64)
-    blocks = codes.reshape(rows, K // 32, 12)
-    words = (blocks[..., 8].astype(np.uint32) | (blocks[..., 9].astype(np.uint32) << 8) |
-             (blocks[..., 10].astype(np.uint32) << 16) | (blocks[..., 11].astype(np.uint32) << 24))
+    blocks = codes.reshape(rows, K // 32, 12).astype(np.int64)
     for i in range(32):
-        lo = (blocks[..., i // 4] >> (2 * (i % 4))) & 3
-        hi = (words >> _high_bit_place(i)) & 1
-        out[:, i::32] = lo.astype(np.int64) + 4 * hi.astype(np.int64)
+        for t in range(3):
+            place = _bit_place(i, t)
+            out[:, i::32] += ((blocks[..., place // 8] >> (place % 8)) & 1) << t
     return out
 
 
@@ -65,20 +71,27 @@ def test_quantize_3bit_hand_cases(case):
 
 def test_pack_3bit_bytes_hand_case():
     # s = 1, z = 0 (a 7 elsewhere in the group fixes the range), so the code is the value.
-    # Code 4 (low pair 0, high bit 1) at k = 1, 9, 18, 27 and code 3 (low pair 3, high bit 0) at
-    # k = 5.  Low plane: only k = 5 has low bits, byte 1 = 3 << 2 = 0x0C.  High word: code 1 ->
-    # bit 1 (byte 8 = 0x02); code 9 -> bit 16 + 1 (byte 10 = 0x02); code 18 -> bit 8 + 2 (byte 9 =
-    # 0x04); code 27 -> bit 24 + 3 (byte 11 = 0x08).
+    # Block 0: code 4 (bit 2 alone) at k = 1, 9, 18, 27 and code 3 (bits 0 and 1) at k = 5.
+    #   k = 1:  word 0, low half, place 1: bits 3..5, bit 2 of the code is bit 5       -> byte 0 = 0x20
+    #   k = 5:  word 0, high half, place 0: bits 16..18, the code's bits 0, 1          -> byte 2 = 0x03
+    #   k = 9:  word 0, high half, place 4: bits 28..30, bit 30                        -> byte 3 = 0x40
+    #   k = 18: word 1, high half, place 3: bits 25..27, bit 27                        -> byte 7 = 0x08
+    #   k = 27: word 2, high half, place 2: bits 22..24, bit 24                        -> byte 11 = 0x01
+    # Block 1: code 5 (bits 0, 2) at its place 30: bit 15 of words 0 and 2 -> bytes 1 and 9 = 0x80;
+    #   code 6 (bits 1, 2) at its place 31: bit 31 of words 1 and 2 -> bytes 7 and 11 = 0x80.
+    # Block 3: the 7 at its place 4: word 0, low half, place 4: bits 12..14 -> byte 1 = 0x70.
     w = np.zeros((1, G), dtype=np.float16)
     w[0, [1, 9, 18, 27]] = 4
     w[0, 5] = 3
+    w[0, 32 + 30] = 5
+    w[0, 32 + 31] = 6
     w[0, 100] = 7
     codes, scales, zeros = oracle.quantize(w, 3, G)
     assert scales[0, 0] == 1.0 and zeros[0, 0] == 0
-    assert list(codes[0, :12]) == [0x00, 0x0C, 0, 0, 0, 0, 0, 0, 0x02, 0x04, 0x02, 0x08]
-    # block 3 (k = 96 .. 127) holds the 7 at its place 4: low pair 3 in byte 1, high bit at bit 4
-    assert list(codes[0, 36:48]) == [0x00, 0x03, 0, 0, 0, 0, 0, 0, 0x10, 0, 0, 0]
-    assert not codes[0, 12:36].any()
+    assert list(codes[0, :12]) == [0x20, 0, 0x03, 0x40, 0, 0, 0, 0x08, 0, 0, 0, 0x01]
+    assert list(codes[0, 12:24]) == [0, 0x80, 0, 0, 0, 0, 0, 0x80, 0, 0x80, 0, 0x80]
+    assert list(codes[0, 36:48]) == [0, 0x70, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0]
+    assert not codes[0, 24:36].any()
 
 
 def test_pack_3bit_every_code_at_every_position():
@@ -89,13 +102,15 @@ def test_pack_3bit_every_code_at_every_position():
             k = 32 + pos
             w[1, k] = c
             codes, _, _ = oracle.quantize(w, 3, G)
-            blk = codes[1, 12:24].astype(np.int64)
-            assert (blk[pos // 4] >> (2 * (pos % 4))) & 3 == c & 3
-            word = int(blk[8]) | int(blk[9]) << 8 | int(blk[10]) << 16 | int(blk[11]) << 24
-            assert word == (c >> 2) << _high_bit_place(pos)
-            assert sum(int(b) for b in blk[:8]) == (c & 3) << (2 * (pos % 4))
+            expect = sum(((c >> t) & 1) << _bit_place(pos, t) for t in range(3))
+            assert _block_int(codes[1, 12:24]) == expect
             assert not codes[0, 12:24].any()  # the other row is untouched: rows follow each other
-    assert sorted(_high_bit_place(i) for i in range(32)) == list(range(32))
+    # every bit of a block belongs to exactly one (code, bit)
+    assert sorted(_bit_place(i, t) for i in range(32) for t in range(3)) == list(range(96))
+    # a whole code keeps its three bits together, inside one 16-bit half of one word
+    for i in range(30):
+        a = _bit_place(i, 0)
+        assert [_bit_place(i, t) for t in range(3)] == [a, a + 1, a + 2] and a // 16 == (a + 2) // 16
 
 
 def test_quantize_3bit_invariants_random():
