@@ -180,7 +180,9 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *              (they would share these, and they write the same ys)
  *   bits_dev   device, int32 [count], each 2, 3, 4, 8 or 16 and attached to its layer;
  *              an entry whose value is anything else (or 3 in a plan with M > 1) is skipped
- *              by the kernel and its y is left untouched.  A large plan with M > 1 whose layers carry
+ *              by the kernel and its y is left untouched.  Such a run sets bit 0 of the plan's
+ *              flags, a word in the workspace that stays set and that fq_plan_status reports
+ *              (gave_up is always 0 for these plans).  A large plan with M > 1 whose layers carry
  *              2-bit copies runs as two kernels (the streaming batch kernel takes 4, 8 and
  *              16 bits; the entries that are at 2 bits follow on the register-fed one)
  */
@@ -212,7 +214,7 @@ int fq_plan_destroy(fq_plan *plan);
  * another kernel holds compute units the waits may run out.  A wait is bounded (about a second
  * by default, fq_plan_set_wait_limit sets the number of polls): a launch that gives up leaves y
  * incomplete, every workgroup still exits, the barrier's counters are put back, and the next
- * launch starts clean.  fq_plan_status waits for `stream` and reports
+ * launch starts clean.  fq_plan_status (for either kind of plan) waits for `stream` and reports
  *   gave_up  launches of this plan that gave up so far (never reset)
  *   flags    bit 0: an entry's bit-width was not 2, 3, 4, 8 or 16 or had no copy attached (its y was
  *            left untouched); bit 1: a workgroup's share of a stage exceeded 4096 rows (skipped)

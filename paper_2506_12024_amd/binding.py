@@ -227,6 +227,13 @@ class Plan:
     def run(self, bits_dev, stream=None):
         _check(lib.fq_plan_run(self.handle, _ptr(bits_dev), _stream(stream)))
 
+    def status(self, stream=None):
+        """Waits for ``stream``; returns (launches that gave up, flags) -- flags bit 0: in some run an
+        entry's bit-width could not be served (not attached, or no kernel for it at this M)."""
+        g, f = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(lib.fq_plan_status(self.handle, ctypes.byref(g), ctypes.byref(f), _stream(stream)))
+        return int(g.value), int(f.value)
+
     def destroy(self):
         if self.handle is not None:
             _check(lib.fq_plan_destroy(self.handle))
@@ -262,12 +269,6 @@ class StagedPlan(Plan):
 
     def set_wait_limit(self, polls: int):
         _check(lib.fq_plan_set_wait_limit(self.handle, polls))
-
-    def status(self, stream=None):
-        """Returns (gave_up, flags) after waiting for the stream."""
-        g, f = ctypes.c_int32(), ctypes.c_int32()
-        _check(lib.fq_plan_status(self.handle, ctypes.byref(g), ctypes.byref(f), _stream(stream)))
-        return g.value, f.value
 
 
 def fq_stream_read(src, nbytes: int, sink, stream=None):

@@ -275,7 +275,7 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
         if (M > 1 && bits == 2 && rows == 16) // the K-split kernel takes 4, 8 and 16 bits
             rows = 64;
         const int tiles = (layer->N + rows - 1) / rows;
-        e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, (hipStream_t)stream)
+        e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, nullptr, (hipStream_t)stream)
                    : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, nullptr, nullptr, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
@@ -406,7 +406,8 @@ hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, in
                           const int32_t *bits_dev, hipStream_t stream)
 {
     hipError_t e = g.M == 1
-        ? fq_launch_decode(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.max_K, g.M, stream)
+        ? fq_launch_decode(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.max_K, g.M,
+                           queue_dev ? queue_dev + FQ_Q_FLAGS : nullptr, stream)
         : fq_launch_skinny(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.M, queue_dev,
                            order_dev, stream);
     if (e == hipSuccess && g.total_tiles2 > 0)
@@ -569,10 +570,10 @@ int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *
 {
     if (!plan || plan->magic != PLAN_MAGIC)
         return fail(FQ_ERR_NULL, "fq_plan_status: plan is NULL or not valid");
-    if (plan->n_stages < 1)
-        return fail(FQ_ERR_SHAPE, "fq_plan_status: not a stage-ordered plan");
     int32_t words[2] = {0, 0}; // the sticky count of launches that gave up, then the flags
-    hipError_t e = hipMemcpyAsync(words, plan->sync_dev + 32 * 32 + 1, sizeof words, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    hipError_t e = plan->n_stages < 1 // a plan of independent entries has no waits to give up
+        ? hipMemcpyAsync(words + 1, plan->queue_dev + FQ_Q_FLAGS, sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)stream)
+        : hipMemcpyAsync(words, plan->sync_dev + 32 * 32 + 1, sizeof words, hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess)
         e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess)

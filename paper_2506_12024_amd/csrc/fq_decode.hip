@@ -171,7 +171,7 @@ __device__ __forceinline__ long long block_scan(long long v, long long *tmp, lon
 
 // Boundaries of this workgroup's slice.  Every thread returns the same values.
 __device__ __forceinline__ void partition(const FqLinearDesc *table, const int32_t *bits_dev, int count,
-                                          Cut &lo, Cut &hi)
+                                          Cut &lo, Cut &hi, int *flags)
 {
     __shared__ long long tmp[WAVES];
     __shared__ Cut cuts[2];
@@ -180,8 +180,11 @@ __device__ __forceinline__ void partition(const FqLinearDesc *table, const int32
     for (int base = 0; base < count; base += WG_THREADS) {
         const int e = base + threadIdx.x;
         long long c = 0;
-        if (e < count)
+        if (e < count) {
             c = entry_unit_cost(table[e], bits_dev[e]) * ((table[e].N + 15) >> 4);
+            if (c == 0 && flags && blockIdx.x == 0) // no such width, or no copy of it: nobody runs this entry
+                *flags = 1;
+        }
         long long chunk;
         block_scan(c, tmp, chunk);
         C += chunk;
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
                                                                const FqLinearDesc *__restrict__ table,
                                                                const int32_t *__restrict__ bits_dev,
                                                                int count, int total_tiles,
-                                                               int tile_rows)
+                                                               int tile_rows, int *flags)
 {
     extern __shared__ uint4 lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // scalar: keeps row math on the SALU
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
         return;
     }
     Cut lo, hi;
-    partition(table, bits_dev, count, lo, hi);
+    partition(table, bits_dev, count, lo, hi, flags);
     for (int e = lo.e; e < count && e <= hi.e; e++) {
         const FqLinearDesc *dp = &table[e];
         const int bits = bits_dev[e];
@@ -324,7 +327,7 @@ int fq_decode_tile_rows(long long total_rows, int max_K, int M)
 
 hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int max_K, int M, hipStream_t stream)
+                            int total_tiles, int tile_rows, int max_K, int M, int *flags, hipStream_t stream)
 {
     (void)M;
     if (total_tiles <= 0)
@@ -348,11 +351,11 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
     const int grid = single ? (total_tiles < cap ? total_tiles : cap) : plan_grid;
     if (single) {
         decode_m1_kernel<true><<<grid, WG_THREADS, lds, stream>>>(*single, bits_host, nullptr,
-                                                                  nullptr, 1, total_tiles, tile_rows);
+                                                                  nullptr, 1, total_tiles, tile_rows, nullptr);
     } else {
         FqLinearDesc none = {};
         decode_m1_kernel<false><<<grid, WG_THREADS, lds, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                   count, total_tiles, tile_rows);
+                                                                   count, total_tiles, tile_rows, flags);
     }
     return hipGetLastError();
 }

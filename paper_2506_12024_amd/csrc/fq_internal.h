@@ -67,9 +67,10 @@ hipError_t fq_launch_entropy_kl_f16(const uint16_t *a, const uint16_t *b, int R,
 
 // Skinny (decode) linears.  `descs` is a device table of `count` entries when
 // `single` is null, else the one entry is passed by value and bits_host applies.
+// `flags` (plans; may be null): a device word that gets bit 0 set when an entry could not be served.
 hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int max_K, int M, hipStream_t stream);
+                            int total_tiles, int tile_rows, int max_K, int M, int *flags, hipStream_t stream);
 // Rows per tile (multiple of 16) for a launch that covers `total_rows` output rows.
 int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 
@@ -101,6 +102,9 @@ hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t 
 // then what plan_order_kernel leaves for the launches that follow it: tiles and entries of the
 // streaming kernel's list, tiles and entries of the second pass's list.
 constexpr int FQ_Q_DONE = 8, FQ_Q_TILES = 9, FQ_Q_ENTRIES = 10;
+// ... and, apart from those, a sticky word of flags that fq_plan_status reports: bit 0 = an entry's
+// bit-width was not one the plan serves, or had no copy attached, in some run (its y was left untouched)
+constexpr int FQ_Q_FLAGS = 16;
 
 // Device-resident state of the precision scheduler (ring of PPLE values follows the header).
 struct FqSchedState {

@@ -532,7 +532,7 @@ template <bool SINGLE, int MT>
 __global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLinearDesc single, int bits_host,
                                                                       const FqLinearDesc *__restrict__ table,
                                                                       const int32_t *__restrict__ bits_dev,
-                                                                      int count, int total_tiles, int M)
+                                                                      int count, int total_tiles, int M, int *flags)
 {
     typedef Chunk<MT, true> C;
     __shared__ uint4 lds_x[WAVES][(C::KC / 8) * 16 * MT];
@@ -559,8 +559,11 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLi
         d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
         d.scales = bits == 4 ? dp->scales4 : dp->scales8;
         d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
-        if (!d.codes)
-            continue; // uniform over the workgroup
+        if (!d.codes) { // uniform over the workgroup
+            if (flags && threadIdx.x == 0)
+                *flags = 1; // no such width here, or no copy of it: nobody runs this entry
+            continue;
+        }
         const int row0 = (tile - dp->tile_begin) * 16;
         if (bits == 4)
             run_tile_sk<4, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
@@ -578,7 +581,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
                                                                    const int32_t *__restrict__ bits_dev,
                                                                    int count, int total_tiles, int M,
                                                                    const int *__restrict__ queue,
-                                                                   const int2 *__restrict__ list)
+                                                                   const int2 *__restrict__ list, int *flags)
 {
     // `list` (with `queue`): the pass over the 2-bit entries of a plan whose other entries the
     // streaming kernel has run, as listed for this launch's bit-widths by plan_order_kernel:
@@ -625,8 +628,11 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
                                : nullptr;
         d.scales = bits == 2 ? dp->scales2 : bits == 4 ? dp->scales4 : dp->scales8;
         d.zeros = bits == 2 ? dp->zeros2 : bits == 4 ? dp->zeros4 : dp->zeros8;
-        if (!d.codes)
-            continue; // uniform over the workgroup
+        if (!d.codes) { // uniform over the workgroup
+            if (flags && threadIdx.x == 0)
+                *flags = 1; // no such width here, or no copy of it: nobody runs this entry
+            continue;
+        }
         // All wavefronts of the workgroup run the tile (rows past N are clamped on load and
         // masked on store) so that every one of them reaches the staging barriers.
         const int wave_row0 = t * TILE_ROWS + wave * RT * 16;
@@ -650,34 +656,35 @@ int resident(int cus)
 template <int MT, int RT>
 hipError_t launch(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
                   const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
-                  hipStream_t stream, const int *queue = nullptr, const int2 *list = nullptr)
+                  hipStream_t stream, const int *queue = nullptr, const int2 *list = nullptr, int *flags = nullptr)
 {
     const int cap = resident<MT, RT>(cus);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
         decode_skinny_kernel<true, MT, RT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr,
-                                                                           nullptr, 1, total_tiles, M, nullptr, nullptr);
+                                                                           nullptr, 1, total_tiles, M, nullptr, nullptr, nullptr);
     } else {
         FqLinearDesc none = {};
         decode_skinny_kernel<false, MT, RT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                            count, total_tiles, M, queue, list);
+                                                                            count, total_tiles, M, queue, list, flags);
     }
     return hipGetLastError();
 }
 
 template <int MT>
 hipError_t launch_sk(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
-                     const int32_t *bits_dev, int count, int total_tiles, int M, int cus, hipStream_t stream)
+                     const int32_t *bits_dev, int count, int total_tiles, int M, int cus, hipStream_t stream,
+                     int *flags = nullptr)
 {
     const int cap = cus * fq_workgroups_per_cu((const void *)decode_skinny_sk_kernel<false, MT>, WG_THREADS, 0, 2);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
         decode_skinny_sk_kernel<true, MT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1,
-                                                                        total_tiles, M);
+                                                                        total_tiles, M, nullptr);
     } else {
         FqLinearDesc none = {};
         decode_skinny_sk_kernel<false, MT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count,
-                                                                         total_tiles, M);
+                                                                         total_tiles, M, flags);
     }
     return hipGetLastError();
 }
@@ -710,23 +717,24 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
         return hipSuccess;
     const int cus = device_cus();
     const int rt = tile_rows / 64;
+    int *fl = !single && queue ? queue + FQ_Q_FLAGS : nullptr;
     if (!single && tile_rows == 256)
         return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, queue, order, stream);
     if (tile_rows == 16)
-        return M <= 16 ? launch_sk<1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream)
-                       : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        return M <= 16 ? launch_sk<1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl)
+                       : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
     if (M <= 16) {
         if (rt == 4)
-            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
         if (rt == 2)
-            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
-        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
+        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
     }
     if (rt == 4)
-        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
     if (rt == 2)
-        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
-    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream);
+        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
+    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
 }
 
 hipError_t fq_launch_skinny_second(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,

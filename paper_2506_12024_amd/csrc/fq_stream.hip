@@ -882,6 +882,8 @@ __global__ __launch_bounds__(256) void plan_order_kernel(const FqLinearDesc *__r
             } else if (bits == 2 && d.codes2) {
                 list = 1;
                 tiles = (d.N + 127) / 128;
+            } else {
+                queue[FQ_Q_FLAGS] = 1; // no such width here, or no copy of it: nobody runs this entry
             }
         }
 #pragma unroll

@@ -385,3 +385,32 @@ def test_entropy_kl_special_cases():
 def test_entropy_r0_is_a_no_op():
     H = torch.zeros(1, device=DEV)
     fq.fq_entropy_kl(H, None, 0, 8, H, None)
+
+
+@pytest.mark.parametrize("M,shapes", [(1, [(256, 1024), (100, 1408)]), (4, [(256, 1024), (100, 1408)]),
+                                      (2, [(40, 256), (24, 128)]), (16, [(11008, 512)] * 24)])
+def test_plan_status_reports_entries_that_could_not_be_served(M, shapes):
+    # M = 1: the batch-1 kernel; 4: the register-fed batch kernel; 2 with few rows: its K-split
+    # form; 16 with many rows: the streaming kernel behind plan_order_kernel
+    layers, xs, ys = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        w = synth.weight(0, "par/status/w%d" % (i % 3), N, K, 0.02)
+        layer, _ = make_layer(w, (4, 8) if i else (4,))
+        layers.append(layer)
+        xs.append(to_dev(synth.activations(0, "par/status/x%d" % (i % 3), M, K)))
+        ys.append(torch.full((M, N), 3.0, dtype=torch.float16, device=DEV))
+    ws = torch.empty(fq.Plan.workspace_bytes(len(layers)), dtype=torch.uint8, device=DEV)
+    plan = fq.Plan(layers, xs, ys, M, ws)
+    n = len(layers)
+    plan.run(torch.tensor([4] * n, dtype=torch.int32, device=DEV))
+    assert plan.status() == (0, 0)
+    assert not torch.all(ys[0] == 3.0)
+    ys[0].fill_(3.0)
+    plan.run(torch.tensor([8] + [4] * (n - 1), dtype=torch.int32, device=DEV))   # entry 0 holds no 8-bit copy
+    assert plan.status() == (0, 1)
+    assert torch.all(ys[0] == 3.0) and not torch.all(ys[1] == 3.0)
+    plan.run(torch.tensor([4] * n, dtype=torch.int32, device=DEV))               # the flag stays
+    assert plan.status() == (0, 1)
+    plan2 = fq.Plan(layers, xs, ys, M, ws)                                        # a new plan starts clean
+    plan2.run(torch.tensor([4] + [5] * (n - 1), dtype=torch.int32, device=DEV))  # 5 is no width at all
+    assert plan2.status() == (0, 1)
