@@ -550,46 +550,62 @@ def bench_lm_head(args):
 
 
 def bench_flexquant(args):
-    """Alg. 1's decode loop on the 7B-shaped stack: every linear starts at INT8; per token the
-    plan runs at the current bit-widths, fq_entropy_kl gives the entropy of the token's logits
-    and fq_sched_step (window 20) moves the next linears of the replacement order (ascending KL
-    between each linear's INT8 and INT4 output, measured once before generation through the
-    library: kl_replacement_order) to INT4 when the average PPLE falls below the threshold --
-    all on the device, three launches per token.  The logits are synthetic with an entropy that falls as generation proceeds (the
-    behaviour Sec. 4.2 reports): one seeded N(0, 1) vector scaled by a growing factor."""
+    """Alg. 1's decode loop on the 7B-shaped stack over a ladder of resident formats (default FP16 ->
+    INT8 -> INT4, the ladder of Sec. 5.1's main setting; `--ladder 8,4` for the two-rung one):
+    every linear starts on the first rung; per token the plan runs at the current bit-widths,
+    fq_entropy_kl gives the entropy of the token's logits and fq_sched_step (window 20) moves the
+    next linears of the replacement order one rung down when the average PPLE falls below the
+    threshold -- all on the device, three launches per token.  The replacement order is ascending
+    KL between each linear's INT8 and INT4 output, measured once before generation through the
+    library (kl_replacement_order); it is walked once per rung.  The logits are synthetic with an
+    entropy that falls as generation proceeds (the behaviour Sec. 4.2 reports): one seeded N(0, 1)
+    vector scaled by a growing factor."""
     import torch
     import paper_2506_12024_amd as fq
     dev = "cuda:0"
     T = max(args.steps, 64)
-    stack = Stack(args.stack, M=1, bit_choices=(4, 8), layers=args.layers, verbose=args.verbose)
+    ladder = [int(b) for b in args.ladder.split(",")]
+    assert len(ladder) >= 2 and all(b in (2, 3, 4, 8, 16) for b in ladder) and sorted(ladder, reverse=True) == ladder
+    widths = tuple(sorted(set(ladder) | {4, 8}))   # 4 and 8 are needed for the KL order
+    stack = Stack(args.stack, M=1, bit_choices=widths, layers=args.layers, verbose=args.verbose)
     n = len(stack.layers)
+    dependent = args.order != "independent"
+    if dependent:
+        stack.build_staged_plan()
+    plan = stack.staged_plan if dependent else stack.plan
     base = synth.normal_f32(SEED, "flexquant/logits", VOCAB, 1.0)
     scale = (2.0 + 2.0 * np.arange(T, dtype=np.float32) / T)[:, None]
     logits = torch.from_numpy(base[None, :] * scale).to(dev)
-    ev_entry, kl = kl_replacement_order(stack)
-    order = ev_entry.cpu().numpy()
+    order_dev, kl = kl_replacement_order(stack)
+    order = order_dev.cpu().numpy()
     kl_host = kl.cpu().numpy().astype(np.float64).sum(axis=1)
-    ev_bits = torch.full((n,), 4, dtype=torch.int32, device=dev)
-    bits = torch.full((n,), 8, dtype=torch.int32, device=dev)
-    ev_token = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    # the events: the whole order once per step down the ladder
+    rungs = len(ladder) - 1
+    ev_entry = order_dev.repeat(rungs).contiguous()
+    ev_bits = torch.cat([torch.full((n,), b, dtype=torch.int32, device=dev) for b in ladder[1:]]).contiguous()
+    n_events = n * rungs
+    bits = torch.full((n,), ladder[0], dtype=torch.int32, device=dev)
+    ev_token = torch.full((n_events,), -1, dtype=torch.int32, device=dev)
     H = torch.zeros(T, dtype=torch.float32, device=dev)
     state = torch.zeros(fq.fq_sched_state_bytes(20), dtype=torch.uint8, device=dev)
-    per_trigger = max(1, n // 28)   # the whole order is walked within the run
+    # a full window of new tokens separates two triggers: size a trigger so that the whole ladder is
+    # walked within the run if every window's average stays under the threshold
+    per_trigger = -(-n_events // max(1, (T - 1) // 20))
 
     def generate(sched: bool):
         for t in range(T):
-            stack.plan.run(bits)
+            plan.run(bits)
             fq.fq_entropy_kl(logits[t], None, 1, VOCAB, H[t:t + 1], None)
             if sched:
                 fq.fq_sched_step(state, H[t:t + 1])
 
     # threshold: the mean PPLE of 20 "prefill" positions taken at the start of the run
     generate(False)
-    fq.fq_sched_init(state, 20, 0.0, per_trigger, ev_entry, ev_bits, n, bits, ev_token)
+    fq.fq_sched_init(state, 20, 0.0, per_trigger, ev_entry, ev_bits, n_events, bits, ev_token)
     fq.fq_sched_threshold_from_prefill(state, H, 20, 20)
     torch.cuda.synchronize()
     results = {}
-    for name, start, sched in (("int8", 8, False), ("int4", 4, False), ("flexquant", 8, True)):
+    for name, start, sched in [("fixed_%d" % b, b, False) for b in ladder] + [("flexquant", ladder[0], True)]:
         bits.fill_(start)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -597,32 +613,39 @@ def bench_flexquant(args):
         torch.cuda.synchronize()
         results[name] = T / (time.perf_counter() - t0)
     next_event, tokens, thre, last_mean = fq.fq_sched_peek(state)
-    fired = ev_token.cpu().numpy()
-    fired = fired[fired >= 0]
-    # average bit-width over the generation, weighted by weights per entry
+    tok = ev_token.cpu().numpy().reshape(rungs, n)
+    fired = tok[tok >= 0]
+    # average bit-width over the generation, weighted by weights per entry: entry order[i] sits on
+    # rung r from the token after its r-th event fired
     sizes = np.array([N * K for (_, _, K, N) in stack.entries], dtype=np.float64)
-    at4 = np.zeros(n)
-    tok = ev_token.cpu().numpy()
+    avg = np.zeros(n)
     for i, e in enumerate(order):
-        if tok[i] >= 0:
-            at4[e] = (T - 1 - tok[i]) / T
-    avg_bits = float(((8 - 4 * at4) * sizes).sum() / sizes.sum())
-    print(json.dumps({
+        since = [0] + [int(tok[r, i]) + 1 if tok[r, i] >= 0 else T for r in range(rungs)] + [T]
+        avg[e] = sum(ladder[r] * (since[r + 1] - since[r]) for r in range(rungs + 1)) / T
+    avg_bits = float((avg * sizes).sum() / sizes.sum())
+    status = plan.status()
+    out = {
         "metric": "decode tokens/s with on-device precision switching", "value": results["flexquant"],
         "unit": "tokens/s", "n_gpus": 1, "steps": T, "warmup": 0,
         "ms_per_step": 1e3 / results["flexquant"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s stack, batch 1, INT8 -> INT4 by the PPLE scheduler (window 20, %d "
-                               "linears per trigger), %d tokens" % (args.stack, per_trigger, T)},
-        "fixed_int8_tokens_per_s": results["int8"], "fixed_int4_tokens_per_s": results["int4"],
-        "speedup_over_int8": results["flexquant"] / results["int8"],
-        "events_fired": int(next_event), "events_total": n, "threshold_pple": thre,
+        "vs_baseline": None, "dtype": "f16 x %s -> f32" % "/".join("fp16" if b == 16 else "int%d" % b for b in ladder),
+        "data": "synthetic",
+        "config": {"workload": "%s stack, batch 1, %s by the PPLE scheduler (window 20, %d events per trigger), "
+                               "%d tokens" % (args.stack, " -> ".join("FP16" if b == 16 else "INT%d" % b for b in ladder),
+                                              per_trigger, T),
+                   "order": "dependent" if dependent else "independent"},
+        "speedup_over_first_rung": results["flexquant"] / results["fixed_%d" % ladder[0]],
+        "events_fired": int(next_event), "events_total": n_events, "threshold_pple": thre,
         "first_switch_token": int(fired.min()) if fired.size else None,
         "last_switch_token": int(fired.max()) if fired.size else None,
         "average_weight_bits": avg_bits,
+        "plan_status": {"gave_up": status[0], "flags": status[1]},
         "kl_order": {"first": [int(e) for e in order[:4]], "last": [int(e) for e in order[-4:]],
                      "kl_min": float(kl_host.min()), "kl_max": float(kl_host.max()),
-                     "ascending": bool(np.all(np.diff(kl_host[order]) >= 0))}}))
+                     "ascending": bool(np.all(np.diff(kl_host[order]) >= 0))}}
+    for b in ladder:
+        out["fixed_%s_tokens_per_s" % ("fp16" if b == 16 else "int%d" % b)] = results["fixed_%d" % b]
+    print(json.dumps(out))
 
 
 def main():
@@ -636,6 +659,7 @@ def main():
     ap.add_argument("--stack", default="llama7b", choices=sorted(synth.STACKS))
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--bits", default="4,8", help="bit-widths drawn per layer per token")
+    ap.add_argument("--ladder", default="16,8,4", help="--workload flexquant: the formats a linear steps down through")
     ap.add_argument("--layers", type=int, default=None, help="truncate the stack (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-mib", type=int, default=0,
