@@ -239,27 +239,37 @@ def cpu_baseline(stack: Stack, sample_layers: int = 8) -> dict:
 def bench_prefill(args):
     """The prefill-shaped slice: x[2048][8192] against W 8192->28672 and x[2048][28672] against
     W 28672->8192 (a 70B-shaped layer slice), int4 and int8, MFMA dequant-GEMM.  One step = the
-    four GEMMs.  Reports TFLOP/s against the dense fp16 MFMA peak."""
+    GEMMs of the chosen shapes (`--shape NxK`, default both) and bit-widths (`--prefill-bits`,
+    default 4,8; 2 and 16 are served too).  Reports TFLOP/s against the dense fp16 MFMA peak, per
+    call and as the mean."""
     import torch
     import paper_2506_12024_amd as fq
     dev, M = "cuda:0", 2048
+    shapes = [(28672, 8192), (8192, 28672)]
+    if args.shape:
+        shapes = [tuple(int(v) for v in args.shape.lower().split("x"))]
+    widths = [int(b) for b in args.prefill_bits.split(",")]
     calls = []
-    for N, K in ((28672, 8192), (8192, 28672)):
+    for N, K in shapes:
         w = synth.weight(SEED, "prefill/%dx%d/w" % (N, K), N, K, 0.015)
         x = synth.activations(SEED, "prefill/%dx%d/x" % (N, K), M, K)
         w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
         x_dev = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
         y = torch.empty((M, N), dtype=torch.float16, device=dev)
         layer = fq.Layer(N, K)
-        for b in (4, 8):
-            cb, sb, zb = fq.fq_packed_sizes(N, K, b)
-            c = torch.empty(cb, dtype=torch.uint8, device=dev)
-            sc = torch.empty(sb // 4, dtype=torch.float32, device=dev)
-            z = torch.empty(zb, dtype=torch.uint8, device=dev)
-            fq.fq_quantize(w_dev, N, K, b, 128, c, sc, z)
-            layer.attach(b, c, sc, z)
+        for b in widths:
+            if b == 16:
+                layer.attach(16, w_dev)
+            else:
+                cb, sb, zb = fq.fq_packed_sizes(N, K, b)
+                c = torch.empty(cb, dtype=torch.uint8, device=dev)
+                sc = torch.empty(sb // 4, dtype=torch.float32, device=dev)
+                z = torch.empty(zb, dtype=torch.uint8, device=dev)
+                fq.fq_quantize(w_dev, N, K, b, 128, c, sc, z)
+                layer.attach(b, c, sc, z)
             calls.append((layer, b, x_dev, y))
-        del w_dev
+        if 16 not in widths:
+            del w_dev
     flop = sum(2.0 * M * l.N * l.K for l, _, _, _ in calls)
 
     def step():
@@ -279,16 +289,27 @@ def bench_prefill(args):
     elapsed = time.perf_counter() - t0
     ms_launch = e0.elapsed_time(e1) / (args.steps * len(calls))
     achieved = flop / len(calls) / (ms_launch * 1e-3) / 1e12
+    per_call = {}
+    for layer, b, x_dev, y in calls:   # each GEMM by itself, back to back
+        e0.record(stream)
+        for _ in range(10):
+            fq.fq_linear(layer, b, x_dev, M, y)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        per_call["%d->%d W%d" % (layer.K, layer.N, b)] = {"ms": ms, "TFLOPs": 2.0 * M * layer.N * layer.K / (ms * 1e-3) / 1e12}
     print(json.dumps({
         "metric": "prefill dequant-GEMM throughput", "value": M * args.steps * len(calls) / elapsed,
         "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "70B-shaped slice: M=2048, 8192->28672 and 28672->8192, W4 and W8 "
-                               "(4 GEMMs per step)"},
+        "config": {"workload": "70B-shaped slice: M=2048, %s, W%s (%d GEMMs per step)"
+                               % (" and ".join("%d->%d" % (K, N) for N, K in shapes),
+                                  "/W".join(str(b) for b in widths), len(calls))},
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": achieved, "peak": 2500.0,
                      "unit": "TFLOP/s", "frac": achieved / 2500.0, "traffic": None,
-                     "avg_launch_ms": ms_launch, "flop_per_launch": flop / len(calls)}}))
+                     "avg_launch_ms": ms_launch, "flop_per_launch": flop / len(calls)},
+        "per_call": per_call}))
 
 
 def bench_prefill_w8a8(args):
@@ -659,6 +680,8 @@ def main():
     ap.add_argument("--stack", default="llama7b", choices=sorted(synth.STACKS))
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--bits", default="4,8", help="bit-widths drawn per layer per token")
+    ap.add_argument("--shape", default=None, help="--workload prefill: one shape NxK (weight rows x inputs) instead of both")
+    ap.add_argument("--prefill-bits", default="4,8", help="--workload prefill: the bit-widths of the GEMMs of a step")
     ap.add_argument("--ladder", default="16,8,4", help="--workload flexquant: the formats a linear steps down through")
     ap.add_argument("--layers", type=int, default=None, help="truncate the stack (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -37,8 +37,7 @@
  *   codes, bits = 4 : u8  [N][K/2]    byte j of row n = code(2j) | code(2j+1) << 4
  *   codes, bits = 2 : u8  [N][K/4]    byte j of row n = code(4j) | code(4j+1) << 2 |
  *                                     code(4j+2) << 4 | code(4j+3) << 6
- *                                     (Table 1's lowest width; served by the decode kernels,
- *                                     M <= FQ_MAX_DECODE_M)
+ *                                     (Table 1's lowest width)
  *   codes, bits = 3 : u8  [N][K/32][12]  a block of 12 bytes holds 32 consecutive codes c(0..31)
  *                                     as three little-endian 32-bit words: word j holds c(10j) ..
  *                                     c(10j+9) whole, c(10j + 5h + p) (h = 0, 1; p = 0 .. 4) in
@@ -151,8 +150,7 @@ int fq_layer_destroy(fq_layer *layer);
  * Decode-phase linear (Sec. 4.1, Eq. (3)):
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
- * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 2 is
- * served in the decode phase only (M <= FQ_MAX_DECODE_M and K <= FQ_MAX_DECODE_K), bits = 3 at
+ * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 3 is served at
  * M = 1 only (K <= FQ_MAX_DECODE_K): FQ_ERR_BITS otherwise.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)

@@ -262,9 +262,6 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
     if (bits == 3 && (M != 1 || layer->K > MAX_DECODE_K))
         return fail(FQ_ERR_BITS, "fq_linear: the 3-bit copy is served by the batch-1 decode kernel only, M = 1 and K <= %d (got M=%d K=%d)",
                     MAX_DECODE_K, M, layer->K);
-    if (bits == 2 && (M > FQ_MAX_DECODE_M || layer->K > MAX_DECODE_K))
-        return fail(FQ_ERR_BITS, "fq_linear: the 2-bit copy is served by the decode kernels only, M <= %d and K <= %d (got M=%d K=%d)",
-                    FQ_MAX_DECODE_M, MAX_DECODE_K, M, layer->K);
     if (!aligned16(x_fp16) || (reinterpret_cast<uintptr_t>(y_fp16) & 1u))
         return fail(FQ_ERR_ALIGN, "fq_linear: x needs 16-byte and y 2-byte alignment");
     FqLinearDesc d;

@@ -20,7 +20,8 @@
 // LDS traffic of the weight operand is that of the packed codes.
 //
 // Dequantization.  Codes become the exact integers q - z as halves (bit tricks: a byte under
-// exponent 0x64 is 1024 + q, a nibble in bits 4..7 under 0x54 is 64 + q; one v_pk_add_f16
+// exponent 0x64 is 1024 + q, a nibble in bits 4..7 under 0x54 is 64 + q, a 2-bit field at bits
+// 0 / 2 / 4 / 6 under 0x64 / 0x5C / 0x54 / 0x4C is 1024 / 256 / 64 / 16 + q; one v_pk_add_f16
 // removes the offset and z) and are multiplied by the group's scale rounded to half (one
 // v_pk_mul_f16 per register): the MFMA operand is half((q - z) * half(s)).  The decode
 // kernels keep the scale in binary32 outside the group sum; here that would need a second
@@ -79,7 +80,10 @@ template <int RB>
 __device__ __forceinline__ DmaLane dma_lane()
 {
     constexpr int RPL = 128 / RB, CPR = RB / 16;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // a slab of 16-byte rows (2-bit weights) is 4 KiB, half a load of the workgroup: wavefronts
+    // 4 .. 7 fetch the same pieces as 0 .. 3 (same bytes to the same place), so that every
+    // wavefront issues the same number of loads per step -- the waits count them
+    const int wave = RB == 16 ? (threadIdx.x >> 6) & 3 : threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int line = wave * 8 + (lane >> 3);
     const int slot = (lane & 7) ^ ((line >> 1) & 7);
     DmaLane L;
@@ -97,9 +101,10 @@ template <int ROWS, int RB>
 __device__ __forceinline__ void dma_slab(const uint8_t *tile, const DmaLane &L, int last_row, uint32_t pitch,
                                          uint8_t *slab)
 {
-    const int wave = threadIdx.x >> 6;
+    const int wave = RB == 16 ? (threadIdx.x >> 6) & 3 : threadIdx.x >> 6;
+    constexpr int LOADS = ROWS * RB / 16 / THREADS > 0 ? ROWS * RB / 16 / THREADS : 1;
 #pragma unroll
-    for (int i = 0; i < ROWS * RB / 16 / THREADS; i++) {
+    for (int i = 0; i < LOADS; i++) {
         const uint32_t off = (uint32_t)min(L.r0 + i * L.rstep, last_row) * pitch + L.byte0;
         __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(tile + off),
                                          (FQ_LDS void *)(slab + (i * WAVES + wave) * 1024), 16, 0, 0);
@@ -122,11 +127,12 @@ __device__ __forceinline__ float16_t mfma32(const u32x4 a, const uint32_t (&b)[4
 // Which 8 k of the 64-k step lane (row, c) supplies in k16-step i, as the index of the
 // 16-byte chunk of 8 halves in an x row:
 //   4-bit: a lane reads one 16-byte chunk of codes (32 codes, k = 32 c ..), word i of it holds
-//          k = 32 c + 8 i ..;   8-bit and fp16: k = 16 i + 8 c ..
+//          k = 32 c + 8 i ..;   2-bit: the same k from 8 bytes of codes, half-word i;
+//          8-bit and fp16: k = 16 i + 8 c ..
 template <int BITS>
 __device__ __forceinline__ int x_chunk(int i, int c)
 {
-    return BITS == 4 ? 4 * c + i : 2 * i + c;
+    return BITS == 4 || BITS == 2 ? 4 * c + i : 2 * i + c;
 }
 
 // Scale and zero point of a lane's two weight rows for one quantization group.
@@ -169,9 +175,9 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (m0 >= M)
         return; // the second half of a last, partly filled tile
 
-    const uint8_t *codes = BITS == 4 ? d.codes4 : BITS == 8 ? d.codes8 : (const uint8_t *)d.w16;
-    const float *scales = BITS == 4 ? d.scales4 : d.scales8;
-    const uint8_t *zeros = BITS == 4 ? d.zeros4 : d.zeros8;
+    const uint8_t *codes = BITS == 2 ? d.codes2 : BITS == 4 ? d.codes4 : BITS == 8 ? d.codes8 : (const uint8_t *)d.w16;
+    const float *scales = BITS == 2 ? d.scales2 : BITS == 4 ? d.scales4 : d.scales8;
+    const uint8_t *zeros = BITS == 2 ? d.zeros2 : BITS == 4 ? d.zeros4 : d.zeros8;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, c = lane >> 5;
@@ -200,7 +206,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int bofs[4];
 #pragma unroll
     for (int i = 0; i < 4; i++)
-        bofs[i] = BITS == 4 ? slab_offset<WRB_>(wn + (i & 1) * 32 + l32, c)
+        bofs[i] = BITS == 2 ? slab_offset<WRB_>(wn + (i & 1) * 32 + l32, 0) + 8 * c
+                : BITS == 4 ? slab_offset<WRB_>(wn + (i & 1) * 32 + l32, c)
                 : BITS == 8 ? slab_offset<WRB_>(wn + l32, i) + 8 * c
                             : slab_offset<WRB_>(wn + l32, 2 * i + c);
     constexpr int BJ = 32 * WRB_; // bytes from n-tile 0 to n-tile 1 (8-bit, fp16)
@@ -236,7 +243,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     Meta cur;
     // VMEM operations a thread issues per step: these may still be in flight at the end of the
     // step when a later stage is being filled (three stages)
-    constexpr int DMA_OPS = (BM * XRB + BN * WRB) / 16 / THREADS;
+    constexpr int DMA_OPS = BM * XRB / 16 / THREADS + (BN * WRB / 16 / THREADS > 0 ? BN * WRB / 16 / THREADS : 1);
     // s_waitcnt vmcnt(n) lgkmcnt(0) (expcnt untouched)
     auto wait_vm = [](auto n) {
         constexpr int N = decltype(n)::value;
@@ -302,14 +309,16 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
         // constants of the group for the two n-tiles
         half2_t sh[2];
-        uint32_t nz[2];
+        uint32_t nz[2], nz2[2];
 #pragma unroll
         for (int j = 0; j < 2; j++) {
             if (BITS != 16) {
                 sh[j] = half2_t{(_Float16)cur.s[j], (_Float16)cur.s[j]};
                 const uint32_t z = cur.z[j];
-                nz[j] = BITS == 8 ? ((z | (z << 16)) | 0xE400E400u)             // -(1024 + z) twice
-                                  : ((z | 0xE400u) | (((z << 4) | 0xD400u) << 16)); // -(1024 + z), -(64 + z)
+                nz[j] = BITS == 8 ? ((z | (z << 16)) | 0xE400E400u)               // -(1024 + z) twice
+                      : BITS == 4 ? ((z | 0xE400u) | (((z << 4) | 0xD400u) << 16)) // -(1024 + z), -(64 + z)
+                                  : ((z | 0xE400u) | (((z << 2) | 0xDC00u) << 16)); // -(1024 + z), -(256 + z)
+                nz2[j] = ((z << 4) | 0xD400u) | (((z << 6) | 0xCC00u) << 16);     // 2 bits: -(64 + z), -(16 + z)
             }
         }
         u32x4 w4[2]; // 4-bit: the lane's 32 codes of the step, per n-tile
@@ -317,6 +326,12 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
             for (int j = 0; j < 2; j++)
                 w4[j] = *reinterpret_cast<const u32x4 *>(wc + bofs[j]);
+        }
+        u32x2 w2[2]; // 2-bit: the same 32 codes in 8 bytes
+        if (BITS == 2) {
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+                w2[j] = *reinterpret_cast<const u32x2 *>(wc + bofs[j]);
         }
 #pragma unroll
         for (int i = 0; i < 4; i++) {
@@ -327,7 +342,18 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
             for (int j = 0; j < 2; j++) {
                 uint32_t b[4];
-                if (BITS == 4) {
+                if (BITS == 2) {
+                    // half-word i: fields q0 .. q7 of k = 32 c + 8 i .., byte t holds q(4t) .. q(4t+3).
+                    // The byte is copied under both halves; fields 0 and 1 (or 2 and 3) of it stay
+                    // where they are, one per half, each under the exponent that makes it offset + q
+                    const uint32_t v = i < 2 ? w2[j].x : w2[j].y;
+                    const uint32_t lo = __builtin_amdgcn_perm(0u, v, (i & 1) ? 0x0c020c02u : 0x0c000c00u);
+                    const uint32_t hi = __builtin_amdgcn_perm(0u, v, (i & 1) ? 0x0c030c03u : 0x0c010c01u);
+                    b[0] = deq((lo & 0x000C0003u) | 0x5C006400u, nz[j], sh[j]);  // q0, q1
+                    b[1] = deq((lo & 0x00C00030u) | 0x4C005400u, nz2[j], sh[j]); // q2, q3
+                    b[2] = deq((hi & 0x000C0003u) | 0x5C006400u, nz[j], sh[j]);  // q4, q5
+                    b[3] = deq((hi & 0x00C00030u) | 0x4C005400u, nz2[j], sh[j]); // q6, q7
+                } else if (BITS == 4) {
                     // word i: nibbles q0 .. q7 of k = 32 c + 8 i ..; byte t holds (q(2t+1) q(2t)).
                     // The byte is copied under both halves, the low nibble kept in the low half
                     // (exponent 0x64: 1024 + q) and the high nibble in the high half (0x54: 64 + q)
@@ -418,7 +444,9 @@ static hipError_t launch_prefill(const FqLinearDesc &d, int bits, int M, int m_t
     if (per_launch <= 0)
         return hipSuccess;
     const unsigned grid = (unsigned)per_launch * (HALF ? 16u : 8u);
-    if (bits == 4)
+    if (bits == 2)
+        prefill_kernel<2, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);
+    else if (bits == 4)
         prefill_kernel<4, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);
     else if (bits == 8)
         prefill_kernel<8, HALF><<<grid, THREADS, 0, stream>>>(d, M, m_tiles, n_tiles, per_xcd, skip);

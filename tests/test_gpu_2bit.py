@@ -1,7 +1,7 @@
 """GPU parity of the packed 2-bit path (Table 1's lowest width; Sec. 2.2 Eq. (2), (3) with n = 2)
 against the CPU oracle: codes, scales and zero points bit-exact, decode outputs (M = 1 and batches
 up to 32, single calls and plans that mix 2 / 4 / 8 / 16 bits per entry) within 2e-3 max-abs
-normalised."""
+normalised; the prefill-shaped GEMM at 2 bits likewise."""
 import numpy as np
 import pytest
 import torch
@@ -185,13 +185,38 @@ def test_batched_plan_with_2bit_entries():
         assert torch.isfinite(y.float()).all()
 
 
-def test_2bit_is_refused_in_the_prefill_path():
-    w = synth.weight(0, "par2/ref/w", 64, 256, 0.02)
-    layer, _ = make_layer(w, (2, 4))
-    x = to_dev(synth.activations(0, "par2/ref/x", 40, 256))
-    y = torch.zeros((40, 64), dtype=torch.float16, device=DEV)
-    with pytest.raises(fq.FlexqError) as e:
-        fq.fq_linear(layer, 2, x, 40, y)
-    assert e.value.code == -2
-    fq.fq_linear(layer, 4, x, 40, y)  # the other copies of the same layer still serve it
-    torch.cuda.synchronize()
+# ------------------------------------------------------------------ prefill-shaped (MFMA GEMM) at 2 bits
+
+@pytest.mark.parametrize("M,N,K", [(33, 100, 1408), (128, 256, 1024), (300, 200, 2048), (257, 130, 128),
+                                   (64, 129, 4096), (2, 48, 32768 + 128)])
+def test_linear_2bit_prefill_matches_oracle(M, N, K):
+    w = synth.weight(0, "par2/pre/%dx%d" % (N, K), N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par2/pre/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (2,))
+    y = gpu_linear(layer, 2, x)
+    c, s, z = (t.cpu().numpy() for t in packed[2])
+    y_ref = oracle.linear(x, c, s, z, 2)
+    assert y.shape == (M, N)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+    for m in (0, M // 2, M - 1):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_linear_2bit_prefill_integer_case_exact():
+    # codes = the integer weights (s = 1, z = 0), small integer x: the GEMM's operands
+    # half((q - z) * half(s)) and its binary32 sums are exact, so the output is the integer product;
+    # one-hot rows of x pick single codes at every position of a 16-byte row of codes
+    rng = np.random.default_rng(9)
+    M, N, K = 200, 150, 1024
+    w = rng.integers(0, 4, size=(N, K))
+    w[:, 0::128] = 0
+    w[:, 1::128] = 3
+    x = rng.integers(-2, 3, size=(M, K))
+    for m in range(70):
+        x[m] = 0
+        x[m, m] = 1
+    layer, packed = make_layer(w.astype(np.float16), (2,))
+    y = gpu_linear(layer, 2, x.astype(np.float16))
+    expect = (x @ w.T).astype(np.float16)
+    assert np.array_equal(y.view(np.uint16), expect.view(np.uint16))

@@ -189,8 +189,9 @@ def test_2bit_copy_limits():
     assert L.fq_layer_create(ctypes.byref(h), 64, 256, 128) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, FAKE, FAKE) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, None, FAKE) == B.FQ_ERR_NULL
-    assert L.fq_linear(h, 2, FAKE, 33, FAKE, None) == B.FQ_ERR_BITS  # decode phase only
-    assert "decode" in fq.fq_last_error()
+    assert L.fq_layer_attach(h, 3, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_linear(h, 3, FAKE, 2, FAKE, None) == B.FQ_ERR_BITS  # 3 bits: batch 1 only
+    assert "3-bit" in fq.fq_last_error()
     assert L.fq_linear(h, 4, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
