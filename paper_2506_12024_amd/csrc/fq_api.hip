@@ -373,6 +373,10 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
         has2 = has2 || layers[i]->codes[3] != nullptr;
     }
     int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
+    // 256-row tiles at M > 1 mean the streaming kernel, whose tile queue deals runs of 8 tiles to 8
+    // XCDs of 8 x k compute units: a device of another shape stays with the register-fed kernel
+    if (M > 1 && rows == 256 && fq_device_cus() % 64 != 0)
+        rows = 128;
     // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits and passes over
     // every entry at another width: a plan of its size that holds a 2-bit copy, whose entries may be
     // switched to it at any token, runs in two launches, the second one the register-fed kernel over

@@ -27,7 +27,9 @@
 // kernels keep the scale in binary32 outside the group sum; here that would need a second
 // set of 128 accumulator registers per wavefront and a 256-instruction fold per group, so
 // the prefill path rounds twice at 2^-11 relative instead.  The error stays well inside the
-// 2e-3 bound (about 5e-4 of the output magnitude in the worst one-group case).
+// 2e-3 bound (about 5e-4 of the output magnitude in the worst one-group case).  So that this
+// holds whatever the magnitude of the weights, the half carries s * 2^e with a power of two per
+// weight row that is taken out of the row's sums at the end.
 //
 // Workgroups that share a weight slab (the M tiles of one N tile) get consecutive logical
 // ids, and logical ids are dealt to the 8 XCDs in contiguous runs, so that a slab is
@@ -116,6 +118,8 @@ __device__ __forceinline__ uint32_t deq(uint32_t a, uint32_t b, half2_t s)
 {
     return __builtin_bit_cast(uint32_t, (__builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b)) * s);
 }
+
+__device__ __forceinline__ float as_float_global(const float *p) { return *(const FQ_GLOBAL float *)p; }
 
 __device__ __forceinline__ float16_t mfma32(const u32x4 a, const uint32_t (&b)[4], float16_t c)
 {
@@ -241,6 +245,20 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     };
 
     Meta cur;
+    // The operand carries the group's scale as a half: a scale below 2^-14 would lose bits there and
+    // one below 2^-25 the whole group.  Every weight row therefore gets a power of two, taken from
+    // two of its scales (the first group's and the middle one's), that brings them to about 2^-4 --
+    // halves then hold scales 2^10 times smaller and 2^12 times larger than those exactly as well --
+    // and the row's sums are multiplied by its inverse at the end.
+    int ex[2] = {0, 0};
+    if (BITS != 16) {
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const float *srow = scales_tile + (size_t)min(wn + j * 32 + l32, w_last) * G;
+            const float m = fmaxf(as_float_global(srow), as_float_global(srow + (G >> 1)));
+            ex[j] = -3 - __builtin_amdgcn_frexp_expf(m);
+        }
+    }
     // VMEM operations a thread issues per step: these may still be in flight at the end of the
     // step when a later stage is being filled (three stages)
     constexpr int DMA_OPS = BM * XRB / 16 / THREADS + (BN * WRB / 16 / THREADS > 0 ? BN * WRB / 16 / THREADS : 1);
@@ -290,7 +308,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
             // (nothing is writing smeta / zmeta now: the next request goes out a step later)
 #pragma unroll
             for (int j = 0; j < 2; j++) {
-                cur.s[j] = smeta[wn + j * 32 + l32];
+                cur.s[j] = __builtin_ldexpf(smeta[wn + j * 32 + l32], ex[j]);
                 cur.z[j] = zmeta[wn + j * 32 + l32];
             }
         }
@@ -430,7 +448,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 const int m = m0 + wm + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
                 if (m < M && n < d.N)
                     ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + n] =
-                        __builtin_bit_cast(uint16_t, (_Float16)acc[mt][j][v]);
+                        __builtin_bit_cast(uint16_t, (_Float16)(BITS == 16 ? acc[mt][j][v] : __builtin_ldexpf(acc[mt][j][v], -ex[j])));
             }
         }
 }

@@ -773,15 +773,6 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
 {
     constexpr int XCD_RUN = 8;
     const int grid = gridDim.x;
-    if (!queue) { // no queue: a fixed deal in the order of the table
-        int e = 0;
-        for (int tile = blockIdx.x; tile < total_tiles; tile += grid) {
-            while (e + 1 < count && tile >= table[e + 1].tile_begin)
-                e++;
-            run_tile<MT, ROLE>(table, bits_dev, e, tile - table[e].tile_begin, M, L, wave, [](int) {});
-        }
-        return;
-    }
     const int xcd = blockIdx.x & 7;
     const int listed_tiles = queue[FQ_Q_TILES], entries = queue[FQ_Q_ENTRIES];
     auto draw = [&](int lane) { // whole wavefront
@@ -934,18 +925,19 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
 
 // A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
 // tiles of 256 rows.  `queue`: 16 ints in device memory that belong to the plan, zeroed once (the
-// kernel leaves the cursors zeroed), and `order`: 2 x `count` pairs of ints of the plan's; or null
-// for a fixed deal of the tiles.
+// kernel leaves the cursors zeroed), and `order`: 2 x `count` pairs of ints of the plan's.  The
+// queue hands out runs of 8 tiles to the 8 XCDs in turn: the grid (one workgroup per compute unit)
+// must be a multiple of 64, which the plan's layout sees to (other devices get smaller tiles and
+// the register-fed kernel).
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
                                    int M, int cus, int *queue, void *order, hipStream_t stream)
 {
     // one workgroup per CU (LDS): persistent over the tiles
     const int grid = total_tiles < cus ? total_tiles : cus;
-    if (queue && order) // what this launch runs, under its bit-widths (a second pass reads its list too)
-        plan_order_kernel<<<1, 256, 0, stream>>>(descs_dev, bits_dev, count, queue, (int2 *)order,
-                                                 (int2 *)order + count);
-    if (!order || grid % 64 != 0) // the queue hands out runs of 8 tiles to 8 XCDs
-        queue = nullptr;
+    if (!queue || !order || grid % 64 != 0)
+        return hipErrorInvalidValue;
+    // what this launch runs, under its bit-widths (a second pass reads its list too)
+    plan_order_kernel<<<1, 256, 0, stream>>>(descs_dev, bits_dev, count, queue, (int2 *)order, (int2 *)order + count);
     if (M <= 16)
         decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue,
                                                               (const int2 *)order);

@@ -414,3 +414,24 @@ def test_plan_status_reports_entries_that_could_not_be_served(M, shapes):
     plan2 = fq.Plan(layers, xs, ys, M, ws)                                        # a new plan starts clean
     plan2.run(torch.tensor([4] + [5] * (n - 1), dtype=torch.int32, device=DEV))  # 5 is no width at all
     assert plan2.status() == (0, 1)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_linear_prefill_small_and_uneven_magnitudes(bits):
+    # the GEMM's operand carries the group's scale as a half: weights of magnitude 2e-4 give 8-bit
+    # scales near 5e-6, below the normal range of a half, and rows 2^-20 apart in magnitude share
+    # a tile; the result must be as close to the oracle as for weights of ordinary size
+    M, N, K = 96, 300, 1024
+    w = synth.weight(0, "par/pre/small/%d" % bits, N, K, 2e-4, outlier_p=0.001).astype(np.float32)
+    w[100:200] *= 2.0 ** -6                       # some rows far smaller still (halves: down to ~1e-7)
+    w[200:] *= 2.0 ** 5
+    w[:, 512:] *= 2.0 ** -3                       # and the scales of a row differ from group to group
+    w = w.astype(np.float16)
+    x = synth.activations(0, "par/pre/small/x", M, K)
+    layer, packed = make_layer(w, (bits,))
+    c, s, z = (t.cpu().numpy() for t in packed[bits])
+    assert s.min() < 2.0 ** -15                   # below the smallest normal half
+    y_ref = oracle.linear(x, c, s, z, bits)
+    y = gpu_linear(layer, bits, x)
+    for lo, hi in ((0, 100), (100, 200), (200, 300)):   # each band against its own magnitude
+        assert rel_err(y[:, lo:hi], y_ref[:, lo:hi]) <= TOL_Y, (lo, hi)
