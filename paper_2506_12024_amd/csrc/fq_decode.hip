@@ -171,25 +171,41 @@ __device__ __forceinline__ long long block_scan(long long v, long long *tmp, lon
 
 // Boundaries of this workgroup's slice.  Every thread returns the same values.
 __device__ __forceinline__ void partition(const FqLinearDesc *table, const int32_t *bits_dev, int count,
-                                          Cut &lo, Cut &hi, int *flags)
+                                          Cut &lo, Cut &hi, int *flags, int cus)
 {
     __shared__ long long tmp[WAVES];
     __shared__ Cut cuts[2];
-    // pass 1: total cost
-    long long C = 0;
+    // pass 1: total cost, and how much of it is at 2 or 3 bits
+    long long C = 0, C_low = 0;
     for (int base = 0; base < count; base += WG_THREADS) {
         const int e = base + threadIdx.x;
-        long long c = 0;
+        long long c = 0, c_low = 0;
         if (e < count) {
-            c = entry_unit_cost(table[e], bits_dev[e]) * ((table[e].N + 15) >> 4);
+            const int bits = bits_dev[e];
+            c = entry_unit_cost(table[e], bits) * ((table[e].N + 15) >> 4);
+            c_low = bits == 2 || bits == 3 ? c : 0;
             if (c == 0 && flags && blockIdx.x == 0) // no such width, or no copy of it: nobody runs this entry
                 *flags = 1;
         }
         long long chunk;
         block_scan(c, tmp, chunk);
         C += chunk;
+        block_scan(c_low, tmp, chunk);
+        C_low += chunk;
     }
-    const long long G = gridDim.x, b = blockIdx.x;
+    // Workgroups per compute unit that take part.  8- and 16-bit entries stream fastest with two
+    // (fewer concurrent streams, better DRAM page locality: measured on the mixed 7B step 0.867 /
+    // 0.763 / 0.788 / 0.795 ms with 1 / 2 / 3 / 4), but 2 and 3 bits are bound by the vector ALUs and
+    // want more wavefronts: all at 2 bits 0.378 / 0.359 / 0.352 ms with 2 / 3 / 4, all at 3 bits
+    // 0.502 / 0.474 / 0.472, bits from {2, 4} 0.465 / 0.453 / 0.458, from {3, 4} 0.529 / 0.515 /
+    // 0.523, all at 4 bits 0.538 / 0.549 / 0.554.  The launch brings four per compute unit (as far
+    // as they fit); those that this launch's bit-widths do not call for leave here.
+    const int per_cu = C_low * 10 >= C * 9 ? 4 : C_low * 10 >= C * 3 ? 3 : 2;
+    const long long G = min((long long)gridDim.x, (long long)per_cu * cus), b = blockIdx.x;
+    if (b >= G) {
+        lo = hi = Cut{count, 0};
+        return;
+    }
     const long long t_lo = b * C / G, t_hi = (b + 1) * C / G;
     if (threadIdx.x == 0) {
         cuts[0] = Cut{count, 0};
@@ -228,7 +244,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
                                                                const FqLinearDesc *__restrict__ table,
                                                                const int32_t *__restrict__ bits_dev,
                                                                int count, int total_tiles,
-                                                               int tile_rows, int *flags)
+                                                               int tile_rows, int *flags, int cus)
 {
     extern __shared__ uint4 lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // scalar: keeps row math on the SALU
@@ -260,7 +276,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_m1_kernel(const FqLinearDes
         return;
     }
     Cut lo, hi;
-    partition(table, bits_dev, count, lo, hi, flags);
+    partition(table, bits_dev, count, lo, hi, flags, cus);
     for (int e = lo.e; e < count && e <= hi.e; e++) {
         const FqLinearDesc *dp = &table[e];
         const int bits = bits_dev[e];
@@ -342,20 +358,19 @@ hipError_t fq_launch_decode(const FqLinearDesc *single, int bits_host,
             return e;
     }
     const int cap = resident_workgroups(lds);
-    // A plan cuts its total cost into one equal slice per workgroup.  Two workgroups per CU
-    // (8 wavefronts, each with eight 128-bit loads per lane in flight) stream measurably
-    // faster than four: fewer concurrent streams, better DRAM page locality (measured on the
-    // mixed 7B step: 0.867 / 0.763 / 0.788 / 0.795 ms with 1 / 2 / 3 / 4 workgroups per CU; a
-    // third register set, i.e. twelve loads per lane in flight, made it slower too: 0.780 ms).
-    const int plan_grid = cap < 2 * fq_device_cus() ? cap : 2 * fq_device_cus();
+    // A plan cuts its total cost into one equal slice per workgroup that takes part: two to four
+    // per compute unit, which the kernel decides from the launch's bit-widths (a third register
+    // set, i.e. twelve loads per lane in flight, made the mixed 7B step slower: 0.780 ms).
+    const int cus = fq_device_cus();
+    const int plan_grid = cap < 4 * cus ? cap : 4 * cus;
     const int grid = single ? (total_tiles < cap ? total_tiles : cap) : plan_grid;
     if (single) {
         decode_m1_kernel<true><<<grid, WG_THREADS, lds, stream>>>(*single, bits_host, nullptr,
-                                                                  nullptr, 1, total_tiles, tile_rows, nullptr);
+                                                                  nullptr, 1, total_tiles, tile_rows, nullptr, cus);
     } else {
         FqLinearDesc none = {};
         decode_m1_kernel<false><<<grid, WG_THREADS, lds, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                   count, total_tiles, tile_rows, flags);
+                                                                   count, total_tiles, tile_rows, flags, cus);
     }
     return hipGetLastError();
 }

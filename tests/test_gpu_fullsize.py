@@ -20,23 +20,26 @@ TOL_Y = 2e-3
 
 
 # Cost model of the batch-1 plan kernel's work partition (a byte of 8-bit codes costs 200, a 4-bit
-# byte 230, a 2-bit group 0.73 of a 4-bit one; units of 16 rows; one slice of the total per
-# workgroup, two workgroups per compute unit).  Only used to AIM samples at the rows where one
+# byte 230, a 2-bit group 0.73 and a 3-bit group 0.95 of a 4-bit one; units of 16 rows; one slice of
+# the total per workgroup; two workgroups per compute unit, three or four when 30 % or 90 % of the
+# cost is at 2 or 3 bits).  Only used to AIM samples at the rows where one
 # workgroup's share ends and the next begins: if the kernel's table changes, the rows checked here
 # are still valid samples, merely no longer the boundary ones.
 def _unit_cost(K, bits):
     groups = K // 128
-    return {2: groups * (64 * 230 * 730 // 1000), 4: groups * 64 * 230, 8: groups * 128 * 200,
-            16: groups * 256 * 200}[bits]
+    return {2: groups * (64 * 230 * 730 // 1000), 3: groups * (64 * 230 * 950 // 1000), 4: groups * 64 * 230,
+            8: groups * 128 * 200, 16: groups * 256 * 200}[bits]
 
 
-def _partition_boundary_rows(entries, pattern, workgroups):
+def _partition_boundary_rows(entries, pattern, cus):
     """{entry: rows on either side of every cut that falls inside it}, cuts as the kernel places
     them: workgroup b starts at cost b C / G."""
     units = [(N + 15) // 16 for (_, _, K, N) in entries]
     ucost = [_unit_cost(K, int(b)) for (_, _, K, N), b in zip(entries, pattern)]
     incl = np.cumsum([u * c for u, c in zip(units, ucost)], dtype=np.int64)
     C = int(incl[-1])
+    low = sum(u * c for u, c, b in zip(units, ucost, pattern) if int(b) in (2, 3))
+    workgroups = cus * (4 if low * 10 >= C * 9 else 3 if low * 10 >= C * 3 else 2)
     out = {}
     for b in range(1, workgroups):
         t = b * C // workgroups
@@ -94,7 +97,7 @@ def _check_stack(st, steps, n_entries, rows_per_entry, rng, boundary_entries=0):
             _check_rows(st, e, rows, int(pattern[e]), y)
         if boundary_entries:
             # the rows where the plan kernel's cost partition hands over from one workgroup to the next
-            cuts = _partition_boundary_rows(st.entries, pattern, 2 * torch.cuda.get_device_properties(0).multi_processor_count)
+            cuts = _partition_boundary_rows(st.entries, pattern, torch.cuda.get_device_properties(0).multi_processor_count)
             for e in rng.choice(sorted(cuts), size=min(boundary_entries, len(cuts)), replace=False):
                 y = st.ys[e].cpu().numpy().astype(np.float64)
                 _check_rows(st, int(e), sorted(cuts[int(e)])[:12], int(pattern[e]), y)
