@@ -233,8 +233,8 @@ int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *
  * Entry i computes ys[i] = linear(layers[i], bits_dev[i], xs[i]); arguments, limits, alignment and
  * errors as for fq_plan_create and fq_plan_run; count <= FQ_STATIC_MAX_ENTRIES (FQ_ERR_SHAPE
  * beyond).  The descriptor table, the tile queue and the entry lists live in a static device array
- * of the library (about 65 KiB, held on every device the library runs on until the process ends);
- * the table is written there by small kernels that carry it in their arguments, one launch per 32
+ * of the library (about 77 KiB, held on every device the library runs on until the process ends);
+ * the table is written there by small kernels that carry it in their arguments, one launch per 24
  * entries, ahead of the launch that computes.  Every call on a device shares that array: calls that
  * overlap in time on one device race (calls on one stream, or ordered by events, do not).  The
  * host-side handles in `layers` are read during the call only.
