@@ -9,11 +9,12 @@
 // table of independent linears (plan).  Rows are cut into tiles of `tile_rows`
 // (a multiple of 16: 4 wavefronts x chunks of 4 rows; small for a single linear
 // so that every CU gets work, large for a plan so that staging x is amortised);
-// tiles of all entries are numbered consecutively and workgroup b takes tiles
-// b, b + gridDim, ...  The bit-width of an entry is a
-// run-time value (host argument or device array): all three inner loops live
-// in the one kernel and the choice is a wavefront-uniform branch, so switching
-// precision per token costs a pointer select and nothing else.
+// a single linear's tiles are dealt round-robin (workgroup b takes tiles b,
+// b + gridDim, ...), a plan's rows are cut by cost (see "work partition" below).
+// The bit-width of an entry (2, 3, 4, 8 or 16) is a run-time value (host argument
+// or device array): all inner loops live in the one kernel and the choice is a
+// wavefront-uniform branch, so switching precision per token costs a pointer
+// select and nothing else.
 //
 // Streaming.  Inside a tile a wavefront walks items = (chunk of 4 rows, slice);
 // an item is four non-temporal 128-bit loads per lane plus the scale and zero
@@ -35,6 +36,10 @@
 // slice is scaled by s[n][g] and added to the row's accumulator.
 // 8-bit: v_perm_b32 places each byte under the exponent 0x64 (1024 + q), the
 // rest is the same.  16-bit: the halves are used as they are.
+// 2-bit and 3-bit: fields of a half that lie inside its mantissa read as offset +
+// code under the exponent that fits their place (the shared header has the layouts);
+// both are bound by the vector ALUs rather than by the stream, which is why a plan
+// launch lets more workgroups per compute unit take part when its bit-widths are low.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
