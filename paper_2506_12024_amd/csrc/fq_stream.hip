@@ -5,9 +5,9 @@
 // rows x 32 k, binary32 accumulation; two batch tiles above 16 rows).  Launches with few or
 // narrow tiles and single calls stay with the register-fed small-batch kernel.
 //
-// Work split.  A workgroup owns a tile of 256 weight rows and has ten wavefronts: eight
+// Work split.  A workgroup owns a tile of 256 weight rows and has twelve wavefronts: eight
 // consumers (two per SIMD, so that one computes while the other waits), 32 rows = 2 MFMA row
-// tiles each, and two loaders.
+// tiles each, and four loaders.
 //
 // Weight stream.  A stage is one 128-byte line of each of the consumer's 32 rows (256 / 128 /
 // 64 k at 4 / 8 / 16 bits); a load instruction covers 8 rows x 128 bytes, whole lines only
@@ -21,12 +21,18 @@
 // in flight while the step computes (three measured the same: the memory system is the limit,
 // not the depth).  These LDS reads are inline assembly: the compiler cannot tell a read of a
 // run-time slot from the slots being filled and would wait for every outstanding load first.
+// At the end of a tile the slots that the tile has no stage left for take the first stages of
+// the workgroup's next tile (whatever its bit-width), so the ring does not run dry across the
+// tile boundary.
 //
 // Loaders.  x and the metadata are what the stream cannot carry: a scale or zero-point fetch
 // per stage touches one cache line per row (64 tiny requests per instruction, more than the
-// weights themselves need), and the 4-bit path wants x permuted.  Two more wavefronts fetch
-// them with ordinary loads -- their own vmcnt, nobody else waits -- in chunks of 512 k, each
-// loader every other chunk, requested two chunk periods before they are due: x as 16-byte
+// weights themselves need), and the 4-bit path wants x permuted.  Four more wavefronts fetch
+// them with ordinary loads -- their own vmcnt, nobody else waits -- in chunks of 512 k, the
+// loaders taking the chunks in turn (a load returns behind everything the compute unit has
+// requested before it, 64 KiB of weights included, so that a loader turns a chunk round in 4 to
+// 5 us; at 4 bits the consumers use one up in 3), each requesting its next chunk as soon as
+// it has written one, and its first chunk of the next tile after its last of this one: x as 16-byte
 // blocks of 8 halves, one request of 1 KiB per batch row and chunk, stored [k block][batch
 // row] with the rows of k block kb XOR-ed by kb % 8 + 8 (kb / 32) -- conflict free for the
 // writer, whose lanes are k blocks (a 128-bit LDS write goes eight lanes at a time), and for the
@@ -35,8 +41,10 @@
 // same ones in all four groups, i.e. whatever the k block) -- zero past K, for the
 // 4-bit path permuted inside the block to the order the unpacking produces (x0 x4 x1 x5 x2 x6
 // x3 x7); scales and zero points for a pair of chunks at a time (8 units: 32 + 8 contiguous
-// bytes per row), stored [consumer][row][row tile][unit].  One barrier per chunk hands a
-// chunk over.
+// bytes per row), stored [consumer][row][row tile][unit].  Chunks are handed over through
+// counters in LDS, not through barriers (a barrier per chunk, two stages at 4 bits, makes every
+// consumer wait for the slowest of the eight and for the loaders each time); the workgroup
+// meets at one barrier per tile.
 //
 // Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is the
 // pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q; bytes go
@@ -64,7 +72,7 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int CONSUMERS = 8;
-constexpr int LOADERS = 2;
+constexpr int LOADERS = 4;                    // 2 or 4 (a workgroup of twelve wavefronts: three to a SIMD)
 constexpr int THREADS = (CONSUMERS + LOADERS) * 64;
 constexpr int RT = 2;                         // MFMA row tiles (16 rows) per consumer
 constexpr int TILE_ROWS = CONSUMERS * RT * 16;
@@ -75,6 +83,9 @@ constexpr int KC = 512;                       // k per chunk of x: one 16-byte b
 constexpr int UC = KC / 128;                  // units (quantization groups) per chunk
 constexpr int UP = 2 * UC;                    // units per metadata fetch: a pair of chunks
 // MT below: batch tiles of 16 rows (1 for M <= 16, 2 for M <= 32); an x buffer is 16 * MT * KC halves
+// x buffers: a consumer may be this many chunks minus one ahead of the slowest one (three is
+// what the metadata's two buffers of a pair of chunks allow; two batch tiles: LDS holds two)
+__host__ __device__ constexpr int nxb(int mt) { return mt == 1 ? 3 : 2; }
 
 // Workgroup barrier without the fence of __syncthreads() (which would wait for every
 // outstanding load, i.e. drain the rings); the waits that matter are issued explicitly.
@@ -105,13 +116,57 @@ struct Sel {
     int N, K;
 };
 
-// The workgroup's LDS.  x and metadata buffers come in pairs (chunk parity).
+// The workgroup's LDS.  Metadata buffers come in pairs (parity of the pair of chunks).
 struct Lds {
     uint8_t *ring;    // [CONSUMERS][NS][STAGE_BYTES]
-    uint8_t *x[2];    // [KC / 8][16 * MT] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 8 + 8 (kb / 32))
+    uint8_t *x;       // nxb(MT) buffers of [KC / 8][16 * MT] blocks of 16 bytes; k block kb holds batch row m at place m ^ (kb % 8 + 8 (kb / 32))
     float *ms[2];     // [CONSUMERS][16 rows][RT][UP] scales of a pair of chunks
     uint8_t *mz[2];   // same order, zero points
+    int *flag;        // hand-over counters: [li] chunks written by loader li, [4] tiles drawn, [8 + w] chunks finished by consumer w
+    int *mail;        // two tile records of 16 words, used in turn
 };
+
+// What a consumer has requested of its next tile while it finished the current one: the first
+// `pf` stages, stage s in ring slot (slot0 + s) % NS.
+struct Ahead {
+    int pf, slot0;
+};
+
+typedef int int2_t __attribute__((ext_vector_type(2)));
+
+// Hand-over of the x and metadata chunks between the loaders and the consumers without a
+// workgroup barrier (a barrier per chunk, every two stages at 4 bits, makes each consumer wait
+// for the slowest of the eight twice per 512 k).  Counters in LDS that only grow, chunks numbered
+// through the tiles of the launch: loader li stores 1 + the number of the last chunk it has
+// written, consumer w stores 1 + the number of the last chunk it has finished reading.  A
+// wavefront's LDS operations are carried out in the order it issues them, and each side has
+// waited for its own before it writes its counter.  The consumers' side is inline assembly for
+// the same reason as take().
+__device__ __forceinline__ void post(uint32_t addr, int value)
+{
+    if ((threadIdx.x & 63) == 0)
+        asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(value) : "memory");
+}
+
+// Until the loaders of chunk number need - 1 have written it (one batch tile: the loader of the
+// chunk's parity, whose counter is at `addr`; two: both, counters at addr and addr + 4).
+template <int MT>
+__device__ __forceinline__ void await_chunk(uint32_t addr, int need)
+{
+    for (;;) {
+        int v;
+        if (MT == 1) {
+            asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+        } else {
+            int2_t v2;
+            asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v2) : "v"(addr) : "memory");
+            v = min(v2.x, v2.y);
+        }
+        if (__builtin_amdgcn_readfirstlane(v) >= need)
+            break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
 
 // What a step holds in registers: the stage's weights (pieces c and c + 4 of the lane's line in
 // each row tile), the scales and zero points of the lane's row in each row tile for the stage's
@@ -298,11 +353,22 @@ struct Consumer {
     // 16 bits: blocks 4 h + c of an even stage, 8 + 4 h + c of an odd one
     uint32_t xq[4];
     float4_t acc[RT][MT], out[RT][MT];
+    const int base;        // number of the tile's first chunk in the launch's count
+    const int tileno;      // number of the tile among the workgroup's
+    // the next tile, looked up when the ring has room for it: 0 not yet, 1 to be requested, 2 not
+    // to be (none, passed over, or rows of no more than NS lines)
+    int nx_state;
+    const uint8_t *ncodes;
+    int nN, nrow_bytes, nrow0;
+    Ahead ahead;
 
-    __device__ __forceinline__ Consumer(const Sel &d_, const Lds &L_, int M_, int tile_row0, int wave_)
+    __device__ __forceinline__ Consumer(const Sel &d_, const Lds &L_, int M_, int tile_row0, int wave_, int base_,
+                                        int tileno_)
         : d(d_), L(L_), M(M_), wave(wave_), lane(threadIdx.x & 63), n(lane & 15), c(lane >> 4),
-          row0(tile_row0 + wave_ * RT * 16), row_bytes(d_.K * BITS / 8), nchunks((d_.K + KC - 1) / KC)
+          row0(tile_row0 + wave_ * RT * 16), row_bytes(d_.K * BITS / 8), nchunks((d_.K + KC - 1) / KC), base(base_), tileno(tileno_), nx_state(0),
+          ncodes(nullptr), nN(0), nrow_bytes(0), nrow0(0)
     {
+        ahead.pf = 0, ahead.slot0 = 0;
         T = (row_bytes + 127) / 128;
         ring = L.ring + wave * NS * STAGE_BYTES;
         // the wavefront's rows span at most 32 * row_bytes < 4 GiB: 32-bit lane offsets from a uniform base
@@ -350,6 +416,52 @@ struct Consumer {
             __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(base + off), (FQ_LDS void *)(dst + i * 1024), 16,
                                              0, 2 /* nt: the weights are read once */);
         }
+    }
+
+    // The ring slot `slot` has just been emptied and the tile has no stage left to put there:
+    // request the next tile's (same rows of the tile, lines from the start), so that the ring
+    // does not run dry across the tile boundary.  The next tile's record is in LDS once loader 1
+    // has counted its draw in flag[4]; if that has not happened yet, nothing is requested.
+    __device__ __forceinline__ void request_ahead(int slot)
+    {
+        if (nx_state == 0) {
+            int drawn;
+            asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(drawn) : "v"(lds_addr(L.flag) + 16u) : "memory");
+            if (__builtin_amdgcn_readfirstlane(drawn) < tileno + 2)
+                return;
+            u32x4 a, b; // words 0 .. 7 of the record: e, t, bits, N, K, codes
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(a), "=&v"(b)
+                         : "v"(lds_addr(L.mail) + 64u * ((tileno + 1) & 1))
+                         : "memory");
+            const int e = __builtin_amdgcn_readfirstlane((int)a.x), t = __builtin_amdgcn_readfirstlane((int)a.y),
+                      bits = __builtin_amdgcn_readfirstlane((int)a.z), K = __builtin_amdgcn_readfirstlane((int)b.x);
+            nN = __builtin_amdgcn_readfirstlane((int)a.w);
+            ncodes = (const uint8_t *)(uintptr_t)((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)b.y) |
+                                                  ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)b.z) << 32));
+            nrow_bytes = K * bits / 8;
+            nrow0 = t * TILE_ROWS + wave * RT * 16;
+            // (a row of more than NS lines: none of the first NS is a last, possibly half, line)
+            nx_state = e >= 0 && bits != 0 && nrow_bytes > NS * 128 ? 1 : 2;
+        }
+        if (nx_state != 1 || ahead.pf >= NS)
+            return;
+        if (ahead.pf == 0)
+            ahead.slot0 = slot;
+        const int first_row = min(nrow0, nN - 1);
+        const uint8_t *src = ncodes + (size_t)first_row * (size_t)nrow_bytes + (size_t)ahead.pf * 128;
+        uint8_t *dst = ring + slot * STAGE_BYTES;
+        const int r = lane >> 3, sl = lane & 7;
+#pragma unroll
+        for (int i = 0; i < SOPS; i++) { // as in the constructor and fetch(), for the next tile
+            const int rl = 8 * i + r;
+            const int piece = sl ^ (((rl & 15) >> 1) & 7);
+            const int row = min(nrow0 + rl, nN - 1);
+            const uint32_t off = (uint32_t)(row - first_row) * (uint32_t)nrow_bytes + (uint32_t)piece * 16;
+            __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(src + off), (FQ_LDS void *)(dst + i * 1024), 16, 0,
+                                             2);
+        }
+        ahead.pf++;
     }
 
     // One unit (128 k) of a 4-bit stage: half h of the line, x blocks a[mt * AM + i].
@@ -458,16 +570,16 @@ struct Consumer {
         }
     }
 
-    // Chunk ch, whose x and metadata are in the buffers of parity XB.
-    template <int XB>
-    __device__ __forceinline__ void chunk(int ch, int &fq, int &slot)
+    // Chunk ch, whose x is in buffer xb.
+    __device__ __forceinline__ void chunk(int ch, int xb, int &fq, int &slot)
     {
-        barrier(); // the loaders have written chunk ch; everybody is done with chunk ch - 1
+        // the loaders have written chunk ch
+        await_chunk<MT>(lds_addr(L.flag) + (MT == 1 ? 4u * (ch % LOADERS) : 8u * (ch % (LOADERS / 2))), base + ch + 1);
         // metadata: buffer of the pair of chunks, the chunk's half of it, the lane's row
         const uint32_t mo = ml * (RT * UP) + (ch & 1) * UC;
         const uint32_t sbase = lds_addr((ch & 2) ? L.ms[1] : L.ms[0]) + mo * 4,
                        zbase = lds_addr((ch & 2) ? L.mz[1] : L.mz[0]) + mo;
-        uint32_t xbase = lds_addr(L.x[XB]);
+        uint32_t xbase = lds_addr(L.x) + (uint32_t)xb * (16 * MT * KC * 2);
         asm volatile("" : "+s"(xbase)); // opaque: or every stage's x addresses are hoisted out of the tile and spill
 #pragma unroll
         for (int j = 0; j < C::SPC; j++) {
@@ -493,7 +605,7 @@ struct Consumer {
                 xa[2] = xa[3] = 0;
             }
             Stage st;
-            const int pend = __builtin_amdgcn_readfirstlane(fq - 1 - q); // younger stages in flight
+            const int pend = __builtin_amdgcn_readfirstlane(fq + ahead.pf - 1 - q); // younger stages in flight
             if (NS > 2 && pend >= 2)
                 take<BITS, MT, 2 * SOPS>(wa, wb, sa, za, xa, st);
             else if (pend == 1)
@@ -503,26 +615,29 @@ struct Consumer {
             if (fq < T) { // the stage NS steps ahead, into the slot just emptied
                 fetch(fq, slot);
                 fq++;
+            } else {
+                request_ahead(slot);
             }
             __builtin_amdgcn_sched_barrier(0); // keep the requests here: the scheduler sinks them otherwise
             compute(st, xa[0], xa[1], xa[2], xa[3]);
             slot = slot == NS - 1 ? 0 : slot + 1;
         }
+        post(lds_addr(L.flag) + 4u * (8 + wave), base + ch + 1); // every read of the chunk's buffers has returned
     }
 
-    __device__ __forceinline__ void run()
+    // `in`: what the tile before this one has requested of this one.
+    __device__ __forceinline__ Ahead run(const Ahead in)
     {
-        int fq = 0, slot = 0;
-        for (int s = 0; s < NS; s++)
+        int fq = in.pf, slot = in.pf ? in.slot0 : 0;
+        for (int s = in.pf; s < NS; s++)
             if (fq < T) {
-                fetch(fq, s);
+                fetch(fq, slot + s >= NS ? slot + s - NS : slot + s);
                 fq++;
             }
         __builtin_amdgcn_sched_barrier(0);
-        for (int ch = 0; ch < nchunks; ch += 2) {
-            chunk<0>(ch, fq, slot);
-            if (ch + 1 < nchunks)
-                chunk<1>(ch + 1, fq, slot);
+        for (int ch = 0, xb = 0; ch < nchunks; ch++) {
+            chunk(ch, xb, fq, slot);
+            xb = xb == nxb(MT) - 1 ? 0 : xb + 1;
         }
         // D layout of the 16x16 MFMA: lane holds column n = lane % 16, rows 4 * (lane / 16) + r.
 #pragma unroll
@@ -540,20 +655,31 @@ struct Consumer {
                 }
             }
         }
-        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0); the requests for the next tile stay in flight
         barrier(); // the loaders may refill the buffers for the next tile
+        return ahead;
     }
 };
 
 // ------------------------------------------------------------------ loader wavefront
-// (One code path for the three bit-widths: instantiated per width, the register allocator sees
-// three sets of staging registers live across the tile loop.)
-template <int MT, int LI>
+// (One code path for the three bit-widths, and one place each where a chunk is requested and
+// where it is written: instantiated per width or per place, the register allocator sees several
+// sets of staging registers live across the tile loop.)
+
+// The tile a loader writes chunks of, or requests them for.
+struct LoaderTile {
+    Sel d;
+    int tile_row0, G, nchunks, bits; // nchunks = 0: nothing to load (no tile, or one that is passed over)
+};
+
+template <int MT>
 struct Loader {
-    const Sel &d;
     const Lds &L;
-    const int M, lane, tile_row0, G, nchunks, BITS;
-    static constexpr int li = LI;
+    const int M, lane;
+    const int li; // which loader: 0 .. LOADERS - 1
+    // With one batch tile the loaders take the chunks in turn; with two, loader li takes batch
+    // tile li % 2 of every chunk (two loaders) or of every other chunk, those of parity li / 2.
+    const int bt; // the batch tile of this loader
     // the chunk's block `lane` of 16 batch rows (with two batch tiles: loader li takes tile li):
     // one 1 KiB request per row
     u32x4 xr[16];
@@ -562,13 +688,12 @@ struct Loader {
     float4_t sr[TILE_ROWS / 32];
     uint32_t zr[TILE_ROWS / 64][2];
 
-    __device__ __forceinline__ Loader(const Sel &d_, const Lds &L_, int M_, int tile_row0_, int bits)
-        : d(d_), L(L_), M(M_), lane(threadIdx.x & 63), tile_row0(tile_row0_), G(d_.K >> 7),
-          nchunks((d_.K + KC - 1) / KC), BITS(bits)
+    __device__ __forceinline__ Loader(const Lds &L_, int M_, int li_)
+        : L(L_), M(M_), lane(threadIdx.x & 63), li(li_), bt(MT == 2 ? li_ & 1 : 0)
     {
     }
 
-    __device__ __forceinline__ void load_x(int ch)
+    __device__ __forceinline__ void load_x(const LoaderTile &T, int ch)
     {
         const int k = ch * KC + lane * 8;
 
@@ -576,25 +701,25 @@ struct Loader {
         for (int m = 0; m < 16; m++) {
             // batch rows past M feed outputs that are never stored; k past K meets re-read weights
             // (the missing half of a last line): x is zero there
-            const int mm = min((MT == 2 ? 16 * LI : 0) + m, M - 1);
-            xr[m] = k < d.K ? *(const FQ_GLOBAL u32x4 *)(d.x + (size_t)mm * d.K + k) : u32x4{0u, 0u, 0u, 0u};
+            const int mm = min(16 * bt + m, M - 1);
+            xr[m] = k < T.d.K ? *(const FQ_GLOBAL u32x4 *)(T.d.x + (size_t)mm * T.d.K + k) : u32x4{0u, 0u, 0u, 0u};
         }
     }
 
-    __device__ __forceinline__ void store_x(int b)
+    __device__ __forceinline__ void store_x(int bits, int b)
     {
-        u32x4 *xb = reinterpret_cast<u32x4 *>(b ? L.x[1] : L.x[0]);
+        u32x4 *xb = reinterpret_cast<u32x4 *>(L.x + b * (16 * MT * KC * 2));
 #pragma unroll
         for (int m = 0; m < 16; m++) {
             u32x4 p = xr[m];
-            if (BITS == 4) { // (x0 .. x7) -> (x0 x4 x1 x5 x2 x6 x3 x7), the unpack order
+            if (bits == 4) { // (x0 .. x7) -> (x0 x4 x1 x5 x2 x6 x3 x7), the unpack order
                 p.x = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x05040100u);
                 p.y = __builtin_amdgcn_perm(xr[m].z, xr[m].x, 0x07060302u);
                 p.z = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x05040100u);
                 p.w = __builtin_amdgcn_perm(xr[m].w, xr[m].y, 0x07060302u);
             }
             // conflict free for the writer and for the readers
-            xb[lane * (16 * MT) + (MT == 2 ? 16 * LI : 0) + (m ^ ((lane & 7) | ((lane >> 2) & 8)))] = p;
+            xb[lane * (16 * MT) + 16 * bt + (m ^ ((lane & 7) | ((lane >> 2) & 8)))] = p;
         }
     }
 
@@ -602,16 +727,17 @@ struct Loader {
     // unit index is clamped, and then every unit is fetched on its own.  Addresses are a uniform
     // base plus a 32-bit lane offset, recomputed per call (kept opaque: hoisted out of the tile
     // they would cost a register each).
-    __device__ __forceinline__ void load_meta(int cp)
+    __device__ __forceinline__ void load_meta(const LoaderTile &T, int cp)
     {
         typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
         typedef uint32_t u32_a1 __attribute__((aligned(1)));
+        const int G = T.G;
         const int u0 = cp * UP;
         const bool whole = u0 + UP <= G;
-        int last = d.N - 1 - tile_row0; // rows of the tile past N repeat row N - 1
+        int last = __builtin_amdgcn_readfirstlane(T.d.N - 1 - T.tile_row0); // rows of the tile past N repeat row N - 1
         asm volatile("" : "+s"(last));
-        const float *sbase = d.scales + (size_t)tile_row0 * (size_t)G;
-        const uint8_t *zbase = d.zeros + (size_t)tile_row0 * (size_t)G;
+        const float *sbase = T.d.scales + (size_t)T.tile_row0 * (size_t)G;
+        const uint8_t *zbase = T.d.zeros + (size_t)T.tile_row0 * (size_t)G;
 #pragma unroll
         for (int i = 0; i < TILE_ROWS / 32; i++) {
             const uint32_t row = (uint32_t)min(32 * i + (lane >> 1), last);
@@ -659,96 +785,91 @@ struct Loader {
         }
     }
 
-    __device__ __forceinline__ void load(int ch)
+    __device__ __forceinline__ void load(const LoaderTile &T, int ch)
     {
-        load_x(ch);
-        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
-            load_meta(ch >> 1);
+        load_x(T, ch);
+        if (T.bits != 16 && (li & 1) == 0 && (ch & 1) == 0) // (with one batch tile: loaders 0 and 2 own the even chunks)
+            load_meta(T, ch >> 1);
     }
-    __device__ __forceinline__ void store(int ch)
+    __device__ __forceinline__ void store(int bits, int ch)
     {
-        store_x(ch & 1);
-        if (BITS != 16 && LI == 0 && (ch & 1) == 0)
+        store_x(bits, ch % nxb(MT));
+        if (bits != 16 && (li & 1) == 0 && (ch & 1) == 0)
             store_meta((ch >> 1) & 1);
     }
 
-    // One batch tile: loader li owns the chunks of parity li (loader 0 with them the metadata,
-    // whose pairs start at even chunks).  Chunk g + 1 is written while the consumers work on chunk
-    // g, and the owner then requests chunk g + 3 at once.  Two batch tiles: each loader owns one
-    // of them in every chunk and requests chunk g + 2 after writing chunk g + 1.
-    // `after_first(lane)` is called once, after the barrier that hands over the first chunk and
-    // after this wavefront's work that follows it: the place where a loader has time to spare.
-    template <class F>
-    __device__ __forceinline__ void run(F after_first)
+    // Until every consumer has finished the chunk numbered need - 1.
+    __device__ __forceinline__ void await_consumers(int need)
     {
-        constexpr int STEP = MT == 1 ? 2 : 1; // distance between the chunks of one loader
-        const int c0 = MT == 1 ? li : 0;
-        if (c0 < nchunks)
-            load(c0);
-        if (c0 == 0) {
-            store(0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (STEP < nchunks)
-                load(STEP);
+        const volatile FQ_LDS int *done = (const volatile FQ_LDS int *)(L.flag + 8);
+        for (;;) {
+            const int v = lane < CONSUMERS ? done[lane] : 0x7fffffff;
+            if (!__ballot(v < need))
+                break;
+            __builtin_amdgcn_s_sleep(1);
         }
-        for (int g = 0; g < nchunks; g++) {
-            __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): this wavefront's LDS writes are done
-            barrier();
-            if (g + 1 < nchunks && (MT == 2 || ((g + 1) & 1) == li)) {
-                store(g + 1);
-                __builtin_amdgcn_sched_barrier(0); // the registers are reused: no load before the last write
-                if (g + 1 + STEP < nchunks)
-                    load(g + 1 + STEP);
-            }
-            if (g == 0)
-                after_first(lane);
-        }
-        barrier(); // the consumers have stored the tile
+    }
+
+    // Chunk c of the tile whose chunks start at number `base`, from the registers into LDS.  It
+    // goes into the x buffer that chunk c - nxb(MT) was read from (the metadata of a pair of
+    // chunks into the buffer of the pair before the last): written once every consumer has
+    // finished that one.
+    __device__ __forceinline__ void write(int bits, int base, int c)
+    {
+        if (c >= nxb(MT))
+            await_consumers(base + c - nxb(MT) + 1);
+        store(bits, c);
+        __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): the chunk is in LDS
+        if (lane == 0)
+            ((volatile FQ_LDS int *)L.flag)[li] = base + c + 1;
+        __builtin_amdgcn_sched_barrier(0); // the registers are reused: no load before the last write
     }
 };
 
-// One tile (rows 256 t .. of entry e), as seen by a loader (ROLE = 1 + li) or by a consumer
-// (ROLE = 0).  Returns false if the entry's selected width is not one of this kernel's or not
-// attached (uniform over the workgroup: nothing is run, no barrier).  Loader 1 calls
-// `after_first` (see Loader::run).
-template <int MT, int ROLE, class F>
-__device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_t *bits_dev, int e, int t, int M,
-                                         const Lds &L, int wave, F after_first)
-{
-    const FqLinearDesc *dp = &table[e];
-    const int bits = bits_dev[e];
+// A tile as the workgroup's wavefronts find it in LDS: entry, tile of 256 rows, the selected
+// bit-width (0: pass the tile over -- no such width in this kernel, or no copy of it attached)
+// and the operands that go with it.  Sixteen words.
+struct Tile {
+    int e, t, bits;
     Sel d;
-    d.N = dp->N;
-    d.K = dp->K;
-    d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-    d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-    d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
-    d.x = dp->x;
-    d.y = dp->y;
-    if (!d.codes)
-        return false;
-    // All wavefronts run the tile (rows past N are clamped on load and masked on store) so
-    // that every one of them reaches the barriers: one per chunk and one at the end.
-    const int tile_row0 = t * TILE_ROWS;
-    if (ROLE > 0) {
-        constexpr int LI = ROLE > 0 ? ROLE - 1 : 0;
-        if constexpr (LI == 1)
-            Loader<MT, LI>(d, L, M, tile_row0, bits).run(after_first);
-        else
-            Loader<MT, LI>(d, L, M, tile_row0, bits).run([](int) {});
-    } else {
-        if (bits == 4)
-            Consumer<4, MT>(d, L, M, tile_row0, wave).run();
-        else if (bits == 8)
-            Consumer<8, MT>(d, L, M, tile_row0, wave).run();
-        else
-            Consumer<16, MT>(d, L, M, tile_row0, wave).run();
+};
+
+__device__ __forceinline__ void write_tile(int *mail, int e, int t, int bits, const Sel &d)
+{
+    volatile FQ_LDS int *m = (volatile FQ_LDS int *)mail;
+    const uint64_t p[5] = {(uint64_t)(uintptr_t)d.codes, (uint64_t)(uintptr_t)d.scales, (uint64_t)(uintptr_t)d.zeros,
+                           (uint64_t)(uintptr_t)d.x, (uint64_t)(uintptr_t)d.y};
+    m[0] = e, m[1] = t, m[2] = bits, m[3] = d.N, m[4] = d.K;
+#pragma unroll
+    for (int i = 0; i < 5; i++) {
+        m[5 + 2 * i] = (int)(uint32_t)p[i];
+        m[6 + 2 * i] = (int)(uint32_t)(p[i] >> 32);
     }
-    return true;
+}
+
+__device__ __forceinline__ Tile read_tile(const int *mail)
+{
+    const volatile FQ_LDS int *m = (const volatile FQ_LDS int *)mail;
+    int w[15];
+#pragma unroll
+    for (int i = 0; i < 15; i++)
+        w[i] = __builtin_amdgcn_readfirstlane(m[i]);
+    auto ptr = [&](int i) { return (uintptr_t)((uint64_t)(uint32_t)w[5 + 2 * i] | ((uint64_t)(uint32_t)w[6 + 2 * i] << 32)); };
+    Tile T;
+    T.e = w[0], T.t = w[1], T.bits = w[2];
+    T.d.N = w[3], T.d.K = w[4];
+    T.d.codes = (const uint8_t *)ptr(0);
+    T.d.scales = (const float *)ptr(1);
+    T.d.zeros = (const uint8_t *)ptr(2);
+    T.d.x = (const uint16_t *)ptr(3);
+    T.d.y = (uint16_t *)ptr(4);
+    return T;
 }
 
 // The tiles of one workgroup: the roles walk the same tiles in separate loops so that neither
-// carries the other's registers.
+// carries the other's registers.  All wavefronts run every tile (rows past N are clamped on load
+// and masked on store) so that every one of them takes part in the hand-over of every chunk and
+// reaches the barrier at the end.
 //
 // Workgroups are dealt to the 8 XCDs in turn.  Tiles are handed out so that an XCD takes runs of
 // XCD_RUN consecutive tiles: the x of a linear is then fetched into a few L2s rather than into all
@@ -762,61 +883,174 @@ __device__ __forceinline__ bool run_tile(const FqLinearDesc *table, const int32_
 // (entries at a width that is not attached, or at 2 bits, which another kernel runs, cost
 // nothing).  Loader 1 draws the next tile while the current one runs, at a point where it would
 // otherwise wait for the consumers (the round trip of the atomic is not hidden anywhere on the
-// way into a tile), looks up its entry, and leaves both in LDS (`mail`): everybody reads them at
-// the top of a tile, they are replaced after the tile's first chunk barrier, and read again
-// after the barrier that ends the tile.  The last workgroup to finish puts the cursors back to
-// zero for the next launch.
-template <int MT, int ROLE> // ROLE: 0 = consumer, 1 + li = loader li
-__device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int count,
-                                          int total_tiles, int M, const Lds &L, int wave, int *queue,
-                                          const int2 *order, int *mail)
+// way into a tile), looks up its entry and the operands of the entry's selected width, and leaves
+// them in LDS (`mail`, two records used in turn): everybody reads a tile's record after the
+// barrier that ends the tile before it -- LDS, not two dependent reads of device memory, stands
+// between that barrier and the tile's first requests -- and the other record is written during
+// the tile.  The loaders read it before that barrier (the others once loader 1 has counted the
+// draw in flag[4]) and request their first chunk of the next tile, and so do the consumers, if
+// the draw has been counted by then, for the first stages of their next tile.  The last workgroup to finish
+// puts the cursors back to zero for the next launch.
+template <int MT, int ROLE> // ROLE: 0 = consumer, 1 = loader
+__device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32_t *bits_dev, int M, const Lds &L,
+                                          int wave, int *queue, const int2 *order, int *mail)
 {
     constexpr int XCD_RUN = 8;
+    const int li = wave - CONSUMERS; // a loader's number
+    const bool draws = ROLE == 1 && li == 1;
     const int grid = gridDim.x;
     const int xcd = blockIdx.x & 7;
     const int listed_tiles = queue[FQ_Q_TILES], entries = queue[FQ_Q_ENTRIES];
-    auto draw = [&](int lane) { // whole wavefront
+    int drawn = 0;
+    auto draw = [&](int lane, int *rec) { // whole wavefront; rec: the record to fill
         int q = 0;
         if (lane == 0)
             q = __hip_atomic_fetch_add(&queue[xcd], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         q = __builtin_amdgcn_readfirstlane(q);
         // the XCD's q-th tile: tile q % XCD_RUN of its run number q / XCD_RUN
         const int v = ((q / XCD_RUN) * 8 + xcd) * XCD_RUN + q % XCD_RUN;
-        if (v >= listed_tiles) {
-            if (lane == 0)
-                *(volatile int *)mail = -1;
-        } else {
-            for (int base = 0; base < entries; base += 64) { // the entry whose tiles [first, next first) hold v
-                const int r = base + lane;
+        int e = -1, t = 0;
+        if (v < listed_tiles) {
+            for (int first = 0; first < entries; first += 64) { // the entry whose tiles [first, next first) hold v
+                const int r = first + lane;
                 const int2 o = r < entries ? order[r] : make_int2(0x7fffffff, 0);
                 const int next = r + 1 < entries ? order[r + 1].x : listed_tiles;
-                const bool hit = r < entries && o.x <= v && v < next;
+                const uint64_t hit = __ballot(r < entries && o.x <= v && v < next);
                 if (hit) {
-                    ((volatile int *)mail)[0] = o.y;
-                    ((volatile int *)mail)[1] = v - o.x;
-                }
-                if (__ballot(hit))
+                    const int src = __builtin_ctzll(hit);
+                    e = __shfl(o.y, src, 64);
+                    t = v - __shfl(o.x, src, 64);
                     break;
+                }
             }
+        }
+        e = __builtin_amdgcn_readfirstlane(e);
+        t = __builtin_amdgcn_readfirstlane(t);
+        Sel d;
+        d.codes = nullptr, d.scales = nullptr, d.zeros = nullptr, d.x = nullptr, d.y = nullptr, d.N = 0, d.K = 0;
+        int bits = 0;
+        if (e >= 0) {
+            const FqLinearDesc *dp = &table[e];
+            bits = bits_dev[e];
+            d.N = dp->N;
+            d.K = dp->K;
+            d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
+            d.scales = bits == 4 ? dp->scales4 : dp->scales8;
+            d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+            d.x = dp->x;
+            d.y = dp->y;
+            if (!d.codes)
+                bits = 0;
+        }
+        drawn++;
+        if (lane == 0) {
+            write_tile(rec, e, t, bits, d);
+            ((volatile FQ_LDS int *)L.flag)[4] = drawn; // after the record: a wavefront's LDS writes keep their order
         }
         __builtin_amdgcn_s_waitcnt(0xc07f); // lgkmcnt(0): written before this wavefront's next barrier
     };
-    if (ROLE == 2)
-        draw(threadIdx.x & 63);
+    if (draws)
+        draw(threadIdx.x & 63, mail);
     __syncthreads();
-    for (;;) {
-        const int e = __builtin_amdgcn_readfirstlane(((volatile int *)mail)[0]);
-        const int t = __builtin_amdgcn_readfirstlane(((volatile int *)mail)[1]);
-        if (e < 0)
-            break;
-        if (!run_tile<MT, ROLE>(table, bits_dev, e, t, M, L, wave, draw)) {
-            __syncthreads(); // a tile that is passed over: everybody has read, then the next one is drawn
-            if (ROLE == 2)
-                draw(threadIdx.x & 63);
-            __syncthreads();
+    int base = 0; // chunks of the tiles run so far
+    if (ROLE == 0) {
+        Tile cur = read_tile(mail);
+        Ahead ahead;
+        ahead.pf = 0, ahead.slot0 = 0;
+        for (int par = 0, tileno = 0; cur.e >= 0; par ^= 1, tileno++) {
+            if (cur.bits == 0) {
+                __syncthreads(); // a tile that is passed over
+            } else {
+                const int tile_row0 = cur.t * TILE_ROWS;
+                if (cur.bits == 4)
+                    ahead = Consumer<4, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
+                else if (cur.bits == 8)
+                    ahead = Consumer<8, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
+                else
+                    ahead = Consumer<16, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
+                base += (cur.d.K + KC - 1) / KC;
+            }
+            cur = read_tile(mail + 16 * (par ^ 1));
+        }
+    } else {
+        // One batch tile: loader li owns the chunks li, li + LOADERS, ... (the owner of an even
+        // chunk with it the metadata, whose pairs start at even chunks) and requests its next
+        // chunk as soon as it has written one.  Two batch tiles: loader li owns batch tile li % 2
+        // of the chunks li / 2, li / 2 + LOADERS / 2, ...  After its last chunk of a tile a loader
+        // requests its first chunk of the next tile (a request made at the start of a tile would
+        // return behind the 64 KiB of weights that the consumers ask for at the same moment, and
+        // they would wait for it), from the same place in the code: the walk starts with a tile
+        // of no chunks before the first one, and a tile that is passed over is one of no chunks.
+        // Loader 1 draws the tile after the current one once it has written its first chunk and
+        // requested its second -- where it has time to spare -- or, in a tile where its first
+        // turn is the last, before the request.
+        constexpr int STEP = MT == 1 ? LOADERS : LOADERS / 2; // distance between the chunks of one loader
+        const int c0 = MT == 1 ? li : li >> 1;
+        auto as_loader_tile = [&](const Tile &T) {
+            LoaderTile A;
+            A.d = T.d;
+            A.tile_row0 = T.t * TILE_ROWS;
+            A.G = T.d.K >> 7;
+            A.bits = T.bits;
+            A.nchunks = T.e >= 0 && T.bits ? (T.d.K + KC - 1) / KC : 0;
+            return A;
+        };
+        Loader<MT> ld(L, M, li);
+        LoaderTile A; // the current tile; at first: none
+        A.d.codes = nullptr, A.d.scales = nullptr, A.d.zeros = nullptr, A.d.x = nullptr, A.d.y = nullptr;
+        A.d.N = 0, A.d.K = 0, A.tile_row0 = 0, A.G = 0, A.nchunks = 0, A.bits = 0;
+        bool real = false;
+        // record of the tile after A: tile number i of the workgroup is in record i % 2
+        for (int par = 1, tileno = -1;; par ^= 1, tileno++) {
+            int *rec = mail + 16 * (par ^ 1);
+            Tile T; // the tile after A, read on A's last turn
+            T.e = -1, T.t = 0, T.bits = 0, T.d = A.d;
+            LoaderTile B = A;
+            for (int c = c0;; c += STEP) {
+                const bool last = c + STEP >= A.nchunks;
+                if (c < A.nchunks)
+                    ld.write(A.bits, base, c);
+                if (last) { // what comes after A
+                    if (draws && real && c == c0)
+                        draw(threadIdx.x & 63, rec);
+                    if (!draws) // until loader 1 has drawn it
+                        while (__builtin_amdgcn_readfirstlane(((volatile FQ_LDS int *)L.flag)[4]) < tileno + 2)
+                            __builtin_amdgcn_s_sleep(1);
+                    T = read_tile(rec);
+                    B = as_loader_tile(T);
+                }
+                // (field by field: a choice between the two objects would keep both in memory)
+                LoaderTile from;
+                from.d.codes = nullptr, from.d.y = nullptr;
+                from.d.x = last ? B.d.x : A.d.x;
+                from.d.scales = last ? B.d.scales : A.d.scales;
+                from.d.zeros = last ? B.d.zeros : A.d.zeros;
+                from.d.N = last ? B.d.N : A.d.N;
+                from.d.K = last ? B.d.K : A.d.K;
+                from.tile_row0 = last ? B.tile_row0 : A.tile_row0;
+                from.G = last ? B.G : A.G;
+                from.nchunks = last ? B.nchunks : A.nchunks;
+                from.bits = last ? B.bits : A.bits;
+                const int ch = last ? c0 : c + STEP;
+                if (ch < from.nchunks)
+                    ld.load(from, ch);
+                if (draws && real && c == c0 && !last)
+                    draw(threadIdx.x & 63, rec);
+                if (last)
+                    break;
+            }
+            if (real) {
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+                barrier(); // the consumers have stored the tile and read its last chunk (or pass it over)
+                base += A.nchunks;
+            }
+            if (T.e < 0)
+                break;
+            A = B;
+            real = true;
         }
     }
-    if (ROLE == 2 && (threadIdx.x & 63) == 0) {
+    if (draws && (threadIdx.x & 63) == 0) {
         const int done = __hip_atomic_fetch_add(&queue[FQ_Q_DONE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (done == grid - 1) { // every workgroup has drawn its last tile
             for (int i = 0; i <= FQ_Q_DONE; i++)
@@ -902,23 +1136,26 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
                                                                 int total_tiles, int M, int *queue,
                                                                 const int2 *__restrict__ order)
 {
-    __shared__ int mail[2];
+    __shared__ __attribute__((aligned(16))) int mail[32];
+    __shared__ __attribute__((aligned(8))) int flag[16];
     __shared__ __attribute__((aligned(1024))) uint8_t ring[CONSUMERS * NS * STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) uint8_t x0[16 * MT * KC * 2], x1[16 * MT * KC * 2];
+    __shared__ __attribute__((aligned(1024))) uint8_t xbuf[nxb(MT) * 16 * MT * KC * 2];
     __shared__ __attribute__((aligned(256))) float ms0[UP * TILE_ROWS], ms1[UP * TILE_ROWS];
     __shared__ __attribute__((aligned(256))) uint8_t mz0[UP * TILE_ROWS], mz1[UP * TILE_ROWS];
     Lds L;
     L.ring = ring;
-    L.x[0] = x0, L.x[1] = x1;
+    L.x = xbuf;
     L.ms[0] = ms0, L.ms[1] = ms1;
     L.mz[0] = mz0, L.mz[1] = mz1;
+    L.flag = flag;
+    L.mail = mail;
+    if (threadIdx.x < 16)
+        flag[threadIdx.x] = 0; // before the barrier that run_tiles starts with
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (wave == CONSUMERS)
-        run_tiles<MT, 1>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
-    else if (wave > CONSUMERS)
-        run_tiles<MT, 2>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
+    if (wave >= CONSUMERS)
+        run_tiles<MT, 1>(table, bits_dev, M, L, wave, queue, order, mail);
     else
-        run_tiles<MT, 0>(table, bits_dev, count, total_tiles, M, L, wave, queue, order, mail);
+        run_tiles<MT, 0>(table, bits_dev, M, L, wave, queue, order, mail);
 }
 
 } // namespace
@@ -929,6 +1166,7 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
 // queue hands out runs of 8 tiles to the 8 XCDs in turn: the grid (one workgroup per compute unit)
 // must be a multiple of 64, which the plan's layout sees to (other devices get smaller tiles and
 // the register-fed kernel).
+
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count, int total_tiles,
                                    int M, int cus, int *queue, void *order, hipStream_t stream)
 {
