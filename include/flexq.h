@@ -173,16 +173,14 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *              descriptor table is copied into it on `stream` by fq_plan_create, which waits for
  *              that copy (the only work it enqueues).  After the
  *              table come the tile queue of the streaming batch kernel, zeroed by
- *              fq_plan_create and left zeroed by every run, and the lists of entries a run
+ *              fq_plan_create and left zeroed by every run, and the list of entries a run
  *              draws up for its bit-widths: runs of one plan must not overlap in time
  *              (they would share these, and they write the same ys)
  *   bits_dev   device, int32 [count], each 2, 3, 4, 8 or 16 and attached to its layer;
  *              an entry whose value is anything else (or 3 in a plan with M > 1) is skipped
  *              by the kernel and its y is left untouched.  Such a run sets bit 0 of the plan's
  *              flags, a word in the workspace that stays set and that fq_plan_status reports
- *              (gave_up is always 0 for these plans).  A large plan with M > 1 whose layers carry
- *              2-bit copies runs as two kernels (the streaming batch kernel takes 4, 8 and
- *              16 bits; the entries that are at 2 bits follow on the register-fed one)
+ *              (gave_up is always 0 for these plans)
  */
 size_t fq_plan_workspace_bytes(int count);
 int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers,
@@ -233,7 +231,7 @@ int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *
  * Entry i computes ys[i] = linear(layers[i], bits_dev[i], xs[i]); arguments, limits, alignment and
  * errors as for fq_plan_create and fq_plan_run; count <= FQ_STATIC_MAX_ENTRIES (FQ_ERR_SHAPE
  * beyond).  The descriptor table, the tile queue and the entry lists live in a static device array
- * of the library (about 77 KiB, held on every device the library runs on until the process ends);
+ * of the library (about 73 KiB, held on every device the library runs on until the process ends);
  * the table is written there by small kernels that carry it in their arguments, one launch per 24
  * entries, ahead of the launch that computes.  Every call on a device shares that array: calls that
  * overlap in time on one device race (calls on one stream, or ordered by events, do not).  The

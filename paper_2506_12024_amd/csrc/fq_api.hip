@@ -61,7 +61,7 @@ struct fq_plan {
     long long wait_limit;           // polls a workgroup spends on one stage boundary before it gives up
     const FqLinearDesc *table_dev;
     int *queue_dev;  // after the table: per-XCD tile cursors, a count of finished workgroups, list totals
-    void *order_dev; // after the queue: two lists of two ints per entry
+    void *order_dev; // after the queue: a list of two ints per entry
 };
 
 namespace {
@@ -324,9 +324,9 @@ size_t fq_plan_workspace_bytes(int count)
 {
     if (count < 1)
         return 0;
-    // the descriptor table, then 256 bytes for the tile queue of the streaming batch kernel and two
-    // lists of 8 bytes per entry: what a launch runs under its bit-widths
-    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256 + ((size_t)count * 16 + 255) / 256 * 256;
+    // the descriptor table, then 256 bytes for the tile queue of the streaming batch kernel and a
+    // list of 8 bytes per entry: what a launch runs under its bit-widths
+    return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256 + 256 + ((size_t)count * 8 + 255) / 256 * 256;
 }
 
 } // extern "C"
@@ -377,27 +377,19 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
     // XCDs of 8 x k compute units: a device of another shape stays with the register-fed kernel
     if (M > 1 && rows == 256 && fq_device_cus() % 64 != 0)
         rows = 128;
-    // The streaming kernel (plans of 256-row tiles at M > 1) takes 4, 8 and 16 bits and passes over
-    // every entry at another width: a plan of its size that holds a 2-bit copy, whose entries may be
-    // switched to it at any token, runs in two launches, the second one the register-fed kernel over
-    // the entries that are at 2 bits, in 128-row tiles of a numbering of their own.
-    const bool split = M > 1 && has2 && rows == 256;
     if (M > 1 && has2 && rows == 16) // the K-split kernel for launches with few rows has no 2-bit path
         rows = 64;
-    long long tiles = 0, tiles2 = 0;
+    long long tiles = 0;
     for (int i = 0; i < count; i++) {
         fill_desc(table[i], layers[i], xs[i], ys[i]);
         table[i].tile_begin = (int)tiles;
         tiles += (layers[i]->N + rows - 1) / rows;
-        if (split)
-            tiles2 += (layers[i]->N + 127) / 128;
-        if (tiles > 0x7fffffffLL || tiles2 > 0x7fffffffLL)
+        if (tiles > 0x7fffffffLL)
             return fail(FQ_ERR_SHAPE, "%s: too many row tiles", who);
     }
     geom->count = count;
     geom->M = M;
     geom->total_tiles = (int)tiles;
-    geom->total_tiles2 = (int)tiles2;
     geom->max_K = max_K;
     geom->tile_rows = rows;
     return FQ_OK;
@@ -411,8 +403,6 @@ hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, in
                            queue_dev ? queue_dev + FQ_Q_FLAGS : nullptr, stream)
         : fq_launch_skinny(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.M, queue_dev,
                            order_dev, stream);
-    if (e == hipSuccess && g.total_tiles2 > 0)
-        e = fq_launch_skinny_second(table_dev, bits_dev, g.count, g.total_tiles2, g.M, queue_dev, order_dev, stream);
     return e;
 }
 

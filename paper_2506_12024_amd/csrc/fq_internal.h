@@ -33,7 +33,6 @@ struct FqLinearDesc {
 // Geometry of a plan: how its entries are cut into row tiles for the kernel that serves its M.
 struct FqPlanGeom {
     int count, M, total_tiles, tile_rows, max_K;
-    int total_tiles2; // 128-row tiles of the second pass of a split batched plan, else 0
 };
 struct fq_layer;
 // Records a message for fq_last_error() on the calling thread and returns `code`.
@@ -88,19 +87,14 @@ hipError_t fq_launch_decode_staged(const FqLinearDesc *table_dev, const int32_t 
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
                             int total_tiles, int tile_rows, int M, int *queue, void *order, hipStream_t stream);
-// Second pass of a split batched plan: the entries whose bit-width is 2, in 128-row tiles, as
-// listed by plan_order_kernel in the launch of the streaming kernel before it (`queue`, `order`:
-// the plan's; total_tiles2: the most there can be).
-hipError_t fq_launch_skinny_second(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                                   int total_tiles2, int M, const int *queue, const void *order, hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
 // Streaming variant for plan launches with 2 <= M <= 32 and tiles of 256 rows (fq_launch_skinny
 // hands those to it).
 hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
                                    int total_tiles, int M, int cus, int *queue, void *order, hipStream_t stream);
 // The plan's queue words (ints): a tile cursor per XCD, the count of workgroups that have finished,
-// then what plan_order_kernel leaves for the launches that follow it: tiles and entries of the
-// streaming kernel's list, tiles and entries of the second pass's list.
+// then what plan_order_kernel leaves for the launch that follows it: tiles and entries of the
+// streaming kernel's list.
 constexpr int FQ_Q_DONE = 8, FQ_Q_TILES = 9, FQ_Q_ENTRIES = 10;
 // ... and, apart from those, a sticky word of flags that fq_plan_status reports: bit 0 = an entry's
 // bit-width was not one the plan serves, or had no copy attached, in some run (its y was left untouched)

@@ -15,7 +15,7 @@ namespace {
 
 constexpr size_t TABLE_BYTES = ((size_t)FQ_STATIC_MAX_ENTRIES * sizeof(FqLinearDesc) + 255) / 256 * 256;
 constexpr size_t QUEUE_BYTES = 256;
-constexpr size_t ORDER_BYTES = ((size_t)FQ_STATIC_MAX_ENTRIES * 16 + 255) / 256 * 256;
+constexpr size_t ORDER_BYTES = ((size_t)FQ_STATIC_MAX_ENTRIES * 8 + 255) / 256 * 256;
 constexpr size_t SCRATCH_BYTES = TABLE_BYTES + QUEUE_BYTES + ORDER_BYTES;
 
 } // namespace

@@ -579,22 +579,14 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
                                                                    int bits_host,
                                                                    const FqLinearDesc *__restrict__ table,
                                                                    const int32_t *__restrict__ bits_dev,
-                                                                   int count, int total_tiles, int M,
-                                                                   const int *__restrict__ queue,
-                                                                   const int2 *__restrict__ list, int *flags)
+                                                                   int count, int total_tiles, int M, int *flags)
 {
-    // `list` (with `queue`): the pass over the 2-bit entries of a plan whose other entries the
-    // streaming kernel has run, as listed for this launch's bit-widths by plan_order_kernel:
-    // list[r] = (first tile of the r-th such entry, entry), queue[FQ_Q_TILES + 2] tiles in all
     __shared__ uint4 lds_x[(Chunk<MT>::KC / 8) * 16 * MT];
     __shared__ float lds_s[WAVES][RT * Chunk<MT>::GROUPS * 16];
     __shared__ uint8_t lds_z[WAVES][RT * Chunk<MT>::GROUPS * 16];
     constexpr int TILE_ROWS = WAVES * RT * 16;
     const int wave = threadIdx.x >> 6;
-    int e = 0, r = 0;
-    const int listed = list ? queue[FQ_Q_ENTRIES + 2] : 0;
-    if (list)
-        total_tiles = queue[FQ_Q_TILES + 2];
+    int e = 0;
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         const FqLinearDesc *dp;
         int bits, t; // t: the tile inside its entry
@@ -602,15 +594,6 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
             dp = &single;
             bits = bits_host;
             t = tile;
-        } else if (list) {
-            while (r + 1 < listed && tile >= list[r + 1].x)
-                r++;
-            e = list[r].y;
-            dp = &table[e];
-            bits = bits_dev[e];
-            t = tile - list[r].x;
-            if (bits != 2)
-                continue; // (not listed otherwise; uniform over the workgroup)
         } else {
             while (e + 1 < count && tile >= table[e + 1].tile_begin)
                 e++;
@@ -656,17 +639,17 @@ int resident(int cus)
 template <int MT, int RT>
 hipError_t launch(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
                   const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
-                  hipStream_t stream, const int *queue = nullptr, const int2 *list = nullptr, int *flags = nullptr)
+                  hipStream_t stream, int *flags = nullptr)
 {
     const int cap = resident<MT, RT>(cus);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
         decode_skinny_kernel<true, MT, RT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr,
-                                                                           nullptr, 1, total_tiles, M, nullptr, nullptr, nullptr);
+                                                                           nullptr, 1, total_tiles, M, nullptr);
     } else {
         FqLinearDesc none = {};
         decode_skinny_kernel<false, MT, RT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                            count, total_tiles, M, queue, list, flags);
+                                                                            count, total_tiles, M, flags);
     }
     return hipGetLastError();
 }
@@ -725,25 +708,14 @@ hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                        : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
     if (M <= 16) {
         if (rt == 4)
-            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
+            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
         if (rt == 2)
-            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
-        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
+            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
     }
     if (rt == 4)
-        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
+        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
     if (rt == 2)
-        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
-    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, nullptr, nullptr, fl);
-}
-
-hipError_t fq_launch_skinny_second(const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                                   int total_tiles2, int M, const int *queue, const void *order, hipStream_t stream)
-{
-    if (total_tiles2 <= 0)
-        return hipSuccess;
-    const int cus = device_cus();
-    const int2 *list = (const int2 *)order + count; // plan_order_kernel's second list
-    return M <= 16 ? launch<1, 2>(nullptr, 0, descs_dev, bits_dev, count, total_tiles2, M, cus, stream, queue, list)
-                   : launch<2, 2>(nullptr, 0, descs_dev, bits_dev, count, total_tiles2, M, cus, stream, queue, list);
+        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
 }

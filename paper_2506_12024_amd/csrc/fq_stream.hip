@@ -9,8 +9,8 @@
 // consumers (two per SIMD, so that one computes while the other waits), 32 rows = 2 MFMA row
 // tiles each, and four loaders.
 //
-// Weight stream.  A stage is one 128-byte line of each of the consumer's 32 rows (256 / 128 /
-// 64 k at 4 / 8 / 16 bits); a load instruction covers 8 rows x 128 bytes, whole lines only
+// Weight stream.  A stage is one 128-byte line of each of the consumer's 32 rows (512 / 256 /
+// 128 / 64 k at 2 / 4 / 8 / 16 bits); a load instruction covers 8 rows x 128 bytes, whole lines only
 // (halves of a line requested apart are fetched from HBM twice more often than not), marked
 // non-temporal (read once).  Stages go from global memory straight into a wavefront-private
 // LDS ring of two slots with direct-to-LDS loads (global_load_lds_dwordx4): no register
@@ -53,6 +53,12 @@
 // that the accumulator holds sum x (q - z) over the stage (every product is exact in
 // binary32), which is folded as out += s * acc -- Eq. (3) with the scale factored out of the
 // group.  The vector ALUs are left with the unpacking (5 instructions per 8 four-bit weights).
+// At 2 bits a stage is four units; an MFMA's 32 k are 8 bytes of a line, 2 from each group of 16
+// lanes, so a lane reads its 8 bytes of every unit (not 16 contiguous ones, which would put two
+// units into one MFMA's sum); a byte holds four consecutive codes, which one v_perm_b32 copies to
+// both halves of a word and two and-or instructions turn into the pairs (1024 + q0, 256 + q1) and
+// (64 + q2, 16 + q3) -- x stays in its natural order -- and the constant operand carries the four
+// offsets by position.  A stage's x is 16 KiB, read from LDS unit by unit.
 //
 // LDS layout of a weight stage: per row tile 16 lines of 128 bytes, the eight 16-byte slots of
 // line n XOR-ed by (n >> 1) & 7 -- a 128-bit read of the 16 rows at one piece is conflict
@@ -70,6 +76,7 @@ namespace {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int CONSUMERS = 8;
 constexpr int LOADERS = 4;                    // 2 or 4 (a workgroup of twelve wavefronts: three to a SIMD)
@@ -177,6 +184,10 @@ struct Stage {
     float s[RT][2]; // [row tile][unit of the stage] (8 bits: one unit)
     uint32_t z;     // byte 2 * rt + unit
     u32x4 a[8];
+    // 2 bits (a stage is four units): the lane's 8 bytes of each unit, 32 k, and the units' metadata
+    u32x2 w2[RT][4];
+    float4_t s4[RT];
+    uint32_t z4[RT]; // byte = unit
 };
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
@@ -324,10 +335,57 @@ __device__ __forceinline__ void more_x(uint32_t xa0, uint32_t xa1, uint32_t xa2,
                  : "memory");
 }
 
+// A 2-bit stage: the lane's 8 bytes of each of the four units of both row tiles (`wq`: their LDS
+// addresses in row tile 0), scales and zero points of the four units, the x blocks of the first
+// unit (and first batch tile).  Same waits as take().
+template <int ALLOW>
+__device__ __forceinline__ void take2(const uint32_t (&wq)[4], uint32_t sa, uint32_t za, const uint32_t (&xa)[4],
+                                      Stage &st)
+{
+    asm volatile("s_waitcnt vmcnt(%26)\n\t"
+                 "ds_read_b64 %0, %16\n\t"
+                 "ds_read_b64 %1, %17\n\t"
+                 "ds_read_b64 %2, %18\n\t"
+                 "ds_read_b64 %3, %19\n\t"
+                 "ds_read_b64 %4, %16 offset:2048\n\t"
+                 "ds_read_b64 %5, %17 offset:2048\n\t"
+                 "ds_read_b64 %6, %18 offset:2048\n\t"
+                 "ds_read_b64 %7, %19 offset:2048\n\t"
+                 "ds_read_b128 %8, %20\n\t"
+                 "ds_read_b128 %9, %20 offset:32\n\t"
+                 "ds_read_b32 %10, %21\n\t"
+                 "ds_read_b32 %11, %21 offset:8\n\t"
+                 "ds_read_b128 %12, %22\n\t"
+                 "ds_read_b128 %13, %23\n\t"
+                 "ds_read_b128 %14, %24\n\t"
+                 "ds_read_b128 %15, %25\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(st.w2[0][0]), "=&v"(st.w2[0][1]), "=&v"(st.w2[0][2]), "=&v"(st.w2[0][3]), "=&v"(st.w2[1][0]),
+                   "=&v"(st.w2[1][1]), "=&v"(st.w2[1][2]), "=&v"(st.w2[1][3]), "=&v"(st.s4[0]), "=&v"(st.s4[1]),
+                   "=&v"(st.z4[0]), "=&v"(st.z4[1]), "=&v"(st.a[0]), "=&v"(st.a[1]), "=&v"(st.a[2]), "=&v"(st.a[3])
+                 : "v"(wq[0]), "v"(wq[1]), "v"(wq[2]), "v"(wq[3]), "v"(sa), "v"(za), "v"(xa[0]), "v"(xa[1]), "v"(xa[2]),
+                   "v"(xa[3]), "n"(ALLOW)
+                 : "memory");
+}
+
+// Four x blocks, OFF bytes past the addresses given, into st.a[D0 ..].
+template <int OFF, int D0>
+__device__ __forceinline__ void read_x4(const uint32_t (&xa)[4], Stage &st)
+{
+    asm volatile("ds_read_b128 %0, %4 offset:%8\n\t"
+                 "ds_read_b128 %1, %5 offset:%8\n\t"
+                 "ds_read_b128 %2, %6 offset:%8\n\t"
+                 "ds_read_b128 %3, %7 offset:%8\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(st.a[D0]), "=&v"(st.a[D0 + 1]), "=&v"(st.a[D0 + 2]), "=&v"(st.a[D0 + 3])
+                 : "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "n"(OFF)
+                 : "memory");
+}
+
 template <int BITS>
 struct Cfg {
-    static constexpr int KPS = 128 * 8 / BITS; // k per stage: 256 / 128 / 64
-    static constexpr int SPC = KC / KPS;       // steps per chunk: 2 / 4 / 8
+    static constexpr int KPS = 128 * 8 / BITS; // k per stage: 512 / 256 / 128 / 64 at 2 / 4 / 8 / 16 bits
+    static constexpr int SPC = KC / KPS;       // steps per chunk: 1 / 2 / 4 / 8
 };
 
 // ------------------------------------------------------------------ consumer wavefronts
@@ -337,7 +395,7 @@ struct Consumer {
     const Sel &d;
     const Lds &L;
     const int M, wave, lane, n, c, row0;
-    const int row_bytes;  // a multiple of 64
+    const int row_bytes;  // a multiple of 64 (2 bits: of 32)
     const int nchunks;
     int T;                // steps: 128-byte lines of a row (the last may be half a line at 4 bits)
     uint8_t *ring;        // this wavefront's NS slots
@@ -346,7 +404,9 @@ struct Consumer {
     // -> row lane / 8 of those, LDS slot lane % 8, i.e. piece slot ^ ((row % 16) >> 1) of the line
     uint32_t ld_off[SOPS]; // byte offset of the lane's row from the first row, plus its piece
     uint32_t ld_hi;        // 64 if the lane's piece in even loads lies in the upper half of the line (odd: the other)
+    uint32_t ld_piece;     // the lane's piece in even loads (odd ones: that ^ 4)
     uint32_t wa0, wb0;     // LDS addresses for take(): the lane's pieces c and c + 4 in slot 0
+    uint32_t wq0;          // 2 bits: of the lane's 8 bytes of the stage's first unit (unit u: wq0 ^ 32 u)
     uint32_t ml;           // wave * 16 + n: the lane's place in the metadata of a pair of chunks
     // byte offsets of the lane's x blocks inside a stage's blocks (block kb of the chunk holds
     // batch row n at place n ^ (kb % 8 + 8 (kb / 32))).  4 bits: blocks 4 c + i of either unit; 8 bits: blocks 8 h + 2 c + i;
@@ -383,12 +443,15 @@ struct Consumer {
             ld_off[i] = (uint32_t)(row - first_row) * (uint32_t)row_bytes + (uint32_t)piece * 16;
         }
         ld_hi = ((slot ^ (r >> 1)) & 4) * 16; // bit 2 of the piece flips with the parity of i
+        ld_piece = (uint32_t)(slot ^ (r >> 1));
         wa0 = lds_addr(ring) + n * 128 + ((c ^ ((n >> 1) & 7)) * 16);
         wb0 = wa0 ^ 64; // piece c + 4
+        // a unit is 32 bytes of a line, an MFMA takes 8 of them: 2 from each group of 16 lanes
+        wq0 = lds_addr(ring) + n * 128 + (((c >> 1) ^ ((n >> 1) & 7)) * 16) + (c & 1) * 8;
         ml = wave * 16 + n;
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const int kb = BITS == 4 ? 4 * c + i : BITS == 8 ? 8 * (i >> 1) + 2 * c + (i & 1) : 4 * i + c;
+            const int kb = BITS == 4 || BITS == 2 ? 4 * c + i : BITS == 8 ? 8 * (i >> 1) + 2 * c + (i & 1) : 4 * i + c;
             xq[i] = (uint32_t)(kb * (256 * MT) + ((n ^ (kb & 7)) * 16));
         }
 #pragma unroll
@@ -407,12 +470,19 @@ struct Consumer {
         const uint8_t *base = gbase + (size_t)q * 128;
         uint8_t *dst = ring + slot * STAGE_BYTES;
         const bool half_line = BITS == 4 && q * 128 + 64 >= row_bytes;
-        const uint32_t back_even = half_line ? ld_hi : 0u, back_odd = half_line ? 64u - ld_hi : 0u;
+        uint32_t back_even = half_line ? ld_hi : 0u, back_odd = half_line ? 64u - ld_hi : 0u;
+        if (BITS == 2 && q * 128 + 128 > row_bytes) {
+            // a 2-bit row may end with 2, 4 or 6 of a line's 8 pieces: piece p -> p % pieces
+            const uint32_t np = (uint32_t)(row_bytes - q * 128) >> 4;
+            const uint32_t pe = ld_piece, po = ld_piece ^ 4u;
+            back_even = ((pe >= np) + (pe >= 2 * np) + (pe >= 3 * np)) * np * 16;
+            back_odd = ((po >= np) + (po >= 2 * np) + (po >= 3 * np)) * np * 16;
+        }
 #pragma unroll
         for (int i = 0; i < SOPS; i++) {
             uint32_t off = ld_off[i];
-            if (BITS == 4)
-                off -= (i & 1) ? back_odd : back_even; // pieces 4..7 -> 0..3
+            if (BITS == 4 || BITS == 2)
+                off -= (i & 1) ? back_odd : back_even; // 4 bits: pieces 4..7 -> 0..3
             __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(base + off), (FQ_LDS void *)(dst + i * 1024), 16,
                                              0, 2 /* nt: the weights are read once */);
         }
@@ -509,6 +579,83 @@ struct Consumer {
             }
     }
 
+    // One unit (128 k) of a 2-bit stage: the lane's 8 bytes st.w2[rt][U], x blocks st.a[mt * 4 + j].
+    // A byte holds four consecutive codes: copied to both halves of a word, (t & 0x000C0003) |
+    // 0x5C006400 is the pair (1024 + q0, 256 + q1) and (t & 0x00C00030) | 0x4C005400 the pair
+    // (64 + q2, 16 + q3); the constant operand removes the four offsets and the zero point.
+    template <int U>
+    __device__ __forceinline__ void unit2(const Stage &st)
+    {
+        uint32_t m01 = 0x5C006400u, m23 = 0x4C005400u;
+        asm volatile("" : "+v"(m01), "+v"(m23));
+        u32x4 nz[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            const uint32_t zb = (st.z4[rt] >> (8 * U)) & 0xFFu, t = zb | (zb << 18);
+            const uint32_t lo = 0xDC00E400u | t;        // -(1024 + z), -(256 + z)
+            const uint32_t hi = 0xCC00D400u | (t << 4); // -(  64 + z), -( 16 + z)
+            nz[rt] = u32x4{lo, hi, lo, hi};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++) {
+                const u32x2 w = st.w2[rt][U];
+                const uint32_t lo = w.x, hi = w.y; // (element by element from a copy)
+                const uint32_t ia = 2 * j, ib = 2 * j + 1; // the two bytes of this MFMA's 8 codes
+                const uint32_t ta = __builtin_amdgcn_perm(hi, lo, 0x0c000c00u | ia | (ia << 16));
+                const uint32_t tb = __builtin_amdgcn_perm(hi, lo, 0x0c000c00u | ib | (ib << 16));
+                u32x4 b;
+                b.x = (ta & 0x000C0003u) | m01;
+                b.y = (ta & 0x00C00030u) | m23;
+                b.z = (tb & 0x000C0003u) | m01;
+                b.w = (tb & 0x00C00030u) | m23;
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) // (the unit's sum starts from the instruction's constant 0)
+                    acc[rt][mt] = mfma(st.a[mt * 4 + j], b, j == 0 ? float4_t{0.f, 0.f, 0.f, 0.f} : acc[rt][mt]);
+            }
+#pragma unroll
+            for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    acc[rt][mt] = mfma(st.a[mt * 4 + j], nz[rt], acc[rt][mt]);
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++) {
+            const float4_t s4 = st.s4[rt];
+            const float sc = U == 0 ? s4.x : U == 1 ? s4.y : U == 2 ? s4.z : s4.w;
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                out[rt][mt] += sc * acc[rt][mt];
+        }
+    }
+
+    // The four units of a 2-bit stage; take2() has brought the first unit's x blocks of the first
+    // batch tile, the others are read here.  `xa`: as given to take2(); the blocks of units 2 and
+    // 3 sit 128 bytes the other way inside their rows of 16 (k block / 32 changes).
+    __device__ __forceinline__ void compute2(Stage &st, uint32_t (&xa)[4])
+    {
+        if (MT == 2)
+            read_x4<256, 4>(xa, st);
+        unit2<0>(st);
+        read_x4<4096 * MT, 0>(xa, st);
+        if (MT == 2)
+            read_x4<4096 * MT + 256, 4>(xa, st);
+        unit2<1>(st);
+        uint32_t(&xb)[4] = xa; // (in place: the addresses of units 0 and 1 are not needed again)
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            xb[i] ^= 128u;
+        read_x4<2 * 4096 * MT, 0>(xb, st);
+        if (MT == 2)
+            read_x4<2 * 4096 * MT + 256, 4>(xb, st);
+        unit2<2>(st);
+        read_x4<3 * 4096 * MT, 0>(xb, st);
+        if (MT == 2)
+            read_x4<3 * 4096 * MT + 256, 4>(xb, st);
+        unit2<3>(st);
+    }
+
     // The stage in `st` (for 4 bits and two batch tiles: its second unit is fetched here, xa as
     // given to take()).
     __device__ __forceinline__ void compute(Stage &st, uint32_t xa0, uint32_t xa1, uint32_t xa2, uint32_t xa3)
@@ -591,7 +738,11 @@ struct Consumer {
             const uint32_t wa = wa0 + slot * STAGE_BYTES, wb = wb0 + slot * STAGE_BYTES, sa = sbase + unit * 4,
                            za = zbase + unit;
             uint32_t xa[4];
-            if (BITS == 4) {
+            if (BITS == 2) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    xa[i] = xbase + xq[i]; // the stage is the chunk
+            } else if (BITS == 4) {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
                     xa[i] = xbase + j * (8192 * MT) + (xq[i] ^ (j ? 128u : 0u));
@@ -606,12 +757,23 @@ struct Consumer {
             }
             Stage st;
             const int pend = __builtin_amdgcn_readfirstlane(fq + ahead.pf - 1 - q); // younger stages in flight
-            if (NS > 2 && pend >= 2)
-                take<BITS, MT, 2 * SOPS>(wa, wb, sa, za, xa, st);
-            else if (pend == 1)
-                take<BITS, MT, SOPS>(wa, wb, sa, za, xa, st);
-            else
-                take<BITS, MT, 0>(wa, wb, sa, za, xa, st);
+            if constexpr (BITS == 2) {
+                const uint32_t w0 = wq0 + slot * STAGE_BYTES;
+                const uint32_t wq[4] = {w0, w0 ^ 32u, w0 ^ 64u, w0 ^ 96u};
+                if (NS > 2 && pend >= 2)
+                    take2<2 * SOPS>(wq, sa, za, xa, st);
+                else if (pend == 1)
+                    take2<SOPS>(wq, sa, za, xa, st);
+                else
+                    take2<0>(wq, sa, za, xa, st);
+            } else {
+                if (NS > 2 && pend >= 2)
+                    take<BITS, MT, 2 * SOPS>(wa, wb, sa, za, xa, st);
+                else if (pend == 1)
+                    take<BITS, MT, SOPS>(wa, wb, sa, za, xa, st);
+                else
+                    take<BITS, MT, 0>(wa, wb, sa, za, xa, st);
+            }
             if (fq < T) { // the stage NS steps ahead, into the slot just emptied
                 fetch(fq, slot);
                 fq++;
@@ -619,7 +781,10 @@ struct Consumer {
                 request_ahead(slot);
             }
             __builtin_amdgcn_sched_barrier(0); // keep the requests here: the scheduler sinks them otherwise
-            compute(st, xa[0], xa[1], xa[2], xa[3]);
+            if constexpr (BITS == 2)
+                compute2(st, xa);
+            else
+                compute(st, xa[0], xa[1], xa[2], xa[3]);
             slot = slot == NS - 1 ? 0 : slot + 1;
         }
         post(lds_addr(L.flag) + 4u * (8 + wave), base + ch + 1); // every read of the chunk's buffers has returned
@@ -880,8 +1045,7 @@ __device__ __forceinline__ Tile read_tile(const int *mail)
 // four times as long as a 4-bit one) and a fixed deal leaves the workgroups with the long ones
 // running alone at the end.  The queue runs over the tiles of the entries this kernel serves at
 // this launch's bit-widths, in table order, as listed by plan_order_kernel just before the launch
-// (entries at a width that is not attached, or at 2 bits, which another kernel runs, cost
-// nothing).  Loader 1 draws the next tile while the current one runs, at a point where it would
+// (entries at a width that is not attached cost nothing).  Loader 1 draws the next tile while the current one runs, at a point where it would
 // otherwise wait for the consumers (the round trip of the atomic is not hidden anywhere on the
 // way into a tile), looks up its entry and the operands of the entry's selected width, and leaves
 // them in LDS (`mail`, two records used in turn): everybody reads a tile's record after the
@@ -934,9 +1098,13 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
             bits = bits_dev[e];
             d.N = dp->N;
             d.K = dp->K;
-            d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-            d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-            d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+            d.codes = bits == 4   ? dp->codes4
+                      : bits == 8 ? dp->codes8
+                      : bits == 2 ? dp->codes2
+                      : bits == 16 ? (const uint8_t *)dp->w16
+                                   : nullptr;
+            d.scales = bits == 4 ? dp->scales4 : bits == 2 ? dp->scales2 : dp->scales8;
+            d.zeros = bits == 4 ? dp->zeros4 : bits == 2 ? dp->zeros2 : dp->zeros8;
             d.x = dp->x;
             d.y = dp->y;
             if (!d.codes)
@@ -966,6 +1134,8 @@ __device__ __forceinline__ void run_tiles(const FqLinearDesc *table, const int32
                     ahead = Consumer<4, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
                 else if (cur.bits == 8)
                     ahead = Consumer<8, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
+                else if (cur.bits == 2)
+                    ahead = Consumer<2, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
                 else
                     ahead = Consumer<16, MT>(cur.d, L, M, tile_row0, wave, base, tileno).run(ahead);
                 base += (cur.d.K + KC - 1) / KC;
@@ -1084,49 +1254,41 @@ __device__ __forceinline__ int scan256(int v, int *tmp, int &total)
     return v + before;
 }
 
-// What a batched plan launch runs under this launch's bit-widths, in table order: list 0 the entries
-// at 4, 8 or 16 bits whose copy is attached, in 256-row tiles (the streaming kernel's), list 1 the
-// entries at 2 bits, in 128-row tiles (the register-fed kernel's second pass).  order[l][r] = (first
-// tile of the list's r-th entry, entry); queue[FQ_Q_TILES + 2 l] = tiles of the list,
-// queue[FQ_Q_ENTRIES + 2 l] = its entries.  One workgroup.
+// What a batched plan launch runs under this launch's bit-widths, in table order: the entries at
+// 2, 4, 8 or 16 bits whose copy is attached, in 256-row tiles.  order[r] = (first tile of the r-th
+// such entry, entry); queue[FQ_Q_TILES] = their tiles, queue[FQ_Q_ENTRIES] = their number.  An
+// entry at another width (3 bits) or without that copy is left out and flagged.  One workgroup.
 __global__ __launch_bounds__(256) void plan_order_kernel(const FqLinearDesc *__restrict__ table,
                                                          const int32_t *__restrict__ bits_dev, int count, int *queue,
-                                                         int2 *order0, int2 *order1)
+                                                         int2 *order)
 {
     __shared__ int tmp[4];
-    int first_tile[2] = {0, 0}, first_rank[2] = {0, 0};
+    int first_tile = 0, first_rank = 0;
     for (int base = 0; base < count; base += 256) {
         const int e = base + threadIdx.x;
-        int list = -1, tiles = 0;
+        int tiles = 0;
+        bool listed = false;
         if (e < count) {
             const FqLinearDesc &d = table[e];
             const int bits = bits_dev[e];
-            if ((bits == 16 && d.w16) || (bits == 8 && d.codes8) || (bits == 4 && d.codes4)) {
-                list = 0;
+            if ((bits == 16 && d.w16) || (bits == 8 && d.codes8) || (bits == 4 && d.codes4) || (bits == 2 && d.codes2)) {
+                listed = true;
                 tiles = (d.N + TILE_ROWS - 1) / TILE_ROWS;
-            } else if (bits == 2 && d.codes2) {
-                list = 1;
-                tiles = (d.N + 127) / 128;
             } else {
                 queue[FQ_Q_FLAGS] = 1; // no such width here, or no copy of it: nobody runs this entry
             }
         }
-#pragma unroll
-        for (int l = 0; l < 2; l++) {
-            int sum_t, sum_e;
-            const int incl_t = scan256(list == l ? tiles : 0, tmp, sum_t);
-            const int incl_e = scan256(list == l ? 1 : 0, tmp, sum_e);
-            if (list == l)
-                (l ? order1 : order0)[first_rank[l] + incl_e - 1] = make_int2(first_tile[l] + incl_t - tiles, e);
-            first_tile[l] += sum_t;
-            first_rank[l] += sum_e;
-        }
+        int sum_t, sum_e;
+        const int incl_t = scan256(tiles, tmp, sum_t);
+        const int incl_e = scan256(listed ? 1 : 0, tmp, sum_e);
+        if (listed)
+            order[first_rank + incl_e - 1] = make_int2(first_tile + incl_t - tiles, e);
+        first_tile += sum_t;
+        first_rank += sum_e;
     }
     if (threadIdx.x == 0) {
-        queue[FQ_Q_TILES] = first_tile[0];
-        queue[FQ_Q_ENTRIES] = first_rank[0];
-        queue[FQ_Q_TILES + 2] = first_tile[1];
-        queue[FQ_Q_ENTRIES + 2] = first_rank[1];
+        queue[FQ_Q_TILES] = first_tile;
+        queue[FQ_Q_ENTRIES] = first_rank;
     }
 }
 
@@ -1162,7 +1324,7 @@ __global__ __launch_bounds__(THREADS) void decode_stream_kernel(const FqLinearDe
 
 // A plan launch (device table of `count` linears, device-side bit-widths) for 2 <= M <= 32 and
 // tiles of 256 rows.  `queue`: 16 ints in device memory that belong to the plan, zeroed once (the
-// kernel leaves the cursors zeroed), and `order`: 2 x `count` pairs of ints of the plan's.  The
+// kernel leaves the cursors zeroed), and `order`: `count` pairs of ints of the plan's.  The
 // queue hands out runs of 8 tiles to the 8 XCDs in turn: the grid (one workgroup per compute unit)
 // must be a multiple of 64, which the plan's layout sees to (other devices get smaller tiles and
 // the register-fed kernel).
@@ -1174,8 +1336,8 @@ hipError_t fq_launch_skinny_stream(const FqLinearDesc *descs_dev, const int32_t 
     const int grid = total_tiles < cus ? total_tiles : cus;
     if (!queue || !order || grid % 64 != 0)
         return hipErrorInvalidValue;
-    // what this launch runs, under its bit-widths (a second pass reads its list too)
-    plan_order_kernel<<<1, 256, 0, stream>>>(descs_dev, bits_dev, count, queue, (int2 *)order, (int2 *)order + count);
+    // what this launch runs, under its bit-widths
+    plan_order_kernel<<<1, 256, 0, stream>>>(descs_dev, bits_dev, count, queue, (int2 *)order);
     if (M <= 16)
         decode_stream_kernel<1><<<grid, THREADS, 0, stream>>>(descs_dev, bits_dev, count, total_tiles, M, queue,
                                                               (const int2 *)order);

@@ -155,8 +155,8 @@ def test_linear_2bit_batched_integer_case_exact(M):
 
 
 def test_batched_plan_with_2bit_entries():
-    # a plan large enough for the streaming kernel were it not for the 2-bit copies: it must run on
-    # the register-fed kernel and serve every width per entry
+    # a plan large enough for the streaming kernel (70 x 4096 rows): every width is served per
+    # entry, the 2-bit entries among the others in the one launch
     M = 8
     shapes = [(4096, 1024)] * 70
     layers, xs, ys, xs_np, packs = [], [], [], [], []

@@ -147,7 +147,7 @@ def test_llama7b_stack_batch_sweep_bits_4_8_16(M):
 
 
 def test_llama7b_stack_batch16_bits_2_4_8():
-    # a plan of the streaming kernel's size whose layers hold 2-bit copies: two kernels per launch
+    # a plan of the streaming kernel's size whose layers hold 2-bit copies, served in the same launch
     st = bench.Stack("llama7b", M=16, bit_choices=(2, 4, 8))
     _check_stack(st, steps=(2,), n_entries=21, rows_per_entry=3, rng=np.random.default_rng(5))
 

@@ -159,29 +159,31 @@ def test_streaming_plan_skipped_entries_and_repeated_runs():
             assert rel_err(y, y_ref) <= TOL_Y, (p, i, b, shapes[i])
 
 
-@pytest.mark.parametrize("M", [16, 23])
-def test_streaming_plan_with_2bit_copies(M):
-    # a plan of the streaming kernel's size whose layers also hold 2-bit copies runs in two
-    # launches: the streaming kernel passes over the entries that are at 2 bits, the register-fed
-    # kernel runs exactly those
+@pytest.mark.parametrize("M,extra", [(16, tuple(LONG)), (23, ()), (2, ()), (32, tuple(LONG[:3]))])
+def test_streaming_plan_with_2bit_copies(M, extra):
+    # 2-bit copies run in the same launch as the others: a stage is a whole chunk of x (512 k,
+    # four units), and a row may end with 2, 4 or 6 of a line's 8 pieces (K % 512 = 128, 256, 384)
     shapes, layers, packs, xs_np, xs, ys, plan = _build(
         M, "par/stream/w2", lambda i, N, K: synth.weight(0, "par/stream/w2/w%d" % i, N, K, 0.02, outlier_p=0.001),
-        widths=(2, 4, 8, 16))
+        extra=list(extra), widths=(2, 4, 8, 16))
     n = len(layers)
     patterns = [[(2, 4, 8, 16)[(i + s) % 4] for i in range(n)] for s in range(2)] + [[2] * n, [(8, 16, 4)[i % 3] for i in range(n)],
                                                                                        [0 if i % 3 == 0 else 2 for i in range(n)]]
+    unserved = False
     for p, pattern in enumerate(patterns):
         for y in ys:
             y.fill_(5.0)
         plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
         torch.cuda.synchronize()
+        unserved = unserved or 0 in pattern  # (the flag word stays set once set)
+        assert plan.status() == (0, int(unserved))
         for i, b in enumerate(pattern):
             y = ys[i].cpu().numpy()
             if b == 0:
                 assert np.all(y == np.float16(5.0)), (p, i)
                 continue
             assert np.isfinite(y.astype(np.float32)).all(), (p, i, b)
-            if (i + p) % 4 and i < n - 2:
+            if (i + p) % 4 and i < n - 2 and i >= len(extra):
                 continue
             w, packed = packs[i]
             if b == 16:
@@ -190,6 +192,48 @@ def test_streaming_plan_with_2bit_copies(M):
                 c, s, z = (t.cpu().numpy() for t in packed[b])
                 y_ref = oracle.linear(xs_np[i], c, s, z, b)
             assert rel_err(y, y_ref) <= TOL_Y, (M, p, i, b, shapes[i])
+
+
+@pytest.mark.parametrize("M", [16, 32])
+def test_streaming_plan_2bit_integer_case_exact(M):
+    # integer activations, weights 0 .. 3 with every group spanning them (s = 1, z = 0): every
+    # product, every partial sum and the four offsets by bit position that the kernel adds and
+    # removes (1024, 256, 64, 16) are integers below 2^24, so the output is the integer product
+    # exactly; each k % 16 carries its own pattern, so a swapped pair or byte shows
+    rng = np.random.default_rng(11)
+
+    def weights(i, N, K):
+        w = rng.integers(0, 4, size=(N, K)).astype(np.float16)
+        w[:, 0::128] = 0
+        w[:, 1::128] = 3
+        return w
+
+    shapes, layers, packs, xs_np, xs, ys, plan = _build(M, "par/stream/int2", weights, extra=[(300, 2432), (260, 4096)],
+                                                        widths=(2, 4))
+    for i, (N, K) in enumerate(shapes):
+        xi = (rng.integers(-2, 3, size=(M, K)) * (rng.random((M, K)) < 0.3)).astype(np.float16)
+        xs_np[i] = xi
+        xs[i].copy_(to_dev(xi))
+    pattern = [(2, 2, 4)[i % 3] for i in range(len(layers))]
+    plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    for i in list(range(0, len(layers), 3)) + [1]:
+        w, packed = packs[i]
+        assert pattern[i] == 2
+        assert torch.all(packed[2][1] == 1.0) and torch.all(packed[2][2] == 0)
+        expect = (xs_np[i].astype(np.float64) @ w.astype(np.float64).T)
+        assert np.abs(expect).max() < 2048
+        assert np.array_equal(ys[i].cpu().numpy().astype(np.float64), expect), (i, shapes[i])
+    # one-hot x on one linear: output n is the code at that k, for every position of a 16-code word
+    i = 0
+    N, K = shapes[i]
+    for k in list(range(0, 33)) + [127, 128, 511, 512, 1023, K - 1]:
+        x1 = np.zeros((M, K), dtype=np.float16)
+        x1[M - 1, k] = 1
+        xs[i].copy_(to_dev(x1))
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert np.array_equal(ys[i].cpu().numpy()[M - 1].astype(np.int64), packs[i][0][:, k].astype(np.int64)), k
 
 
 def test_streaming_plan_with_more_than_256_entries():
