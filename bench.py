@@ -808,9 +808,7 @@ def main():
 
     traffic_key = (args.stack, args.batch, bit_choices)
     kernel_of = {"dependent": "decode_staged_kernel (one launch: %d stages)" % getattr(stack, "n_stages", 0),
-                 "independent": "decode_m1_kernel (plan launch)" if args.batch == 1 else
-                                "decode_stream_kernel + decode_skinny_kernel" if 2 in bit_choices else
-                                "decode_stream_kernel"}
+                 "independent": "decode_m1_kernel (plan launch)" if args.batch == 1 else "decode_stream_kernel"}
 
     def roofline(kernel, ms, traffic=None, traffic_source=None):
         achieved = alg_bytes / (ms * 1e-3) / 1e9
@@ -838,7 +836,7 @@ def main():
                                "%d linears + entropy/KL over %d logits per step"
                                % (args.stack, args.batch, args.bits, len(stack.layers), VOCAB),
                    "order": order,
-                   "launches_per_step": 2 if args.batch == 1 else (4 if 2 in bit_choices else 3),
+                   "launches_per_step": 2 if args.batch == 1 else 3,
                    "build_seconds": round(stack.build_seconds, 1)},
         "weight_GBps": total_bytes / elapsed / 1e9,
         "weight_GB_per_step": alg_bytes / 1e9,
