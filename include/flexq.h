@@ -78,6 +78,8 @@ typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch
 #define FQ_MAX_DECODE_M 32 /* rows of x served by the skinny (decode) kernels */
 #define FQ_MAX_DECODE_K 32768 /* longest row they take (a row of x stays in LDS at M = 1) */
 #define FQ_MAX_LM_HEAD_M 4 /* rows of x served by fq_lm_head_entropy */
+#define FQ_SCRATCH_BANKS 16 /* streams per device with a copy of their own of the library's static
+                               scratch (fq_entropy_kl over a few rows, fq_lm_head_entropy) */
 
 /* Message describing the calling thread's most recent error ("" if none).  (Interface only: the
  * paper defines no error model.) */
@@ -287,8 +289,10 @@ int fq_linear_w8a8(const fq_layer *layer, const void *xq, const float *sx, const
  *   logits_p, logits_q  device, f32 [R][V]     (read)
  *   entropy_out, kl_out device, f32 [R]        (written)
  * R >= 0 (R = 0 launches nothing), V >= 1.  Calls with R <= 64 combine per-row
- * partials in a small device-resident scratch of the library: do not let two such
- * calls overlap on different streams.
+ * partials in a small device-resident scratch of the library, of which every stream
+ * gets a copy of its own (FQ_SCRATCH_BANKS per device; further streams take a slower path that
+ * needs none): such calls may overlap on different streams.  A launch captured into a
+ * graph keeps the copy of the stream it was captured on.
  */
 int fq_entropy_kl(const float *logits_p, const float *logits_q, int R, int V,
                   float *entropy_out, float *kl_out, void *stream);
@@ -331,8 +335,10 @@ int fq_rank_ascending(const float *values, int n, int m, int32_t *order, void *s
  *   argmax  device, int32 [M], or NULL                (written if not NULL)
  * 1 <= M <= FQ_MAX_LM_HEAD_M; K a multiple of 512 with M * K <= 32768; V >= 1.  Two logits that
  * differ by less than the rounding of a binary32 sum of K products may swap places in argmax.
- * Uses a static device array for the partial results of its workgroups: calls must not overlap
- * each other on one device (same-stream order is enough).
+ * Uses a static device array for the partial results of its workgroups, of which every stream
+ * gets a copy of its own, so calls may overlap on different streams; a stream beyond the first
+ * FQ_SCRATCH_BANKS distinct ones on a device is refused (FQ_ERR_HIP).  A call captured into a graph keeps the copy of the
+ * stream it was captured on.
  */
 int fq_lm_head_entropy(const void *x_fp16, const void *w_fp16, int M, int V, int K,
                        float *logits, float *H, int32_t *argmax, void *stream);

@@ -9,7 +9,7 @@ _EXPORTS = (
     "FQ_GROUP", "FQ_MAX_DECODE_M", "FlexqError", "Layer", "Plan", "StagedPlan", "fq_entropy_kl", "fq_entropy_kl_f16",
     "fq_last_error", "fq_linear", "fq_linear_w8a8", "fq_packed_sizes", "fq_quantize", "fq_quantize_act",
     "fq_quantize_sym", "fq_fake_quantize", "fq_lm_head_entropy", "FQ_MAX_LM_HEAD_M",
-    "fq_linears_static", "fq_stream_read", "FQ_STATIC_MAX_ENTRIES",
+    "fq_linears_static", "fq_stream_read", "FQ_STATIC_MAX_ENTRIES", "FQ_SCRATCH_BANKS",
     "fq_rank_ascending", "fq_sched_init", "fq_sched_peek",
     "fq_sched_state_bytes", "fq_sched_step", "fq_sched_threshold_from_prefill", "lib", "lib_path",
 )

@@ -16,6 +16,7 @@ FQ_GROUP = 128
 FQ_MAX_DECODE_M = 32
 FQ_MAX_LM_HEAD_M = 4
 FQ_STATIC_MAX_ENTRIES = 512
+FQ_SCRATCH_BANKS = 16
 FQ_OK, FQ_ERR_NULL, FQ_ERR_BITS, FQ_ERR_SHAPE, FQ_ERR_NOT_ATTACHED, FQ_ERR_ALIGN, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
 

@@ -395,6 +395,8 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
     return FQ_OK;
 }
 
+static_assert(FQ_BANKS == FQ_SCRATCH_BANKS, "the public header states the number of scratch banks");
+
 hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, int *queue_dev, void *order_dev,
                           const int32_t *bits_dev, hipStream_t stream)
 {

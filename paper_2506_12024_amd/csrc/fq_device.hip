@@ -1,7 +1,8 @@
 // Per-device facts the launch code needs on every call -- the number of compute units, how many
 // workgroups of a kernel fit on one, whether a kernel's dynamic LDS limit has been raised -- asked
 // of the HIP runtime once per device and kept in fixed-size tables (no allocation), under a mutex
-// so that several host threads, each with its own current device, may launch at once.
+// so that several host threads, each with its own current device, may launch at once; and which
+// bank of the library's static scratch arrays a stream uses.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -27,6 +28,8 @@ struct DeviceFacts {
     int n_raised;
     const void *raised[MAX_KERNEL_FACTS]; // kernels whose dynamic LDS limit was raised
     size_t raised_to[MAX_KERNEL_FACTS];
+    int n_banks;
+    hipStream_t bank_stream[FQ_BANKS]; // the stream that bank i of the static scratch arrays belongs to
 };
 
 std::mutex g_lock;
@@ -77,6 +80,21 @@ int fq_workgroups_per_cu(const void *func, int threads, size_t lds, int fallback
     if (d && d->n_facts < MAX_KERNEL_FACTS)
         d->facts[d->n_facts++] = KernelFact{func, threads, lds, per_cu};
     return per_cu;
+}
+
+int fq_stream_bank(hipStream_t stream)
+{
+    std::lock_guard<std::mutex> hold(g_lock);
+    DeviceFacts *d = current();
+    if (!d)
+        return -1;
+    for (int i = 0; i < d->n_banks; i++)
+        if (d->bank_stream[i] == stream)
+            return i;
+    if (d->n_banks == FQ_BANKS)
+        return -1;
+    d->bank_stream[d->n_banks] = stream;
+    return d->n_banks++;
 }
 
 hipError_t fq_raise_dynamic_lds(const void *func, size_t bytes)

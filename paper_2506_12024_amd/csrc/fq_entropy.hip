@@ -127,17 +127,18 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// Scratch of the split mode: partials [row][split][S, U, D, Sb, m, mb] and arrival tickets.
-// Tickets are zero at load and the combining workgroup resets its row's ticket, so every
-// launch finds them zero.  Calls that use the split mode must not overlap each other.
+// Scratch of the split mode: partials [row][split][S, U, D, Sb, m, mb] and arrival tickets, one
+// bank per stream (calls on one stream follow one another; calls on different streams use different
+// banks).  Tickets are zero at load and the combining workgroup resets its row's ticket, so every
+// launch finds them zero.
 constexpr int MAX_SPLIT_ROWS = 64, MAX_SPLITS = 32;
-__device__ double g_part[MAX_SPLIT_ROWS][MAX_SPLITS][6];
-__device__ unsigned int g_ticket[MAX_SPLIT_ROWS];
+__device__ double g_part[FQ_BANKS][MAX_SPLIT_ROWS][MAX_SPLITS][6];
+__device__ unsigned int g_ticket[FQ_BANKS][MAX_SPLIT_ROWS];
 
 template <int THREADS, bool HAS_B, bool VEC, typename T>
 __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict__ a,
                                                              const T *__restrict__ b, int V,
-                                                             int splits, float *__restrict__ H,
+                                                             int splits, int bank, float *__restrict__ H,
                                                              float *__restrict__ KL)
 {
     constexpr int WAVES = THREADS / 64;
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict
     if (splits > 1) {
         // publish this workgroup's partial, then see whether it is the last to arrive
         if (t == 0) {
-            double *slot = g_part[r][sidx];
+            double *slot = g_part[bank][r][sidx];
             slot[0] = S;
             slot[1] = U;
             slot[2] = D;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict
             slot[4] = (double)gm;
             slot[5] = (double)gmb;
             __threadfence();
-            s_last = atomicAdd(&g_ticket[r], 1u) == (unsigned)splits - 1 ? 1u : 0u;
+            s_last = atomicAdd(&g_ticket[bank][r], 1u) == (unsigned)splits - 1 ? 1u : 0u;
         }
         __syncthreads();
         if (!s_last || wave != 0)
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict
         double pm = -INFINITY, pmb = -INFINITY;
         S = U = D = Sb = 0.0;
         if (lane < splits) {
-            const double *slot = g_part[r][lane];
+            const double *slot = g_part[bank][r][lane];
             S = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             U = __hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             D = __hip_atomic_load(&slot[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict
         D = wave_sum(D);
         Sb = wave_sum(Sb);
         if (lane == 0)
-            g_ticket[r] = 0u; // ready for the next launch
+            g_ticket[bank][r] = 0u; // ready for the next launch
     }
     if (t == 0) {
         H[r] = (float)(log(S) - U / S);
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(THREADS) void entropy_kl_kernel(const T *__restrict
 }
 
 template <int THREADS, typename T>
-hipError_t launch(const T *a, const T *b, int R, int V, int splits, float *H, float *KL,
+hipError_t launch(const T *a, const T *b, int R, int V, int splits, int bank, float *H, float *KL,
                   hipStream_t stream)
 {
     const uintptr_t mask = 4 * sizeof(T) - 1;
@@ -296,14 +297,14 @@ hipError_t launch(const T *a, const T *b, int R, int V, int splits, float *H, fl
     const dim3 grid((unsigned)R * (unsigned)splits), block(THREADS);
     if (b) {
         if (vec)
-            entropy_kl_kernel<THREADS, true, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, true, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, bank, H, KL);
         else
-            entropy_kl_kernel<THREADS, true, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, true, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, bank, H, KL);
     } else {
         if (vec)
-            entropy_kl_kernel<THREADS, false, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, false, true, T><<<grid, block, 0, stream>>>(a, b, V, splits, bank, H, KL);
         else
-            entropy_kl_kernel<THREADS, false, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, H, KL);
+            entropy_kl_kernel<THREADS, false, false, T><<<grid, block, 0, stream>>>(a, b, V, splits, bank, H, KL);
     }
     return hipGetLastError();
 }
@@ -314,17 +315,19 @@ hipError_t dispatch(const T *a, const T *b, int R, int V, float *H, float *KL, h
     if (R == 0)
         return hipSuccess;
     // A few rows: split every row over several workgroups (>= 1024 entries each).
-    if (R <= MAX_SPLIT_ROWS && V >= 2048) {
+    // (if more streams than there are scratch banks have come by: whole rows, as below)
+    const int bank = R <= MAX_SPLIT_ROWS && V >= 2048 ? fq_stream_bank(stream) : -1;
+    if (bank >= 0) {
         int splits = V / 1024;
         if (splits > MAX_SPLITS)
             splits = MAX_SPLITS;
-        return launch<256, T>(a, b, R, V, splits, H, KL, stream);
+        return launch<256, T>(a, b, R, V, splits, bank, H, KL, stream);
     }
     // Otherwise one workgroup per row: large ones while there are too few rows to fill the
     // machine, 256 threads (several rows per CU) beyond that.
     if (R < 512)
-        return launch<1024, T>(a, b, R, V, 1, H, KL, stream);
-    return launch<256, T>(a, b, R, V, 1, H, KL, stream);
+        return launch<1024, T>(a, b, R, V, 1, 0, H, KL, stream);
+    return launch<256, T>(a, b, R, V, 1, 0, H, KL, stream);
 }
 
 } // namespace

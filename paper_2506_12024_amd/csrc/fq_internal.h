@@ -41,7 +41,7 @@ int fq_fail(int code, const char *fmt, ...);
 // fills table[count] and *geom, or returns a negative fq_status with the message recorded.
 int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, const void *const *xs,
                    void *const *ys, int M, FqLinearDesc *table, FqPlanGeom *geom);
-// The launch (or two) of a laid-out plan whose table, queue words and entry lists are in device memory.
+// The launch of a laid-out plan whose table, queue words and entry list are in device memory.
 hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, int *queue_dev, void *order_dev,
                           const int32_t *bits_dev, hipStream_t stream);
 
@@ -52,6 +52,12 @@ hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, in
 int fq_device_cus();
 int fq_workgroups_per_cu(const void *func, int threads, size_t lds, int fallback);
 hipError_t fq_raise_dynamic_lds(const void *func, size_t bytes);
+// The kernels that combine the partial results of their workgroups through a static device array
+// (entropy / KL over a few long rows, the fused output layer) keep FQ_BANKS copies of it,
+// one per stream: calls on different streams then never share one.  The bank of `stream` on the
+// current device (the first FQ_BANKS distinct streams get one each), or -1 if none is left.
+constexpr int FQ_BANKS = 16; // FQ_SCRATCH_BANKS of the public header
+int fq_stream_bank(hipStream_t stream);
 
 hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
                               void *scales, void *zeros, hipStream_t stream);

@@ -35,10 +35,11 @@ constexpr int ROWS_PER_WG = WAVES * RPW;
 constexpr int MAX_M = 4;
 constexpr int MAX_WGS = 1024; // also the size of the combining workgroup: one partial per thread
 
-// Partials [workgroup][row of x]: (max, S, U), index of the max.  Calls must not overlap each
-// other on one device.
-__device__ float g_part[MAX_WGS][MAX_M][3];
-__device__ int g_part_idx[MAX_WGS][MAX_M];
+// Partials [workgroup][row of x]: (max, S, U), index of the max; one bank per stream (the two
+// launches of a call follow one another on their stream; calls on different streams use different
+// banks).
+__device__ float g_part[FQ_BANKS][MAX_WGS][MAX_M][3];
+__device__ int g_part_idx[FQ_BANKS][MAX_WGS][MAX_M];
 
 __device__ __forceinline__ float dot8(const u32x4 w, const u32x4 x, float acc)
 {
@@ -122,7 +123,7 @@ struct State {
 template <int M>
 __global__ __launch_bounds__(THREADS) void lm_head_entropy_kernel(const uint16_t *__restrict__ x,
                                                                   const uint16_t *__restrict__ w, int V, int K,
-                                                                  float *__restrict__ logits)
+                                                                  int bank, float *__restrict__ logits)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[]; // x: [K / 512][M][64] blocks of 16 bytes
     __shared__ float s_part[WAVES][M][3];
@@ -222,10 +223,10 @@ __global__ __launch_bounds__(THREADS) void lm_head_entropy_kernel(const uint16_t
         }
         wg[m].merge_lanes(WAVES - 1);
         if (lane == 0) {
-            g_part[blockIdx.x][m][0] = wg[m].mx;
-            g_part[blockIdx.x][m][1] = wg[m].S;
-            g_part[blockIdx.x][m][2] = wg[m].U;
-            g_part_idx[blockIdx.x][m] = wg[m].idx;
+            g_part[bank][blockIdx.x][m][0] = wg[m].mx;
+            g_part[bank][blockIdx.x][m][1] = wg[m].S;
+            g_part[bank][blockIdx.x][m][2] = wg[m].U;
+            g_part_idx[bank][blockIdx.x][m] = wg[m].idx;
         }
     }
 }
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(THREADS) void lm_head_entropy_kernel(const uint16_t
 // partial visible to the other XCDs first, and that fence writes back an L2 per workgroup
 // (measured: 50 us for 1024 workgroups, more than the whole weight stream).
 template <int M>
-__global__ __launch_bounds__(MAX_WGS) void lm_head_combine_kernel(int parts, float *__restrict__ H,
+__global__ __launch_bounds__(MAX_WGS) void lm_head_combine_kernel(int parts, int bank, float *__restrict__ H,
                                                                   int32_t *__restrict__ argmax)
 {
     // one partial per thread (all loads in flight at once), wavefront butterflies, LDS, once more
@@ -247,10 +248,10 @@ __global__ __launch_bounds__(MAX_WGS) void lm_head_combine_kernel(int parts, flo
     for (int m = 0; m < M; m++) {
         st[m].init();
         if (t < parts) {
-            st[m].mx = g_part[t][m][0];
-            st[m].S = g_part[t][m][1];
-            st[m].U = g_part[t][m][2];
-            st[m].idx = g_part_idx[t][m];
+            st[m].mx = g_part[bank][t][m][0];
+            st[m].S = g_part[bank][t][m][1];
+            st[m].U = g_part[bank][t][m][2];
+            st[m].idx = g_part_idx[bank][t][m];
         }
     }
 #pragma unroll
@@ -303,8 +304,11 @@ hipError_t launch(const uint16_t *x, const uint16_t *w, int V, int K, float *log
         grid = MAX_WGS;
     if (grid > nblocks)
         grid = nblocks;
-    lm_head_entropy_kernel<M><<<grid, THREADS, lds, stream>>>(x, w, V, K, logits);
-    lm_head_combine_kernel<M><<<1, MAX_WGS, 0, stream>>>(grid, H, argmax);
+    const int bank = fq_stream_bank(stream);
+    if (bank < 0) // more streams than banks of partial results have used this call on this device
+        return hipErrorOutOfMemory;
+    lm_head_entropy_kernel<M><<<grid, THREADS, lds, stream>>>(x, w, V, K, bank, logits);
+    lm_head_combine_kernel<M><<<1, MAX_WGS, 0, stream>>>(grid, bank, H, argmax);
     return hipGetLastError();
 }
 
