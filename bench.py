@@ -808,7 +808,9 @@ def main():
 
     traffic_key = (args.stack, args.batch, bit_choices)
     kernel_of = {"dependent": "decode_staged_kernel (one launch: %d stages)" % getattr(stack, "n_stages", 0),
-                 "independent": "decode_m1_kernel (plan launch)" if args.batch == 1 else "decode_stream_kernel"}
+                 "independent": "decode_m1_kernel (plan launch)" if args.batch == 1
+                 else "decode_skinny_kernel (128-row tiles: the plan holds 3-bit copies)" if 3 in bit_choices
+                 else "decode_stream_kernel"}
 
     def roofline(kernel, ms, traffic=None, traffic_source=None):
         achieved = alg_bytes / (ms * 1e-3) / 1e9

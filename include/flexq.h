@@ -152,12 +152,13 @@ int fq_layer_destroy(fq_layer *layer);
  * Decode-phase linear (Sec. 4.1, Eq. (3)):
  *   y[m][n] = fp16( sum_g s[n][g] * sum_{k in g} x[m][k] * (q[n][k] - z[n][g]) )
  * accumulated in binary32, using the copy attached for `bits` -- chosen at call
- * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.  bits = 3 is served at
- * M = 1 only (K <= FQ_MAX_DECODE_K): FQ_ERR_BITS otherwise.
+ * time, nothing is repacked.  bits = 16 multiplies by the fp16 weights.
  *   x_fp16  device, fp16 [M][K], 16-byte aligned   (read)
  *   y_fp16  device, fp16 [M][N]                    (written)
  * 1 <= M <= FQ_MAX_DECODE_M with K <= FQ_MAX_DECODE_K selects the memory-bound skinny
- * kernels; anything else (prefill-shaped, any M >= 1) runs the MFMA dequant-GEMM.
+ * kernels; anything else (prefill-shaped, any M >= 1) runs the MFMA dequant-GEMM -- but for
+ * bits = 3, which the GEMM does not unpack: there the small-batch kernel runs the call in slabs of
+ * FQ_MAX_DECODE_M rows of x, one launch per slab, reading the weights once per slab.
  */
 int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
               void *y_fp16, void *stream);

@@ -259,21 +259,30 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *
         return fail(FQ_ERR_NOT_ATTACHED, "fq_linear: no %d-bit copy attached to this layer", bits);
     if (M < 1)
         return fail(FQ_ERR_SHAPE, "fq_linear: M must be >= 1 (got %d)", M);
-    if (bits == 3 && (M != 1 || layer->K > MAX_DECODE_K))
-        return fail(FQ_ERR_BITS, "fq_linear: the 3-bit copy is served by the batch-1 decode kernel only, M = 1 and K <= %d (got M=%d K=%d)",
-                    MAX_DECODE_K, M, layer->K);
     if (!aligned16(x_fp16) || (reinterpret_cast<uintptr_t>(y_fp16) & 1u))
         return fail(FQ_ERR_ALIGN, "fq_linear: x needs 16-byte and y 2-byte alignment");
     FqLinearDesc d;
     fill_desc(d, layer, x_fp16, y_fp16);
-    hipError_t e;
-    if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
+    hipError_t e = hipSuccess;
+    if (bits == 3 && (M > FQ_MAX_DECODE_M || layer->K > MAX_DECODE_K)) {
+        // The GEMM has no 3-bit unpacking: the small-batch kernel runs the call in slabs of
+        // FQ_MAX_DECODE_M batch rows (it walks K in chunks, whatever its length), reading the
+        // weights once per slab.
+        const int rows = 128;
+        const int tiles = (layer->N + rows - 1) / rows;
+        for (int m0 = 0; m0 < M && e == hipSuccess; m0 += FQ_MAX_DECODE_M) {
+            const int m = M - m0 < FQ_MAX_DECODE_M ? M - m0 : FQ_MAX_DECODE_M;
+            d.x = (const uint16_t *)x_fp16 + (size_t)m0 * layer->K;
+            d.y = (uint16_t *)y_fp16 + (size_t)m0 * layer->N;
+            e = fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, m, true, nullptr, nullptr, (hipStream_t)stream);
+        }
+    } else if (M <= FQ_MAX_DECODE_M && layer->K <= MAX_DECODE_K) {
         int rows = M == 1 ? fq_decode_tile_rows(layer->N, layer->K, M) : fq_skinny_tile_rows(layer->N, M);
-        if (M > 1 && bits == 2 && rows == 16) // the K-split kernel takes 4, 8 and 16 bits
+        if (M > 1 && bits == 2 && rows == 16) // the K-split kernel takes 3, 4, 8 and 16 bits
             rows = 64;
         const int tiles = (layer->N + rows - 1) / rows;
         e = M == 1 ? fq_launch_decode(&d, bits, nullptr, nullptr, 1, tiles, rows, layer->K, M, nullptr, (hipStream_t)stream)
-                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, nullptr, nullptr, (hipStream_t)stream);
+                   : fq_launch_skinny(&d, bits, nullptr, nullptr, 1, tiles, rows, M, bits == 3, nullptr, nullptr, (hipStream_t)stream);
     } else {
         e = fq_launch_prefill(d, bits, M, (hipStream_t)stream);
     }
@@ -353,7 +362,7 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
         return fail(FQ_ERR_SHAPE, "%s: M must be in 1..%d (got %d)", who, FQ_MAX_DECODE_M, M);
     long long total_rows = 0;
     int max_K = 0;
-    bool has2 = false;
+    bool has2 = false, has3 = false;
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
             return rc;
@@ -371,6 +380,7 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
         if (layers[i]->K > max_K)
             max_K = layers[i]->K;
         has2 = has2 || layers[i]->codes[3] != nullptr;
+        has3 = has3 || layers[i]->codes[4] != nullptr;
     }
     int rows = M == 1 ? fq_decode_tile_rows(total_rows, max_K, M) : fq_skinny_tile_rows(total_rows, M);
     // 256-row tiles at M > 1 mean the streaming kernel, whose tile queue deals runs of 8 tiles to 8
@@ -379,6 +389,11 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
         rows = 128;
     if (M > 1 && has2 && rows == 16) // the K-split kernel for launches with few rows has no 2-bit path
         rows = 64;
+    // the streaming kernel's stages are whole 128-byte lines of a row, which blocks of 12 bytes do not
+    // fill evenly: a batched plan that holds a 3-bit copy, whose entries may be switched to it at any
+    // token, runs on the register-fed kernel
+    if (M > 1 && has3 && rows == 256)
+        rows = 128;
     long long tiles = 0;
     for (int i = 0; i < count; i++) {
         fill_desc(table[i], layers[i], xs[i], ys[i]);
@@ -392,6 +407,7 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
     geom->total_tiles = (int)tiles;
     geom->max_K = max_K;
     geom->tile_rows = rows;
+    geom->has3 = has3 ? 1 : 0;
     return FQ_OK;
 }
 
@@ -403,7 +419,7 @@ hipError_t fq_plan_launch(const FqPlanGeom &g, const FqLinearDesc *table_dev, in
     hipError_t e = g.M == 1
         ? fq_launch_decode(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.max_K, g.M,
                            queue_dev ? queue_dev + FQ_Q_FLAGS : nullptr, stream)
-        : fq_launch_skinny(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.M, queue_dev,
+        : fq_launch_skinny(nullptr, 0, table_dev, bits_dev, g.count, g.total_tiles, g.tile_rows, g.M, g.has3 != 0, queue_dev,
                            order_dev, stream);
     return e;
 }

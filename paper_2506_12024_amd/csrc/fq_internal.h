@@ -19,7 +19,7 @@ struct FqLinearDesc {
     const uint8_t *codes2;  // [N][K/4] or null (not served by the streaming batch kernel and the GEMM)
     const float *scales2;
     const uint8_t *zeros2;
-    const uint8_t *codes3;  // [N][K/32] blocks of 12 bytes, or null (served at M = 1 only)
+    const uint8_t *codes3;  // [N][K/32] blocks of 12 bytes, or null (not served by the streaming batch kernel and the GEMM)
     const float *scales3;
     const uint8_t *zeros3;
     const uint16_t *x;      // fp16 [M][K]
@@ -33,6 +33,7 @@ struct FqLinearDesc {
 // Geometry of a plan: how its entries are cut into row tiles for the kernel that serves its M.
 struct FqPlanGeom {
     int count, M, total_tiles, tile_rows, max_K;
+    int has3; // some layer of the plan holds a 3-bit copy
 };
 struct fq_layer;
 // Records a message for fq_last_error() on the calling thread and returns `code`.
@@ -90,9 +91,11 @@ hipError_t fq_launch_decode_staged(const FqLinearDesc *table_dev, const int32_t 
                                    int *sync_dev, long long wait_limit, hipStream_t stream);
 
 // Same contract for 2 <= M <= 32 (MFMA skinny kernel); tile rows are 16 (K split), 64, 128 or 256.
+// with3: the launch may meet a 3-bit entry (the instance with the 3-bit path, which costs registers)
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int M, int *queue, void *order, hipStream_t stream);
+                            int total_tiles, int tile_rows, int M, bool with3, int *queue, void *order,
+                            hipStream_t stream);
 int fq_skinny_tile_rows(long long total_rows, int M);
 // Streaming variant for plan launches with 2 <= M <= 32 and tiles of 256 rows (fq_launch_skinny
 // hands those to it).

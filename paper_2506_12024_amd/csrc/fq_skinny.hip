@@ -105,7 +105,7 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
 {
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     const uint32_t K = (uint32_t)d.K;
-    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
+    const uint32_t row_bytes = BITS == 2 ? (K >> 2) : BITS == 3 ? (K >> 3) * 3 : BITS == 4 ? (K >> 1) : (BITS == 8 ? K : 2 * K);
 #pragma unroll
     for (int rt = 0; rt < RT; rt++) {
         const uint32_t row = (uint32_t)min(wave_row0 + rt * 16 + n, d.N - 1);
@@ -123,10 +123,36 @@ __device__ __forceinline__ void issue(const Sel &d, int wave_row0, int st, int n
                 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                 const u32x2 a = *(const FQ_GLOBAL u32x2 *)p, b = *(const FQ_GLOBAL u32x2 *)(p + second);
                 L.w[rt][ku] = make_uint4(a.x, a.y, b.x, b.y);
+            } else if (BITS == 3) {
+                // a load is one quantization group: the four lanes of a row take its four blocks of
+                // 12 bytes (32 codes each), 48 consecutive bytes of the row
+                typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+                typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
+                const u32x3 a = *(const FQ_GLOBAL u32x3_a4 *)(d.codes + (size_t)row * row_bytes + (li * 4 + c) * 12);
+                L.w[rt][ku] = make_uint4(a.x, a.y, a.z, 0u);
             } else {
                 L.w[rt][ku] = load16_weights(d.codes + (size_t)row * row_bytes + li * 64 + c * 16);
             }
         }
+    }
+}
+
+// Which 16-byte block of a chunk of x (batch row m, k block kb) a thread stages as its block `it`:
+// consecutive threads take consecutive k of one row; at 3 bits consecutive runs of four blocks
+// (32 k, one block of codes), a thread's blocks 4 u .. 4 u + 3 being one run.
+template <int BITS, class C>
+__device__ __forceinline__ void x_block(int it, int &m, int &kb)
+{
+    constexpr int BLK = C::KC / 8;
+    if (BITS == 3) {
+        static_assert(C::XPER % 4 == 0, "a thread stages whole runs of four blocks");
+        const int idx = (it >> 2) * C::STAGERS + C::tid();
+        m = idx / (BLK / 4);
+        kb = (idx % (BLK / 4)) * 4 + (it & 3);
+    } else {
+        const int idx = it * C::STAGERS + C::tid();
+        m = idx / BLK;
+        kb = idx % BLK;
     }
 }
 
@@ -137,12 +163,11 @@ template <int BITS, int MT, int RT, class C = Chunk<MT>>
 __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, int M, int wave_row0,
                                                int ch, Staged<MT, RT, C> &S)
 {
-    constexpr int BLK = C::KC / 8;
     const int kc = ch * C::KC;
 #pragma unroll
     for (int it = 0; it < C::XPER; it++) {
-        const int idx = it * C::STAGERS + C::tid();
-        const int m = idx / BLK, kb = idx % BLK; // consecutive threads: consecutive k of one row
+        int m, kb;
+        x_block<BITS, C>(it, m, kb);
         // rows past M and k past K are clamped: those blocks only feed outputs that are
         // never stored (rows) or are never read (k)
         const int mc = min(m, M - 1), k = min(kc + kb * 8, d.K - 8);
@@ -172,11 +197,42 @@ __device__ __forceinline__ void prefetch_chunk(const Sel &d, const uint16_t *x, 
 template <int BITS, int MT, int RT, class C = Chunk<MT>>
 __device__ __forceinline__ void commit_chunk(const Staged<MT, RT, C> &S, uint4 *lds_x, float *ms, uint8_t *mz)
 {
-    constexpr int ROWS = 16 * MT, BLK = C::KC / 8;
+    constexpr int ROWS = 16 * MT;
+    if (BITS == 3) {
+        // The 32 k of a lane's block of codes reach the MFMAs as 16 pairs in the order the unpacking
+        // meets them (pair 5 j + p = (x[10 j + p], x[10 j + 5 + p]), pair 15 = (x[30], x[31])), four
+        // pairs to an operand: a thread holds all four blocks of such a run and regroups them.
 #pragma unroll
-    for (int it = 0; it < C::XPER; it++) {
-        const int idx = it * C::STAGERS + C::tid();
-        const int m = idx / BLK, kb = idx % BLK;
+        for (int u4 = 0; u4 < C::XPER / 4; u4++) {
+            int m, kb;
+            x_block<BITS, C>(4 * u4, m, kb);
+            uint32_t w[16];
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                w[4 * q + 0] = S.x[4 * u4 + q].x;
+                w[4 * q + 1] = S.x[4 * u4 + q].y;
+                w[4 * q + 2] = S.x[4 * u4 + q].z;
+                w[4 * q + 3] = S.x[4 * u4 + q].w;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                uint32_t o[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int u = 4 * q + i;
+                    const int a = u < 15 ? 10 * (u / 5) + u % 5 : 30, b = u < 15 ? a + 5 : 31; // the pair (x[a], x[b])
+                    const uint32_t sel = ((b & 1) ? 0x07060000u : 0x05040000u) | ((a & 1) ? 0x0302u : 0x0100u);
+                    o[i] = __builtin_amdgcn_perm(w[b >> 1], w[a >> 1], sel);
+                }
+                lds_x[(kb + q) * ROWS + m] = make_uint4(o[0], o[1], o[2], o[3]);
+                asm volatile("" ::: "memory"); // one block at a time: the regrouped words are not all held at once
+            }
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < (BITS == 3 ? 0 : C::XPER); it++) {
+        int m, kb;
+        x_block<BITS, C>(it, m, kb);
         uint4 p = S.x[it];
         if (BITS == 2) {
             // Blocks kb (A = x0..7) and kb + 1 (B = x8..15) of 16 consecutive k, held by
@@ -296,7 +352,7 @@ __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4
                                         float4_t (&out)[RT][MT])
 {
     constexpr int ROWS = 16 * MT;
-    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32); // k per load
+    constexpr int KPL = BITS == 4 || BITS == 3 ? 128 : (BITS == 8 ? 64 : 32); // k per load
     constexpr int NM = KPL / 32;                                 // MFMAs per load
     constexpr int LPC = C::KC / KPL;                             // loads per chunk
     const int li = st * KU + ku;
@@ -326,7 +382,50 @@ __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4
         for (int rt = 0; rt < RT; rt++) {
             const uint32_t ww[4] = {L.w[rt][ku].x, L.w[rt][ku].y, L.w[rt][ku].z, L.w[rt][ku].w};
             uint32_t b[4];
-            if (BITS == 4) {
+            if (BITS == 3) {
+                // Word j of the block holds the codes 10 j + 5 h + p (h: the word's halves, p = 0 .. 4:
+                // bits 3 p .. 3 p + 2 of the half); a field at bit 0 / 3 / 6 of a half reads as 1024 + q /
+                // 128 + q / 16 + q under the exponents 0x64 / 0x58 / 0x4C, the fields p = 3, 4 after a
+                // shift by 9 bits.  Bit 15 of the halves of word j is bit j of the codes 30 and 31:
+                // after that shift it sits at bit 6, worth 1 / 2 / 4 under the exponents of 16 / 32 /
+                // 64, and the three add up to 112 + q exactly.  Pair 5 j + p is the operand's k, four
+                // pairs to an MFMA (x is staged in that order).
+                const uint32_t zz = z[rt] | (z[rt] << 16);
+                const uint32_t nz0 = zz | 0xE400E400u, nz1 = (zz << 3) | 0xD800D800u, nz2 = (zz << 6) | 0xCC00CC00u;
+                const uint32_t M0 = 0x00070007u, M1 = 0x00380038u, M2 = 0x01C001C0u;
+                const uint32_t e0 = 0x64006400u, e1 = 0x58005800u, e2 = 0x4C004C00u;
+                auto pair = [&](int j, int p) -> uint32_t {
+                    const uint32_t v = p < 3 ? ww[j] : ww[j] >> 9;
+                    const int f = p < 3 ? p : p - 3;
+                    return f == 0   ? pk_add((v & M0) | e0, nz0)
+                           : f == 1 ? pk_add((v & M1) | e1, nz1)
+                                    : pk_add((v & M2) | e2, nz2);
+                };
+                if (i == 0) {
+                    b[0] = pair(0, 0);
+                    b[1] = pair(0, 1);
+                    b[2] = pair(0, 2);
+                    b[3] = pair(0, 3);
+                } else if (i == 1) {
+                    b[0] = pair(0, 4);
+                    b[1] = pair(1, 0);
+                    b[2] = pair(1, 1);
+                    b[3] = pair(1, 2);
+                } else if (i == 2) {
+                    b[0] = pair(1, 3);
+                    b[1] = pair(1, 4);
+                    b[2] = pair(2, 0);
+                    b[3] = pair(2, 1);
+                } else {
+                    b[0] = pair(2, 2);
+                    b[1] = pair(2, 3);
+                    b[2] = pair(2, 4);
+                    const uint32_t t0 = ((ww[0] >> 9) & 0x00400040u) | 0x4C004C00u; // 16 + bit 0
+                    const uint32_t t1 = ((ww[1] >> 9) & 0x00400040u) | 0x50005000u; // 32 + 2 bit 1
+                    const uint32_t t2 = ((ww[2] >> 9) & 0x00400040u) | 0x54005400u; // 64 + 4 bit 2
+                    b[3] = pk_add(pk_add(pk_add(t0, t1), t2), (zz << 4) | 0xD700D700u); // - (112 + z)
+                }
+            } else if (BITS == 4) {
                 const uint32_t nz_lo = (z[rt] | (z[rt] << 16)) | 0xE400E400u;        // -(1024 + z) twice
                 const uint32_t nz_hi = ((z[rt] << 4) | (z[rt] << 20)) | 0xD400D400u; // -(  64 + z) twice
                 const uint32_t v = ww[i], v8 = v >> 8;
@@ -352,8 +451,8 @@ __device__ __forceinline__ void compute(int st, const Loaded<RT> &L, const uint4
                 acc[rt][mt] = mfma(a[mt], b, acc[rt][mt]);
         }
     }
-    // group complete: 4-bit after every load, 8-bit after every second load
-    constexpr bool group_end = BITS == 4 || (BITS == 8 && ku == 1);
+    // group complete: 3- and 4-bit after every load, 8-bit after every second load
+    constexpr bool group_end = BITS == 4 || BITS == 3 || (BITS == 8 && ku == 1);
     if (group_end) {
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
@@ -370,7 +469,7 @@ __device__ __forceinline__ void run_tile(const Sel &d, const uint16_t *x, uint16
                                          int wave_row0, uint4 *lds_x, float *ms, uint8_t *mz)
 {
     typedef Chunk<MT> C;
-    constexpr int KPL = BITS == 2 ? 256 : BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
+    constexpr int KPL = BITS == 2 ? 256 : BITS == 4 || BITS == 3 ? 128 : (BITS == 8 ? 64 : 32);
     constexpr int SPC = C::KC / KPL / KU; // steps per chunk
     const int nload = (d.K + KPL - 1) / KPL; // 2 bits: a last load may hold one group only
     const int nstep = (nload + KU - 1) / KU;
@@ -446,7 +545,7 @@ __device__ __forceinline__ void run_tile_sk(const Sel &d, const uint16_t *x, uin
 {
     typedef Chunk<MT, true> C;
     constexpr int RT = 1;
-    constexpr int KPL = BITS == 4 ? 128 : (BITS == 8 ? 64 : 32);
+    constexpr int KPL = BITS == 4 || BITS == 3 ? 128 : (BITS == 8 ? 64 : 32);
     constexpr int SPC = C::KC / KPL / KU; // steps per chunk: 1 / 2 / 4
     const int nload = d.K / KPL;
     const int nstep = (nload + KU - 1) / KU;
@@ -528,7 +627,9 @@ __device__ __forceinline__ void run_tile_sk(const Sel &d, const uint16_t *x, uin
     __syncthreads(); // `red` is free again
 }
 
-template <bool SINGLE, int MT>
+// W3: with the 3-bit path (its unpacking and the regrouping of x cost registers: a launch that cannot
+// meet a 3-bit entry runs the instance without)
+template <bool SINGLE, int MT, bool W3>
 __global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLinearDesc single, int bits_host,
                                                                       const FqLinearDesc *__restrict__ table,
                                                                       const int32_t *__restrict__ bits_dev,
@@ -556,16 +657,22 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLi
         Sel d;
         d.N = dp->N;
         d.K = dp->K;
-        d.codes = bits == 4 ? dp->codes4 : bits == 8 ? dp->codes8 : bits == 16 ? (const uint8_t *)dp->w16 : nullptr;
-        d.scales = bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.codes = bits == 3    ? (W3 ? dp->codes3 : nullptr)
+                  : bits == 4  ? dp->codes4
+                  : bits == 8  ? dp->codes8
+                  : bits == 16 ? (const uint8_t *)dp->w16
+                               : nullptr;
+        d.scales = bits == 3 ? dp->scales3 : bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 3 ? dp->zeros3 : bits == 4 ? dp->zeros4 : dp->zeros8;
         if (!d.codes) { // uniform over the workgroup
             if (flags && threadIdx.x == 0)
                 *flags = 1; // no such width here, or no copy of it: nobody runs this entry
             continue;
         }
         const int row0 = (tile - dp->tile_begin) * 16;
-        if (bits == 4)
+        if (W3 && bits == 3)
+            run_tile_sk<3, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
+        else if (bits == 4)
             run_tile_sk<4, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
         else if (bits == 8)
             run_tile_sk<8, MT>(d, dp->x, dp->y, M, row0, wave, lds_x[wave], lds_s[wave], lds_z[wave], red);
@@ -574,7 +681,7 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_sk_kernel(const FqLi
     }
 }
 
-template <bool SINGLE, int MT, int RT>
+template <bool SINGLE, int MT, int RT, bool W3>
 __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinearDesc single,
                                                                    int bits_host,
                                                                    const FqLinearDesc *__restrict__ table,
@@ -605,12 +712,13 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
         d.N = dp->N;
         d.K = dp->K;
         d.codes = bits == 2    ? dp->codes2
+                  : bits == 3  ? (W3 ? dp->codes3 : nullptr)
                   : bits == 4  ? dp->codes4
                   : bits == 8  ? dp->codes8
                   : bits == 16 ? (const uint8_t *)dp->w16
                                : nullptr;
-        d.scales = bits == 2 ? dp->scales2 : bits == 4 ? dp->scales4 : dp->scales8;
-        d.zeros = bits == 2 ? dp->zeros2 : bits == 4 ? dp->zeros4 : dp->zeros8;
+        d.scales = bits == 2 ? dp->scales2 : bits == 3 ? dp->scales3 : bits == 4 ? dp->scales4 : dp->scales8;
+        d.zeros = bits == 2 ? dp->zeros2 : bits == 3 ? dp->zeros3 : bits == 4 ? dp->zeros4 : dp->zeros8;
         if (!d.codes) { // uniform over the workgroup
             if (flags && threadIdx.x == 0)
                 *flags = 1; // no such width here, or no copy of it: nobody runs this entry
@@ -621,6 +729,8 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
         const int wave_row0 = t * TILE_ROWS + wave * RT * 16;
         if (bits == 2)
             run_tile<2, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
+        else if (W3 && bits == 3)
+            run_tile<3, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
         else if (bits == 4)
             run_tile<4, MT, RT>(d, dp->x, dp->y, M, wave_row0, lds_x, lds_s[wave], lds_z[wave]);
         else if (bits == 8)
@@ -630,46 +740,63 @@ __global__ __launch_bounds__(WG_THREADS) void decode_skinny_kernel(const FqLinea
     }
 }
 
-template <int MT, int RT>
-int resident(int cus)
-{
-    return cus * fq_workgroups_per_cu((const void *)decode_skinny_kernel<false, MT, RT>, WG_THREADS, 0, 2);
-}
-
-template <int MT, int RT>
+template <int MT, int RT, bool W3>
 hipError_t launch(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
                   const int32_t *bits_dev, int count, int total_tiles, int M, int cus,
                   hipStream_t stream, int *flags = nullptr)
 {
-    const int cap = resident<MT, RT>(cus);
+    const int cap = cus * fq_workgroups_per_cu((const void *)decode_skinny_kernel<false, MT, RT, W3>, WG_THREADS, 0, 2);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
-        decode_skinny_kernel<true, MT, RT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr,
-                                                                           nullptr, 1, total_tiles, M, nullptr);
+        decode_skinny_kernel<true, MT, RT, W3><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr,
+                                                                               nullptr, 1, total_tiles, M, nullptr);
     } else {
         FqLinearDesc none = {};
-        decode_skinny_kernel<false, MT, RT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev,
-                                                                            count, total_tiles, M, flags);
+        decode_skinny_kernel<false, MT, RT, W3><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev,
+                                                                                count, total_tiles, M, flags);
     }
     return hipGetLastError();
 }
 
-template <int MT>
+template <int MT, bool W3>
 hipError_t launch_sk(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
                      const int32_t *bits_dev, int count, int total_tiles, int M, int cus, hipStream_t stream,
                      int *flags = nullptr)
 {
-    const int cap = cus * fq_workgroups_per_cu((const void *)decode_skinny_sk_kernel<false, MT>, WG_THREADS, 0, 2);
+    const int cap = cus * fq_workgroups_per_cu((const void *)decode_skinny_sk_kernel<false, MT, W3>, WG_THREADS, 0, 2);
     const int grid = total_tiles < cap ? total_tiles : cap;
     if (single) {
-        decode_skinny_sk_kernel<true, MT><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1,
-                                                                        total_tiles, M, nullptr);
+        decode_skinny_sk_kernel<true, MT, W3><<<grid, WG_THREADS, 0, stream>>>(*single, bits_host, nullptr, nullptr, 1,
+                                                                            total_tiles, M, nullptr);
     } else {
         FqLinearDesc none = {};
-        decode_skinny_sk_kernel<false, MT><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count,
-                                                                         total_tiles, M, flags);
+        decode_skinny_sk_kernel<false, MT, W3><<<grid, WG_THREADS, 0, stream>>>(none, 0, descs_dev, bits_dev, count,
+                                                                             total_tiles, M, flags);
     }
     return hipGetLastError();
+}
+
+template <bool W3>
+hipError_t launch_any(const FqLinearDesc *single, int bits_host, const FqLinearDesc *descs_dev,
+                      const int32_t *bits_dev, int count, int total_tiles, int tile_rows, int M, int cus,
+                      hipStream_t stream, int *fl)
+{
+    const int rt = tile_rows / 64;
+    if (tile_rows == 16)
+        return M <= 16 ? launch_sk<1, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl)
+                       : launch_sk<2, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    if (M <= 16) {
+        if (rt == 4)
+            return launch<1, 4, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+        if (rt == 2)
+            return launch<1, 2, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+        return launch<1, 1, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    }
+    if (rt == 4)
+        return launch<2, 4, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    if (rt == 2)
+        return launch<2, 2, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    return launch<2, 1, W3>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
 }
 
 int device_cus() { return fq_device_cus(); }
@@ -694,28 +821,15 @@ int fq_skinny_tile_rows(long long total_rows, int M)
 
 hipError_t fq_launch_skinny(const FqLinearDesc *single, int bits_host,
                             const FqLinearDesc *descs_dev, const int32_t *bits_dev, int count,
-                            int total_tiles, int tile_rows, int M, int *queue, void *order, hipStream_t stream)
+                            int total_tiles, int tile_rows, int M, bool with3, int *queue, void *order,
+                            hipStream_t stream)
 {
     if (total_tiles <= 0)
         return hipSuccess;
     const int cus = device_cus();
-    const int rt = tile_rows / 64;
     int *fl = !single && queue ? queue + FQ_Q_FLAGS : nullptr;
     if (!single && tile_rows == 256)
         return fq_launch_skinny_stream(descs_dev, bits_dev, count, total_tiles, M, cus, queue, order, stream);
-    if (tile_rows == 16)
-        return M <= 16 ? launch_sk<1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl)
-                       : launch_sk<2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-    if (M <= 16) {
-        if (rt == 4)
-            return launch<1, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-        if (rt == 2)
-            return launch<1, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-        return launch<1, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-    }
-    if (rt == 4)
-        return launch<2, 4>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-    if (rt == 2)
-        return launch<2, 2>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
-    return launch<2, 1>(single, bits_host, descs_dev, bits_dev, count, total_tiles, M, cus, stream, fl);
+    return with3 ? launch_any<true>(single, bits_host, descs_dev, bits_dev, count, total_tiles, tile_rows, M, cus, stream, fl)
+                 : launch_any<false>(single, bits_host, descs_dev, bits_dev, count, total_tiles, tile_rows, M, cus, stream, fl);
 }

@@ -1,7 +1,8 @@
 """GPU parity of the packed 3-bit path (Table 1 / Sec. 5.1 run 3-bit models; Sec. 2.2 Eq. (2), (3)
 with n = 3; the packing is this library's, blocks of 12 bytes) against the CPU oracle: codes,
 scales and zero points bit-exact, decode outputs at M = 1 (single calls, one-launch plans and
-stage-ordered plans that mix 2 / 3 / 4 / 8 / 16 bits per entry) within 2e-3 max-abs normalised."""
+stage-ordered plans that mix 2 / 3 / 4 / 8 / 16 bits per entry), in batches of 2 to 32 rows (single
+calls and plans) and above (slabs of 32 rows) within 2e-3 max-abs normalised."""
 import numpy as np
 import pytest
 import torch
@@ -88,16 +89,49 @@ def test_linear_3bit_integer_case_exact():
         assert np.array_equal(gpu_linear(layer, 3, x1)[0].astype(np.int64), w[:, k]), k
 
 
-def test_3bit_is_refused_above_m1():
-    w = synth.weight(0, "par3/refuse", 64, 256, 0.02)
-    layer, _ = make_layer(w, (3, 4))
-    x = to_dev(synth.activations(0, "par3/refuse/x", 2, 256))
-    y = torch.zeros((2, 64), dtype=torch.float16, device=DEV)
-    with pytest.raises(fq.FlexqError) as e:
-        fq.fq_linear(layer, 3, x, 2, y)
-    assert "3-bit" in str(e.value)
-    fq.fq_linear(layer, 4, x, 2, y)
-    torch.cuda.synchronize()
+# batches of the small-batch kernels (one and two batch tiles; K: a single group, an odd number of
+# groups, several chunks of x with a ragged last one; N: ragged tiles) and, above 32 rows and past
+# the longest row the decode kernels take, the same kernel in slabs of 32 batch rows
+@pytest.mark.parametrize("N,K,M", [(4096, 4096, 16), (100, 1408, 2), (37, 128, 5), (530, 5120, 17), (64, 11008, 32),
+                                   (200, 384, 8), (2000, 2048, 4), (16, 13824, 3), (300, 1024, 40),
+                                   (256, 4096, 100), (130, 2432, 33), (48, 32768 + 128, 1), (48, 32768 + 128, 3)])
+def test_linear_3bit_batched_matches_oracle(N, K, M):
+    w = synth.weight(0, "par3/blin/%dx%d" % (N, K), N, K, 0.02, outlier_p=0.001)
+    x = synth.activations(0, "par3/blin/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (3,))
+    y = gpu_linear(layer, 3, x)
+    c, s, z = (t.cpu().numpy() for t in packed[3])
+    y_ref = oracle.linear(x, c, s, z, 3)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+
+
+@pytest.mark.parametrize("M", [2, 16, 21, 37])
+def test_linear_3bit_batched_integer_case_exact(M):
+    # as at M = 1: integer codes (s = 1, z = 0) and small integer x make every product and partial
+    # sum an integer below 2^24, so the batched kernels must return the integer matrix product
+    # exactly; one-hot rows of x read every position of a 32-code block back
+    rng = np.random.default_rng(11 + M)
+    N, K = 80, 1024 + 384
+    w = rng.integers(0, 8, size=(N, K))
+    w[:, 0::128] = 0
+    w[:, 1::128] = 7
+    x = (rng.integers(-2, 3, size=(M, K)) * (rng.random((M, K)) < 0.25)).astype(np.float16)
+    layer, packed = make_layer(w.astype(np.float16), (3,))
+    assert torch.all(packed[3][1] == 1.0) and torch.all(packed[3][2] == 0)
+    y = gpu_linear(layer, 3, x)
+    expect = x.astype(np.float64) @ w.T.astype(np.float64)
+    assert np.abs(expect).max() < 2048
+    assert np.array_equal(y.astype(np.float64), expect)
+    ks = list(range(0, 34)) + [63, 64, 127, 128, 1023, 1024, K - 1]
+    for k0 in range(0, len(ks), M):
+        part = ks[k0:k0 + M]
+        x1 = np.zeros((M, K), dtype=np.float16)
+        for m, k in enumerate(part):
+            x1[m, k] = 1
+        y1 = gpu_linear(layer, 3, x1)
+        for m, k in enumerate(part):
+            assert np.array_equal(y1[m].astype(np.int64), w[:, k]), k
 
 
 def _refs(xs_np, packs, pattern):
@@ -145,22 +179,34 @@ def test_plans_with_3bit_entries_match_individual_calls_and_oracle():
             assert rel_err(ys2[i].cpu().numpy(), y_ref) <= TOL_Y, ("staged", trial, i, b)
 
 
-def test_batched_plan_skips_3bit_entries():
-    # above M = 1 there is no 3-bit kernel: such an entry is left untouched, like any entry whose
-    # bit-width the plan cannot serve
-    shapes = [(256, 1024), (128, 512)]
-    layers, xs, ys = [], [], []
+@pytest.mark.parametrize("M,widths", [(4, (3, 4, 8, 16)), (4, (2, 3, 4, 8, 16)), (20, (3, 4, 8, 16)), (16, (2, 3, 8))])
+def test_batched_plans_with_3bit_entries(M, widths):
+    # small plans: the kernel whose wavefronts split K (no layer holds a 2-bit copy) or the
+    # register-fed kernel in 64-row tiles; within tolerance of the oracle under patterns that move
+    # the 3-bit entries around
+    shapes = [(256, 1024), (100, 1408), (512, 4096), (64, 11008), (40, 128), (300, 4096)]
+    layers, xs, ys, xs_np, packs = [], [], [], [], []
     for i, (N, K) in enumerate(shapes):
-        layer, _ = make_layer(synth.weight(0, "par3/skip/w%d" % i, N, K, 0.02), (3, 4))
+        w = synth.weight(0, "par3/bplan/w%d" % i, N, K, 0.02, outlier_p=0.001)
+        layer, packed = make_layer(w, widths)
+        x = synth.activations(0, "par3/bplan/x%d/%d" % (i, M), M, K)
         layers.append(layer)
-        xs.append(to_dev(synth.activations(0, "par3/skip/x%d" % i, 4, K)))
-        ys.append(torch.full((4, N), 7.0, dtype=torch.float16, device=DEV))
-    ws = torch.empty(fq.Plan.workspace_bytes(2), dtype=torch.uint8, device=DEV)
-    plan = fq.Plan(layers, xs, ys, 4, ws)
-    plan.run(torch.tensor([3, 4], dtype=torch.int32, device=DEV))
-    torch.cuda.synchronize()
-    assert torch.all(ys[0] == 7.0)
-    assert not torch.all(ys[1] == 7.0)
+        packs.append((w, packed))
+        xs_np.append(x)
+        xs.append(to_dev(x))
+        ys.append(torch.zeros((M, N), dtype=torch.float16, device=DEV))
+    ws = torch.empty(fq.Plan.workspace_bytes(len(layers)), dtype=torch.uint8, device=DEV)
+    plan = fq.Plan(layers, xs, ys, M, ws)
+    rng = np.random.default_rng(M)
+    patterns = [[3] * len(shapes)] + [[int(b) for b in rng.choice(widths, size=len(shapes))] for _ in range(3)]
+    for trial, pattern in enumerate(patterns):
+        for y in ys:
+            y.fill_(float("nan"))
+        plan.run(torch.tensor(pattern, dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert plan.status()[1] == 0
+        for i, (b, y_ref) in enumerate(zip(pattern, _refs(xs_np, packs, pattern))):
+            assert rel_err(ys[i].cpu().numpy(), y_ref) <= TOL_Y, (trial, i, b)
 
 
 def test_plan_of_layers_that_hold_only_a_3bit_copy():

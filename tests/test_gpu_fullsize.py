@@ -152,6 +152,13 @@ def test_llama7b_stack_batch16_bits_2_4_8():
     _check_stack(st, steps=(2,), n_entries=21, rows_per_entry=3, rng=np.random.default_rng(5))
 
 
+def test_llama7b_stack_batch16_bits_3_4_8():
+    # a plan of the streaming kernel's size whose layers hold 3-bit copies: the register-fed kernel
+    # in 128-row tiles serves every entry
+    st = bench.Stack("llama7b", M=16, bit_choices=(3, 4, 8))
+    _check_stack(st, steps=(4,), n_entries=21, rows_per_entry=3, rng=np.random.default_rng(6))
+
+
 def test_llama13b_stack_batch8_outliers():
     st = bench.Stack("llama13b", M=8, bit_choices=(4, 8))
     _check_stack(st, steps=(5,), n_entries=21, rows_per_entry=4, rng=np.random.default_rng(2))

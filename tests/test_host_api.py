@@ -184,14 +184,14 @@ def test_w8a8_validation():
 
 def test_2bit_copy_limits():
     L = fq.lib
+    vp_odd = ctypes.c_void_p(FAKE + 1)
     assert fq.fq_packed_sizes(4096, 4096, 2) == (4096 * 4096 // 4, 4096 * 32 * 4, 4096 * 32)
     h = ctypes.c_void_p()
     assert L.fq_layer_create(ctypes.byref(h), 64, 256, 128) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, FAKE, FAKE) == B.FQ_OK
     assert L.fq_layer_attach(h, 2, FAKE, None, FAKE) == B.FQ_ERR_NULL
     assert L.fq_layer_attach(h, 3, FAKE, FAKE, FAKE) == B.FQ_OK
-    assert L.fq_linear(h, 3, FAKE, 2, FAKE, None) == B.FQ_ERR_BITS  # 3 bits: batch 1 only
-    assert "3-bit" in fq.fq_last_error()
+    assert L.fq_linear(h, 3, FAKE, 2, vp_odd, None) == B.FQ_ERR_ALIGN  # 3 bits at any batch: checked like the others
     assert L.fq_linear(h, 4, FAKE, 1, FAKE, None) == B.FQ_ERR_NOT_ATTACHED
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
