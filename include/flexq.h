@@ -180,7 +180,7 @@ int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M,
  *              draws up for its bit-widths: runs of one plan must not overlap in time
  *              (they would share these, and they write the same ys)
  *   bits_dev   device, int32 [count], each 2, 3, 4, 8 or 16 and attached to its layer;
- *              an entry whose value is anything else (or 3 in a plan with M > 1) is skipped
+ *              an entry whose value is anything else is skipped
  *              by the kernel and its y is left untouched.  Such a run sets bit 0 of the plan's
  *              flags, a word in the workspace that stays set and that fq_plan_status reports
  *              (gave_up is always 0 for these plans)
