@@ -173,6 +173,34 @@ class Stack:
             plan.run(bits[first:first + n])
 
 
+def dependent_order_as_launches(stack: "Stack", W: int, K_steps: int) -> dict:
+    """The dependent order as separate launches: 4 plan launches per decoder layer (q/k/v, o, gate/up,
+    down), captured once in a HIP graph and replayed; milliseconds per step."""
+    import torch
+    stack.build_stage_plans()
+    stack.run_linears_staged(W)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        stack.run_linears_staged(W)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            stack.run_linears_staged(W)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = max(8, K_steps // 4)
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / reps * 1e3
+    return {"dependent_order_as_%d_launches_ms" % len(stack.stage_plans): ms,
+            "dependent_order_as_launches_tokens_per_s": stack.M * 1e3 / ms}
+
+
 def _set_omp_threads(n: int) -> bool:
     """Number of threads of the OpenMP runtime the oracle's library runs on (the oracle itself is
     untouched: this is the call OMP_NUM_THREADS would make at start-up)."""
@@ -860,30 +888,13 @@ def main():
             ind["switching"] = switching_cost(stack.plan, ind_ms)
         out["independent_order"] = ind
         if args.staged:
-            # the dependent order as separate launches: 4 plan launches per layer, captured in a HIP graph
-            stack.build_stage_plans()
-            stack.run_linears_staged(W)
-            torch.cuda.synchronize()
-            side = torch.cuda.Stream()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(side):
-                stack.run_linears_staged(W)
-                side.synchronize()
-                with torch.cuda.graph(graph, stream=side):
-                    stack.run_linears_staged(W)
-            torch.cuda.synchronize()
-            for _ in range(3):
-                graph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            reps = max(8, K_steps // 4)
-            for _ in range(reps):
-                graph.replay()
-            torch.cuda.synchronize()
-            out["dependent_order_as_%d_launches_ms" % len(stack.stage_plans)] = (time.perf_counter() - t0) / reps * 1e3
+            out.update(dependent_order_as_launches(stack, W, K_steps))
     else:
         traffic, source = measured_traffic()
         out["roofline"] = roofline(kernel_of["independent"], lin_ms, traffic, source)
+        if args.staged:
+            # batches above 1 have no stage-ordered launch: the dependent order is 4 plan launches per layer
+            out.update(dependent_order_as_launches(stack, W, K_steps))
     if switching is not None:
         out["switching"] = switching
     if not args.no_cpu_baseline:

@@ -473,7 +473,7 @@ int fq_plan_create(fq_plan **out, int count, const fq_layer *const *layers, cons
 // Layout of a stage-ordered plan's workspace: table | stage_begin | sync words.
 static size_t staged_table_bytes(int count) { return ((size_t)count * sizeof(FqLinearDesc) + 255) / 256 * 256; }
 static size_t staged_begin_bytes(int n_stages) { return ((size_t)(n_stages + 1) * 4 + 255) / 256 * 256; }
-constexpr size_t STAGED_SYNC_BYTES = 8192; // 32 counters on lines of their own, then the status words
+constexpr size_t STAGED_SYNC_BYTES = FQ_STAGED_SYNC_BYTES;
 constexpr int STAGED_RES_CHUNKS = 1024; // 4-row chunks of one stage a workgroup can hold results for
 constexpr long long STAGED_WAIT_LIMIT = 1LL << 21; // about a second of polling
 
@@ -582,7 +582,7 @@ int fq_plan_status(const fq_plan *plan, int32_t *gave_up, int32_t *flags, void *
     int32_t words[2] = {0, 0}; // the sticky count of launches that gave up, then the flags
     hipError_t e = plan->n_stages < 1 // a plan of independent entries has no waits to give up
         ? hipMemcpyAsync(words + 1, plan->queue_dev + FQ_Q_FLAGS, sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)stream)
-        : hipMemcpyAsync(words, plan->sync_dev + 32 * 32 + 1, sizeof words, hipMemcpyDeviceToHost, (hipStream_t)stream);
+        : hipMemcpyAsync(words, plan->sync_dev + 1, sizeof words, hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess)
         e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess)

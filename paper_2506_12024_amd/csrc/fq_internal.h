@@ -86,6 +86,8 @@ int fq_decode_tile_rows(long long total_rows, int max_K, int M);
 // launched with (0 = does not fit the current device).
 size_t fq_staged_lds_bytes(int n_stages, int max_K, int res_chunks);
 int fq_staged_grid(size_t lds_bytes);
+// Bytes of a stage-ordered plan's sync words: status words, then the arrival counters of the barrier.
+constexpr size_t FQ_STAGED_SYNC_BYTES = 32768;
 hipError_t fq_launch_decode_staged(const FqLinearDesc *table_dev, const int32_t *bits_dev,
                                    const int32_t *stage_begin_dev, int n_stages, int max_K, int res_chunks,
                                    int *sync_dev, long long wait_limit, hipStream_t stream);

@@ -30,13 +30,14 @@
 // bit-width array), and an entry's 4-row chunks are dealt evenly to its workgroups.  So a stage
 // needs one x per workgroup, staged once, right after the barrier.
 //
-// Barrier.  NC arrival counters on lines of their own (workgroup b adds to counter b % NC: adds to
-// one address are served one after the other, with 32 workgroups behind one counter they alone
-// took 2 to 3 microseconds) count up through the launch: after stage s counter l holds (s + 1) *
-// (workgroups with b % NC = l).  One more word is the abort flag.  The wait is bounded: a service
+// Barrier.  Every workgroup has an arrival word of its own that counts up through the launch: after
+// its rows of stage s are acknowledged it stores s + 1 there (a plain write-through store; adds to
+// shared counters are served one after the other where the counter lives, and with 8 workgroups
+// behind each of 32 counters they still cost 0.6 us per stage), and a poll reads all the words, four
+// per lane.  One more word is the abort flag.  The wait is bounded: a service
 // wavefront that has polled `wait_limit` times raises the abort flag and, if it is the first, adds
 // one to a sticky count; every waiter sees the flag at its next poll and every workgroup leaves the
-// kernel.  The last workgroup out (one more counter) puts the counters and the flag back to zero,
+// kernel.  The last workgroup out (one more counter) puts the words and the flag back to zero,
 // so that the next launch, and a replayed HIP graph, find them clean.  All workgroups must be
 // resident together (the host launches at most as many as fit).
 //
@@ -400,42 +401,68 @@ __device__ __forceinline__ void store_share_y(const Share *sh, const float *part
     }
 }
 
-// Layout of the plan's sync words (ints): counter l at 32 l (l = 0 .. NC - 1), then the abort flag,
-// the sticky count of launches that gave up, flags (bit 0: an entry's bit-width is not attached to
-// its layer, its y was left untouched; bit 1: a share too large for the results buffer), and on the
-// next line the count of finished workgroups.
-constexpr int NC = 32; // arrival counters
-constexpr int SY_ABORT = 32 * NC, SY_GAVE_UP = SY_ABORT + 1, SY_FLAGS = SY_ABORT + 2, SY_DONE = SY_ABORT + 32;
+// Layout of the plan's sync words (ints): the abort flag, the sticky count of launches that gave
+// up, flags (bit 0: an entry's bit-width is not attached to its layer, its y was left untouched;
+// bit 1: a share too large for the results buffer), on the next line the count of finished
+// workgroups, and from SY_COUNTERS on the NC arrival counters, CSTRIDE ints apart.
+constexpr int NC = 128;     // arrival counters (workgroup b adds to counter b % NC)
+constexpr int CSTRIDE = 32; // ints between two counters: a line each
+constexpr int CPL = (NC + 63) / 64;  // counters a polling lane watches
+static_assert(NC >= 1 && CPL <= 4, "a lane polls up to four counters");
+constexpr int SY_ABORT = 0, SY_GAVE_UP = 1, SY_FLAGS = 2, SY_DONE = 32, SY_COUNTERS = 64;
+static_assert((SY_COUNTERS + NC * CSTRIDE) * 4 <= FQ_STAGED_SYNC_BYTES, "the sync words fit the plan's workspace");
+
+struct Polled {
+    int c[CPL];
+    int flag;
+};
 
 // Waits until every workgroup has arrived at the end of stage s.  False: the launch is aborted.
-// Lanes 0 .. NC - 1 watch one counter each, lane NC the abort flag.  A poll is a round trip to memory of a
-// microsecond or more, so four are kept in flight, a fraction of that apart: the arrival of the last
-// workgroup is seen one round trip after it happened, not up to two.
+// Lane l watches counter l (and l + 64), lane 0 the abort flag besides.  A poll is a round trip to
+// memory of a microsecond or more, so two are kept in flight: the arrival of the last workgroup is
+// seen about one round trip after it happened, not up to two.  (A poll is 129 requests of the
+// workgroup, and the polls of 256 workgroups compete with the arrivals they wait for: 7B-shaped
+// step with 8 / 6 / 4 / 3 / 2 polls in flight: 1.58 / 1.56 / 1.51 / 1.50 / 1.50 ms.)
 __device__ __forceinline__ bool wait_stage(int *sync, int s, int G, long long wait_limit)
 {
     const int lane = threadIdx.x & 63;
-    const int mine = lane < NC ? (s + 1) * ((G - lane + NC - 1) / NC) : 0;
-    const int *word = &sync[lane < NC ? 32 * lane : SY_ABORT];
-    auto poll = [&]() -> int {
-        return lane <= NC ? __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    int mine[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; i++)
+        mine[i] = lane + 64 * i < NC ? (s + 1) * ((G - (lane + 64 * i) + NC - 1) / NC) : 0; // workgroups b with b % NC = lane + 64 i
+    auto poll = [&]() -> Polled {
+        Polled p;
+#pragma unroll
+        for (int i = 0; i < CPL; i++)
+            p.c[i] = lane + 64 * i < NC ? __hip_atomic_load(&sync[SY_COUNTERS + CSTRIDE * (lane + 64 * i)], __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT)
+                                        : 0;
+        p.flag = 0;
+        if (lane == 0)
+            p.flag = __hip_atomic_load(&sync[SY_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return p;
     };
-    constexpr int Q = 4;
-    int v[Q];
+    constexpr int Q = 2;
+    Polled v[Q];
 #pragma unroll
     for (int q = 0; q + 1 < Q; q++) {
         v[q] = poll();
-        __builtin_amdgcn_s_sleep(4);
+        __builtin_amdgcn_s_sleep(1);
     }
     for (long long it = 0;; it += Q) {
 #pragma unroll
         for (int q = 0; q < Q; q++) {
             v[(q + Q - 1) % Q] = poll();
-            const int got = v[q]; // the oldest of the polls in flight
-            if (__builtin_amdgcn_readlane(got, NC))
+            const Polled got = v[q]; // the oldest of the polls in flight
+            if (__builtin_amdgcn_readfirstlane(got.flag))
                 return false;
-            if (__builtin_amdgcn_ballot_w64(lane >= NC || got >= mine) == ~0ull)
+            bool ok = true;
+#pragma unroll
+            for (int i = 0; i < CPL; i++)
+                ok = ok && got.c[i] >= mine[i];
+            if (__builtin_amdgcn_ballot_w64(ok) == ~0ull)
                 return true;
-            __builtin_amdgcn_s_sleep(4);
+            __builtin_amdgcn_s_sleep(1);
         }
         if (it >= wait_limit) {
             // the first to give up in this launch raises the flag and counts the launch
@@ -539,7 +566,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
                 break;
             __builtin_amdgcn_s_waitcnt(0x0f70); // vmcnt(0): the stores are acknowledged
             if (lane == 0)
-                __hip_atomic_fetch_add(&sync[32 * (b % NC)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sync[SY_COUNTERS + CSTRIDE * (b % NC)], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const bool aborted = !wait_stage(sync, s, G, wait_limit);
             if (aborted && lane == 0)
                 flags[0] = 1;
@@ -555,7 +582,7 @@ __global__ __launch_bounds__(THREADS) void decode_staged_kernel(const FqLinearDe
             const int done = __hip_atomic_fetch_add(&sync[SY_DONE], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (done == G - 1) {
                 for (int l = 0; l < NC; l++)
-                    __hip_atomic_store(&sync[32 * l], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&sync[SY_COUNTERS + CSTRIDE * l], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(&sync[SY_ABORT], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(&sync[SY_DONE], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
