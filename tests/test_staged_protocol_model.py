@@ -1,10 +1,10 @@
 """A thread-per-workgroup model of the stage-ordered kernel's barrier protocol (CPU only).
 
 The kernel (csrc/fq_staged.hip) separates two stages by a grid-wide barrier built from plain
-device-scope loads, stores and atomics: one arrival word per workgroup that counts up through the
-launch (workgroup b stores s + 1 into word b once its rows of stage s are written; a waiter reads
-all the words), an abort flag, a sticky count of launches that gave up, and a count of finished
-workgroups whose last arrival puts words and flag back to zero.  This model runs the same steps with one Python thread per
+device-scope atomics: 128 arrival counters that count up through the launch (workgroup b adds to
+counter b % 128; after stage s counter l must hold (s + 1) * |{b : b % 128 = l}|), an abort flag, a
+sticky count of launches that gave up, and a count of finished workgroups whose last arrival puts
+counters and flag back to zero.  This model runs the same steps with one Python thread per
 workgroup and checks what the kernel relies on:
   - no workgroup reads a stage's input before every workgroup has written the previous stage,
   - a bounded wait that runs out makes EVERY workgroup leave, whatever the others are doing,
@@ -16,7 +16,7 @@ import time
 
 import pytest
 
-MAX_GRID = 1024
+N_COUNTERS = 128
 
 
 class SyncWords:
@@ -25,7 +25,7 @@ class SyncWords:
 
     def __init__(self):
         self.lock = threading.Lock()
-        self.word = [0] * MAX_GRID
+        self.counter = [0] * N_COUNTERS
         self.abort = 0
         self.gave_up = 0
         self.done = 0
@@ -47,10 +47,10 @@ class SyncWords:
             return old
 
     def snapshot(self):
-        """What one poll of the wavefront sees: every arrival word and the flag (the lanes' loads
-        are issued together; each word is read atomically, and the protocol does not rely on more)."""
+        """What one poll of the wavefront sees: every counter and the flag (the lanes' loads are
+        issued together; each word is read atomically, and the protocol does not rely on more)."""
         with self.lock:
-            return list(self.word), self.abort
+            return list(self.counter), self.abort
 
     def load(self, name, idx=None):
         with self.lock:
@@ -64,13 +64,17 @@ class SyncWords:
                 getattr(self, name)[idx] = v
 
 
+def members(G, l):
+    return (G - l + N_COUNTERS - 1) // N_COUNTERS
+
+
 def wait_stage(sync, s, G, wait_limit):
     it = 0
     while True:
         vals, aborted = sync.snapshot()
         if aborted:
             return False
-        if all(vals[b] >= s + 1 for b in range(G)):
+        if all(vals[l] >= (s + 1) * members(G, l) for l in range(N_COUNTERS)):
             return True
         if it >= wait_limit:
             if sync.exchange("abort", 1) == 0:     # the first to give up counts the launch
@@ -90,14 +94,14 @@ def workgroup(b, G, n_stages, sync, wait_limit, written, violations, delay, star
         written[s][b] = True                       # this workgroup's rows of stage s, write-through
         if s + 1 == n_stages:
             break
-        sync.store("word", s + 1, b)               # arrival, after the stores are acknowledged
+        sync.add("counter", b % N_COUNTERS)        # arrival, after the stores are acknowledged
         if not wait_stage(sync, s, G, wait_limit):
             break
         if not all(written[s]):                    # stage s + 1 reads what stage s wrote
             violations.append((b, s))
     if sync.add("done") == G - 1:                  # last one out puts the words back
-        for l in range(G):
-            sync.store("word", 0, l)
+        for l in range(N_COUNTERS):
+            sync.store("counter", 0, l)
         sync.store("abort", 0)
         sync.store("done", 0)
 
@@ -122,10 +126,10 @@ def join_all(threads, timeout=60):
 
 
 def clean(sync):
-    return sync.word == [0] * MAX_GRID and sync.abort == 0 and sync.done == 0
+    return sync.counter == [0] * N_COUNTERS and sync.abort == 0 and sync.done == 0
 
 
-@pytest.mark.parametrize("G,n_stages", [(1, 5), (7, 9), (32, 4), (45, 6)])
+@pytest.mark.parametrize("G,n_stages", [(1, 5), (7, 9), (32, 4), (45, 6), (140, 3)])
 def test_stages_are_ordered_and_words_end_clean(G, n_stages):
     sync = SyncWords()
     for _ in range(3):                             # replays on the same words, as a HIP graph would
@@ -136,21 +140,11 @@ def test_stages_are_ordered_and_words_end_clean(G, n_stages):
         assert clean(sync) and sync.gave_up == 0
 
 
-def test_a_waiter_needs_every_word_of_the_grid_and_no_other():
-    # words past the grid (the kernel's lanes read them in groups of four) must not count, and a
-    # single workgroup that is one stage behind holds everyone
-    for G in (1, 3, 4, 5, 255, 256, 257, 1024):
-        sync = SyncWords()
-        for b in range(G):
-            sync.store("word", 2, b)
-        assert wait_stage(sync, 1, G, 0)
-        sync.store("word", 1, G - 1)
-        assert not wait_stage(sync, 1, G, 0)
-        sync.store("abort", 0)
-        sync.store("word", 2, G - 1)
-        if G < MAX_GRID:
-            sync.store("word", 0, G)
-        assert wait_stage(sync, 1, G, 0)
+def test_counter_targets_cover_every_workgroup():
+    for G in range(1, 300):
+        assert sum(members(G, l) for l in range(N_COUNTERS)) == G
+        for l in range(N_COUNTERS):
+            assert members(G, l) == len([b for b in range(G) if b % N_COUNTERS == l])
 
 
 def test_a_wait_that_runs_out_lets_everyone_leave_and_the_next_launch_is_clean():
