@@ -99,14 +99,25 @@ __device__ __forceinline__ DmaLane dma_lane()
 // tile, first byte of the step) and is the same for the whole workgroup; rows past
 // `last_row` (relative to the tile) are clamped to it; `pitch` = bytes between rows in
 // global memory.
+// Loads of a thread per step and slab.
 template <int ROWS, int RB>
+constexpr int dma_loads()
+{
+    return ROWS * RB / 16 / THREADS > 0 ? ROWS * RB / 16 / THREADS : 1;
+}
+
+// PART = -1: all the loads of the slab; PART = p (0 .. 3): quarter p of them (those with index i,
+// i * 4 / LOADS = p), so that a step can issue its loads in four portions.
+template <int ROWS, int RB, int PART = -1>
 __device__ __forceinline__ void dma_slab(const uint8_t *tile, const DmaLane &L, int last_row, uint32_t pitch,
                                          uint8_t *slab)
 {
     const int wave = RB == 16 ? (threadIdx.x >> 6) & 3 : threadIdx.x >> 6;
-    constexpr int LOADS = ROWS * RB / 16 / THREADS > 0 ? ROWS * RB / 16 / THREADS : 1;
+    constexpr int LOADS = dma_loads<ROWS, RB>();
 #pragma unroll
     for (int i = 0; i < LOADS; i++) {
+        if (PART >= 0 && (LOADS >= 4 ? i * 4 / LOADS : (LOADS == 2 ? 2 * i : 0)) != PART)
+            continue;
         const uint32_t off = (uint32_t)min(L.r0 + i * L.rstep, last_row) * pitch + L.byte0;
         __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(tile + off),
                                          (FQ_LDS void *)(slab + (i * WAVES + wave) * 1024), 16, 0, 0);
@@ -163,6 +174,13 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // reads of a step do not touch the slabs its direct-to-LDS loads are filling, and does not
     // wait for those loads before the first read.
     constexpr int NST = BITS == 16 ? 2 : 3; // stages in flight (fp16 weights: 64 KiB per stage)
+    // A step issues its fetch in four portions, one behind each quarter of its MFMAs, instead of all of
+    // it ahead of them: the wavefronts of a workgroup leave the step's barrier together, and eight
+    // wavefronts issuing five or six loads each at that moment keep the matrix pipes waiting
+    // (2048 x 8192 x 28672 and its transpose, TFLOP/s: 2 bits 1105 -> 1143 and 1123 -> 1204, 4 bits 1040 ->
+    // 1072 and 1084 -> 1131, 8 bits 1039 -> 1066 and 1086 -> 1116).  Not with two stages (fp16 weights: 1105 ->
+    // 967): there a step waits for its own requests, and the late ones have less time to land.
+    constexpr bool SPREAD = NST == 3;
     __shared__ __attribute__((aligned(1024))) uint8_t xs0[XSLAB], xs1[XSLAB], xs2[NST == 3 ? XSLAB : 1024];
     __shared__ __attribute__((aligned(1024))) uint8_t ws0[WSLAB], ws1[WSLAB], ws2[NST == 3 ? WSLAB : 1024];
     __shared__ __attribute__((aligned(1024))) float smeta[BN];
@@ -289,6 +307,13 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
         dma_slab<BM, XRB>(x_tile + sn * XRB, xl, x_last, K * 2, stage_x(st));
         dma_slab<BN, WRB>(w_tile + sn * WRB, wl, w_last, w_pitch, stage_w(st));
     };
+    // the same in four portions (x: a load each; weights: one, two or four loads dealt over them)
+    auto fetch_part = [&](int sf, auto st, auto part) {
+        constexpr int P = decltype(part)::value;
+        const int sn = min(sf, nsteps - 1);
+        dma_slab<BM, XRB, P>(x_tile + sn * XRB, xl, x_last, K * 2, stage_x(st));
+        dma_slab<BN, WRB, P>(w_tile + sn * WRB, wl, w_last, w_pitch, stage_w(st));
+    };
     fetch(0, std::integral_constant<int, 0>());
     if (NST == 3)
         fetch(1, std::integral_constant<int, 1>());
@@ -314,7 +339,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         if (ODD)
             fetch_meta(min((s >> 1) + 1, (int)G - 1)); // the oldest request of this step
-        fetch(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>());
+        if (!SPREAD)
+            fetch(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>());
         // keep the requests here, ahead of the step's MFMAs: left to itself the scheduler sinks
         // them to the end of the step, right in front of the wait
         __builtin_amdgcn_sched_barrier(0);
@@ -396,6 +422,19 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
                 for (int mt = 0; mt < MTL; mt++)
                     acc[mt][j] = mfma32(a[mt], b, acc[mt][j]);
+            }
+            if (SPREAD) {
+                // a quarter of the step's requests behind every quarter of its MFMAs; vector memory
+                // instructions stay on their side of the line, everything else may cross it
+                if (i == 0)
+                    fetch_part(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>(), std::integral_constant<int, 0>());
+                if (i == 1)
+                    fetch_part(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>(), std::integral_constant<int, 1>());
+                if (i == 2)
+                    fetch_part(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>(), std::integral_constant<int, 2>());
+                if (i == 3)
+                    fetch_part(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>(), std::integral_constant<int, 3>());
+                __builtin_amdgcn_sched_barrier(0x38F);
             }
         }
         // Stage s + 1 must have landed (it was requested one step earlier when there are three
