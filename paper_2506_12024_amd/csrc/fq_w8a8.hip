@@ -180,30 +180,34 @@ __device__ __forceinline__ void dma_slab(const uint8_t *tile, const DmaLane &L, 
     }
 }
 
-// Scale and zero point of this lane's two weight rows for one step, and (threads < BM) one
-// token's group sum.
-struct Meta {
-    float s[2];
-    uint32_t z[2];
-    int sum;
-};
+// Scales and zero points reach the wavefronts through LDS, eight groups (steps) at a time: a lane
+// needs those of its two weight rows for every step, and fetched per step and lane that is four
+// loads of 64 different cache lines each per wavefront -- four times the requests of the operand
+// slabs themselves (measured: a fifth of the kernel's time).  Block b (groups 8 b .. 8 b + 7) of
+// the tile's 256 rows is 2 x 2048 words; it is requested with direct-to-LDS loads (a dword resp. a
+// byte per lane, either landing in the lane's word, the byte zero-extended) during the first step
+// of block b - 1, 64 instructions dealt over the eight wavefronts: instruction q fetches, for
+// rows (q & 3) * 64 + lane, group (q >> 2) & 7 of the block, scales for q < 32 and zero points
+// from there on.
+constexpr int MB = 8; // groups per block of metadata
 
-// Lane offsets (elements) from the tile's first scale / zero / group sum, set up once.
-struct MetaOffsets {
-    uint32_t row[2]; // (row - n0) * G for the lane's two weight rows
-    uint32_t tok;    // token - m0 for the thread's group sum
-};
-
-__device__ __forceinline__ void load_meta(const float *scales_tile, const uint8_t *zeros_tile,
-                                          const int32_t *xsum_tile, const MetaOffsets &O, int g, size_t g_stride,
-                                          Meta &R)
+__device__ __forceinline__ void dma_meta(const float *scales_tile, const uint8_t *zeros_tile, uint32_t G, int w_last,
+                                         int block, float *sm, uint32_t *zm)
 {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-        R.s[j] = ((const FQ_GLOBAL float *)(scales_tile + g))[O.row[j]];
-        R.z[j] = ((const FQ_GLOBAL uint8_t *)(zeros_tile + g))[O.row[j]];
+    for (int j = 0; j < 8; j++) {
+        const int q = wave * 8 + j;
+        const int rb = q & 3, gi = (q >> 2) & 7;
+        const uint32_t g = min((uint32_t)(block * MB + gi), G - 1); // (past the last group: fetched again, never read)
+        const uint32_t idx = (uint32_t)min(rb * 64 + lane, w_last) * G + g;
+        if (q < 32)
+            __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(scales_tile + idx),
+                                             (__attribute__((address_space(3))) void *)(sm + gi * BN + rb * 64), 4, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(zeros_tile + idx),
+                                             (__attribute__((address_space(3))) void *)(zm + gi * BN + rb * 64), 1, 0, 0);
     }
-    R.sum = ((const FQ_GLOBAL int32_t *)(xsum_tile + g * g_stride))[O.tok];
 }
 
 template <int V>
@@ -219,6 +223,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // does not wait for those loads before the first read.
     __shared__ __attribute__((aligned(1024))) uint8_t xs0[XSLAB], xs1[XSLAB], ws0[WSLAB], ws1[WSLAB];
     __shared__ float xsm[2][BM];
+    __shared__ __attribute__((aligned(1024))) float sm[2][MB * BN];   // scales of two blocks of groups: [group][row]
+    __shared__ __attribute__((aligned(1024))) uint32_t zm[2][MB * BN]; // zero points, same order
 
     // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous run
     // of logical tiles (the M tiles of one N tile are neighbours and share the weight slab)
@@ -251,24 +257,21 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
         lofs[i] = slab_offset(l32, 2 * i + c);
 
     const int nsteps = d.K / BKB;
-    Meta cur, nxt;
     const DmaLane dl = dma_lane();
     const int x_last = d.M - 1 - m0, w_last = d.N - 1 - n0;
     const uint8_t *x_tile = (const uint8_t *)d.xq + (size_t)m0 * d.K;
     const uint8_t *w_tile = d.codes + (size_t)n0 * d.K;
     const uint32_t G = (uint32_t)d.K >> 7;
-    MetaOffsets mo;
-    mo.row[0] = (uint32_t)min(wn + l32, d.N - 1 - n0) * G;
-    mo.row[1] = (uint32_t)min(wn + 32 + l32, d.N - 1 - n0) * G;
-    mo.tok = (uint32_t)min((int)min(threadIdx.x, (unsigned)BM - 1), d.M - 1 - m0);
+    const uint32_t tok = (uint32_t)min((int)min(threadIdx.x, (unsigned)BM - 1), d.M - 1 - m0); // the thread's token (group sums)
     const float *scales_tile = d.scales + (size_t)n0 * G;
     const uint8_t *zeros_tile = d.zeros + (size_t)n0 * G;
     const int32_t *xsum_tile = d.xsum + m0;
     dma_slab<BM>(x_tile, dl, x_last, d.K, xs0);
     dma_slab<BN>(w_tile, dl, w_last, d.K, ws0);
-    load_meta(scales_tile, zeros_tile, xsum_tile, mo, 0, (size_t)d.M, cur);
+    dma_meta(scales_tile, zeros_tile, G, w_last, 0, sm[0], zm[0]);
+    int sum_next = ((const FQ_GLOBAL int32_t *)xsum_tile)[tok];
     if (threadIdx.x < BM)
-        xsm[0][threadIdx.x] = (float)cur.sum; // |sum| <= 128 * 127: exact
+        xsm[0][threadIdx.x] = (float)sum_next; // |sum| <= 128 * 127: exact
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -289,10 +292,22 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     auto step = [&](int s, auto phase) {
         constexpr int PHASE = decltype(phase)::value;
         constexpr bool ODD = PHASE == 1; // steps alternate between the two buffer sets (s & 1)
+        // scale and zero point of the lane's two weight rows for this step: read ahead of the step's
+        // requests (the compiler cannot tell these words from the ones the direct-to-LDS loads below
+        // write and would wait for every outstanding load first)
+        float cur_s[2];
+        uint32_t cur_z[2];
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            cur_s[j] = sm[(s >> 3) & 1][(s & (MB - 1)) * BN + wn + j * 32 + l32];
+            cur_z[j] = zm[(s >> 3) & 1][(s & (MB - 1)) * BN + wn + j * 32 + l32];
+        }
         const int sn = min(s + 1, nsteps - 1); // always issued: the last step refetches itself
         dma_slab<BM>(x_tile + sn * BKB, dl, x_last, d.K, ODD ? xs0 : xs1); // last read in step s-1: a barrier has passed
         dma_slab<BN>(w_tile + sn * BKB, dl, w_last, d.K, ODD ? ws0 : ws1);
-        load_meta(scales_tile, zeros_tile, xsum_tile, mo, sn, (size_t)d.M, nxt);
+        if ((s & (MB - 1)) == 0) // the next block of scales and zero points; its buffer was last read a block ago
+            dma_meta(scales_tile, zeros_tile, G, w_last, (s >> 3) + 1, sm[((s >> 3) + 1) & 1], zm[((s >> 3) + 1) & 1]);
+        sum_next = ((const FQ_GLOBAL int32_t *)(xsum_tile + (size_t)sn * (size_t)d.M))[tok];
         const uint8_t *xc = (ODD ? xs1 : xs0) + wm * BKB, *wc = (ODD ? ws1 : ws0) + wn * BKB;
 
         v4i b[2][4];
@@ -306,7 +321,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
         float az[MT], bz[2];
 #pragma unroll
         for (int j = 0; j < 2; j++)
-            bz[j] = cur.s[j] * (float)(128 - (int)cur.z[j]);
+            bz[j] = cur_s[j] * (float)(128 - (int)cur_z[j]);
         // group sums of this step for the wavefront's tokens: only xsm[s & 1] is read during
         // step s (the other buffer receives step s + 1's values at the end of the step)
         const float *sc = xsm[s & 1] + wm;
@@ -359,7 +374,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 acc[(t + 1) & 1] = chain((t + 1) & 1);
 #pragma unroll
             for (int v = 0; v < 16; v++)
-                out[mt][j][v] += cur.s[j] * (float)acc[t & 1][v];
+                out[mt][j][v] += cur_s[j] * (float)acc[t & 1][v];
             if (t + 1 < 2 * MT) {
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
@@ -377,8 +392,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
             asm volatile("" : "+v"(out[mt][j]), "+v"(a[0]));
         }
         if (threadIdx.x < BM)
-            xsm[(s + 1) & 1][threadIdx.x] = (float)nxt.sum;
-        cur = nxt;
+            xsm[(s + 1) & 1][threadIdx.x] = (float)sum_next;
         __builtin_amdgcn_s_waitcnt(0); // this wavefront's direct-to-LDS loads have landed
         __syncthreads();               // everyone's have; buffers of step s are free
     };
