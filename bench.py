@@ -37,7 +37,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy
 # (profiles/decode_m1_plan_llama7b_hbm_traffic.md); reported only for that workload.
 MEASURED_TRAFFIC_RATIO = {("llama7b", 1, (4, 8)): 4993151.0 / 4978290.0,
-                          ("llama7b", 1, (4, 8), "dependent"): 5020670.0 / 4978290.0,
+                          ("llama7b", 1, (4, 8), "dependent"): 5040493.0 / 4978290.0,
                           ("llama7b", 16, (4, 8, 16)): 8.052 / 7.857}
 # where those ratios come from (a constant carried from a profile, not counters read in this run)
 TRAFFIC_SOURCE = {("llama7b", 1, (4, 8)): "profiles/decode_m1_plan_llama7b_hbm_traffic.md (rocprofv3 --pmc, scaled by a 1 GiB copy)",
