@@ -183,8 +183,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr bool SPREAD = NST == 3;
     __shared__ __attribute__((aligned(1024))) uint8_t xs0[XSLAB], xs1[XSLAB], xs2[NST == 3 ? XSLAB : 1024];
     __shared__ __attribute__((aligned(1024))) uint8_t ws0[WSLAB], ws1[WSLAB], ws2[NST == 3 ? WSLAB : 1024];
-    __shared__ __attribute__((aligned(1024))) float smeta[BN];
-    __shared__ __attribute__((aligned(1024))) uint32_t zmeta[BN];
+    __shared__ __attribute__((aligned(1024))) float smeta[BN * 4]; // [row][4 groups] (one group per request: the first BN words)
+    __shared__ __attribute__((aligned(1024))) uint32_t zmeta[BN];  // [row]: four groups' bytes, or one zero-extended
 
     // hardware deals consecutive workgroup ids round-robin to the 8 XCDs: give each XCD a
     // contiguous run of logical tiles
@@ -250,9 +250,26 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // per step -- the waits below count them.  An ordinary load would do, but the compiler
     // assumes it may overtake pending direct-to-LDS loads and waits for all of them before its
     // first use, which would drain the fetch pipeline every other step.
+    // A request of a lane's scale touches a cache line of its own, 512 lines per group and
+    // workgroup against 384 for the operand slabs of a step (3 to 5 % of the kernel's time).  Where
+    // a row's scales of four consecutive groups are 16 bytes that a 16-byte request may fetch --
+    // K / 128 a multiple of 4 and the arrays aligned -- a request brings four groups (their zero
+    // points are one 4-byte request), during the second step of every fourth group.
+    const bool meta4 = BITS != 16 && (G & 3u) == 0 && ((uintptr_t)scales & 15u) == 0 && ((uintptr_t)zeros & 3u) == 0;
     auto fetch_meta = [&](int g) {
         if (BITS != 16) {
             const uint32_t row = (uint32_t)min((wave & 3) * 64 + lane, w_last) * G;
+            if (meta4) {
+                if ((g & 3) != 0)
+                    return; // (requested with the first group of its four)
+                if (wave < 4)
+                    __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(scales_tile + g + row),
+                                                     (FQ_LDS void *)(smeta + (wave & 3) * 256), 16, 0, 0);
+                else
+                    __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(zeros_tile + g + row),
+                                                     (FQ_LDS void *)(zmeta + (wave & 3) * 64), 4, 0, 0);
+                return;
+            }
             if (wave < 4)
                 __builtin_amdgcn_global_load_lds((const FQ_GLOBAL void *)(scales_tile + g + row),
                                                  (FQ_LDS void *)(smeta + (wave & 3) * 64), 4, 0, 0);
@@ -333,11 +350,12 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
             // (nothing is writing smeta / zmeta now: the next request goes out a step later)
 #pragma unroll
             for (int j = 0; j < 2; j++) {
-                cur.s[j] = __builtin_ldexpf(smeta[wn + j * 32 + l32], ex[j]);
-                cur.z[j] = zmeta[wn + j * 32 + l32];
+                const int row = wn + j * 32 + l32, g4 = (s >> 1) & 3;
+                cur.s[j] = __builtin_ldexpf(meta4 ? smeta[row * 4 + g4] : smeta[row], ex[j]);
+                cur.z[j] = meta4 ? (zmeta[row] >> (8 * g4)) & 255u : zmeta[row];
             }
         }
-        if (ODD)
+        if (ODD && (!meta4 || (s >> 1) + 1 < (int)G)) // (four groups at a time: nothing to request past the last)
             fetch_meta(min((s >> 1) + 1, (int)G - 1)); // the oldest request of this step
         if (!SPREAD)
             fetch(s + NST - 1, std::integral_constant<int, (ST + NST - 1) % NST>());
