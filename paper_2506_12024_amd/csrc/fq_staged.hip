@@ -67,10 +67,14 @@ namespace {
 
 constexpr int CW = 8;                  // compute wavefronts per workgroup
 constexpr int THREADS = (CW + 1) * 64; // + the service wavefront: up to three wavefronts per SIMD, 168 registers each
-constexpr int P = 4;                   // items in flight per compute wavefront (register sets), 8 loads each.
+constexpr int P = 3;                   // items in flight per compute wavefront (register sets), 8 loads each.
                                        // Measured on the 7B-shaped step (ms, bits from {4,8} / all 4 / all 8):
                                        // CW 7, P 7: 1.86 / 1.57 / 2.05;  CW 8, P 4: 1.77 / 1.50 / 1.97;
-                                       // CW 7, P 5: 1.84 / 1.54 / 2.03;  CW 11, P 3: 1.79 / 1.52 / 2.05
+                                       // CW 7, P 5: 1.84 / 1.54 / 2.03;  CW 11, P 3: 1.79 / 1.52 / 2.05;
+                                       // and with the 128-counter barrier: CW 8, P 4 / 3 / 2: 1.485 / 1.476 / 1.476
+                                       // (P 5 spills: 2.11), CW 9, P 3: 1.52, CW 10, P 3: 1.54, CW 6, P 5: 1.58,
+                                       // CW 11 and 12, P 2: 1.54 and 1.56 -- the depth hardly matters, more
+                                       // wavefronts cost
 constexpr int XU = 3;                  // 16-byte blocks of x a thread fetches before it places them
 
 // What a workgroup does in one stage.  64 bytes, kept in LDS for every stage of the plan.
