@@ -354,12 +354,13 @@ def bench_prefill_w8a8(args):
         x = synth.activations(SEED, "prefill/%dx%d/x" % (N, K), M, K)
         w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
         x_dev = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
-        layer = fq.Layer(N, K)
-        cb, sb, zb = fq.fq_packed_sizes(N, K, 8)
+        group = K if args.w8a8_group == "row" else 128
+        layer = fq.Layer(N, K, group)
+        cb, sb, zb = fq.fq_packed_sizes(N, K, 8, group)
         c = torch.empty(cb, dtype=torch.uint8, device=dev)
         sc = torch.empty(sb // 4, dtype=torch.float32, device=dev)
         z = torch.empty(zb, dtype=torch.uint8, device=dev)
-        fq.fq_quantize(w_dev, N, K, 8, 128, c, sc, z)
+        fq.fq_quantize(w_dev, N, K, 8, group, c, sc, z)
         layer.attach(8, c, sc, z)
         del w_dev
         calls.append((layer, x_dev, torch.empty((M, K), dtype=torch.int8, device=dev),
@@ -403,8 +404,9 @@ def bench_prefill_w8a8(args):
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "70B-shaped slice: M=2048, 8192->28672 and 28672->8192, per-token int8 "
-                               "activations x group-128 INT8 weights (2 quantize + 2 GEMM launches per step)"},
-        "roofline": {"bound": "mfma", "kernel": "w8a8_kernel", "achieved": achieved, "peak": 5000.0,
+                               "activations x %s INT8 weights (2 quantize + 2 GEMM launches per step)"
+                               % ("one-scale-per-row" if args.w8a8_group == "row" else "group-128")},
+        "roofline": {"bound": "mfma", "kernel": "w8a8_row_kernel" if args.w8a8_group == "row" else "w8a8_kernel", "achieved": achieved, "peak": 5000.0,
                      "unit": "TOP/s", "frac": achieved / 5000.0, "traffic": None,
                      "avg_launch_ms": ms_launch, "ops_per_launch": ops / len(calls)},
         "quantize_act_avg_launch_ms": ms_quant}))
@@ -720,6 +722,9 @@ def main():
     ap.add_argument("--order", default="dependent", choices=["dependent", "independent"],
                     help="batch 1: the step's linears in the order a decoder must issue them (one launch of "
                          "the stage-ordered plan; default) or as one plan of independent entries")
+    ap.add_argument("--w8a8-group", default="128", choices=["128", "row"],
+                    help="--workload prefill-w8a8: the INT8 copy's scales, per group of 128 inputs (default) or one "
+                         "per weight row (group = K)")
     ap.add_argument("--staged", action="store_true",
                     help="also time the dependent order as 4 separate plan launches per layer (HIP graph)")
     args = ap.parse_args()

@@ -74,7 +74,8 @@ typedef enum fq_status {
 typedef struct fq_layer fq_layer; /* opaque: borrows the caller's packed buffers */
 typedef struct fq_plan fq_plan;   /* opaque: a list of linears run by one launch */
 
-#define FQ_GROUP 128      /* the only group size the kernels are built for */
+#define FQ_GROUP 128      /* the group size the kernels are built for */
+#define FQ_MAX_ROW_GROUP_K 65536 /* longest row of an 8-bit copy with one scale per row (group = K) */
 #define FQ_MAX_DECODE_M 32 /* rows of x served by the skinny (decode) kernels */
 #define FQ_MAX_DECODE_K 32768 /* longest row they take (a row of x stays in LDS at M = 1) */
 #define FQ_MAX_LM_HEAD_M 4 /* rows of x served by fq_lm_head_entropy */
@@ -88,7 +89,8 @@ const char *fq_last_error(void);
 /*
  * Bytes of the three packed buffers for an N x K weight at `bits` (2, 3, 4 or 8): what Eq. (2) of
  * Sec. 2.2 produces per weight (an n-bit code) and per group (s, z), in the layout above.
- * Any of the three outputs may be NULL.  Host-only; launches nothing.
+ * Any of the three outputs may be NULL.  Host-only; launches nothing.  group = FQ_GROUP, or, at 8 bits,
+ * group = K: one scale and zero point per weight row (see fq_quantize).
  */
 int fq_packed_sizes(int N, int K, int bits, int group,
                     size_t *codes_bytes, size_t *scales_bytes, size_t *zeros_bytes);
@@ -103,6 +105,10 @@ int fq_packed_sizes(int N, int K, int bits, int group,
  *   scales  device, f32 [N][K/group]                   (written)
  *   zeros   device, u8  [N][K/group]                   (written)
  * bits in {2, 3, 4, 8}; group = FQ_GROUP; K a multiple of group; N, K >= 1.
+ * At 8 bits group = K is accepted as well (K a multiple of FQ_GROUP, at most FQ_MAX_ROW_GROUP_K): Xmin and
+ * Xmax of Eq. (2) are then taken over the whole row, scales and zeros are [N][1] -- the granularity at
+ * which the INT8 copy meets 8-bit activations in the prefill without a fold per group (Sec. 4.1: W8A8
+ * is there to use the integer matrix units fully).  Such a copy is served by fq_linear_w8a8 only.
  * Non-finite weights give unspecified codes.
  */
 int fq_quantize(const void *w_fp16, int N, int K, int bits, int group,
@@ -141,7 +147,9 @@ int fq_fake_quantize(const void *w_fp16, int N, int K, int bits, int group, int 
  * value (attaching again replaces the pointers).  For bits = 16 pass the fp16
  * weights as `codes` and NULL scales/zeros.  Buffers must be 16-byte aligned.
  * Launches nothing and takes no stream: the kernels stream the packed layout as it is, so there is
- * nothing to re-tile when a copy is attached.
+ * nothing to re-tile when a copy is attached.  group = FQ_GROUP; or group = K for a layer that holds
+ * nothing but an 8-bit copy with one scale per row: fq_layer_attach then takes bits = 8 only, and
+ * fq_linear, the plans and fq_linears_static answer FQ_ERR_SHAPE for it (fq_linear_w8a8 serves it).
  */
 int fq_layer_create(fq_layer **out, int N, int K, int group);
 int fq_layer_attach(fq_layer *layer, int bits, const void *codes,
@@ -272,7 +280,9 @@ int fq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
  * fq_linear_w8a8: y[m][n] = fp16( s_x[m] * sum_g s[n][g] * sum_{k in g} xq[m][k] (q[n][k] - z[n][g]) )
  * with q, s, z the layer's 8-bit copy (FQ_ERR_NOT_ATTACHED without one): the products and the
  * sums inside a group are exact integers, groups are accumulated in binary32.  xq, sx, xsum
- * as written by fq_quantize_act for the same M and the layer's K.
+ * as written by fq_quantize_act for the same M and the layer's K.  For a layer created with group = K
+ * the sum over g is one term: the whole row is summed exactly in int32 and scaled once,
+ * y[m][n] = fp16( s_x[m] * (s[n] * float( sum_k xq[m][k] (q[n][k] - z[n]) )) ).
  *   y_fp16  device, fp16 [M][N], 2-byte aligned             (written)
  * M >= 1.
  */

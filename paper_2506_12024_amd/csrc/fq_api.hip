@@ -97,14 +97,30 @@ void fill_desc(FqLinearDesc &d, const fq_layer *l, const void *x, void *y)
     d.K = l->K;
 }
 
-int check_shape(int N, int K, int group)
+// per_row: group = K (one scale per weight row: 8-bit copies for fq_linear_w8a8) is accepted as well
+int check_shape(int N, int K, int group, bool per_row = false)
 {
-    if (group != FQ_GROUP)
-        return fail(FQ_ERR_SHAPE, "group must be %d (got %d)", FQ_GROUP, group);
     if (N < 1 || K < 1)
         return fail(FQ_ERR_SHAPE, "N and K must be >= 1 (got N=%d K=%d)", N, K);
+    if (per_row && group == K && group != FQ_GROUP) {
+        if (K % FQ_GROUP != 0 || K > FQ_MAX_ROW_GROUP_K)
+            return fail(FQ_ERR_SHAPE, "group = K needs K a multiple of %d and at most %d (got %d)", FQ_GROUP,
+                        FQ_MAX_ROW_GROUP_K, K);
+        return FQ_OK;
+    }
+    if (group != FQ_GROUP)
+        return fail(FQ_ERR_SHAPE, "group must be %d%s (got %d)", FQ_GROUP, per_row ? " or K" : "", group);
     if (K % group != 0)
         return fail(FQ_ERR_SHAPE, "K=%d is not a multiple of group=%d", K, group);
+    return FQ_OK;
+}
+
+// A layer whose copies are quantized per row is served by fq_linear_w8a8 only.
+int check_group128(const fq_layer *l, const char *who)
+{
+    if (l->group != FQ_GROUP)
+        return fail(FQ_ERR_SHAPE, "%s: the layer's copies have one scale per row (group = K = %d): they are served by "
+                                  "fq_linear_w8a8 only", who, l->K);
     return FQ_OK;
 }
 
@@ -119,7 +135,7 @@ int fq_packed_sizes(int N, int K, int bits, int group, size_t *codes_bytes, size
 {
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8)
         return fail(FQ_ERR_BITS, "fq_packed_sizes: bits must be 2, 3, 4 or 8 (got %d)", bits);
-    if (int rc = check_shape(N, K, group))
+    if (int rc = check_shape(N, K, group, bits == 8))
         return rc;
     const size_t groups = (size_t)N * (size_t)(K / group);
     if (codes_bytes)
@@ -138,12 +154,14 @@ static int quantize_any(const char *who, bool symmetric, const void *w_fp16, int
         return fail(FQ_ERR_NULL, "%s: NULL tensor pointer", who);
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8)
         return fail(FQ_ERR_BITS, "%s: bits must be 2, 3, 4 or 8 (got %d)", who, bits);
-    if (int rc = check_shape(N, K, group))
+    if (int rc = check_shape(N, K, group, bits == 8))
         return rc;
     if (!aligned16(w_fp16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u))
         return fail(FQ_ERR_ALIGN, "%s: w and codes need 16-byte, scales 4-byte alignment", who);
     const long long n_groups = (long long)N * (K / group);
-    hipError_t e = fq_launch_quantize(w_fp16, n_groups, bits, symmetric, codes, scales, zeros, (hipStream_t)stream);
+    hipError_t e = group != FQ_GROUP
+        ? fq_launch_quantize_row8(w_fp16, N, K, symmetric, codes, scales, zeros, (hipStream_t)stream)
+        : fq_launch_quantize(w_fp16, n_groups, bits, symmetric, codes, scales, zeros, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "quantize launch");
     return FQ_OK;
@@ -204,7 +222,7 @@ int fq_layer_create(fq_layer **out, int N, int K, int group)
     if (!out)
         return fail(FQ_ERR_NULL, "fq_layer_create: out is NULL");
     *out = nullptr;
-    if (int rc = check_shape(N, K, group))
+    if (int rc = check_shape(N, K, group, true))
         return rc;
     fq_layer *l = new (std::nothrow) fq_layer();
     if (!l)
@@ -225,6 +243,9 @@ int fq_layer_attach(fq_layer *layer, int bits, const void *codes, const void *sc
     const int slot = slot_of(bits);
     if (slot < 0)
         return fail(FQ_ERR_BITS, "fq_layer_attach: bits must be 2, 3, 4, 8 or 16 (got %d)", bits);
+    if (layer->group != FQ_GROUP && bits != 8)
+        return fail(FQ_ERR_BITS, "fq_layer_attach: a layer with one scale per row (group = K) holds an 8-bit copy only "
+                                 "(got %d)", bits);
     if (!codes)
         return fail(FQ_ERR_NULL, "fq_layer_attach: codes is NULL");
     if (bits != 16 && (!scales || !zeros))
@@ -249,6 +270,8 @@ int fq_layer_destroy(fq_layer *layer)
 int fq_linear(const fq_layer *layer, int bits, const void *x_fp16, int M, void *y_fp16, void *stream)
 {
     if (int rc = check_layer(layer))
+        return rc;
+    if (int rc = check_group128(layer, "fq_linear"))
         return rc;
     if (!x_fp16 || !y_fp16)
         return fail(FQ_ERR_NULL, "fq_linear: x or y is NULL");
@@ -323,7 +346,7 @@ int fq_linear_w8a8(const fq_layer *layer, const void *xq, const float *sx, const
         return fail(FQ_ERR_ALIGN, "fq_linear_w8a8: xq needs 16-byte, sx and xsum 4-byte, y 2-byte alignment");
     FqLinearDesc d;
     fill_desc(d, layer, nullptr, y_fp16);
-    hipError_t e = fq_launch_w8a8(d, xq, sx, xsum, M, (hipStream_t)stream);
+    hipError_t e = fq_launch_w8a8(d, xq, sx, xsum, M, layer->group != FQ_GROUP, (hipStream_t)stream);
     if (e != hipSuccess)
         return hip_fail(e, "fq_linear_w8a8 launch");
     return FQ_OK;
@@ -365,6 +388,8 @@ int fq_plan_layout(const char *who, int count, const fq_layer *const *layers, co
     bool has2 = false, has3 = false;
     for (int i = 0; i < count; i++) {
         if (int rc = check_layer(layers[i]))
+            return rc;
+        if (int rc = check_group128(layers[i], who))
             return rc;
         if (!xs[i] || !ys[i])
             return fail(FQ_ERR_NULL, "%s: x or y of entry %d is NULL", who, i);

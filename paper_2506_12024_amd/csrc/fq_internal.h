@@ -62,6 +62,9 @@ int fq_stream_bank(hipStream_t stream);
 
 hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
                               void *scales, void *zeros, hipStream_t stream);
+// 8 bits, one group per row (group = K)
+hipError_t fq_launch_quantize_row8(const void *w, int N, int K, bool symmetric, void *codes, void *scales, void *zeros,
+                                   hipStream_t stream);
 hipError_t fq_launch_fake_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *w_hat,
                                    hipStream_t stream);
 
@@ -140,8 +143,9 @@ hipError_t fq_launch_prefill(const FqLinearDesc &d, int bits, int M, hipStream_t
 // code sums, [K/128][M]) and the int8 MFMA GEMM against the resident 8-bit copy.
 hipError_t fq_launch_quantize_act(const void *x, int M, int K, void *xq, float *sx, int32_t *xsum,
                                   hipStream_t stream);
+// per_row: the 8-bit copy has one scale and zero point per weight row (group = K) instead of per 128 inputs
 hipError_t fq_launch_w8a8(const FqLinearDesc &d, const void *xq, const float *sx, const int32_t *xsum,
-                          int M, hipStream_t stream);
+                          int M, bool per_row, hipStream_t stream);
 
 // Output layer (fp16 weight [V][K], 1 <= M <= 4 rows of x) fused with entropy and argmax of its logits.
 hipError_t fq_launch_lm_head_entropy(const void *x, const void *w, int M, int V, int K, float *logits, float *H,

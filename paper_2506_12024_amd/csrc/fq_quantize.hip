@@ -199,6 +199,62 @@ __global__ __launch_bounds__(256) void fake_quantize_kernel(const half8 *w, long
     w_hat[seg * 16 + sub] = out;
 }
 
+// One scale and zero point per weight row (group = K) at 8 bits: the granularity at which the INT8 copy
+// meets 8-bit activations on the integer matrix cores without a fold per group (Sec. 4.1, 4.3).  Eq. (2)
+// as above with Xmin / Xmax taken over the whole row.  One workgroup per row, two passes over it (the
+// second finds it in cache).
+template <bool SYM>
+__global__ __launch_bounds__(256) void quantize_row8_kernel(const half8 *__restrict__ w, int K,
+                                                            uint8_t *__restrict__ codes, float *__restrict__ scales,
+                                                            uint8_t *__restrict__ zeros)
+{
+#pragma clang fp contract(off)
+    __shared__ float s_lo[4], s_hi[4];
+    const int t = threadIdx.x, nvec = K >> 3;
+    const half8 *row = w + (size_t)blockIdx.x * nvec;
+    float lo = 0.0f, hi = 0.0f; // the range always contains 0
+    for (int i = t; i < nvec; i += 256) {
+        const half8 v = row[i];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            lo = fminf(lo, (float)v[j]);
+            hi = fmaxf(hi, (float)v[j]);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+    }
+    if ((t & 63) == 0) {
+        s_lo[t >> 6] = lo;
+        s_hi[t >> 6] = hi;
+    }
+    __syncthreads();
+    lo = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
+    hi = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+    const GroupParams p = group_params<SYM>(lo, hi, 8);
+    const float z = SYM ? 128.0f : p.z; // what is stored
+    for (int i = t; i < nvec; i += 256) {
+        const half8 v = row[i];
+        uint32_t q[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            float c = rintf(__fadd_rn(__fdiv_rn((float)v[j], p.s), p.z));
+            c = fminf(fmaxf(c, p.qlo), p.qhi);
+            q[j] = (uint32_t)(int)(SYM ? c + z : c);
+        }
+        uint2 word;
+        word.x = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+        word.y = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+        reinterpret_cast<uint2 *>(codes + (size_t)blockIdx.x * K)[i] = word;
+    }
+    if (t == 0) {
+        scales[blockIdx.x] = p.s;
+        zeros[blockIdx.x] = (uint8_t)(int)z;
+    }
+}
+
 } // namespace
 
 hipError_t fq_launch_quantize(const void *w, long long n_groups, int bits, bool symmetric, void *codes,
@@ -241,5 +297,17 @@ hipError_t fq_launch_fake_quantize(const void *w, long long n_groups, int bits, 
         fake_quantize_kernel<true><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, bits, (half8 *)w_hat);
     else
         fake_quantize_kernel<false><<<blocks, 256, 0, stream>>>((const half8 *)w, n_groups, bits, (half8 *)w_hat);
+    return hipGetLastError();
+}
+
+hipError_t fq_launch_quantize_row8(const void *w, int N, int K, bool symmetric, void *codes, void *scales, void *zeros,
+                                   hipStream_t stream)
+{
+    if (N <= 0)
+        return hipSuccess;
+    if (symmetric)
+        quantize_row8_kernel<true><<<N, 256, 0, stream>>>((const half8 *)w, K, (uint8_t *)codes, (float *)scales, (uint8_t *)zeros);
+    else
+        quantize_row8_kernel<false><<<N, 256, 0, stream>>>((const half8 *)w, K, (uint8_t *)codes, (float *)scales, (uint8_t *)zeros);
     return hipGetLastError();
 }

@@ -32,6 +32,7 @@
 // kernel, so the tile has to be this large to keep the L2 traffic per MFMA down.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "fq_internal.h"
 
@@ -425,6 +426,137 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
 }
 
+// ---- one scale per weight row ------------------------------------------------------------------
+// With a scale and a zero point per weight ROW (group = K) nothing has to be folded per group:
+//   y[m][n] = s_x[m] * s[n] * ( sum_k xq[m][k] (q[n][k] - 128)  -  (z[n] - 128) * sum_k xq[m][k] ),
+// the first sum exact in int32 over the whole of K (|.| <= K * 127 * 128 < 2^31 for K <= 65536), the
+// second from the activations' group sums.  Same tiles, slabs and fetch as above; the six MFMA tiles of a
+// wavefront are six independent int32 chains that run through all the steps, so that consecutive MFMAs
+// never wait for each other, and the vector ALUs are left with the XOR of the weight bytes.
+// RMT MFMA tiles along the tokens per wavefront: 4 (256 tokens per workgroup) -- the int32 accumulators
+// are touched by MFMAs only, so 128 of them fit beside the operands.
+constexpr int RMT = 4;
+constexpr int RBM = 2 * RMT * 32;
+constexpr int RXSLAB = RBM * BKB;
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void w8a8_row_kernel(
+    const W8A8Args d, int m_tiles, int n_tiles, int per_xcd)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[RXSLAB], xs1[RXSLAB], ws0[WSLAB], ws1[WSLAB];
+    __shared__ int xtot[RBM];
+
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= m_tiles * n_tiles)
+        return;
+    const int m0 = (logical % m_tiles) * RBM, n0 = (logical / m_tiles) * BN;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int l32 = lane & 31, c = lane >> 5;
+    const int wm = (wave & 1) * (RMT * 32);
+    const int wn = (wave >> 1) * WN;
+    const int n_wave0 = n0 + wn;
+
+    v16i acc[RMT][2];
+#pragma unroll
+    for (int mt = 0; mt < RMT; mt++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int v = 0; v < 16; v++)
+                acc[mt][j][v] = 0;
+
+    int lofs[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+        lofs[i] = slab_offset(l32, 2 * i + c);
+
+    const int nsteps = d.K / BKB;
+    const DmaLane dl = dma_lane();
+    const int x_last = d.M - 1 - m0, w_last = d.N - 1 - n0;
+    const uint8_t *x_tile = (const uint8_t *)d.xq + (size_t)m0 * d.K;
+    const uint8_t *w_tile = d.codes + (size_t)n0 * d.K;
+    dma_slab<RBM>(x_tile, dl, x_last, d.K, xs0);
+    dma_slab<BN>(w_tile, dl, w_last, d.K, ws0);
+    // the tokens' sums over the whole row: the sum of their group sums
+    if (threadIdx.x < RBM) {
+        const int tok = min((int)threadIdx.x, d.M - 1 - m0);
+        int t = 0;
+        for (int g = 0; g < nsteps; g++)
+            t += ((const FQ_GLOBAL int32_t *)(d.xsum + m0 + (size_t)g * (size_t)d.M))[tok];
+        xtot[threadIdx.x] = t;
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    auto step = [&](int s, auto odd) {
+        constexpr bool ODD = decltype(odd)::value;
+        const int sn = min(s + 1, nsteps - 1); // always issued: the last step refetches itself
+        dma_slab<RBM>(x_tile + sn * BKB, dl, x_last, d.K, ODD ? xs0 : xs1); // last read in step s-1: a barrier has passed
+        dma_slab<BN>(w_tile + sn * BKB, dl, w_last, d.K, ODD ? ws0 : ws1);
+        const uint8_t *xc = (ODD ? xs1 : xs0) + wm * BKB, *wc = (ODD ? ws1 : ws0) + wn * BKB;
+        v4i b[2][4];
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) { // stored code q -> signed byte q - 128
+                const v4i raw = *reinterpret_cast<const v4i *>(wc + j * 32 * BKB + lofs[i]);
+                b[j][i] = raw ^ (int)0x80808080;
+            }
+        v4i a[RMT][4];
+#pragma unroll
+        for (int mt = 0; mt < RMT; mt++)
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                a[mt][i] = *reinterpret_cast<const v4i *>(xc + mt * 32 * BKB + lofs[i]);
+        // six MFMAs in a row that do not depend on each other, four times
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int mt = 0; mt < RMT; mt++)
+#pragma unroll
+                for (int j = 0; j < 2; j++)
+                    acc[mt][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mt][i], b[j][i], acc[mt][j], 0, 0, 0);
+        __builtin_amdgcn_s_waitcnt(0); // this wavefront's direct-to-LDS loads have landed
+        __syncthreads();               // everyone's have; buffers of step s are free
+    };
+    int s = 0;
+    for (; s + 1 < nsteps; s += 2) {
+        step(s, std::false_type());
+        step(s + 1, std::true_type());
+    }
+    if (s < nsteps)
+        step(s, std::false_type());
+
+    // D layout of the 32x32 MFMA: lane holds column l32 (weight row), rows (tokens)
+    // 8 * (v / 4) + 4 * (lane / 32) + v % 4.
+    float sn_[2];
+    int zn[2];
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+        const int n = min(n_wave0 + j * 32 + l32, d.N - 1);
+        sn_[j] = d.scales[n];
+        zn[j] = (int)d.zeros[n] - 128;
+    }
+#pragma unroll
+    for (int mt = 0; mt < RMT; mt++) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+            const int tl = wm + mt * 32 + 8 * (v >> 2) + 4 * c + (v & 3);
+            const int m = m0 + tl;
+            if (m < d.M) {
+                const float sxm = d.sx[m];
+                const int xt = xtot[tl];
+#pragma unroll
+                for (int j = 0; j < 2; j++) {
+                    const int n = n_wave0 + j * 32 + l32;
+                    if (n < d.N)
+                        ((FQ_GLOBAL uint16_t *)d.y)[(size_t)m * d.N + n] = __builtin_bit_cast(
+                            uint16_t, (_Float16)(sxm * (sn_[j] * (float)(acc[mt][j][v] - zn[j] * xt))));
+                }
+            }
+        }
+    }
+}
+
 } // namespace
 
 hipError_t fq_launch_quantize_act(const void *x, int M, int K, void *xq, float *sx, int32_t *xsum,
@@ -437,7 +569,7 @@ hipError_t fq_launch_quantize_act(const void *x, int M, int K, void *xq, float *
 }
 
 hipError_t fq_launch_w8a8(const FqLinearDesc &l, const void *xq, const float *sx, const int32_t *xsum,
-                          int M, hipStream_t stream)
+                          int M, bool per_row, hipStream_t stream)
 {
     if (M == 0)
         return hipSuccess;
@@ -452,11 +584,15 @@ hipError_t fq_launch_w8a8(const FqLinearDesc &l, const void *xq, const float *sx
     d.M = M;
     d.N = l.N;
     d.K = l.K;
-    const int m_tiles = (M + BM - 1) / BM, n_tiles = (l.N + BN - 1) / BN;
+    const int bm = per_row ? RBM : BM;
+    const int m_tiles = (M + bm - 1) / bm, n_tiles = (l.N + BN - 1) / BN;
     const long long total = (long long)m_tiles * n_tiles;
     if (total > 0x3fffffffLL)
         return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
-    w8a8_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
+    if (per_row)
+        w8a8_row_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
+    else
+        w8a8_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
     return hipGetLastError();
 }

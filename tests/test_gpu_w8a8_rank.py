@@ -121,6 +121,87 @@ def test_linear_w8a8_integer_case_exact():
     assert np.array_equal(y.astype(np.float64), expect.astype(np.float64))
 
 
+# ------------------------------------------------------------------ one scale per weight row (group = K)
+
+@pytest.mark.parametrize("sym", [False, True])
+@pytest.mark.parametrize("N,K", [(300, 1024), (5, 128), (64, 28672), (2049, 384)])
+def test_quantize_per_row_bit_exact(N, K, sym):
+    w = synth.weight(0, "par/rowq/%dx%d" % (N, K), N, K, 0.02, outlier_p=0.001)
+    w[0] = 0                                         # an all-zero row: s = 1
+    if N > 2:
+        w[1] = np.abs(w[1])                          # a one-signed row: z = 0
+    c_ref, s_ref, z_ref = (oracle.quantize_sym if sym else oracle.quantize)(w, 8, group=K)
+    assert fq.fq_packed_sizes(N, K, 8, K) == (N * K, N * 4, N)
+    c = torch.full((N * K,), 0xAA, dtype=torch.uint8, device=DEV)
+    sc = torch.full((N,), float("nan"), dtype=torch.float32, device=DEV)
+    z = torch.full((N,), 77, dtype=torch.uint8, device=DEV)
+    (fq.fq_quantize_sym if sym else fq.fq_quantize)(to_dev(w), N, K, 8, K, c, sc, z)
+    torch.cuda.synchronize()
+    assert np.array_equal(c.cpu().numpy().reshape(N, K), c_ref)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), s_ref.reshape(N).view(np.uint32))
+    assert np.array_equal(z.cpu().numpy(), z_ref.reshape(N))
+
+
+@pytest.mark.parametrize("M,N,K", [(33, 100, 1408), (128, 256, 1024), (300, 200, 2048), (257, 130, 128),
+                                   (64, 129, 4096), (1, 64, 256), (129, 513, 384), (200, 300, 28672)])
+def test_linear_w8a8_per_row_matches_oracle(M, N, K):
+    w = synth.weight(0, "par/w8a8row/%dx%d" % (N, K), N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/w8a8row/x/%dx%d" % (M, K), M, K)
+    layer, packed = make_layer(w, (8,), group=K)
+    y, xq, sx = _w8a8(layer, x)
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    y_ref = oracle.linear_w8a8(xq, sx, c, s, z, group=K)
+    assert y.shape == (M, N)
+    assert not np.isnan(y.astype(np.float32)).any()
+    assert rel_err(y, y_ref) <= TOL_Y
+    for m in (0, M // 2, M - 1):
+        assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
+
+
+def test_linear_w8a8_per_row_skewed_zero_points_and_integer_case():
+    # one-signed rows (z = 0 or 255) make the zero-point term as large as it gets
+    N, K, M = 96, 640, 70
+    w = np.abs(synth.weight(0, "par/w8a8row/skew", N, K, 0.02)).astype(np.float16)
+    w[::2] = -w[::2]
+    x = np.abs(synth.activations(0, "par/w8a8row/skew/x", M, K)).astype(np.float16)
+    layer, packed = make_layer(w, (8,), group=K)
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    assert set(np.unique(z)) <= {0, 255}
+    y, xq, sx = _w8a8(layer, x)
+    assert rel_err(y, oracle.linear_w8a8(xq, sx, c, s, z, group=K)) <= TOL_Y
+    # integer weights with s = 1 (every row spans 0 .. 255), integer activations with max 127 (s_x = 1):
+    # the result is the integer matrix product, exact in binary16
+    rng = np.random.default_rng(9)
+    M, N, K = 130, 70, 640
+    w = rng.integers(0, 3, size=(N, K))
+    w[:, 0] = 0
+    w[:, 1] = 255
+    x = rng.integers(-2, 3, size=(M, K))
+    x[:, 0] = 127                       # meets the weight 0: adds nothing
+    x[:, 1] = 0                         # the 255s add nothing either
+    layer, packed = make_layer(w.astype(np.float16), (8,), group=K)
+    assert torch.all(packed[8][1] == 1.0) and torch.all(packed[8][2] == 0)
+    y, xq, sx = _w8a8(layer, x.astype(np.float16))
+    assert np.all(sx == 1.0) and np.array_equal(xq.astype(np.int64), x)
+    expect = x @ w.T
+    assert np.abs(expect).max() <= 2048
+    assert np.array_equal(y.astype(np.float64), expect.astype(np.float64))
+
+
+def test_per_row_copies_are_served_by_w8a8_only():
+    w = synth.weight(0, "par/w8a8row/refuse", 64, 256, 0.02)
+    layer, _ = make_layer(w, (8,), group=256)
+    x = to_dev(synth.activations(0, "par/w8a8row/refuse/x", 1, 256))
+    y = torch.zeros((1, 64), dtype=torch.float16, device=DEV)
+    with pytest.raises(fq.FlexqError):
+        fq.fq_linear(layer, 8, x, 1, y)
+    with pytest.raises(fq.FlexqError):
+        ws = torch.empty(fq.Plan.workspace_bytes(1), dtype=torch.uint8, device=DEV)
+        fq.Plan([layer], [x], [y], 1, ws)
+    with pytest.raises(fq.FlexqError):
+        layer.attach(4, x, x, x)
+
+
 def test_linear_w8a8_close_to_weight_only_result():
     # the activation rounding bound of the oracle pins, on the GPU results
     M, N, K = 64, 128, 1024

@@ -182,6 +182,29 @@ def test_w8a8_validation():
     assert L.fq_layer_destroy(h) == B.FQ_OK
 
 
+def test_one_scale_per_row_is_an_8_bit_copy_for_w8a8_only():
+    L = fq.lib
+    assert fq.fq_packed_sizes(64, 1024, 8, 1024) == (64 * 1024, 64 * 4, 64)
+    with pytest.raises(fq.FlexqError):
+        fq.fq_packed_sizes(64, 1024, 4, 1024)               # 8 bits only
+    with pytest.raises(fq.FlexqError):
+        fq.fq_packed_sizes(64, 1000, 8, 1000)               # K a multiple of 128
+    with pytest.raises(fq.FlexqError):
+        fq.fq_packed_sizes(64, 131072, 8, 131072)           # int32 sums over the row: K <= 65536
+    with pytest.raises(fq.FlexqError):
+        fq.fq_packed_sizes(64, 1024, 8, 256)                # no other group size
+    assert L.fq_quantize(FAKE, 64, 1024, 4, 1024, FAKE, FAKE, FAKE, None) == B.FQ_ERR_SHAPE
+    h = ctypes.c_void_p()
+    assert L.fq_layer_create(ctypes.byref(h), 64, 1024, 1024) == B.FQ_OK
+    assert L.fq_layer_attach(h, 4, FAKE, FAKE, FAKE) == B.FQ_ERR_BITS
+    assert L.fq_layer_attach(h, 16, FAKE, None, None) == B.FQ_ERR_BITS
+    assert L.fq_layer_attach(h, 8, FAKE, FAKE, FAKE) == B.FQ_OK
+    assert L.fq_linear(h, 8, FAKE, 1, FAKE, None) == B.FQ_ERR_SHAPE
+    assert "fq_linear_w8a8" in fq.fq_last_error()
+    assert L.fq_linear_w8a8(h, FAKE, None, FAKE, 4, FAKE, None) == B.FQ_ERR_NULL   # (validated like the others)
+    assert L.fq_layer_destroy(h) == B.FQ_OK
+
+
 def test_2bit_copy_limits():
     L = fq.lib
     vp_odd = ctypes.c_void_p(FAKE + 1)

@@ -209,3 +209,30 @@ def test_rank_nan_last_and_is_a_permutation():
     v = np.array([2.0, np.nan, 1.0, np.nan, 0.5], dtype=np.float32)
     assert oracle.rank_ascending(v).tolist() == [4, 2, 0, 1, 3]
     assert oracle.rank_ascending(np.zeros(0, dtype=np.float32)).size == 0
+
+
+def test_quantize_with_one_group_per_row_closed_form_and_equivalence():
+    # group = K: the row is one group.  On-grid row j * 2^-10, j in [-127, 128]: s = 2^-10, z = 127, codes j + 127
+    # exactly (Sec. 2.2 Eq. 2 with Xmin / Xmax over the row); and a row quantized as one group of K equals
+    # the same values quantized as a 1 x K matrix with group K -- whatever the other rows hold
+    K = 256
+    j = np.arange(-127, 129)
+    w = np.zeros((3, K), dtype=np.float16)
+    w[0] = (j * 2.0 ** -10).astype(np.float16)
+    w[1] = np.linspace(-0.3, 0.1, K).astype(np.float16)
+    w[2] = np.linspace(0.0, 7.0, K).astype(np.float16)
+    c, s, z = oracle.quantize(w, 8, group=K)
+    assert s.shape == (3, 1) and z.shape == (3, 1)
+    assert s[0, 0] == np.float32(2.0 ** -10) and z[0, 0] == 127
+    assert np.array_equal(c[0].astype(np.int64), j + 127)
+    for r in range(3):
+        c1, s1, z1 = oracle.quantize(w[r:r + 1], 8, group=K)
+        assert np.array_equal(c1[0], c[r]) and s1[0, 0] == s[r, 0] and z1[0, 0] == z[r, 0]
+    assert z[2, 0] == 0 and c[2].max() == 255 and c[2].min() == 0
+    # the W8A8 linear with one group per row against the integer definition written out
+    rng = np.random.default_rng(3)
+    xq = rng.integers(-127, 128, size=(4, K)).astype(np.int8)
+    sx = np.array([0.5, 1.0, 0.25, 2.0], dtype=np.float32)
+    y = oracle.linear_w8a8(xq, sx, c, s, z, group=K).astype(np.float64)
+    ref = (xq.astype(np.int64) @ (c.astype(np.int64) - z.astype(np.int64)).T) * s[:, 0].astype(np.float64) * sx[:, None].astype(np.float64)
+    assert np.all(np.abs(y - ref) <= np.abs(ref) * 2.0 ** -10 + 1e-6)
