@@ -103,6 +103,12 @@ __device__ __forceinline__ void barrier()
     asm volatile("" ::: "memory");
 }
 
+__device__ __forceinline__ uint32_t pk_add_h(uint32_t a, uint32_t b)
+{
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, a) + __builtin_bit_cast(half2_t, b));
+}
+
 __device__ __forceinline__ float4_t mfma(const u32x4 a, const u32x4 b, float4_t c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c,
@@ -539,6 +545,9 @@ struct Consumer {
     __device__ __forceinline__ void unit4(const Stage &st, const u32x4 *a)
     {
         constexpr int h = H;
+        // Offsets and zero point: with one batch tile a second MFMA per operand on the constant -(offset + z)
+        // (the vector ALUs are the busier side); with two, where the matrix pipe is, a packed add per register.
+        constexpr bool SUBTRACT = MT == 2;
         uint32_t magic_lo = 0x64006400u, magic_hi = 0x54005400u;
         asm volatile("" : "+v"(magic_lo), "+v"(magic_hi));
         const uint32_t z4 = (st.z << 4) & 0xF0F0F0F0u;
@@ -560,15 +569,23 @@ struct Consumer {
                 b.y = (w & 0x00F000F0u) | magic_hi;  // (  64 + q1,   64 + q5)
                 b.z = (w8 & 0x000F000Fu) | magic_lo; // (1024 + q2, 1024 + q6)
                 b.w = (w8 & 0x00F000F0u) | magic_hi; // (  64 + q3,   64 + q7)
+                if (SUBTRACT) { // q - z in the operand itself: four packed adds instead of MT more MFMAs
+                    b.x = pk_add_h(b.x, nz[rt].x);
+                    b.y = pk_add_h(b.y, nz[rt].y);
+                    b.z = pk_add_h(b.z, nz[rt].z);
+                    b.w = pk_add_h(b.w, nz[rt].w);
+                }
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++)
                     acc[rt][mt] = mfma(a[mt * AM + i], b, acc[rt][mt]);
             }
+            if (!SUBTRACT) {
 #pragma unroll
-            for (int rt = 0; rt < RT; rt++)
+                for (int rt = 0; rt < RT; rt++)
 #pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-                    acc[rt][mt] = mfma(a[mt * AM + i], nz[rt], acc[rt][mt]);
+                    for (int mt = 0; mt < MT; mt++)
+                        acc[rt][mt] = mfma(a[mt * AM + i], nz[rt], acc[rt][mt]);
+            }
         }
 #pragma unroll
         for (int rt = 0; rt < RT; rt++)
@@ -689,15 +706,23 @@ struct Consumer {
                         b.y = __builtin_amdgcn_perm(0x64646464u, v0, 0x04030402u);
                         b.z = __builtin_amdgcn_perm(0x64646464u, v1, 0x04010400u);
                         b.w = __builtin_amdgcn_perm(0x64646464u, v1, 0x04030402u);
+                        if (MT == 2) { // two batch tiles: q - z in the operand (as at 4 bits)
+                            b.x = pk_add_h(b.x, nz[rt].x);
+                            b.y = pk_add_h(b.y, nz[rt].x);
+                            b.z = pk_add_h(b.z, nz[rt].x);
+                            b.w = pk_add_h(b.w, nz[rt].x);
+                        }
 #pragma unroll
                         for (int mt = 0; mt < MT; mt++)
                             acc[rt][mt] = mfma(st.a[mt * 4 + 2 * h + i], b, acc[rt][mt]);
                     }
+                    if (MT != 2) {
 #pragma unroll
-                    for (int rt = 0; rt < RT; rt++)
+                        for (int rt = 0; rt < RT; rt++)
 #pragma unroll
-                        for (int mt = 0; mt < MT; mt++)
-                            acc[rt][mt] = mfma(st.a[mt * 4 + 2 * h + i], nz[rt], acc[rt][mt]);
+                            for (int mt = 0; mt < MT; mt++)
+                                acc[rt][mt] = mfma(st.a[mt * 4 + 2 * h + i], nz[rt], acc[rt][mt]);
+                    }
                 }
 #pragma unroll
             for (int rt = 0; rt < RT; rt++)
