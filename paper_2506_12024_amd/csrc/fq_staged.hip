@@ -30,14 +30,16 @@
 // bit-width array), and an entry's 4-row chunks are dealt evenly to its workgroups.  So a stage
 // needs one x per workgroup, staged once, right after the barrier.
 //
-// Barrier.  Every workgroup has an arrival word of its own that counts up through the launch: after
-// its rows of stage s are acknowledged it stores s + 1 there (a plain write-through store; adds to
-// shared counters are served one after the other where the counter lives, and with 8 workgroups
-// behind each of 32 counters they still cost 0.6 us per stage), and a poll reads all the words, four
-// per lane.  One more word is the abort flag.  The wait is bounded: a service
+// Barrier.  128 arrival counters, each on a cache line of its own, count up through the launch:
+// after its rows of stage s are acknowledged workgroup b adds one to counter b % 128 (adds to one
+// counter are served one after the other where the counter lives, 80 ns each: with a single counter
+// the last of 256 arrivals is 20 us late, with two workgroups per counter it does not show; an
+// arrival word per workgroup, stored or added, made the polls four times as large and the stage
+// slower), and a poll reads all the counters, two per lane, against what they must have reached
+// after stage s.  One more word is the abort flag.  The wait is bounded: a service
 // wavefront that has polled `wait_limit` times raises the abort flag and, if it is the first, adds
 // one to a sticky count; every waiter sees the flag at its next poll and every workgroup leaves the
-// kernel.  The last workgroup out (one more counter) puts the words and the flag back to zero,
+// kernel.  The last workgroup out (one more counter) puts the counters and the flag back to zero,
 // so that the next launch, and a replayed HIP graph, find them clean.  All workgroups must be
 // resident together (the host launches at most as many as fit).
 //
