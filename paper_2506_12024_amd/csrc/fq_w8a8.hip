@@ -441,19 +441,29 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // never wait for each other, and the vector ALUs are left with the XOR of the weight bytes.
 // RMT MFMA tiles along the tokens per wavefront: 4 (256 tokens per workgroup) -- the int32 accumulators
 // are touched by MFMAs only, so 128 of them fit beside the operands.
-constexpr int RMT = 4;
-constexpr int RBM = 2 * RMT * 32;
-constexpr int RXSLAB = RBM * BKB;
+// HALF: the workgroup takes half a tile, 128 tokens x 256 rows (RMT = 2): the tiles left over for a last
+// round that would fill at most half of the compute units run this way, in a second launch (`skip`: the
+// tiles of an XCD's run that the first launch has taken).
+constexpr int RBM_FULL = 256;
+template <bool HALF>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void w8a8_row_kernel(
-    const W8A8Args d, int m_tiles, int n_tiles, int per_xcd)
+    const W8A8Args d, int m_tiles, int n_tiles, int per_xcd, int skip)
 {
+    constexpr int RMT = HALF ? 2 : 4;
+    constexpr int RBM = 2 * RMT * 32;
+    constexpr int RXSLAB = RBM * BKB;
+    static_assert(RBM == (HALF ? RBM_FULL / 2 : RBM_FULL), "two half tiles to a tile");
     __shared__ __attribute__((aligned(1024))) uint8_t xs0[RXSLAB], xs1[RXSLAB], ws0[WSLAB], ws1[WSLAB];
     __shared__ int xtot[RBM];
 
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= m_tiles * n_tiles)
+    const int in_run = skip + (HALF ? (int)(blockIdx.x >> 4) : (int)(blockIdx.x >> 3));
+    const int logical = (blockIdx.x & 7) * per_xcd + in_run;
+    if (in_run >= per_xcd || logical >= m_tiles * n_tiles)
         return;
-    const int m0 = (logical % m_tiles) * RBM, n0 = (logical / m_tiles) * BN;
+    const int m0 = (logical % m_tiles) * RBM_FULL + (HALF ? (int)((blockIdx.x >> 3) & 1) * RBM : 0);
+    const int n0 = (logical / m_tiles) * BN;
+    if (m0 >= d.M)
+        return; // the second half of a last, partly filled tile
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, c = lane >> 5;
@@ -593,15 +603,31 @@ hipError_t fq_launch_w8a8(const FqLinearDesc &l, const void *xq, const float *sx
     d.M = M;
     d.N = l.N;
     d.K = l.K;
-    const int bm = per_row ? RBM : BM;
+    const int bm = per_row ? RBM_FULL : BM;
     const int m_tiles = (M + bm - 1) / bm, n_tiles = (l.N + BN - 1) / BN;
     const long long total = (long long)m_tiles * n_tiles;
     if (total > 0x3fffffffLL)
         return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
-    if (per_row)
-        w8a8_row_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
-    else
+    if (!per_row) {
         w8a8_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
+        return hipGetLastError();
+    }
+    // One workgroup per compute unit at a time: an XCD works through its run of tiles in rounds of its
+    // compute units.  What is left for the last round, if it would fill at most half of them, runs as
+    // half tiles in a second launch (2048 x 28672: 112 tiles per XCD = 3 rounds of 32 + 16 tiles, which
+    // then take half a round instead of a whole one).
+    const int cus = fq_device_cus();
+    const int per_round = cus / 8 > 0 ? cus / 8 : 1;
+    const int rest = per_xcd % per_round;
+    const int tail = rest > 0 && 2 * rest <= per_round ? rest : 0;
+    if (per_xcd - tail > 0) {
+        w8a8_row_kernel<false><<<(unsigned)(per_xcd - tail) * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd, 0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+    }
+    if (tail > 0)
+        w8a8_row_kernel<true><<<(unsigned)tail * 16, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd, per_xcd - tail);
     return hipGetLastError();
 }
