@@ -349,7 +349,10 @@ def bench_prefill_w8a8(args):
     import paper_2506_12024_amd as fq
     dev, M = "cuda:0", 2048
     calls = []
-    for N, K in ((28672, 8192), (8192, 28672)):
+    shapes = [(28672, 8192), (8192, 28672)]
+    if args.shape:
+        shapes = [tuple(int(v) for v in args.shape.lower().split("x"))]
+    for N, K in shapes:
         w = synth.weight(SEED, "prefill/%dx%d/w" % (N, K), N, K, 0.015)
         x = synth.activations(SEED, "prefill/%dx%d/x" % (N, K), M, K)
         w_dev = torch.from_numpy(w.view(np.int16)).to(dev).view(torch.float16)
@@ -710,7 +713,7 @@ def main():
     ap.add_argument("--stack", default="llama7b", choices=sorted(synth.STACKS))
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--bits", default="4,8", help="bit-widths drawn per layer per token")
-    ap.add_argument("--shape", default=None, help="--workload prefill: one shape NxK (weight rows x inputs) instead of both")
+    ap.add_argument("--shape", default=None, help="--workload prefill and prefill-w8a8: one shape NxK (weight rows x inputs) instead of both")
     ap.add_argument("--prefill-bits", default="4,8", help="--workload prefill: the bit-widths of the GEMMs of a step")
     ap.add_argument("--ladder", default="16,8,4", help="--workload flexquant: the formats a linear steps down through")
     ap.add_argument("--layers", type=int, default=None, help="truncate the stack (debugging only)")

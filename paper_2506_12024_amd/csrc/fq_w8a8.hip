@@ -24,7 +24,9 @@
 // Tiling.  A workgroup of 8 wavefronts (two per SIMD) owns 192 tokens x 256 weight rows, a
 // wavefront 96 tokens x 64 rows = 3 x 2 MFMA tiles; the 96 binary32 accumulators are
 // updated by vector instructions, so they sit in architectural registers (4 x 2 tiles would
-// need 128 and no longer fit beside the operands without spilling).  One step = one
+// need 128 and no longer fit beside the operands without spilling).  A second instance with
+// 128 tokens (2 x 2 tiles per wavefront) serves the launches whose tile count fits the chip
+// better that way.  One step = one
 // quantization group: both operand slabs of a step (192 and 256 rows x 128 bytes) are fetched
 // straight into LDS by global_load_lds_dwordx4 -- no staging registers, nothing for the
 // register allocator to juggle -- double buffered, one wait and one barrier per step.
@@ -116,11 +118,11 @@ __global__ __launch_bounds__(QA_THREADS) void quantize_act_kernel(const half8 *_
 
 constexpr int THREADS = 512;
 constexpr int WAVES = THREADS / 64;
-constexpr int MT = 3;            // MFMA tiles along the tokens, per wavefront (96 tokens)
-constexpr int BM = 2 * MT * 32, BN = 256;
+constexpr int MT_MAX = 3;        // MFMA tiles along the tokens, per wavefront (96 tokens; the kernel also
+                                 // exists with 2: the launcher takes the one with fewer, cheaper rounds)
+constexpr int BN = 256;
 constexpr int BKB = 128;         // k (= bytes of a row) per step: one quantization group
 constexpr int WN = 64;           // weight rows per wavefront (2 MFMA tiles)
-constexpr int XSLAB = BM * BKB;  // bytes of the x slab of a step (BM rows x 128 bytes)
 constexpr int WSLAB = BN * BKB;  // bytes of the weight slab
 
 struct W8A8Args {
@@ -216,9 +218,13 @@ struct IntC {
     static constexpr int value = V;
 };
 
+template <int MT>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void w8a8_kernel(
     const W8A8Args d, int m_tiles, int n_tiles, int per_xcd)
 {
+    static_assert(MT >= 2 && MT <= MT_MAX, "two or three token tiles per wavefront");
+    constexpr int BM = 2 * MT * 32;  // tokens per workgroup
+    constexpr int XSLAB = BM * BKB;  // bytes of the x slab of a step (BM rows x 128 bytes)
     // Four separate arrays, selected at compile time: the compiler can then tell that the
     // operand reads of a step do not touch the slabs its direct-to-LDS loads are filling, and
     // does not wait for those loads before the first read.
@@ -603,21 +609,37 @@ hipError_t fq_launch_w8a8(const FqLinearDesc &l, const void *xq, const float *sx
     d.M = M;
     d.N = l.N;
     d.K = l.K;
-    const int bm = per_row ? RBM_FULL : BM;
-    const int m_tiles = (M + bm - 1) / bm, n_tiles = (l.N + BN - 1) / BN;
+    const int cus = fq_device_cus();
+    const int n_tiles = (l.N + BN - 1) / BN;
+    // Groups of 128: 192 or 128 tokens per workgroup.  The larger tile unpacks a weight operand for three
+    // MFMAs instead of two (2048 x 28672, five rounds of the one against seven of the other: 1142 against
+    // 1077 TOP/s), so the smaller one is taken only where its rounds (one workgroup per compute unit at a
+    // time) cost at least an eighth less in all -- 2048 x 8192: 352 tiles of 192 are two rounds, 512
+    // tiles of 128 two rounds of two thirds the work (982 -> 1133 TOP/s).
+    int mt = MT_MAX;
+    if (!per_row) {
+        const long long t3 = (long long)((M + 191) / 192) * n_tiles, t2 = (long long)((M + 127) / 128) * n_tiles;
+        const long long c = cus > 0 ? cus : 1;
+        if (((t2 + c - 1) / c) * 2 * 8 < ((t3 + c - 1) / c) * 3 * 7)
+            mt = 2;
+    }
+    const int bm = per_row ? RBM_FULL : 2 * mt * 32;
+    const int m_tiles = (M + bm - 1) / bm;
     const long long total = (long long)m_tiles * n_tiles;
     if (total > 0x3fffffffLL)
         return hipErrorInvalidValue;
     const int per_xcd = (int)((total + 7) / 8);
     if (!per_row) {
-        w8a8_kernel<<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
+        if (mt == 2)
+            w8a8_kernel<2><<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
+        else
+            w8a8_kernel<3><<<(unsigned)per_xcd * 8, THREADS, 0, stream>>>(d, m_tiles, n_tiles, per_xcd);
         return hipGetLastError();
     }
     // One workgroup per compute unit at a time: an XCD works through its run of tiles in rounds of its
     // compute units.  What is left for the last round, if it would fill at most half of them, runs as
     // half tiles in a second launch (2048 x 28672: 112 tiles per XCD = 3 rounds of 32 + 16 tiles, which
     // then take half a round instead of a whole one).
-    const int cus = fq_device_cus();
     const int per_round = cus / 8 > 0 ? cus / 8 : 1;
     const int rest = per_xcd % per_round;
     const int tail = rest > 0 && 2 * rest <= per_round ? rest : 0;

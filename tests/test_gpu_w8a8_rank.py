@@ -88,6 +88,30 @@ def test_linear_w8a8_matches_oracle(M, N, K):
         assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
 
 
+def test_linear_w8a8_both_token_tilings_on_a_full_grid():
+    # The kernel for groups of 128 exists with 192 and with 128 tokens per workgroup and the launcher
+    # takes the one whose rounds (one workgroup per compute unit at a time) cost less.  One round or
+    # less always goes to 128 tokens, which is what the shapes above exercise; 1536 x 8192 is 8 x 32 =
+    # 256 tiles of 192 tokens (one round on 256 compute units) against 384 tiles of 128 (two), so
+    # this launch runs the 192-token kernel.  Weight rows sampled from every part of a tile, all
+    # tokens; both launches repeatable bit for bit.
+    M, N, K = 1536, 8192, 256
+    w = synth.weight(0, "par/w8a8/grid/w", N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/w8a8/grid/x", M, K)
+    layer, packed = make_layer(w, (8,))
+    y, xq, sx = _w8a8(layer, x)
+    y2, _, _ = _w8a8(layer, x)
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    assert not np.isnan(y.astype(np.float32)).any()
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    for n0 in (0, 31, 63, 64, 127, 255, 256, 4095, 4160, 8190):
+        y_ref = oracle.linear_w8a8(xq, sx, c, s, z, row0=n0, rows=2)
+        assert rel_err(y[:, n0:n0 + 2], y_ref) <= TOL_Y, n0
+    for m in (0, 95, 96, 191, 192, 767, 1535):
+        y_ref = oracle.linear_w8a8(xq[m:m + 1], sx[m:m + 1], c, s, z)
+        assert rel_err(y[m:m + 1], y_ref) <= TOL_Y, m
+
+
 def test_linear_w8a8_skewed_zero_points():
     # one-signed groups (z = 0 or 255) make the zero-point term as large as it gets
     rng = np.random.default_rng(21)
