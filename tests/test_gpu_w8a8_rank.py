@@ -182,6 +182,28 @@ def test_linear_w8a8_per_row_matches_oracle(M, N, K):
         assert rel_err(y[m:m + 1], y_ref[m:m + 1]) <= TOL_Y, m
 
 
+def test_linear_w8a8_per_row_whole_and_half_tiles_on_a_full_grid():
+    # 2560 x 8192 is 10 x 32 = 320 tiles of 256 x 256, 40 per XCD: on 32 compute units per XCD one
+    # round of whole tiles and a last quarter round, which the launcher runs as half tiles in a second
+    # launch -- the small shapes above fit half a round and run as half tiles only.  Weight rows and
+    # tokens sampled from both kinds of tile; repeatable bit for bit.
+    M, N, K = 2560, 8192, 256
+    w = synth.weight(0, "par/w8a8row/grid/w", N, K, 0.015, outlier_p=0.001)
+    x = synth.activations(0, "par/w8a8row/grid/x", M, K)
+    layer, packed = make_layer(w, (8,), group=K)
+    y, xq, sx = _w8a8(layer, x)
+    y2, _, _ = _w8a8(layer, x)
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    assert not np.isnan(y.astype(np.float32)).any()
+    c, s, z = (t.cpu().numpy() for t in packed[8])
+    for n0 in (0, 63, 64, 255, 256, 1023, 1024, 4095, 6400, 7000, 8190):
+        y_ref = oracle.linear_w8a8(xq, sx, c, s, z, group=K, row0=n0, rows=2)
+        assert rel_err(y[:, n0:n0 + 2], y_ref) <= TOL_Y, n0
+    for m in (0, 127, 128, 255, 256, 1279, 1280, 2559):
+        y_ref = oracle.linear_w8a8(xq[m:m + 1], sx[m:m + 1], c, s, z, group=K)
+        assert rel_err(y[m:m + 1], y_ref) <= TOL_Y, m
+
+
 def test_linear_w8a8_per_row_skewed_zero_points_and_integer_case():
     # one-signed rows (z = 0 or 255) make the zero-point term as large as it gets
     N, K, M = 96, 640, 70
