@@ -216,21 +216,24 @@ def test_batched_entropy_kl_full_size_sampled_rows():
     assert np.all(np.abs(KLn - KL_ref) <= 1e-4 * np.abs(KL_ref) + 1e-7)
 
 
+@pytest.mark.parametrize("per_row", [False, True])
 @pytest.mark.parametrize("N,K", [(28672, 8192), (8192, 28672)])
-def test_w8a8_slice_sampled_outputs(N, K):
-    """The W8A8 prefill at the benchmark's shapes: activation codes and scales of sampled tokens
-    bit-exact, group sums exact everywhere, sampled outputs against the oracle."""
+def test_w8a8_slice_sampled_outputs(N, K, per_row):
+    """The W8A8 prefill at the benchmark's shapes, with groups of 128 and with one scale per weight
+    row: activation codes and scales of sampled tokens bit-exact, group sums exact everywhere,
+    sampled outputs against the oracle."""
     M = 2048
+    group = K if per_row else 128
     name = "full/prefill/%dx%d" % (N, K)
     w = synth.weight(0, name + "/w", N, K, 0.015)
     x = synth.activations(0, name + "/x", M, K)
     w_dev, x_dev = to_dev(w), to_dev(x)
-    cb, sb, zb = fq.fq_packed_sizes(N, K, 8)
+    cb, sb, zb = fq.fq_packed_sizes(N, K, 8, group)
     c = torch.empty(cb, dtype=torch.uint8, device=DEV)
     s = torch.empty(sb // 4, dtype=torch.float32, device=DEV)
     z = torch.empty(zb, dtype=torch.uint8, device=DEV)
-    fq.fq_quantize(w_dev, N, K, 8, 128, c, s, z)
-    layer = fq.Layer(N, K).attach(8, c, s, z)
+    fq.fq_quantize(w_dev, N, K, 8, group, c, s, z)
+    layer = fq.Layer(N, K, group).attach(8, c, s, z)
     xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
     sx = torch.empty(M, dtype=torch.float32, device=DEV)
     xsum = torch.empty((K // 128, M), dtype=torch.int32, device=DEV)
@@ -248,8 +251,8 @@ def test_w8a8_slice_sampled_outputs(N, K):
     assert torch.equal(xsum, sums)
     refs, gots = [], []
     for n in [0, N - 1] + [int(n) for n in rng.integers(0, N, size=10)]:
-        cr, sr, zr = oracle.quantize(w[n:n + 1], 8)
-        refs.append(oracle.linear_w8a8(xq_ref, sx_ref, cr, sr, zr)[:, 0].astype(np.float64))
+        cr, sr, zr = oracle.quantize(w[n:n + 1], 8, group=group)
+        refs.append(oracle.linear_w8a8(xq_ref, sx_ref, cr, sr, zr, group=group)[:, 0].astype(np.float64))
         gots.append(y[ms, n].cpu().numpy().astype(np.float64))
     refs, gots = np.stack(refs), np.stack(gots)
     assert np.abs(gots - refs).max() <= TOL_Y * np.abs(refs).max(), (np.abs(gots - refs).max(), np.abs(refs).max())
