@@ -48,17 +48,20 @@
 //
 // Dequantization.  Codes become halves by bit tricks ((w & 0x000F000F) | 0x64006400 is the
 // pair (1024 + q0, 1024 + q4); nibbles in bits 4..7 use exponent 0x54 = 64 + q; bytes go
-// under 0x64 with v_perm_b32).  The offsets and the zero point are not subtracted per weight:
-// a second MFMA per operand multiplies the same x block by the constant -(offset + z), so
-// that the accumulator holds sum x (q - z) over the stage (every product is exact in
-// binary32), which is folded as out += s * acc -- Eq. (3) with the scale factored out of the
-// group.  The vector ALUs are left with the unpacking (5 instructions per 8 four-bit weights).
+// under 0x64 with v_perm_b32).  Offsets and zero point come off the operand by one packed fp16
+// add per register, -(offset + z) in both halves: the difference is the small integer q - z,
+// exact in binary16, so the accumulator holds sum x (q - z) over the stage, which is folded as
+// out += s * acc -- Eq. (3) with the scale factored out of the group.  (At 8 bits with one batch
+// tile, where the stream is memory-bound and registers are short, the offsets stay in the
+// operand and a second MFMA per operand multiplies the same x block by the constant
+// -(offset + z) instead; every product is exact in binary32.)  The vector ALUs carry 9
+// instructions per 8 four-bit weights.
 // At 2 bits a stage is four units; an MFMA's 32 k are 8 bytes of a line, 2 from each group of 16
 // lanes, so a lane reads its 8 bytes of every unit (not 16 contiguous ones, which would put two
 // units into one MFMA's sum); a byte holds four consecutive codes, which one v_perm_b32 copies to
 // both halves of a word and two and-or instructions turn into the pairs (1024 + q0, 256 + q1) and
-// (64 + q2, 16 + q3) -- x stays in its natural order -- and the constant operand carries the four
-// offsets by position.  A stage's x is 16 KiB, read from LDS unit by unit.
+// (64 + q2, 16 + q3) -- x stays in its natural order -- and the constant that is added carries the
+// four offsets by position.  A stage's x is 16 KiB, read from LDS unit by unit.
 //
 // LDS layout of a weight stage: per row tile 16 lines of 128 bytes, the eight 16-byte slots of
 // line n XOR-ed by (n >> 1) & 7 -- a 128-bit read of the 16 rows at one piece is conflict
